@@ -1,0 +1,130 @@
+/*
+ * knm.h -- C ABI of the MI355X (gfx950) Nystrom kernel-ridge hot path.
+ *
+ * Implements, on one GPU, the operations of the preconditioned Nystrom kernel ridge
+ * solver ("Falkon") of arXiv 2006.10350 with the Gaussian kernel
+ *     k(x, c) = exp(-||x - c||^2 / (2 sigma^2))                      (Section 2)
+ * for n data points X (n x d), M Nystrom centres C (M x d) and t right-hand sides.
+ *
+ * Conventions for every entry point
+ *  - All array arguments are DEVICE pointers owned by the caller; the library reads or
+ *    writes them only during the call's enqueued work and keeps no reference afterwards.
+ *    The only host pointers are the out-parameters that say so explicitly.
+ *  - Matrices are row-major fp32.  X has leading dimension ldx >= d, C has ldc >= d.
+ *    V, U, R, alpha are M x t with leading dimension t; W, Y, out are n x t with
+ *    leading dimension t.
+ *  - Work is enqueued on the context's HIP stream.  Calls return without synchronising
+ *    unless a host value is needed (Cholesky status, CG scalars, timing queries).
+ *  - Outputs are overwritten, never accumulated into.
+ *  - Return value: KNM_OK (0) or a negative knm_status.  No exception crosses the ABI.
+ *  - Indices are 64-bit; n * d and n * M may exceed 2^32.
+ *  - Results are deterministic: partial sums are merged in a fixed order (no atomics).
+ */
+#ifndef KNM_H
+#define KNM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KNM_OK = 0,
+    KNM_INVALID_ARG = -1, /* null pointer, non-positive size, sigma <= 0, lambda < 0, ld < d */
+    KNM_UNSUPPORTED = -2, /* shape outside what the kernels were compiled for (see knm_max_*) */
+    KNM_ALLOC = -3,       /* workspace allocation failed */
+    KNM_HIP_ERROR = -4,   /* a HIP / rocBLAS / rocSOLVER call failed; text via knm_last_error */
+    KNM_NOT_PD = -5       /* a Cholesky factorisation met a non-positive pivot */
+} knm_status;
+
+typedef struct knm_ctx knm_ctx;         /* device, stream, library-owned workspace */
+typedef struct knm_precond knm_precond; /* fp64 factors T, A of the preconditioner  */
+
+/* Create a context on HIP device `device`.  `hip_stream` is a hipStream_t passed as
+ * void* (NULL = the default stream); the caller keeps ownership of the stream. */
+int knm_create(knm_ctx **out, int device, void *hip_stream);
+int knm_destroy(knm_ctx *ctx);
+/* Static description of a status code / text of the last failing runtime call. */
+const char *knm_strerror(int status);
+const char *knm_last_error(const knm_ctx *ctx);
+/* Largest d and t the compiled kernels accept. */
+int knm_max_d(void);
+int knm_max_t(void);
+/* Device bytes of library-owned workspace knm_prod will hold for this shape. */
+size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t);
+
+/* W[n x t] = k(X, C) V  -- the kernel-matrix-vector product k(X1, X2) v of the
+ * matrix-vector comparison in the appendix on performance, and the predictor
+ * f(x) = sum_j alpha_j k(x, c_j) of Eq. 4. */
+int knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
+          const float *C, int64_t M, int64_t ldc, float sigma,
+          const float *V, int t, float *W);
+
+/* U[M x t] = K_nm^T (K_nm V), the product evaluated once per conjugate-gradient
+ * iteration (Section 3.1, "Blockwise K_nm-vector product"); K_nm is never formed.
+ * If W_or_null is not NULL it also receives W[n x t] = K_nm V. */
+int knm_prod(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
+             const float *C, int64_t M, int64_t ldc, float sigma,
+             const float *V, int t, float *W_or_null, float *U);
+
+/* U[M x t] = K_nm^T diag(dw) K_nm V with dw[n] >= 0: the product inside LinOp of the
+ * weighted solver for generalised self-concordant losses (Alg. 2, WeightedFalkon). */
+int knm_prod_weighted(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
+                      const float *C, int64_t M, int64_t ldc, float sigma,
+                      const float *dw, const float *V, int t, float *U);
+
+/* R[M x t] = K_nm^T Y, the right-hand side of the Nystrom system (Eq. 5; line
+ * "R <- ..." of Alg. 1 read as k(X_m, X) y). */
+int knm_t_y(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
+            const float *C, int64_t M, int64_t ldc, float sigma,
+            const float *Y, int t, float *R);
+
+/* Preconditioner of Alg. 1 / Eq. 7, all in fp64 on the device:
+ *   T = chol_upper(k(C, C) + jitter I),   A = chol_upper(T T^T / M + lambda I),
+ * with T^T T = K_MM and A^T A = T T^T / M + lambda I.  *out owns 2 M^2 doubles of
+ * device memory until precond_free.  On KNM_NOT_PD, *bad_pivot_or_null (HOST pointer)
+ * receives the 1-based failing pivot, negative if it was the second factorisation. */
+int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma,
+                  double lambda, double jitter, knm_precond **out, int64_t *bad_pivot_or_null);
+int precond_free(knm_precond *p);
+/* Copy the factors to HOST buffers of M*M doubles each (row-major, upper triangular,
+ * strict lower triangle zero); either may be NULL.  For tests and inspection. */
+int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, double *A_host);
+
+/* Preconditioned operator of Eq. 9 applied to beta (M x t, fp64 DEVICE pointers):
+ *   out = A^-T ( T^-T K_nm^T K_nm T^-1 A^-1 beta + lambda n A^-1 beta ). */
+int falkon_linop(knm_ctx *ctx, const knm_precond *p,
+                 const float *X, int64_t n, int d, int64_t ldx,
+                 const float *C, int64_t M, int64_t ldc, float sigma, double lambda,
+                 const double *beta, int t, double *out);
+
+/* Falkon (Alg. 1) with the centres given by the caller: builds the preconditioner,
+ * forms rhs = A^-T T^-T K_nm^T Y, runs exactly `iters` conjugate-gradient steps on the
+ * operator of Eq. 9 from beta = 0 (one step size per column of Y), and writes
+ * alpha[M x t] = T^-1 A^-1 beta (fp32).  resid_norms_or_null is a HOST buffer of
+ * (iters + 1) * t doubles receiving the residual 2-norm of every column before the
+ * first and after each step. */
+int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
+               const float *Y, int t, const float *C, int64_t M, int64_t ldc,
+               float sigma, double lambda, double jitter, int iters,
+               float *alpha, double *resid_norms_or_null);
+
+/* out[ntest x t] = k(Xtest, C) alpha  (Eq. 4). */
+int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64_t ldx,
+                   const float *C, int64_t M, int64_t ldc, float sigma,
+                   const float *alpha, int t, float *out);
+
+/* Timing aid for benchmarks: when enabled, knm_v / knm_prod / knm_t_y bracket their
+ * kernels with HIP events on the context's stream.  knm_get_timing synchronises the
+ * stream and writes milliseconds of the most recent call to the HOST array ms[4]:
+ * [0] row sweep (W = K V), [1] column sweep (K^T W partials), [2] merge of partials,
+ * [3] whole call.  Phases a call did not run are reported as 0. */
+int knm_set_timing(knm_ctx *ctx, int enabled);
+int knm_get_timing(knm_ctx *ctx, float *ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KNM_H */

@@ -1,0 +1,295 @@
+"""MI355X-native hot path of the preconditioned Nystrom kernel ridge solver (arXiv 2006.10350).
+
+Thin ctypes binding over ``libknm.so`` (hand-written HIP for gfx950).  The functions
+here have the names of the C entry points declared in ``include/knm.h`` and only
+marshal arguments: PyTorch supplies device memory and the stream, every step of the
+computation runs in the library's kernels.  There is no CPU fallback: importing works
+without a GPU (so the library's symbols can be checked), any compute call needs one.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libknm.so")
+
+KNM_OK = 0
+STATUS_NAMES = {0: "KNM_OK", -1: "KNM_INVALID_ARG", -2: "KNM_UNSUPPORTED", -3: "KNM_ALLOC",
+                -4: "KNM_HIP_ERROR", -5: "KNM_NOT_PD"}
+
+_vp = ctypes.c_void_p
+_i64 = ctypes.c_int64
+_int = ctypes.c_int
+_f32 = ctypes.c_float
+_f64 = ctypes.c_double
+
+_PTS = [_vp, _i64, _int, _i64, _vp, _i64, _i64, _f32]  # X n d ldx C M ldc sigma
+
+SIGNATURES = {
+    "knm_create": (_int, [ctypes.POINTER(_vp), _int, _vp]),
+    "knm_destroy": (_int, [_vp]),
+    "knm_strerror": (ctypes.c_char_p, [_int]),
+    "knm_last_error": (ctypes.c_char_p, [_vp]),
+    "knm_max_d": (_int, []),
+    "knm_max_t": (_int, []),
+    "knm_workspace_bytes": (ctypes.c_size_t, [_i64, _i64, _int, _int]),
+    "knm_v": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
+    "knm_prod": (_int, [_vp] + _PTS + [_vp, _int, _vp, _vp]),
+    "knm_prod_weighted": (_int, [_vp] + _PTS + [_vp, _vp, _int, _vp]),
+    "knm_t_y": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
+    "precond_build": (_int, [_vp, _vp, _i64, _int, _i64, _f32, _f64, _f64, ctypes.POINTER(_vp),
+                             ctypes.POINTER(_i64)]),
+    "precond_free": (_int, [_vp]),
+    "precond_get_factors": (_int, [_vp, _vp, _vp, _vp]),
+    "falkon_linop": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _int, _vp]),
+    "falkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _int, _vp, _i64, _i64, _f32, _f64, _f64, _int,
+                          _vp, _vp]),
+    "falkon_predict": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
+    "knm_set_timing": (_int, [_vp, _int]),
+    "knm_get_timing": (_int, [_vp, ctypes.POINTER(_f32)]),
+}
+
+_lib = None
+
+
+class KnmError(RuntimeError):
+    def __init__(self, status: int, detail: str = ""):
+        self.status = status
+        name = STATUS_NAMES.get(status, str(status))
+        super().__init__(f"{name}: {detail}" if detail else name)
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libknm.so and declare every entry point; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: build it with __graft_entry__.build() "
+                              "(python paper_2006_10350_amd/build.py); there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _dev_f32(x: torch.Tensor, what: str) -> torch.Tensor:
+    if not (isinstance(x, torch.Tensor) and x.is_cuda and x.dtype == torch.float32):
+        raise TypeError(f"{what} must be a float32 tensor on the GPU")
+    return x
+
+
+def _points(x: torch.Tensor, what: str):
+    _dev_f32(x, what)
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError(f"{what} must be 2-D with unit stride along features")
+    return x, x.shape[0], x.shape[1], (x.stride(0) if x.shape[0] > 1 else x.shape[1])
+
+
+def _cols(x: torch.Tensor, rows: int, what: str):
+    _dev_f32(x, what)
+    sq = x.dim() == 1
+    x2 = x.reshape(rows, -1)
+    if not x2.is_contiguous():
+        x2 = x2.contiguous()
+    return x2, x2.shape[1], sq
+
+
+class Context:
+    """A library context bound to a device and to the torch stream current at creation."""
+
+    def __init__(self, device: Optional[int] = None):
+        lib = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: libknm has no CPU path")
+        self.device = torch.cuda.current_device() if device is None else int(device)
+        with torch.cuda.device(self.device):
+            self.stream = torch.cuda.current_stream()
+        h = _vp()
+        st = lib.knm_create(ctypes.byref(h), self.device, _vp(self.stream.cuda_stream))
+        if st != KNM_OK:
+            raise KnmError(st, "knm_create")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().knm_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def check(self, st: int):
+        if st != KNM_OK:
+            raise KnmError(st, load_library().knm_last_error(self._h).decode())
+
+    # ---- timing -----------------------------------------------------------------------
+    def set_timing(self, enabled: bool):
+        self.check(load_library().knm_set_timing(self._h, int(enabled)))
+
+    def get_timing(self):
+        ms = (_f32 * 4)()
+        self.check(load_library().knm_get_timing(self._h, ms))
+        return {"row_sweep_ms": ms[0], "col_sweep_ms": ms[1], "merge_ms": ms[2], "total_ms": ms[3]}
+
+
+_default_ctx = {}
+
+
+def default_context() -> Context:
+    dev = torch.cuda.current_device()
+    key = (dev, torch.cuda.current_stream().cuda_stream)
+    if key not in _default_ctx:
+        _default_ctx[key] = Context(dev)
+    return _default_ctx[key]
+
+
+def _geom(X, C):
+    X, n, d, ldx = _points(X, "X")
+    C, M, d2, ldc = _points(C, "C")
+    if d != d2:
+        raise ValueError("X and C must have the same number of features")
+    return X, n, d, ldx, C, M, ldc
+
+
+def knm_v(X, C, sigma: float, V, ctx: Optional[Context] = None) -> torch.Tensor:
+    """W = k(X, C) V."""
+    ctx = ctx or default_context()
+    X, n, d, ldx, C, M, ldc = _geom(X, C)
+    V, t, sq = _cols(V, M, "V")
+    W = torch.empty(n, t, device=X.device, dtype=torch.float32)
+    ctx.check(load_library().knm_v(ctx._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc, float(sigma),
+                                   V.data_ptr(), t, W.data_ptr()))
+    return W[:, 0] if sq else W
+
+
+def knm_prod(X, C, sigma: float, V, return_w: bool = False, out: Optional[torch.Tensor] = None,
+             ctx: Optional[Context] = None):
+    """U = K_nm^T (K_nm V); optionally also W = K_nm V."""
+    ctx = ctx or default_context()
+    X, n, d, ldx, C, M, ldc = _geom(X, C)
+    V, t, sq = _cols(V, M, "V")
+    U = out if out is not None else torch.empty(M, t, device=X.device, dtype=torch.float32)
+    W = torch.empty(n, t, device=X.device, dtype=torch.float32) if return_w else None
+    ctx.check(load_library().knm_prod(ctx._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc, float(sigma),
+                                      V.data_ptr(), t, W.data_ptr() if return_w else None, U.data_ptr()))
+    if sq:
+        U = U.reshape(M)
+        W = W[:, 0] if return_w else None
+    return (U, W) if return_w else U
+
+
+def knm_prod_weighted(X, C, sigma: float, dw, V, ctx: Optional[Context] = None) -> torch.Tensor:
+    """U = K_nm^T diag(dw) K_nm V."""
+    ctx = ctx or default_context()
+    X, n, d, ldx, C, M, ldc = _geom(X, C)
+    V, t, sq = _cols(V, M, "V")
+    dw = _dev_f32(dw, "dw").reshape(n).contiguous()
+    U = torch.empty(M, t, device=X.device, dtype=torch.float32)
+    ctx.check(load_library().knm_prod_weighted(ctx._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc,
+                                               float(sigma), dw.data_ptr(), V.data_ptr(), t, U.data_ptr()))
+    return U[:, 0] if sq else U
+
+
+def knm_t_y(X, C, sigma: float, Y, ctx: Optional[Context] = None) -> torch.Tensor:
+    """R = K_nm^T Y."""
+    ctx = ctx or default_context()
+    X, n, d, ldx, C, M, ldc = _geom(X, C)
+    Y, t, sq = _cols(Y, n, "Y")
+    R = torch.empty(M, t, device=X.device, dtype=torch.float32)
+    ctx.check(load_library().knm_t_y(ctx._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc, float(sigma),
+                                     Y.data_ptr(), t, R.data_ptr()))
+    return R[:, 0] if sq else R
+
+
+class Preconditioner:
+    """Owns the fp64 factors T, A built by precond_build."""
+
+    def __init__(self, C, sigma: float, lam: float, jitter: float = 0.0, ctx: Optional[Context] = None):
+        self.ctx = ctx or default_context()
+        C, M, d, ldc = _points(C, "C")
+        h = _vp()
+        bad = _i64(0)
+        st = load_library().precond_build(self.ctx._h, C.data_ptr(), M, d, ldc, float(sigma), float(lam),
+                                          float(jitter), ctypes.byref(h), ctypes.byref(bad))
+        self.bad_pivot = bad.value
+        if st != KNM_OK:
+            raise KnmError(st, load_library().knm_last_error(self.ctx._h).decode() + f" (pivot {bad.value})")
+        self._h = h
+        self.M = M
+
+    def factors(self):
+        import numpy as np
+
+        T = np.empty((self.M, self.M), dtype=np.float64)
+        A = np.empty((self.M, self.M), dtype=np.float64)
+        self.ctx.check(load_library().precond_get_factors(self.ctx._h, self._h, T.ctypes.data, A.ctypes.data))
+        return T, A
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().precond_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def precond_build(C, sigma: float, lam: float, jitter: float = 0.0, ctx: Optional[Context] = None) -> Preconditioner:
+    return Preconditioner(C, sigma, lam, jitter, ctx)
+
+
+def falkon_linop(precond: Preconditioner, X, C, sigma: float, lam: float, beta) -> torch.Tensor:
+    """Preconditioned operator of Eq. 9 applied to beta (float64, M x t)."""
+    ctx = precond.ctx
+    X, n, d, ldx, C, M, ldc = _geom(X, C)
+    if not (beta.is_cuda and beta.dtype == torch.float64):
+        raise TypeError("beta must be a float64 tensor on the GPU")
+    sq = beta.dim() == 1
+    b2 = beta.reshape(M, -1).contiguous()
+    t = b2.shape[1]
+    out = torch.empty_like(b2)
+    ctx.check(load_library().falkon_linop(ctx._h, precond._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc,
+                                          float(sigma), float(lam), b2.data_ptr(), t, out.data_ptr()))
+    return out[:, 0] if sq else out
+
+
+def falkon_fit(X, Y, C, sigma: float, lam: float, iters: int, jitter: float = 0.0, return_resid: bool = False,
+               ctx: Optional[Context] = None):
+    """alpha (M x t) after exactly `iters` preconditioned CG steps (Alg. 1)."""
+    import numpy as np
+
+    ctx = ctx or default_context()
+    X, n, d, ldx, C, M, ldc = _geom(X, C)
+    Y, t, sq = _cols(Y, n, "Y")
+    alpha = torch.empty(M, t, device=X.device, dtype=torch.float32)
+    resid = np.zeros((iters + 1, t), dtype=np.float64)
+    ctx.check(load_library().falkon_fit(ctx._h, X.data_ptr(), n, d, ldx, Y.data_ptr(), t, C.data_ptr(), M, ldc,
+                                        float(sigma), float(lam), float(jitter), int(iters), alpha.data_ptr(),
+                                        resid.ctypes.data))
+    if sq:
+        alpha, resid = alpha[:, 0], resid[:, 0]
+    return (alpha, resid) if return_resid else alpha
+
+
+def falkon_predict(Xtest, C, sigma: float, alpha, ctx: Optional[Context] = None) -> torch.Tensor:
+    """out = k(Xtest, C) alpha (Eq. 4)."""
+    ctx = ctx or default_context()
+    Xt, n, d, ldx, C, M, ldc = _geom(Xtest, C)
+    A, t, sq = _cols(alpha, M, "alpha")
+    out = torch.empty(n, t, device=Xt.device, dtype=torch.float32)
+    ctx.check(load_library().falkon_predict(ctx._h, Xt.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc, float(sigma),
+                                            A.data_ptr(), t, out.data_ptr()))
+    return out[:, 0] if sq else out

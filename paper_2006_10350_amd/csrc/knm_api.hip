@@ -1,0 +1,310 @@
+// C ABI of libknm: context, workspace and the kernel-matrix-vector products.
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "knm_internal.h"
+
+namespace knm {
+
+int fail(knm_ctx *ctx, int status, const char *what, hipError_t e)
+{
+    if (ctx) {
+        ctx->last_error = what ? what : "";
+        if (e != hipSuccess) {
+            ctx->last_error += ": ";
+            ctx->last_error += hipGetErrorString(e);
+        }
+    }
+    return status;
+}
+
+int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need)
+{
+    if (*cur >= need) return KNM_OK;
+    if (*buf) {
+        hipError_t e = hipFree(*buf);
+        *buf = nullptr;
+        *cur = 0;
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipFree(workspace)", e);
+    }
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, need);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, KNM_ALLOC, "hipMalloc(workspace)", e);
+    }
+    *buf = static_cast<float *>(p);
+    *cur = need;
+    return KNM_OK;
+}
+
+// Chunking of the stream dimension.  More chunks = more workgroups (needed when there
+// are few fixed blocks) and shorter fp32 running sums; each chunk costs one partial
+// vector that the merge pass adds up in fp64.
+int64_t choose_chunks(int64_t nF, int64_t nS, int d, int64_t *chunk_len)
+{
+    const int64_t stage = stage_points();
+    const int64_t blocks = (nF + fixed_per_block(d) - 1) / fixed_per_block(d);
+    const int64_t target_wgs = 4096;       // several waves of workgroups over 256 CUs
+    const int64_t min_len = 16 * stage;    // amortise the per-workgroup prologue/epilogue
+    const int64_t max_len = (int64_t)1 << 18; // bound the length of a per-lane fp32 running sum
+    int64_t chunks = (target_wgs + blocks - 1) / blocks;
+    const int64_t max_chunks_by_len = (nS + min_len - 1) / min_len;
+    if (chunks > max_chunks_by_len) chunks = max_chunks_by_len;
+    const int64_t min_chunks_by_len = (nS + max_len - 1) / max_len;
+    if (chunks < min_chunks_by_len) chunks = min_chunks_by_len;
+    if (chunks < 1) chunks = 1;
+    int64_t len = (nS + chunks - 1) / chunks;
+    len = (len + stage - 1) / stage * stage;
+    chunks = (nS + len - 1) / len;
+    *chunk_len = len;
+    return chunks;
+}
+
+static bool bad_geom(const void *X, int64_t n, int d, int64_t ldx, const void *C, int64_t M, int64_t ldc,
+                     float sigma, int t)
+{
+    return !X || !C || n <= 0 || M <= 0 || d <= 0 || t <= 0 || ldx < d || ldc < d || !(sigma > 0.0f);
+}
+
+// out[f, c] = sum_s k(F_f, S_s) vec[s, c] wgt[s]  for c < t (all arrays leading dimension t)
+static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const float *S, int64_t nS, int64_t lds,
+                 int d, float sigma, const float *vec, const float *wgt, int t, float *out, hipEvent_t after_sweep)
+{
+    int64_t chunk_len = 0;
+    const int64_t chunks = choose_chunks(nF, nS, d, &chunk_len);
+    if (chunks > 65535) return fail(ctx, KNM_UNSUPPORTED, "too many stream chunks");
+    float *part = nullptr;
+    if (chunks > 1) {
+        int st = ensure(ctx, &ctx->part_buf, &ctx->part_bytes, sizeof(float) * (size_t)chunks * nF * t);
+        if (st) return st;
+        part = ctx->part_buf;
+    }
+    for (int c = 0; c < t; ++c) {
+        SweepArgs a;
+        a.F = F; a.nF = nF; a.ldf = ldf;
+        a.S = S; a.nS = nS; a.lds = lds;
+        a.d = d;
+        a.vec = vec + c; a.ldv = t;
+        a.wgt = wgt;
+        a.out = (chunks > 1) ? part + c : out + c;
+        a.ldo = t;
+        a.chunk_stride = nF * t;
+        a.chunk_len = chunk_len;
+        a.n_chunks = chunks;
+        a.sigma = sigma;
+        hipError_t e = launch_sweep(a, ctx->stream);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "launch_sweep", e);
+    }
+    if (after_sweep) (void)hipEventRecord(after_sweep, ctx->stream);
+    if (chunks > 1) {
+        hipError_t e = launch_merge(part, chunks, nF * t, 1, out, 1, nF * t, ctx->stream);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "launch_merge", e);
+    }
+    return KNM_OK;
+}
+
+static void mark(knm_ctx *ctx, int i)
+{
+    if (ctx->timing) {
+        (void)hipEventRecord(ctx->ev[i], ctx->stream);
+        ctx->ev_used[i] = true;
+    }
+}
+
+static void begin_timing(knm_ctx *ctx)
+{
+    for (int i = 0; i < 5; ++i) ctx->ev_used[i] = false;
+    mark(ctx, 0);
+}
+
+int do_knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
+             int64_t ldc, float sigma, const float *V, int t, float *W)
+{
+    return sweep(ctx, X, n, ldx, C, M, ldc, d, sigma, V, nullptr, t, W, nullptr);
+}
+
+int do_knm_t_w(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
+               int64_t ldc, float sigma, const float *Wv, const float *wgt, int t, float *U)
+{
+    hipEvent_t ev = nullptr;
+    if (ctx->timing) {
+        ev = ctx->ev[2];
+        ctx->ev_used[2] = true;
+    }
+    return sweep(ctx, C, M, ldc, X, n, ldx, d, sigma, Wv, wgt, t, U, ev);
+}
+
+} // namespace knm
+
+using namespace knm;
+
+extern "C" {
+
+int knm_create(knm_ctx **out, int device, void *hip_stream)
+{
+    if (!out) return KNM_INVALID_ARG;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return KNM_INVALID_ARG;
+    if (hipSetDevice(device) != hipSuccess) return KNM_HIP_ERROR;
+    knm_ctx *ctx = new (std::nothrow) knm_ctx();
+    if (!ctx) return KNM_ALLOC;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    for (int i = 0; i < 5; ++i) {
+        if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
+            delete ctx;
+            return KNM_HIP_ERROR;
+        }
+    }
+    *out = ctx;
+    return KNM_OK;
+}
+
+int knm_destroy(knm_ctx *ctx)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->w_buf) (void)hipFree(ctx->w_buf);
+    if (ctx->part_buf) (void)hipFree(ctx->part_buf);
+    for (int i = 0; i < 5; ++i)
+        if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+    extern void knm_solver_release(knm_ctx *);
+    knm_solver_release(ctx);
+    delete ctx;
+    return KNM_OK;
+}
+
+const char *knm_strerror(int status)
+{
+    switch (status) {
+    case KNM_OK: return "ok";
+    case KNM_INVALID_ARG: return "invalid argument";
+    case KNM_UNSUPPORTED: return "shape not supported by the compiled kernels";
+    case KNM_ALLOC: return "device workspace allocation failed";
+    case KNM_HIP_ERROR: return "HIP runtime or library error";
+    case KNM_NOT_PD: return "matrix not positive definite in Cholesky factorisation";
+    default: return "unknown status";
+    }
+}
+
+const char *knm_last_error(const knm_ctx *ctx) { return ctx ? ctx->last_error.c_str() : ""; }
+
+int knm_max_d(void) { return knm::max_d(); }
+int knm_max_t(void) { return 64; }
+
+size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
+{
+    if (n <= 0 || M <= 0 || d <= 0 || t <= 0) return 0;
+    int64_t len = 0;
+    size_t bytes = sizeof(float) * (size_t)n * t; // W
+    const int64_t c1 = choose_chunks(n, M, d, &len);
+    const int64_t c2 = choose_chunks(M, n, d, &len);
+    size_t p1 = c1 > 1 ? sizeof(float) * (size_t)c1 * n * t : 0;
+    size_t p2 = c2 > 1 ? sizeof(float) * (size_t)c2 * M * t : 0;
+    return bytes + (p1 > p2 ? p1 : p2);
+}
+
+static int check_common(knm_ctx *ctx, const void *X, int64_t n, int d, int64_t ldx, const void *C, int64_t M,
+                        int64_t ldc, float sigma, int t)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (bad_geom(X, n, d, ldx, C, M, ldc, sigma, t)) return fail(ctx, KNM_INVALID_ARG, "bad shape or pointer");
+    if (d > knm_max_d() || t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "d or t above compiled maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    return KNM_OK;
+}
+
+int knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M, int64_t ldc,
+          float sigma, const float *V, int t, float *W)
+{
+    int st = check_common(ctx, X, n, d, ldx, C, M, ldc, sigma, t);
+    if (st) return st;
+    if (!V || !W) return fail(ctx, KNM_INVALID_ARG, "null vector");
+    begin_timing(ctx);
+    st = do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, V, t, W);
+    mark(ctx, 1);
+    mark(ctx, 4);
+    return st;
+}
+
+static int prod_impl(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
+                     int64_t ldc, float sigma, const float *dw, const float *V, int t, float *W_or_null, float *U)
+{
+    int st = check_common(ctx, X, n, d, ldx, C, M, ldc, sigma, t);
+    if (st) return st;
+    if (!V || !U) return fail(ctx, KNM_INVALID_ARG, "null vector");
+    float *W = W_or_null;
+    if (!W) {
+        st = ensure(ctx, &ctx->w_buf, &ctx->w_bytes, sizeof(float) * (size_t)n * t);
+        if (st) return st;
+        W = ctx->w_buf;
+    }
+    begin_timing(ctx);
+    st = do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, V, t, W);
+    if (st) return st;
+    mark(ctx, 1);
+    st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, W, dw, t, U);
+    if (st) return st;
+    mark(ctx, 3);
+    mark(ctx, 4);
+    return KNM_OK;
+}
+
+int knm_prod(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M, int64_t ldc,
+             float sigma, const float *V, int t, float *W_or_null, float *U)
+{
+    return prod_impl(ctx, X, n, d, ldx, C, M, ldc, sigma, nullptr, V, t, W_or_null, U);
+}
+
+int knm_prod_weighted(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
+                      int64_t ldc, float sigma, const float *dw, const float *V, int t, float *U)
+{
+    if (ctx && !dw) return fail(ctx, KNM_INVALID_ARG, "null weights");
+    return prod_impl(ctx, X, n, d, ldx, C, M, ldc, sigma, dw, V, t, nullptr, U);
+}
+
+int knm_t_y(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M, int64_t ldc,
+            float sigma, const float *Y, int t, float *R)
+{
+    int st = check_common(ctx, X, n, d, ldx, C, M, ldc, sigma, t);
+    if (st) return st;
+    if (!Y || !R) return fail(ctx, KNM_INVALID_ARG, "null vector");
+    begin_timing(ctx);
+    mark(ctx, 1);
+    st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, Y, nullptr, t, R);
+    if (st) return st;
+    mark(ctx, 3);
+    mark(ctx, 4);
+    return KNM_OK;
+}
+
+int knm_set_timing(knm_ctx *ctx, int enabled)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    ctx->timing = enabled != 0;
+    for (int i = 0; i < 5; ++i) ctx->ev_used[i] = false;
+    return KNM_OK;
+}
+
+int knm_get_timing(knm_ctx *ctx, float *ms)
+{
+    if (!ctx || !ms) return KNM_INVALID_ARG;
+    for (int i = 0; i < 4; ++i) ms[i] = 0.0f;
+    if (!ctx->ev_used[0] || !ctx->ev_used[4]) return fail(ctx, KNM_INVALID_ARG, "no timed call recorded");
+    hipError_t e = hipEventSynchronize(ctx->ev[4]);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipEventSynchronize", e);
+    // events: 0 start, 1 after row sweep, 2 after column sweep kernels, 3 after merge, 4 end
+    auto span = [&](int a, int b, float *dst) {
+        if (ctx->ev_used[a] && ctx->ev_used[b]) (void)hipEventElapsedTime(dst, ctx->ev[a], ctx->ev[b]);
+    };
+    span(0, 1, &ms[0]);
+    span(1, 2, &ms[1]);
+    span(2, 3, &ms[2]);
+    span(0, 4, &ms[3]);
+    return KNM_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,76 @@
+// Internal declarations shared by the HIP sources of libknm (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "knm.h"
+
+namespace knm {
+
+// ---- tile engine (knm_tile.hip) ---------------------------------------------------
+//
+// One engine serves both sweeps of K_nm^T (K_nm v) because the Gaussian kernel is
+// symmetric in its two arguments:
+//   out[f] = sum_s k(F_f, S_s) * vec[s]
+// with "fixed" points F held in registers as the MFMA A operand and "stream" points S
+// staged through LDS as the B operand.  Row sweep: F = X, S = C, vec = v.  Column
+// sweep: F = C, S = X, vec = w, with the stream cut into chunks whose partial results
+// are merged afterwards in a fixed order.
+struct SweepArgs {
+    const float *F;   // fixed points, nF x d, leading dimension ldf
+    int64_t nF, ldf;
+    const float *S;   // stream points, nS x d, leading dimension lds
+    int64_t nS, lds;
+    int d;
+    const float *vec; // stream-side vector: element of stream point i is vec[i * ldv]
+    int64_t ldv;
+    const float *wgt; // optional per-stream-point weight multiplied into vec (may be null)
+    float *out;       // out[chunk * chunk_stride + f * ldo]
+    int64_t ldo, chunk_stride;
+    int64_t chunk_len; // stream points per chunk (multiple of the stage size)
+    int64_t n_chunks;
+    float sigma;
+};
+
+int max_d();
+int64_t stage_points();                 // stream points staged per LDS buffer
+int64_t fixed_per_block(int d);         // fixed points one workgroup covers
+hipError_t launch_sweep(const SweepArgs &a, hipStream_t stream);
+// out[j * ldo] = sum over chunks of part[chunk * chunk_stride + j * ldp], summed in fp64
+hipError_t launch_merge(const float *part, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
+                        float *out, int64_t ldo, int64_t count, hipStream_t stream);
+// w[i * ld + c] *= dw[i] for c < t
+hipError_t launch_row_scale(float *w, int64_t n, int t, const float *dw, hipStream_t stream);
+
+} // namespace knm
+
+struct knm_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    // workspace grown on demand and kept until knm_destroy
+    float *w_buf = nullptr;
+    size_t w_bytes = 0;
+    float *part_buf = nullptr;
+    size_t part_bytes = 0;
+    // timing
+    bool timing = false;
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    bool ev_used[5] = {false, false, false, false, false};
+    std::string last_error;
+    // solver handles (created lazily by knm_solver.hip)
+    void *blas = nullptr;
+};
+
+namespace knm {
+int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need);
+int fail(knm_ctx *ctx, int status, const char *what, hipError_t e = hipSuccess);
+// number of stream chunks used for a column sweep over nS stream points, nF fixed points
+int64_t choose_chunks(int64_t nF, int64_t nS, int d, int64_t *chunk_len);
+int do_knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
+             int64_t ldc, float sigma, const float *V, int t, float *W);
+int do_knm_t_w(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
+               int64_t ldc, float sigma, const float *Wv, const float *wgt, int t, float *U);
+} // namespace knm

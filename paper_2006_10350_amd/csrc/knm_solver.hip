@@ -1,0 +1,413 @@
+// Preconditioner, preconditioned operator, conjugate gradient and predictor (Alg. 1).
+//
+// Everything here is fp64 and runs once per fit or is O(M^2) per iteration; the
+// O(n M) work of every iteration is the fp32 kernel product of knm_tile.hip.
+// Factorisations and triangular solves use rocSOLVER / rocBLAS on column-major
+// storage: T and A are upper triangular with T^T T = K_MM + jitter I and
+// A^T A = T T^T / M + lambda I  (Eq. 7 with K_mm = T^T T).
+#include <rocblas/rocblas.h>
+#include <rocsolver/rocsolver.h>
+
+#include <cmath>
+#include <new>
+#include <vector>
+
+#include "knm_internal.h"
+
+struct knm_precond {
+    int device = 0;
+    int64_t M = 0;
+    double lambda = 0.0, jitter = 0.0;
+    double *T = nullptr; // column-major M x M, upper triangle valid, strict lower zero
+    double *A = nullptr;
+};
+
+namespace {
+
+using namespace knm;
+
+// K[i, j] = exp(-|c_i - c_j|^2 / (2 sigma^2)) + jitter [i == j], fp64, direct differences.
+__global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_t ldc, double inv2s2, double jitter,
+                           double *__restrict__ K)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = (int64_t)blockIdx.y * blockDim.y + threadIdx.y;
+    if (i >= M || j >= M) return;
+    const float *ci = C + i * ldc;
+    const float *cj = C + j * ldc;
+    double s = 0.0;
+    for (int k = 0; k < d; ++k) {
+        double diff = (double)ci[k] - (double)cj[k];
+        s += diff * diff;
+    }
+    double v = exp(-s * inv2s2);
+    if (i == j) v += jitter;
+    K[i * M + j] = v; // symmetric, so row- vs column-major does not matter
+}
+
+// zero the strict lower triangle (column-major) and optionally add `shift` to the diagonal
+__global__ void tri_fix_kernel(double *A, int64_t M, double shift, int zero_lower)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; // row
+    const int64_t j = (int64_t)blockIdx.y * blockDim.y + threadIdx.y; // column
+    if (i >= M || j >= M) return;
+    if (i > j && zero_lower) A[i + j * M] = 0.0;
+    if (i == j && shift != 0.0) A[i + j * M] += shift;
+}
+
+// row-major (rows x t, leading dimension t) float  <->  column-major (rows x t) double
+__global__ void f32_rows_to_f64_cols(const float *__restrict__ src, int64_t rows, int t, double *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * t) return;
+    const int64_t r = i / t;
+    const int c = (int)(i % t);
+    dst[r + (int64_t)c * rows] = (double)src[i];
+}
+__global__ void f64_cols_to_f32_rows(const double *__restrict__ src, int64_t rows, int t, float *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * t) return;
+    const int64_t r = i / t;
+    const int c = (int)(i % t);
+    dst[i] = (float)src[r + (int64_t)c * rows];
+}
+__global__ void f64_rows_to_cols(const double *__restrict__ src, int64_t rows, int t, double *__restrict__ dst, int back)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * t) return;
+    const int64_t r = i / t;
+    const int c = (int)(i % t);
+    if (back) dst[i] = src[r + (int64_t)c * rows];
+    else dst[r + (int64_t)c * rows] = src[i];
+}
+
+inline dim3 grid1(int64_t n, int threads = 256) { return dim3((unsigned)((n + threads - 1) / threads)); }
+
+int blas_handle(knm_ctx *ctx, rocblas_handle *h)
+{
+    if (!ctx->blas) {
+        rocblas_handle nh = nullptr;
+        if (rocblas_create_handle(&nh) != rocblas_status_success) return fail(ctx, KNM_HIP_ERROR, "rocblas_create_handle");
+        ctx->blas = nh;
+    }
+    *h = static_cast<rocblas_handle>(ctx->blas);
+    if (rocblas_set_stream(*h, ctx->stream) != rocblas_status_success) return fail(ctx, KNM_HIP_ERROR, "rocblas_set_stream");
+    if (rocblas_set_pointer_mode(*h, rocblas_pointer_mode_host) != rocblas_status_success)
+        return fail(ctx, KNM_HIP_ERROR, "rocblas_set_pointer_mode");
+    return KNM_OK;
+}
+
+struct DevBuf {
+    void *p = nullptr;
+    ~DevBuf() { if (p) (void)hipFree(p); }
+    int alloc(knm_ctx *ctx, size_t bytes)
+    {
+        hipError_t e = hipMalloc(&p, bytes ? bytes : 1);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            p = nullptr;
+            return fail(ctx, KNM_ALLOC, "hipMalloc", e);
+        }
+        return KNM_OK;
+    }
+    template <class T> T *as() { return static_cast<T *>(p); }
+};
+
+// B <- op(R)^-1 B for column-major B (M x t)
+int tri_solve(knm_ctx *ctx, rocblas_handle h, const double *R, int64_t M, bool trans, double *B, int t)
+{
+    rocblas_status s;
+    const rocblas_operation op = trans ? rocblas_operation_transpose : rocblas_operation_none;
+    if (t == 1) {
+        s = rocblas_dtrsv(h, rocblas_fill_upper, op, rocblas_diagonal_non_unit, (rocblas_int)M, R, (rocblas_int)M, B, 1);
+    } else {
+        const double one = 1.0;
+        s = rocblas_dtrsm(h, rocblas_side_left, rocblas_fill_upper, op, rocblas_diagonal_non_unit, (rocblas_int)M, t,
+                          &one, R, (rocblas_int)M, B, (rocblas_int)M);
+    }
+    if (s != rocblas_status_success) return fail(ctx, KNM_HIP_ERROR, "rocblas triangular solve");
+    return KNM_OK;
+}
+
+// Workspace of one application of the operator of Eq. 9 on column-major fp64 vectors.
+struct LinopWork {
+    DevBuf v, z32, u32;
+    int alloc(knm_ctx *ctx, int64_t M, int t)
+    {
+        int st = v.alloc(ctx, sizeof(double) * M * t);
+        if (!st) st = z32.alloc(ctx, sizeof(float) * M * t);
+        if (!st) st = u32.alloc(ctx, sizeof(float) * M * t);
+        return st;
+    }
+};
+
+// out <- A^-T ( T^-T K^T K T^-1 A^-1 beta + lambda n A^-1 beta );  beta, out column-major, may not alias
+int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &wk, const float *X, int64_t n, int d,
+               int64_t ldx, const float *C, int64_t M, int64_t ldc, float sigma, double lambda, const double *beta,
+               int t, double *out)
+{
+    const size_t bytes = sizeof(double) * M * t;
+    double *v = wk.v.as<double>();
+    hipError_t e = hipMemcpyAsync(v, beta, bytes, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
+    int st = tri_solve(ctx, h, p->A, M, false, v, t); // v = A^-1 beta
+    if (st) return st;
+    e = hipMemcpyAsync(out, v, bytes, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
+    st = tri_solve(ctx, h, p->T, M, false, out, t); // z = T^-1 v
+    if (st) return st;
+    hipLaunchKernelGGL(f64_cols_to_f32_rows, grid1(M * t), dim3(256), 0, ctx->stream, out, M, t, wk.z32.as<float>());
+    // c = K_nm^T (K_nm z), the O(n M) step
+    st = ensure(ctx, &ctx->w_buf, &ctx->w_bytes, sizeof(float) * (size_t)n * t);
+    if (st) return st;
+    st = do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, wk.z32.as<float>(), t, ctx->w_buf);
+    if (st) return st;
+    st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, ctx->w_buf, nullptr, t, wk.u32.as<float>());
+    if (st) return st;
+    hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(M * t), dim3(256), 0, ctx->stream, wk.u32.as<float>(), M, t, out);
+    st = tri_solve(ctx, h, p->T, M, true, out, t); // T^-T c
+    if (st) return st;
+    const double ln = lambda * (double)n;
+    if (rocblas_daxpy(h, (rocblas_int)(M * t), &ln, v, 1, out, 1) != rocblas_status_success)
+        return fail(ctx, KNM_HIP_ERROR, "rocblas_daxpy");
+    return tri_solve(ctx, h, p->A, M, true, out, t); // A^-T (...)
+}
+
+} // namespace
+
+extern "C" {
+
+void knm_solver_release(knm_ctx *ctx)
+{
+    if (ctx && ctx->blas) {
+        (void)rocblas_destroy_handle(static_cast<rocblas_handle>(ctx->blas));
+        ctx->blas = nullptr;
+    }
+}
+
+int precond_free(knm_precond *p)
+{
+    if (!p) return KNM_INVALID_ARG;
+    (void)hipSetDevice(p->device);
+    if (p->T) (void)hipFree(p->T);
+    if (p->A) (void)hipFree(p->A);
+    delete p;
+    return KNM_OK;
+}
+
+int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma, double lambda,
+                  double jitter, knm_precond **out, int64_t *bad_pivot_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!out) return fail(ctx, KNM_INVALID_ARG, "null output");
+    *out = nullptr;
+    if (bad_pivot_or_null) *bad_pivot_or_null = 0;
+    if (!C || M <= 0 || d <= 0 || ldc < d || !(sigma > 0.0f) || !(lambda >= 0.0) || !(jitter >= 0.0))
+        return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
+    if (M > 2000000000LL / 1) return fail(ctx, KNM_UNSUPPORTED, "M too large");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    rocblas_handle h;
+    int st = blas_handle(ctx, &h);
+    if (st) return st;
+
+    knm_precond *p = new (std::nothrow) knm_precond();
+    if (!p) return fail(ctx, KNM_ALLOC, "host allocation");
+    p->device = ctx->device;
+    p->M = M;
+    p->lambda = lambda;
+    p->jitter = jitter;
+    const size_t bytes = sizeof(double) * (size_t)M * (size_t)M;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&p->T), bytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->A), bytes);
+    DevBuf info;
+    if (e != hipSuccess || info.alloc(ctx, sizeof(rocblas_int))) {
+        (void)hipGetLastError();
+        precond_free(p);
+        return fail(ctx, KNM_ALLOC, "hipMalloc(preconditioner)", e);
+    }
+    auto bail = [&](int status, const char *what) {
+        precond_free(p);
+        return fail(ctx, status, what);
+    };
+
+    const dim3 tb(32, 8);
+    const dim3 tg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
+    const double inv2s2 = 1.0 / (2.0 * (double)sigma * (double)sigma);
+    hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, inv2s2, jitter, p->T);
+    if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "kmm_kernel launch");
+
+    rocblas_int host_info = 0;
+    if (rocsolver_dpotrf(h, rocblas_fill_upper, (rocblas_int)M, p->T, (rocblas_int)M, info.as<rocblas_int>()) !=
+        rocblas_status_success)
+        return bail(KNM_HIP_ERROR, "rocsolver_dpotrf(T)");
+    e = hipMemcpyAsync(&host_info, info.p, sizeof(rocblas_int), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return bail(KNM_HIP_ERROR, "dpotrf(T) status copy");
+    if (host_info != 0) {
+        if (bad_pivot_or_null) *bad_pivot_or_null = host_info;
+        return bail(KNM_NOT_PD, "K_MM + jitter I is not positive definite");
+    }
+    const dim3 fb(32, 8);
+    const dim3 fg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
+    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->T, M, 0.0, 1);
+
+    // A <- T T^T / M (upper triangle), then + lambda I, then factorise
+    const double alpha = 1.0 / (double)M, beta = 0.0;
+    if (rocblas_dsyrk(h, rocblas_fill_upper, rocblas_operation_none, (rocblas_int)M, (rocblas_int)M, &alpha, p->T,
+                      (rocblas_int)M, &beta, p->A, (rocblas_int)M) != rocblas_status_success)
+        return bail(KNM_HIP_ERROR, "rocblas_dsyrk");
+    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, lambda, 0);
+    if (rocsolver_dpotrf(h, rocblas_fill_upper, (rocblas_int)M, p->A, (rocblas_int)M, info.as<rocblas_int>()) !=
+        rocblas_status_success)
+        return bail(KNM_HIP_ERROR, "rocsolver_dpotrf(A)");
+    e = hipMemcpyAsync(&host_info, info.p, sizeof(rocblas_int), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return bail(KNM_HIP_ERROR, "dpotrf(A) status copy");
+    if (host_info != 0) {
+        if (bad_pivot_or_null) *bad_pivot_or_null = -(int64_t)host_info;
+        return bail(KNM_NOT_PD, "T T^T / M + lambda I is not positive definite");
+    }
+    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, 0.0, 1);
+    if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "tri_fix_kernel launch");
+    *out = p;
+    return KNM_OK;
+}
+
+int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, double *A_host)
+{
+    if (!ctx || !p) return KNM_INVALID_ARG;
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    const int64_t M = p->M;
+    std::vector<double> tmp((size_t)M * M);
+    const double *src[2] = {p->T, p->A};
+    double *dst[2] = {T_host, A_host};
+    for (int k = 0; k < 2; ++k) {
+        if (!dst[k]) continue;
+        hipError_t e = hipStreamSynchronize(ctx->stream);
+        if (e == hipSuccess) e = hipMemcpy(tmp.data(), src[k], sizeof(double) * M * M, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpy(factor)", e);
+        for (int64_t i = 0; i < M; ++i)
+            for (int64_t j = 0; j < M; ++j) dst[k][i * M + j] = (j >= i) ? tmp[i + j * M] : 0.0;
+    }
+    return KNM_OK;
+}
+
+int falkon_linop(knm_ctx *ctx, const knm_precond *p, const float *X, int64_t n, int d, int64_t ldx, const float *C,
+                 int64_t M, int64_t ldc, float sigma, double lambda, const double *beta, int t, double *out)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!p || !X || !C || !beta || !out || n <= 0 || M <= 0 || d <= 0 || t <= 0 || ldx < d || ldc < d ||
+        !(sigma > 0.0f) || p->M != M)
+        return fail(ctx, KNM_INVALID_ARG, "bad linop argument");
+    if (d > knm_max_d() || t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "d or t above compiled maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    rocblas_handle h;
+    int st = blas_handle(ctx, &h);
+    if (st) return st;
+    LinopWork wk;
+    DevBuf bc, oc;
+    st = wk.alloc(ctx, M, t);
+    if (!st) st = bc.alloc(ctx, sizeof(double) * M * t);
+    if (!st) st = oc.alloc(ctx, sizeof(double) * M * t);
+    if (st) return st;
+    hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, beta, M, t, bc.as<double>(), 0);
+    st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, bc.as<double>(), t, oc.as<double>());
+    if (st) return st;
+    hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, oc.as<double>(), M, t, out, 1);
+    hipError_t e = hipStreamSynchronize(ctx->stream); // temporaries are freed on return
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "falkon_linop", e);
+    return KNM_OK;
+}
+
+int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *Y, int t, const float *C,
+               int64_t M, int64_t ldc, float sigma, double lambda, double jitter, int iters, float *alpha,
+               double *resid_norms_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!X || !Y || !C || !alpha || n <= 0 || M <= 0 || d <= 0 || t <= 0 || iters <= 0 || ldx < d || ldc < d ||
+        !(sigma > 0.0f) || !(lambda >= 0.0) || !(jitter >= 0.0))
+        return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
+    if (d > knm_max_d() || t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "d or t above compiled maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    rocblas_handle h;
+    int st = blas_handle(ctx, &h);
+    if (st) return st;
+
+    knm_precond *p = nullptr;
+    st = precond_build(ctx, C, M, d, ldc, sigma, lambda, jitter, &p, nullptr);
+    if (st) return st;
+    struct Guard {
+        knm_precond *p;
+        ~Guard() { precond_free(p); }
+    } guard{p};
+
+    const int64_t len = M * t;
+    LinopWork wk;
+    DevBuf beta, r, pv, q, r32;
+    st = wk.alloc(ctx, M, t);
+    if (!st) st = beta.alloc(ctx, sizeof(double) * len);
+    if (!st) st = r.alloc(ctx, sizeof(double) * len);
+    if (!st) st = pv.alloc(ctx, sizeof(double) * len);
+    if (!st) st = q.alloc(ctx, sizeof(double) * len);
+    if (!st) st = r32.alloc(ctx, sizeof(float) * len);
+    if (st) return st;
+    double *db = beta.as<double>(), *dr = r.as<double>(), *dp = pv.as<double>(), *dq = q.as<double>();
+
+    // rhs = A^-T T^-T K_nm^T Y
+    st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, Y, nullptr, t, r32.as<float>());
+    if (st) return st;
+    hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(len), dim3(256), 0, ctx->stream, r32.as<float>(), M, t, dr);
+    st = tri_solve(ctx, h, p->T, M, true, dr, t);
+    if (!st) st = tri_solve(ctx, h, p->A, M, true, dr, t);
+    if (st) return st;
+    hipError_t e = hipMemsetAsync(db, 0, sizeof(double) * len, ctx->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(dp, dr, sizeof(double) * len, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "CG initialisation", e);
+
+    auto blas_ok = [&](rocblas_status s) { return s == rocblas_status_success; };
+    std::vector<double> rho(t), pq(t);
+    for (int c = 0; c < t; ++c) {
+        if (!blas_ok(rocblas_ddot(h, (rocblas_int)M, dr + c * M, 1, dr + c * M, 1, &rho[c])))
+            return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
+        if (resid_norms_or_null) resid_norms_or_null[c] = std::sqrt(rho[c]);
+    }
+    for (int it = 0; it < iters; ++it) {
+        st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, dp, t, dq);
+        if (st) return st;
+        for (int c = 0; c < t; ++c) {
+            double *pc = dp + c * M, *qc = dq + c * M, *rc = dr + c * M, *bc = db + c * M;
+            if (!blas_ok(rocblas_ddot(h, (rocblas_int)M, pc, 1, qc, 1, &pq[c]))) return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
+            const double a = (pq[c] != 0.0) ? rho[c] / pq[c] : 0.0;
+            const double ma = -a;
+            double rn = 0.0;
+            if (!blas_ok(rocblas_daxpy(h, (rocblas_int)M, &a, pc, 1, bc, 1)) ||
+                !blas_ok(rocblas_daxpy(h, (rocblas_int)M, &ma, qc, 1, rc, 1)) ||
+                !blas_ok(rocblas_ddot(h, (rocblas_int)M, rc, 1, rc, 1, &rn)))
+                return fail(ctx, KNM_HIP_ERROR, "rocblas CG update");
+            const double b = (rho[c] != 0.0) ? rn / rho[c] : 0.0;
+            const double one = 1.0;
+            if (!blas_ok(rocblas_dscal(h, (rocblas_int)M, &b, pc, 1)) ||
+                !blas_ok(rocblas_daxpy(h, (rocblas_int)M, &one, rc, 1, pc, 1)))
+                return fail(ctx, KNM_HIP_ERROR, "rocblas CG update");
+            rho[c] = rn;
+            if (resid_norms_or_null) resid_norms_or_null[(int64_t)(it + 1) * t + c] = std::sqrt(rn);
+        }
+    }
+    // alpha = T^-1 A^-1 beta
+    st = tri_solve(ctx, h, p->A, M, false, db, t);
+    if (!st) st = tri_solve(ctx, h, p->T, M, false, db, t);
+    if (st) return st;
+    hipLaunchKernelGGL(f64_cols_to_f32_rows, grid1(len), dim3(256), 0, ctx->stream, db, M, t, alpha);
+    e = hipStreamSynchronize(ctx->stream); // temporaries are freed on return
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "falkon_fit", e);
+    return KNM_OK;
+}
+
+int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64_t ldx, const float *C, int64_t M,
+                   int64_t ldc, float sigma, const float *alpha, int t, float *out)
+{
+    return knm_v(ctx, Xtest, ntest, d, ldx, C, M, ldc, sigma, alpha, t, out);
+}
+
+} // extern "C"

@@ -1,0 +1,170 @@
+"""GPU parity: the HIP kernel-matrix-vector products against the fp64 CPU oracle,
+element by element on the same seeded inputs, through the C ABI (ctypes binding).
+
+Bar: relative L2 error <= 1e-4 per product (the stated target); measured errors are
+~1e-6, so the assertions use 2e-5 to catch regressions early.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+TIGHT = 2e-5
+
+
+def rel_l2(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def _rand(n, d, seed, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return (scale * torch.randn(n, d, generator=g)).to(torch.float32)
+
+
+SHAPES = [
+    # n, M, d, t, sigma  -- several tiles plus ragged tails in every dimension
+    (1000, 300, 8, 1, 2.0),
+    (2049, 515, 28, 1, 4.0),
+    (777, 129, 9, 1, 1.5),
+    (4100, 1030, 5, 3, 1.0),
+    (515, 2049, 28, 2, 4.0),
+    (1500, 260, 1, 1, 0.7),
+    (1300, 400, 33, 1, 5.0),
+    (900, 300, 64, 1, 8.0),
+    (640, 256, 12, 10, 2.5),
+]
+
+
+@pytest.mark.parametrize("n,M,d,t,sigma", SHAPES)
+def test_products_match_oracle(knm, n, M, d, t, sigma):
+    print(f"case n={n} M={M} d={d} t={t}", flush=True)
+    X, C = _rand(n, d, 1), _rand(M, d, 2)
+    V = _rand(M, t, 3)
+    Y = _rand(n, t, 4)
+    Xd, Cd, Vd, Yd = X.cuda(), C.cuda(), V.cuda(), Y.cuda()
+    Xn, Cn = X.numpy(), C.numpy()
+
+    W = knm.knm_v(Xd, Cd, sigma, Vd).cpu().numpy()
+    assert rel_l2(W, oracle.knm_v(Xn, Cn, sigma, V.numpy())) < TIGHT
+
+    R = knm.knm_t_y(Xd, Cd, sigma, Yd).cpu().numpy()
+    assert rel_l2(R, oracle.knm_t_y(Xn, Cn, sigma, Y.numpy())) < TIGHT
+
+    U, W2 = knm.knm_prod(Xd, Cd, sigma, Vd, return_w=True)
+    Uo, Wo = oracle.knm_prod(Xn, Cn, sigma, V.numpy(), return_w=True)
+    assert rel_l2(U.cpu().numpy(), Uo) < TIGHT
+    assert rel_l2(W2.cpu().numpy(), Wo) < TIGHT
+    for c in range(t):  # per column as well as Frobenius
+        assert rel_l2(U.cpu().numpy().reshape(M, t)[:, c], np.asarray(Uo).reshape(M, t)[:, c]) < TOL
+    # without the W output the library uses its own workspace: same result bit for bit
+    U2 = knm.knm_prod(Xd, Cd, sigma, Vd)
+    assert torch.equal(U2, U)
+
+
+@pytest.mark.parametrize("kind", ["ones", "unit"])
+def test_special_vectors(knm, kind):
+    n, M, d, sigma = 3000, 700, 28, 4.0
+    X, C = _rand(n, d, 5), _rand(M, d, 6)
+    v = synth.probe_vector(M, 1, kind, j=123)
+    U = knm.knm_prod(X.cuda(), C.cuda(), sigma, v.cuda()).cpu().numpy()
+    assert rel_l2(U, oracle.knm_prod(X.numpy(), C.numpy(), sigma, v.numpy())) < TIGHT
+
+
+def test_weighted_product(knm):
+    n, M, d, sigma = 2500, 300, 9, 2.0
+    X, C, V = _rand(n, d, 7), _rand(M, d, 8), _rand(M, 2, 9)
+    dw = torch.rand(n, generator=torch.Generator().manual_seed(10)) + 0.05
+    U = knm.knm_prod_weighted(X.cuda(), C.cuda(), sigma, dw.cuda(), V.cuda()).cpu().numpy()
+    ref = oracle.knm_prod_weighted(X.numpy(), C.numpy(), sigma, dw.numpy(), V.numpy())
+    assert rel_l2(U, ref) < TIGHT
+
+
+def test_strided_points_and_determinism(knm):
+    n, M, d, sigma = 1200, 333, 10, 2.0
+    Xw = _rand(n, 16, 11).cuda()
+    Cw = _rand(M, 13, 12).cuda()
+    X, C = Xw[:, :d], Cw[:, :d]  # leading dimension larger than d, odd for C
+    V = _rand(M, 1, 13).cuda()
+    U1 = knm.knm_prod(X, C, sigma, V)
+    U2 = knm.knm_prod(X, C, sigma, V)
+    assert torch.equal(U1, U2)
+    ref = oracle.knm_prod(X.cpu().numpy(), C.cpu().numpy(), sigma, V.cpu().numpy())
+    assert rel_l2(U1.cpu().numpy(), ref) < TIGHT
+
+
+def test_degenerate_sizes(knm):
+    sigma = 1.0
+    X, C = _rand(1, 3, 14), _rand(1, 3, 15)
+    v = torch.tensor([[2.0]])
+    U = knm.knm_prod(X.cuda(), C.cuda(), sigma, v.cuda()).cpu().numpy()
+    k = oracle.gauss(X.numpy()[0], C.numpy()[0], sigma)
+    assert U.ravel()[0] == pytest.approx(2.0 * k * k, rel=1e-5)
+    # identical points: kernel exactly 1 on the diagonal, never above
+    P = _rand(200, 28, 16, scale=3.0).cuda()
+    W = knm.knm_v(P, P, 0.5, torch.ones(200, 1).cuda())  # small sigma: off-diagonal underflows to 0
+    Wn = W.cpu().numpy()
+    assert np.all(np.isfinite(Wn)) and Wn.max() <= 1.0 and Wn.min() >= 0.0
+    assert np.allclose(Wn, 1.0, atol=2e-3)
+    # far-apart points: exact zeros, no NaN / Inf
+    far = torch.zeros(64, 4)
+    far[:, 0] = 1.0e4
+    W = knm.knm_v(far.cuda(), torch.zeros(64, 4).cuda(), 1.0, torch.ones(64, 1).cuda()).cpu().numpy()
+    assert np.array_equal(W, np.zeros_like(W))
+
+
+def test_large_norm_close_pairs(knm):
+    # the cancellation hazard of the norm expansion: large |x|, small distances.
+    # With |x|^2 ~ 1e3 the fp32 expansion keeps ~1e-4 absolute accuracy on the exponent.
+    n, M, d, sigma = 2000, 256, 8, 1.0
+    base = _rand(1, d, 17) * 0.0 + 11.0
+    X = base + 0.5 * _rand(n, d, 18)
+    C = base + 0.5 * _rand(M, d, 19)
+    V = torch.ones(M, 1)
+    W = knm.knm_v(X.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
+    assert rel_l2(W, oracle.knm_v(X.numpy(), C.numpy(), sigma, V.numpy())) < 1e-3
+
+
+def test_invalid_arguments_are_rejected(knm):
+    X, C, V = _rand(10, 4, 20).cuda(), _rand(5, 4, 21).cuda(), _rand(5, 1, 22).cuda()
+    with pytest.raises(knm.KnmError) as e:
+        knm.knm_prod(X, C, -1.0, V)
+    assert e.value.status == -1
+    big = _rand(4, knm.load_library().knm_max_d() + 1, 23).cuda()
+    with pytest.raises(knm.KnmError) as e:
+        knm.knm_v(big, big, 1.0, _rand(4, 1, 24).cuda())
+    assert e.value.status == -2
+    with pytest.raises(ValueError):
+        knm.knm_v(X, _rand(5, 3, 25).cuda(), 1.0, V)
+
+
+def test_tiny_workload_full_product(knm):
+    w = synth.workload("tiny")
+    inp = synth.make_inputs(w, device="cpu")
+    X, C = inp["X"], inp["C"]
+    v = synth.probe_vector(w.M, w.t, "normal")
+    U, W = knm.knm_prod(X.cuda(), C.cuda(), w.sigma, v.cuda(), return_w=True)
+    Uo, Wo = oracle.knm_prod(X.numpy(), C.numpy(), w.sigma, v.numpy(), return_w=True)
+    assert rel_l2(W.cpu().numpy(), Wo) < TIGHT
+    assert rel_l2(U.cpu().numpy(), Uo) < TIGHT
+    R = knm.knm_t_y(X.cuda(), C.cuda(), w.sigma, inp["Y"].cuda())
+    assert rel_l2(R.cpu().numpy(), oracle.knm_t_y(X.numpy(), C.numpy(), w.sigma, inp["Y"].numpy())) < TIGHT
+
+
+@pytest.mark.parametrize("name,n_sub,M_sub", [("mid", 1 << 15, 4096), ("lowdim", 1 << 15, 4096), ("billion", 1 << 15, 4096)])
+def test_workload_shaped_sample(knm, name, n_sub, M_sub):
+    """Rows and centres drawn with a workload's distribution (heavy tails included)."""
+    w = synth.workload(name, n=n_sub, M=M_sub)
+    inp = synth.make_inputs(w, device="cpu", with_targets=False)
+    X, C = inp["X"], inp["C"]
+    v = synth.probe_vector(w.M, 1, "normal")
+    U = knm.knm_prod(X.cuda(), C.cuda(), w.sigma, v.cuda()).cpu().numpy()
+    assert rel_l2(U, oracle.knm_prod(X.numpy(), C.numpy(), w.sigma, v.numpy())) < TOL
