@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path u = K_nm^T (K_nm v) on one MI355X.
+
+A step is one full product (row sweep, column sweep, merge) on synthetic inputs that are
+resident in HBM before the timed region.  Prints ONE JSON line with the whole-job
+throughput in logical kernel entries per second (n * M per product, each entry counted
+once although the two sweeps both evaluate it), the fp32-MFMA roofline fraction of the
+tile kernel measured with HIP events on the library's stream, and the fp64 CPU oracle
+timed on a bounded row sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak: 256 CU x 256 flop/clk x 2.4 GHz
+
+
+def cpu_baseline(w, X_rows, C, v, budget_entries: float):
+    """Time the oracle's knm_prod on `X_rows` (a strided row sample) x all centres."""
+    import numpy as np
+
+    import oracle
+
+    Xn = X_rows.cpu().numpy()
+    Cn = C.cpu().numpy()
+    vn = v.cpu().numpy().astype(np.float64)
+    t0 = time.perf_counter()
+    oracle.knm_prod(Xn, Cn, w.sigma, vn)
+    dt = time.perf_counter() - t0
+    entries = Xn.shape[0] * Cn.shape[0]
+    return {
+        "value": entries / dt / 1e9,
+        "unit": "G entries/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{Xn.shape[0]} strided rows x all {Cn.shape[0]} centres, d={Xn.shape[1]}, t={vn.shape[1]}, "
+                  f"fp64, {dt:.1f} s",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="mid", help="tiny | mid | lowdim | highdim | billion")
+    ap.add_argument("--n", type=int, default=None, help="override the number of rows (same distribution)")
+    ap.add_argument("--M", type=int, default=None, help="override the number of centres")
+    ap.add_argument("--cpu-rows", type=int, default=None, help="rows of the oracle's timing sample")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (rows of X would be sharded across GPUs with one "
+              "all-reduce of the M x t result per product; not built). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2006_10350_amd as knm
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    w = synth.workload(args.workload, n=args.n, M=args.M)
+    inp = synth.make_inputs(w, device="cuda", with_targets=False)
+    X, C = inp["X"], inp["C"]
+    v = synth.probe_vector(w.M, w.t, "normal", device="cuda")
+    U = torch.empty(w.M, w.t, device="cuda", dtype=torch.float32)
+    ctx = knm.default_context()
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
+    torch.cuda.synchronize()
+
+    ctx.set_timing(True)
+    row_ms, col_ms, merge_ms = [], [], []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
+        tm = ctx.get_timing()  # HIP events on the library's stream; waits for this step
+        row_ms.append(tm["row_sweep_ms"])
+        col_ms.append(tm["col_sweep_ms"])
+        merge_ms.append(tm["merge_ms"])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ctx.set_timing(False)
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    entries = float(w.n) * float(w.M)
+    value = entries / (elapsed / args.steps) / 1e9
+
+    # the tile kernel is launched t times per sweep (once per output column), two sweeps per step
+    launches = 2 * w.t * args.steps
+    avg_launch_ms = (sum(row_ms) + sum(col_ms)) / launches
+    flop_per_launch = entries * 2.0 * w.d  # algorithmic: one evaluation of every entry, 2 d flop each
+    achieved = flop_per_launch / (avg_launch_ms * 1e-3) / 1e12
+    roofline = {
+        "bound": "mfma",
+        "kernel": "gauss_sweep_kernel",
+        "achieved": achieved,
+        "peak": PEAK_FP32_MFMA_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+        "traffic": None,
+        "avg_launch_ms": avg_launch_ms,
+        "row_sweep_ms": sum(row_ms) / len(row_ms),
+        "col_sweep_ms": sum(col_ms) / len(col_ms),
+        "merge_ms": sum(merge_ms) / len(merge_ms),
+        "flop_per_launch": flop_per_launch,
+    }
+
+    out = {
+        "metric": "G kernel-entries/s in K_nm^T(K_nm v)",
+        "value": value,
+        "unit": "G entries/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "d": w.d, "M": w.M, "t": w.t, "sigma": w.sigma,
+                   "stands_in_for": w.stands_in_for},
+        "s_per_product": ms_per_step / 1e3,
+        "mfma_frac_two_sweeps": 2.0 * entries * 2.0 * w.d / (elapsed / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu:
+        # bounded sample: about 10-30 s of oracle work on the host cores
+        rows = args.cpu_rows or max(64, int(4.0e9 * (8.0 / max(w.d, 8)) ** 0.5 / w.M))
+        rows = min(rows, w.n)
+        stride = max(1, w.n // rows)
+        idx = torch.arange(0, rows, device="cuda") * stride
+        out["cpu_baseline"] = cpu_baseline(w, X[idx], C, v, 0.0)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
