@@ -18,6 +18,8 @@ FLAGS = [
     # packed fp32 VALU forms are kept out of generated code on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+    # keep MFMA accumulators in architectural VGPRs so the VALU reads them without copies
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes",
 ]
 

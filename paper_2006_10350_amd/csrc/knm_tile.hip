@@ -63,39 +63,104 @@ __host__ __device__ constexpr int ks_for_d(int d)
     return ks;
 }
 
-// Loads virtual features [base, base + N) of one point into registers (zero beyond d).
+// Loads virtual features [base, base + N) of one point into registers (zero beyond d or
+// when the point is padding).  Branch-free: out-of-range pieces re-read the row's first
+// elements and are zeroed by a select, so all loads issue back to back and their latency
+// is hidden behind a whole stage of MFMA work.  `row` must point at a readable row.
 template <int N, int VW>
 __device__ __forceinline__ void load_features(const float *__restrict__ row, int base, int d, bool valid,
                                               float (&x)[N])
 {
-#pragma unroll
-    for (int k = 0; k < N; ++k) x[k] = 0.0f;
-    if (!valid) return;
     if constexpr (VW == 4) {
 #pragma unroll
         for (int k = 0; k < N; k += 4) {
-            if (base + k < d) { // d % 4 == 0 in this mode
-                f32x4 v = *reinterpret_cast<const f32x4 *>(row + base + k);
-                x[k] = v[0]; x[k + 1] = v[1]; x[k + 2] = v[2]; x[k + 3] = v[3];
-            }
+            const bool in = valid && (base + k < d); // d % 4 == 0 in this mode
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(row + (in ? base + k : 0));
+            x[k] = in ? v[0] : 0.0f; x[k + 1] = in ? v[1] : 0.0f; x[k + 2] = in ? v[2] : 0.0f; x[k + 3] = in ? v[3] : 0.0f;
         }
     } else if constexpr (VW == 2) {
 #pragma unroll
         for (int k = 0; k < N; k += 2) {
-            if (base + k < d) { // d % 2 == 0 in this mode
-                f32x2 v = *reinterpret_cast<const f32x2 *>(row + base + k);
-                x[k] = v[0]; x[k + 1] = v[1];
-            }
+            const bool in = valid && (base + k < d); // d % 2 == 0 in this mode
+            const f32x2 v = *reinterpret_cast<const f32x2 *>(row + (in ? base + k : 0));
+            x[k] = in ? v[0] : 0.0f; x[k + 1] = in ? v[1] : 0.0f;
         }
     } else {
 #pragma unroll
-        for (int k = 0; k < N; ++k)
-            if (base + k < d) x[k] = row[base + k];
+        for (int k = 0; k < N; ++k) {
+            const bool in = valid && (base + k < d);
+            const float v = row[in ? base + k : 0];
+            x[k] = in ? v : 0.0f;
+        }
     }
 }
 
+// The hot instructions are issued through volatile inline assembly: the compiler keeps
+// volatile statements in program order, which is what the schedule below relies on.
+//
+// Measured on gfx950: fp32 MFMA and VALU instructions of one SIMD do not overlap in time,
+// so the best order for a stream tile is simply one in which nothing waits:
+//     chain(block 0), chain(block 1), finish(block 0), finish(block 1).
+// An MFMA result may be read by the VALU only after the MFMA has retired (16 passes); the
+// compiler cannot see into the assembly, so the order itself guarantees it: block 0's
+// accumulator is read a whole 15-MFMA chain after its last MFMA, block 1's after the 32
+// VALU instructions that finish block 0.  Each exp is separated from the FMA consuming it
+// by three instructions (a transcendental result needs one idle issue slot).
+// acc = sum_{s < KS} a[s] (x) b[s] as one dependent chain of 32x32x2 fp32 MFMAs, emitted in
+// assembly blocks of up to four instructions (operand-count limit of an asm statement).
+template <int KS, int S0>
+__device__ __forceinline__ void mfma_chain_from(f32x16 &acc, const float *a, const float *b)
+{
+    constexpr int n = KS - S0 >= 4 ? 4 : KS - S0;
+    if constexpr (n == 4)
+        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0\n\t"
+                     "v_mfma_f32_32x32x2_f32 %0, %3, %4, %0\n\t"
+                     "v_mfma_f32_32x32x2_f32 %0, %5, %6, %0\n\t"
+                     "v_mfma_f32_32x32x2_f32 %0, %7, %8, %0"
+                     : "+v"(acc)
+                     : "v"(a[S0]), "v"(b[S0]), "v"(a[S0 + 1]), "v"(b[S0 + 1]), "v"(a[S0 + 2]), "v"(b[S0 + 2]),
+                       "v"(a[S0 + 3]), "v"(b[S0 + 3]));
+    else if constexpr (n == 3)
+        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0\n\t"
+                     "v_mfma_f32_32x32x2_f32 %0, %3, %4, %0\n\t"
+                     "v_mfma_f32_32x32x2_f32 %0, %5, %6, %0"
+                     : "+v"(acc)
+                     : "v"(a[S0]), "v"(b[S0]), "v"(a[S0 + 1]), "v"(b[S0 + 1]), "v"(a[S0 + 2]), "v"(b[S0 + 2]));
+    else if constexpr (n == 2)
+        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0\n\t"
+                     "v_mfma_f32_32x32x2_f32 %0, %3, %4, %0"
+                     : "+v"(acc)
+                     : "v"(a[S0]), "v"(b[S0]), "v"(a[S0 + 1]), "v"(b[S0 + 1]));
+    else if constexpr (n == 1)
+        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a[S0]), "v"(b[S0]));
+    if constexpr (S0 + n < KS) mfma_chain_from<KS, S0 + n>(acc, a, b);
+}
+template <int KS>
+__device__ __forceinline__ void mfma_chain(f32x16 &acc, const float *a, const float *b)
+{
+    // first instruction takes the literal 0 as its C operand
+    asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, 0" : "=&v"(acc) : "v"(a[0]), "v"(b[0]));
+    if constexpr (KS > 1) mfma_chain_from<KS, 1>(acc, a, b);
+}
+// s_i += min(max(2^x_i, 0), 1) * vl for four entries; the clamp keeps kernel values in [0, 1]
+__device__ __forceinline__ void exp_fma4(float x0, float x1, float x2, float x3, float vl, float &s0, float &s1,
+                                         float &s2, float &s3)
+{
+    float p0, p1, p2, p3;
+    asm volatile("v_exp_f32_e64 %0, %8 clamp\n\t"
+                 "v_exp_f32_e64 %1, %9 clamp\n\t"
+                 "v_exp_f32_e64 %2, %10 clamp\n\t"
+                 "v_exp_f32_e64 %3, %11 clamp\n\t"
+                 "v_fmac_f32_e32 %4, %0, %12\n\t"
+                 "v_fmac_f32_e32 %5, %1, %12\n\t"
+                 "v_fmac_f32_e32 %6, %2, %12\n\t"
+                 "v_fmac_f32_e32 %7, %3, %12"
+                 : "=&v"(p0), "=&v"(p1), "=&v"(p2), "=&v"(p3), "+v"(s0), "+v"(s1), "+v"(s2), "+v"(s3)
+                 : "v"(x0), "v"(x1), "v"(x2), "v"(x3), "v"(vl));
+}
+
 template <int KS, int R, int VW>
-__global__ __launch_bounds__(kThreads) void gauss_sweep_kernel(SweepArgs a)
+__global__ __launch_bounds__(kThreads, (KS <= 15 ? 3 : 1)) void gauss_sweep_kernel(SweepArgs a)
 {
     using geo = Geo<KS>;
     constexpr int G = geo::G;
@@ -153,10 +218,10 @@ __global__ __launch_bounds__(kThreads) void gauss_sweep_kernel(SweepArgs a)
         const bool valid = idx < chunk_end;
         const float *p = a.S + (valid ? idx : 0) * a.lds;
         load_features<VPT, VW>(p, part * VPT, d, valid, xs);
-        if (part == 0) {
-            vs = valid ? a.vec[idx * a.ldv] : 0.0f;
-            if (a.wgt != nullptr && valid) vs *= a.wgt[idx];
-        }
+        const int64_t vi = valid ? idx : 0;
+        const float vraw = a.vec[vi * a.ldv];
+        const float wraw = (a.wgt != nullptr) ? a.wgt[vi] : 1.0f;
+        vs = valid ? vraw * wraw : 0.0f;
     };
     auto commit = [&](int buf) {
         float nrm = 0.0f;
@@ -191,37 +256,36 @@ __global__ __launch_bounds__(kThreads) void gauss_sweep_kernel(SweepArgs a)
         __syncthreads();
         if (st + 1 < n_stages) fetch(st + 1);
 
-#pragma unroll
-        for (int tile = 0; tile < kTilesPerStage; ++tile) {
+        // B operands are read one tile ahead so the LDS latency hides under the MFMA chains
+        float b[2][4 * G];
+        float vl[2];
+        auto read_tile = [&](int tile, int slot) {
             const float *tb = &img[buf][tile * geo::TILE_FLOATS];
-            float b[4 * G];
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 f32x4 u = *reinterpret_cast<const f32x4 *>(tb + (g * 64 + lane) * 4);
-                b[4 * g] = u[0]; b[4 * g + 1] = u[1]; b[4 * g + 2] = u[2]; b[4 * g + 3] = u[3];
+                b[slot][4 * g] = u[0]; b[slot][4 * g + 1] = u[1]; b[slot][4 * g + 2] = u[2]; b[slot][4 * g + 3] = u[3];
             }
-            const float vl = vv[buf][tile * 32 + row];
+            vl[slot] = vv[buf][tile * 32 + row];
+        };
+        read_tile(0, 0);
+#pragma unroll
+        for (int tile = 0; tile < kTilesPerStage; ++tile) {
+            const int cur = tile & 1;
+            if (tile + 1 < kTilesPerStage) read_tile(tile + 1, cur ^ 1);
             f32x16 acc[R];
 #pragma unroll
-            for (int rb = 0; rb < R; ++rb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[rb][r] = 0.0f;
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-#pragma unroll
-                for (int rb = 0; rb < R; ++rb)
-                    acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[rb][s], b[s], acc[rb], 0, 0, 0);
+            for (int rb = 0; rb < R; ++rb) {
+                mfma_chain<KS>(acc[rb], af[rb], b[cur]);
+            }
 #pragma unroll
             for (int rb = 0; rb < R; ++rb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // exponent <= 0 up to rounding; med3 keeps the kernel value in [0, 1]
-                    float p = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(acc[rb][r]), 0.0f, 1.0f);
-                    sum[rb][r] = fmaf(p, vl, sum[rb][r]);
-                }
+                for (int r = 0; r < 16; r += 4)
+                    exp_fma4(acc[rb][r], acc[rb][r + 1], acc[rb][r + 2], acc[rb][r + 3], vl[cur], sum[rb][r],
+                             sum[rb][r + 1], sum[rb][r + 2], sum[rb][r + 3]);
         }
     }
-
     // ---- reduce over the 32 stream lanes of each half-wave and store ----------------------
     float *out = a.out + (int64_t)blockIdx.y * a.chunk_stride;
 #pragma unroll
