@@ -55,6 +55,16 @@ __global__ void tri_fix_kernel(double *A, int64_t M, double shift, int zero_lowe
     if (i == j && shift != 0.0) A[i + j * M] += shift;
 }
 
+// first (1-based) index whose diagonal entry is not a positive finite number, else unchanged;
+// catches NaN/Inf pivots, which a "pivot <= 0" test inside the factorisation lets through
+__global__ void diag_check_kernel(const double *__restrict__ A, int64_t M, unsigned long long *bad)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    const double v = A[i + i * M];
+    if (!(v > 0.0) || !(v < 1.0e300)) atomicMin(bad, (unsigned long long)(i + 1));
+}
+
 // row-major (rows x t, leading dimension t) float  <->  column-major (rows x t) double
 __global__ void f32_rows_to_f64_cols(const float *__restrict__ src, int64_t rows, int t, double *__restrict__ dst)
 {
@@ -237,6 +247,22 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
     hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, inv2s2, jitter, p->T);
     if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "kmm_kernel launch");
 
+    DevBuf badbuf;
+    if (badbuf.alloc(ctx, sizeof(unsigned long long))) return bail(KNM_ALLOC, "hipMalloc");
+    // returns the failing pivot (1-based) of the factor in `F`, or 0
+    auto bad_diagonal = [&](const double *F, int64_t *pivot) -> hipError_t {
+        const unsigned long long none = ~0ull;
+        unsigned long long got = none;
+        hipError_t err = hipMemcpyAsync(badbuf.p, &none, sizeof(none), hipMemcpyHostToDevice, ctx->stream);
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(diag_check_kernel, grid1(M), dim3(256), 0, ctx->stream, F, M,
+                           badbuf.as<unsigned long long>());
+        err = hipMemcpyAsync(&got, badbuf.p, sizeof(got), hipMemcpyDeviceToHost, ctx->stream);
+        if (err == hipSuccess) err = hipStreamSynchronize(ctx->stream);
+        *pivot = (got == none) ? 0 : (int64_t)got;
+        return err;
+    };
+
     rocblas_int host_info = 0;
     if (rocsolver_dpotrf(h, rocblas_fill_upper, (rocblas_int)M, p->T, (rocblas_int)M, info.as<rocblas_int>()) !=
         rocblas_status_success)
@@ -244,8 +270,10 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
     e = hipMemcpyAsync(&host_info, info.p, sizeof(rocblas_int), hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return bail(KNM_HIP_ERROR, "dpotrf(T) status copy");
-    if (host_info != 0) {
-        if (bad_pivot_or_null) *bad_pivot_or_null = host_info;
+    int64_t pivot = host_info;
+    if (pivot == 0 && bad_diagonal(p->T, &pivot) != hipSuccess) return bail(KNM_HIP_ERROR, "diagonal check");
+    if (pivot != 0) {
+        if (bad_pivot_or_null) *bad_pivot_or_null = pivot;
         return bail(KNM_NOT_PD, "K_MM + jitter I is not positive definite");
     }
     const dim3 fb(32, 8);
@@ -264,8 +292,10 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
     e = hipMemcpyAsync(&host_info, info.p, sizeof(rocblas_int), hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return bail(KNM_HIP_ERROR, "dpotrf(A) status copy");
-    if (host_info != 0) {
-        if (bad_pivot_or_null) *bad_pivot_or_null = -(int64_t)host_info;
+    pivot = host_info;
+    if (pivot == 0 && bad_diagonal(p->A, &pivot) != hipSuccess) return bail(KNM_HIP_ERROR, "diagonal check");
+    if (pivot != 0) {
+        if (bad_pivot_or_null) *bad_pivot_or_null = -pivot;
         return bail(KNM_NOT_PD, "T T^T / M + lambda I is not positive definite");
     }
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, 0.0, 1);

@@ -1,0 +1,156 @@
+"""GPU parity for the secondary path: preconditioner (Alg. 1, Eq. 7), the preconditioned
+operator (Eq. 9), the conjugate-gradient fit and the predictor (Eq. 4), against the fp64
+CPU oracle, through the C ABI.  End-to-end bar: relative L2 error of predictions <= 1e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def rel_l2(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def _rand(n, d, seed, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return (scale * torch.randn(n, d, generator=g)).to(torch.float32)
+
+
+def test_preconditioner_factors_match_oracle(knm):
+    M, d, sigma, lam, jitter = 300, 5, 0.75, 1e-4, 1e-9  # sigma exactly representable in fp32
+    C = _rand(M, d, 31)
+    pre = knm.precond_build(C.cuda(), sigma, lam, jitter)
+    T, A = pre.factors()
+    To, Ao = oracle.precond(C.numpy(), sigma, lam, jitter)
+    assert np.array_equal(np.tril(T, -1), np.zeros_like(T))
+    # two fp64 factorisations with different summation orders differ by cond(K) * eps
+    assert rel_l2(T, To) < 1e-6
+    assert rel_l2(A, Ao) < 1e-6
+    # the defining identities, independent of the oracle
+    K = oracle.kernel_matrix(C.numpy(), C.numpy(), sigma) + jitter * np.eye(M)
+    assert np.abs(T.T @ T - K).max() < 1e-12
+    assert np.abs(A.T @ A - (T @ T.T / M + lam * np.eye(M))).max() < 1e-12
+    pre.close()
+
+
+def test_not_positive_definite_is_reported(knm):
+    # A Gaussian K_MM is positive semi-definite, so a Cholesky failure only comes from
+    # rounding or from bad data.  Bad data (a NaN centre) must surface as NOT_PD with the pivot.
+    C = _rand(64, 3, 32)
+    Cbad = C.clone()
+    Cbad[10, 1] = float("nan")
+    with pytest.raises(knm.KnmError) as e:
+        knm.precond_build(Cbad.cuda(), 1.0, 1e-6, 0.0)
+    assert e.value.status == -5
+    # A duplicated centre makes K_MM exactly singular: a zero pivot up to rounding.  Either
+    # outcome is legitimate (error, or a factor that still satisfies T^T T = K); with jitter
+    # the factorisation must succeed.
+    Cdup = C.clone()
+    Cdup[10] = Cdup[3]
+    try:
+        pre = knm.precond_build(Cdup.cuda(), 1.0, 1e-6, 0.0)
+    except knm.KnmError as err:
+        assert err.status == -5
+    else:
+        T, _ = pre.factors()
+        K = oracle.kernel_matrix(Cdup.numpy(), Cdup.numpy(), 1.0)
+        assert np.abs(T.T @ T - K).max() < 1e-7
+        pre.close()
+    with pytest.raises(np.linalg.LinAlgError):
+        oracle.precond(Cdup.numpy(), 1.0, 1e-6, 0.0)
+    knm.precond_build(Cdup.cuda(), 1.0, 1e-6, 1e-8).close()
+
+
+@pytest.mark.parametrize("t", [1, 3])
+def test_linop_matches_oracle(knm, t):
+    n, M, d, sigma, lam, jitter = 3000, 200, 4, 1.0, 1e-5, 1e-10
+    X = _rand(n, d, 33)
+    C = X[:M].clone()
+    beta = torch.randn(M, t, generator=torch.Generator().manual_seed(34), dtype=torch.float64)
+    pre = knm.precond_build(C.cuda(), sigma, lam, jitter)
+    got = knm.falkon_linop(pre, X.cuda(), C.cuda(), sigma, lam, beta.cuda()).cpu().numpy()
+    To, Ao = oracle.precond(C.numpy(), sigma, lam, jitter)
+    ref = oracle.linop(X.numpy(), C.numpy(), sigma, lam, To, Ao, beta.numpy())
+    assert rel_l2(got, ref) < 1e-4
+    pre.close()
+
+
+def test_linop_is_n_identity_when_centres_are_the_data(knm):
+    # T^-1 amplifies the fp32 rounding of the product by the conditioning of K, so the bar
+    # here is the end-to-end one (1e-3), on a moderately conditioned K (small sigma).
+    n, d, sigma, lam = 256, 2, 0.25, 1e-2
+    X = _rand(n, d, 35, scale=2.0)
+    pre = knm.precond_build(X.cuda(), sigma, lam, 0.0)
+    beta = torch.randn(n, generator=torch.Generator().manual_seed(36), dtype=torch.float64)
+    got = knm.falkon_linop(pre, X.cuda(), X.cuda(), sigma, lam, beta.cuda()).cpu().numpy()
+    assert rel_l2(got, n * beta.numpy()) < 1e-3
+    pre.close()
+
+
+def test_tiny_workload_fit_and_predict(knm):
+    w = synth.workload("tiny")
+    inp = synth.make_inputs(w, device="cpu", n_test=2000)
+    X, C, Y, Xt = inp["X"], inp["C"], inp["Y"], inp["Xtest"]
+    jitter = 1e-9
+    alpha, resid = knm.falkon_fit(X.cuda(), Y.cuda(), C.cuda(), w.sigma, w.lam, w.iters, jitter, return_resid=True)
+    pred = knm.falkon_predict(Xt.cuda(), C.cuda(), w.sigma, alpha).cpu().numpy()
+    ao, ro = oracle.falkon_fit(X.numpy(), Y.numpy(), C.numpy(), w.sigma, w.lam, w.iters, jitter, return_resid=True)
+    po = oracle.falkon_predict(Xt.numpy(), C.numpy(), w.sigma, ao)
+    err = rel_l2(pred, po)
+    print(f"end-to-end prediction error {err:.3e}; residuals gpu {resid[:3].ravel()} oracle {ro[:3].ravel()}")
+    assert err < 1e-3
+    # training-set predictions as well
+    ptr = knm.falkon_predict(X.cuda(), C.cuda(), w.sigma, alpha).cpu().numpy()
+    assert rel_l2(ptr, oracle.falkon_predict(X.numpy(), C.numpy(), w.sigma, ao)) < 1e-3
+    # same CG path: residual histories agree while they are well above the fp32 noise floor
+    np.testing.assert_allclose(resid[:4].ravel(), np.asarray(ro)[:4].ravel(), rtol=1e-2)
+    # the fit is useful: clearly better than predicting zero after 10 iterations
+    clean = np.sin(Xt.numpy().astype(np.float64).sum(1))
+    assert np.mean((pred.ravel() - clean) ** 2) < 0.8 * np.var(clean)
+
+
+def test_multi_output_fit(knm):
+    # sigma chosen so that K_MM is moderately conditioned: T^-1 amplifies the fp32 rounding of
+    # the products by ~sqrt(cond(K_MM)), the accuracy limit of single precision the paper notes
+    n, M, d, t, sigma, lam, iters, jitter = 4000, 256, 6, 3, 1.0, 1e-6, 8, 1e-9
+    X = _rand(n, d, 37)
+    C = X[torch.randperm(n, generator=torch.Generator().manual_seed(38))[:M]].clone()
+    Y = torch.stack([torch.sin(X.sum(1)), torch.cos(X[:, 0]), X[:, 1] * X[:, 2]], dim=1).contiguous()
+    alpha = knm.falkon_fit(X.cuda(), Y.cuda(), C.cuda(), sigma, lam, iters, jitter)
+    ao = oracle.falkon_fit(X.numpy(), Y.numpy(), C.numpy(), sigma, lam, iters, jitter)
+    Xt = _rand(500, d, 39)
+    pred = knm.falkon_predict(Xt.cuda(), C.cuda(), sigma, alpha).cpu().numpy()
+    po = oracle.falkon_predict(Xt.numpy(), C.numpy(), sigma, ao)
+    assert rel_l2(pred, po) < 1e-3
+    for c in range(t):
+        assert rel_l2(pred[:, c], po[:, c]) < 1e-3
+
+
+def test_all_points_as_centres_reaches_exact_krr(knm):
+    # M = n, C = X: the preconditioned operator is n I, one CG step gives (K + n lam I)^-1 y
+    # (moderately conditioned K, as above: the fp32 products are amplified by T^-1)
+    n, d, sigma, lam = 256, 2, 0.25, 1e-3
+    X = _rand(n, d, 40, scale=2.0)
+    y = (torch.sin(X.sum(1)) + 0.1 * _rand(n, 1, 41)[:, 0]).contiguous()
+    alpha = knm.falkon_fit(X.cuda(), y.cuda(), X.cuda(), sigma, lam, 1, 0.0)
+    K = oracle.kernel_matrix(X.numpy(), X.numpy(), sigma)
+    exact = np.linalg.solve(K + n * lam * np.eye(n), y.numpy().astype(np.float64))
+    pred = knm.falkon_predict(X.cuda(), X.cuda(), sigma, alpha).cpu().numpy()
+    assert rel_l2(pred, K @ exact) < 1e-3
+
+
+def test_fit_rejects_bad_arguments(knm):
+    X, C, Y = _rand(100, 3, 42).cuda(), _rand(10, 3, 43).cuda(), _rand(100, 1, 44).cuda()
+    with pytest.raises(knm.KnmError) as e:
+        knm.falkon_fit(X, Y, C, 1.0, -1.0, 3)
+    assert e.value.status == -1
+    with pytest.raises(knm.KnmError) as e:
+        knm.falkon_fit(X, Y, C, 1.0, 1e-3, 0)
+    assert e.value.status == -1

@@ -1,0 +1,69 @@
+"""Full-size parity in the launch configuration the benchmark times: the mid workload
+(n = 11M, d = 28, M = 100k) and the low-dimensional one (n = 5.9M, d = 8, M = 100k).
+
+The oracle cannot sweep 1e12 entries, so it checks sampled outputs one by one: rows of
+W = K V (each needs all M centres) and entries of R = K^T Y (each needs all n rows), plus
+identities that hold at any size.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def rel_l2(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+@pytest.mark.parametrize("name", ["mid", "lowdim"])
+def test_full_size_sampled_outputs(knm, name):
+    w = synth.workload(name)
+    print(f"workload {name}: n={w.n} d={w.d} M={w.M}", flush=True)
+    inp = synth.make_inputs(w, device="cuda", with_targets=True)
+    X, C, Y = inp["X"], inp["C"], inp["Y"]
+    v = synth.probe_vector(w.M, w.t, "normal", device="cuda")
+    U, W = knm.knm_prod(X, C, w.sigma, v, return_w=True)
+    R = knm.knm_t_y(X, C, w.sigma, Y)
+    torch.cuda.synchronize()
+    print("gpu products done", flush=True)
+
+    Cn = C.cpu().numpy()
+    vn = v.cpu().numpy()
+    g = np.random.default_rng(7)
+
+    # rows of W = K V: first and last tiles plus random rows
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 255, 256, w.n - 257, w.n - 2, w.n - 1], g.integers(0, w.n, 503)]))
+    Xs = X[torch.from_numpy(rows).cuda()].cpu().numpy()
+    Wo = oracle.knm_v(Xs, Cn, w.sigma, vn)
+    Wg = W[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert rel_l2(Wg, Wo) < 1e-4
+    assert np.max(np.abs(Wg - Wo)) < 1e-4 * np.max(np.abs(Wo)) + 1e-6
+    print("row samples ok", flush=True)
+
+    # entries of R = K^T Y: every one is a sum over all n rows
+    cols = np.unique(np.concatenate([[0, 31, 32, 255, 256, w.M - 1], g.integers(0, w.M, 6)]))
+    Xn = X.cpu().numpy()
+    Yn = Y.cpu().numpy()
+    Ro = oracle.knm_t_y(Xn, Cn[cols], w.sigma, Yn)
+    Rg = R[torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert rel_l2(Rg, Ro) < 1e-4
+    print("column samples ok", flush=True)
+
+    # the same column entries of U = K^T W, with the GPU's own W as the oracle's input
+    Wn = W.cpu().numpy()
+    Uo = oracle.knm_t_y(Xn, Cn[cols], w.sigma, Wn)
+    Ug = U[torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert rel_l2(Ug, Uo) < 1e-4
+
+    # identities at full size: v^T K^T K v = |K v|^2 and U = K^T W bit for bit
+    uv = float((U.double() * v.double()).sum())
+    ww = float((W.double() ** 2).sum())
+    assert abs(uv - ww) <= 1e-4 * float(U.double().norm() * v.double().norm())
+    U2 = knm.knm_t_y(X, C, w.sigma, W)
+    assert torch.equal(U2, U)
