@@ -46,6 +46,19 @@ def cpu_baseline(w, X_rows, C, v, budget_entries: float):
     }
 
 
+def measured_traffic_bytes(workload: str):
+    """HBM-side bytes per launch of the tile kernel, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE, each scaled by its copy-probe factor); None if not profiled."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            t = json.load(f).get(workload)
+        if not t:
+            return None
+        return 1024.0 * (t["fetch_kib_raw"] * t["fetch_scale"] + t["write_kib_raw"] * t["write_scale"])
+    except (OSError, ValueError, KeyError):
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +69,9 @@ def main() -> int:
     ap.add_argument("--M", type=int, default=None, help="override the number of centres")
     ap.add_argument("--cpu-rows", type=int, default=None, help="rows of the oracle's timing sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (a dispatch of known "
+                         "traffic that calibrates the HBM byte counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (rows of X would be sharded across GPUs with one "
@@ -78,6 +94,12 @@ def main() -> int:
     U = torch.empty(w.M, w.t, device="cuda", dtype=torch.float32)
     ctx = knm.default_context()
     torch.cuda.synchronize()
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib * (1 << 18), device="cuda", dtype=torch.float32)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
@@ -113,7 +135,7 @@ def main() -> int:
         "peak": PEAK_FP32_MFMA_TFLOPS,
         "unit": "TFLOP/s",
         "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-        "traffic": None,
+        "traffic": measured_traffic_bytes(w.name) if (args.n is None and args.M is None) else None,
         "avg_launch_ms": avg_launch_ms,
         "row_sweep_ms": sum(row_ms) / len(row_ms),
         "col_sweep_ms": sum(col_ms) / len(col_ms),
