@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libknm.so")
-SOURCES = ["knm_tile.hip", "knm_api.hip", "knm_solver.hip"]
+SOURCES = ["knm_tile.hip", "knm_gemm.hip", "knm_api.hip", "knm_solver.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -18,15 +18,18 @@ FLAGS = [
     # packed fp32 VALU forms are kept out of generated code on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-    # keep MFMA accumulators in architectural VGPRs so the VALU reads them without copies
-    "-mllvm", "-amdgpu-mfma-vgpr-form",
-    "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes",
+    "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes", "-Wno-pass-failed",
 ]
+# per-source extras
+EXTRA = {
+    # keep MFMA accumulators in architectural VGPRs so the VALU reads them without copies
+    "knm_tile.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+}
 
 
 def _compile(src: str, extra) -> str:
     obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)

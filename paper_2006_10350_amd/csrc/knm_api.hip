@@ -39,13 +39,17 @@ int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need)
     return KNM_OK;
 }
 
+bool use_gemm_engine(int d, int t) { return d > small_max_d() || t > 1; }
+
 // Chunking of the stream dimension.  More chunks = more workgroups (needed when there
 // are few fixed blocks) and shorter fp32 running sums; each chunk costs one partial
 // vector that the merge pass adds up in fp64.
-int64_t choose_chunks(int64_t nF, int64_t nS, int d, int64_t *chunk_len)
+int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int64_t *chunk_len)
 {
-    const int64_t stage = stage_points();
-    const int64_t blocks = (nF + fixed_per_block(d) - 1) / fixed_per_block(d);
+    const bool gemm = use_gemm_engine(d, t);
+    const int64_t stage = gemm ? gemm_stage_points() : stage_points();
+    const int64_t per_block = gemm ? gemm_fixed_per_block() : fixed_per_block(d);
+    const int64_t blocks = (nF + per_block - 1) / per_block;
     const int64_t target_wgs = 4096;       // several waves of workgroups over 256 CUs
     const int64_t min_len = 16 * stage;    // amortise the per-workgroup prologue/epilogue
     const int64_t max_len = (int64_t)1 << 18; // bound the length of a per-lane fp32 running sum
@@ -73,7 +77,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
                  int d, float sigma, const float *vec, const float *wgt, int t, float *out, hipEvent_t after_sweep)
 {
     int64_t chunk_len = 0;
-    const int64_t chunks = choose_chunks(nF, nS, d, &chunk_len);
+    const int64_t chunks = choose_chunks(nF, nS, d, t, &chunk_len);
     if (chunks > 65535) return fail(ctx, KNM_UNSUPPORTED, "too many stream chunks");
     float *part = nullptr;
     if (chunks > 1) {
@@ -81,12 +85,15 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         if (st) return st;
         part = ctx->part_buf;
     }
-    for (int c = 0; c < t; ++c) {
+    const bool gemm = use_gemm_engine(d, t);
+    const int group = gemm ? gemm_max_t() : 1; // columns per launch
+    for (int c = 0; c < t; c += group) {
         SweepArgs a;
         a.F = F; a.nF = nF; a.ldf = ldf;
         a.S = S; a.nS = nS; a.lds = lds;
         a.d = d;
         a.vec = vec + c; a.ldv = t;
+        a.t = (t - c < group) ? t - c : group;
         a.wgt = wgt;
         a.out = (chunks > 1) ? part + c : out + c;
         a.ldo = t;
@@ -94,7 +101,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.chunk_len = chunk_len;
         a.n_chunks = chunks;
         a.sigma = sigma;
-        hipError_t e = launch_sweep(a, ctx->stream);
+        hipError_t e = gemm ? launch_sweep_gemm(a, ctx->stream) : launch_sweep(a, ctx->stream);
         if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "launch_sweep", e);
     }
     if (after_sweep) (void)hipEventRecord(after_sweep, ctx->stream);
@@ -192,16 +199,16 @@ const char *knm_strerror(int status)
 
 const char *knm_last_error(const knm_ctx *ctx) { return ctx ? ctx->last_error.c_str() : ""; }
 
-int knm_max_d(void) { return knm::max_d(); }
-int knm_max_t(void) { return 64; }
+int knm_max_d(void) { return 65536; }
+int knm_max_t(void) { return 1024; }
 
 size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
 {
     if (n <= 0 || M <= 0 || d <= 0 || t <= 0) return 0;
     int64_t len = 0;
     size_t bytes = sizeof(float) * (size_t)n * t; // W
-    const int64_t c1 = choose_chunks(n, M, d, &len);
-    const int64_t c2 = choose_chunks(M, n, d, &len);
+    const int64_t c1 = choose_chunks(n, M, d, t, &len);
+    const int64_t c2 = choose_chunks(M, n, d, t, &len);
     size_t p1 = c1 > 1 ? sizeof(float) * (size_t)c1 * n * t : 0;
     size_t p2 = c2 > 1 ? sizeof(float) * (size_t)c2 * M * t : 0;
     return bytes + (p1 > p2 ? p1 : p2);

@@ -1,0 +1,293 @@
+// Gaussian-kernel tile engine, K-loop variant: out[f, c] = sum_s k(F_f, S_s) vec[s, c]
+// for any number of features d and up to 16 right-hand sides per launch.
+//
+// Used where the register-resident engine of knm_tile.hip does not apply: d too large
+// to keep a block of points in registers (the image-like workload, d = 784), or several
+// output columns sharing every kernel evaluation (multi-class targets).  Same
+// formulation (Section 3.1, "Blockwise K_nm-vector product"; Gaussian kernel of
+// Section 2): the cross term runs on fp32 MFMA with the contraction over d split into
+// chunks of 16 features staged through LDS for BOTH operands, one augmented K-step adds
+// the two norms, and exp plus the reduction against the vectors are fused behind it.
+//
+// Tile shape.  Workgroup = 4 wavefronts = 256 fixed points x 128 stream points per tile;
+// each wavefront owns 64 fixed points (2 blocks of 32) x all 128 stream points (4 blocks)
+// = 8 accumulators of 32x32.  Arithmetic intensity against L2 is
+// 256*128 / (2*(256+128)) = 43 flop/B.
+//
+// Orientation.  The stream block is the MFMA A operand and the fixed block the B operand,
+// so a lane's accumulator registers run over 16 stream points of ONE fixed point.  The
+// reduction over stream points is then in-lane: t running sums per fixed block and lane,
+// with the vector rows read from LDS as broadcasts.  The two half-waves hold different
+// stream rows of the same fixed point and are added once, when the workgroup finishes.
+
+#include "knm_internal.h"
+
+namespace knm {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int kFixed = 256;            // fixed points per workgroup
+constexpr int kStream = 128;           // stream points per tile
+constexpr int kPts = kFixed + kStream; // points staged per K-chunk
+constexpr int kBlocks = kPts / 32;     // 32-point blocks in LDS: 8 fixed then 4 stream
+constexpr int kChunk = 16;             // features per K-chunk = 8 K-steps
+constexpr int kLoads = kPts * (kChunk / 4) / kThreads; // float4 loads per thread and chunk (6)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kBlockFloats = 2 * 64 * 4; // one block, one chunk: 2 units x 64 lanes x 4 K-steps
+
+static_assert(kLoads * kThreads == kPts * (kChunk / 4), "staging must divide evenly");
+
+// The eight 32x32 accumulators of a wavefront are pinned to the accumulation registers
+// (AGPRs) through the asm constraint, which leaves the architectural VGPRs to staging,
+// operands and running sums: 128 + <= 128 registers = two wavefronts per SIMD.
+__device__ __forceinline__ void mfma_zero(f32x16 &acc, float a, float b)
+{
+    asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, 0" : "=&a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_acc(f32x16 &acc, float a, float b)
+{
+    asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// TP: number of vector columns, padded to a multiple of 4.  VW: 4 if rows can be read
+// with aligned 16-byte loads, else 1.
+template <int TP, int VW>
+__global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float img[2][kBlocks * kBlockFloats]; // 2 x 24 KB
+    __shared__ float aug[kBlocks * 64];                                            // last K-step
+    __shared__ __attribute__((aligned(16))) float vimg[kStream * TP];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int h = lane >> 5;
+    const int t = a.t;
+    const int d = a.d;
+    const float s2 = kLog2e / (2.0f * a.sigma * a.sigma);
+    const int n_kc = (d + kChunk - 1) / kChunk;
+
+    const int64_t fixed0 = (int64_t)blockIdx.x * kFixed;
+    const int64_t chunk_begin = (int64_t)blockIdx.y * a.chunk_len;
+    int64_t chunk_end = chunk_begin + a.chunk_len;
+    if (chunk_end > a.nS) chunk_end = a.nS;
+    const int n_tiles = (int)((chunk_end - chunk_begin + kStream - 1) / kStream);
+
+    // staging role of this thread for load i: point (0..383) and feature quad (0..3)
+    // id = tid + 256 i  ->  point = id / 4 = tid / 4 + 64 i,  quad = tid % 4
+    const int sq = tid & 3;
+    const int sp0 = tid >> 2;
+
+    float sum[2][TP];
+#pragma unroll
+    for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int c = 0; c < TP; ++c) sum[fb][c] = 0.0f;
+
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int64_t stream0 = chunk_begin + (int64_t)tile * kStream;
+
+        // staged points of this thread (4 fixed, 2 stream): uniform base pointer of the
+        // block plus a 32-bit element offset of the (clamped) row
+        const float *const fbase = a.F + fixed0 * a.ldf;
+        const float *const sbase = a.S + stream0 * a.lds;
+        const int f_rows = (int)((a.nF - fixed0 < kFixed) ? a.nF - fixed0 : kFixed);
+        const int s_rows = (int)((chunk_end - stream0 < kStream) ? chunk_end - stream0 : kStream);
+        int roff[kLoads];
+        bool valid[kLoads];
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+            const int p = sp0 + 64 * i;
+            if (i < kFixed / 64) {
+                valid[i] = p < f_rows;
+                roff[i] = (valid[i] ? p : 0) * (int)a.ldf;
+            } else {
+                valid[i] = (p - kFixed) < s_rows;
+                roff[i] = (valid[i] ? p - kFixed : 0) * (int)a.lds;
+            }
+        }
+        auto rowp = [&](int i) { return (i < kFixed / 64 ? fbase : sbase) + roff[i]; };
+
+        f32x16 acc[2][4];
+        float nrm[kLoads];
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) nrm[i] = 0.0f;
+
+        f32x4 pre[kLoads];
+        auto fetch = [&](int kc) {
+            const int f0 = kc * kChunk + sq * 4;
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+                if constexpr (VW == 4) {
+                    const bool in = valid[i] && (f0 < d); // d % 4 == 0 in this mode
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(rowp(i) + (in ? f0 : 0));
+                    pre[i][0] = in ? v[0] : 0.0f; pre[i][1] = in ? v[1] : 0.0f;
+                    pre[i][2] = in ? v[2] : 0.0f; pre[i][3] = in ? v[3] : 0.0f;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool in = valid[i] && (f0 + e < d);
+                        const float v = rowp(i)[in ? f0 + e : 0];
+                        pre[i][e] = in ? v : 0.0f;
+                    }
+                }
+            }
+        };
+        // K-step s of a chunk takes feature 4 (s / 2) + 2 h + (s % 2) from half-wave h, so the
+        // quad of features `sq` lands in unit sq / 2, entries 2 (sq % 2) + {0, 1}, for h = 0, 1.
+        auto commit = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+                const int p = sp0 + 64 * i;
+                const float scale = (i < kFixed / 64) ? 2.0f * s2 : 1.0f;
+                nrm[i] = fmaf(pre[i][0], pre[i][0], nrm[i]);
+                nrm[i] = fmaf(pre[i][1], pre[i][1], nrm[i]);
+                nrm[i] = fmaf(pre[i][2], pre[i][2], nrm[i]);
+                nrm[i] = fmaf(pre[i][3], pre[i][3], nrm[i]);
+                float *base = &img[buf][(p >> 5) * kBlockFloats + (sq >> 1) * 256 + (sq & 1) * 2];
+                f32x2 lo, hi;
+                lo[0] = scale * pre[i][0]; lo[1] = scale * pre[i][1];
+                hi[0] = scale * pre[i][2]; hi[1] = scale * pre[i][3];
+                *reinterpret_cast<f32x2 *>(base + (p & 31) * 4) = lo;        // half-wave 0
+                *reinterpret_cast<f32x2 *>(base + (32 + (p & 31)) * 4) = hi; // half-wave 1
+            }
+        };
+
+        fetch(0);
+        for (int kc = 0; kc < n_kc; ++kc) {
+            const int buf = kc & 1;
+            commit(buf);
+            __syncthreads();
+            if (kc + 1 < n_kc) fetch(kc + 1);
+            const float *ib = img[buf];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                f32x4 av[4], bv[2];
+#pragma unroll
+                for (int sb = 0; sb < 4; ++sb)
+                    av[sb] = *reinterpret_cast<const f32x4 *>(ib + (kFixed / 32 + sb) * kBlockFloats + g * 256 + lane * 4);
+#pragma unroll
+                for (int fb = 0; fb < 2; ++fb)
+                    bv[fb] = *reinterpret_cast<const f32x4 *>(ib + (wave * 2 + fb) * kBlockFloats + g * 256 + lane * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+                        for (int sb = 0; sb < 4; ++sb) {
+                            if (kc == 0 && g == 0 && e == 0) mfma_zero(acc[fb][sb], av[sb][e], bv[fb][e]);
+                            else mfma_acc(acc[fb][sb], av[sb][e], bv[fb][e]);
+                        }
+            }
+        }
+
+        // augmented K-step: stream side [1, -s2 |x|^2], fixed side [-s2 |f|^2, 1]; plus the vectors
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+            float v = nrm[i];
+            v += __shfl_xor(v, 1);
+            v += __shfl_xor(v, 2);
+            if (sq == 0) {
+                const int p = sp0 + 64 * i;
+                const bool fixed = i < kFixed / 64;
+                float *ab = &aug[(p >> 5) * 64 + (p & 31)];
+                ab[0] = fixed ? -s2 * v : 1.0f;
+                ab[32] = fixed ? 1.0f : -s2 * v;
+            }
+        }
+        for (int k = tid; k < kStream * TP; k += kThreads) {
+            const int j = k / TP, c = k % TP;
+            const int64_t idx = stream0 + j;
+            const bool in = idx < chunk_end && c < t;
+            const int64_t vi = in ? idx : 0;
+            float v = a.vec[vi * a.ldv + (in ? c : 0)];
+            if (a.wgt != nullptr) v *= a.wgt[vi];
+            vimg[k] = in ? v : 0.0f;
+        }
+        __syncthreads();
+        {
+            float av[4], bv[2];
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) av[sb] = aug[(kFixed / 32 + sb) * 64 + lane];
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb) bv[fb] = aug[(wave * 2 + fb) * 64 + lane];
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+                for (int sb = 0; sb < 4; ++sb)
+                    mfma_acc(acc[fb][sb], av[sb], bv[fb]);
+        }
+
+        // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block
+#pragma unroll
+        for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                float vr[TP];
+#pragma unroll
+                for (int c4 = 0; c4 < TP; c4 += 4) {
+                    const f32x4 u = *reinterpret_cast<const f32x4 *>(&vimg[j * TP + c4]);
+                    vr[c4] = u[0]; vr[c4 + 1] = u[1]; vr[c4 + 2] = u[2]; vr[c4 + 3] = u[3];
+                }
+#pragma unroll
+                for (int fb = 0; fb < 2; ++fb) {
+                    // exponent <= 0 up to rounding; med3 keeps the kernel value in [0, 1]
+                    const float p = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(acc[fb][sb][r]), 0.0f, 1.0f);
+#pragma unroll
+                    for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[c], sum[fb][c]);
+                }
+            }
+        __syncthreads(); // aug / vimg / img are rewritten by the next tile
+    }
+
+    // the two half-waves hold different stream rows of the same fixed point
+    float *out = a.out + (int64_t)blockIdx.y * a.chunk_stride;
+#pragma unroll
+    for (int fb = 0; fb < 2; ++fb) {
+        const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
+#pragma unroll
+        for (int c = 0; c < TP; ++c) {
+            float v = sum[fb][c];
+            v += __shfl_xor(v, 32);
+            if (h == 0 && idx < a.nF && c < t) out[idx * a.ldo + c] = v;
+        }
+    }
+}
+
+template <int TP>
+hipError_t launch_tp(const SweepArgs &a, hipStream_t stream)
+{
+    const int64_t blocks = (a.nF + kFixed - 1) / kFixed;
+    dim3 grid((unsigned)blocks, (unsigned)a.n_chunks);
+    const bool a16 = (a.d % 4 == 0) && (a.lds % 4 == 0) && (a.ldf % 4 == 0) &&
+                     ((reinterpret_cast<uintptr_t>(a.S) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.F) & 15) == 0);
+    if (a16)
+        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 4>), grid, dim3(kThreads), 0, stream, a);
+    else
+        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 1>), grid, dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+} // namespace
+
+int gemm_max_t() { return 16; }
+int64_t gemm_stage_points() { return kStream; }
+int64_t gemm_fixed_per_block() { return kFixed; }
+
+hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream)
+{
+    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > gemm_max_t()) return hipErrorInvalidValue;
+    if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
+    if (a.n_chunks > 65535) return hipErrorInvalidValue;
+    if (a.t <= 4) return launch_tp<4>(a, stream);
+    if (a.t <= 8) return launch_tp<8>(a, stream);
+    if (a.t <= 12) return launch_tp<12>(a, stream);
+    return launch_tp<16>(a, stream);
+}
+
+} // namespace knm

@@ -25,25 +25,30 @@ struct SweepArgs {
     const float *S;   // stream points, nS x d, leading dimension lds
     int64_t nS, lds;
     int d;
-    const float *vec; // stream-side vector: element of stream point i is vec[i * ldv]
+    const float *vec; // stream-side vectors: column c of stream point i is vec[i * ldv + c]
     int64_t ldv;
+    int t;            // columns handled by this launch (1 for the register-resident engine)
     const float *wgt; // optional per-stream-point weight multiplied into vec (may be null)
-    float *out;       // out[chunk * chunk_stride + f * ldo]
+    float *out;       // out[chunk * chunk_stride + f * ldo + c]
     int64_t ldo, chunk_stride;
     int64_t chunk_len; // stream points per chunk (multiple of the stage size)
     int64_t n_chunks;
     float sigma;
 };
 
-int max_d();
+// register-resident engine (knm_tile.hip): d <= small_max_d(), one column per launch
+int small_max_d();
 int64_t stage_points();                 // stream points staged per LDS buffer
 int64_t fixed_per_block(int d);         // fixed points one workgroup covers
 hipError_t launch_sweep(const SweepArgs &a, hipStream_t stream);
+// K-loop engine (knm_gemm.hip): any d, up to gemm_max_t() columns per launch
+int gemm_max_t();
+int64_t gemm_stage_points();
+int64_t gemm_fixed_per_block();
+hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream);
 // out[j * ldo] = sum over chunks of part[chunk * chunk_stride + j * ldp], summed in fp64
 hipError_t launch_merge(const float *part, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
                         float *out, int64_t ldo, int64_t count, hipStream_t stream);
-// w[i * ld + c] *= dw[i] for c < t
-hipError_t launch_row_scale(float *w, int64_t n, int t, const float *dw, hipStream_t stream);
 
 } // namespace knm
 
@@ -67,8 +72,10 @@ struct knm_ctx {
 namespace knm {
 int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need);
 int fail(knm_ctx *ctx, int status, const char *what, hipError_t e = hipSuccess);
-// number of stream chunks used for a column sweep over nS stream points, nF fixed points
-int64_t choose_chunks(int64_t nF, int64_t nS, int d, int64_t *chunk_len);
+// true if (d, t) runs on the K-loop engine, false for the register-resident one
+bool use_gemm_engine(int d, int t);
+// number of stream chunks for a sweep over nS stream points against nF fixed points
+int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int64_t *chunk_len);
 int do_knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
              int64_t ldc, float sigma, const float *V, int t, float *W);
 int do_knm_t_w(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,

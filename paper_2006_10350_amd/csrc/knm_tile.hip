@@ -334,13 +334,13 @@ hipError_t launch_ks(const SweepArgs &a, hipStream_t stream)
 
 } // namespace
 
-int max_d() { return 64; }
+int small_max_d() { return 64; }
 int64_t stage_points() { return kStage; }
 int64_t fixed_per_block(int) { return (int64_t)kWaves * 32 * kR; }
 
 hipError_t launch_sweep(const SweepArgs &a, hipStream_t stream)
 {
-    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0) return hipErrorInvalidValue;
+    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t != 1 || a.d > small_max_d()) return hipErrorInvalidValue;
     if (a.chunk_len % kStage != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
     const int ks = ks_for_d(a.d);

@@ -62,8 +62,9 @@ _CHUNK = 1 << 22  # rows generated at a time
 def _rows(w: Workload, n: int, g: torch.Generator, device, out: torch.Tensor) -> None:
     """Fill out[n, d] (fp32) with the workload's feature distribution, chunk by chunk."""
     d = w.d
-    for lo in range(0, n, _CHUNK):
-        hi = min(n, lo + _CHUNK)
+    step = max(1, min(_CHUNK, (1 << 27) // d))  # bound the temporaries of one chunk
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
         m = hi - lo
         dst = out[lo:hi]
         if w.name in ("tiny", "mid"):

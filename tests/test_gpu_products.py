@@ -41,6 +41,12 @@ SHAPES = [
     (1300, 400, 33, 1, 5.0),
     (900, 300, 64, 1, 8.0),
     (640, 256, 12, 10, 2.5),
+    # K-loop engine: d above the register-resident limit, several columns, unaligned d
+    (515, 260, 130, 1, 8.0),
+    (300, 129, 70, 5, 6.0),
+    (600, 300, 784, 10, 24.0),
+    (257, 385, 99, 3, 7.0),
+    (1000, 2100, 16, 17, 3.0),
 ]
 
 
