@@ -123,14 +123,19 @@ def main() -> int:
     entries = float(w.n) * float(w.M)
     value = entries / (elapsed / args.steps) / 1e9
 
-    # the tile kernel is launched t times per sweep (once per output column), two sweeps per step
-    launches = 2 * w.t * args.steps
+    # two sweeps per step; the register-resident engine (d <= 64, t = 1) is one launch per sweep,
+    # the K-loop engine handles up to 16 columns per launch
+    k_loop = w.d > 64 or w.t > 1
+    kernel_name = "gauss_gemm_kernel" if k_loop else "gauss_sweep_kernel"
+    launches = 2 * ((w.t + 15) // 16) * args.steps
     avg_launch_ms = (sum(row_ms) + sum(col_ms)) / launches
-    flop_per_launch = entries * 2.0 * w.d  # algorithmic: one evaluation of every entry, 2 d flop each
+    # algorithmic: one evaluation of every entry, 2 d flop each (the 2 t flop of the reduction
+    # against the vectors and the exp are not counted)
+    flop_per_launch = entries * 2.0 * w.d
     achieved = flop_per_launch / (avg_launch_ms * 1e-3) / 1e12
     roofline = {
         "bound": "mfma",
-        "kernel": "gauss_sweep_kernel",
+        "kernel": kernel_name,
         "achieved": achieved,
         "peak": PEAK_FP32_MFMA_TFLOPS,
         "unit": "TFLOP/s",
