@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--M", type=int, default=None, help="override the number of centres")
     ap.add_argument("--cpu-rows", type=int, default=None, help="rows of the oracle's timing sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--cross", default="f32", choices=["f32", "f16x3"],
+                    help="arithmetic of the cross term: fp32 MFMA, or three split-fp16 MFMA products")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of known "
                          "traffic that calibrates the HBM byte counters of a rocprofv3 --pmc run)")
@@ -93,6 +95,7 @@ def main() -> int:
     v = synth.probe_vector(w.M, w.t, "normal", device="cuda")
     U = torch.empty(w.M, w.t, device="cuda", dtype=torch.float32)
     ctx = knm.default_context()
+    ctx.set_cross_term(args.cross)
     torch.cuda.synchronize()
     if args.copy_probe_mib > 0:
         src = torch.ones(args.copy_probe_mib * (1 << 18), device="cuda", dtype=torch.float32)

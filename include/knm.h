@@ -116,6 +116,18 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
                    const float *C, int64_t M, int64_t ldc, float sigma,
                    const float *alpha, int t, float *out);
 
+/* Arithmetic of the cross term <x, c> inside the kernel evaluation, for d <= 44 and t = 1
+ * (other shapes always use KNM_CROSS_F32):
+ *   KNM_CROSS_F32   fp32 MFMA (default).
+ *   KNM_CROSS_F16X3 each scaled feature is split into two fp16 halves (22 significant bits)
+ *                   and the product is evaluated as hi*hi + hi*lo + lo*hi on the f16 matrix
+ *                   cores with fp32 accumulation; norms are carried as exact fixed-point
+ *                   digits.  Same accuracy class as fp32 (error of the dropped lo*lo term
+ *                   ~2^-22 per feature); features scaled by sqrt(log2 e)/sigma must stay
+ *                   below 65000 in magnitude, larger values saturate.  About 3x faster. */
+typedef enum { KNM_CROSS_F32 = 0, KNM_CROSS_F16X3 = 1 } knm_cross_term;
+int knm_set_cross_term(knm_ctx *ctx, int mode);
+
 /* Timing aid for benchmarks: when enabled, knm_v / knm_prod / knm_t_y bracket their
  * kernels with HIP events on the context's stream.  knm_get_timing synchronises the
  * stream and writes milliseconds of the most recent call to the HOST array ms[4]:

@@ -49,6 +49,7 @@ SIGNATURES = {
     "falkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _int, _vp, _i64, _i64, _f32, _f64, _f64, _int,
                           _vp, _vp]),
     "falkon_predict": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
+    "knm_set_cross_term": (_int, [_vp, _int]),
     "knm_set_timing": (_int, [_vp, _int]),
     "knm_get_timing": (_int, [_vp, ctypes.POINTER(_f32)]),
 }
@@ -131,6 +132,11 @@ class Context:
     def check(self, st: int):
         if st != KNM_OK:
             raise KnmError(st, load_library().knm_last_error(self._h).decode())
+
+    def set_cross_term(self, mode):
+        """'f32' (fp32 MFMA, default) or 'f16x3' (split-fp16 products on the f16 matrix cores)."""
+        code = {"f32": 0, "f16x3": 1}[mode] if isinstance(mode, str) else int(mode)
+        self.check(load_library().knm_set_cross_term(self._h, code))
 
     # ---- timing -----------------------------------------------------------------------
     def set_timing(self, enabled: bool):

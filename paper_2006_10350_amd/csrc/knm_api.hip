@@ -101,7 +101,9 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.chunk_len = chunk_len;
         a.n_chunks = chunks;
         a.sigma = sigma;
-        hipError_t e = gemm ? launch_sweep_gemm(a, ctx->stream) : launch_sweep(a, ctx->stream);
+        const bool f16 = !gemm && ctx->cross_term == KNM_CROSS_F16X3 && d <= f16_max_d();
+        hipError_t e = gemm ? launch_sweep_gemm(a, ctx->stream)
+                            : (f16 ? launch_sweep_f16(a, ctx->stream) : launch_sweep(a, ctx->stream));
         if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "launch_sweep", e);
     }
     if (after_sweep) (void)hipEventRecord(after_sweep, ctx->stream);
@@ -285,6 +287,14 @@ int knm_t_y(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const f
     if (st) return st;
     mark(ctx, 3);
     mark(ctx, 4);
+    return KNM_OK;
+}
+
+int knm_set_cross_term(knm_ctx *ctx, int mode)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (mode != KNM_CROSS_F32 && mode != KNM_CROSS_F16X3) return fail(ctx, KNM_INVALID_ARG, "unknown cross-term mode");
+    ctx->cross_term = mode;
     return KNM_OK;
 }
 

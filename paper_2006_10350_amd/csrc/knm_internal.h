@@ -41,6 +41,9 @@ int small_max_d();
 int64_t stage_points();                 // stream points staged per LDS buffer
 int64_t fixed_per_block(int d);         // fixed points one workgroup covers
 hipError_t launch_sweep(const SweepArgs &a, hipStream_t stream);
+// same shapes with the cross term as three f16 MFMA products (knm_tile_f16.hip): d <= f16_max_d()
+int f16_max_d();
+hipError_t launch_sweep_f16(const SweepArgs &a, hipStream_t stream);
 // K-loop engine (knm_gemm.hip): any d, up to gemm_max_t() columns per launch
 int gemm_max_t();
 int64_t gemm_stage_points();
@@ -60,6 +63,7 @@ struct knm_ctx {
     size_t w_bytes = 0;
     float *part_buf = nullptr;
     size_t part_bytes = 0;
+    int cross_term = KNM_CROSS_F32;
     // timing
     bool timing = false;
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};

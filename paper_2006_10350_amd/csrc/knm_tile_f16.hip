@@ -1,0 +1,392 @@
+// Gaussian-kernel tile engine with the cross term on the f16 matrix cores:
+//     out[f] = sum_s k(F_f, S_s) vec[s]          (d <= 44, one column per launch)
+//
+// Same computation as knm_tile.hip (Section 3.1, "Blockwise K_nm-vector product"; Gaussian
+// kernel of Section 2), different arithmetic for the contraction over d.  Measured on
+// gfx950, fp32 MFMA shares the vector ALU's issue with the exp/FMA work that finishes
+// every kernel entry, so the fp32 engine is bound by MFMA time PLUS VALU time.  The f16
+// MFMA (v_mfma_f32_32x32x16_f16, 16x the rate, products exact, fp32 accumulation, fp16
+// subnormal inputs honoured -- all checked on the device) runs beside the VALU instead.
+// To keep fp32-level accuracy every scaled feature z = x sqrt(log2(e)) / sigma is split
+// into two halves, z = zh + zl (22 significant bits), and the cross term is evaluated as
+//     <f, x>  ~=  fh.xh + fh.xl + fl.xh                        (drops fl.xl ~ 2^-22)
+// i.e. three "planes" of the same MFMA shape.  With this scaling the base-2 exponent is
+//     log2 k(f, x) = <zf, zx> - |zf|^2 / 2 - |zx|^2 / 2 .
+// The two norm terms ride in four spare K-slots per side as 4-digit fixed-point numbers,
+//     n = q1 2^13 + q2 2^2 + q3 2^-9 + q4 2^-20,   q_i integers <= 2048 (exact in fp16),
+// multiplied by the constants 2^13, 2^2, 2^-9, 2^-20 on the other operand, so the MFMA
+// accumulator again holds the exponent itself (resolution 2^-21, range 2^24).
+// Inputs outside the fp16 range (|z| > 65000, norm term >= 2^24) saturate.
+//
+// Layout.  A K=16 MFMA takes 8 halves ("unit") from each half-wave.  Unit u holds
+// features 8u .. 8u+7; the last four slots of the last unit are the special slots.
+// Plane 1 = (fh | -q^f) x (xh | consts), plane 2 = (fh | consts) x (xl | -q^x),
+// plane 3 = (fl | 0) x (xh | consts); the stream side keeps two register sets (xh, xl), the
+// fixed side three (fh, a variant of fh's last MFMA operand with the constants, fl).
+//
+// Schedule.  Accumulators are double-buffered across stream tiles: while the matrix
+// cores run the 3 NU MFMAs of tile k (two fixed blocks), the VALU finishes tile k-1
+// (exp, FMA), spread behind the MFMAs.  The hot instructions are volatile inline
+// assembly so this order survives the compiler; no MFMA result is read until a whole
+// tile after it was issued, and no exp result by the instruction right after it.
+
+#include "knm_internal.h"
+
+namespace knm {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kStage = 128; // stream points per LDS stage (2 threads per point)
+constexpr int kTilesPerStage = kStage / 32;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kC1 = 8192.0f, kC2 = 4.0f, kC3 = 0.001953125f, kC4 = 9.5367431640625e-07f; // 2^13 2^2 2^-9 2^-20
+
+__device__ __forceinline__ void split_half(float z, _Float16 &hi, _Float16 &lo)
+{
+    z = fminf(fmaxf(z, -65000.0f), 65000.0f);
+    hi = (_Float16)z;
+    lo = (_Float16)(z - (float)hi);
+}
+
+// -n as four fixed-point digits (see the header comment); n >= 0
+__device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
+{
+    n = fminf(n, 16777215.0f);
+    const float q1 = floorf(n * (1.0f / 8192.0f));
+    float r = fmaf(-q1, 8192.0f, n);
+    const float q2 = floorf(r * 0.25f);
+    r = fmaf(-q2, 4.0f, r);
+    const float q3 = floorf(r * 512.0f);
+    r = fmaf(-q3, kC3, r);
+    const float q4 = rintf(r * 1048576.0f);
+    q[0] = (_Float16)(-q1); q[1] = (_Float16)(-q2); q[2] = (_Float16)(-q3); q[3] = (_Float16)(-q4);
+}
+
+// branch-free row loads (see knm_tile.hip): virtual features [base, base + N), zero beyond d
+template <int N, int VW>
+__device__ __forceinline__ void load_features(const float *__restrict__ row, int base, int d, bool valid,
+                                              float (&x)[N])
+{
+    if constexpr (VW == 4) {
+#pragma unroll
+        for (int k = 0; k < N; k += 4) {
+            const bool in = valid && (base + k < d); // d % 4 == 0 in this mode
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(row + (in ? base + k : 0));
+            x[k] = in ? v[0] : 0.0f; x[k + 1] = in ? v[1] : 0.0f; x[k + 2] = in ? v[2] : 0.0f; x[k + 3] = in ? v[3] : 0.0f;
+        }
+    } else if constexpr (VW == 2) {
+#pragma unroll
+        for (int k = 0; k < N; k += 2) {
+            const bool in = valid && (base + k < d); // d % 2 == 0 in this mode
+            const f32x2 v = *reinterpret_cast<const f32x2 *>(row + (in ? base + k : 0));
+            x[k] = in ? v[0] : 0.0f; x[k + 1] = in ? v[1] : 0.0f;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            const bool in = valid && (base + k < d);
+            const float v = row[in ? base + k : 0];
+            x[k] = in ? v : 0.0f;
+        }
+    }
+}
+
+// ---- one MFMA followed by G (exp, FMA) pairs of the previous tile -------------------------
+#define KNM_MFMA_FIRST "v_mfma_f32_32x32x16_f16 %[acc], %[a], %[b], 0\n\t"
+#define KNM_MFMA_NEXT "v_mfma_f32_32x32x16_f16 %[acc], %[a], %[b], %[acc]\n\t"
+#define KNM_EXP(i) "v_exp_f32_e64 %[p" #i "], %[x" #i "] clamp\n\t"
+#define KNM_FMA(i) "v_fmac_f32_e32 %[s" #i "], %[p" #i "], %[vl]\n\t"
+#define KNM_P(i) [p##i] "=&v"(p##i)
+#define KNM_S(i) [s##i] "+v"(s[R0 + i])
+#define KNM_X(i) [x##i] "v"(pa[R0 + i])
+
+template <bool FIRST, int G, int R0>
+__device__ __forceinline__ void mfma_step(f32x16 &acc, const f16x8 &a, const f16x8 &b, const f32x16 &pa, float vl,
+                                          float (&s)[16])
+{
+    float p0, p1, p2, p3, p4, p5;
+    (void)p0; (void)p1; (void)p2; (void)p3; (void)p4; (void)p5;
+    if constexpr (FIRST) {
+        static_assert(G == 1 || G == 2 || G == 3 || G == 5, "first step of a chain");
+        if constexpr (G == 1)
+            asm volatile(KNM_MFMA_FIRST KNM_EXP(0) "s_nop 0\n\t" KNM_FMA(0)
+                         : [acc] "=&v"(acc), KNM_P(0), KNM_S(0)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), [vl] "v"(vl));
+        else if constexpr (G == 2)
+            asm volatile(KNM_MFMA_FIRST KNM_EXP(0) KNM_EXP(1) KNM_FMA(0) KNM_FMA(1)
+                         : [acc] "=&v"(acc), KNM_P(0), KNM_P(1), KNM_S(0), KNM_S(1)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), KNM_X(1), [vl] "v"(vl));
+        else if constexpr (G == 3)
+            asm volatile(KNM_MFMA_FIRST KNM_EXP(0) KNM_EXP(1) KNM_EXP(2) KNM_FMA(0) KNM_FMA(1) KNM_FMA(2)
+                         : [acc] "=&v"(acc), KNM_P(0), KNM_P(1), KNM_P(2), KNM_S(0), KNM_S(1), KNM_S(2)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), KNM_X(1), KNM_X(2), [vl] "v"(vl));
+        else
+            asm volatile(KNM_MFMA_FIRST KNM_EXP(0) KNM_EXP(1) KNM_EXP(2) KNM_EXP(3) KNM_EXP(4) KNM_FMA(0) KNM_FMA(1)
+                             KNM_FMA(2) KNM_FMA(3) KNM_FMA(4)
+                         : [acc] "=&v"(acc), KNM_P(0), KNM_P(1), KNM_P(2), KNM_P(3), KNM_P(4), KNM_S(0), KNM_S(1),
+                           KNM_S(2), KNM_S(3), KNM_S(4)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), KNM_X(1), KNM_X(2), KNM_X(3), KNM_X(4), [vl] "v"(vl));
+    } else {
+        static_assert(G >= 1 && G <= 6 && G != 4, "group size");
+        if constexpr (G == 1)
+            asm volatile(KNM_MFMA_NEXT KNM_EXP(0) "s_nop 0\n\t" KNM_FMA(0)
+                         : [acc] "+v"(acc), KNM_P(0), KNM_S(0)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), [vl] "v"(vl));
+        else if constexpr (G == 2)
+            asm volatile(KNM_MFMA_NEXT KNM_EXP(0) KNM_EXP(1) KNM_FMA(0) KNM_FMA(1)
+                         : [acc] "+v"(acc), KNM_P(0), KNM_P(1), KNM_S(0), KNM_S(1)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), KNM_X(1), [vl] "v"(vl));
+        else if constexpr (G == 3)
+            asm volatile(KNM_MFMA_NEXT KNM_EXP(0) KNM_EXP(1) KNM_EXP(2) KNM_FMA(0) KNM_FMA(1) KNM_FMA(2)
+                         : [acc] "+v"(acc), KNM_P(0), KNM_P(1), KNM_P(2), KNM_S(0), KNM_S(1), KNM_S(2)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), KNM_X(1), KNM_X(2), [vl] "v"(vl));
+        else if constexpr (G == 5)
+            asm volatile(KNM_MFMA_NEXT KNM_EXP(0) KNM_EXP(1) KNM_EXP(2) KNM_EXP(3) KNM_EXP(4) KNM_FMA(0) KNM_FMA(1)
+                             KNM_FMA(2) KNM_FMA(3) KNM_FMA(4)
+                         : [acc] "+v"(acc), KNM_P(0), KNM_P(1), KNM_P(2), KNM_P(3), KNM_P(4), KNM_S(0), KNM_S(1),
+                           KNM_S(2), KNM_S(3), KNM_S(4)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), KNM_X(1), KNM_X(2), KNM_X(3), KNM_X(4), [vl] "v"(vl));
+        else
+            asm volatile(KNM_MFMA_NEXT KNM_EXP(0) KNM_EXP(1) KNM_EXP(2) KNM_EXP(3) KNM_EXP(4) KNM_EXP(5) KNM_FMA(0)
+                             KNM_FMA(1) KNM_FMA(2) KNM_FMA(3) KNM_FMA(4) KNM_FMA(5)
+                         : [acc] "+v"(acc), KNM_P(0), KNM_P(1), KNM_P(2), KNM_P(3), KNM_P(4), KNM_P(5), KNM_S(0),
+                           KNM_S(1), KNM_S(2), KNM_S(3), KNM_S(4), KNM_S(5)
+                         : [a] "v"(a), [b] "v"(b), KNM_X(0), KNM_X(1), KNM_X(2), KNM_X(3), KNM_X(4), KNM_X(5),
+                           [vl] "v"(vl));
+    }
+}
+
+// The 3 HU MFMAs of one fixed block on one stream tile, with the 16 (exp, FMA) pairs that
+// finish the same block's accumulator of the previous tile (`pa`, weight `vl_prev`).
+template <int HU, int I = 0>
+__device__ __forceinline__ void block_tile(f32x16 &acc, const f16x8 (&fh)[HU], const f16x8 &fhv,
+                                           const f16x8 (&fl)[HU], const f16x8 (&bh)[HU], const f16x8 (&bl)[HU],
+                                           const f32x16 &pa, float vl_prev, float (&s)[16])
+{
+    constexpr int NM = 3 * HU;
+    if constexpr (I < NM) {
+        constexpr int R0 = (16 * I) / NM;
+        constexpr int G = (16 * (I + 1)) / NM - R0;
+        constexpr int plane = I / HU, m = I % HU;
+        const f16x8 &a = plane == 0 ? fh[m] : (plane == 1 ? (m == HU - 1 ? fhv : fh[m]) : fl[m]);
+        const f16x8 &b = plane == 1 ? bl[m] : bh[m];
+        mfma_step<I == 0, G, R0>(acc, a, b, pa, vl_prev, s);
+        block_tile<HU, I + 1>(acc, fh, fhv, fl, bh, bl, pa, vl_prev, s);
+    }
+}
+
+template <int NU, int VW>
+__global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs a)
+{
+    constexpr int HU = NU / 2;       // MFMAs per plane
+    constexpr int FPT = 8 * HU;      // features staged per thread (half a point)
+    static_assert(NU % 2 == 0 && NU >= 2, "an MFMA takes two units");
+
+    __shared__ f16x8 img[2][kTilesPerStage][2][HU][64]; // [buffer][tile][plane xh/xl][mfma][lane]
+    __shared__ float vv[2][kStage];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int row = lane & 31;
+    const int h = lane >> 5;
+    const float gamma = sqrtf(kLog2e) / a.sigma;
+    const int d = a.d;
+
+    // ---- fixed operand: 2 blocks of 32 points per wavefront, in registers -----------------
+    const int64_t fixed0 = ((int64_t)blockIdx.x * kWaves + wave) * 64;
+    f16x8 fh[2][HU], fl[2][HU], fhv[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int64_t idx = fixed0 + rb * 32 + row;
+        const bool valid = idx < a.nF;
+        const float *p = a.F + (valid ? idx : 0) * a.ldf;
+        float nrm = 0.0f;
+#pragma unroll
+        for (int m = 0; m < HU; ++m) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = 8 * (2 * m + h) + e;
+                const float z = (valid && k < d) ? gamma * p[k] : 0.0f;
+                nrm = fmaf(z, z, nrm);
+                _Float16 zh, zl;
+                split_half(z, zh, zl);
+                fh[rb][m][e] = zh;
+                fl[rb][m][e] = zl;
+            }
+        }
+        nrm += __shfl_xor(nrm, 32);
+        _Float16 q[4];
+        norm_digits(valid ? 0.5f * nrm : 0.0f, q);
+        fhv[rb] = fh[rb][HU - 1];
+        if (h == 1) { // the special slots live in the last unit, which half-wave 1 supplies
+            fh[rb][HU - 1][4] = q[0]; fh[rb][HU - 1][5] = q[1]; fh[rb][HU - 1][6] = q[2]; fh[rb][HU - 1][7] = q[3];
+            fhv[rb][4] = (_Float16)kC1; fhv[rb][5] = (_Float16)kC2; fhv[rb][6] = (_Float16)kC3; fhv[rb][7] = (_Float16)kC4;
+        }
+    }
+
+    float sum[2][16];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[rb][r] = 0.0f;
+
+    // ---- stream staging: thread (p, part) converts half of one point per stage ---------------
+    const int sp = tid >> 1;
+    const int part = tid & 1;
+    const int64_t chunk_begin = (int64_t)blockIdx.y * a.chunk_len;
+    int64_t chunk_end = chunk_begin + a.chunk_len;
+    if (chunk_end > a.nS) chunk_end = a.nS;
+    const int n_stages = (int)((chunk_end - chunk_begin + kStage - 1) / kStage);
+
+    float xs[FPT];
+    float vs = 0.0f;
+    auto fetch = [&](int stage) {
+        const int64_t idx = chunk_begin + (int64_t)stage * kStage + sp;
+        const bool valid = idx < chunk_end;
+        const float *p = a.S + (valid ? idx : 0) * a.lds;
+        load_features<FPT, VW>(p, part * FPT, d, valid, xs);
+        const int64_t vi = valid ? idx : 0;
+        const float vraw = a.vec[vi * a.ldv];
+        const float wraw = (a.wgt != nullptr) ? a.wgt[vi] : 1.0f;
+        vs = valid ? vraw * wraw : 0.0f;
+    };
+    auto commit = [&](int buf) {
+        float nrm = 0.0f;
+#pragma unroll
+        for (int k = 0; k < FPT; ++k) {
+            xs[k] *= gamma;
+            nrm = fmaf(xs[k], xs[k], nrm);
+        }
+        nrm += __shfl_xor(nrm, 1);
+        _Float16 q[4];
+        norm_digits(0.5f * nrm, q);
+        const int tile = sp >> 5;
+        const int prow = sp & 31;
+#pragma unroll
+        for (int j = 0; j < HU; ++j) {
+            const int u = part * HU + j; // unit of the point
+            f16x8 hi, lo;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                _Float16 zh, zl;
+                split_half(xs[8 * j + e], zh, zl);
+                hi[e] = zh;
+                lo[e] = zl;
+            }
+            if (j == HU - 1 && part == 1) { // last unit: constants beside xh, norm digits beside xl
+                hi[4] = (_Float16)kC1; hi[5] = (_Float16)kC2; hi[6] = (_Float16)kC3; hi[7] = (_Float16)kC4;
+                lo[4] = q[0]; lo[5] = q[1]; lo[6] = q[2]; lo[7] = q[3];
+            }
+            img[buf][tile][0][u >> 1][(u & 1) * 32 + prow] = hi;
+            img[buf][tile][1][u >> 1][(u & 1) * 32 + prow] = lo;
+        }
+        if (part == 0) vv[buf][sp] = vs;
+    };
+
+    // accumulators of the tile in flight (cur) and of the tile being finished (prev)
+    f32x16 accA[2], accB[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { accA[rb][r] = 0.0f; accB[rb][r] = 0.0f; }
+    float vl_prev = 0.0f; // zero weight: the first "previous tile" contributes nothing
+
+    if (n_stages > 0) fetch(0);
+    for (int st = 0; st < n_stages; ++st) {
+        const int buf = st & 1;
+        commit(buf);
+        __syncthreads();
+        if (st + 1 < n_stages) fetch(st + 1);
+
+        f16x8 bh[2][HU], bl[2][HU];
+        float vl[2];
+        auto read_tile = [&](int tile, int slot) {
+#pragma unroll
+            for (int m = 0; m < HU; ++m) {
+                bh[slot][m] = img[buf][tile][0][m][lane];
+                bl[slot][m] = img[buf][tile][1][m][lane];
+            }
+            vl[slot] = vv[buf][tile * 32 + row];
+        };
+        read_tile(0, 0);
+#pragma unroll
+        for (int tile = 0; tile < kTilesPerStage; ++tile) {
+            const int cur = tile & 1;
+            if (tile + 1 < kTilesPerStage) read_tile(tile + 1, cur ^ 1);
+            if (cur == 0) {
+                block_tile<HU>(accA[0], fh[0], fhv[0], fl[0], bh[cur], bl[cur], accB[0], vl_prev, sum[0]);
+                block_tile<HU>(accA[1], fh[1], fhv[1], fl[1], bh[cur], bl[cur], accB[1], vl_prev, sum[1]);
+            } else {
+                block_tile<HU>(accB[0], fh[0], fhv[0], fl[0], bh[cur], bl[cur], accA[0], vl_prev, sum[0]);
+                block_tile<HU>(accB[1], fh[1], fhv[1], fl[1], bh[cur], bl[cur], accA[1], vl_prev, sum[1]);
+            }
+            vl_prev = vl[cur];
+        }
+    }
+    // the last tile's accumulators (tiles per stage is even, so they are in set B)
+    static_assert(kTilesPerStage % 2 == 0, "accumulator sets alternate per tile");
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(accB[rb][r]), 0.0f, 1.0f);
+            sum[rb][r] = fmaf(p, vl_prev, sum[rb][r]);
+        }
+
+    // ---- reduce over the 32 stream lanes of each half-wave and store ----------------------
+    float *out = a.out + (int64_t)blockIdx.y * a.chunk_stride;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float v = sum[rb][r];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 8);
+            v += __shfl_xor(v, 4);
+            v += __shfl_xor(v, 2);
+            v += __shfl_xor(v, 1);
+            const int64_t idx = fixed0 + rb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+            if (row == 0 && idx < a.nF) out[idx * a.ldo] = v;
+        }
+}
+
+template <int NU>
+hipError_t launch_nu(const SweepArgs &a, hipStream_t stream)
+{
+    const int64_t per_block = (int64_t)kWaves * 64;
+    const int64_t blocks = (a.nF + per_block - 1) / per_block;
+    dim3 grid((unsigned)blocks, (unsigned)a.n_chunks);
+    const bool a16 = (a.d % 4 == 0) && (a.lds % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.S) & 15) == 0);
+    const bool a8 = (a.d % 2 == 0) && (a.lds % 2 == 0) && ((reinterpret_cast<uintptr_t>(a.S) & 7) == 0);
+    if (a16)
+        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, 4>), grid, dim3(kThreads), 0, stream, a);
+    else if (a8)
+        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, 2>), grid, dim3(kThreads), 0, stream, a);
+    else
+        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, 1>), grid, dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+} // namespace
+
+int f16_max_d() { return 44; } // 6 units of 8 features; larger images exceed 64 KB of static LDS
+
+hipError_t launch_sweep_f16(const SweepArgs &a, hipStream_t stream)
+{
+    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t != 1 || a.d > f16_max_d()) return hipErrorInvalidValue;
+    if (a.chunk_len % kStage != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
+    if (a.n_chunks > 65535) return hipErrorInvalidValue;
+    // units of 8 features; the last unit keeps 4 slots for the norm digits
+    if (a.d <= 12) return launch_nu<2>(a, stream);
+    if (a.d <= 28) return launch_nu<4>(a, stream);
+    return launch_nu<6>(a, stream);
+}
+
+} // namespace knm

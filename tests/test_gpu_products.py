@@ -19,6 +19,15 @@ TOL = 1e-4
 TIGHT = 2e-5
 
 
+@pytest.fixture(params=["f32", "f16x3"])
+def cross(request, knm):
+    """Runs a test once per cross-term arithmetic (fp32 MFMA / split-fp16 MFMA)."""
+    ctx = knm.default_context()
+    ctx.set_cross_term(request.param)
+    yield request.param
+    ctx.set_cross_term("f32")
+
+
 def rel_l2(got, ref):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
@@ -51,7 +60,7 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("n,M,d,t,sigma", SHAPES)
-def test_products_match_oracle(knm, n, M, d, t, sigma):
+def test_products_match_oracle(knm, cross, n, M, d, t, sigma):
     print(f"case n={n} M={M} d={d} t={t}", flush=True)
     X, C = _rand(n, d, 1), _rand(M, d, 2)
     V = _rand(M, t, 3)
@@ -77,7 +86,7 @@ def test_products_match_oracle(knm, n, M, d, t, sigma):
 
 
 @pytest.mark.parametrize("kind", ["ones", "unit"])
-def test_special_vectors(knm, kind):
+def test_special_vectors(knm, cross, kind):
     n, M, d, sigma = 3000, 700, 28, 4.0
     X, C = _rand(n, d, 5), _rand(M, d, 6)
     v = synth.probe_vector(M, 1, kind, j=123)
@@ -85,7 +94,7 @@ def test_special_vectors(knm, kind):
     assert rel_l2(U, oracle.knm_prod(X.numpy(), C.numpy(), sigma, v.numpy())) < TIGHT
 
 
-def test_weighted_product(knm):
+def test_weighted_product(knm, cross):
     n, M, d, sigma = 2500, 300, 9, 2.0
     X, C, V = _rand(n, d, 7), _rand(M, d, 8), _rand(M, 2, 9)
     dw = torch.rand(n, generator=torch.Generator().manual_seed(10)) + 0.05
@@ -94,7 +103,7 @@ def test_weighted_product(knm):
     assert rel_l2(U, ref) < TIGHT
 
 
-def test_strided_points_and_determinism(knm):
+def test_strided_points_and_determinism(knm, cross):
     n, M, d, sigma = 1200, 333, 10, 2.0
     Xw = _rand(n, 16, 11).cuda()
     Cw = _rand(M, 13, 12).cuda()
@@ -107,7 +116,7 @@ def test_strided_points_and_determinism(knm):
     assert rel_l2(U1.cpu().numpy(), ref) < TIGHT
 
 
-def test_degenerate_sizes(knm):
+def test_degenerate_sizes(knm, cross):
     sigma = 1.0
     X, C = _rand(1, 3, 14), _rand(1, 3, 15)
     v = torch.tensor([[2.0]])
@@ -127,7 +136,7 @@ def test_degenerate_sizes(knm):
     assert np.array_equal(W, np.zeros_like(W))
 
 
-def test_large_norm_close_pairs(knm):
+def test_large_norm_close_pairs(knm, cross):
     # the cancellation hazard of the norm expansion: large |x|, small distances.
     # With |x|^2 ~ 1e3 the fp32 expansion keeps ~1e-4 absolute accuracy on the exponent.
     n, M, d, sigma = 2000, 256, 8, 1.0
@@ -137,6 +146,31 @@ def test_large_norm_close_pairs(knm):
     V = torch.ones(M, 1)
     W = knm.knm_v(X.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
     assert rel_l2(W, oracle.knm_v(X.numpy(), C.numpy(), sigma, V.numpy())) < 1e-3
+
+
+def test_split_half_range_limits(knm):
+    """The split-fp16 cross term saturates instead of producing Inf/NaN, and huge norms
+    (far outliers) still give exact zeros against ordinary points."""
+    ctx = knm.default_context()
+    ctx.set_cross_term("f16x3")
+    try:
+        n, M, d, sigma = 512, 256, 9, 1.0
+        X, C = _rand(n, d, 50), _rand(M, d, 51)
+        X[7, 3] = 3.0e2       # norm term ~ 6.5e4: needs the upper fixed-point digits
+        X[11, 0] = 2.0e5      # beyond fp16: saturates
+        C[5] = X[7]           # an outlier centre equal to an outlier row
+        V = torch.ones(M, 1)
+        W = knm.knm_v(X.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
+        Wo = oracle.knm_v(X.numpy(), C.numpy(), sigma, V.numpy())
+        assert np.all(np.isfinite(W))
+        keep = np.ones(n, dtype=bool)
+        keep[11] = False
+        keep[7] = False       # its twin centre: |x|^2 ~ 1e5 cancels to 0, fp32 keeps ~1e-2 of the exponent
+        assert rel_l2(W[keep], Wo[keep]) < 1e-4
+        assert W[7, 0] == pytest.approx(Wo[7, 0], rel=2e-2) and Wo[7, 0] >= 1.0  # sees its twin centre
+        assert abs(W[11, 0]) < 1e-6
+    finally:
+        ctx.set_cross_term("f32")
 
 
 def test_invalid_arguments_are_rejected(knm):
@@ -152,7 +186,7 @@ def test_invalid_arguments_are_rejected(knm):
         knm.knm_v(X, _rand(5, 3, 25).cuda(), 1.0, V)
 
 
-def test_tiny_workload_full_product(knm):
+def test_tiny_workload_full_product(knm, cross):
     w = synth.workload("tiny")
     inp = synth.make_inputs(w, device="cpu")
     X, C = inp["X"], inp["C"]
@@ -166,7 +200,7 @@ def test_tiny_workload_full_product(knm):
 
 
 @pytest.mark.parametrize("name,n_sub,M_sub", [("mid", 1 << 15, 4096), ("lowdim", 1 << 15, 4096), ("billion", 1 << 15, 4096)])
-def test_workload_shaped_sample(knm, name, n_sub, M_sub):
+def test_workload_shaped_sample(knm, cross, name, n_sub, M_sub):
     """Rows and centres drawn with a workload's distribution (heavy tails included)."""
     w = synth.workload(name, n=n_sub, M=M_sub)
     inp = synth.make_inputs(w, device="cpu", with_targets=False)
