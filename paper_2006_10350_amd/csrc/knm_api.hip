@@ -102,8 +102,21 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.n_chunks = chunks;
         a.sigma = sigma;
         const bool f16 = !gemm && ctx->cross_term == KNM_CROSS_F16X3 && d <= f16_max_d();
-        hipError_t e = gemm ? launch_sweep_gemm(a, ctx->stream)
-                            : (f16 ? launch_sweep_f16(a, ctx->stream) : launch_sweep(a, ctx->stream));
+        hipError_t e;
+        if (gemm) {
+            e = launch_sweep_gemm(a, ctx->stream);
+        } else if (f16) {
+            // packed image of the stream points: all of it, or slabs of at most 1 GiB
+            const size_t per_point = f16_pack_bytes_per_point(d);
+            size_t want = per_point * (size_t)(chunks * chunk_len);
+            const size_t cap = (size_t)1 << 30;
+            if (want > cap) want = (cap / (per_point * chunk_len) + 1) * per_point * chunk_len;
+            int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
+            if (st) return st;
+            e = launch_sweep_f16(a, ctx->pack_buf, ctx->pack_bytes, ctx->stream);
+        } else {
+            e = launch_sweep(a, ctx->stream);
+        }
         if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "launch_sweep", e);
     }
     if (after_sweep) (void)hipEventRecord(after_sweep, ctx->stream);
@@ -178,6 +191,7 @@ int knm_destroy(knm_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->w_buf) (void)hipFree(ctx->w_buf);
     if (ctx->part_buf) (void)hipFree(ctx->part_buf);
+    if (ctx->pack_buf) (void)hipFree(ctx->pack_buf);
     for (int i = 0; i < 5; ++i)
         if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     extern void knm_solver_release(knm_ctx *);

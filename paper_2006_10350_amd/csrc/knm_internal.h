@@ -43,7 +43,9 @@ int64_t fixed_per_block(int d);         // fixed points one workgroup covers
 hipError_t launch_sweep(const SweepArgs &a, hipStream_t stream);
 // same shapes with the cross term as three f16 MFMA products (knm_tile_f16.hip): d <= f16_max_d()
 int f16_max_d();
-hipError_t launch_sweep_f16(const SweepArgs &a, hipStream_t stream);
+size_t f16_pack_bytes_per_point(int d);
+// pack_buf: device workspace for the packed stream image, at least one chunk's worth
+hipError_t launch_sweep_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream);
 // K-loop engine (knm_gemm.hip): any d, up to gemm_max_t() columns per launch
 int gemm_max_t();
 int64_t gemm_stage_points();
@@ -63,6 +65,8 @@ struct knm_ctx {
     size_t w_bytes = 0;
     float *part_buf = nullptr;
     size_t part_bytes = 0;
+    float *pack_buf = nullptr; // packed stream image of the split-fp16 engine
+    size_t pack_bytes = 0;
     int cross_term = KNM_CROSS_F32;
     // timing
     bool timing = false;

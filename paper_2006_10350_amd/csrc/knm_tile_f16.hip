@@ -24,6 +24,14 @@
 // plane 3 = (fl | 0) x (xh | consts); the stream side keeps two register sets (xh, xl), the
 // fixed side three (fh, a variant of fh's last MFMA operand with the constants, fl).
 //
+// Packing.  Converting a stream point (scale, split, norm digits) costs ~10 VALU
+// instructions per feature, and every workgroup of a sweep would repeat it for the same
+// points.  A small pre-pass (`pack_stream_kernel`) therefore converts the stream points
+// once into a packed image in device memory, laid out exactly as the LDS stage (per
+// 32-point tile: [plane xh/xl][MFMA][lane] units of 8 halves); the sweep's staging is then
+// a straight 16-byte copy.  The image is built slab by slab (bounded workspace) and the
+// sweep is launched once per slab.
+//
 // Schedule.  Accumulators are double-buffered across stream tiles: while the matrix
 // cores run the 3 NU MFMAs of tile k (two fixed blocks), the VALU finishes tile k-1
 // (exp, FMA), spread behind the MFMAs.  The hot instructions are volatile inline
@@ -52,6 +60,19 @@ __device__ __forceinline__ void split_half(float z, _Float16 &hi, _Float16 &lo)
     z = fminf(fmaxf(z, -65000.0f), 65000.0f);
     hi = (_Float16)z;
     lo = (_Float16)(z - (float)hi);
+}
+
+typedef __fp16 f16x2 __attribute__((ext_vector_type(2)));
+// Two features at once: hi with the packed round-toward-zero conversion (which saturates at
+// the largest finite half instead of overflowing), lo = nearest half of the exact remainder
+// z - hi; hi + lo carries 22 significant bits of z.
+__device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 &lo)
+{
+    hi = __builtin_amdgcn_cvt_pkrtz(z0, z1);
+    f32x2 rem;
+    rem[0] = z0 - (float)hi[0];
+    rem[1] = z1 - (float)hi[1];
+    lo = __builtin_convertvector(rem, f16x2);
 }
 
 // -n as four fixed-point digits (see the header comment); n >= 0
@@ -181,11 +202,64 @@ __device__ __forceinline__ void block_tile(f32x16 &acc, const f16x8 (&fh)[HU], c
     }
 }
 
+// Packed image of stream points [row0, row0 + rows) (rows beyond nS are zero points):
+// tile g of the slab occupies 2 * HU * 64 units at packed + g * 2 * HU * 64.
 template <int NU, int VW>
-__global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs a)
+__global__ __launch_bounds__(kThreads) void pack_stream_kernel(const float *__restrict__ S, int64_t nS, int64_t lds,
+                                                               int d, float sigma, int64_t row0, int64_t rows,
+                                                               f16x8 *__restrict__ packed)
 {
-    constexpr int HU = NU / 2;       // MFMAs per plane
-    constexpr int FPT = 8 * HU;      // features staged per thread (half a point)
+    constexpr int HU = NU / 2;
+    constexpr int FPT = 8 * HU;
+    const int tid = threadIdx.x;
+    const int part = tid & 1;
+    const int64_t rel = (int64_t)blockIdx.x * (kThreads / 2) + (tid >> 1); // point within the slab
+    if (rel >= rows) return;
+    const int64_t idx = row0 + rel;
+    const bool valid = idx < nS;
+    const float gamma = sqrtf(kLog2e) / sigma;
+    float xs[FPT];
+    load_features<FPT, VW>(S + (valid ? idx : 0) * lds, part * FPT, d, valid, xs);
+    float nrm = 0.0f;
+#pragma unroll
+    for (int k = 0; k < FPT; ++k) {
+        xs[k] *= gamma;
+        nrm = fmaf(xs[k], xs[k], nrm);
+    }
+    nrm += __shfl_xor(nrm, 1);
+    _Float16 q[4];
+    norm_digits(0.5f * nrm, q);
+    f16x8 *tile = packed + (rel >> 5) * (2 * HU * 64);
+    const int prow = (int)(rel & 31);
+#pragma unroll
+    for (int j = 0; j < HU; ++j) {
+        const int u = part * HU + j; // unit of the point
+        f16x8 hi, lo;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            f16x2 ph, pl;
+            split_pair(xs[8 * j + e], xs[8 * j + e + 1], ph, pl);
+            hi[e] = (_Float16)ph[0]; hi[e + 1] = (_Float16)ph[1];
+            lo[e] = (_Float16)pl[0]; lo[e + 1] = (_Float16)pl[1];
+        }
+        if (j == HU - 1 && part == 1) { // last unit: constants beside xh, norm digits beside xl
+            hi[4] = (_Float16)kC1; hi[5] = (_Float16)kC2; hi[6] = (_Float16)kC3; hi[7] = (_Float16)kC4;
+            lo[4] = q[0]; lo[5] = q[1]; lo[6] = q[2]; lo[7] = q[3];
+        }
+        tile[(0 * HU + (u >> 1)) * 64 + (u & 1) * 32 + prow] = hi;
+        tile[(1 * HU + (u >> 1)) * 64 + (u & 1) * 32 + prow] = lo;
+    }
+}
+
+// `packed` is the image of the stream chunks [chunk0, chunk0 + gridDim.y) built by
+// pack_stream_kernel; blockIdx.y counts chunks within that slab.
+template <int NU>
+__global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs a, const f16x8 *__restrict__ packed,
+                                                                      int64_t chunk0)
+{
+    constexpr int HU = NU / 2;                      // MFMAs per plane
+    constexpr int UPS = kTilesPerStage * 2 * HU * 64; // 16-byte units per stage
+    constexpr int UPT = UPS / kThreads;             // units copied per thread and stage
     static_assert(NU % 2 == 0 && NU >= 2, "an MFMA takes two units");
 
     __shared__ f16x8 img[2][kTilesPerStage][2][HU][64]; // [buffer][tile][plane xh/xl][mfma][lane]
@@ -237,57 +311,31 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
 #pragma unroll
         for (int r = 0; r < 16; ++r) sum[rb][r] = 0.0f;
 
-    // ---- stream staging: thread (p, part) converts half of one point per stage ---------------
-    const int sp = tid >> 1;
-    const int part = tid & 1;
-    const int64_t chunk_begin = (int64_t)blockIdx.y * a.chunk_len;
+    // ---- stream staging: a straight copy of the packed image, 16 bytes per thread and unit --------
+    const int64_t chunk = chunk0 + blockIdx.y;
+    const int64_t chunk_begin = chunk * a.chunk_len;
     int64_t chunk_end = chunk_begin + a.chunk_len;
     if (chunk_end > a.nS) chunk_end = a.nS;
     const int n_stages = (int)((chunk_end - chunk_begin + kStage - 1) / kStage);
+    const f16x8 *src = packed + ((int64_t)blockIdx.y * a.chunk_len / kStage) * UPS + tid;
 
-    float xs[FPT];
+    f16x8 xs[UPT];
     float vs = 0.0f;
     auto fetch = [&](int stage) {
-        const int64_t idx = chunk_begin + (int64_t)stage * kStage + sp;
+#pragma unroll
+        for (int k = 0; k < UPT; ++k) xs[k] = src[(int64_t)stage * UPS + k * kThreads];
+        const int64_t idx = chunk_begin + (int64_t)stage * kStage + (tid & (kStage - 1));
         const bool valid = idx < chunk_end;
-        const float *p = a.S + (valid ? idx : 0) * a.lds;
-        load_features<FPT, VW>(p, part * FPT, d, valid, xs);
         const int64_t vi = valid ? idx : 0;
         const float vraw = a.vec[vi * a.ldv];
         const float wraw = (a.wgt != nullptr) ? a.wgt[vi] : 1.0f;
         vs = valid ? vraw * wraw : 0.0f;
     };
     auto commit = [&](int buf) {
-        float nrm = 0.0f;
+        f16x8 *dst = &img[buf][0][0][0][0];
 #pragma unroll
-        for (int k = 0; k < FPT; ++k) {
-            xs[k] *= gamma;
-            nrm = fmaf(xs[k], xs[k], nrm);
-        }
-        nrm += __shfl_xor(nrm, 1);
-        _Float16 q[4];
-        norm_digits(0.5f * nrm, q);
-        const int tile = sp >> 5;
-        const int prow = sp & 31;
-#pragma unroll
-        for (int j = 0; j < HU; ++j) {
-            const int u = part * HU + j; // unit of the point
-            f16x8 hi, lo;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                _Float16 zh, zl;
-                split_half(xs[8 * j + e], zh, zl);
-                hi[e] = zh;
-                lo[e] = zl;
-            }
-            if (j == HU - 1 && part == 1) { // last unit: constants beside xh, norm digits beside xl
-                hi[4] = (_Float16)kC1; hi[5] = (_Float16)kC2; hi[6] = (_Float16)kC3; hi[7] = (_Float16)kC4;
-                lo[4] = q[0]; lo[5] = q[1]; lo[6] = q[2]; lo[7] = q[3];
-            }
-            img[buf][tile][0][u >> 1][(u & 1) * 32 + prow] = hi;
-            img[buf][tile][1][u >> 1][(u & 1) * 32 + prow] = lo;
-        }
-        if (part == 0) vv[buf][sp] = vs;
+        for (int k = 0; k < UPT; ++k) dst[k * kThreads + tid] = xs[k];
+        if (tid < kStage) vv[buf][tid] = vs;
     };
 
     // accumulators of the tile in flight (cur) and of the tile being finished (prev)
@@ -341,7 +389,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         }
 
     // ---- reduce over the 32 stream lanes of each half-wave and store ----------------------
-    float *out = a.out + (int64_t)blockIdx.y * a.chunk_stride;
+    float *out = a.out + chunk * a.chunk_stride;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -358,35 +406,55 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
 }
 
 template <int NU>
-hipError_t launch_nu(const SweepArgs &a, hipStream_t stream)
+hipError_t launch_nu(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
+    constexpr int HU = NU / 2;
+    constexpr size_t bytes_per_point = 2 * HU * 2 * 16; // two planes, HU MFMAs, two half-waves, 16 B units / 32 rows * 32
     const int64_t per_block = (int64_t)kWaves * 64;
     const int64_t blocks = (a.nF + per_block - 1) / per_block;
-    dim3 grid((unsigned)blocks, (unsigned)a.n_chunks);
+    // slab = whole chunks whose packed image fits the workspace
+    int64_t slab_chunks = (int64_t)(pack_bytes / bytes_per_point) / a.chunk_len;
+    if (slab_chunks < 1) return hipErrorInvalidValue;
     const bool a16 = (a.d % 4 == 0) && (a.lds % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.S) & 15) == 0);
     const bool a8 = (a.d % 2 == 0) && (a.lds % 2 == 0) && ((reinterpret_cast<uintptr_t>(a.S) & 7) == 0);
-    if (a16)
-        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, 4>), grid, dim3(kThreads), 0, stream, a);
-    else if (a8)
-        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, 2>), grid, dim3(kThreads), 0, stream, a);
-    else
-        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, 1>), grid, dim3(kThreads), 0, stream, a);
-    return hipGetLastError();
+    f16x8 *packed = static_cast<f16x8 *>(pack_buf);
+    for (int64_t c0 = 0; c0 < a.n_chunks; c0 += slab_chunks) {
+        const int64_t nc = (a.n_chunks - c0 < slab_chunks) ? a.n_chunks - c0 : slab_chunks;
+        const int64_t row0 = c0 * a.chunk_len, rows = nc * a.chunk_len;
+        const dim3 pgrid((unsigned)((rows + kThreads / 2 - 1) / (kThreads / 2)));
+        if (a16)
+            hipLaunchKernelGGL((pack_stream_kernel<NU, 4>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.d,
+                               a.sigma, row0, rows, packed);
+        else if (a8)
+            hipLaunchKernelGGL((pack_stream_kernel<NU, 2>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.d,
+                               a.sigma, row0, rows, packed);
+        else
+            hipLaunchKernelGGL((pack_stream_kernel<NU, 1>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.d,
+                               a.sigma, row0, rows, packed);
+        const dim3 grid((unsigned)blocks, (unsigned)nc);
+        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU>), grid, dim3(kThreads), 0, stream, a, packed, c0);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 } // namespace
 
 int f16_max_d() { return 44; } // 6 units of 8 features; larger images exceed 64 KB of static LDS
 
-hipError_t launch_sweep_f16(const SweepArgs &a, hipStream_t stream)
+// bytes of packed image per stream point for this d
+size_t f16_pack_bytes_per_point(int d) { return d <= 12 ? 64 : (d <= 28 ? 128 : 192); }
+
+hipError_t launch_sweep_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
     if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t != 1 || a.d > f16_max_d()) return hipErrorInvalidValue;
     if (a.chunk_len % kStage != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
     // units of 8 features; the last unit keeps 4 slots for the norm digits
-    if (a.d <= 12) return launch_nu<2>(a, stream);
-    if (a.d <= 28) return launch_nu<4>(a, stream);
-    return launch_nu<6>(a, stream);
+    if (a.d <= 12) return launch_nu<2>(a, pack_buf, pack_bytes, stream);
+    if (a.d <= 28) return launch_nu<4>(a, pack_buf, pack_bytes, stream);
+    return launch_nu<6>(a, pack_buf, pack_bytes, stream);
 }
 
 } // namespace knm
