@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak: 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_FP32_VALU_TFLOPS = 78.6   # fp32 vector peak without packed issue: 256 CU x 64 lanes x 2 flop x 2.4 GHz
 
 
 def cpu_baseline(w, X_rows, C, v, budget_entries: float):
@@ -69,8 +70,11 @@ def main() -> int:
     ap.add_argument("--M", type=int, default=None, help="override the number of centres")
     ap.add_argument("--cpu-rows", type=int, default=None, help="rows of the oracle's timing sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--cross", default="f32", choices=["f32", "f16x3"],
-                    help="arithmetic of the cross term: fp32 MFMA, or three split-fp16 MFMA products")
+    ap.add_argument("--cross", default="f16x3", choices=["f32", "f16x3"],
+                    help="arithmetic of the cross term (d <= 44, t = 1): three split-fp16 MFMA products (library "
+                         "default) or fp32 MFMA")
+    ap.add_argument("--no-fp32-leg", action="store_true",
+                    help="skip the extra (untimed-region) product in the fp32-MFMA cross-term mode")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of known "
                          "traffic that calibrates the HBM byte counters of a rocprofv3 --pmc run)")
@@ -126,30 +130,58 @@ def main() -> int:
     entries = float(w.n) * float(w.M)
     value = entries / (elapsed / args.steps) / 1e9
 
-    # two sweeps per step; the register-resident engine (d <= 64, t = 1) is one launch per sweep,
-    # the K-loop engine handles up to 16 columns per launch
+    # Which tile engine ran (same rule as the library): K-loop fp32-MFMA engine for d > 64 or t > 1
+    # (up to 16 columns per launch); otherwise the register-resident engine, with the cross term as
+    # three split-fp16 MFMA products (d <= 44, default) or as fp32 MFMA.  Two sweeps per step.
     k_loop = w.d > 64 or w.t > 1
-    kernel_name = "gauss_gemm_kernel" if k_loop else "gauss_sweep_kernel"
+    f16 = (not k_loop) and args.cross == "f16x3" and w.d <= 44
+    kernel_name = "gauss_gemm_kernel" if k_loop else ("gauss_sweep_f16_kernel" if f16 else "gauss_sweep_kernel")
     launches = 2 * ((w.t + 15) // 16) * args.steps
     avg_launch_ms = (sum(row_ms) + sum(col_ms)) / launches
-    # algorithmic: one evaluation of every entry, 2 d flop each (the 2 t flop of the reduction
-    # against the vectors and the exp are not counted)
+    # algorithmic contraction work: one evaluation of every entry, 2 d flop each
     flop_per_launch = entries * 2.0 * w.d
-    achieved = flop_per_launch / (avg_launch_ms * 1e-3) / 1e12
+    if f16:
+        # Bound by the vector ALU, not the matrix cores: per entry one v_exp_f32 (half rate: two issue
+        # slots) and one FMA (one slot) = 3 lane-slots = 6 flop-equivalents at 2 flop per slot, against
+        # the un-packed fp32 vector peak 256 CU x 64 lanes x 2 flop x 2.4 GHz = 78.6 TFLOP/s.
+        alu_per_launch = entries * 6.0
+        achieved = alu_per_launch / (avg_launch_ms * 1e-3) / 1e12
+        bound, peak, work = "alu", PEAK_FP32_VALU_TFLOPS, alu_per_launch
+    else:
+        achieved = flop_per_launch / (avg_launch_ms * 1e-3) / 1e12
+        bound, peak, work = "mfma", PEAK_FP32_MFMA_TFLOPS, flop_per_launch
     roofline = {
-        "bound": "mfma",
+        "bound": bound,
         "kernel": kernel_name,
         "achieved": achieved,
-        "peak": PEAK_FP32_MFMA_TFLOPS,
+        "peak": peak,
         "unit": "TFLOP/s",
-        "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-        "traffic": measured_traffic_bytes(w.name) if (args.n is None and args.M is None) else None,
+        "frac": achieved / peak,
+        "traffic": measured_traffic_bytes(w.name + ("" if f16 or k_loop else "_f32"))
+        if (args.n is None and args.M is None) else None,
         "avg_launch_ms": avg_launch_ms,
         "row_sweep_ms": sum(row_ms) / len(row_ms),
         "col_sweep_ms": sum(col_ms) / len(col_ms),
         "merge_ms": sum(merge_ms) / len(merge_ms),
-        "flop_per_launch": flop_per_launch,
+        "work_per_launch": work,
+        "contraction_flop_per_launch": flop_per_launch,
+        # the same launch priced as if its 2 d flop per entry had run on fp32 MFMA
+        "fp32_mfma_equiv_frac": flop_per_launch / (avg_launch_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
     }
+
+    fp32_mode = None
+    if f16 and not args.no_fp32_leg:
+        # the fp32-MFMA cross-term mode on the same inputs, outside the timed region
+        ctx.set_cross_term("f32")
+        knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
+        ctx.set_timing(True)
+        knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
+        tm = ctx.get_timing()
+        ctx.set_timing(False)
+        ctx.set_cross_term(args.cross)
+        l_ms = 0.5 * (tm["row_sweep_ms"] + tm["col_sweep_ms"])
+        fp32_mode = {"kernel": "gauss_sweep_kernel", "ms_per_product": tm["total_ms"], "avg_launch_ms": l_ms,
+                     "frac_of_fp32_mfma_peak": flop_per_launch / (l_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
 
     out = {
         "metric": "G kernel-entries/s in K_nm^T(K_nm v)",
@@ -168,12 +200,15 @@ def main() -> int:
                    "stands_in_for": w.stands_in_for},
         "s_per_product": ms_per_step / 1e3,
         "mfma_frac_two_sweeps": 2.0 * entries * 2.0 * w.d / (elapsed / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+        "cross_term": "f16x3" if f16 else "f32",
         "roofline": roofline,
     }
+    if fp32_mode is not None:
+        out["fp32_mfma_mode"] = fp32_mode
 
     if not args.no_cpu:
         # bounded sample: about 10-30 s of oracle work on the host cores
-        rows = args.cpu_rows or max(64, int(4.0e9 * (8.0 / max(w.d, 8)) ** 0.5 / w.M))
+        rows = args.cpu_rows or max(64, int(1.2e10 * (8.0 / max(w.d, 8)) ** 0.5 / w.M))
         rows = min(rows, w.n)
         stride = max(1, w.n // rows)
         idx = torch.arange(0, rows, device="cuda") * stride

@@ -134,7 +134,7 @@ class Context:
             raise KnmError(st, load_library().knm_last_error(self._h).decode())
 
     def set_cross_term(self, mode):
-        """'f32' (fp32 MFMA, default) or 'f16x3' (split-fp16 products on the f16 matrix cores)."""
+        """'f16x3' (split-fp16 products on the f16 matrix cores, default) or 'f32' (fp32 MFMA)."""
         code = {"f32": 0, "f16x3": 1}[mode] if isinstance(mode, str) else int(mode)
         self.check(load_library().knm_set_cross_term(self._h, code))
 

@@ -106,10 +106,10 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         if (gemm) {
             e = launch_sweep_gemm(a, ctx->stream);
         } else if (f16) {
-            // packed image of the stream points: all of it, or slabs of at most 1 GiB
+            // packed image of the stream points: all of it, or slabs of at most 2 GiB
             const size_t per_point = f16_pack_bytes_per_point(d);
             size_t want = per_point * (size_t)(chunks * chunk_len);
-            const size_t cap = (size_t)1 << 30;
+            const size_t cap = (size_t)2 << 30;
             if (want > cap) want = (cap / (per_point * chunk_len) + 1) * per_point * chunk_len;
             int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
             if (st) return st;

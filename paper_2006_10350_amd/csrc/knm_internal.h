@@ -67,7 +67,7 @@ struct knm_ctx {
     size_t part_bytes = 0;
     float *pack_buf = nullptr; // packed stream image of the split-fp16 engine
     size_t pack_bytes = 0;
-    int cross_term = KNM_CROSS_F32;
+    int cross_term = KNM_CROSS_F16X3;
     // timing
     bool timing = false;
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};

@@ -25,7 +25,7 @@ def cross(request, knm):
     ctx = knm.default_context()
     ctx.set_cross_term(request.param)
     yield request.param
-    ctx.set_cross_term("f32")
+    ctx.set_cross_term("f16x3")
 
 
 def rel_l2(got, ref):
@@ -170,7 +170,7 @@ def test_split_half_range_limits(knm):
         assert W[7, 0] == pytest.approx(Wo[7, 0], rel=2e-2) and Wo[7, 0] >= 1.0  # sees its twin centre
         assert abs(W[11, 0]) < 1e-6
     finally:
-        ctx.set_cross_term("f32")
+        ctx.set_cross_term("f16x3")
 
 
 def test_invalid_arguments_are_rejected(knm):
