@@ -60,6 +60,43 @@ def measured_traffic_bytes(workload: str):
         return None
 
 
+def fit_benchmark(w, args) -> int:
+    """falkon_fit end to end (preconditioner, right-hand side, CG iterations) with phase timings."""
+    import torch
+
+    import paper_2006_10350_amd as knm
+    import synth
+
+    inp = synth.make_inputs(w, device="cuda", with_targets=True)
+    X, C, Y = inp["X"], inp["C"], inp["Y"]
+    ctx = knm.default_context()
+    ctx.set_cross_term(args.cross)
+    iters = args.iters or w.iters
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    alpha, resid = knm.falkon_fit(X, Y, C, w.sigma, w.lam, iters, args.jitter, return_resid=True, ctx=ctx)
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t0
+    ft = ctx.get_fit_timing()
+    print(json.dumps({
+        "metric": "s per CG iteration (falkon_fit)",
+        "value": ft["iterations_s"] / iters,
+        "unit": "s",
+        "higher_is_better": False,
+        "n_gpus": 1,
+        "config": {"workload": w.name, "n": w.n, "d": w.d, "M": w.M, "t": w.t, "sigma": w.sigma, "lambda": w.lam,
+                   "iters": iters, "jitter": args.jitter},
+        "cross_term": args.cross,
+        "fit_total_s": total,
+        "precond_s": ft["precond_s"],
+        "rhs_s": ft["rhs_s"],
+        "iterations_s": ft["iterations_s"],
+        "residual_first_last": [float(resid.reshape(iters + 1, -1)[0].max()), float(resid.reshape(iters + 1, -1)[-1].max())],
+        "alpha_finite": bool(torch.isfinite(alpha).all()),
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +110,11 @@ def main() -> int:
     ap.add_argument("--cross", default="f16x3", choices=["f32", "f16x3"],
                     help="arithmetic of the cross term (d <= 44, t = 1): three split-fp16 MFMA products (library "
                          "default) or fp32 MFMA")
+    ap.add_argument("--fit", action="store_true",
+                    help="instead of the product benchmark, run falkon_fit end to end on the workload and "
+                         "report seconds per conjugate-gradient iteration")
+    ap.add_argument("--iters", type=int, default=None, help="CG iterations for --fit (default: the workload's)")
+    ap.add_argument("--jitter", type=float, default=1e-8, help="diagonal jitter on K_MM for --fit")
     ap.add_argument("--no-fp32-leg", action="store_true",
                     help="skip the extra (untimed-region) product in the fp32-MFMA cross-term mode")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -94,6 +136,8 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     w = synth.workload(args.workload, n=args.n, M=args.M)
+    if args.fit:
+        return fit_benchmark(w, args)
     inp = synth.make_inputs(w, device="cuda", with_targets=False)
     X, C = inp["X"], inp["C"]
     v = synth.probe_vector(w.M, w.t, "normal", device="cuda")

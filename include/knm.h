@@ -111,6 +111,11 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
                float sigma, double lambda, double jitter, int iters,
                float *alpha, double *resid_norms_or_null);
 
+/* Wall-clock seconds of the phases of the most recent successful falkon_fit on this context,
+ * written to the HOST array seconds[4]: [0] preconditioner, [1] right-hand side
+ * (K_nm^T Y and two solves), [2] all conjugate-gradient iterations, [3] final solves. */
+int knm_get_fit_timing(const knm_ctx *ctx, double *seconds);
+
 /* out[ntest x t] = k(Xtest, C) alpha  (Eq. 4). */
 int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64_t ldx,
                    const float *C, int64_t M, int64_t ldc, float sigma,

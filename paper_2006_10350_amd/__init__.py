@@ -48,6 +48,7 @@ SIGNATURES = {
     "falkon_linop": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _int, _vp]),
     "falkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _int, _vp, _i64, _i64, _f32, _f64, _f64, _int,
                           _vp, _vp]),
+    "knm_get_fit_timing": (_int, [_vp, ctypes.POINTER(_f64)]),
     "falkon_predict": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
     "knm_set_cross_term": (_int, [_vp, _int]),
     "knm_set_timing": (_int, [_vp, _int]),
@@ -137,6 +138,11 @@ class Context:
         """'f16x3' (split-fp16 products on the f16 matrix cores, default) or 'f32' (fp32 MFMA)."""
         code = {"f32": 0, "f16x3": 1}[mode] if isinstance(mode, str) else int(mode)
         self.check(load_library().knm_set_cross_term(self._h, code))
+
+    def get_fit_timing(self):
+        sec = (_f64 * 4)()
+        self.check(load_library().knm_get_fit_timing(self._h, sec))
+        return {"precond_s": sec[0], "rhs_s": sec[1], "iterations_s": sec[2], "tail_s": sec[3]}
 
     # ---- timing -----------------------------------------------------------------------
     def set_timing(self, enabled: bool):

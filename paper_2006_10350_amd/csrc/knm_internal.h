@@ -72,6 +72,7 @@ struct knm_ctx {
     bool timing = false;
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     bool ev_used[5] = {false, false, false, false, false};
+    double fit_seconds[4] = {0.0, 0.0, 0.0, 0.0}; // last falkon_fit: preconditioner, rhs, iterations, tail
     std::string last_error;
     // solver handles (created lazily by knm_solver.hip)
     void *blas = nullptr;

@@ -8,6 +8,7 @@
 #include <rocblas/rocblas.h>
 #include <rocsolver/rocsolver.h>
 
+#include <chrono>
 #include <cmath>
 #include <new>
 #include <vector>
@@ -20,6 +21,10 @@ struct knm_precond {
     double lambda = 0.0, jitter = 0.0;
     double *T = nullptr; // column-major M x M, upper triangle valid, strict lower zero
     double *A = nullptr;
+    // inverses of the kSolveBlock x kSolveBlock diagonal blocks of T and A (column-major blocks,
+    // the last one padded with the identity), used by the blocked triangular solves
+    double *Tdinv = nullptr;
+    double *Adinv = nullptr;
 };
 
 namespace {
@@ -92,6 +97,100 @@ __global__ void f64_rows_to_cols(const double *__restrict__ src, int64_t rows, i
     else dst[r + (int64_t)c * rows] = src[i];
 }
 
+// ---- blocked triangular solves -----------------------------------------------------------------
+// R (upper, column-major, leading dimension M) is cut into block columns of kSolveBlock.  A
+// solve walks the diagonal blocks in dependency order; each step is a small dense product
+// with the pre-inverted diagonal block followed by a bandwidth-bound panel update of the
+// remaining right-hand side, which streams the panel of R once with coalesced loads.  The
+// off-diagonal panels are ~all of the 8 M^2 / 2 bytes, so a solve runs at HBM speed instead
+// of at the latency of M dependent steps.
+constexpr int kSolveBlock = 256;
+
+// Inverse of every diagonal block: thread c of block k back-substitutes R_kk y = e_c.
+__global__ __launch_bounds__(kSolveBlock) void invert_diag_blocks_kernel(const double *__restrict__ R, int64_t M,
+                                                                        double *__restrict__ Dinv)
+{
+    const int64_t k0 = (int64_t)blockIdx.x * kSolveBlock;
+    const int nb = (int)((M - k0 < kSolveBlock) ? M - k0 : kSolveBlock);
+    const int c = threadIdx.x;
+    double *y = Dinv + (int64_t)blockIdx.x * kSolveBlock * kSolveBlock + (int64_t)c * kSolveBlock; // column c
+    for (int i = 0; i < kSolveBlock; ++i) y[i] = (i == c && c >= nb) ? 1.0 : 0.0; // identity padding
+    if (c >= nb) return;
+    const double *U = R + k0 + k0 * M;
+    y[c] = 1.0 / U[c + (int64_t)c * M];
+    for (int i = c - 1; i >= 0; --i) {
+        double s = 0.0;
+        for (int j = i + 1; j <= c; ++j) s += U[i + (int64_t)j * M] * y[j];
+        y[i] = -s / U[i + (int64_t)i * M];
+    }
+}
+
+// x_k = op(Dinv_k) b_k in place (one workgroup; op = transpose for the transposed solve)
+__global__ __launch_bounds__(kSolveBlock) void diag_apply_kernel(const double *__restrict__ Dinv, int trans,
+                                                                double *__restrict__ b, int nb)
+{
+    __shared__ double bs[kSolveBlock];
+    const int i = threadIdx.x;
+    bs[i] = (i < nb) ? b[i] : 0.0;
+    __syncthreads();
+    double s = 0.0;
+    if (!trans) {
+        for (int j = 0; j < kSolveBlock; ++j) s += Dinv[i + j * kSolveBlock] * bs[j];
+    } else {
+        const double *col = Dinv + (int64_t)i * kSolveBlock; // row i of the transpose
+        for (int j = 0; j < kSolveBlock; ++j) s += col[j] * bs[j];
+    }
+    if (i < nb) b[i] = s;
+}
+
+// b[0:k0] -= R[0:k0, k0:k0+nb] x   (x = b[k0:k0+nb] already solved): one thread per row
+__global__ __launch_bounds__(256) void panel_update_n_kernel(const double *__restrict__ R, int64_t M, int64_t k0,
+                                                            int nb, double *__restrict__ b)
+{
+    __shared__ double xs[kSolveBlock];
+    for (int j = threadIdx.x; j < kSolveBlock; j += blockDim.x) xs[j] = (j < nb) ? b[k0 + j] : 0.0;
+    __syncthreads();
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= k0) return;
+    const double *p = R + i + k0 * M;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int j = 0;
+    for (; j + 4 <= nb; j += 4) {
+        s0 += p[(int64_t)(j + 0) * M] * xs[j + 0];
+        s1 += p[(int64_t)(j + 1) * M] * xs[j + 1];
+        s2 += p[(int64_t)(j + 2) * M] * xs[j + 2];
+        s3 += p[(int64_t)(j + 3) * M] * xs[j + 3];
+    }
+    for (; j < nb; ++j) s0 += p[(int64_t)j * M] * xs[j];
+    b[i] -= (s0 + s1) + (s2 + s3);
+}
+
+// b[j] -= sum_i R[k0 + i, j] x[i] for j in [j0, M)   (x = b[k0:k0+nb]): one wavefront per column
+__global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__restrict__ R, int64_t M, int64_t k0,
+                                                            int nb, int64_t j0, double *__restrict__ b)
+{
+    __shared__ double xs[kSolveBlock];
+    for (int j = threadIdx.x; j < kSolveBlock; j += blockDim.x) xs[j] = (j < nb) ? b[k0 + j] : 0.0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);
+    constexpr int kColsPerWave = 4;
+    for (int c = 0; c < kColsPerWave; ++c) {
+        const int64_t j = j0 + wave * kColsPerWave + c;
+        if (j >= M) return;
+        const double *p = R + k0 + j * M;
+        double s = 0.0;
+        for (int i = lane; i < nb; i += 64) s += p[i] * xs[i];
+        s += __shfl_xor(s, 32);
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 8);
+        s += __shfl_xor(s, 4);
+        s += __shfl_xor(s, 2);
+        s += __shfl_xor(s, 1);
+        if (lane == 0) b[j] -= s;
+    }
+}
+
 inline dim3 grid1(int64_t n, int threads = 256) { return dim3((unsigned)((n + threads - 1) / threads)); }
 
 int blas_handle(knm_ctx *ctx, rocblas_handle *h)
@@ -124,19 +223,41 @@ struct DevBuf {
     template <class T> T *as() { return static_cast<T *>(p); }
 };
 
-// B <- op(R)^-1 B for column-major B (M x t)
-int tri_solve(knm_ctx *ctx, rocblas_handle h, const double *R, int64_t M, bool trans, double *B, int t)
+// B <- op(R)^-1 B for column-major B (M x t); Dinv = inverted diagonal blocks of R
+int tri_solve(knm_ctx *ctx, rocblas_handle h, const double *R, const double *Dinv, int64_t M, bool trans, double *B,
+              int t)
 {
-    rocblas_status s;
-    const rocblas_operation op = trans ? rocblas_operation_transpose : rocblas_operation_none;
-    if (t == 1) {
-        s = rocblas_dtrsv(h, rocblas_fill_upper, op, rocblas_diagonal_non_unit, (rocblas_int)M, R, (rocblas_int)M, B, 1);
-    } else {
-        const double one = 1.0;
-        s = rocblas_dtrsm(h, rocblas_side_left, rocblas_fill_upper, op, rocblas_diagonal_non_unit, (rocblas_int)M, t,
-                          &one, R, (rocblas_int)M, B, (rocblas_int)M);
+    (void)h;
+    const int64_t nblk = (M + kSolveBlock - 1) / kSolveBlock;
+    for (int c = 0; c < t; ++c) {
+        double *b = B + (int64_t)c * M;
+        if (!trans) { // backward: last block first
+            for (int64_t k = nblk - 1; k >= 0; --k) {
+                const int64_t k0 = k * kSolveBlock;
+                const int nb = (int)((M - k0 < kSolveBlock) ? M - k0 : kSolveBlock);
+                hipLaunchKernelGGL(diag_apply_kernel, dim3(1), dim3(kSolveBlock), 0, ctx->stream,
+                                   Dinv + k * kSolveBlock * kSolveBlock, 0, b + k0, nb);
+                if (k0 > 0)
+                    hipLaunchKernelGGL(panel_update_n_kernel, grid1(k0), dim3(256), 0, ctx->stream, R, M, k0, nb, b);
+            }
+        } else { // forward with R^T (lower): first block first
+            for (int64_t k = 0; k < nblk; ++k) {
+                const int64_t k0 = k * kSolveBlock;
+                const int nb = (int)((M - k0 < kSolveBlock) ? M - k0 : kSolveBlock);
+                hipLaunchKernelGGL(diag_apply_kernel, dim3(1), dim3(kSolveBlock), 0, ctx->stream,
+                                   Dinv + k * kSolveBlock * kSolveBlock, 1, b + k0, nb);
+                const int64_t j0 = k0 + nb;
+                if (j0 < M) {
+                    const int64_t cols = M - j0;
+                    const int64_t blocks = (cols + 15) / 16; // 4 wavefronts x 4 columns per workgroup
+                    hipLaunchKernelGGL(panel_update_t_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, R, M,
+                                       k0, nb, j0, b);
+                }
+            }
+        }
     }
-    if (s != rocblas_status_success) return fail(ctx, KNM_HIP_ERROR, "rocblas triangular solve");
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "blocked triangular solve", e);
     return KNM_OK;
 }
 
@@ -161,11 +282,11 @@ int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &
     double *v = wk.v.as<double>();
     hipError_t e = hipMemcpyAsync(v, beta, bytes, hipMemcpyDeviceToDevice, ctx->stream);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
-    int st = tri_solve(ctx, h, p->A, M, false, v, t); // v = A^-1 beta
+    int st = tri_solve(ctx, h, p->A, p->Adinv, M, false, v, t); // v = A^-1 beta
     if (st) return st;
     e = hipMemcpyAsync(out, v, bytes, hipMemcpyDeviceToDevice, ctx->stream);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
-    st = tri_solve(ctx, h, p->T, M, false, out, t); // z = T^-1 v
+    st = tri_solve(ctx, h, p->T, p->Tdinv, M, false, out, t); // z = T^-1 v
     if (st) return st;
     hipLaunchKernelGGL(f64_cols_to_f32_rows, grid1(M * t), dim3(256), 0, ctx->stream, out, M, t, wk.z32.as<float>());
     // c = K_nm^T (K_nm z), the O(n M) step
@@ -176,12 +297,12 @@ int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &
     st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, ctx->w_buf, nullptr, t, wk.u32.as<float>());
     if (st) return st;
     hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(M * t), dim3(256), 0, ctx->stream, wk.u32.as<float>(), M, t, out);
-    st = tri_solve(ctx, h, p->T, M, true, out, t); // T^-T c
+    st = tri_solve(ctx, h, p->T, p->Tdinv, M, true, out, t); // T^-T c
     if (st) return st;
     const double ln = lambda * (double)n;
     if (rocblas_daxpy(h, (rocblas_int)(M * t), &ln, v, 1, out, 1) != rocblas_status_success)
         return fail(ctx, KNM_HIP_ERROR, "rocblas_daxpy");
-    return tri_solve(ctx, h, p->A, M, true, out, t); // A^-T (...)
+    return tri_solve(ctx, h, p->A, p->Adinv, M, true, out, t); // A^-T (...)
 }
 
 } // namespace
@@ -202,6 +323,8 @@ int precond_free(knm_precond *p)
     (void)hipSetDevice(p->device);
     if (p->T) (void)hipFree(p->T);
     if (p->A) (void)hipFree(p->A);
+    if (p->Tdinv) (void)hipFree(p->Tdinv);
+    if (p->Adinv) (void)hipFree(p->Adinv);
     delete p;
     return KNM_OK;
 }
@@ -230,6 +353,10 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
     const size_t bytes = sizeof(double) * (size_t)M * (size_t)M;
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&p->T), bytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->A), bytes);
+    const int64_t nblk = (M + kSolveBlock - 1) / kSolveBlock;
+    const size_t dbytes = sizeof(double) * (size_t)nblk * kSolveBlock * kSolveBlock;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Tdinv), dbytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Adinv), dbytes);
     DevBuf info;
     if (e != hipSuccess || info.alloc(ctx, sizeof(rocblas_int))) {
         (void)hipGetLastError();
@@ -299,7 +426,11 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
         return bail(KNM_NOT_PD, "T T^T / M + lambda I is not positive definite");
     }
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, 0.0, 1);
-    if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "tri_fix_kernel launch");
+    hipLaunchKernelGGL(invert_diag_blocks_kernel, dim3((unsigned)nblk), dim3(kSolveBlock), 0, ctx->stream, p->T, M,
+                       p->Tdinv);
+    hipLaunchKernelGGL(invert_diag_blocks_kernel, dim3((unsigned)nblk), dim3(kSolveBlock), 0, ctx->stream, p->A, M,
+                       p->Adinv);
+    if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "preconditioner kernel launch");
     *out = p;
     return KNM_OK;
 }
@@ -364,9 +495,13 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
     int st = blas_handle(ctx, &h);
     if (st) return st;
 
+    using clk = std::chrono::steady_clock;
+    auto secs = [](clk::time_point a, clk::time_point b) { return std::chrono::duration<double>(b - a).count(); };
+    const clk::time_point t_start = clk::now();
     knm_precond *p = nullptr;
-    st = precond_build(ctx, C, M, d, ldc, sigma, lambda, jitter, &p, nullptr);
+    st = precond_build(ctx, C, M, d, ldc, sigma, lambda, jitter, &p, nullptr); // synchronises
     if (st) return st;
+    const clk::time_point t_precond = clk::now();
     struct Guard {
         knm_precond *p;
         ~Guard() { precond_free(p); }
@@ -388,8 +523,8 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
     st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, Y, nullptr, t, r32.as<float>());
     if (st) return st;
     hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(len), dim3(256), 0, ctx->stream, r32.as<float>(), M, t, dr);
-    st = tri_solve(ctx, h, p->T, M, true, dr, t);
-    if (!st) st = tri_solve(ctx, h, p->A, M, true, dr, t);
+    st = tri_solve(ctx, h, p->T, p->Tdinv, M, true, dr, t);
+    if (!st) st = tri_solve(ctx, h, p->A, p->Adinv, M, true, dr, t);
     if (st) return st;
     hipError_t e = hipMemsetAsync(db, 0, sizeof(double) * len, ctx->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(dp, dr, sizeof(double) * len, hipMemcpyDeviceToDevice, ctx->stream);
@@ -402,6 +537,7 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
             return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
         if (resid_norms_or_null) resid_norms_or_null[c] = std::sqrt(rho[c]);
     }
+    const clk::time_point t_rhs = clk::now(); // the host-pointer dot products above synchronise
     for (int it = 0; it < iters; ++it) {
         st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, dp, t, dq);
         if (st) return st;
@@ -425,12 +561,24 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
         }
     }
     // alpha = T^-1 A^-1 beta
-    st = tri_solve(ctx, h, p->A, M, false, db, t);
-    if (!st) st = tri_solve(ctx, h, p->T, M, false, db, t);
+    st = tri_solve(ctx, h, p->A, p->Adinv, M, false, db, t);
+    if (!st) st = tri_solve(ctx, h, p->T, p->Tdinv, M, false, db, t);
     if (st) return st;
     hipLaunchKernelGGL(f64_cols_to_f32_rows, grid1(len), dim3(256), 0, ctx->stream, db, M, t, alpha);
+    const clk::time_point t_iters = clk::now(); // each iteration ends with synchronising dot products
     e = hipStreamSynchronize(ctx->stream); // temporaries are freed on return
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "falkon_fit", e);
+    ctx->fit_seconds[0] = secs(t_start, t_precond);
+    ctx->fit_seconds[1] = secs(t_precond, t_rhs);
+    ctx->fit_seconds[2] = secs(t_rhs, t_iters);
+    ctx->fit_seconds[3] = secs(t_iters, clk::now());
+    return KNM_OK;
+}
+
+int knm_get_fit_timing(const knm_ctx *ctx, double *seconds)
+{
+    if (!ctx || !seconds) return KNM_INVALID_ARG;
+    for (int i = 0; i < 4; ++i) seconds[i] = ctx->fit_seconds[i];
     return KNM_OK;
 }
 
