@@ -358,7 +358,7 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Tdinv), dbytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Adinv), dbytes);
     DevBuf info;
-    if (e != hipSuccess || info.alloc(ctx, sizeof(rocblas_int))) {
+    if (e != hipSuccess || info.alloc(ctx, sizeof(int64_t))) {
         (void)hipGetLastError();
         precond_free(p);
         return fail(ctx, KNM_ALLOC, "hipMalloc(preconditioner)", e);
@@ -390,11 +390,13 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
         return err;
     };
 
-    rocblas_int host_info = 0;
-    if (rocsolver_dpotrf(h, rocblas_fill_upper, (rocblas_int)M, p->T, (rocblas_int)M, info.as<rocblas_int>()) !=
+    // The 64-bit interfaces are required: M^2 exceeds 2^31 elements for M > 46340, which the
+    // 32-bit interfaces' internal element offsets cannot address.
+    int64_t host_info = 0;
+    if (rocsolver_dpotrf_64(h, rocblas_fill_upper, M, p->T, M, info.as<int64_t>()) !=
         rocblas_status_success)
         return bail(KNM_HIP_ERROR, "rocsolver_dpotrf(T)");
-    e = hipMemcpyAsync(&host_info, info.p, sizeof(rocblas_int), hipMemcpyDeviceToHost, ctx->stream);
+    e = hipMemcpyAsync(&host_info, info.p, sizeof(int64_t), hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return bail(KNM_HIP_ERROR, "dpotrf(T) status copy");
     int64_t pivot = host_info;
@@ -409,14 +411,14 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
 
     // A <- T T^T / M (upper triangle), then + lambda I, then factorise
     const double alpha = 1.0 / (double)M, beta = 0.0;
-    if (rocblas_dsyrk(h, rocblas_fill_upper, rocblas_operation_none, (rocblas_int)M, (rocblas_int)M, &alpha, p->T,
-                      (rocblas_int)M, &beta, p->A, (rocblas_int)M) != rocblas_status_success)
+    if (rocblas_dsyrk_64(h, rocblas_fill_upper, rocblas_operation_none, M, M, &alpha, p->T, M, &beta, p->A, M) !=
+        rocblas_status_success)
         return bail(KNM_HIP_ERROR, "rocblas_dsyrk");
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, lambda, 0);
-    if (rocsolver_dpotrf(h, rocblas_fill_upper, (rocblas_int)M, p->A, (rocblas_int)M, info.as<rocblas_int>()) !=
+    if (rocsolver_dpotrf_64(h, rocblas_fill_upper, M, p->A, M, info.as<int64_t>()) !=
         rocblas_status_success)
         return bail(KNM_HIP_ERROR, "rocsolver_dpotrf(A)");
-    e = hipMemcpyAsync(&host_info, info.p, sizeof(rocblas_int), hipMemcpyDeviceToHost, ctx->stream);
+    e = hipMemcpyAsync(&host_info, info.p, sizeof(int64_t), hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return bail(KNM_HIP_ERROR, "dpotrf(A) status copy");
     pivot = host_info;
