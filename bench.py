@@ -22,6 +22,7 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak: 256 CU x 256 flop/clk x 2.4 GHz
 PEAK_FP32_VALU_TFLOPS = 78.6   # fp32 vector peak without packed issue: 256 CU x 64 lanes x 2 flop x 2.4 GHz
+PEAK_FP16_MFMA_TFLOPS = 2500.0  # MI355X dense fp16 matrix peak
 
 
 def cpu_baseline(w, X_rows, C, v, budget_entries: float):
@@ -179,7 +180,9 @@ def main() -> int:
     # three split-fp16 MFMA products (d <= 44, default) or as fp32 MFMA.  Two sweeps per step.
     k_loop = w.d > 64 or w.t > 1
     f16 = (not k_loop) and args.cross == "f16x3" and w.d <= 44
-    kernel_name = "gauss_gemm_kernel" if k_loop else ("gauss_sweep_f16_kernel" if f16 else "gauss_sweep_kernel")
+    k_loop_f16 = k_loop and args.cross == "f16x3"
+    kernel_name = (("gauss_gemm_f16_kernel" if k_loop_f16 else "gauss_gemm_kernel") if k_loop
+                   else ("gauss_sweep_f16_kernel" if f16 else "gauss_sweep_kernel"))
     launches = 2 * ((w.t + 15) // 16) * args.steps
     avg_launch_ms = (sum(row_ms) + sum(col_ms)) / launches
     # algorithmic contraction work: one evaluation of every entry, 2 d flop each
@@ -191,6 +194,12 @@ def main() -> int:
         alu_per_launch = entries * 6.0
         achieved = alu_per_launch / (avg_launch_ms * 1e-3) / 1e12
         bound, peak, work = "alu", PEAK_FP32_VALU_TFLOPS, alu_per_launch
+    elif k_loop_f16:
+        # Dense contraction on the f16 matrix cores: the split-fp16 cross term is three f16 products per
+        # feature pair (fh.xh + fh.xl + fl.xh), 6 d flop per entry, against the dense fp16 MFMA peak.
+        f16_flop = 3.0 * flop_per_launch
+        achieved = f16_flop / (avg_launch_ms * 1e-3) / 1e12
+        bound, peak, work = "mfma", PEAK_FP16_MFMA_TFLOPS, f16_flop
     else:
         achieved = flop_per_launch / (avg_launch_ms * 1e-3) / 1e12
         bound, peak, work = "mfma", PEAK_FP32_MFMA_TFLOPS, flop_per_launch
@@ -201,7 +210,7 @@ def main() -> int:
         "peak": peak,
         "unit": "TFLOP/s",
         "frac": achieved / peak,
-        "traffic": measured_traffic_bytes(w.name + ("" if f16 or k_loop else "_f32"))
+        "traffic": measured_traffic_bytes(w.name + ("" if f16 or k_loop_f16 else "_f32"))
         if (args.n is None and args.M is None) else None,
         "avg_launch_ms": avg_launch_ms,
         "row_sweep_ms": sum(row_ms) / len(row_ms),
@@ -214,7 +223,7 @@ def main() -> int:
     }
 
     fp32_mode = None
-    if f16 and not args.no_fp32_leg:
+    if (f16 or k_loop_f16) and not args.no_fp32_leg:
         # the fp32-MFMA cross-term mode on the same inputs, outside the timed region
         ctx.set_cross_term("f32")
         knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
@@ -224,7 +233,7 @@ def main() -> int:
         ctx.set_timing(False)
         ctx.set_cross_term(args.cross)
         l_ms = 0.5 * (tm["row_sweep_ms"] + tm["col_sweep_ms"])
-        fp32_mode = {"kernel": "gauss_sweep_kernel", "ms_per_product": tm["total_ms"], "avg_launch_ms": l_ms,
+        fp32_mode = {"kernel": "gauss_gemm_kernel" if k_loop else "gauss_sweep_kernel", "ms_per_product": tm["total_ms"], "avg_launch_ms": l_ms,
                      "frac_of_fp32_mfma_peak": flop_per_launch / (l_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
 
     out = {
@@ -244,7 +253,7 @@ def main() -> int:
                    "stands_in_for": w.stands_in_for},
         "s_per_product": ms_per_step / 1e3,
         "mfma_frac_two_sweeps": 2.0 * entries * 2.0 * w.d / (elapsed / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
-        "cross_term": "f16x3" if f16 else "f32",
+        "cross_term": "f16x3" if (f16 or k_loop_f16) else "f32",
         "roofline": roofline,
     }
     if fp32_mode is not None:

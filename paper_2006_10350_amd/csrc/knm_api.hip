@@ -103,7 +103,20 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.sigma = sigma;
         const bool f16 = !gemm && ctx->cross_term == KNM_CROSS_F16X3 && d <= f16_max_d();
         hipError_t e;
-        if (gemm) {
+        if (gemm && ctx->cross_term == KNM_CROSS_F16X3) {
+            // packed images of both operands: whole if they fit 8 GiB, else the smaller one
+            // whole and the other in slabs
+            const size_t per_point = gemm_f16_pack_bytes_per_point(d);
+            const int64_t nFp = (nF + gemm_fixed_per_block() - 1) / gemm_fixed_per_block() * gemm_fixed_per_block();
+            size_t want = per_point * (size_t)(nFp + chunks * chunk_len);
+            const size_t cap = (size_t)8 << 30;
+            const size_t least = gemm_f16_min_pack_bytes(nF, chunks * chunk_len, chunk_len, d);
+            if (want > cap) want = cap;
+            if (want < least) want = least;
+            int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
+            if (st) return st;
+            e = launch_sweep_gemm_f16(a, ctx->pack_buf, ctx->pack_bytes, ctx->stream);
+        } else if (gemm) {
             e = launch_sweep_gemm(a, ctx->stream);
         } else if (f16) {
             // packed image of the stream points: all of it, or slabs of at most 2 GiB

@@ -1,0 +1,414 @@
+// Gaussian-kernel tile engine, K-loop variant with the cross term on the f16 matrix cores:
+//     out[f, c] = sum_s k(F_f, S_s) vec[s, c]        (any d, up to 16 columns per launch)
+//
+// Same computation as knm_gemm.hip (Section 3.1, "Blockwise K_nm-vector product"; Gaussian
+// kernel of Section 2) with the arithmetic of knm_tile_f16.hip: every scaled feature
+// z = x sqrt(log2 e) / sigma is split into two halves z = zh + zl (22 significant bits) and
+// the cross term is evaluated as three f16 MFMA products with fp32 accumulation,
+//     <zf, zx>  ~=  fh.xh + fh.xl + fl.xh                      (drops fl.xl ~ 2^-22),
+// so that the accumulator holds  log2 k(f, x) = <zf, zx> - |zf|^2 / 2 - |zx|^2 / 2  after
+// one more MFMA whose K-slots carry the two norm terms as 4-digit fixed-point numbers
+//     n = q1 2^13 + q2 2^2 + q3 2^-9 + q4 2^-20,   q_i integers <= 2048 (exact in fp16),
+// against the constants 2^13, 2^2, 2^-9, 2^-20 on the other operand.
+//
+// Packed images.  Both operands are converted once per sweep (`pack_points_kernel`) into
+// images laid out exactly as the LDS stage, so staging is a 16-byte copy and the
+// conversion cost (scale, split, norms) is not repeated by every workgroup that visits a
+// point.  Per block of 32 points the image holds n_kc + 1 chunks of 2 KB:
+//     chunk kc < n_kc : [plane hi | lo][lane = 32 h + point] units of 8 halves = features
+//                       16 kc + 8 h .. + 7 of the point               (MFMA operand layout)
+//     chunk n_kc      : plane 0 = the point's slots when it is a FIXED point
+//                       (-q1..-q4 of its norm term, then the four constants), plane 1 = its
+//                       slots as a STREAM point (constants, then -q1..-q4); half-wave 1 zero.
+// The same image therefore serves either role, and X and C are each packed once per sweep.
+// Images are built slab by slab when they exceed the workspace.
+//
+// Tile shape and orientation as in knm_gemm.hip: workgroup = 256 fixed x 128 stream
+// points, each wavefront 64 fixed x 128 stream = 8 accumulators of 32x32 pinned to AGPRs;
+// the stream block is the A operand, so a lane's accumulator registers run over stream
+// points of one fixed point and the reduction against the vector columns is in-lane.
+
+#include <type_traits>
+
+#include "knm_internal.h"
+
+namespace knm {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __fp16 f16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int kFixed = 256;                    // fixed points per workgroup
+constexpr int kStream = 128;                   // stream points per tile
+constexpr int kBlocks = (kFixed + kStream) / 32; // 32-point blocks per stage: 8 fixed, 4 stream
+constexpr int kChunk = 16;                     // features per K-chunk = one MFMA K
+constexpr int kUnits = 128;                    // 16-byte units per block and chunk (2 planes x 64 lanes)
+constexpr int kLoads = kBlocks * kUnits / kThreads; // units copied per thread and stage (6)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kC1 = 8192.0f, kC2 = 4.0f, kC3 = 0.001953125f, kC4 = 9.5367431640625e-07f; // 2^13 2^2 2^-9 2^-20
+
+static_assert(kLoads * kThreads == kBlocks * kUnits, "staging must divide evenly");
+
+// hi with the packed round-toward-zero conversion (saturates at the largest finite half),
+// lo = nearest half of the exact remainder z - hi
+__device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 &lo)
+{
+    z0 = fminf(fmaxf(z0, -65000.0f), 65000.0f);
+    z1 = fminf(fmaxf(z1, -65000.0f), 65000.0f);
+    hi = __builtin_amdgcn_cvt_pkrtz(z0, z1);
+    f32x2 rem;
+    rem[0] = z0 - (float)hi[0];
+    rem[1] = z1 - (float)hi[1];
+    lo = __builtin_convertvector(rem, f16x2);
+}
+
+// -n as four fixed-point digits; n >= 0
+__device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
+{
+    n = fminf(n, 16777215.0f);
+    const float q1 = floorf(n * (1.0f / 8192.0f));
+    float r = fmaf(-q1, 8192.0f, n);
+    const float q2 = floorf(r * 0.25f);
+    r = fmaf(-q2, 4.0f, r);
+    const float q3 = floorf(r * 512.0f);
+    r = fmaf(-q3, kC3, r);
+    const float q4 = rintf(r * 1048576.0f);
+    q[0] = (_Float16)(-q1); q[1] = (_Float16)(-q2); q[2] = (_Float16)(-q3); q[3] = (_Float16)(-q4);
+}
+
+// Image of points [row0, row0 + 32 gridDim.x) of P (points at or beyond nP become zero
+// points).  One workgroup per 32-point block; thread = (point, 8-feature unit), four
+// chunks (64 features) per pass over the row.
+template <int VW>
+__global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__restrict__ P, int64_t nP, int64_t ld,
+                                                               int d, float sigma, int64_t row0, int n_kc,
+                                                               f16x8 *__restrict__ img)
+{
+    const int tid = threadIdx.x;
+    const int u = tid & 7;
+    const int prow = tid >> 3;
+    const int h = u & 1;
+    const int64_t idx = row0 + (int64_t)blockIdx.x * 32 + prow;
+    const bool valid = idx < nP;
+    const float *row = P + (valid ? idx : 0) * ld;
+    const float gamma = sqrtf(kLog2e) / sigma;
+    f16x8 *blk = img + (int64_t)blockIdx.x * (n_kc + 1) * kUnits;
+
+    float nrm = 0.0f;
+    for (int g = 0; 4 * g < n_kc; ++g) {
+        const int kc = 4 * g + (u >> 1);
+        const int f0 = kChunk * kc + 8 * h;
+        float z[8];
+        if constexpr (VW == 4) {
+#pragma unroll
+            for (int k = 0; k < 8; k += 4) {
+                const bool in = valid && (f0 + k < d); // d % 4 == 0 in this mode
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(row + (in ? f0 + k : 0));
+                z[k] = in ? v[0] : 0.0f; z[k + 1] = in ? v[1] : 0.0f;
+                z[k + 2] = in ? v[2] : 0.0f; z[k + 3] = in ? v[3] : 0.0f;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool in = valid && (f0 + k < d);
+                const float v = row[in ? f0 + k : 0];
+                z[k] = in ? v : 0.0f;
+            }
+        }
+        f16x8 hi, lo;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float z0 = gamma * z[e], z1 = gamma * z[e + 1];
+            nrm = fmaf(z0, z0, nrm);
+            nrm = fmaf(z1, z1, nrm);
+            f16x2 ph, pl;
+            split_pair(z0, z1, ph, pl);
+            hi[e] = (_Float16)ph[0]; hi[e + 1] = (_Float16)ph[1];
+            lo[e] = (_Float16)pl[0]; lo[e + 1] = (_Float16)pl[1];
+        }
+        if (kc < n_kc) {
+            f16x8 *c = blk + (int64_t)kc * kUnits;
+            c[32 * h + prow] = hi;
+            c[64 + 32 * h + prow] = lo;
+        }
+    }
+    nrm += __shfl_xor(nrm, 1);
+    nrm += __shfl_xor(nrm, 2);
+    nrm += __shfl_xor(nrm, 4);
+    f16x8 *c = blk + (int64_t)n_kc * kUnits;
+    if (u == 0) {
+        _Float16 q[4];
+        norm_digits(0.5f * nrm, q);
+        f16x8 fx, st;
+        fx[0] = q[0]; fx[1] = q[1]; fx[2] = q[2]; fx[3] = q[3];
+        fx[4] = (_Float16)kC1; fx[5] = (_Float16)kC2; fx[6] = (_Float16)kC3; fx[7] = (_Float16)kC4;
+        st[0] = (_Float16)kC1; st[1] = (_Float16)kC2; st[2] = (_Float16)kC3; st[3] = (_Float16)kC4;
+        st[4] = q[0]; st[5] = q[1]; st[6] = q[2]; st[7] = q[3];
+        c[prow] = fx;
+        c[64 + prow] = st;
+    } else if (u == 1) {
+        f16x8 zero;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) zero[e] = (_Float16)0.0f;
+        c[32 + prow] = zero;
+        c[64 + 32 + prow] = zero;
+    }
+}
+
+__device__ __forceinline__ void mfma_zero(f32x16 &acc, const f16x8 &a, const f16x8 &b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_acc(f32x16 &acc, const f16x8 &a, const f16x8 &b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// Fimg: image of the fixed points [fixed_row0, fixed_row0 + 256 gridDim.x);
+// Simg: image of the stream chunks [chunk0, chunk0 + gridDim.y).
+// TP: number of vector columns, padded to a multiple of 4.
+template <int TP>
+__global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
+                                                                     const f16x8 *__restrict__ Simg,
+                                                                     int64_t fixed_row0, int64_t chunk0, int n_kc)
+{
+    __shared__ f16x8 img[2][kBlocks * kUnits]; // 2 x 24 KB
+    __shared__ __attribute__((aligned(16))) float vimg[kStream * TP];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int h = lane >> 5;
+    const int t = a.t;
+    const int n_st = n_kc + 1; // stages per tile: the feature chunks, then the norm slots
+
+    const int64_t fixed0 = fixed_row0 + (int64_t)blockIdx.x * kFixed;
+    const int64_t chunk = chunk0 + blockIdx.y;
+    const int64_t chunk_begin = chunk * a.chunk_len;
+    int64_t chunk_end = chunk_begin + a.chunk_len;
+    if (chunk_end > a.nS) chunk_end = a.nS;
+    const int n_tiles = (int)((chunk_end - chunk_begin + kStream - 1) / kStream);
+
+    // staging role of this thread: unit id = tid + 256 i  ->  block id / 128, unit id % 128;
+    // loads 0..3 cover the 8 fixed blocks, loads 4..5 the 4 stream blocks of a tile.  All
+    // per-load and per-stage offsets are uniform, the thread's own offset fits 32 bits.
+    const int64_t blk_units = (int64_t)n_st * kUnits;
+    const int toff = (tid >> 7) * (int)blk_units + (tid & (kUnits - 1));
+    const f16x8 *const fbase = Fimg + (int64_t)blockIdx.x * (kFixed / 32) * blk_units;
+    const f16x8 *const sbase = Simg + (int64_t)blockIdx.y * (a.chunk_len / 32) * blk_units;
+
+    float sum[2][TP];
+#pragma unroll
+    for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int c = 0; c < TP; ++c) sum[fb][c] = 0.0f;
+
+    f16x8 pre[kLoads];
+    auto fetch = [&](int tile, int st) {
+        const f16x8 *const fs = fbase + (int64_t)st * kUnits;
+        const f16x8 *const ss = sbase + (int64_t)tile * (kStream / 32) * blk_units + (int64_t)st * kUnits;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pre[i] = (fs + 2 * i * blk_units)[toff];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) pre[4 + i] = (ss + 2 * i * blk_units)[toff];
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) img[buf][tid + kThreads * i] = pre[i];
+    };
+
+    f32x16 acc[2][4];
+    // one feature chunk: three planes against the 8 accumulators
+    auto feature_stage = [&](const f16x8 *ib, auto first) {
+        f16x8 bh[2], bl[2];
+#pragma unroll
+        for (int fb = 0; fb < 2; ++fb) {
+            bh[fb] = ib[(wave * 2 + fb) * kUnits + lane];
+            bl[fb] = ib[(wave * 2 + fb) * kUnits + 64 + lane];
+        }
+#pragma unroll
+        for (int sb = 0; sb < 4; ++sb) {
+            const f16x8 ah = ib[(kFixed / 32 + sb) * kUnits + lane];
+            const f16x8 al = ib[(kFixed / 32 + sb) * kUnits + 64 + lane];
+            if constexpr (decltype(first)::value) {
+                mfma_zero(acc[0][sb], ah, bh[0]);
+                mfma_zero(acc[1][sb], ah, bh[1]);
+            } else {
+                mfma_acc(acc[0][sb], ah, bh[0]);
+                mfma_acc(acc[1][sb], ah, bh[1]);
+            }
+            mfma_acc(acc[0][sb], al, bh[0]);
+            mfma_acc(acc[1][sb], al, bh[1]);
+            mfma_acc(acc[0][sb], ah, bl[0]);
+            mfma_acc(acc[1][sb], ah, bl[1]);
+        }
+    };
+
+    int stage = 0; // running stage counter: buffer parity
+    if (n_tiles > 0) fetch(0, 0);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int64_t stream0 = chunk_begin + (int64_t)tile * kStream;
+
+        // first feature chunk: starts the accumulators
+        commit(stage & 1);
+        __syncthreads();
+        fetch(tile, 1); // n_st >= 2
+        feature_stage(img[stage & 1], std::true_type{});
+        ++stage;
+
+        for (int st = 1; st < n_kc; ++st, ++stage) {
+            commit(stage & 1);
+            __syncthreads();
+            fetch(tile, st + 1);
+            feature_stage(img[stage & 1], std::false_type{});
+        }
+
+        // last stage: the norm slots, stream role (plane 1) against fixed role (plane 0);
+        // the vectors of this tile are staged with it (every wavefront has passed this
+        // tile's first barrier, so it is done with the previous tile's vectors)
+        commit(stage & 1);
+        for (int k = tid; k < kStream * TP; k += kThreads) {
+            const int j = k / TP, c = k % TP;
+            const int64_t idx = stream0 + j;
+            const bool in = idx < chunk_end && c < t;
+            const int64_t vi = in ? idx : 0;
+            float v = a.vec[vi * a.ldv + (in ? c : 0)];
+            if (a.wgt != nullptr) v *= a.wgt[vi];
+            vimg[k] = in ? v : 0.0f;
+        }
+        __syncthreads();
+        if (tile + 1 < n_tiles) fetch(tile + 1, 0);
+        {
+            const f16x8 *ib = img[stage & 1];
+            f16x8 bf[2];
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb) bf[fb] = ib[(wave * 2 + fb) * kUnits + lane];
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) {
+                const f16x8 as = ib[(kFixed / 32 + sb) * kUnits + 64 + lane];
+                mfma_acc(acc[0][sb], as, bf[0]);
+                mfma_acc(acc[1][sb], as, bf[1]);
+            }
+        }
+        ++stage;
+
+        // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block
+#pragma unroll
+        for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                float vr[TP];
+#pragma unroll
+                for (int c4 = 0; c4 < TP; c4 += 4) {
+                    const f32x4 u = *reinterpret_cast<const f32x4 *>(&vimg[j * TP + c4]);
+                    vr[c4] = u[0]; vr[c4 + 1] = u[1]; vr[c4 + 2] = u[2]; vr[c4 + 3] = u[3];
+                }
+#pragma unroll
+                for (int fb = 0; fb < 2; ++fb) {
+                    // exponent <= 0 up to rounding; med3 keeps the kernel value in [0, 1]
+                    const float p = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(acc[fb][sb][r]), 0.0f, 1.0f);
+#pragma unroll
+                    for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[c], sum[fb][c]);
+                }
+            }
+    }
+
+    // the two half-waves hold different stream rows of the same fixed point
+    float *out = a.out + chunk * a.chunk_stride;
+#pragma unroll
+    for (int fb = 0; fb < 2; ++fb) {
+        const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
+#pragma unroll
+        for (int c = 0; c < TP; ++c) {
+            float v = sum[fb][c];
+            v += __shfl_xor(v, 32);
+            if (h == 0 && idx < a.nF && c < t) out[idx * a.ldo + c] = v;
+        }
+    }
+}
+
+hipError_t pack_points(const float *P, int64_t nP, int64_t ld, int d, float sigma, int64_t row0, int64_t rows,
+                       int n_kc, f16x8 *img, hipStream_t stream)
+{
+    const dim3 grid((unsigned)(rows / 32));
+    const bool a16 = (d % 4 == 0) && (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(P) & 15) == 0);
+    if (a16)
+        hipLaunchKernelGGL((pack_points_kernel<4>), grid, dim3(kThreads), 0, stream, P, nP, ld, d, sigma, row0, n_kc, img);
+    else
+        hipLaunchKernelGGL((pack_points_kernel<1>), grid, dim3(kThreads), 0, stream, P, nP, ld, d, sigma, row0, n_kc, img);
+    return hipGetLastError();
+}
+
+template <int TP>
+void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t fixed_row0, int64_t f_blocks,
+               int64_t chunk0, int64_t chunks, int n_kc, hipStream_t stream)
+{
+    const dim3 grid((unsigned)f_blocks, (unsigned)chunks);
+    hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP>), grid, dim3(kThreads), 0, stream, a, Fimg, Simg, fixed_row0, chunk0,
+                       n_kc);
+}
+
+} // namespace
+
+// bytes of packed image per point
+size_t gemm_f16_pack_bytes_per_point(int d) { return (size_t)((d + kChunk - 1) / kChunk + 1) * 64; }
+
+// least workspace: the smaller operand whole plus one slab unit of the other
+size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len, int d)
+{
+    const size_t pp = gemm_f16_pack_bytes_per_point(d);
+    const size_t f = (size_t)((nF + kFixed - 1) / kFixed * kFixed) * pp, s = (size_t)nS_padded * pp;
+    return f <= s ? f + (size_t)chunk_len * pp : s + (size_t)kFixed * pp;
+}
+
+hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
+{
+    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > 16) return hipErrorInvalidValue;
+    if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
+    if (a.n_chunks > 65535) return hipErrorInvalidValue;
+    const int n_kc = (a.d + kChunk - 1) / kChunk;
+    const size_t pp = gemm_f16_pack_bytes_per_point(a.d);
+    const int64_t nFp = (a.nF + kFixed - 1) / kFixed * kFixed;
+    const int64_t nSp = a.n_chunks * a.chunk_len;
+    const size_t bytesF = (size_t)nFp * pp, bytesS = (size_t)nSp * pp;
+    if (pack_bytes < gemm_f16_min_pack_bytes(a.nF, nSp, a.chunk_len, a.d)) return hipErrorInvalidValue;
+
+    // slab sizes: the smaller operand is packed whole, the other in slabs that fill the rest
+    int64_t f_slab = nFp, s_slab = a.n_chunks; // fixed rows / stream chunks per slab
+    if (bytesF + bytesS > pack_bytes) {
+        if (bytesF <= bytesS) s_slab = (int64_t)((pack_bytes - bytesF) / ((size_t)a.chunk_len * pp));
+        else f_slab = (int64_t)((pack_bytes - bytesS) / ((size_t)kFixed * pp)) * kFixed;
+    }
+    if (f_slab < kFixed || s_slab < 1) return hipErrorInvalidValue;
+    f16x8 *Fimg = static_cast<f16x8 *>(pack_buf);
+    const int64_t f_rows_max = f_slab < nFp ? f_slab : nFp;
+    f16x8 *Simg = Fimg + (size_t)f_rows_max * pp / sizeof(f16x8);
+
+    for (int64_t f0 = 0; f0 < nFp; f0 += f_slab) {
+        const int64_t f_rows = (nFp - f0 < f_slab) ? nFp - f0 : f_slab;
+        hipError_t e = pack_points(a.F, a.nF, a.ldf, a.d, a.sigma, f0, f_rows, n_kc, Fimg, stream);
+        if (e != hipSuccess) return e;
+        for (int64_t c0 = 0; c0 < a.n_chunks; c0 += s_slab) {
+            const int64_t nc = (a.n_chunks - c0 < s_slab) ? a.n_chunks - c0 : s_slab;
+            if (f0 == 0 || s_slab < a.n_chunks) { // a whole stream image is built once
+                e = pack_points(a.S, a.nS, a.lds, a.d, a.sigma, c0 * a.chunk_len, nc * a.chunk_len, n_kc, Simg, stream);
+                if (e != hipSuccess) return e;
+            }
+            const int64_t fb = f_rows / kFixed;
+            if (a.t <= 4) launch_tp<4>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream);
+            else if (a.t <= 8) launch_tp<8>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream);
+            else if (a.t <= 12) launch_tp<12>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream);
+            else launch_tp<16>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
+} // namespace knm

@@ -51,6 +51,11 @@ int gemm_max_t();
 int64_t gemm_stage_points();
 int64_t gemm_fixed_per_block();
 hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream);
+// the same shapes with the cross term as three f16 MFMA products (knm_gemm_f16.hip); both
+// operands are packed into the workspace, whole or slab by slab
+size_t gemm_f16_pack_bytes_per_point(int d);
+size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len, int d);
+hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream);
 // out[j * ldo] = sum over chunks of part[chunk * chunk_stride + j * ldp], summed in fp64
 hipError_t launch_merge(const float *part, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
                         float *out, int64_t ldo, int64_t count, hipStream_t stream);
@@ -65,7 +70,7 @@ struct knm_ctx {
     size_t w_bytes = 0;
     float *part_buf = nullptr;
     size_t part_bytes = 0;
-    float *pack_buf = nullptr; // packed stream image of the split-fp16 engine
+    float *pack_buf = nullptr; // packed operand images of the split-fp16 engines
     size_t pack_bytes = 0;
     int cross_term = KNM_CROSS_F16X3;
     // timing

@@ -1,5 +1,6 @@
 """Full-size parity in the launch configuration the benchmark times: the mid workload
-(n = 11M, d = 28, M = 100k) and the low-dimensional one (n = 5.9M, d = 8, M = 100k).
+(n = 11M, d = 28, M = 100k), the low-dimensional one (n = 5.9M, d = 8, M = 100k) and the
+high-dimensional multi-output one (n = 2M, d = 784, M = 50k, t = 10; the K-loop engine).
 
 The oracle cannot sweep 1e12 entries, so it checks sampled outputs one by one: rows of
 W = K V (each needs all M centres) and entries of R = K^T Y (each needs all n rows), plus
@@ -21,8 +22,8 @@ def rel_l2(got, ref):
     return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-@pytest.mark.parametrize("name", ["mid", "lowdim"])
-def test_full_size_sampled_outputs(knm, name):
+@pytest.mark.parametrize("name,n_rows,n_cols", [("mid", 503, 6), ("lowdim", 503, 6), ("highdim", 120, 2)])
+def test_full_size_sampled_outputs(knm, name, n_rows, n_cols):
     w = synth.workload(name)
     print(f"workload {name}: n={w.n} d={w.d} M={w.M}", flush=True)
     inp = synth.make_inputs(w, device="cuda", with_targets=True)
@@ -38,7 +39,7 @@ def test_full_size_sampled_outputs(knm, name):
     g = np.random.default_rng(7)
 
     # rows of W = K V: first and last tiles plus random rows
-    rows = np.unique(np.concatenate([[0, 1, 31, 32, 255, 256, w.n - 257, w.n - 2, w.n - 1], g.integers(0, w.n, 503)]))
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 255, 256, w.n - 257, w.n - 2, w.n - 1], g.integers(0, w.n, n_rows)]))
     Xs = X[torch.from_numpy(rows).cuda()].cpu().numpy()
     Wo = oracle.knm_v(Xs, Cn, w.sigma, vn)
     Wg = W[torch.from_numpy(rows).cuda()].cpu().numpy()
@@ -47,7 +48,7 @@ def test_full_size_sampled_outputs(knm, name):
     print("row samples ok", flush=True)
 
     # entries of R = K^T Y: every one is a sum over all n rows
-    cols = np.unique(np.concatenate([[0, 31, 32, 255, 256, w.M - 1], g.integers(0, w.M, 6)]))
+    cols = np.unique(np.concatenate([[0, 31, 32, 255, 256, w.M - 1], g.integers(0, w.M, n_cols)]))
     Xn = X.cpu().numpy()
     Yn = Y.cpu().numpy()
     Ro = oracle.knm_t_y(Xn, Cn[cols], w.sigma, Yn)
