@@ -261,7 +261,7 @@ def main() -> int:
 
     if not args.no_cpu:
         # bounded sample: about 10-30 s of oracle work on the host cores
-        rows = args.cpu_rows or max(64, int(1.2e10 * (8.0 / max(w.d, 8)) ** 0.5 / w.M))
+        rows = args.cpu_rows or max(64, int(3.2e11 / (w.M * (w.d + 30.0))))
         rows = min(rows, w.n)
         stride = max(1, w.n // rows)
         idx = torch.arange(0, rows, device="cuda") * stride
