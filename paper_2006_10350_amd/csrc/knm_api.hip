@@ -54,6 +54,7 @@ int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int64_t *chunk_len)
     const int64_t min_len = 16 * stage;    // amortise the per-workgroup prologue/epilogue
     const int64_t max_len = (int64_t)1 << 18; // bound the length of a per-lane fp32 running sum
     int64_t chunks = (target_wgs + blocks - 1) / blocks;
+    if (gemm && chunks < 16) chunks = 16;  // the K-loop engine tiles (fixed blocks x chunks) over each XCD's L2
     const int64_t max_chunks_by_len = (nS + min_len - 1) / min_len;
     if (chunks > max_chunks_by_len) chunks = max_chunks_by_len;
     const int64_t min_chunks_by_len = (nS + max_len - 1) / max_len;

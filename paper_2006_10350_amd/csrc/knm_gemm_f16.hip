@@ -28,6 +28,8 @@
 // the stream block is the A operand, so a lane's accumulator registers run over stream
 // points of one fixed point and the reduction against the vector columns is in-lane.
 
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "knm_internal.h"
@@ -168,14 +170,36 @@ __device__ __forceinline__ void mfma_acc(f32x16 &acc, const f16x8 &a, const f16x
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
-// Fimg: image of the fixed points [fixed_row0, fixed_row0 + 256 gridDim.x);
-// Simg: image of the stream chunks [chunk0, chunk0 + gridDim.y).
+// Workgroup -> (fixed block, stream chunk).  Workgroups are dealt round-robin to the 8 XCDs
+// (each with its own L2) in launch order, and the ones resident together on an XCD are
+// consecutive in that order.  They are therefore numbered so that each XCD works through
+// "patches" of pf fixed blocks x pc chunks: the pf fixed-block images, which every
+// workgroup re-reads for each of its stream tiles, stay in that XCD's L2, and a stream tile
+// fetched by one workgroup is reused by the pf - 1 others on the same chunk.
+struct PatchMap {
+    int pf, pc;          // patch shape
+    int64_t n_fblocks;   // fixed blocks of this launch
+    int64_t n_chunks;    // stream chunks of this launch
+    int64_t n_patch_f;   // ceil(n_fblocks / pf)
+};
+
+// Fimg: image of the fixed points [fixed_row0, fixed_row0 + 256 n_fblocks);
+// Simg: image of the stream chunks [chunk0, chunk0 + n_chunks).
 // TP: number of vector columns, padded to a multiple of 4.
 template <int TP>
 __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
                                                                      const f16x8 *__restrict__ Simg,
-                                                                     int64_t fixed_row0, int64_t chunk0, int n_kc)
+                                                                     int64_t fixed_row0, int64_t chunk0, int n_kc,
+                                                                     PatchMap pm)
 {
+    const int per_patch = pm.pf * pm.pc;
+    const int64_t slot = (int64_t)blockIdx.x >> 3;
+    const int64_t patch = (slot / per_patch) * 8 + (blockIdx.x & 7);
+    const int within = (int)(slot % per_patch);
+    const int64_t fblk = (patch % pm.n_patch_f) * pm.pf + within % pm.pf;
+    const int64_t cblk = (patch / pm.n_patch_f) * pm.pc + within / pm.pf;
+    if (fblk >= pm.n_fblocks || cblk >= pm.n_chunks) return; // whole workgroup, before any barrier
+
     __shared__ f16x8 img[2][kBlocks * kUnits]; // 2 x 24 KB
     __shared__ __attribute__((aligned(16))) float vimg[kStream * TP];
 
@@ -186,8 +210,8 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     const int t = a.t;
     const int n_st = n_kc + 1; // stages per tile: the feature chunks, then the norm slots
 
-    const int64_t fixed0 = fixed_row0 + (int64_t)blockIdx.x * kFixed;
-    const int64_t chunk = chunk0 + blockIdx.y;
+    const int64_t fixed0 = fixed_row0 + fblk * kFixed;
+    const int64_t chunk = chunk0 + cblk;
     const int64_t chunk_begin = chunk * a.chunk_len;
     int64_t chunk_end = chunk_begin + a.chunk_len;
     if (chunk_end > a.nS) chunk_end = a.nS;
@@ -198,8 +222,8 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     // per-load and per-stage offsets are uniform, the thread's own offset fits 32 bits.
     const int64_t blk_units = (int64_t)n_st * kUnits;
     const int toff = (tid >> 7) * (int)blk_units + (tid & (kUnits - 1));
-    const f16x8 *const fbase = Fimg + (int64_t)blockIdx.x * (kFixed / 32) * blk_units;
-    const f16x8 *const sbase = Simg + (int64_t)blockIdx.y * (a.chunk_len / 32) * blk_units;
+    const f16x8 *const fbase = Fimg + fblk * (kFixed / 32) * blk_units;
+    const f16x8 *const sbase = Simg + cblk * (a.chunk_len / 32) * blk_units;
 
     float sum[2][TP];
 #pragma unroll
@@ -344,13 +368,29 @@ hipError_t pack_points(const float *P, int64_t nP, int64_t ld, int d, float sigm
     return hipGetLastError();
 }
 
+constexpr int kPatch = 64; // workgroups per patch = resident workgroups per XCD (32 CUs x 2)
+int patch_pf()
+{
+    const char *e = getenv("KNM_GEMM_PF");
+    const int v = e ? atoi(e) : 8;
+    return (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) ? v : 8;
+}
+
 template <int TP>
 void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t fixed_row0, int64_t f_blocks,
                int64_t chunk0, int64_t chunks, int n_kc, hipStream_t stream)
 {
-    const dim3 grid((unsigned)f_blocks, (unsigned)chunks);
+    PatchMap pm;
+    pm.pf = patch_pf();
+    pm.pc = kPatch / pm.pf;
+    pm.n_fblocks = f_blocks;
+    pm.n_chunks = chunks;
+    pm.n_patch_f = (f_blocks + pm.pf - 1) / pm.pf;
+    const int64_t n_patch_c = (chunks + pm.pc - 1) / pm.pc;
+    const int64_t patches = (pm.n_patch_f * n_patch_c + 7) / 8 * 8;
+    const dim3 grid((unsigned)(patches * kPatch));
     hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP>), grid, dim3(kThreads), 0, stream, a, Fimg, Simg, fixed_row0, chunk0,
-                       n_kc);
+                       n_kc, pm);
 }
 
 } // namespace
