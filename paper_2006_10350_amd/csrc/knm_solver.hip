@@ -329,6 +329,50 @@ int precond_free(knm_precond *p)
     return KNM_OK;
 }
 
+// Upper Cholesky factor in place, R^T R = A (column-major, leading dimension M), right-looking
+// with wide block rows: factor the diagonal block (rocSOLVER), solve the block row against it
+// (TRSM), downdate the trailing triangle (SYRK, which carries M^3 / 3 of the flop and runs
+// near the fp64 matrix peak at this width).  rocSOLVER's own blocking is much narrower and
+// reaches about half that rate on these sizes.  `info` holds one status word per block row
+// (filled asynchronously); first_bad receives the 1-based index of the first failing pivot, or 0.
+int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t M, int64_t *info_dev, int64_t info_len,
+                       int64_t *first_bad)
+{
+    int64_t b = ((M + 7) / 8 + 255) / 256 * 256;
+    if (b > 4096) b = 4096;
+    const int64_t nb = (M + b - 1) / b;
+    if (nb > info_len) return fail(ctx, KNM_HIP_ERROR, "status buffer too small");
+    const double one = 1.0, minus_one = -1.0;
+    for (int64_t k = 0; k < nb; ++k) {
+        const int64_t r0 = k * b;
+        const int64_t w = (M - r0 < b) ? M - r0 : b;
+        const int64_t rest = M - r0 - w;
+        double *Akk = A + r0 + (size_t)r0 * M;
+        if (rocsolver_dpotrf_64(h, rocblas_fill_upper, w, Akk, M, info_dev + k) != rocblas_status_success)
+            return fail(ctx, KNM_HIP_ERROR, "rocsolver_dpotrf");
+        if (rest == 0) break;
+        double *Akr = A + r0 + (size_t)(r0 + w) * M; // block row to the right of the diagonal block
+        if (rocblas_dtrsm_64(h, rocblas_side_left, rocblas_fill_upper, rocblas_operation_transpose,
+                             rocblas_diagonal_non_unit, w, rest, &one, Akk, M, Akr, M) != rocblas_status_success)
+            return fail(ctx, KNM_HIP_ERROR, "rocblas_dtrsm");
+        double *Arr = A + (r0 + w) + (size_t)(r0 + w) * M;
+        if (rocblas_dsyrk_64(h, rocblas_fill_upper, rocblas_operation_transpose, rest, w, &minus_one, Akr, M, &one,
+                             Arr, M) != rocblas_status_success)
+            return fail(ctx, KNM_HIP_ERROR, "rocblas_dsyrk");
+    }
+    std::vector<int64_t> host(nb, 0);
+    hipError_t e = hipMemcpyAsync(host.data(), info_dev, sizeof(int64_t) * nb, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "factorisation status copy", e);
+    *first_bad = 0;
+    for (int64_t k = 0; k < nb; ++k)
+        if (host[k] != 0) {
+            *first_bad = k * b + host[k];
+            break;
+        }
+    return KNM_OK;
+}
+
 int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma, double lambda,
                   double jitter, knm_precond **out, int64_t *bad_pivot_or_null)
 {
@@ -358,7 +402,8 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Tdinv), dbytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Adinv), dbytes);
     DevBuf info;
-    if (e != hipSuccess || info.alloc(ctx, sizeof(int64_t))) {
+    const int64_t info_len = 64; // status words: one per block row of the factorisation (at most 8 + M / 4096)
+    if (e != hipSuccess || info.alloc(ctx, sizeof(int64_t) * info_len)) {
         (void)hipGetLastError();
         precond_free(p);
         return fail(ctx, KNM_ALLOC, "hipMalloc(preconditioner)", e);
@@ -390,15 +435,16 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
         return err;
     };
 
-    // The 64-bit interfaces are required: M^2 exceeds 2^31 elements for M > 46340, which the
-    // 32-bit interfaces' internal element offsets cannot address.
+    // The 64-bit library interfaces are required throughout: M^2 exceeds 2^31 elements for
+    // M > 46340, which the 32-bit interfaces' internal element offsets cannot address.
     int64_t host_info = 0;
-    if (rocsolver_dpotrf_64(h, rocblas_fill_upper, M, p->T, M, info.as<int64_t>()) !=
-        rocblas_status_success)
-        return bail(KNM_HIP_ERROR, "rocsolver_dpotrf(T)");
-    e = hipMemcpyAsync(&host_info, info.p, sizeof(int64_t), hipMemcpyDeviceToHost, ctx->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    if (e != hipSuccess) return bail(KNM_HIP_ERROR, "dpotrf(T) status copy");
+    {
+        int st2 = chol_upper_blocked(ctx, h, p->T, M, info.as<int64_t>(), info_len, &host_info);
+        if (st2) {
+            precond_free(p);
+            return st2;
+        }
+    }
     int64_t pivot = host_info;
     if (pivot == 0 && bad_diagonal(p->T, &pivot) != hipSuccess) return bail(KNM_HIP_ERROR, "diagonal check");
     if (pivot != 0) {
@@ -429,12 +475,13 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
         }
     }
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, lambda, 0);
-    if (rocsolver_dpotrf_64(h, rocblas_fill_upper, M, p->A, M, info.as<int64_t>()) !=
-        rocblas_status_success)
-        return bail(KNM_HIP_ERROR, "rocsolver_dpotrf(A)");
-    e = hipMemcpyAsync(&host_info, info.p, sizeof(int64_t), hipMemcpyDeviceToHost, ctx->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    if (e != hipSuccess) return bail(KNM_HIP_ERROR, "dpotrf(A) status copy");
+    {
+        int st2 = chol_upper_blocked(ctx, h, p->A, M, info.as<int64_t>(), info_len, &host_info);
+        if (st2) {
+            precond_free(p);
+            return st2;
+        }
+    }
     pivot = host_info;
     if (pivot == 0 && bad_diagonal(p->A, &pivot) != hipSuccess) return bail(KNM_HIP_ERROR, "diagonal check");
     if (pivot != 0) {
