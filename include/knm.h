@@ -121,17 +121,18 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
                    const float *C, int64_t M, int64_t ldc, float sigma,
                    const float *alpha, int t, float *out);
 
-/* Arithmetic of the cross term <x, c> inside the kernel evaluation, for d <= 44 and t = 1
- * (other shapes always use fp32 MFMA):
+/* Arithmetic of the cross term <x, c> inside the kernel evaluation:
  *   KNM_CROSS_F16X3 (default) each feature, scaled by sqrt(log2 e)/sigma, is split into two
  *                   fp16 halves (22 significant bits) and the product is evaluated as
  *                   hi*hi + hi*lo + lo*hi on the f16 matrix cores with fp32 accumulation; the
  *                   norms are carried as exact fixed-point digits.  Same accuracy class as
  *                   fp32 (the dropped lo*lo term is ~2^-22 per feature; measured ~4e-7
- *                   relative L2 against the fp64 oracle).  Scaled features beyond 65504 in
- *                   magnitude and squared norms beyond 2^25 saturate.  Uses a library-owned
- *                   workspace of at most 2 GiB for the converted stream operand.
- *   KNM_CROSS_F32   fp32 MFMA on the unsplit features: no range limits, about 2.9x slower
+ *                   relative L2 against the fp64 oracle).  Scaled features beyond 65000 in
+ *                   magnitude and squared norms of scaled points beyond 2^22 saturate.  Uses a
+ *                   library-owned workspace for the converted operands: at most 2 GiB for
+ *                   d <= 44 with t = 1, at most 8 GiB otherwise.  Shapes with 44 < d <= 64 and
+ *                   t = 1 run in fp32 in either mode.
+ *   KNM_CROSS_F32   fp32 MFMA on the unsplit features: no range limits, 3 to 5 times slower
  *                   (fp32 MFMA and the exp/FMA work share the vector ALU's issue). */
 typedef enum { KNM_CROSS_F32 = 0, KNM_CROSS_F16X3 = 1 } knm_cross_term;
 int knm_set_cross_term(knm_ctx *ctx, int mode);

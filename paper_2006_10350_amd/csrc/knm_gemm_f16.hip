@@ -8,8 +8,8 @@
 //     <zf, zx>  ~=  fh.xh + fh.xl + fl.xh                      (drops fl.xl ~ 2^-22),
 // so that the accumulator holds  log2 k(f, x) = <zf, zx> - |zf|^2 / 2 - |zx|^2 / 2  after
 // one more MFMA whose K-slots carry the two norm terms as 4-digit fixed-point numbers
-//     n = q1 2^13 + q2 2^2 + q3 2^-9 + q4 2^-20,   q_i integers <= 2048 (exact in fp16),
-// against the constants 2^13, 2^2, 2^-9, 2^-20 on the other operand.
+//     n = q1 2^10 + q2 2^-1 + q3 2^-12 + q4 2^-23,   q_i integers <= 2048 (exact in fp16),
+// against the constants 2^10, 2^-1, 2^-12, 2^-23 on the other operand.
 //
 // Packed images.  Both operands are converted once per sweep (`pack_points_kernel`) into
 // images laid out exactly as the LDS stage, so staging is a 16-byte copy and the
@@ -49,34 +49,35 @@ constexpr int kChunk = 16;                     // features per K-chunk = one MFM
 constexpr int kUnits = 128;                    // 16-byte units per block and chunk (2 planes x 64 lanes)
 constexpr int kLoads = kBlocks * kUnits / kThreads; // units copied per thread and stage (6)
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kC1 = 8192.0f, kC2 = 4.0f, kC3 = 0.001953125f, kC4 = 9.5367431640625e-07f; // 2^13 2^2 2^-9 2^-20
+constexpr float kC1 = 1024.0f, kC2 = 0.5f, kC3 = 0.000244140625f, kC4 = 1.1920928955078125e-07f; // 2^10 2^-1 2^-12 2^-23
 
 static_assert(kLoads * kThreads == kBlocks * kUnits, "staging must divide evenly");
 
-// hi with the packed round-toward-zero conversion (saturates at the largest finite half),
-// lo = nearest half of the exact remainder z - hi
+// hi = nearest half of z (clamped to the finite range first), lo = nearest half of the exact
+// remainder z - hi; hi + lo carries 22-23 significant bits of z
 __device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 &lo)
 {
-    z0 = fminf(fmaxf(z0, -65000.0f), 65000.0f);
-    z1 = fminf(fmaxf(z1, -65000.0f), 65000.0f);
-    hi = __builtin_amdgcn_cvt_pkrtz(z0, z1);
+    f32x2 z;
+    z[0] = fminf(fmaxf(z0, -65000.0f), 65000.0f);
+    z[1] = fminf(fmaxf(z1, -65000.0f), 65000.0f);
+    hi = __builtin_convertvector(z, f16x2);
     f32x2 rem;
-    rem[0] = z0 - (float)hi[0];
-    rem[1] = z1 - (float)hi[1];
+    rem[0] = z[0] - (float)hi[0];
+    rem[1] = z[1] - (float)hi[1];
     lo = __builtin_convertvector(rem, f16x2);
 }
 
 // -n as four fixed-point digits; n >= 0
 __device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
 {
-    n = fminf(n, 16777215.0f);
-    const float q1 = floorf(n * (1.0f / 8192.0f));
-    float r = fmaf(-q1, 8192.0f, n);
-    const float q2 = floorf(r * 0.25f);
-    r = fmaf(-q2, 4.0f, r);
-    const float q3 = floorf(r * 512.0f);
+    n = fminf(n, 2097151.0f);
+    const float q1 = floorf(n * (1.0f / 1024.0f));
+    float r = fmaf(-q1, 1024.0f, n);
+    const float q2 = floorf(r * 2.0f);
+    r = fmaf(-q2, 0.5f, r);
+    const float q3 = floorf(r * 4096.0f);
     r = fmaf(-q3, kC3, r);
-    const float q4 = rintf(r * 1048576.0f);
+    const float q4 = rintf(r * 8388608.0f);
     q[0] = (_Float16)(-q1); q[1] = (_Float16)(-q2); q[2] = (_Float16)(-q3); q[3] = (_Float16)(-q4);
 }
 

@@ -13,10 +13,11 @@
 // i.e. three "planes" of the same MFMA shape.  With this scaling the base-2 exponent is
 //     log2 k(f, x) = <zf, zx> - |zf|^2 / 2 - |zx|^2 / 2 .
 // The two norm terms ride in four spare K-slots per side as 4-digit fixed-point numbers,
-//     n = q1 2^13 + q2 2^2 + q3 2^-9 + q4 2^-20,   q_i integers <= 2048 (exact in fp16),
-// multiplied by the constants 2^13, 2^2, 2^-9, 2^-20 on the other operand, so the MFMA
-// accumulator again holds the exponent itself (resolution 2^-21, range 2^24).
-// Inputs outside the fp16 range (|z| > 65000, norm term >= 2^24) saturate.
+//     n = q1 2^10 + q2 2^-1 + q3 2^-12 + q4 2^-23,   q_i integers <= 2048 (exact in fp16),
+// multiplied by the constants 2^10, 2^-1, 2^-12, 2^-23 on the other operand, so the MFMA
+// accumulator again holds the exponent itself (resolution 2^-24, range 2^21; the last constant
+// is an fp16 subnormal, which the MFMA honours).
+// Inputs outside that range (|z| > 65000, norm term |z|^2 / 2 >= 2^21) saturate.
 //
 // Layout.  A K=16 MFMA takes 8 halves ("unit") from each half-wave.  Unit u holds
 // features 8u .. 8u+7; the last four slots of the last unit are the special slots.
@@ -53,7 +54,7 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kStage = 128; // stream points per LDS stage (2 threads per point)
 constexpr int kTilesPerStage = kStage / 32;
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kC1 = 8192.0f, kC2 = 4.0f, kC3 = 0.001953125f, kC4 = 9.5367431640625e-07f; // 2^13 2^2 2^-9 2^-20
+constexpr float kC1 = 1024.0f, kC2 = 0.5f, kC3 = 0.000244140625f, kC4 = 1.1920928955078125e-07f; // 2^10 2^-1 2^-12 2^-23
 
 __device__ __forceinline__ void split_half(float z, _Float16 &hi, _Float16 &lo)
 {
@@ -63,29 +64,31 @@ __device__ __forceinline__ void split_half(float z, _Float16 &hi, _Float16 &lo)
 }
 
 typedef __fp16 f16x2 __attribute__((ext_vector_type(2)));
-// Two features at once: hi with the packed round-toward-zero conversion (which saturates at
-// the largest finite half instead of overflowing), lo = nearest half of the exact remainder
-// z - hi; hi + lo carries 22 significant bits of z.
+// Two features at once: hi = nearest half of z (clamped to the finite range first), lo = nearest
+// half of the exact remainder z - hi; hi + lo carries 22-23 significant bits of z.
 __device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 &lo)
 {
-    hi = __builtin_amdgcn_cvt_pkrtz(z0, z1);
+    f32x2 z;
+    z[0] = fminf(fmaxf(z0, -65000.0f), 65000.0f);
+    z[1] = fminf(fmaxf(z1, -65000.0f), 65000.0f);
+    hi = __builtin_convertvector(z, f16x2);
     f32x2 rem;
-    rem[0] = z0 - (float)hi[0];
-    rem[1] = z1 - (float)hi[1];
+    rem[0] = z[0] - (float)hi[0];
+    rem[1] = z[1] - (float)hi[1];
     lo = __builtin_convertvector(rem, f16x2);
 }
 
 // -n as four fixed-point digits (see the header comment); n >= 0
 __device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
 {
-    n = fminf(n, 16777215.0f);
-    const float q1 = floorf(n * (1.0f / 8192.0f));
-    float r = fmaf(-q1, 8192.0f, n);
-    const float q2 = floorf(r * 0.25f);
-    r = fmaf(-q2, 4.0f, r);
-    const float q3 = floorf(r * 512.0f);
+    n = fminf(n, 2097151.0f);
+    const float q1 = floorf(n * (1.0f / 1024.0f));
+    float r = fmaf(-q1, 1024.0f, n);
+    const float q2 = floorf(r * 2.0f);
+    r = fmaf(-q2, 0.5f, r);
+    const float q3 = floorf(r * 4096.0f);
     r = fmaf(-q3, kC3, r);
-    const float q4 = rintf(r * 1048576.0f);
+    const float q4 = rintf(r * 8388608.0f);
     q[0] = (_Float16)(-q1); q[1] = (_Float16)(-q2); q[2] = (_Float16)(-q3); q[3] = (_Float16)(-q4);
 }
 

@@ -23,8 +23,9 @@ def _rand(n, d, seed, scale=1.0):
     return (scale * torch.randn(n, d, generator=g)).to(torch.float32)
 
 
-def test_preconditioner_factors_match_oracle(knm):
-    M, d, sigma, lam, jitter = 300, 5, 0.75, 1e-4, 1e-9  # sigma exactly representable in fp32
+@pytest.mark.parametrize("M", [300, 1100])  # 2 and 5 block rows of the blocked factorisation
+def test_preconditioner_factors_match_oracle(knm, M):
+    d, sigma, lam, jitter = 5, 0.75, 1e-4, 1e-9  # sigma exactly representable in fp32
     C = _rand(M, d, 31)
     pre = knm.precond_build(C.cuda(), sigma, lam, jitter)
     T, A = pre.factors()
@@ -144,6 +145,30 @@ def test_all_points_as_centres_reaches_exact_krr(knm):
     exact = np.linalg.solve(K + n * lam * np.eye(n), y.numpy().astype(np.float64))
     pred = knm.falkon_predict(X.cuda(), X.cuda(), sigma, alpha).cpu().numpy()
     assert rel_l2(pred, K @ exact) < 1e-3
+
+
+def test_product_parity_on_a_cg_shaped_vector(knm, capsys):
+    """The vectors the product sees inside CG are v = T^-1 A^-1 p: huge dynamic range and sign
+    alternation (T^-1 amplifies by ~ sqrt(cond K_MM)), so K^T K v cancels heavily and fp32 rounding
+    of the entries is amplified.  The error is reported; the assertion is only a sanity bound."""
+    n, M, d, sigma, lam, jitter = 6000, 400, 6, 1.5, 1e-6, 1e-7
+    X, C = _rand(n, d, 71), _rand(M, d, 72)
+    T, A = oracle.precond(C.numpy(), sigma, lam, jitter)
+    p = _rand(M, 1, 73).numpy().astype(np.float64)
+    v = oracle.solve_upper(T, oracle.solve_upper(A, p))
+    v32 = torch.from_numpy(v.astype(np.float32))
+    for mode in ("f16x3", "f32"):
+        ctx = knm.default_context()
+        ctx.set_cross_term(mode)
+        try:
+            U = knm.knm_prod(X.cuda(), C.cuda(), sigma, v32.cuda()).cpu().numpy()
+        finally:
+            ctx.set_cross_term("f16x3")
+        err = rel_l2(U, oracle.knm_prod(X.numpy(), C.numpy(), sigma, v32.numpy()))
+        with capsys.disabled():
+            print(f"\n  CG-shaped v ({mode}): max|v|/rms = {np.abs(v).max() / np.sqrt((v ** 2).mean()):.1f}, "
+                  f"|v| = {np.linalg.norm(v):.3e}, rel L2 error of K^T K v = {err:.2e}", flush=True)
+        assert err < 1e-2
 
 
 def test_fit_rejects_bad_arguments(knm):
