@@ -100,6 +100,22 @@ int falkon_linop(knm_ctx *ctx, const knm_precond *p,
                  const float *C, int64_t M, int64_t ldc, float sigma, double lambda,
                  const double *beta, int t, double *out);
 
+/* The same operator with the weighted product (LinOp of Alg. 2, WeightedFalkon):
+ *   out = A^-T ( T^-T K_nm^T diag(dw) K_nm T^-1 A^-1 beta + lambda n A^-1 beta ),
+ * dw[n] >= 0 fp32 DEVICE pointer, NULL for the identity. */
+int falkon_linop_weighted(knm_ctx *ctx, const knm_precond *p,
+                          const float *X, int64_t n, int d, int64_t ldx,
+                          const float *C, int64_t M, int64_t ldc, float sigma, double lambda,
+                          const float *dw_or_null, const double *beta, int t, double *out);
+
+/* Second factor of the weighted preconditioner (Alg. 2, WeightedPreconditioner), rebuilt in
+ * place from the first:  A = chol_upper(T diag(dw) T^T / M + lambda I), dw[M] >= 0 fp64 DEVICE
+ * pointer (NULL for the identity, which gives precond_build's A for the new lambda).  T, which
+ * depends on the centres only, is kept.  On KNM_NOT_PD the factor is unusable until the next
+ * successful call; *bad_pivot_or_null (HOST) receives minus the 1-based failing pivot. */
+int precond_reweight(knm_ctx *ctx, knm_precond *p, double lambda, const double *dw_or_null,
+                     int64_t *bad_pivot_or_null);
+
 /* Falkon (Alg. 1) with the centres given by the caller: builds the preconditioner,
  * forms rhs = A^-T T^-T K_nm^T Y, runs exactly `iters` conjugate-gradient steps on the
  * operator of Eq. 9 from beta = 0 (one step size per column of Y), and writes
@@ -110,6 +126,24 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
                const float *Y, int t, const float *C, int64_t M, int64_t ldc,
                float sigma, double lambda, double jitter, int iters,
                float *alpha, double *resid_norms_or_null);
+
+/* Approximate Newton method for the logistic loss l(z, y) = log(1 + exp(-y z)), y = +-1
+ * (Appendix "Logistic Falkon Algorithm", Alg. 2).  The schedule of regularisers is not given in
+ * the paper: Newton step k uses lambdas[k] and iters[k] conjugate-gradient iterations (HOST
+ * arrays of n_steps entries).  Reading of Alg. 2: the objective is
+ *   J(alpha) = 1/n sum_i l((K_nm alpha)_i, y_i) + lambda/2 alpha^T (K_MM + jitter I) alpha,
+ * and step k, from alpha_k with g = l', D = diag l'' at K_nm alpha_k, runs CG from zero on
+ *   P^T (K_nm^T D K_nm + lambda n (K_MM + jitter I)) P beta
+ *        = -P^T (K_nm^T g + lambda n (K_MM + jitter I) alpha_k),      P = T^-1 A^-1,
+ * with the weighted preconditioner T^T T = K_MM + jitter I, A^T A = T Dm T^T / M + lambda I,
+ * Dm = diag l''((K_MM alpha_k)_j, yC_j); then alpha_{k+1} = alpha_k + P beta, from alpha_0 = 0.
+ * y[n], yC[M] (labels of the rows and of the centres) and alpha[M] are fp32 DEVICE pointers;
+ * loss_or_null is a HOST buffer of n_steps + 1 doubles receiving the mean loss before each
+ * step and after the last. */
+int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *y,
+                  const float *C, int64_t M, int64_t ldc, const float *yC, float sigma,
+                  const double *lambdas, const int *iters, int n_steps, double jitter,
+                  float *alpha, double *loss_or_null);
 
 /* Wall-clock seconds of the phases of the most recent successful falkon_fit on this context,
  * written to the HOST array seconds[4]: [0] preconditioner, [1] right-hand side

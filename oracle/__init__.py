@@ -214,3 +214,90 @@ def falkon_fit(X, Y, C, sigma: float, lam: float, iters: int, jitter: float = 0.
 
 def falkon_predict(Xtest, C, sigma: float, alpha) -> np.ndarray:
     return knm_v(Xtest, C, sigma, alpha)
+
+
+# ---- logistic loss (Appendix "Logistic Falkon Algorithm", Alg. 2) -------------------------
+#
+# Reading of Alg. 2 used here (the listing's right-hand side and the text's equation both
+# leave terms out; the Newton schedule mu_0, q is not in the paper, so the caller gives the
+# sequence of regularisers and iteration counts):
+#   objective   J(alpha) = 1/n sum_i l(z_i, y_i) + mu/2 alpha^T (K_MM + eps I) alpha,  z = K_nm alpha,
+#               l(z, y) = log(1 + exp(-y z)),  y in {-1, +1};
+#   one call of WeightedFalkon(mu, t, alpha_0) = one approximate Newton step: with
+#   g_i = l'(z_i, y_i), D = diag l''(z_i, y_i) at alpha_0, t conjugate-gradient iterations from
+#   zero on the preconditioned Newton system
+#       P^T (K_nm^T D K_nm + mu n (K_MM + eps I)) P beta = -P^T (K_nm^T g + mu n (K_MM + eps I) alpha_0),
+#   P = T^-1 A^-1, then alpha_1 = alpha_0 + P beta  (the operator is LinOp of Alg. 2 as printed);
+#   WeightedPreconditioner: T^T T = K_MM + eps I, A^T A = T Dm T^T / M + mu I with
+#   Dm = diag l''((K_MM alpha_0)_j, (y_m)_j) at the centres, as printed.
+
+def logistic_terms(z, y):
+    """Loss, first and second derivative in z of log(1 + exp(-y z)), elementwise, fp64."""
+    z = np.asarray(z, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    m = y * z
+    loss = np.logaddexp(0.0, -m)
+    s = 0.5 * (1.0 - np.tanh(0.5 * m))  # sigma(-m), stable for either sign
+    return loss, -y * s, s * (1.0 - s)
+
+
+def precond_weighted(C, sigma: float, lam: float, jitter: float, dm):
+    """T^T T = K_MM + jitter I;  A^T A = T diag(dm) T^T / M + lam I  (WeightedPreconditioner)."""
+    C = _pts(C)
+    M = C.shape[0]
+    dm = np.asarray(dm, dtype=np.float64).reshape(M)
+    T = chol_upper(kernel_matrix(C, C, sigma) + jitter * np.eye(M))
+    G = np.zeros((M, M))
+    for i in range(M):          # G = T diag(dm) T^T / M, entry by entry of the definition
+        G[i, :] = (T[i, :] * dm) @ T.T / M
+    A = chol_upper(G + lam * np.eye(M))
+    return T, A
+
+
+def linop_weighted(X, C, sigma: float, lam: float, T, A, dw, beta) -> np.ndarray:
+    """A^-T ( T^-T K^T D K T^-1 A^-1 beta + lam n A^-1 beta )  (LinOp of Alg. 2), t = 1."""
+    X, C, _ = _geom(X, C)
+    v = solve_upper(A, np.asarray(beta, dtype=np.float64).reshape(-1))
+    u = solve_upper(T, v)
+    c = knm_prod_weighted(X, C, sigma, dw, u)
+    w = solve_upper(T, np.asarray(c).reshape(-1), trans=True)
+    return solve_upper(A, w + lam * X.shape[0] * v, trans=True)
+
+
+def logfalkon_fit(X, y, C, yC, sigma: float, lambdas, iters, jitter: float = 0.0,
+                  return_loss: bool = False):
+    """Approximate Newton method of Alg. 2 with the reading above.  lambdas[k], iters[k]:
+    regulariser and conjugate-gradient iterations of Newton step k.  Returns alpha (M,), and
+    with return_loss the mean logistic loss before each step and after the last."""
+    X, C, _ = _geom(X, C)
+    n, M = X.shape[0], C.shape[0]
+    y = np.asarray(y, dtype=np.float64).reshape(n)
+    yC = np.asarray(yC, dtype=np.float64).reshape(M)
+    alpha = np.zeros(M)
+    losses = []
+    Kmm = kernel_matrix(C, C, sigma)
+    for mu, t in zip(lambdas, iters):
+        z = knm_v(X, C, sigma, alpha)
+        zc = Kmm @ alpha
+        loss, g, dw = logistic_terms(z, y)
+        losses.append(float(loss.mean()))
+        _, _, dm = logistic_terms(zc, yC)
+        T, A = precond_weighted(C, sigma, mu, jitter, dm)
+        rhs = -(knm_t_w(X, C, sigma, g) + mu * n * (zc + jitter * alpha))
+        r = solve_upper(A, solve_upper(T, rhs, trans=True), trans=True)
+        beta = np.zeros(M)
+        p = r.copy()
+        rho = float(r @ r)
+        for _ in range(int(t)):                      # Hestenes-Stiefel, from zero, t steps
+            q = linop_weighted(X, C, sigma, mu, T, A, dw, p)
+            pq = float(p @ q)
+            a = rho / pq if pq != 0.0 else 0.0
+            beta += a * p
+            r -= a * q
+            rho_new = float(r @ r)
+            p = r + (rho_new / rho if rho != 0.0 else 0.0) * p
+            rho = rho_new
+        alpha = alpha + solve_upper(T, solve_upper(A, beta))
+    loss, _, _ = logistic_terms(knm_v(X, C, sigma, alpha), y)
+    losses.append(float(loss.mean()))
+    return (alpha, np.array(losses)) if return_loss else alpha

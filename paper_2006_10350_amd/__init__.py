@@ -46,8 +46,12 @@ SIGNATURES = {
     "precond_free": (_int, [_vp]),
     "precond_get_factors": (_int, [_vp, _vp, _vp, _vp]),
     "falkon_linop": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _int, _vp]),
+    "falkon_linop_weighted": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _vp, _int, _vp]),
+    "precond_reweight": (_int, [_vp, _vp, _f64, _vp, ctypes.POINTER(_i64)]),
     "falkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _int, _vp, _i64, _i64, _f32, _f64, _f64, _int,
                           _vp, _vp]),
+    "logfalkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _vp, _i64, _i64, _vp, _f32, _vp, _vp, _int, _f64,
+                             _vp, _vp]),
     "knm_get_fit_timing": (_int, [_vp, ctypes.POINTER(_f64)]),
     "falkon_predict": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
     "knm_set_cross_term": (_int, [_vp, _int]),
@@ -247,6 +251,20 @@ class Preconditioner:
         self.ctx.check(load_library().precond_get_factors(self.ctx._h, self._h, T.ctypes.data, A.ctypes.data))
         return T, A
 
+    def reweight(self, lam: float, dw=None):
+        """Rebuild A = chol(T diag(dw) T^T / M + lam I) in place (dw: float64 GPU tensor, M)."""
+        ptr = None
+        if dw is not None:
+            if not (dw.is_cuda and dw.dtype == torch.float64 and dw.numel() == self.M):
+                raise TypeError("dw must be a float64 GPU tensor with M entries")
+            dw = dw.contiguous()
+            ptr = dw.data_ptr()
+        bad = _i64(0)
+        st = load_library().precond_reweight(self.ctx._h, self._h, float(lam), ptr, ctypes.byref(bad))
+        self.bad_pivot = bad.value
+        if st != KNM_OK:
+            raise KnmError(st, load_library().knm_last_error(self.ctx._h).decode() + f" (pivot {bad.value})")
+
     def close(self):
         if getattr(self, "_h", None):
             load_library().precond_free(self._h)
@@ -263,8 +281,9 @@ def precond_build(C, sigma: float, lam: float, jitter: float = 0.0, ctx: Optiona
     return Preconditioner(C, sigma, lam, jitter, ctx)
 
 
-def falkon_linop(precond: Preconditioner, X, C, sigma: float, lam: float, beta) -> torch.Tensor:
-    """Preconditioned operator of Eq. 9 applied to beta (float64, M x t)."""
+def falkon_linop(precond: Preconditioner, X, C, sigma: float, lam: float, beta, dw=None) -> torch.Tensor:
+    """Preconditioned operator of Eq. 9 applied to beta (float64, M x t); with dw (float32, n) the
+    weighted operator of Alg. 2."""
     ctx = precond.ctx
     X, n, d, ldx, C, M, ldc = _geom(X, C)
     if not (beta.is_cuda and beta.dtype == torch.float64):
@@ -273,8 +292,14 @@ def falkon_linop(precond: Preconditioner, X, C, sigma: float, lam: float, beta) 
     b2 = beta.reshape(M, -1).contiguous()
     t = b2.shape[1]
     out = torch.empty_like(b2)
-    ctx.check(load_library().falkon_linop(ctx._h, precond._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc,
-                                          float(sigma), float(lam), b2.data_ptr(), t, out.data_ptr()))
+    if dw is None:
+        ctx.check(load_library().falkon_linop(ctx._h, precond._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc,
+                                              float(sigma), float(lam), b2.data_ptr(), t, out.data_ptr()))
+    else:
+        dw, _, _ = _cols(dw, n, "dw")
+        ctx.check(load_library().falkon_linop_weighted(ctx._h, precond._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M,
+                                                       ldc, float(sigma), float(lam), dw.data_ptr(), b2.data_ptr(),
+                                                       t, out.data_ptr()))
     return out[:, 0] if sq else out
 
 
@@ -294,6 +319,28 @@ def falkon_fit(X, Y, C, sigma: float, lam: float, iters: int, jitter: float = 0.
     if sq:
         alpha, resid = alpha[:, 0], resid[:, 0]
     return (alpha, resid) if return_resid else alpha
+
+
+def logfalkon_fit(X, y, C, yC, sigma: float, lambdas, iters, jitter: float = 0.0, return_loss: bool = False,
+                  ctx: Optional[Context] = None):
+    """alpha (M) after the approximate Newton steps of Alg. 2 for the logistic loss; step k uses
+    lambdas[k] and iters[k] CG iterations."""
+    import numpy as np
+
+    ctx = ctx or default_context()
+    X, n, d, ldx, C, M, ldc = _geom(X, C)
+    y, _, _ = _cols(y, n, "y")
+    yC, _, _ = _cols(yC, M, "yC")
+    lam = np.ascontiguousarray(lambdas, dtype=np.float64)
+    its = np.ascontiguousarray(iters, dtype=np.int32)
+    if lam.ndim != 1 or lam.shape != its.shape or lam.size == 0:
+        raise ValueError("lambdas and iters must be equally long, non-empty sequences")
+    alpha = torch.empty(M, device=X.device, dtype=torch.float32)
+    loss = np.zeros(lam.size + 1, dtype=np.float64)
+    ctx.check(load_library().logfalkon_fit(ctx._h, X.data_ptr(), n, d, ldx, y.data_ptr(), C.data_ptr(), M, ldc,
+                                           yC.data_ptr(), float(sigma), lam.ctypes.data, its.ctypes.data,
+                                           int(lam.size), float(jitter), alpha.data_ptr(), loss.ctypes.data))
+    return (alpha, loss) if return_loss else alpha
 
 
 def falkon_predict(Xtest, C, sigma: float, alpha, ctx: Optional[Context] = None) -> torch.Tensor:

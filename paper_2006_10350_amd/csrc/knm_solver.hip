@@ -207,6 +207,52 @@ int blas_handle(knm_ctx *ctx, rocblas_handle *h)
     return KNM_OK;
 }
 
+// dst (rows x width, leading dimension rows) <- src (leading dimension ld) with column j scaled
+// by sqrt(w[j])
+__global__ void scale_cols_kernel(const double *__restrict__ src, int64_t ld, int64_t rows, int64_t width,
+                                  const double *__restrict__ w, double *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t j = blockIdx.y;
+    if (i >= rows || j >= width) return;
+    dst[i + j * rows] = src[i + j * ld] * sqrt(w[j]);
+}
+
+// Logistic loss l(z, y) = log(1 + exp(-y z)), y = +-1 (Appendix "Logistic Falkon Algorithm",
+// Example 1a), evaluated in fp64 from fp32 predictions: first derivative g, second derivative
+// dw (as float for the sweeps and/or as double for the preconditioner), loss.  Any output may
+// be null.
+__global__ void logistic_terms_kernel(const float *__restrict__ z, const float *__restrict__ y, int64_t n,
+                                      float *__restrict__ g, float *__restrict__ dw32, double *__restrict__ dw64,
+                                      double *__restrict__ loss)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const double yi = (double)y[i];
+    const double m = yi * (double)z[i];
+    const double s = 0.5 * (1.0 - tanh(0.5 * m)); // sigma(-m), stable for either sign
+    if (g) g[i] = (float)(-yi * s);
+    if (dw32) dw32[i] = (float)(s * (1.0 - s));
+    if (dw64) dw64[i] = s * (1.0 - s);
+    if (loss) loss[i] = (m > 0.0) ? log1p(exp(-m)) : -m + log1p(exp(m));
+}
+
+// r[j] = -(u[j] + c (zc[j] + eps a[j]))   (right-hand side of a Newton step, fp64)
+__global__ void newton_rhs_kernel(const float *__restrict__ u, const float *__restrict__ zc,
+                                  const double *__restrict__ a, double c, double eps, int64_t M,
+                                  double *__restrict__ r)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= M) return;
+    r[j] = -((double)u[j] + c * ((double)zc[j] + eps * a[j]));
+}
+
+__global__ void f64_to_f32_kernel(const double *__restrict__ a, int64_t n, float *__restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = (float)a[i];
+}
+
 struct DevBuf {
     void *p = nullptr;
     ~DevBuf() { if (p) (void)hipFree(p); }
@@ -273,10 +319,11 @@ struct LinopWork {
     }
 };
 
-// out <- A^-T ( T^-T K^T K T^-1 A^-1 beta + lambda n A^-1 beta );  beta, out column-major, may not alias
+// out <- A^-T ( T^-T K^T D K T^-1 A^-1 beta + lambda n A^-1 beta );  beta, out column-major, may not alias;
+// D = diag(wgt) over the rows of X, identity if wgt is null
 int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &wk, const float *X, int64_t n, int d,
                int64_t ldx, const float *C, int64_t M, int64_t ldc, float sigma, double lambda, const double *beta,
-               int t, double *out)
+               int t, double *out, const float *wgt = nullptr)
 {
     const size_t bytes = sizeof(double) * M * t;
     double *v = wk.v.as<double>();
@@ -294,7 +341,7 @@ int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &
     if (st) return st;
     st = do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, wk.z32.as<float>(), t, ctx->w_buf);
     if (st) return st;
-    st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, ctx->w_buf, nullptr, t, wk.u32.as<float>());
+    st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, ctx->w_buf, wgt, t, wk.u32.as<float>());
     if (st) return st;
     hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(M * t), dim3(256), 0, ctx->stream, wk.u32.as<float>(), M, t, out);
     st = tri_solve(ctx, h, p->T, p->Tdinv, M, true, out, t); // T^-T c
@@ -335,7 +382,7 @@ int precond_free(knm_precond *p)
 // near the fp64 matrix peak at this width).  rocSOLVER's own blocking is much narrower and
 // reaches about half that rate on these sizes.  `info` holds one status word per block row
 // (filled asynchronously); first_bad receives the 1-based index of the first failing pivot, or 0.
-int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t M, int64_t *info_dev, int64_t info_len,
+static int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t M, int64_t *info_dev, int64_t info_len,
                        int64_t *first_bad)
 {
     int64_t b = ((M + 7) / 8 + 255) / 256 * 256;
@@ -373,8 +420,78 @@ int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t M, int
     return KNM_OK;
 }
 
-int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma, double lambda,
-                  double jitter, knm_precond **out, int64_t *bad_pivot_or_null)
+// A <- upper Cholesky factor of T D T^T / M + lambda I, D = diag(dw) (identity if dw is null), and
+// the inverses of its diagonal blocks.  T is upper triangular, so block column k of T (width b)
+// only reaches the leading (k + 1) b rows: T D T^T is the sum over k of rank-b updates of
+// growing leading blocks, M^3 / 3 flop instead of the M^3 of one dense rank-M update.  The
+// last block column touches the whole triangle, so it goes first and overwrites (beta = 0);
+// the others accumulate.  With weights each block column is first copied, scaled by sqrt(dw).
+static int build_second_factor(knm_ctx *ctx, rocblas_handle h, knm_precond *p, double lambda, const double *dw,
+                               int64_t *bad_pivot)
+{
+    const int64_t M = p->M;
+    *bad_pivot = 0;
+    int64_t b = ((M + 7) / 8 + 255) / 256 * 256;
+    if (b > 4096) b = 4096;
+    const int64_t nblk_cols = (M + b - 1) / b;
+    DevBuf panel, info, badbuf;
+    const int64_t info_len = 64;
+    int st = info.alloc(ctx, sizeof(int64_t) * info_len);
+    if (!st) st = badbuf.alloc(ctx, sizeof(unsigned long long));
+    if (!st && dw) st = panel.alloc(ctx, sizeof(double) * (size_t)M * (size_t)b);
+    if (st) return st;
+    const double alpha = 1.0 / (double)M;
+    for (int64_t k = nblk_cols - 1; k >= 0; --k) {
+        const int64_t rows = ((k + 1) * b < M) ? (k + 1) * b : M;
+        const int64_t width = ((k + 1) * b <= M) ? b : M - k * b;
+        const double beta = (k == nblk_cols - 1) ? 0.0 : 1.0;
+        const double *src = p->T + (size_t)k * b * M;
+        int64_t ld = M;
+        if (dw) {
+            const dim3 g((unsigned)((rows + 255) / 256), (unsigned)width);
+            hipLaunchKernelGGL(scale_cols_kernel, g, dim3(256), 0, ctx->stream, src, M, rows, width, dw + k * b,
+                               panel.as<double>());
+            src = panel.as<double>();
+            ld = rows;
+        }
+        if (rocblas_dsyrk_64(h, rocblas_fill_upper, rocblas_operation_none, rows, width, &alpha, src, ld, &beta,
+                             p->A, M) != rocblas_status_success)
+            return fail(ctx, KNM_HIP_ERROR, "rocblas_dsyrk");
+    }
+    const dim3 fb(32, 8);
+    const dim3 fg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
+    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, lambda, 0);
+    int64_t pivot = 0;
+    st = chol_upper_blocked(ctx, h, p->A, M, info.as<int64_t>(), info_len, &pivot);
+    if (st) return st;
+    if (pivot == 0) {
+        const unsigned long long none = ~0ull;
+        unsigned long long got = none;
+        hipError_t err = hipMemcpyAsync(badbuf.p, &none, sizeof(none), hipMemcpyHostToDevice, ctx->stream);
+        if (err == hipSuccess) {
+            hipLaunchKernelGGL(diag_check_kernel, grid1(M), dim3(256), 0, ctx->stream, p->A, M,
+                               badbuf.as<unsigned long long>());
+            err = hipMemcpyAsync(&got, badbuf.p, sizeof(got), hipMemcpyDeviceToHost, ctx->stream);
+        }
+        if (err == hipSuccess) err = hipStreamSynchronize(ctx->stream);
+        if (err != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "diagonal check", err);
+        pivot = (got == none) ? 0 : (int64_t)got;
+    }
+    if (pivot != 0) {
+        *bad_pivot = pivot;
+        return fail(ctx, KNM_NOT_PD, "T D T^T / M + lambda I is not positive definite");
+    }
+    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, 0.0, 1);
+    const int64_t nblk = (M + kSolveBlock - 1) / kSolveBlock;
+    hipLaunchKernelGGL(invert_diag_blocks_kernel, dim3((unsigned)nblk), dim3(kSolveBlock), 0, ctx->stream, p->A, M,
+                       p->Adinv);
+    if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "preconditioner kernel launch");
+    p->lambda = lambda;
+    return KNM_OK;
+}
+
+static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma, double lambda,
+                              double jitter, bool second_factor, knm_precond **out, int64_t *bad_pivot_or_null)
 {
     if (!ctx) return KNM_INVALID_ARG;
     if (!out) return fail(ctx, KNM_INVALID_ARG, "null output");
@@ -455,47 +572,26 @@ int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, f
     const dim3 fg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->T, M, 0.0, 1);
 
-    // A <- T T^T / M (upper triangle), then + lambda I, then factorise.  T is upper triangular,
-    // so block column k of T (width b) only reaches the leading (k + 1) b rows: T T^T is the sum
-    // over k of rank-b updates of growing leading blocks, M^3 / 3 flop instead of the M^3 of one
-    // dense rank-M update.  The last block column touches the whole triangle, so it goes first
-    // and overwrites (beta = 0); the others accumulate.
-    {
-        int64_t b = ((M + 7) / 8 + 255) / 256 * 256;
-        if (b > 4096) b = 4096;
-        const int64_t nblk_cols = (M + b - 1) / b;
-        const double alpha = 1.0 / (double)M;
-        for (int64_t k = nblk_cols - 1; k >= 0; --k) {
-            const int64_t rows = ((k + 1) * b < M) ? (k + 1) * b : M;
-            const int64_t width = ((k + 1) * b <= M) ? b : M - k * b;
-            const double beta = (k == nblk_cols - 1) ? 0.0 : 1.0;
-            if (rocblas_dsyrk_64(h, rocblas_fill_upper, rocblas_operation_none, rows, width, &alpha,
-                                 p->T + (size_t)k * b * M, M, &beta, p->A, M) != rocblas_status_success)
-                return bail(KNM_HIP_ERROR, "rocblas_dsyrk");
-        }
-    }
-    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, lambda, 0);
-    {
-        int st2 = chol_upper_blocked(ctx, h, p->A, M, info.as<int64_t>(), info_len, &host_info);
-        if (st2) {
-            precond_free(p);
-            return st2;
-        }
-    }
-    pivot = host_info;
-    if (pivot == 0 && bad_diagonal(p->A, &pivot) != hipSuccess) return bail(KNM_HIP_ERROR, "diagonal check");
-    if (pivot != 0) {
-        if (bad_pivot_or_null) *bad_pivot_or_null = -pivot;
-        return bail(KNM_NOT_PD, "T T^T / M + lambda I is not positive definite");
-    }
-    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, 0.0, 1);
     hipLaunchKernelGGL(invert_diag_blocks_kernel, dim3((unsigned)nblk), dim3(kSolveBlock), 0, ctx->stream, p->T, M,
                        p->Tdinv);
-    hipLaunchKernelGGL(invert_diag_blocks_kernel, dim3((unsigned)nblk), dim3(kSolveBlock), 0, ctx->stream, p->A, M,
-                       p->Adinv);
     if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "preconditioner kernel launch");
+    if (second_factor) {
+        int64_t bad = 0;
+        st = build_second_factor(ctx, h, p, lambda, nullptr, &bad);
+        if (st) {
+            if (bad_pivot_or_null) *bad_pivot_or_null = -bad;
+            precond_free(p);
+            return st;
+        }
+    }
     *out = p;
     return KNM_OK;
+}
+
+int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma, double lambda,
+                  double jitter, knm_precond **out, int64_t *bad_pivot_or_null)
+{
+    return precond_build_impl(ctx, C, M, d, ldc, sigma, lambda, jitter, true, out, bad_pivot_or_null);
 }
 
 int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, double *A_host)
@@ -517,8 +613,9 @@ int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, doub
     return KNM_OK;
 }
 
-int falkon_linop(knm_ctx *ctx, const knm_precond *p, const float *X, int64_t n, int d, int64_t ldx, const float *C,
-                 int64_t M, int64_t ldc, float sigma, double lambda, const double *beta, int t, double *out)
+int falkon_linop_weighted(knm_ctx *ctx, const knm_precond *p, const float *X, int64_t n, int d, int64_t ldx,
+                          const float *C, int64_t M, int64_t ldc, float sigma, double lambda, const float *dw_or_null,
+                          const double *beta, int t, double *out)
 {
     if (!ctx) return KNM_INVALID_ARG;
     if (!p || !X || !C || !beta || !out || n <= 0 || M <= 0 || d <= 0 || t <= 0 || ldx < d || ldc < d ||
@@ -536,12 +633,34 @@ int falkon_linop(knm_ctx *ctx, const knm_precond *p, const float *X, int64_t n, 
     if (!st) st = oc.alloc(ctx, sizeof(double) * M * t);
     if (st) return st;
     hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, beta, M, t, bc.as<double>(), 0);
-    st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, bc.as<double>(), t, oc.as<double>());
+    st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, bc.as<double>(), t, oc.as<double>(),
+                    dw_or_null);
     if (st) return st;
     hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, oc.as<double>(), M, t, out, 1);
     hipError_t e = hipStreamSynchronize(ctx->stream); // temporaries are freed on return
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "falkon_linop", e);
     return KNM_OK;
+}
+
+int falkon_linop(knm_ctx *ctx, const knm_precond *p, const float *X, int64_t n, int d, int64_t ldx, const float *C,
+                 int64_t M, int64_t ldc, float sigma, double lambda, const double *beta, int t, double *out)
+{
+    return falkon_linop_weighted(ctx, p, X, n, d, ldx, C, M, ldc, sigma, lambda, nullptr, beta, t, out);
+}
+
+int precond_reweight(knm_ctx *ctx, knm_precond *p, double lambda, const double *dw_or_null, int64_t *bad_pivot_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (bad_pivot_or_null) *bad_pivot_or_null = 0;
+    if (!p || !(lambda >= 0.0)) return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    rocblas_handle h;
+    int st = blas_handle(ctx, &h);
+    if (st) return st;
+    int64_t bad = 0;
+    st = build_second_factor(ctx, h, p, lambda, dw_or_null, &bad);
+    if (bad_pivot_or_null) *bad_pivot_or_null = -bad;
+    return st;
 }
 
 int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *Y, int t, const float *C,
@@ -649,6 +768,135 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
                    int64_t ldc, float sigma, const float *alpha, int t, float *out)
 {
     return knm_v(ctx, Xtest, ntest, d, ldx, C, M, ldc, sigma, alpha, t, out);
+}
+
+int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *y, const float *C, int64_t M,
+                  int64_t ldc, const float *yC, float sigma, const double *lambdas, const int *iters, int n_steps,
+                  double jitter, float *alpha, double *loss_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!X || !y || !C || !yC || !alpha || !lambdas || !iters || n <= 0 || M <= 0 || d <= 0 || n_steps <= 0 ||
+        ldx < d || ldc < d || !(sigma > 0.0f) || !(jitter >= 0.0))
+        return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
+    for (int k = 0; k < n_steps; ++k)
+        if (!(lambdas[k] >= 0.0) || iters[k] <= 0) return fail(ctx, KNM_INVALID_ARG, "bad Newton schedule");
+    if (d > knm_max_d()) return fail(ctx, KNM_UNSUPPORTED, "d above compiled maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    rocblas_handle h;
+    int st = blas_handle(ctx, &h);
+    if (st) return st;
+
+    // T depends on the centres only: built once; A is rebuilt per Newton step
+    knm_precond *p = nullptr;
+    st = precond_build_impl(ctx, C, M, d, ldc, sigma, lambdas[0], jitter, false, &p, nullptr);
+    if (st) return st;
+    struct Guard {
+        knm_precond *p;
+        ~Guard() { precond_free(p); }
+    } guard{p};
+
+    LinopWork wk;
+    DevBuf a64, a32, z, zc, g, dw, dm, lossv, u32, beta, r, pv, q;
+    st = wk.alloc(ctx, M, 1);
+    if (!st) st = a64.alloc(ctx, sizeof(double) * M);
+    if (!st) st = a32.alloc(ctx, sizeof(float) * M);
+    if (!st) st = z.alloc(ctx, sizeof(float) * n);
+    if (!st) st = zc.alloc(ctx, sizeof(float) * M);
+    if (!st) st = g.alloc(ctx, sizeof(float) * n);
+    if (!st) st = dw.alloc(ctx, sizeof(float) * n);
+    if (!st) st = dm.alloc(ctx, sizeof(double) * M);
+    if (!st && loss_or_null) st = lossv.alloc(ctx, sizeof(double) * n);
+    if (!st) st = u32.alloc(ctx, sizeof(float) * M);
+    if (!st) st = beta.alloc(ctx, sizeof(double) * M);
+    if (!st) st = r.alloc(ctx, sizeof(double) * M);
+    if (!st) st = pv.alloc(ctx, sizeof(double) * M);
+    if (!st) st = q.alloc(ctx, sizeof(double) * M);
+    if (st) return st;
+    double *da = a64.as<double>(), *db = beta.as<double>(), *dr = r.as<double>(), *dp = pv.as<double>(),
+           *dq = q.as<double>();
+    hipError_t e = hipMemsetAsync(da, 0, sizeof(double) * M, ctx->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(a32.p, 0, sizeof(float) * M, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+    auto blas_ok = [&](rocblas_status s) { return s == rocblas_status_success; };
+    // predictions at the rows and at the centres for the current alpha, and the loss terms
+    auto evaluate = [&](bool derivatives, double *mean_loss) -> int {
+        int s2 = do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, a32.as<float>(), 1, z.as<float>());
+        if (s2) return s2;
+        hipLaunchKernelGGL(logistic_terms_kernel, grid1(n), dim3(256), 0, ctx->stream, z.as<float>(), y, n,
+                           derivatives ? g.as<float>() : nullptr, derivatives ? dw.as<float>() : nullptr,
+                           (double *)nullptr, mean_loss ? lossv.as<double>() : nullptr);
+        if (mean_loss) {
+            // sum in pieces that fit the 32-bit BLAS interface
+            double total = 0.0;
+            for (int64_t o = 0; o < n; o += (1 << 30)) {
+                const int64_t len = (n - o < (1 << 30)) ? n - o : (1 << 30);
+                double part = 0.0;
+                if (!blas_ok(rocblas_dasum(h, (rocblas_int)len, lossv.as<double>() + o, 1, &part)))
+                    return fail(ctx, KNM_HIP_ERROR, "rocblas_dasum");
+                total += part;
+            }
+            *mean_loss = total / (double)n;
+        }
+        return KNM_OK;
+    };
+
+    for (int k = 0; k < n_steps; ++k) {
+        const double mu = lambdas[k];
+        st = evaluate(true, loss_or_null ? loss_or_null + k : nullptr);
+        if (st) return st;
+        // weights at the centres -> second factor of the preconditioner for this step
+        st = do_knm_v(ctx, C, M, d, ldc, C, M, ldc, sigma, a32.as<float>(), 1, zc.as<float>());
+        if (st) return st;
+        hipLaunchKernelGGL(logistic_terms_kernel, grid1(M), dim3(256), 0, ctx->stream, zc.as<float>(), yC, M,
+                           (float *)nullptr, (float *)nullptr, dm.as<double>(), (double *)nullptr);
+        int64_t bad = 0;
+        st = build_second_factor(ctx, h, p, mu, dm.as<double>(), &bad);
+        if (st) return st;
+        // right-hand side  -P^T (K^T g + mu n (K_MM + eps I) alpha)
+        st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, g.as<float>(), nullptr, 1, u32.as<float>());
+        if (st) return st;
+        hipLaunchKernelGGL(newton_rhs_kernel, grid1(M), dim3(256), 0, ctx->stream, u32.as<float>(), zc.as<float>(), da,
+                           mu * (double)n, jitter, M, dr);
+        st = tri_solve(ctx, h, p->T, p->Tdinv, M, true, dr, 1);
+        if (!st) st = tri_solve(ctx, h, p->A, p->Adinv, M, true, dr, 1);
+        if (st) return st;
+        e = hipMemsetAsync(db, 0, sizeof(double) * M, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(dp, dr, sizeof(double) * M, hipMemcpyDeviceToDevice, ctx->stream);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "CG initialisation", e);
+        double rho = 0.0;
+        if (!blas_ok(rocblas_ddot(h, (rocblas_int)M, dr, 1, dr, 1, &rho))) return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
+        for (int it = 0; it < iters[k]; ++it) {
+            st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, mu, dp, 1, dq, dw.as<float>());
+            if (st) return st;
+            double pq = 0.0, rn = 0.0;
+            if (!blas_ok(rocblas_ddot(h, (rocblas_int)M, dp, 1, dq, 1, &pq))) return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
+            const double a = (pq != 0.0) ? rho / pq : 0.0, ma = -a, one = 1.0;
+            if (!blas_ok(rocblas_daxpy(h, (rocblas_int)M, &a, dp, 1, db, 1)) ||
+                !blas_ok(rocblas_daxpy(h, (rocblas_int)M, &ma, dq, 1, dr, 1)) ||
+                !blas_ok(rocblas_ddot(h, (rocblas_int)M, dr, 1, dr, 1, &rn)))
+                return fail(ctx, KNM_HIP_ERROR, "rocblas CG update");
+            const double b = (rho != 0.0) ? rn / rho : 0.0;
+            if (!blas_ok(rocblas_dscal(h, (rocblas_int)M, &b, dp, 1)) ||
+                !blas_ok(rocblas_daxpy(h, (rocblas_int)M, &one, dr, 1, dp, 1)))
+                return fail(ctx, KNM_HIP_ERROR, "rocblas CG update");
+            rho = rn;
+        }
+        // alpha += T^-1 A^-1 beta
+        st = tri_solve(ctx, h, p->A, p->Adinv, M, false, db, 1);
+        if (!st) st = tri_solve(ctx, h, p->T, p->Tdinv, M, false, db, 1);
+        if (st) return st;
+        const double one = 1.0;
+        if (!blas_ok(rocblas_daxpy(h, (rocblas_int)M, &one, db, 1, da, 1))) return fail(ctx, KNM_HIP_ERROR, "rocblas_daxpy");
+        hipLaunchKernelGGL(f64_to_f32_kernel, grid1(M), dim3(256), 0, ctx->stream, da, M, a32.as<float>());
+    }
+    if (loss_or_null) {
+        st = evaluate(false, loss_or_null + n_steps);
+        if (st) return st;
+    }
+    e = hipMemcpyAsync(alpha, a32.p, sizeof(float) * M, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream); // temporaries are freed on return
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "logfalkon_fit", e);
+    return KNM_OK;
 }
 
 } // extern "C"
