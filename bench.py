@@ -73,6 +73,36 @@ def fit_benchmark(w, args) -> int:
     ctx = knm.default_context()
     ctx.set_cross_term(args.cross)
     iters = args.iters or w.iters
+    if args.loss == "logistic":
+        # Newton schedule: regularisers decreasing by 10x per step to the workload's lambda, then
+        # repeated; `iters` CG iterations per step (the paper leaves the schedule to its reference)
+        if w.t != 1:
+            print("bench.py: the logistic loss needs a binary (t = 1) workload", file=sys.stderr)
+            return 2
+        y = torch.where(Y[:, 0] >= Y[:, 0].median(), 1.0, -1.0).contiguous()
+        yC = y[inp["centre_rows"]].contiguous()
+        steps = args.newton_steps
+        lambdas = [max(w.lam, w.lam * 10.0 ** (steps - 2 - k)) for k in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        alpha, loss = knm.logfalkon_fit(X, y, C, yC, w.sigma, lambdas, [iters] * steps, args.jitter, return_loss=True,
+                                        ctx=ctx)
+        torch.cuda.synchronize()
+        total = time.perf_counter() - t0
+        print(json.dumps({
+            "metric": "s per Newton step (logfalkon_fit)",
+            "value": total / steps,
+            "unit": "s",
+            "higher_is_better": False,
+            "n_gpus": 1,
+            "config": {"workload": w.name, "n": w.n, "d": w.d, "M": w.M, "sigma": w.sigma, "lambdas": lambdas,
+                       "cg_iters_per_step": iters, "newton_steps": steps, "jitter": args.jitter},
+            "cross_term": args.cross,
+            "fit_total_s": total,
+            "mean_loss": [float(v) for v in loss],
+            "alpha_finite": bool(torch.isfinite(alpha).all()),
+        }))
+        return 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     alpha, resid = knm.falkon_fit(X, Y, C, w.sigma, w.lam, iters, args.jitter, return_resid=True, ctx=ctx)
@@ -115,6 +145,10 @@ def main() -> int:
                     help="instead of the product benchmark, run falkon_fit end to end on the workload and "
                          "report seconds per conjugate-gradient iteration")
     ap.add_argument("--iters", type=int, default=None, help="CG iterations for --fit (default: the workload's)")
+    ap.add_argument("--loss", default="squared", choices=["squared", "logistic"],
+                    help="--fit: squared loss (falkon_fit) or logistic loss (logfalkon_fit, labels = sign of the "
+                         "targets about their median)")
+    ap.add_argument("--newton-steps", type=int, default=4, help="Newton steps for --fit --loss logistic")
     ap.add_argument("--jitter", type=float, default=1e-8, help="diagonal jitter on K_MM for --fit")
     ap.add_argument("--no-fp32-leg", action="store_true",
                     help="skip the extra (untimed-region) product in the fp32-MFMA cross-term mode")
