@@ -209,10 +209,11 @@ def main() -> int:
     entries = float(w.n) * float(w.M)
     value = entries / (elapsed / args.steps) / 1e9
 
-    # Which tile engine ran (same rule as the library): K-loop fp32-MFMA engine for d > 64 or t > 1
-    # (up to 16 columns per launch); otherwise the register-resident engine, with the cross term as
-    # three split-fp16 MFMA products (d <= 44, default) or as fp32 MFMA.  Two sweeps per step.
-    k_loop = w.d > 64 or w.t > 1
+    # Which tile engine ran (same rule as the library): the K-loop engine for t > 1 (up to 16 columns
+    # per launch) or d beyond the register-resident engine's limit (44 features with the split-fp16
+    # cross term, the default; 64 with fp32 MFMA); otherwise the register-resident engine.  Two sweeps
+    # per step.
+    k_loop = w.t > 1 or w.d > (44 if args.cross == "f16x3" else 64)
     f16 = (not k_loop) and args.cross == "f16x3" and w.d <= 44
     k_loop_f16 = k_loop and args.cross == "f16x3"
     kernel_name = (("gauss_gemm_f16_kernel" if k_loop_f16 else "gauss_gemm_kernel") if k_loop

@@ -164,8 +164,7 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
  *                   relative L2 against the fp64 oracle).  Scaled features beyond 65000 in
  *                   magnitude and squared norms of scaled points beyond 2^22 saturate.  Uses a
  *                   library-owned workspace for the converted operands: at most 2 GiB for
- *                   d <= 44 with t = 1, at most 8 GiB otherwise.  Shapes with 44 < d <= 64 and
- *                   t = 1 run in fp32 in either mode.
+ *                   d <= 44 with t = 1, at most 8 GiB otherwise.
  *   KNM_CROSS_F32   fp32 MFMA on the unsplit features: no range limits, 3 to 5 times slower
  *                   (fp32 MFMA and the exp/FMA work share the vector ALU's issue). */
 typedef enum { KNM_CROSS_F32 = 0, KNM_CROSS_F16X3 = 1 } knm_cross_term;

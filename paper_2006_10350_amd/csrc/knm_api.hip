@@ -39,14 +39,19 @@ int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need)
     return KNM_OK;
 }
 
-bool use_gemm_engine(int d, int t) { return d > small_max_d() || t > 1; }
+// K-loop engine for several columns or for d beyond what the register-resident engine of the
+// selected arithmetic holds (44 features for the split-fp16 one, 64 for fp32)
+bool use_gemm_engine(int d, int t, int cross_term)
+{
+    return t > 1 || d > (cross_term == KNM_CROSS_F16X3 ? f16_max_d() : small_max_d());
+}
 
 // Chunking of the stream dimension.  More chunks = more workgroups (needed when there
 // are few fixed blocks) and shorter fp32 running sums; each chunk costs one partial
 // vector that the merge pass adds up in fp64.
-int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int64_t *chunk_len)
+int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int cross_term, int64_t *chunk_len)
 {
-    const bool gemm = use_gemm_engine(d, t);
+    const bool gemm = use_gemm_engine(d, t, cross_term);
     const int64_t stage = gemm ? gemm_stage_points() : stage_points();
     const int64_t per_block = gemm ? gemm_fixed_per_block() : fixed_per_block(d);
     const int64_t blocks = (nF + per_block - 1) / per_block;
@@ -78,7 +83,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
                  int d, float sigma, const float *vec, const float *wgt, int t, float *out, hipEvent_t after_sweep)
 {
     int64_t chunk_len = 0;
-    const int64_t chunks = choose_chunks(nF, nS, d, t, &chunk_len);
+    const int64_t chunks = choose_chunks(nF, nS, d, t, ctx->cross_term, &chunk_len);
     if (chunks > 65535) return fail(ctx, KNM_UNSUPPORTED, "too many stream chunks");
     float *part = nullptr;
     if (chunks > 1) {
@@ -86,7 +91,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         if (st) return st;
         part = ctx->part_buf;
     }
-    const bool gemm = use_gemm_engine(d, t);
+    const bool gemm = use_gemm_engine(d, t, ctx->cross_term);
     const int group = gemm ? gemm_max_t() : 1; // columns per launch
     for (int c = 0; c < t; c += group) {
         SweepArgs a;
@@ -237,11 +242,17 @@ size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
     if (n <= 0 || M <= 0 || d <= 0 || t <= 0) return 0;
     int64_t len = 0;
     size_t bytes = sizeof(float) * (size_t)n * t; // W
-    const int64_t c1 = choose_chunks(n, M, d, t, &len);
-    const int64_t c2 = choose_chunks(M, n, d, t, &len);
-    size_t p1 = c1 > 1 ? sizeof(float) * (size_t)c1 * n * t : 0;
-    size_t p2 = c2 > 1 ? sizeof(float) * (size_t)c2 * M * t : 0;
-    return bytes + (p1 > p2 ? p1 : p2);
+    // the larger of the two arithmetic modes' needs (they may cut the stream differently)
+    size_t part = 0;
+    for (int mode = 0; mode < 2; ++mode) {
+        const int64_t c1 = choose_chunks(n, M, d, t, mode, &len);
+        const int64_t c2 = choose_chunks(M, n, d, t, mode, &len);
+        const size_t p1 = c1 > 1 ? sizeof(float) * (size_t)c1 * n * t : 0;
+        const size_t p2 = c2 > 1 ? sizeof(float) * (size_t)c2 * M * t : 0;
+        if (p1 > part) part = p1;
+        if (p2 > part) part = p2;
+    }
+    return bytes + part;
 }
 
 static int check_common(knm_ctx *ctx, const void *X, int64_t n, int d, int64_t ldx, const void *C, int64_t M,

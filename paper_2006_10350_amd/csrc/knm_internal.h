@@ -87,9 +87,9 @@ namespace knm {
 int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need);
 int fail(knm_ctx *ctx, int status, const char *what, hipError_t e = hipSuccess);
 // true if (d, t) runs on the K-loop engine, false for the register-resident one
-bool use_gemm_engine(int d, int t);
+bool use_gemm_engine(int d, int t, int cross_term);
 // number of stream chunks for a sweep over nS stream points against nF fixed points
-int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int64_t *chunk_len);
+int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int cross_term, int64_t *chunk_len);
 int do_knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
              int64_t ldc, float sigma, const float *V, int t, float *W);
 int do_knm_t_w(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
