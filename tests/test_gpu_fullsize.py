@@ -68,3 +68,37 @@ def test_full_size_sampled_outputs(knm, name, n_rows, n_cols):
     assert abs(uv - ww) <= 1e-4 * float(U.double().norm() * v.double().norm())
     U2 = knm.knm_t_y(X, C, w.sigma, W)
     assert torch.equal(U2, U)
+
+
+def test_more_than_2_pow_31_elements(knm):
+    """64-bit indexing end to end: n d = 2.34e9 > 2^31 elements of X (billion-shaped rows, n = 260M).
+    Rows of W at both ends of the array against the oracle; K^T W of the last rows against the
+    oracle; and the whole product as the sum of the products of two row ranges (linearity)."""
+    w = synth.workload("billion", n=260_000_000)
+    assert w.n * w.d > 2 ** 31
+    print(f"workload billion-shaped: n={w.n} d={w.d} M={w.M}", flush=True)
+    inp = synth.make_inputs(w, device="cuda", with_targets=False)
+    X, C = inp["X"], inp["C"]
+    v = synth.probe_vector(w.M, 1, "normal", device="cuda")
+    U, W = knm.knm_prod(X, C, w.sigma, v, return_w=True)
+    torch.cuda.synchronize()
+    print("gpu product done", flush=True)
+    Cn, vn = C.cpu().numpy(), v.cpu().numpy()
+    g = np.random.default_rng(11)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256], w.n - 1 - np.arange(300), g.integers(0, w.n, 200)]))
+    ridx = torch.from_numpy(rows).cuda()
+    Wo = oracle.knm_v(X[ridx].cpu().numpy(), Cn, w.sigma, vn)
+    assert rel_l2(W[ridx].cpu().numpy(), Wo) < 1e-4
+    print("row samples ok", flush=True)
+
+    tail = 1_000_000
+    Xt, Wt = X[w.n - tail:], W[w.n - tail:]
+    Ut = knm.knm_t_y(Xt, C, w.sigma, Wt)
+    cols = np.array([0, 31, 32, 4097, w.M - 1])
+    Uo = oracle.knm_t_y(Xt.cpu().numpy(), Cn[cols], w.sigma, Wt.cpu().numpy())
+    assert rel_l2(Ut[torch.from_numpy(cols).cuda()].cpu().numpy(), Uo) < 1e-4
+    Uh = knm.knm_t_y(X[: w.n - tail], C, w.sigma, W[: w.n - tail])
+    assert rel_l2((Uh.double() + Ut.double()).cpu().numpy(), U.double().cpu().numpy()) < 1e-5
+    uv = float((U.double() * v.double()).sum())
+    ww = float((W.double() ** 2).sum())
+    assert abs(uv - ww) <= 1e-4 * float(U.double().norm() * v.double().norm())
