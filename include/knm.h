@@ -170,6 +170,13 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
 typedef enum { KNM_CROSS_F32 = 0, KNM_CROSS_F16X3 = 1 } knm_cross_term;
 int knm_set_cross_term(knm_ctx *ctx, int mode);
 
+/* Cap, in bytes, on the library-owned workspace that holds the converted operands of the
+ * split-fp16 engines (0 restores the defaults: 2 GiB, or 8 GiB for the K-loop engine).  Operands
+ * that do not fit are converted and swept slab by slab; results do not depend on the cap.  The
+ * workspace never shrinks below what one slab needs (one stream chunk, plus the whole smaller
+ * operand for the K-loop engine). */
+int knm_set_pack_limit(knm_ctx *ctx, size_t bytes);
+
 /* Timing aid for benchmarks: when enabled, knm_v / knm_prod / knm_t_y bracket their
  * kernels with HIP events on the context's stream.  knm_get_timing synchronises the
  * stream and writes milliseconds of the most recent call to the HOST array ms[4]:

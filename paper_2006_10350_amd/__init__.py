@@ -55,6 +55,7 @@ SIGNATURES = {
     "knm_get_fit_timing": (_int, [_vp, ctypes.POINTER(_f64)]),
     "falkon_predict": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
     "knm_set_cross_term": (_int, [_vp, _int]),
+    "knm_set_pack_limit": (_int, [_vp, ctypes.c_size_t]),
     "knm_set_timing": (_int, [_vp, _int]),
     "knm_get_timing": (_int, [_vp, ctypes.POINTER(_f32)]),
 }
@@ -142,6 +143,10 @@ class Context:
         """'f16x3' (split-fp16 products on the f16 matrix cores, default) or 'f32' (fp32 MFMA)."""
         code = {"f32": 0, "f16x3": 1}[mode] if isinstance(mode, str) else int(mode)
         self.check(load_library().knm_set_cross_term(self._h, code))
+
+    def set_pack_limit(self, nbytes: int):
+        """Cap on the workspace of the split-fp16 engines' converted operands (0: defaults)."""
+        self.check(load_library().knm_set_pack_limit(self._h, int(nbytes)))
 
     def get_fit_timing(self):
         sec = (_f64 * 4)()

@@ -115,24 +115,24 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
             const size_t per_point = gemm_f16_pack_bytes_per_point(d);
             const int64_t nFp = (nF + gemm_fixed_per_block() - 1) / gemm_fixed_per_block() * gemm_fixed_per_block();
             size_t want = per_point * (size_t)(nFp + chunks * chunk_len);
-            const size_t cap = (size_t)8 << 30;
+            const size_t cap = ctx->pack_limit ? ctx->pack_limit : (size_t)8 << 30;
             const size_t least = gemm_f16_min_pack_bytes(nF, chunks * chunk_len, chunk_len, d);
             if (want > cap) want = cap;
             if (want < least) want = least;
             int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
             if (st) return st;
-            e = launch_sweep_gemm_f16(a, ctx->pack_buf, ctx->pack_bytes, ctx->stream);
+            e = launch_sweep_gemm_f16(a, ctx->pack_buf, want, ctx->stream);
         } else if (gemm) {
             e = launch_sweep_gemm(a, ctx->stream);
         } else if (f16) {
             // packed image of the stream points: all of it, or slabs of at most 2 GiB
             const size_t per_point = f16_pack_bytes_per_point(d);
             size_t want = per_point * (size_t)(chunks * chunk_len);
-            const size_t cap = (size_t)2 << 30;
+            const size_t cap = ctx->pack_limit ? ctx->pack_limit : (size_t)2 << 30;
             if (want > cap) want = (cap / (per_point * chunk_len) + 1) * per_point * chunk_len;
             int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
             if (st) return st;
-            e = launch_sweep_f16(a, ctx->pack_buf, ctx->pack_bytes, ctx->stream);
+            e = launch_sweep_f16(a, ctx->pack_buf, want, ctx->stream);
         } else {
             e = launch_sweep(a, ctx->stream);
         }
@@ -334,6 +334,13 @@ int knm_set_cross_term(knm_ctx *ctx, int mode)
     if (!ctx) return KNM_INVALID_ARG;
     if (mode != KNM_CROSS_F32 && mode != KNM_CROSS_F16X3) return fail(ctx, KNM_INVALID_ARG, "unknown cross-term mode");
     ctx->cross_term = mode;
+    return KNM_OK;
+}
+
+int knm_set_pack_limit(knm_ctx *ctx, size_t bytes)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    ctx->pack_limit = bytes;
     return KNM_OK;
 }
 

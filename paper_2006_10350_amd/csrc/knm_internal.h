@@ -72,6 +72,7 @@ struct knm_ctx {
     size_t part_bytes = 0;
     float *pack_buf = nullptr; // packed operand images of the split-fp16 engines
     size_t pack_bytes = 0;
+    size_t pack_limit = 0;     // cap on the image workspace chosen by the caller; 0 = engine defaults
     int cross_term = KNM_CROSS_F16X3;
     // timing
     bool timing = false;

@@ -173,6 +173,25 @@ def test_split_half_range_limits(knm):
         ctx.set_cross_term("f16x3")
 
 
+@pytest.mark.parametrize("d,t,limit", [(28, 1, 300 << 10), (9, 1, 200 << 10), (130, 1, 4 << 20), (16, 5, 1 << 20)])
+def test_results_do_not_depend_on_the_pack_workspace_cap(knm, d, t, limit):
+    """With a small cap the split-fp16 engines convert and sweep their operands slab by slab (the
+    path the billion-row workload takes); the results must be the same bit for bit."""
+    n, M, sigma = 20000, 3000, 3.0
+    X, C, V = _rand(n, d, 60).cuda(), _rand(M, d, 61).cuda(), _rand(M, t, 62).cuda()
+    ctx = knm.default_context()
+    ctx.set_cross_term("f16x3")
+    U0, W0 = knm.knm_prod(X, C, sigma, V, return_w=True)
+    try:
+        ctx.set_pack_limit(limit)
+        U1, W1 = knm.knm_prod(X, C, sigma, V, return_w=True)
+    finally:
+        ctx.set_pack_limit(0)
+    assert torch.equal(W0, W1) and torch.equal(U0, U1)
+    ref = oracle.knm_prod(X[:3000].cpu().numpy(), C.cpu().numpy(), sigma, V.cpu().numpy())
+    assert rel_l2(knm.knm_prod(X[:3000], C, sigma, V).cpu().numpy(), ref) < TIGHT
+
+
 def test_invalid_arguments_are_rejected(knm):
     X, C, V = _rand(10, 4, 20).cuda(), _rand(5, 4, 21).cuda(), _rand(5, 1, 22).cuda()
     with pytest.raises(knm.KnmError) as e:
