@@ -116,6 +116,20 @@ def test_strided_points_and_determinism(knm, cross):
     assert rel_l2(U1.cpu().numpy(), ref) < TIGHT
 
 
+@pytest.mark.parametrize("d,t", [(10, 3), (70, 1), (52, 1)])
+def test_strided_unaligned_points_on_the_k_loop_engine(knm, cross, d, t):
+    # leading dimensions larger than d and base pointers that are only 4-byte aligned: the
+    # scalar-load paths of the packing and staging code
+    n, M, sigma = 900, 333, 3.0
+    Xw = _rand(n, d + 7, 41).cuda()
+    Cw = _rand(M * (d + 3) + 1, 1, 42).cuda().reshape(-1)[1:].reshape(M, d + 3)
+    X, C = Xw[:, 1:d + 1], Cw[:, :d]
+    V = _rand(M, t, 43).cuda()
+    U = knm.knm_prod(X, C, sigma, V)
+    ref = oracle.knm_prod(X.cpu().numpy(), C.cpu().numpy(), sigma, V.cpu().numpy())
+    assert rel_l2(U.cpu().numpy(), ref) < TIGHT
+
+
 def test_degenerate_sizes(knm, cross):
     sigma = 1.0
     X, C = _rand(1, 3, 14), _rand(1, 3, 15)
