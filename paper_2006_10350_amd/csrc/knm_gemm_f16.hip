@@ -184,7 +184,7 @@ struct PatchMap {
 
 // Fimg: image of the fixed points [fixed_row0, fixed_row0 + 256 n_fblocks);
 // Simg: image of the stream chunks [chunk0, chunk0 + n_chunks).
-// TP: number of vector columns, padded to a multiple of 4.
+// TP: number of vector columns, padded to a multiple of 2.
 template <int TP>
 __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
                                                                      const f16x8 *__restrict__ Simg,
@@ -327,14 +327,15 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                 const int j = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
                 float vr[TP];
 #pragma unroll
-                for (int c4 = 0; c4 < TP; c4 += 4) {
-                    const f32x4 u = *reinterpret_cast<const f32x4 *>(&vimg[j * TP + c4]);
-                    vr[c4] = u[0]; vr[c4 + 1] = u[1]; vr[c4 + 2] = u[2]; vr[c4 + 3] = u[3];
+                for (int c2 = 0; c2 < TP; c2 += 2) {
+                    const f32x2 u = *reinterpret_cast<const f32x2 *>(&vimg[j * TP + c2]);
+                    vr[c2] = u[0]; vr[c2 + 1] = u[1];
                 }
 #pragma unroll
                 for (int fb = 0; fb < 2; ++fb) {
-                    // exponent <= 0 up to rounding; med3 keeps the kernel value in [0, 1]
-                    const float p = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(acc[fb][sb][r]), 0.0f, 1.0f);
+                    // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
+                    float p;
+                    asm("v_exp_f32_e64 %0, %1 clamp" : "=v"(p) : "v"(acc[fb][sb][r]));
 #pragma unroll
                     for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[c], sum[fb][c]);
                 }
@@ -434,10 +435,16 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
                 if (e != hipSuccess) return e;
             }
             const int64_t fb = f_rows / kFixed;
-            if (a.t <= 4) launch_tp<4>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream);
-            else if (a.t <= 8) launch_tp<8>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream);
-            else if (a.t <= 12) launch_tp<12>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream);
-            else launch_tp<16>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream);
+            switch ((a.t + 1) / 2) {
+            case 1: launch_tp<2>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            case 2: launch_tp<4>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            case 3: launch_tp<6>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            case 4: launch_tp<8>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            case 5: launch_tp<10>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            case 6: launch_tp<12>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            case 7: launch_tp<14>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            default: launch_tp<16>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            }
             e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
