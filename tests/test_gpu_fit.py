@@ -134,6 +134,30 @@ def test_multi_output_fit(knm):
         assert rel_l2(pred[:, c], po[:, c]) < 1e-3
 
 
+@pytest.mark.parametrize("name,n,M,iters,sigma", [("mid", 60000, 1500, 8, None), ("highdim", 8000, 600, 5, 8.0),
+                                                  ("lowdim", 60000, 1500, 8, None)])
+def test_workload_shaped_fit(knm, name, n, M, iters, sigma):
+    """End-to-end fit on reduced copies of the benchmark workloads (their distributions, number of
+    outputs; every tile engine), predictions against the oracle.  The image-like workload runs with
+    sigma = 8 here: at its own sigma = 24 every kernel value lies within 8 % of 1, K_MM is close to
+    a rank-one matrix and fp32 products limit the predictions to 2e-3 (measured, the same with the
+    fp32-MFMA cross term): the single-precision limit the paper discusses, not a property of a kernel."""
+    w = synth.workload(name, n=n, M=M)
+    if sigma is not None:
+        w = w._replace(sigma=sigma) if hasattr(w, "_replace") else __import__("dataclasses").replace(w, sigma=sigma)
+    inp = synth.make_inputs(w, device="cpu", n_test=1000)
+    X, Y, C, Xt = inp["X"], inp["Y"], inp["C"], inp["Xtest"]
+    lam, jitter = 1e-6, 1e-7
+    alpha, resid = knm.falkon_fit(X.cuda(), Y.cuda(), C.cuda(), w.sigma, lam, iters, jitter, return_resid=True)
+    ao, ro = oracle.falkon_fit(X.numpy(), Y.numpy(), C.numpy(), w.sigma, lam, iters, jitter, return_resid=True)
+    pred = knm.falkon_predict(Xt.cuda(), C.cuda(), w.sigma, alpha).cpu().numpy()
+    po = oracle.falkon_predict(Xt.numpy(), C.numpy(), w.sigma, ao)
+    err = rel_l2(pred, po)
+    print(f"\n  {name}-shaped fit (n={n}, M={M}, d={w.d}, t={w.t}): prediction error {err:.2e}", flush=True)
+    assert err < 1e-3
+    assert np.all(np.isfinite(resid)) and np.all(np.asarray(resid)[-1] < np.asarray(resid)[0])
+
+
 def test_all_points_as_centres_reaches_exact_krr(knm):
     # M = n, C = X: the preconditioned operator is n I, one CG step gives (K + n lam I)^-1 y
     # (moderately conditioned K, as above: the fp32 products are amplified by T^-1)
