@@ -319,27 +319,34 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         }
         ++stage;
 
-        // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block
-#pragma unroll
-        for (int sb = 0; sb < 4; ++sb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
+        // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block; the
+        // vector row of the next register is read from LDS while this one is used
+        {
+            float vr[2][TP];
+            auto load_row = [&](float (&dst)[TP], int it) {
+                const int sb = it >> 4, r = it & 15;
                 const int j = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                float vr[TP];
 #pragma unroll
                 for (int c2 = 0; c2 < TP; c2 += 2) {
                     const f32x2 u = *reinterpret_cast<const f32x2 *>(&vimg[j * TP + c2]);
-                    vr[c2] = u[0]; vr[c2 + 1] = u[1];
+                    dst[c2] = u[0]; dst[c2 + 1] = u[1];
                 }
+            };
+            load_row(vr[0], 0);
+#pragma unroll
+            for (int it = 0; it < 64; ++it) {
+                const int cur = it & 1;
+                if (it + 1 < 64) load_row(vr[cur ^ 1], it + 1);
 #pragma unroll
                 for (int fb = 0; fb < 2; ++fb) {
                     // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
                     float p;
-                    asm("v_exp_f32_e64 %0, %1 clamp" : "=v"(p) : "v"(acc[fb][sb][r]));
+                    asm("v_exp_f32_e64 %0, %1 clamp" : "=v"(p) : "v"(acc[fb][it >> 4][it & 15]));
 #pragma unroll
-                    for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[c], sum[fb][c]);
+                    for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[cur][c], sum[fb][c]);
                 }
             }
+        }
     }
 
     // the two half-waves hold different stream rows of the same fixed point
