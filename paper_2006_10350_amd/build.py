@@ -25,6 +25,9 @@ EXTRA = {
     # keep MFMA accumulators in architectural VGPRs so the VALU reads them without copies
     "knm_tile.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "knm_tile_f16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    # its builtin MFMAs (the reduction against the vectors) accumulate in VGPRs; the AGPRs are
+    # taken by the inline-assembly accumulators of the cross term
+    "knm_gemm_f16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

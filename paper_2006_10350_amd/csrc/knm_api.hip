@@ -92,7 +92,8 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         part = ctx->part_buf;
     }
     const bool gemm = use_gemm_engine(d, t, ctx->cross_term);
-    const int group = gemm ? gemm_max_t() : 1; // columns per launch
+    // columns per launch
+    const int group = !gemm ? 1 : (ctx->cross_term == KNM_CROSS_F16X3 ? gemm_f16_max_t() : gemm_max_t());
     for (int c = 0; c < t; c += group) {
         SweepArgs a;
         a.F = F; a.nF = nF; a.ldf = ldf;
@@ -114,7 +115,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
             // whole and the other in slabs
             const size_t per_point = gemm_f16_pack_bytes_per_point(d);
             const int64_t nFp = (nF + gemm_fixed_per_block() - 1) / gemm_fixed_per_block() * gemm_fixed_per_block();
-            size_t want = per_point * (size_t)(nFp + chunks * chunk_len);
+            size_t want = 256 + per_point * (size_t)(nFp + chunks * chunk_len); // head + both images
             const size_t cap = ctx->pack_limit ? ctx->pack_limit : (size_t)8 << 30;
             const size_t least = gemm_f16_min_pack_bytes(nF, chunks * chunk_len, chunk_len, d);
             if (want > cap) want = cap;

@@ -27,6 +27,18 @@
 // points, each wavefront 64 fixed x 128 stream = 8 accumulators of 32x32 pinned to AGPRs;
 // the stream block is the A operand, so a lane's accumulator registers run over stream
 // points of one fixed point and the reduction against the vector columns is in-lane.
+//
+// Reduction against the vectors.  For a few columns each kernel value is multiplied into
+// per-lane running sums on the vector ALU (one FMA per column).  For more columns (see the
+// launcher for the rule) the
+// reduction  out[f, c] += sum_s P[s, f] V[s, c]  is itself run on the matrix cores: a lane's
+// 16 kernel values of a 32x32 tile are, without any data movement, the B operand of two
+// K = 16 MFMAs whose K-slots are stream points; the kernel values (in [0, 1]) are split into
+// two halves like the features, the vector rows are scaled per column by a power of two
+// into the fp16 range, split likewise and staged in LDS in A-operand layout, and three
+// products P_hi V_hi + P_lo V_hi + P_hi V_lo accumulate a 32-column x 32-point output tile in
+// fp32.  That replaces t FMAs per kernel value by about three conversion instructions and
+// serves up to 32 columns per launch.
 
 #include <type_traits>
 
@@ -40,6 +52,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __fp16 f16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kFixed = 256;                    // fixed points per workgroup
@@ -169,6 +182,43 @@ __device__ __forceinline__ void mfma_acc(f32x16 &acc, const f16x8 &a, const f16x
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
+// exp2 of an accumulator element with the clamp modifier (kernel value in [0, 1]).  Volatile and
+// reading the accumulation register itself: the compiler does not look inside inline assembly,
+// so it must neither move this read up towards the MFMA that produces the element (it knows
+// nothing of that instruction's latency) nor be relied on for the wait state a transcendental
+// result needs before its first use.
+__device__ __forceinline__ float exp2_clamped(const float &x)
+{
+    float p;
+    asm volatile("v_accvgpr_read_b32 %0, %1\n\tv_exp_f32_e64 %0, %0 clamp\n\ts_nop 0" : "=v"(p) : "a"(x));
+    return p;
+}
+
+// Wait states between the last MFMA written in inline assembly and the first read of its result
+// by other instructions (the compiler cannot insert them for instructions it does not see).
+__device__ __forceinline__ void mfma_results_ready()
+{
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory");
+}
+
+// The second contraction uses the compiler's MFMA builtin, not inline assembly: its operands are
+// rewritten by vector-ALU instructions every few cycles and its result is read by ordinary
+// code, and only for an instruction it knows can the compiler keep the required distances.
+__device__ __forceinline__ void mfma_accv(f32x16 &acc, const f16x8 &a, const f16x8 &b)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+}
+
+// Power of two that brings a column with largest magnitude `bits` (a float's bit pattern) into
+// [2^13, 2^14), or its inverse; 1 for an all-zero (or denormal) column.
+__device__ __forceinline__ float column_scale(uint32_t bits, bool inverse)
+{
+    const int e = (int)((bits >> 23) & 255u);
+    if (e == 0 || e == 255) return 1.0f;
+    const int shift = 13 - (e - 127);
+    return ldexpf(1.0f, inverse ? -shift : shift);
+}
+
 // Workgroup -> (fixed block, stream chunk).  Workgroups are dealt round-robin to the 8 XCDs
 // (each with its own L2) in launch order, and the ones resident together on an XCD are
 // consecutive in that order.  They are therefore numbered so that each XCD works through
@@ -184,12 +234,13 @@ struct PatchMap {
 
 // Fimg: image of the fixed points [fixed_row0, fixed_row0 + 256 n_fblocks);
 // Simg: image of the stream chunks [chunk0, chunk0 + n_chunks).
-// TP: number of vector columns, padded to a multiple of 2.
-template <int TP>
+// TP: number of vector columns, padded to a multiple of 2 (vector-ALU reduction).  MV: reduce
+// on the matrix cores instead (up to 32 columns; TP unused); colmax[c] = bits of max |vec[:, c]|.
+template <int TP, bool MV>
 __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
                                                                      const f16x8 *__restrict__ Simg,
                                                                      int64_t fixed_row0, int64_t chunk0, int n_kc,
-                                                                     PatchMap pm)
+                                                                     PatchMap pm, const uint32_t *__restrict__ colmax)
 {
     const int per_patch = pm.pf * pm.pc;
     const int64_t slot = (int64_t)blockIdx.x >> 3;
@@ -200,7 +251,11 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     if (fblk >= pm.n_fblocks || cblk >= pm.n_chunks) return; // whole workgroup, before any barrier
 
     __shared__ f16x8 img[2][kBlocks * kUnits]; // 2 x 24 KB
-    __shared__ __attribute__((aligned(16))) float vimg[kStream * TP];
+    // vector rows of a tile: fp32 [stream point][column], or for MV split halves in A-operand
+    // layout [stream block][K-step][plane hi/lo][lane]
+    constexpr int kVecUnits = MV ? 4 * 2 * 2 * 64 : (kStream * TP * 4 + 15) / 16;
+    __shared__ f16x8 vstore[kVecUnits];
+    float *const vimg = reinterpret_cast<float *>(vstore);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -220,7 +275,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     // loads 0..3 cover the 8 fixed blocks, loads 4..5 the 4 stream blocks of a tile.  All
     // per-load and per-stage offsets are uniform, the thread's own offset fits 32 bits.
     const int64_t blk_units = (int64_t)n_st * kUnits;
-    const int toff = (tid >> 7) * (int)blk_units + (tid & (kUnits - 1));
+    const unsigned toff = (unsigned)((tid >> 7) * (int)blk_units + (tid & (kUnits - 1)));
     const f16x8 *const fbase = Fimg + fblk * (kFixed / 32) * blk_units;
     const f16x8 *const sbase = Simg + cblk * (a.chunk_len / 32) * blk_units;
 
@@ -229,15 +284,27 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
         for (int c = 0; c < TP; ++c) sum[fb][c] = 0.0f;
+    // MV: output tile [column][fixed point] of each fixed block, and this thread's column scale
+    f32x16 dacc[2];
+#pragma unroll
+    for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dacc[fb][r] = 0.0f;
+    float vscale = 1.0f;
+    if constexpr (MV) vscale = column_scale(colmax[lane & 31], false);
 
     f16x8 pre[kLoads];
     auto fetch = [&](int tile, int st) {
         const f16x8 *const fs = fbase + (int64_t)st * kUnits;
         const f16x8 *const ss = sbase + (int64_t)tile * (kStream / 32) * blk_units + (int64_t)st * kUnits;
+        // the offset is made opaque here so that the six 64-bit addresses are formed where they are
+        // used instead of being kept (and spilled) across the whole tile loop
+        unsigned o = toff;
+        asm volatile("" : "+v"(o));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pre[i] = (fs + 2 * i * blk_units)[toff];
+        for (int i = 0; i < 4; ++i) pre[i] = (fs + 2 * i * blk_units)[o];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) pre[4 + i] = (ss + 2 * i * blk_units)[toff];
+        for (int i = 0; i < 2; ++i) pre[4 + i] = (ss + 2 * i * blk_units)[o];
     };
     auto commit = [&](int buf) {
 #pragma unroll
@@ -294,14 +361,45 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         // the vectors of this tile are staged with it (every wavefront has passed this
         // tile's first barrier, so it is done with the previous tile's vectors)
         commit(stage & 1);
-        for (int k = tid; k < kStream * TP; k += kThreads) {
-            const int j = k / TP, c = k % TP;
-            const int64_t idx = stream0 + j;
-            const bool in = idx < chunk_end && c < t;
-            const int64_t vi = in ? idx : 0;
-            float v = a.vec[vi * a.ldv + (in ? c : 0)];
-            if (a.wgt != nullptr) v *= a.wgt[vi];
-            vimg[k] = in ? v : 0.0f;
+        if constexpr (MV) {
+            // combination id = tid + 256 i: stream block id / 128, K-step (id / 64) % 2, lane id % 64
+            // = (column c, half hh); slot e of that lane is stream row 8 (2 q + e / 4) + 4 hh + e % 4
+            const int c = lane & 31, hh = lane >> 5;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int id = tid + kThreads * i;
+                const int sb = id >> 7, q = (id >> 6) & 1;
+                f16x8 hi, lo;
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    float v2[2];
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        const int64_t idx = stream0 + sb * 32 + 8 * (2 * q + (e + k) / 4) + 4 * hh + (e + k) % 4;
+                        const bool in = idx < chunk_end && c < t;
+                        const int64_t vi = in ? idx : 0;
+                        float v = a.vec[vi * a.ldv + (in ? c : 0)];
+                        if (a.wgt != nullptr) v *= a.wgt[vi];
+                        v2[k] = in ? v * vscale : 0.0f;
+                    }
+                    f16x2 ph, pl;
+                    split_pair(v2[0], v2[1], ph, pl);
+                    hi[e] = (_Float16)ph[0]; hi[e + 1] = (_Float16)ph[1];
+                    lo[e] = (_Float16)pl[0]; lo[e + 1] = (_Float16)pl[1];
+                }
+                vstore[((sb * 2 + q) * 2 + 0) * 64 + lane] = hi;
+                vstore[((sb * 2 + q) * 2 + 1) * 64 + lane] = lo;
+            }
+        } else {
+            for (int k = tid; k < kStream * TP; k += kThreads) {
+                const int j = k / TP, c = k % TP;
+                const int64_t idx = stream0 + j;
+                const bool in = idx < chunk_end && c < t;
+                const int64_t vi = in ? idx : 0;
+                float v = a.vec[vi * a.ldv + (in ? c : 0)];
+                if (a.wgt != nullptr) v *= a.wgt[vi];
+                vimg[k] = in ? v : 0.0f;
+            }
         }
         __syncthreads();
         if (tile + 1 < n_tiles) fetch(tile + 1, 0);
@@ -319,9 +417,37 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         }
         ++stage;
 
-        // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block; the
-        // vector row of the next register is read from LDS while this one is used
-        {
+        // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block
+        mfma_results_ready();
+        if constexpr (MV) {
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const f16x8 vh = vstore[((sb * 2 + q) * 2 + 0) * 64 + lane];
+                    const f16x8 vl = vstore[((sb * 2 + q) * 2 + 1) * 64 + lane];
+#pragma unroll
+                    for (int fb = 0; fb < 2; ++fb) {
+                        // kernel values of registers 8 q .. 8 q + 7, split into halves: K-slot e of
+                        // this half-wave is the same stream row as in the vector image
+                        u32x4 ph, pl;
+#pragma unroll
+                        for (int e = 0; e < 8; e += 2) {
+                            const float p0 = exp2_clamped(acc[fb][sb][8 * q + e]);
+                            const float p1 = exp2_clamped(acc[fb][sb][8 * q + e + 1]);
+                            const f16x2 h2 = __builtin_amdgcn_cvt_pkrtz(p0, p1);
+                            const f16x2 l2 = __builtin_amdgcn_cvt_pkrtz(p0 - (float)h2[0], p1 - (float)h2[1]);
+                            ph[e / 2] = __builtin_bit_cast(uint32_t, h2);
+                            pl[e / 2] = __builtin_bit_cast(uint32_t, l2);
+                        }
+                        const f16x8 bh = __builtin_bit_cast(f16x8, ph), bl = __builtin_bit_cast(f16x8, pl);
+                        mfma_accv(dacc[fb], vh, bh);
+                        mfma_accv(dacc[fb], vh, bl);
+                        mfma_accv(dacc[fb], vl, bh);
+                    }
+                }
+        } else {
+            // the vector row of the next register is read from LDS while this one is used
             float vr[2][TP];
             auto load_row = [&](float (&dst)[TP], int it) {
                 const int sb = it >> 4, r = it & 15;
@@ -340,8 +466,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
 #pragma unroll
                 for (int fb = 0; fb < 2; ++fb) {
                     // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
-                    float p;
-                    asm("v_exp_f32_e64 %0, %1 clamp" : "=v"(p) : "v"(acc[fb][it >> 4][it & 15]));
+                    const float p = exp2_clamped(acc[fb][it >> 4][it & 15]);
 #pragma unroll
                     for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[cur][c], sum[fb][c]);
                 }
@@ -349,18 +474,47 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         }
     }
 
-    // the two half-waves hold different stream rows of the same fixed point
     float *out = a.out + chunk * a.chunk_stride;
+    mfma_results_ready();
+    if constexpr (MV) {
+        // register r of a lane: column 8 (r / 4) + 4 h + r % 4 of fixed point lane % 32; undo the scale
 #pragma unroll
-    for (int fb = 0; fb < 2; ++fb) {
-        const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
+        for (int fb = 0; fb < 2; ++fb) {
+            const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
 #pragma unroll
-        for (int c = 0; c < TP; ++c) {
-            float v = sum[fb][c];
-            v += __shfl_xor(v, 32);
-            if (h == 0 && idx < a.nF && c < t) out[idx * a.ldo + c] = v;
+            for (int r = 0; r < 16; ++r) {
+                const int c = 8 * (r / 4) + 4 * h + (r % 4);
+                if (idx < a.nF && c < t) out[idx * a.ldo + c] = dacc[fb][r] * column_scale(colmax[c], true);
+            }
+        }
+    } else {
+        // the two half-waves hold different stream rows of the same fixed point
+#pragma unroll
+        for (int fb = 0; fb < 2; ++fb) {
+            const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
+#pragma unroll
+            for (int c = 0; c < TP; ++c) {
+                float v = sum[fb][c];
+                v += __shfl_xor(v, 32);
+                if (h == 0 && idx < a.nF && c < t) out[idx * a.ldo + c] = v;
+            }
         }
     }
+}
+
+// bits of max_i |vec[i, c] wgt[i]| per column (non-negative floats order like their bit patterns)
+__global__ void col_absmax_kernel(const float *__restrict__ vec, int64_t ldv, const float *__restrict__ wgt, int64_t n,
+                                  int t, uint32_t *__restrict__ out)
+{
+    const int c = threadIdx.x & 31;
+    float m = 0.0f;
+    if (c < t)
+        for (int64_t i = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5); i < n; i += (int64_t)gridDim.x * 8) {
+            float v = vec[i * ldv + c];
+            if (wgt != nullptr) v *= wgt[i];
+            m = fmaxf(m, fabsf(v));
+        }
+    if (c < t && m > 0.0f) atomicMax(out + c, __float_as_uint(m));
 }
 
 hipError_t pack_points(const float *P, int64_t nP, int64_t ld, int d, float sigma, int64_t row0, int64_t rows,
@@ -378,9 +532,12 @@ hipError_t pack_points(const float *P, int64_t nP, int64_t ld, int d, float sigm
 constexpr int kPatch = 64;  // workgroups per patch = resident workgroups per XCD (32 CUs x 2)
 constexpr int kPatchF = 8;  // fixed blocks per patch (measured: 2..8 within 4 % of each other, 64 is 25 % slower)
 
-template <int TP>
+constexpr int kMvMinT = 8;    // columns from which the reduction against the vectors may run on the matrix cores
+constexpr size_t kHeadBytes = 256; // head of the workspace: per-column magnitude words for that path
+
+template <int TP, bool MV>
 void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t fixed_row0, int64_t f_blocks,
-               int64_t chunk0, int64_t chunks, int n_kc, hipStream_t stream)
+               int64_t chunk0, int64_t chunks, int n_kc, const uint32_t *colmax, hipStream_t stream)
 {
     PatchMap pm;
     pm.pf = kPatchF;
@@ -391,8 +548,8 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
     const int64_t n_patch_c = (chunks + pm.pc - 1) / pm.pc;
     const int64_t patches = (pm.n_patch_f * n_patch_c + 7) / 8 * 8;
     const dim3 grid((unsigned)(patches * kPatch));
-    hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP>), grid, dim3(kThreads), 0, stream, a, Fimg, Simg, fixed_row0, chunk0,
-                       n_kc, pm);
+    hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP, MV>), grid, dim3(kThreads), 0, stream, a, Fimg, Simg, fixed_row0,
+                       chunk0, n_kc, pm, colmax);
 }
 
 } // namespace
@@ -405,12 +562,14 @@ size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len,
 {
     const size_t pp = gemm_f16_pack_bytes_per_point(d);
     const size_t f = (size_t)((nF + kFixed - 1) / kFixed * kFixed) * pp, s = (size_t)nS_padded * pp;
-    return f <= s ? f + (size_t)chunk_len * pp : s + (size_t)kFixed * pp;
+    return kHeadBytes + (f <= s ? f + (size_t)chunk_len * pp : s + (size_t)kFixed * pp);
 }
+
+int gemm_f16_max_t() { return 32; }
 
 hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
-    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > 16) return hipErrorInvalidValue;
+    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > gemm_f16_max_t()) return hipErrorInvalidValue;
     if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
     const int n_kc = (a.d + kChunk - 1) / kChunk;
@@ -421,15 +580,30 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
     if (pack_bytes < gemm_f16_min_pack_bytes(a.nF, nSp, a.chunk_len, a.d)) return hipErrorInvalidValue;
 
     // slab sizes: the smaller operand is packed whole, the other in slabs that fill the rest
+    const size_t room = pack_bytes - kHeadBytes;
     int64_t f_slab = nFp, s_slab = a.n_chunks; // fixed rows / stream chunks per slab
-    if (bytesF + bytesS > pack_bytes) {
-        if (bytesF <= bytesS) s_slab = (int64_t)((pack_bytes - bytesF) / ((size_t)a.chunk_len * pp));
-        else f_slab = (int64_t)((pack_bytes - bytesS) / ((size_t)kFixed * pp)) * kFixed;
+    if (bytesF + bytesS > room) {
+        if (bytesF <= bytesS) s_slab = (int64_t)((room - bytesF) / ((size_t)a.chunk_len * pp));
+        else f_slab = (int64_t)((room - bytesS) / ((size_t)kFixed * pp)) * kFixed;
     }
     if (f_slab < kFixed || s_slab < 1) return hipErrorInvalidValue;
-    f16x8 *Fimg = static_cast<f16x8 *>(pack_buf);
+    uint32_t *colmax = static_cast<uint32_t *>(pack_buf);
+    f16x8 *Fimg = reinterpret_cast<f16x8 *>(static_cast<char *>(pack_buf) + kHeadBytes);
     const int64_t f_rows_max = f_slab < nFp ? f_slab : nFp;
     f16x8 *Simg = Fimg + (size_t)f_rows_max * pp / sizeof(f16x8);
+    // Matrix-core reduction when it pays: from kMvMinT columns on, unless the cross term is so long
+    // (large d) that the vector-ALU reduction hides behind it anyway.  Above 16 columns it is the
+    // only path.
+    const bool mv = a.t > 16 || (a.t >= kMvMinT && 4 * (3 + a.t) >= 3 * n_kc + 1);
+    if (mv) {
+        // largest magnitude of every vector column: the power-of-two scale into the fp16 range
+        hipError_t e = hipMemsetAsync(colmax, 0, kHeadBytes, stream);
+        if (e != hipSuccess) return e;
+        int64_t blocks = (a.nS + 7) / 8;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(col_absmax_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a.vec, a.ldv, a.wgt, a.nS,
+                           a.t, colmax);
+    }
 
     for (int64_t f0 = 0; f0 < nFp; f0 += f_slab) {
         const int64_t f_rows = (nFp - f0 < f_slab) ? nFp - f0 : f_slab;
@@ -442,15 +616,19 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
                 if (e != hipSuccess) return e;
             }
             const int64_t fb = f_rows / kFixed;
-            switch ((a.t + 1) / 2) {
-            case 1: launch_tp<2>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
-            case 2: launch_tp<4>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
-            case 3: launch_tp<6>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
-            case 4: launch_tp<8>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
-            case 5: launch_tp<10>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
-            case 6: launch_tp<12>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
-            case 7: launch_tp<14>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
-            default: launch_tp<16>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, stream); break;
+            if (mv) {
+                launch_tp<2, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+            } else {
+                switch ((a.t + 1) / 2) {
+                case 1: launch_tp<2, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
+                case 2: launch_tp<4, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
+                case 3: launch_tp<6, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
+                case 4: launch_tp<8, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
+                case 5: launch_tp<10, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
+                case 6: launch_tp<12, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
+                case 7: launch_tp<14, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
+                default: launch_tp<16, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
+                }
             }
             e = hipGetLastError();
             if (e != hipSuccess) return e;
