@@ -53,6 +53,23 @@ __device__ __forceinline__ void mfma_acc(f32x16 &acc, float a, float b)
     asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
+// exp2 of an accumulator element with the clamp modifier (kernel value in [0, 1]).  Volatile and
+// reading the accumulation register itself: the compiler does not look inside inline assembly,
+// so it must neither move this read up towards the MFMA that produces the element nor be
+// relied on for the wait state a transcendental result needs before its first use.
+__device__ __forceinline__ float exp2_clamped(const float &x)
+{
+    float p;
+    asm volatile("v_accvgpr_read_b32 %0, %1\n\tv_exp_f32_e64 %0, %0 clamp\n\ts_nop 0" : "=v"(p) : "a"(x));
+    return p;
+}
+
+// Wait states between the last MFMA written in inline assembly and the first read of its result.
+__device__ __forceinline__ void mfma_results_ready()
+{
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory");
+}
+
 // TP: number of vector columns, padded to a multiple of 4.  VW: 4 if rows can be read
 // with aligned 16-byte loads, else 1.
 template <int TP, int VW>
@@ -223,6 +240,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
         }
 
         // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block
+        mfma_results_ready();
 #pragma unroll
         for (int sb = 0; sb < 4; ++sb)
 #pragma unroll
@@ -236,8 +254,8 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
                 }
 #pragma unroll
                 for (int fb = 0; fb < 2; ++fb) {
-                    // exponent <= 0 up to rounding; med3 keeps the kernel value in [0, 1]
-                    const float p = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(acc[fb][sb][r]), 0.0f, 1.0f);
+                    // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
+                    const float p = exp2_clamped(acc[fb][sb][r]);
 #pragma unroll
                     for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[c], sum[fb][c]);
                 }
