@@ -381,8 +381,11 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
             vl_prev = vl[cur];
         }
     }
-    // the last tile's accumulators (tiles per stage is even, so they are in set B)
+    // the last tile's accumulators (tiles per stage is even, so they are in set B); the wait states
+    // an MFMA result needs before ordinary code may read it are explicit, because the compiler
+    // does not know that the inline assembly above contains MFMAs
     static_assert(kTilesPerStage % 2 == 0, "accumulator sets alternate per tile");
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+v"(accB[0]), "+v"(accB[1]));
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
