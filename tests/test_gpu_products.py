@@ -56,6 +56,10 @@ SHAPES = [
     (600, 300, 784, 10, 24.0),
     (257, 385, 99, 3, 7.0),
     (1000, 2100, 16, 17, 3.0),
+    # 8-32 columns: reduction against the vectors on the matrix cores; 40 = two launches
+    (700, 390, 20, 32, 3.0),
+    (500, 300, 6, 40, 1.5),
+    (2300, 700, 28, 9, 4.0),
 ]
 
 
@@ -94,9 +98,38 @@ def test_special_vectors(knm, cross, kind):
     assert rel_l2(U, oracle.knm_prod(X.numpy(), C.numpy(), sigma, v.numpy())) < TIGHT
 
 
-def test_weighted_product(knm, cross):
+def test_columns_of_very_different_scale(knm):
+    """Matrix-core reduction: every vector column is scaled by its own power of two into the fp16
+    range, so columns of magnitude 1e-6 and 1e5, an all-zero column and a column dominated by one
+    entry must each keep the product accuracy."""
+    n, M, d, t, sigma = 1500, 600, 12, 12, 2.0
+    X, C, V = _rand(n, d, 90), _rand(M, d, 91), _rand(M, t, 92)
+    V[:, 1] *= 1e-6
+    V[:, 2] *= 1e5
+    V[:, 3] = 0.0
+    V[17, 4] = 3.0e4           # one entry 1e4 times the rest of its column
+    V[:, 5] = 1.0
+    V[:, 6] *= 1e-30           # near the bottom of the fp32 range
+    knm.default_context().set_cross_term("f16x3")
+    W = knm.knm_v(X.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
+    Wo = oracle.knm_v(X.numpy(), C.numpy(), sigma, V.numpy())
+    assert np.array_equal(W[:, 3], np.zeros(n, dtype=np.float32))
+    for c in range(t):
+        if c != 3:
+            assert rel_l2(W[:, c], Wo[:, c]) < TOL, c
+    # the small entries of the outlier column are resolved relative to its largest entry
+    assert np.abs(W[:, 4] - Wo[:, 4]).max() < 1e-6 * 3.0e4
+    U = knm.knm_prod(X.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
+    Uo = oracle.knm_prod(X.numpy(), C.numpy(), sigma, V.numpy())
+    for c in range(t):
+        if c != 3:
+            assert rel_l2(U[:, c], Uo[:, c]) < TOL, c
+
+
+@pytest.mark.parametrize("t", [2, 9])
+def test_weighted_product(knm, cross, t):
     n, M, d, sigma = 2500, 300, 9, 2.0
-    X, C, V = _rand(n, d, 7), _rand(M, d, 8), _rand(M, 2, 9)
+    X, C, V = _rand(n, d, 7), _rand(M, d, 8), _rand(M, t, 9)
     dw = torch.rand(n, generator=torch.Generator().manual_seed(10)) + 0.05
     U = knm.knm_prod_weighted(X.cuda(), C.cuda(), sigma, dw.cuda(), V.cuda()).cpu().numpy()
     ref = oracle.knm_prod_weighted(X.numpy(), C.numpy(), sigma, dw.numpy(), V.numpy())
