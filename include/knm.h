@@ -100,6 +100,14 @@ int falkon_linop(knm_ctx *ctx, const knm_precond *p,
                  const float *C, int64_t M, int64_t ldc, float sigma, double lambda,
                  const double *beta, int t, double *out);
 
+/* The two triangular solves that take the preconditioned unknown to the coefficients (last
+ * step of Alg. 1, alpha = T^-1 A^-1 beta) or a right-hand side into the preconditioned system
+ * (its first step, A^-T T^-T r):
+ *   transpose == 0:  out = T^-1 A^-1 b        transpose != 0:  out = A^-T T^-T b
+ * b, out: M x t row-major fp64 DEVICE pointers, may alias; 1 <= t <= knm_max_t().  Solves on one
+ * preconditioner share its staging vector: issue them from one context at a time. */
+int precond_solve(knm_ctx *ctx, const knm_precond *p, int transpose, const double *b, int t, double *out);
+
 /* The same operator with the weighted product (LinOp of Alg. 2, WeightedFalkon):
  *   out = A^-T ( T^-T K_nm^T diag(dw) K_nm T^-1 A^-1 beta + lambda n A^-1 beta ),
  * dw[n] >= 0 fp32 DEVICE pointer, NULL for the identity. */

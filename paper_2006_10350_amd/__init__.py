@@ -48,6 +48,7 @@ SIGNATURES = {
     "falkon_linop": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _int, _vp]),
     "falkon_linop_weighted": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _vp, _int, _vp]),
     "precond_reweight": (_int, [_vp, _vp, _f64, _vp, ctypes.POINTER(_i64)]),
+    "precond_solve": (_int, [_vp, _vp, _int, _vp, _int, _vp]),
     "falkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _int, _vp, _i64, _i64, _f32, _f64, _f64, _int,
                           _vp, _vp]),
     "logfalkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _vp, _i64, _i64, _vp, _f32, _vp, _vp, _int, _f64,
@@ -269,6 +270,16 @@ class Preconditioner:
         self.bad_pivot = bad.value
         if st != KNM_OK:
             raise KnmError(st, load_library().knm_last_error(self.ctx._h).decode() + f" (pivot {bad.value})")
+
+    def solve(self, b, transpose: bool = False) -> torch.Tensor:
+        """T^-1 A^-1 b, or A^-T T^-T b with transpose (b: float64 GPU tensor, M or M x t)."""
+        if not (b.is_cuda and b.dtype == torch.float64 and b.shape[0] == self.M):
+            raise TypeError("b must be a float64 GPU tensor with M rows")
+        b2 = b.reshape(self.M, -1).contiguous()
+        out = torch.empty_like(b2)
+        self.ctx.check(load_library().precond_solve(self.ctx._h, self._h, int(bool(transpose)), b2.data_ptr(),
+                                                    b2.shape[1], out.data_ptr()))
+        return out.reshape(b.shape)
 
     def close(self):
         if getattr(self, "_h", None):

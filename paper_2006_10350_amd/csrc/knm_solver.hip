@@ -21,10 +21,13 @@ struct knm_precond {
     double lambda = 0.0, jitter = 0.0;
     double *T = nullptr; // column-major M x M, upper triangle valid, strict lower zero
     double *A = nullptr;
-    // inverses of the kSolveBlock x kSolveBlock diagonal blocks of T and A (column-major blocks,
-    // the last one padded with the identity), used by the blocked triangular solves
+    // inverses of the sb x sb diagonal blocks of T and A (column-major blocks, each mirrored onto
+    // its lower triangle, the last one padded with the identity), used by the blocked
+    // triangular solves; xw (M entries) stages the solved blocks
+    int sb = 0;
     double *Tdinv = nullptr;
     double *Adinv = nullptr;
+    double *xw = nullptr;
 };
 
 namespace {
@@ -98,96 +101,175 @@ __global__ void f64_rows_to_cols(const double *__restrict__ src, int64_t rows, i
 }
 
 // ---- blocked triangular solves -----------------------------------------------------------------
-// R (upper, column-major, leading dimension M) is cut into block columns of kSolveBlock.  A
-// solve walks the diagonal blocks in dependency order; each step is a small dense product
-// with the pre-inverted diagonal block followed by a bandwidth-bound panel update of the
-// remaining right-hand side, which streams the panel of R once with coalesced loads.  The
-// off-diagonal panels are ~all of the 8 M^2 / 2 bytes, so a solve runs at HBM speed instead
-// of at the latency of M dependent steps.
-constexpr int kSolveBlock = 256;
-
-// Inverse of every diagonal block: thread c of block k back-substitutes R_kk y = e_c.
-__global__ __launch_bounds__(kSolveBlock) void invert_diag_blocks_kernel(const double *__restrict__ R, int64_t M,
-                                                                        double *__restrict__ Dinv)
+// R (upper, column-major, leading dimension M) is cut into block columns of width sb.  A solve
+// walks the diagonal blocks in dependency order; each step multiplies a right-hand-side block
+// by the pre-inverted diagonal block and then updates the remaining right-hand side with the
+// off-diagonal panel, which is streamed once with coalesced loads.  The panels are ~all of
+// the 8 M^2 / 2 bytes of the factor, so a solve is bound by HBM bandwidth; wide blocks keep the
+// chain of dependent launches short (M / sb steps) and every launch large enough to fill the
+// chip.
+//
+// Each inverted diagonal block is stored mirrored: S[i, j] = S[j, i] = inv(R_kk)[min, max].  Both
+// the plain and the transposed product then read contiguous pieces of the columns of S.
+inline int solve_block_width(int64_t M)
 {
-    const int64_t k0 = (int64_t)blockIdx.x * kSolveBlock;
-    const int nb = (int)((M - k0 < kSolveBlock) ? M - k0 : kSolveBlock);
-    const int c = threadIdx.x;
-    double *y = Dinv + (int64_t)blockIdx.x * kSolveBlock * kSolveBlock + (int64_t)c * kSolveBlock; // column c
-    for (int i = 0; i < kSolveBlock; ++i) y[i] = (i == c && c >= nb) ? 1.0 : 0.0; // identity padding
-    if (c >= nb) return;
-    const double *U = R + k0 + k0 * M;
-    y[c] = 1.0 / U[c + (int64_t)c * M];
-    for (int i = c - 1; i >= 0; --i) {
-        double s = 0.0;
-        for (int j = i + 1; j <= c; ++j) s += U[i + (int64_t)j * M] * y[j];
-        y[i] = -s / U[i + (int64_t)i * M];
-    }
+    int64_t b = ((M + 15) / 16 + 255) / 256 * 256;
+    if (b > 2048) b = 2048;
+    return (int)b;
 }
 
-// x_k = op(Dinv_k) b_k in place (one workgroup; op = transpose for the transposed solve)
-__global__ __launch_bounds__(kSolveBlock) void diag_apply_kernel(const double *__restrict__ Dinv, int trans,
-                                                                double *__restrict__ b, int nb)
+// every sb x sb block of S <- identity
+__global__ void identity_blocks_kernel(double *__restrict__ S, int sb, int64_t total)
 {
-    __shared__ double bs[kSolveBlock];
-    const int i = threadIdx.x;
-    bs[i] = (i < nb) ? b[i] : 0.0;
-    __syncthreads();
-    double s = 0.0;
-    if (!trans) {
-        for (int j = 0; j < kSolveBlock; ++j) s += Dinv[i + j * kSolveBlock] * bs[j];
-    } else {
-        const double *col = Dinv + (int64_t)i * kSolveBlock; // row i of the transpose
-        for (int j = 0; j < kSolveBlock; ++j) s += col[j] * bs[j];
-    }
-    if (i < nb) b[i] = s;
-}
-
-// b[0:k0] -= R[0:k0, k0:k0+nb] x   (x = b[k0:k0+nb] already solved): one thread per row
-__global__ __launch_bounds__(256) void panel_update_n_kernel(const double *__restrict__ R, int64_t M, int64_t k0,
-                                                            int nb, double *__restrict__ b)
-{
-    __shared__ double xs[kSolveBlock];
-    for (int j = threadIdx.x; j < kSolveBlock; j += blockDim.x) xs[j] = (j < nb) ? b[k0 + j] : 0.0;
-    __syncthreads();
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= k0) return;
-    const double *p = R + i + k0 * M;
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    int j = 0;
-    for (; j + 4 <= nb; j += 4) {
-        s0 += p[(int64_t)(j + 0) * M] * xs[j + 0];
-        s1 += p[(int64_t)(j + 1) * M] * xs[j + 1];
-        s2 += p[(int64_t)(j + 2) * M] * xs[j + 2];
-        s3 += p[(int64_t)(j + 3) * M] * xs[j + 3];
-    }
-    for (; j < nb; ++j) s0 += p[(int64_t)j * M] * xs[j];
-    b[i] -= (s0 + s1) + (s2 + s3);
+    if (i >= total) return;
+    const int64_t in_block = i % ((int64_t)sb * sb);
+    S[i] = (in_block % sb == in_block / sb) ? 1.0 : 0.0;
 }
 
-// b[j] -= sum_i R[k0 + i, j] x[i] for j in [j0, M)   (x = b[k0:k0+nb]): one wavefront per column
-__global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__restrict__ R, int64_t M, int64_t k0,
-                                                            int nb, int64_t j0, double *__restrict__ b)
+// copy the upper triangle of every block onto its strict lower triangle
+__global__ void mirror_upper_kernel(double *__restrict__ S, int sb)
 {
-    __shared__ double xs[kSolveBlock];
-    for (int j = threadIdx.x; j < kSolveBlock; j += blockDim.x) xs[j] = (j < nb) ? b[k0 + j] : 0.0;
-    __syncthreads();
+    const int i = blockIdx.x * blockDim.x + threadIdx.x; // row in the lower triangle
+    const int j = blockIdx.y;                            // column
+    if (i >= sb || i <= j) return;
+    double *blk = S + (int64_t)blockIdx.z * sb * sb;
+    blk[i + (int64_t)j * sb] = blk[j + (int64_t)i * sb];
+}
+
+__device__ __forceinline__ double wave_sum(double s)
+{
+    s += __shfl_xor(s, 32);
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 8);
+    s += __shfl_xor(s, 4);
+    s += __shfl_xor(s, 2);
+    s += __shfl_xor(s, 1);
+    return s;
+}
+
+// x = inv(R_kk) b (lower = 1: x[c] = sum_{i >= c} S[i, c] b[i]) or x = inv(R_kk)^T b (lower = 0:
+// x[c] = sum_{i <= c} S[i, c] b[i]) for one mirrored block S of live order nbk; one wavefront
+// per entry of x, lanes along the column of S.
+__global__ __launch_bounds__(256) void diag_apply_kernel(const double *__restrict__ S, int sb, int nbk, int lower,
+                                                        const double *__restrict__ b, double *__restrict__ x)
+{
     const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);
-    constexpr int kColsPerWave = 4;
-    for (int c = 0; c < kColsPerWave; ++c) {
-        const int64_t j = j0 + wave * kColsPerWave + c;
-        if (j >= M) return;
-        const double *p = R + k0 + j * M;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (c >= nbk) return;
+    const double *col = S + (int64_t)c * sb;
+    const int lo = lower ? c : 0;
+    const int hi = lower ? nbk : c + 1;
+    double s0 = 0.0, s1 = 0.0;
+    int i = lo + lane;
+    for (; i + 64 < hi; i += 128) {
+        s0 += col[i] * b[i];
+        s1 += col[i + 64] * b[i + 64];
+    }
+    if (i < hi) s0 += col[i] * b[i];
+    const double s = wave_sum(s0 + s1);
+    if (lane == 0) x[c] = s;
+}
+
+constexpr int kPanelWaves = 8;  // wavefronts of a panel_update_n workgroup, sharing the columns
+constexpr int kPanelRows = 64;  // rows of a panel_update_n workgroup, one per lane
+constexpr int kPanelCols = 4;   // columns of one panel_update_t wavefront
+
+// b[r] -= sum_j R[r, k0 + j] x[j] for r in [0, k0)  (x = the solved block, nbk entries).
+// Workgroups past the row range copy x into b[k0 : k0 + nbk].
+__global__ __launch_bounds__(kPanelWaves * 64) void panel_update_n_kernel(const double *__restrict__ R, int64_t M,
+                                                                         int64_t k0, int nbk,
+                                                                         const double *__restrict__ x,
+                                                                         double *__restrict__ b)
+{
+    __shared__ double part[kPanelWaves][kPanelRows];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t row_groups = (k0 + kPanelRows - 1) / kPanelRows;
+    if ((int64_t)blockIdx.x >= row_groups) {
+        const int64_t i = ((int64_t)blockIdx.x - row_groups) * blockDim.x + threadIdx.x;
+        if (i < nbk) b[k0 + i] = x[i];
+        return;
+    }
+    const int64_t r = (int64_t)blockIdx.x * kPanelRows + lane;
+    const bool live = r < k0;
+    const double *p = R + (live ? r : 0) + k0 * M;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int j = w;
+    for (; j + 7 * kPanelWaves < nbk; j += 8 * kPanelWaves) {
+        const double a0 = p[(int64_t)(j + 0 * kPanelWaves) * M];
+        const double a1 = p[(int64_t)(j + 1 * kPanelWaves) * M];
+        const double a2 = p[(int64_t)(j + 2 * kPanelWaves) * M];
+        const double a3 = p[(int64_t)(j + 3 * kPanelWaves) * M];
+        const double a4 = p[(int64_t)(j + 4 * kPanelWaves) * M];
+        const double a5 = p[(int64_t)(j + 5 * kPanelWaves) * M];
+        const double a6 = p[(int64_t)(j + 6 * kPanelWaves) * M];
+        const double a7 = p[(int64_t)(j + 7 * kPanelWaves) * M];
+        s0 += a0 * x[j + 0 * kPanelWaves];
+        s1 += a1 * x[j + 1 * kPanelWaves];
+        s2 += a2 * x[j + 2 * kPanelWaves];
+        s3 += a3 * x[j + 3 * kPanelWaves];
+        s0 += a4 * x[j + 4 * kPanelWaves];
+        s1 += a5 * x[j + 5 * kPanelWaves];
+        s2 += a6 * x[j + 6 * kPanelWaves];
+        s3 += a7 * x[j + 7 * kPanelWaves];
+    }
+    for (; j < nbk; j += kPanelWaves) s0 += p[(int64_t)j * M] * x[j];
+    part[w][lane] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (w == 0 && live) {
         double s = 0.0;
-        for (int i = lane; i < nb; i += 64) s += p[i] * xs[i];
-        s += __shfl_xor(s, 32);
-        s += __shfl_xor(s, 16);
-        s += __shfl_xor(s, 8);
-        s += __shfl_xor(s, 4);
-        s += __shfl_xor(s, 2);
-        s += __shfl_xor(s, 1);
-        if (lane == 0) b[j] -= s;
+        for (int q = 0; q < kPanelWaves; ++q) s += part[q][lane];
+        b[r] -= s;
+    }
+}
+
+// b[j] -= sum_i R[k0 + i, j] x[i] for j in [j0, M)  (x = the solved block, nbk entries): one
+// wavefront per kPanelCols columns, lanes along the rows.  Workgroups past the column range copy
+// x into b[k0 : k0 + nbk].
+__global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__restrict__ R, int64_t M, int64_t k0,
+                                                            int nbk, int64_t j0, const double *__restrict__ x,
+                                                            double *__restrict__ b)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t col_groups = (M - j0 + 4 * kPanelCols - 1) / (4 * kPanelCols);
+    if ((int64_t)blockIdx.x >= col_groups) {
+        const int64_t i = ((int64_t)blockIdx.x - col_groups) * blockDim.x + threadIdx.x;
+        if (i < nbk) b[k0 + i] = x[i];
+        return;
+    }
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t jb = j0 + wave * kPanelCols;
+    if (jb >= M) return;
+    const double *p[kPanelCols];
+    double s[kPanelCols];
+#pragma unroll
+    for (int c = 0; c < kPanelCols; ++c) {
+        const int64_t j = (jb + c < M) ? jb + c : M - 1; // a clamped column is computed and dropped
+        p[c] = R + k0 + j * M;
+        s[c] = 0.0;
+    }
+    int i = lane;
+    for (; i + 64 < nbk; i += 128) {
+        const double x0 = x[i], x1 = x[i + 64];
+        double a[kPanelCols], c2[kPanelCols];
+#pragma unroll
+        for (int c = 0; c < kPanelCols; ++c) {
+            a[c] = p[c][i];
+            c2[c] = p[c][i + 64];
+        }
+#pragma unroll
+        for (int c = 0; c < kPanelCols; ++c) s[c] += a[c] * x0 + c2[c] * x1;
+    }
+    if (i < nbk) {
+        const double x0 = x[i];
+#pragma unroll
+        for (int c = 0; c < kPanelCols; ++c) s[c] += p[c][i] * x0;
+    }
+#pragma unroll
+    for (int c = 0; c < kPanelCols; ++c) {
+        const double tot = wave_sum(s[c]);
+        if (lane == 0 && jb + c < M) b[jb + c] -= tot;
     }
 }
 
@@ -269,41 +351,63 @@ struct DevBuf {
     template <class T> T *as() { return static_cast<T *>(p); }
 };
 
-// B <- op(R)^-1 B for column-major B (M x t); Dinv = inverted diagonal blocks of R
-int tri_solve(knm_ctx *ctx, rocblas_handle h, const double *R, const double *Dinv, int64_t M, bool trans, double *B,
-              int t)
+// B <- op(R)^-1 B for column-major B (M x t); S = mirrored inverses of the diagonal blocks of R
+// (R = p->T or p->A).  p->xw stages each solved block; solves on one context are stream-ordered.
+int tri_solve(knm_ctx *ctx, const knm_precond *p, const double *R, const double *S, bool trans, double *B, int t)
 {
-    (void)h;
-    const int64_t nblk = (M + kSolveBlock - 1) / kSolveBlock;
+    const int64_t M = p->M;
+    const int sb = p->sb;
+    const int64_t nblk = (M + sb - 1) / sb;
     for (int c = 0; c < t; ++c) {
         double *b = B + (int64_t)c * M;
-        if (!trans) { // backward: last block first
-            for (int64_t k = nblk - 1; k >= 0; --k) {
-                const int64_t k0 = k * kSolveBlock;
-                const int nb = (int)((M - k0 < kSolveBlock) ? M - k0 : kSolveBlock);
-                hipLaunchKernelGGL(diag_apply_kernel, dim3(1), dim3(kSolveBlock), 0, ctx->stream,
-                                   Dinv + k * kSolveBlock * kSolveBlock, 0, b + k0, nb);
-                if (k0 > 0)
-                    hipLaunchKernelGGL(panel_update_n_kernel, grid1(k0), dim3(256), 0, ctx->stream, R, M, k0, nb, b);
-            }
-        } else { // forward with R^T (lower): first block first
-            for (int64_t k = 0; k < nblk; ++k) {
-                const int64_t k0 = k * kSolveBlock;
-                const int nb = (int)((M - k0 < kSolveBlock) ? M - k0 : kSolveBlock);
-                hipLaunchKernelGGL(diag_apply_kernel, dim3(1), dim3(kSolveBlock), 0, ctx->stream,
-                                   Dinv + k * kSolveBlock * kSolveBlock, 1, b + k0, nb);
-                const int64_t j0 = k0 + nb;
-                if (j0 < M) {
-                    const int64_t cols = M - j0;
-                    const int64_t blocks = (cols + 15) / 16; // 4 wavefronts x 4 columns per workgroup
-                    hipLaunchKernelGGL(panel_update_t_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, R, M,
-                                       k0, nb, j0, b);
-                }
+        for (int64_t step = 0; step < nblk; ++step) {
+            const int64_t k = trans ? step : nblk - 1 - step; // R^T is lower: forward; R: backward
+            const int64_t k0 = k * sb;
+            const int nbk = (int)((M - k0 < sb) ? M - k0 : sb);
+            double *x = p->xw + k0;
+            hipLaunchKernelGGL(diag_apply_kernel, dim3((unsigned)((nbk + 3) / 4)), dim3(256), 0, ctx->stream,
+                               S + k * sb * sb, sb, nbk, trans ? 0 : 1, b + k0, x);
+            if (!trans) {
+                const int64_t groups = (k0 + kPanelRows - 1) / kPanelRows;
+                const int64_t copy = (nbk + kPanelWaves * 64 - 1) / (kPanelWaves * 64);
+                hipLaunchKernelGGL(panel_update_n_kernel, dim3((unsigned)(groups + copy)), dim3(kPanelWaves * 64), 0,
+                                   ctx->stream, R, M, k0, nbk, x, b);
+            } else {
+                const int64_t j0 = k0 + nbk;
+                const int64_t groups = (M - j0 + 4 * kPanelCols - 1) / (4 * kPanelCols);
+                const int64_t copy = (nbk + 255) / 256;
+                hipLaunchKernelGGL(panel_update_t_kernel, dim3((unsigned)(groups + copy)), dim3(256), 0, ctx->stream,
+                                   R, M, k0, nbk, j0, x, b);
             }
         }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "blocked triangular solve", e);
+    return KNM_OK;
+}
+
+// S <- mirrored inverses of the diagonal blocks of the upper-triangular R: each block solves
+// R_kk X = I (TRSM on an identity, backward stable column by column), then the upper triangle
+// of X is copied onto the lower.
+int invert_diag_blocks(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, const double *R, double *S)
+{
+    const int64_t M = p->M;
+    const int sb = p->sb;
+    const int64_t nblk = (M + sb - 1) / sb;
+    const int64_t total = nblk * sb * sb;
+    hipLaunchKernelGGL(identity_blocks_kernel, grid1(total), dim3(256), 0, ctx->stream, S, sb, total);
+    const double one = 1.0;
+    for (int64_t k = 0; k < nblk; ++k) {
+        const int64_t k0 = k * sb;
+        const int64_t nbk = (M - k0 < sb) ? M - k0 : sb;
+        if (rocblas_dtrsm_64(h, rocblas_side_left, rocblas_fill_upper, rocblas_operation_none,
+                             rocblas_diagonal_non_unit, nbk, nbk, &one, R + k0 + (size_t)k0 * M, M,
+                             S + (size_t)k * sb * sb, sb) != rocblas_status_success)
+            return fail(ctx, KNM_HIP_ERROR, "rocblas_dtrsm");
+    }
+    hipLaunchKernelGGL(mirror_upper_kernel, dim3((unsigned)((sb + 255) / 256), (unsigned)sb, (unsigned)nblk), dim3(256),
+                       0, ctx->stream, S, sb);
+    if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "diagonal block inversion launch");
     return KNM_OK;
 }
 
@@ -329,11 +433,11 @@ int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &
     double *v = wk.v.as<double>();
     hipError_t e = hipMemcpyAsync(v, beta, bytes, hipMemcpyDeviceToDevice, ctx->stream);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
-    int st = tri_solve(ctx, h, p->A, p->Adinv, M, false, v, t); // v = A^-1 beta
+    int st = tri_solve(ctx, p, p->A, p->Adinv, false, v, t); // v = A^-1 beta
     if (st) return st;
     e = hipMemcpyAsync(out, v, bytes, hipMemcpyDeviceToDevice, ctx->stream);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
-    st = tri_solve(ctx, h, p->T, p->Tdinv, M, false, out, t); // z = T^-1 v
+    st = tri_solve(ctx, p, p->T, p->Tdinv, false, out, t); // z = T^-1 v
     if (st) return st;
     hipLaunchKernelGGL(f64_cols_to_f32_rows, grid1(M * t), dim3(256), 0, ctx->stream, out, M, t, wk.z32.as<float>());
     // c = K_nm^T (K_nm z), the O(n M) step
@@ -344,12 +448,12 @@ int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &
     st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, ctx->w_buf, wgt, t, wk.u32.as<float>());
     if (st) return st;
     hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(M * t), dim3(256), 0, ctx->stream, wk.u32.as<float>(), M, t, out);
-    st = tri_solve(ctx, h, p->T, p->Tdinv, M, true, out, t); // T^-T c
+    st = tri_solve(ctx, p, p->T, p->Tdinv, true, out, t); // T^-T c
     if (st) return st;
     const double ln = lambda * (double)n;
     if (rocblas_daxpy(h, (rocblas_int)(M * t), &ln, v, 1, out, 1) != rocblas_status_success)
         return fail(ctx, KNM_HIP_ERROR, "rocblas_daxpy");
-    return tri_solve(ctx, h, p->A, p->Adinv, M, true, out, t); // A^-T (...)
+    return tri_solve(ctx, p, p->A, p->Adinv, true, out, t); // A^-T (...)
 }
 
 } // namespace
@@ -372,6 +476,7 @@ int precond_free(knm_precond *p)
     if (p->A) (void)hipFree(p->A);
     if (p->Tdinv) (void)hipFree(p->Tdinv);
     if (p->Adinv) (void)hipFree(p->Adinv);
+    if (p->xw) (void)hipFree(p->xw);
     delete p;
     return KNM_OK;
 }
@@ -482,9 +587,8 @@ static int build_second_factor(knm_ctx *ctx, rocblas_handle h, knm_precond *p, d
         return fail(ctx, KNM_NOT_PD, "T D T^T / M + lambda I is not positive definite");
     }
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, 0.0, 1);
-    const int64_t nblk = (M + kSolveBlock - 1) / kSolveBlock;
-    hipLaunchKernelGGL(invert_diag_blocks_kernel, dim3((unsigned)nblk), dim3(kSolveBlock), 0, ctx->stream, p->A, M,
-                       p->Adinv);
+    st = invert_diag_blocks(ctx, h, p, p->A, p->Adinv);
+    if (st) return st;
     if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "preconditioner kernel launch");
     p->lambda = lambda;
     return KNM_OK;
@@ -514,10 +618,12 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
     const size_t bytes = sizeof(double) * (size_t)M * (size_t)M;
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&p->T), bytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->A), bytes);
-    const int64_t nblk = (M + kSolveBlock - 1) / kSolveBlock;
-    const size_t dbytes = sizeof(double) * (size_t)nblk * kSolveBlock * kSolveBlock;
+    p->sb = solve_block_width(M);
+    const int64_t nblk = (M + p->sb - 1) / p->sb;
+    const size_t dbytes = sizeof(double) * (size_t)nblk * p->sb * p->sb;
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Tdinv), dbytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Adinv), dbytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->xw), sizeof(double) * (size_t)M);
     DevBuf info;
     const int64_t info_len = 64; // status words: one per block row of the factorisation (at most 8 + M / 4096)
     if (e != hipSuccess || info.alloc(ctx, sizeof(int64_t) * info_len)) {
@@ -572,9 +678,12 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
     const dim3 fg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->T, M, 0.0, 1);
 
-    hipLaunchKernelGGL(invert_diag_blocks_kernel, dim3((unsigned)nblk), dim3(kSolveBlock), 0, ctx->stream, p->T, M,
-                       p->Tdinv);
     if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "preconditioner kernel launch");
+    st = invert_diag_blocks(ctx, h, p, p->T, p->Tdinv);
+    if (st) {
+        precond_free(p);
+        return st;
+    }
     if (second_factor) {
         int64_t bad = 0;
         st = build_second_factor(ctx, h, p, lambda, nullptr, &bad);
@@ -648,6 +757,31 @@ int falkon_linop(knm_ctx *ctx, const knm_precond *p, const float *X, int64_t n, 
     return falkon_linop_weighted(ctx, p, X, n, d, ldx, C, M, ldc, sigma, lambda, nullptr, beta, t, out);
 }
 
+int precond_solve(knm_ctx *ctx, const knm_precond *p, int transpose, const double *b, int t, double *out)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!p || !b || !out || t <= 0 || t > knm_max_t()) return fail(ctx, KNM_INVALID_ARG, "bad solve argument");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    const int64_t M = p->M;
+    DevBuf bc;
+    int st = bc.alloc(ctx, sizeof(double) * M * t);
+    if (st) return st;
+    double *v = bc.as<double>();
+    hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, b, M, t, v, 0);
+    if (transpose) {
+        st = tri_solve(ctx, p, p->T, p->Tdinv, true, v, t);
+        if (!st) st = tri_solve(ctx, p, p->A, p->Adinv, true, v, t);
+    } else {
+        st = tri_solve(ctx, p, p->A, p->Adinv, false, v, t);
+        if (!st) st = tri_solve(ctx, p, p->T, p->Tdinv, false, v, t);
+    }
+    if (st) return st;
+    hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, v, M, t, out, 1);
+    hipError_t e = hipStreamSynchronize(ctx->stream); // the temporary is freed on return
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "precond_solve", e);
+    return KNM_OK;
+}
+
 int precond_reweight(knm_ctx *ctx, knm_precond *p, double lambda, const double *dw_or_null, int64_t *bad_pivot_or_null)
 {
     if (!ctx) return KNM_INVALID_ARG;
@@ -705,8 +839,8 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
     st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, Y, nullptr, t, r32.as<float>());
     if (st) return st;
     hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(len), dim3(256), 0, ctx->stream, r32.as<float>(), M, t, dr);
-    st = tri_solve(ctx, h, p->T, p->Tdinv, M, true, dr, t);
-    if (!st) st = tri_solve(ctx, h, p->A, p->Adinv, M, true, dr, t);
+    st = tri_solve(ctx, p, p->T, p->Tdinv, true, dr, t);
+    if (!st) st = tri_solve(ctx, p, p->A, p->Adinv, true, dr, t);
     if (st) return st;
     hipError_t e = hipMemsetAsync(db, 0, sizeof(double) * len, ctx->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(dp, dr, sizeof(double) * len, hipMemcpyDeviceToDevice, ctx->stream);
@@ -743,8 +877,8 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
         }
     }
     // alpha = T^-1 A^-1 beta
-    st = tri_solve(ctx, h, p->A, p->Adinv, M, false, db, t);
-    if (!st) st = tri_solve(ctx, h, p->T, p->Tdinv, M, false, db, t);
+    st = tri_solve(ctx, p, p->A, p->Adinv, false, db, t);
+    if (!st) st = tri_solve(ctx, p, p->T, p->Tdinv, false, db, t);
     if (st) return st;
     hipLaunchKernelGGL(f64_cols_to_f32_rows, grid1(len), dim3(256), 0, ctx->stream, db, M, t, alpha);
     const clk::time_point t_iters = clk::now(); // each iteration ends with synchronising dot products
@@ -857,8 +991,8 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         if (st) return st;
         hipLaunchKernelGGL(newton_rhs_kernel, grid1(M), dim3(256), 0, ctx->stream, u32.as<float>(), zc.as<float>(), da,
                            mu * (double)n, jitter, M, dr);
-        st = tri_solve(ctx, h, p->T, p->Tdinv, M, true, dr, 1);
-        if (!st) st = tri_solve(ctx, h, p->A, p->Adinv, M, true, dr, 1);
+        st = tri_solve(ctx, p, p->T, p->Tdinv, true, dr, 1);
+        if (!st) st = tri_solve(ctx, p, p->A, p->Adinv, true, dr, 1);
         if (st) return st;
         e = hipMemsetAsync(db, 0, sizeof(double) * M, ctx->stream);
         if (e == hipSuccess) e = hipMemcpyAsync(dp, dr, sizeof(double) * M, hipMemcpyDeviceToDevice, ctx->stream);
@@ -882,8 +1016,8 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
             rho = rn;
         }
         // alpha += T^-1 A^-1 beta
-        st = tri_solve(ctx, h, p->A, p->Adinv, M, false, db, 1);
-        if (!st) st = tri_solve(ctx, h, p->T, p->Tdinv, M, false, db, 1);
+        st = tri_solve(ctx, p, p->A, p->Adinv, false, db, 1);
+        if (!st) st = tri_solve(ctx, p, p->T, p->Tdinv, false, db, 1);
         if (st) return st;
         const double one = 1.0;
         if (!blas_ok(rocblas_daxpy(h, (rocblas_int)M, &one, db, 1, da, 1))) return fail(ctx, KNM_HIP_ERROR, "rocblas_daxpy");
