@@ -100,6 +100,21 @@ int falkon_linop(knm_ctx *ctx, const knm_precond *p,
                  const float *C, int64_t M, int64_t ldc, float sigma, double lambda,
                  const double *beta, int t, double *out);
 
+/* Symmetric rank-k update of the upper triangle of C (n x n, column-major, leading dimension
+ * ldc) in fp64 on the matrix cores: the trailing-matrix step of the block Cholesky column
+ * update (Sec. 4, block Cholesky paragraph, third step; appendix on out-of-core algorithms)
+ * and the triangular product T diag(w) T^T of the preconditioner (Alg. 1; Alg. 2,
+ * WeightedPreconditioner):
+ *   C[i, j] = alpha sum_{q < k} w[q] a(i, q) a(j, q) + beta C[i, j] + shift [i == j],   i <= j < n
+ *   form_nt == 0:  a(i, q) = A[q + i lda]  (A is k x n)      form_nt != 0:  a(i, q) = A[i + q lda]  (A is n x k)
+ * w_or_null: k weights or NULL (all one).  triangular != 0 (form_nt only): A is upper
+ * triangular with zeros stored below its diagonal (a(i, q) = 0 for q < i), and the part of
+ * the sum that those zeros make vanish is skipped.  The strict lower triangle of C is neither read nor written; with
+ * beta == 0 C is not read.  A must not overlap the upper triangle of C.  All pointers DEVICE,
+ * the call is asynchronous on the context's stream. */
+int precond_rank_k_update(knm_ctx *ctx, int form_nt, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+                          const double *w_or_null, int triangular, double beta, double shift, double *C, int64_t ldc);
+
 /* The two triangular solves that take the preconditioned unknown to the coefficients (last
  * step of Alg. 1, alpha = T^-1 A^-1 beta) or a right-hand side into the preconditioned system
  * (its first step, A^-T T^-T r):

@@ -161,6 +161,26 @@ def chol_upper(G) -> np.ndarray:
     return R
 
 
+def rank_k_upper(a, C0=None, alpha: float = 1.0, beta: float = 0.0, w=None, shift: float = 0.0,
+                 triangular: bool = False) -> np.ndarray:
+    """Upper triangle of alpha a diag(w) a^T + beta C0 + shift I for a (n x k): the trailing
+    update of the block Cholesky column step (Sec. 4, block Cholesky paragraph) when
+    a = (block row of the factor)^T, alpha = -1, beta = 1, and the product T diag(w) T^T of
+    the (weighted) preconditioner when a = T (Alg. 1; Alg. 2, WeightedPreconditioner).
+    With `triangular` the entries a[i, q], q < i, count as zero.  The strict lower triangle
+    of the result is C0's (zero without C0): the operation leaves it alone."""
+    a = np.array(a, dtype=np.float64, copy=True)
+    n, k = a.shape
+    if triangular:
+        a = np.triu(a)
+    ww = np.ones(k) if w is None else np.asarray(w, dtype=np.float64)
+    full = alpha * (a * ww[None, :]) @ a.T + shift * np.eye(n)
+    out = np.zeros((n, n)) if C0 is None else np.array(C0, dtype=np.float64, copy=True)
+    iu = np.triu_indices(n)
+    out[iu] = full[iu] + (beta * out[iu] if beta != 0.0 else 0.0)
+    return out
+
+
 def solve_upper(R, B, trans: bool = False) -> np.ndarray:
     R = np.ascontiguousarray(R, dtype=np.float64)
     Z, sq = _vec(np.array(B, dtype=np.float64, copy=True), R.shape[0])

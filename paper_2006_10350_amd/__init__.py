@@ -49,6 +49,7 @@ SIGNATURES = {
     "falkon_linop_weighted": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _vp, _int, _vp]),
     "precond_reweight": (_int, [_vp, _vp, _f64, _vp, ctypes.POINTER(_i64)]),
     "precond_solve": (_int, [_vp, _vp, _int, _vp, _int, _vp]),
+    "precond_rank_k_update": (_int, [_vp, _int, _i64, _i64, _f64, _vp, _i64, _vp, _int, _f64, _f64, _vp, _i64]),
     "falkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _int, _vp, _i64, _i64, _f32, _f64, _f64, _int,
                           _vp, _vp]),
     "logfalkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _vp, _i64, _i64, _vp, _f32, _vp, _vp, _int, _f64,
@@ -291,6 +292,39 @@ class Preconditioner:
             self.close()
         except Exception:
             pass
+
+
+def rank_k_update(A, C, alpha: float = 1.0, beta: float = 0.0, form_nt: bool = False, w=None,
+                  triangular: bool = False, shift: float = 0.0, ctx: Optional[Context] = None) -> None:
+    """Upper triangle of C (n x n) <- alpha a diag(w) a^T + beta C + shift I, in place, fp64 on the matrix cores.
+
+    A and C are float64 GPU tensors read as COLUMN-major storage: a torch tensor of shape (c, r)
+    that is contiguous holds an r x c column-major matrix with leading dimension r.  With
+    form_nt the operand is n x k (A.shape == (k, n)), otherwise k x n (A.shape == (n, k))."""
+    ctx = ctx or default_context()
+    for x in (A, C):
+        if not (x.is_cuda and x.dtype == torch.float64 and x.dim() == 2 and x.is_contiguous()):
+            raise TypeError("A and C must be contiguous 2-D float64 GPU tensors")
+    n = C.shape[0]
+    if C.shape[1] != n:
+        raise ValueError("C must be square")
+    if form_nt:
+        k, lda = A.shape[0], A.shape[1]
+        if A.shape[1] != n:
+            raise ValueError("A must hold an n x k column-major matrix")
+    else:
+        k, lda = A.shape[1], A.shape[1]
+        if A.shape[0] != n:
+            raise ValueError("A must hold a k x n column-major matrix")
+    wp = None
+    if w is not None:
+        if not (w.is_cuda and w.dtype == torch.float64 and w.numel() == k):
+            raise TypeError("w must be a float64 GPU tensor with k entries")
+        w = w.contiguous()
+        wp = w.data_ptr()
+    ctx.check(load_library().precond_rank_k_update(ctx._h, int(bool(form_nt)), n, k, float(alpha), A.data_ptr(),
+                                                   max(lda, 1), wp, int(bool(triangular)), float(beta), float(shift),
+                                                   C.data_ptr(), max(n, 1)))
 
 
 def precond_build(C, sigma: float, lam: float, jitter: float = 0.0, ctx: Optional[Context] = None) -> Preconditioner:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libknm.so")
-SOURCES = ["knm_tile.hip", "knm_tile_f16.hip", "knm_gemm.hip", "knm_gemm_f16.hip", "knm_api.hip", "knm_solver.hip"]
+SOURCES = ["knm_tile.hip", "knm_tile_f16.hip", "knm_gemm.hip", "knm_gemm_f16.hip", "knm_api.hip", "knm_solver.hip", "knm_dsyrk.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -28,6 +28,8 @@ EXTRA = {
     # its builtin MFMAs (the reduction against the vectors) accumulate in VGPRs; the AGPRs are
     # taken by the inline-assembly accumulators of the cross term
     "knm_gemm_f16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    # 128 accumulator registers per wavefront, read and written by the epilogue
+    "knm_dsyrk.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

@@ -1,0 +1,325 @@
+// fp64 symmetric rank-k updates on the matrix cores: the bulk of the preconditioner's flop.
+//
+// Both factorisations of the preconditioner (Alg. 1, the two Cholesky lines) spend M^3 / 3 flop
+// each in the third step of the block Cholesky column update (Sec. 4, block Cholesky
+// paragraph; appendix on the out-of-core algorithms): the trailing matrix loses the product
+// of the just-solved block row with itself.  The triangular product between them (the same
+// algorithm's T T^T line, with the diagonal weights of Alg. 2's WeightedPreconditioner) is the
+// same contraction over a triangular operand.  One kernel serves both:
+//
+//   C[i, j] = alpha * sum_{k in [k0(j), K)} w[k] * a(i, k) * a(j, k) + beta * C[i, j] + shift * [i == j],   i <= j < n
+//
+//   form TN:  a(i, k) = A[k + i * lda]   (block row of the factor: contraction index contiguous)
+//   form NT:  a(i, k) = A[i + k * lda]   (columns of the triangular factor: row index contiguous)
+//
+// A workgroup of 8 wavefronts owns a 256 x 128 tile of C, each wavefront a 64 x 64 piece as
+// 4 x 4 accumulators of v_mfma_f64_16x16x4_f64.  Operand tiles (16 deep) are staged through
+// LDS, double buffered, with the global loads issued a stage and a half ahead.
+//
+// On this chip the fp64 matrix instruction and the vector ALU do not overlap: every VALU
+// cycle of either wavefront of a SIMD is taken from the matrix pipe (8 dependent fp64 adds per
+// 16 products cost 7 % in a micro-benchmark).  The loop is therefore written to issue next
+// to no VALU work: operands are fetched with buffer loads whose range check replaces the
+// bounds tests (rows past the matrix read zeros or neighbouring rows, and only ever reach
+// entries of C that are not stored), per-thread offsets are computed once, the per-stage
+// advance is scalar arithmetic on the buffer descriptor, and every LDS address is a fixed
+// per-thread base plus an immediate.
+//
+// Workgroups are numbered so that the 32 that share an XCD (and its L2) cover a 1024 x 1024
+// patch of C and re-use each other's operand rows.
+#include "knm_internal.h"
+
+namespace knm {
+namespace {
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kTI = 256;      // tile rows of C
+constexpr int kTJ = 128;      // tile columns of C
+constexpr int kTK = 16;       // contraction depth of a stage
+constexpr int kThreads = 512; // 8 wavefronts: 4 along i, 2 along j
+// LDS image of an operand tile: element (k, i) at k * stride + i, for the k-contiguous form at
+// k * stride + (i ^ k).  The strides are 16 mod 32 doubles, so the four 16-lane groups of an
+// operand read (four consecutive k) fall on alternating halves of the banks; the XOR spreads
+// the 16 k of one column, which the k-contiguous form writes at once, over 16 bank pairs.
+constexpr int kSA = kTI + 16;
+constexpr int kSB = kTJ + 16;
+constexpr int kStageDoubles = kTK * (kSA + kSB);
+constexpr int kPatchI = 4, kPatchJ = 8; // tiles of a patch: 1024 x 1024 entries of C
+constexpr int kPatchWgs = kPatchI * kPatchJ;
+constexpr int kXcds = 8;
+
+struct RankKArgs {
+    const double *A;
+    int64_t lda;
+    int64_t extent;  // elements from A to one past the last one of the operand
+    const double *w; // weights along the contraction, or null
+    double *C;
+    int64_t ldc;
+    int64_t n, K;
+    double alpha, beta, shift;
+    int tri;          // operand is upper triangular with explicit zeros below: tile column j0 starts at k = j0
+    int64_t n_patches; // upper-triangular patches in all
+};
+
+// Stage loader of one operand: a (kTK x R) tile, kPer elements per thread, held in registers
+// between the buffer loads and the LDS stores.
+//   TN (FORM 0): thread -> k = tid % 16 (contiguous in memory), rows tid / 16 + 32 r
+//   NT (FORM 1): thread -> row tid % R (contiguous in memory), k = tid / R + (512 / R) r
+template <int FORM, int R> struct Fetch {
+    static constexpr int kPer = kTK * R / kThreads;
+    static constexpr int kStepK = kThreads / R; // NT: k advance per element
+    double v[kPer];
+    unsigned voff[kPer]; // byte offsets of this thread's elements from the stage base
+    const double *base;  // uniform: first element of the current stage of this tile
+    int64_t left;        // uniform: elements from base to the end of the operand
+    int64_t stage;       // uniform: elements per stage advance
+    int row, k;          // tile-relative row and k of element 0
+
+    __device__ __forceinline__ void init(const RankKArgs &a, int64_t row0, int64_t kbeg)
+    {
+        const int tid = threadIdx.x;
+        int64_t first;
+        if (FORM == 0) {
+            k = tid & 15;
+            row = tid >> 4;
+            first = kbeg + row0 * a.lda;
+            stage = kTK;
+#pragma unroll
+            for (int r = 0; r < kPer; ++r) voff[r] = (unsigned)(((int64_t)k + (int64_t)(row + 32 * r) * a.lda) * 8);
+        } else {
+            row = tid % R;
+            k = tid / R;
+            first = row0 + kbeg * a.lda;
+            stage = kTK * a.lda;
+#pragma unroll
+            for (int r = 0; r < kPer; ++r) voff[r] = (unsigned)(((int64_t)row + (int64_t)(k + kStepK * r) * a.lda) * 8);
+        }
+        base = a.A + first;
+        left = a.extent - first;
+    }
+    // issue the loads of the next stage; reads past the operand's last element return zero
+    __device__ __forceinline__ void load()
+    {
+        // left > 0 for every stage that is loaded; the descriptor's range is 32 bits
+        const unsigned records = ((uint64_t)left >> 29) != 0 ? 0xffffffffu : (unsigned)left * 8u;
+        const __amdgpu_buffer_rsrc_t rs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<double *>(base), 0, (int)records, 0x00020000);
+#pragma unroll
+        for (int r = 0; r < kPer; ++r)
+            v[r] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rs, (int)voff[r], 0, 0));
+        base += stage;
+        left -= stage;
+    }
+    // the k-contiguous form can run past K inside the operand: zero k >= k_left (last stage only)
+    __device__ __forceinline__ void mask_tail(int k_left)
+    {
+        if (FORM == 0 && k >= k_left) {
+#pragma unroll
+            for (int r = 0; r < kPer; ++r) v[r] = 0.0;
+        }
+    }
+    __device__ __forceinline__ void scale(const double *w_stage, int k_left)
+    {
+#pragma unroll
+        for (int r = 0; r < kPer; ++r) {
+            const int kk = FORM == 0 ? k : k + kStepK * r;
+            v[r] *= kk < k_left ? w_stage[kk] : 0.0;
+        }
+    }
+    __device__ __forceinline__ void store(double *lds, int stride) const
+    {
+#pragma unroll
+        for (int r = 0; r < kPer; ++r) {
+            const int i = FORM == 0 ? row + 32 * r : row;
+            const int kk = FORM == 0 ? k : k + kStepK * r;
+            lds[kk * stride + (FORM == 0 ? (i ^ kk) : i)] = v[r];
+        }
+    }
+};
+
+template <int FORM, bool WEIGHTED>
+__global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
+{
+    __shared__ double lds[2 * kStageDoubles];
+    // workgroup -> patch -> tile: consecutive workgroup ids go to consecutive XCDs, so the
+    // 32 workgroups of one patch are those with equal id % 8 and equal (id / 8) / 32
+    const int64_t g = blockIdx.x;
+    const int64_t slot = g / kXcds;
+    const int64_t q = (slot / kPatchWgs) * kXcds + g % kXcds;
+    if (q >= a.n_patches) return;
+    // q = pj (pj + 1) / 2 + pi, pi <= pj
+    int64_t pj = (int64_t)((sqrt(8.0 * (double)q + 1.0) - 1.0) * 0.5);
+    while (pj * (pj + 1) / 2 > q) --pj;
+    while ((pj + 1) * (pj + 2) / 2 <= q) ++pj;
+    const int64_t pi = q - pj * (pj + 1) / 2;
+    const int wq = (int)(slot % kPatchWgs);
+    const int64_t i0 = (pi * kPatchI + wq % kPatchI) * kTI;
+    const int64_t j0 = (pj * kPatchJ + wq / kPatchI) * kTJ;
+    if (i0 >= a.n || j0 >= a.n || i0 > j0 + (kTJ - 1)) return; // outside C or strictly below its diagonal
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wi = (wave & 3) * 64, wj = (wave >> 2) * 64;
+    const int64_t kbeg = a.tri ? j0 : 0; // a multiple of kTK
+    const int64_t span = (a.K - kbeg + kTK - 1) / kTK;
+    const int stages = span > 0x7fffffff ? 0x7fffffff : (int)span; // launch_rank_k_upper bounds K
+
+    d4 acc[4][4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int nn = 0; nn < 4; ++nn) acc[m][nn] = d4{0.0, 0.0, 0.0, 0.0};
+
+    if (stages > 0) {
+        Fetch<FORM, kTI> fa;
+        Fetch<FORM, kTJ> fb;
+        fa.init(a, i0, kbeg);
+        fb.init(a, j0, kbeg);
+        // operand registers of k-step ks of the stage in `buf`: lane l takes k = 4 ks + l / 16
+        const int qk = lane >> 4, l15 = lane & 15;
+        auto read_ops = [&](const double *buf, int ks, double (&av)[4], double (&bv)[4]) {
+            const int krow = ks * 4 + qk;
+            const int col = FORM == 0 ? (l15 ^ krow) : l15;
+            const double *pa = buf + krow * kSA + wi + col;
+            const double *pb = buf + kTK * kSA + krow * kSB + wj + col;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) av[m] = pa[m * 16];
+#pragma unroll
+            for (int nn = 0; nn < 4; ++nn) bv[nn] = pb[nn * 16];
+        };
+        auto products = [&](const double (&av)[4], const double (&bv)[4]) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+#pragma unroll
+                for (int nn = 0; nn < 4; ++nn)
+                    acc[m][nn] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[m], bv[nn], acc[m][nn], 0, 0, 0);
+        };
+        // registers -> LDS for stage s (whose loads were issued earlier)
+        const int k_total = (int)(a.K - kbeg);
+        auto commit = [&](int s, double *buf) {
+            const int k_left = k_total - s * kTK;
+            if (k_left < kTK) {
+                fa.mask_tail(k_left);
+                fb.mask_tail(k_left);
+            }
+            if (WEIGHTED) fb.scale(a.w + kbeg + (int64_t)s * kTK, k_left < kTK ? k_left : kTK);
+            fa.store(buf, kSA);
+            fb.store(buf + kTK * kSA, kSB);
+        };
+
+        double a0[4], b0[4], a1[4], b1[4];
+        fa.load();
+        fb.load();
+        commit(0, lds);
+        if (stages > 1) {
+            fa.load();
+            fb.load();
+        }
+        __syncthreads();
+        read_ops(lds, 0, a0, b0);
+        // Per stage: the operands of a k-step are read while the products of the one before
+        // run; the next stage's tile goes to the other LDS buffer in mid-stage (its loads were
+        // issued a stage earlier) and the loads of the stage after that follow; the one
+        // barrier sits before the last k-step, after which the first operands of the next
+        // stage are read under the last products.  Two stages per trip keep the buffer
+        // offsets compile-time constants.
+        // The products have no side effects the compiler must order against LDS traffic or
+        // barriers, and left alone it sinks them below the barrier, which then waits for the
+        // LDS stores with nothing to run; the scheduling fences keep each group where it is.
+        auto stage_body = [&](int s, const double *cur, double *nxt) {
+            read_ops(cur, 1, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            products(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            read_ops(cur, 2, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            products(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s + 1 < stages) {
+                commit(s + 1, nxt);
+                if (s + 2 < stages) {
+                    fa.load();
+                    fb.load();
+                }
+            }
+            read_ops(cur, 3, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            products(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            if (s + 1 < stages) read_ops(nxt, 0, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            products(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        for (int s = 0; s < stages; s += 2) {
+            stage_body(s, lds, lds + kStageDoubles);
+            if (s + 1 < stages) stage_body(s + 1, lds + kStageDoubles, lds);
+        }
+    }
+
+    // accumulator entry r of lane l is C[4 r + l / 16][l % 16] of its 16 x 16 block
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int nn = 0; nn < 4; ++nn) {
+            const int64_t j = j0 + wj + nn * 16 + (lane & 15);
+            const int64_t ib = i0 + wi + m * 16 + (lane >> 4);
+            if (j >= a.n) continue;
+            double *col = a.C + j * a.ldc;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t i = ib + 4 * r;
+                if (i > j || i >= a.n) continue;
+                double v = a.alpha * acc[m][nn][r];
+                if (a.beta != 0.0) v += a.beta * col[i];
+                if (i == j) v += a.shift;
+                col[i] = v;
+            }
+        }
+}
+
+} // namespace
+
+hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, const double *A, int64_t lda,
+                               const double *w, int tri, double beta, double shift, double *C, int64_t ldc,
+                               hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    RankKArgs a;
+    a.A = A;
+    a.lda = lda;
+    a.w = w;
+    a.C = C;
+    a.ldc = ldc;
+    a.n = n;
+    a.K = K;
+    a.alpha = alpha;
+    a.beta = beta;
+    a.shift = shift;
+    a.tri = tri;
+    a.extent = K <= 0 ? 0 : (form_nt ? (K - 1) * lda + n : (n - 1) * lda + K);
+    const int64_t patch = (int64_t)kPatchI * kTI; // = kPatchJ * kTJ
+    const int64_t n_patch = (n + patch - 1) / patch;
+    a.n_patches = n_patch * (n_patch + 1) / 2;
+    const int64_t groups = (a.n_patches + kXcds - 1) / kXcds;
+    const int64_t wgs = groups * kXcds * kPatchWgs;
+    if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+    // a thread's byte offsets inside a stage must fit the 32-bit buffer offset
+    const int64_t span = form_nt ? (int64_t)kTK * lda + kTI : (int64_t)kTI * lda + kTK;
+    if (span * 8 >= 0xffffffffLL || K >= (int64_t)0x7fffffff * kTK) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)wgs), block(kThreads);
+    if (form_nt && w)
+        hipLaunchKernelGGL((rank_k_upper_kernel<1, true>), grid, block, 0, stream, a);
+    else if (form_nt)
+        hipLaunchKernelGGL((rank_k_upper_kernel<1, false>), grid, block, 0, stream, a);
+    else if (w)
+        hipLaunchKernelGGL((rank_k_upper_kernel<0, true>), grid, block, 0, stream, a);
+    else
+        hipLaunchKernelGGL((rank_k_upper_kernel<0, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+} // namespace knm

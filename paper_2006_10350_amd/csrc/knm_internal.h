@@ -61,6 +61,14 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
 hipError_t launch_merge(const float *part, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
                         float *out, int64_t ldo, int64_t count, hipStream_t stream);
 
+// fp64 rank-k update of the upper triangle of C on the matrix cores (knm_dsyrk.hip):
+//   C[i, j] = alpha sum_{k < K} w[k] a(i, k) a(j, k) + beta C[i, j] + shift [i == j],  i <= j < n,
+// a(i, k) = A[k + i lda] (form_nt = 0) or A[i + k lda] (form_nt = 1); w may be null; with tri the
+// operand is upper triangular (a(i, k) = 0 for k < i) and the zero part of the contraction is skipped
+hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, const double *A, int64_t lda,
+                               const double *w, int tri, double beta, double shift, double *C, int64_t ldc,
+                               hipStream_t stream);
+
 } // namespace knm
 
 struct knm_ctx {

@@ -289,17 +289,6 @@ int blas_handle(knm_ctx *ctx, rocblas_handle *h)
     return KNM_OK;
 }
 
-// dst (rows x width, leading dimension rows) <- src (leading dimension ld) with column j scaled
-// by sqrt(w[j])
-__global__ void scale_cols_kernel(const double *__restrict__ src, int64_t ld, int64_t rows, int64_t width,
-                                  const double *__restrict__ w, double *__restrict__ dst)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t j = blockIdx.y;
-    if (i >= rows || j >= width) return;
-    dst[i + j * rows] = src[i + j * ld] * sqrt(w[j]);
-}
-
 // Logistic loss l(z, y) = log(1 + exp(-y z)), y = +-1 (Appendix "Logistic Falkon Algorithm",
 // Example 1a), evaluated in fp64 from fp32 predictions: first derivative g, second derivative
 // dw (as float for the sweeps and/or as double for the preconditioner), loss.  Any output may
@@ -494,7 +483,7 @@ static int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t
     if (b > 4096) b = 4096;
     const int64_t nb = (M + b - 1) / b;
     if (nb > info_len) return fail(ctx, KNM_HIP_ERROR, "status buffer too small");
-    const double one = 1.0, minus_one = -1.0;
+    const double one = 1.0;
     for (int64_t k = 0; k < nb; ++k) {
         const int64_t r0 = k * b;
         const int64_t w = (M - r0 < b) ? M - r0 : b;
@@ -508,9 +497,8 @@ static int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t
                              rocblas_diagonal_non_unit, w, rest, &one, Akk, M, Akr, M) != rocblas_status_success)
             return fail(ctx, KNM_HIP_ERROR, "rocblas_dtrsm");
         double *Arr = A + (r0 + w) + (size_t)(r0 + w) * M;
-        if (rocblas_dsyrk_64(h, rocblas_fill_upper, rocblas_operation_transpose, rest, w, &minus_one, Akr, M, &one,
-                             Arr, M) != rocblas_status_success)
-            return fail(ctx, KNM_HIP_ERROR, "rocblas_dsyrk");
+        if (launch_rank_k_upper(0, rest, w, -1.0, Akr, M, nullptr, 0, 1.0, 0.0, Arr, M, ctx->stream) != hipSuccess)
+            return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
     }
     std::vector<int64_t> host(nb, 0);
     hipError_t e = hipMemcpyAsync(host.data(), info_dev, sizeof(int64_t) * nb, hipMemcpyDeviceToHost, ctx->stream);
@@ -526,46 +514,23 @@ static int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t
 }
 
 // A <- upper Cholesky factor of T D T^T / M + lambda I, D = diag(dw) (identity if dw is null), and
-// the inverses of its diagonal blocks.  T is upper triangular, so block column k of T (width b)
-// only reaches the leading (k + 1) b rows: T D T^T is the sum over k of rank-b updates of
-// growing leading blocks, M^3 / 3 flop instead of the M^3 of one dense rank-M update.  The
-// last block column touches the whole triangle, so it goes first and overwrites (beta = 0);
-// the others accumulate.  With weights each block column is first copied, scaled by sqrt(dw).
+// the inverses of its diagonal blocks.  T is upper triangular, so entry (i, j) of the product
+// only sums over k >= max(i, j): M^3 / 3 flop instead of the M^3 of a dense rank-M update,
+// in one launch of the rank-k kernel, which skips the vanishing part tile by tile.
 static int build_second_factor(knm_ctx *ctx, rocblas_handle h, knm_precond *p, double lambda, const double *dw,
                                int64_t *bad_pivot)
 {
     const int64_t M = p->M;
     *bad_pivot = 0;
-    int64_t b = ((M + 7) / 8 + 255) / 256 * 256;
-    if (b > 4096) b = 4096;
-    const int64_t nblk_cols = (M + b - 1) / b;
-    DevBuf panel, info, badbuf;
+    DevBuf info, badbuf;
     const int64_t info_len = 64;
     int st = info.alloc(ctx, sizeof(int64_t) * info_len);
     if (!st) st = badbuf.alloc(ctx, sizeof(unsigned long long));
-    if (!st && dw) st = panel.alloc(ctx, sizeof(double) * (size_t)M * (size_t)b);
     if (st) return st;
-    const double alpha = 1.0 / (double)M;
-    for (int64_t k = nblk_cols - 1; k >= 0; --k) {
-        const int64_t rows = ((k + 1) * b < M) ? (k + 1) * b : M;
-        const int64_t width = ((k + 1) * b <= M) ? b : M - k * b;
-        const double beta = (k == nblk_cols - 1) ? 0.0 : 1.0;
-        const double *src = p->T + (size_t)k * b * M;
-        int64_t ld = M;
-        if (dw) {
-            const dim3 g((unsigned)((rows + 255) / 256), (unsigned)width);
-            hipLaunchKernelGGL(scale_cols_kernel, g, dim3(256), 0, ctx->stream, src, M, rows, width, dw + k * b,
-                               panel.as<double>());
-            src = panel.as<double>();
-            ld = rows;
-        }
-        if (rocblas_dsyrk_64(h, rocblas_fill_upper, rocblas_operation_none, rows, width, &alpha, src, ld, &beta,
-                             p->A, M) != rocblas_status_success)
-            return fail(ctx, KNM_HIP_ERROR, "rocblas_dsyrk");
-    }
+    if (launch_rank_k_upper(1, M, M, 1.0 / (double)M, p->T, M, dw, 1, 0.0, lambda, p->A, M, ctx->stream) != hipSuccess)
+        return fail(ctx, KNM_HIP_ERROR, "triangular product launch");
     const dim3 fb(32, 8);
     const dim3 fg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
-    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, lambda, 0);
     int64_t pivot = 0;
     st = chol_upper_blocked(ctx, h, p->A, M, info.as<int64_t>(), info_len, &pivot);
     if (st) return st;
@@ -755,6 +720,21 @@ int falkon_linop(knm_ctx *ctx, const knm_precond *p, const float *X, int64_t n, 
                  int64_t M, int64_t ldc, float sigma, double lambda, const double *beta, int t, double *out)
 {
     return falkon_linop_weighted(ctx, p, X, n, d, ldx, C, M, ldc, sigma, lambda, nullptr, beta, t, out);
+}
+
+int precond_rank_k_update(knm_ctx *ctx, int form_nt, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+                          const double *w_or_null, int triangular, double beta, double shift, double *C, int64_t ldc)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (n < 0 || k < 0 || !C || ldc < (n > 1 ? n : 1) || (n > 0 && k > 0 && !A))
+        return fail(ctx, KNM_INVALID_ARG, "bad rank-k update argument");
+    if (n > 0 && k > 0 && lda < (form_nt ? n : k)) return fail(ctx, KNM_INVALID_ARG, "leading dimension too small");
+    if (triangular && !form_nt) return fail(ctx, KNM_INVALID_ARG, "triangular operand needs the row-contiguous form");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    hipError_t e = launch_rank_k_upper(form_nt, n, k, alpha, A, lda, w_or_null, triangular, beta, shift, C, ldc,
+                                       ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "rank-k update launch", e);
+    return KNM_OK;
 }
 
 int precond_solve(knm_ctx *ctx, const knm_precond *p, int transpose, const double *b, int t, double *out)

@@ -172,6 +172,35 @@ def test_chol_and_solves_match_library():
         oracle.chol_upper(np.array([[1.0, 2.0], [2.0, 1.0]]))
 
 
+def test_rank_k_upper_against_element_sums_and_a_cholesky_step():
+    # element by element on a tiny case, every option at once
+    n, k = 5, 4
+    a = RNG.standard_normal((n, k))
+    w = RNG.random(k) + 0.5
+    C0 = RNG.standard_normal((n, n))
+    got = oracle.rank_k_upper(a, C0, alpha=-0.7, beta=1.0, w=w, shift=0.25)
+    for i in range(n):
+        for j in range(n):
+            if i <= j:
+                want = -0.7 * sum(w[q] * a[i, q] * a[j, q] for q in range(k)) + C0[i, j] + (0.25 if i == j else 0.0)
+            else:
+                want = C0[i, j]  # the strict lower triangle is left alone
+            assert got[i, j] == pytest.approx(want, rel=1e-13, abs=1e-13)
+    # beta = 0 ignores C0's upper triangle; a triangular operand drops a[i, q], q < i
+    sq = RNG.standard_normal((n, n))
+    got = oracle.rank_k_upper(sq, None, triangular=True)
+    np.testing.assert_allclose(got, np.triu(np.triu(sq) @ np.triu(sq).T), rtol=1e-13, atol=1e-14)
+    # one block step of the factorisation: with R = chol(G), R11 and R12 its first block row,
+    # G22 - R12^T R12 is the matrix whose factor is R22 (Sec. 4, block Cholesky paragraph)
+    M, b = 40, 12
+    B = RNG.standard_normal((M, M))
+    G = B @ B.T + M * np.eye(M)
+    R = np.linalg.cholesky(G).T
+    S = oracle.rank_k_upper(R[:b, b:].T, G[b:, b:], alpha=-1.0, beta=1.0)
+    S = np.triu(S) + np.triu(S, 1).T
+    np.testing.assert_allclose(np.linalg.cholesky(S).T, R[b:, b:], rtol=1e-10, atol=1e-12)
+
+
 def test_preconditioner_identities():
     M, d, sigma, lam, n = 80, 3, 0.6, 1e-3, 1000
     C = _pts(M, d)
