@@ -12,9 +12,12 @@
 //   form TN:  a(i, k) = A[k + i * lda]   (block row of the factor: contraction index contiguous)
 //   form NT:  a(i, k) = A[i + k * lda]   (columns of the triangular factor: row index contiguous)
 //
-// A workgroup of 8 wavefronts owns a 256 x 128 tile of C, each wavefront a 64 x 64 piece as
+// A workgroup of 4 wavefronts owns a 128 x 128 tile of C, each wavefront a 64 x 64 piece as
 // 4 x 4 accumulators of v_mfma_f64_16x16x4_f64.  Operand tiles (16 deep) are staged through
-// LDS, double buffered, with the global loads issued a stage and a half ahead.
+// LDS, double buffered, with the global loads issued a stage and a half ahead.  Two
+// workgroups share a CU (72 KB of LDS and 4 x ~225 registers each), so that one runs while the
+// other sits at its per-stage barrier: 256 x 128 tiles with one 8-wavefront workgroup per CU
+// were 4 % slower.
 //
 // On this chip the fp64 matrix instruction and the vector ALU do not overlap: every VALU
 // cycle of either wavefront of a SIMD is taken from the matrix pipe (8 dependent fp64 adds per
@@ -25,20 +28,24 @@
 // advance is scalar arithmetic on the buffer descriptor, and every LDS address is a fixed
 // per-thread base plus an immediate.
 //
-// Workgroups are numbered so that the 32 that share an XCD (and its L2) cover a 1024 x 1024
-// patch of C and re-use each other's operand rows.
+// Workgroups are numbered so that the 64 that run together on an XCD (and share its L2) cover
+// a 1024 x 1024 patch of C and re-use each other's operand rows.
 #include "knm_internal.h"
 
 namespace knm {
 namespace {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef double d2 __attribute__((ext_vector_type(2)));
 
-constexpr int kTI = 256;      // tile rows of C
+#ifndef KNM_RANKK_TI
+#define KNM_RANKK_TI 128
+#endif
+constexpr int kTI = KNM_RANKK_TI; // tile rows of C
 constexpr int kTJ = 128;      // tile columns of C
 constexpr int kTK = 16;       // contraction depth of a stage
-constexpr int kThreads = 512; // 8 wavefronts: 4 along i, 2 along j
+constexpr int kWavesI = kTI / 64, kWavesJ = kTJ / 64; // wavefront grid of a workgroup
+constexpr int kThreads = 64 * kWavesI * kWavesJ;
 // LDS image of an operand tile: element (k, i) at k * stride + i, for the k-contiguous form at
 // k * stride + (i ^ k).  The strides are 16 mod 32 doubles, so the four 16-lane groups of an
 // operand read (four consecutive k) fall on alternating halves of the banks; the XOR spreads
@@ -46,7 +53,7 @@ constexpr int kThreads = 512; // 8 wavefronts: 4 along i, 2 along j
 constexpr int kSA = kTI + 16;
 constexpr int kSB = kTJ + 16;
 constexpr int kStageDoubles = kTK * (kSA + kSB);
-constexpr int kPatchI = 4, kPatchJ = 8; // tiles of a patch: 1024 x 1024 entries of C
+constexpr int kPatchI = 1024 / kTI, kPatchJ = 1024 / kTJ; // tiles of a patch: 1024 x 1024 entries of C
 constexpr int kPatchWgs = kPatchI * kPatchJ;
 constexpr int kXcds = 8;
 
@@ -63,39 +70,45 @@ struct RankKArgs {
     int64_t n_patches; // upper-triangular patches in all
 };
 
-// Stage loader of one operand: a (kTK x R) tile, kPer elements per thread, held in registers
-// between the buffer loads and the LDS stores.
-//   TN (FORM 0): thread -> k = tid % 16 (contiguous in memory), rows tid / 16 + 32 r
-//   NT (FORM 1): thread -> row tid % R (contiguous in memory), k = tid / R + (512 / R) r
-template <int FORM, int R> struct Fetch {
+// Stage loader of one operand: a (kTK x R) tile, kPer elements per thread in kPer / VEC loads of
+// VEC consecutive doubles, held in registers between the buffer loads and the LDS stores.
+// VEC = 2 needs every load 16-byte aligned (even leading dimension, 16-byte aligned operand).
+//   TN (FORM 0): thread -> k = VEC (tid % (16 / VEC)) .. + VEC (contiguous in memory), rows tid / (16 / VEC) + kPass r
+//   NT (FORM 1): thread -> rows VEC (tid % (R / VEC)) .. + VEC (contiguous in memory), k = tid / (R / VEC) + kStepK r
+template <int FORM, int R, int VEC> struct Fetch {
     static constexpr int kPer = kTK * R / kThreads;
-    static constexpr int kStepK = kThreads / R; // NT: k advance per element
-    double v[kPer];
-    unsigned voff[kPer]; // byte offsets of this thread's elements from the stage base
-    const double *base;  // uniform: first element of the current stage of this tile
-    int64_t left;        // uniform: elements from base to the end of the operand
-    int64_t stage;       // uniform: elements per stage advance
-    int row, k;          // tile-relative row and k of element 0
+    static constexpr int kLoads = kPer / VEC;
+    static constexpr int kPass = kThreads / (kTK / VEC);  // TN: row advance per load
+    static constexpr int kStepK = kThreads / (R / VEC);   // NT: k advance per load
+    double v[kPer];        // element e of load r at v[r * VEC + e]
+    unsigned voff[kLoads]; // byte offsets of this thread's loads from the stage base
+    const double *base;    // uniform: first element of the current stage of this tile
+    int64_t left;          // uniform: elements from base to the end of the operand
+    int64_t stage;         // uniform: elements per stage advance
+    int row, k;            // tile-relative row and k of element 0
+
+    __device__ __forceinline__ int row_of(int r, int e) const { return FORM == 0 ? row + kPass * r : row + e; }
+    __device__ __forceinline__ int k_of(int r, int e) const { return FORM == 0 ? k + e : k + kStepK * r; }
 
     __device__ __forceinline__ void init(const RankKArgs &a, int64_t row0, int64_t kbeg)
     {
         const int tid = threadIdx.x;
         int64_t first;
         if (FORM == 0) {
-            k = tid & 15;
-            row = tid >> 4;
+            k = VEC * (tid % (kTK / VEC));
+            row = tid / (kTK / VEC);
             first = kbeg + row0 * a.lda;
             stage = kTK;
-#pragma unroll
-            for (int r = 0; r < kPer; ++r) voff[r] = (unsigned)(((int64_t)k + (int64_t)(row + 32 * r) * a.lda) * 8);
         } else {
-            row = tid % R;
-            k = tid / R;
+            row = VEC * (tid % (R / VEC));
+            k = tid / (R / VEC);
             first = row0 + kbeg * a.lda;
             stage = kTK * a.lda;
-#pragma unroll
-            for (int r = 0; r < kPer; ++r) voff[r] = (unsigned)(((int64_t)row + (int64_t)(k + kStepK * r) * a.lda) * 8);
         }
+#pragma unroll
+        for (int r = 0; r < kLoads; ++r)
+            voff[r] = (unsigned)((FORM == 0 ? (int64_t)k_of(r, 0) + (int64_t)row_of(r, 0) * a.lda
+                                            : (int64_t)row_of(r, 0) + (int64_t)k_of(r, 0) * a.lda) * 8);
         base = a.A + first;
         left = a.extent - first;
     }
@@ -107,44 +120,62 @@ template <int FORM, int R> struct Fetch {
         const __amdgpu_buffer_rsrc_t rs =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<double *>(base), 0, (int)records, 0x00020000);
 #pragma unroll
-        for (int r = 0; r < kPer; ++r)
-            v[r] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rs, (int)voff[r], 0, 0));
+        for (int r = 0; r < kLoads; ++r) {
+            if (VEC == 1) {
+                v[r] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rs, (int)voff[r], 0, 0));
+            } else {
+                const d2 x = __builtin_bit_cast(d2, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff[r], 0, 0));
+                v[2 * r] = x[0];
+                v[2 * r + 1] = x[1];
+            }
+        }
         base += stage;
         left -= stage;
     }
     // the k-contiguous form can run past K inside the operand: zero k >= k_left (last stage only)
     __device__ __forceinline__ void mask_tail(int k_left)
     {
-        if (FORM == 0 && k >= k_left) {
+        if (FORM == 0) {
 #pragma unroll
-            for (int r = 0; r < kPer; ++r) v[r] = 0.0;
+            for (int r = 0; r < kLoads; ++r)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    if (k_of(r, e) >= k_left) v[r * VEC + e] = 0.0;
         }
     }
     __device__ __forceinline__ void scale(const double *w_stage, int k_left)
     {
 #pragma unroll
-        for (int r = 0; r < kPer; ++r) {
-            const int kk = FORM == 0 ? k : k + kStepK * r;
-            v[r] *= kk < k_left ? w_stage[kk] : 0.0;
-        }
+        for (int r = 0; r < kLoads; ++r)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const int kk = k_of(r, e);
+                v[r * VEC + e] *= kk < k_left ? w_stage[kk] : 0.0;
+            }
     }
     __device__ __forceinline__ void store(double *lds, int stride) const
     {
 #pragma unroll
-        for (int r = 0; r < kPer; ++r) {
-            const int i = FORM == 0 ? row + 32 * r : row;
-            const int kk = FORM == 0 ? k : k + kStepK * r;
-            lds[kk * stride + (FORM == 0 ? (i ^ kk) : i)] = v[r];
+        for (int r = 0; r < kLoads; ++r) {
+            if (FORM == 1 && VEC == 2) {
+                *reinterpret_cast<d2 *>(lds + k_of(r, 0) * stride + row_of(r, 0)) = d2{v[2 * r], v[2 * r + 1]};
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int i = row_of(r, e), kk = k_of(r, e);
+                    lds[kk * stride + (FORM == 0 ? (i ^ kk) : i)] = v[r * VEC + e];
+                }
+            }
         }
     }
 };
 
-template <int FORM, bool WEIGHTED>
+template <int FORM, bool WEIGHTED, int VEC>
 __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
 {
     __shared__ double lds[2 * kStageDoubles];
     // workgroup -> patch -> tile: consecutive workgroup ids go to consecutive XCDs, so the
-    // 32 workgroups of one patch are those with equal id % 8 and equal (id / 8) / 32
+    // workgroups of one patch are those with equal id % 8 and equal (id / 8) / kPatchWgs
     const int64_t g = blockIdx.x;
     const int64_t slot = g / kXcds;
     const int64_t q = (slot / kPatchWgs) * kXcds + g % kXcds;
@@ -161,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int wi = (wave & 3) * 64, wj = (wave >> 2) * 64;
+    const int wi = (wave % kWavesI) * 64, wj = (wave / kWavesI) * 64;
     const int64_t kbeg = a.tri ? j0 : 0; // a multiple of kTK
     const int64_t span = (a.K - kbeg + kTK - 1) / kTK;
     const int stages = span > 0x7fffffff ? 0x7fffffff : (int)span; // launch_rank_k_upper bounds K
@@ -173,8 +204,8 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
         for (int nn = 0; nn < 4; ++nn) acc[m][nn] = d4{0.0, 0.0, 0.0, 0.0};
 
     if (stages > 0) {
-        Fetch<FORM, kTI> fa;
-        Fetch<FORM, kTJ> fb;
+        Fetch<FORM, kTI, VEC> fa;
+        Fetch<FORM, kTJ, VEC> fb;
         fa.init(a, i0, kbeg);
         fb.init(a, j0, kbeg);
         // operand registers of k-step ks of the stage in `buf`: lane l takes k = 4 ks + l / 16
@@ -311,14 +342,19 @@ hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, 
     const int64_t span = form_nt ? (int64_t)kTK * lda + kTI : (int64_t)kTI * lda + kTK;
     if (span * 8 >= 0xffffffffLL || K >= (int64_t)0x7fffffff * kTK) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs), block(kThreads);
-    if (form_nt && w)
-        hipLaunchKernelGGL((rank_k_upper_kernel<1, true>), grid, block, 0, stream, a);
-    else if (form_nt)
-        hipLaunchKernelGGL((rank_k_upper_kernel<1, false>), grid, block, 0, stream, a);
-    else if (w)
-        hipLaunchKernelGGL((rank_k_upper_kernel<0, true>), grid, block, 0, stream, a);
-    else
-        hipLaunchKernelGGL((rank_k_upper_kernel<0, false>), grid, block, 0, stream, a);
+    // 16-byte loads when every one of them is aligned: tile origins are multiples of 128
+    const bool vec2 = lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
+    const int which = (form_nt ? 4 : 0) + (w ? 2 : 0) + (vec2 ? 1 : 0);
+    switch (which) {
+    case 0: hipLaunchKernelGGL((rank_k_upper_kernel<0, false, 1>), grid, block, 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((rank_k_upper_kernel<0, false, 2>), grid, block, 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((rank_k_upper_kernel<0, true, 1>), grid, block, 0, stream, a); break;
+    case 3: hipLaunchKernelGGL((rank_k_upper_kernel<0, true, 2>), grid, block, 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((rank_k_upper_kernel<1, false, 1>), grid, block, 0, stream, a); break;
+    case 5: hipLaunchKernelGGL((rank_k_upper_kernel<1, false, 2>), grid, block, 0, stream, a); break;
+    case 6: hipLaunchKernelGGL((rank_k_upper_kernel<1, true, 1>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((rank_k_upper_kernel<1, true, 2>), grid, block, 0, stream, a); break;
+    }
     return hipGetLastError();
 }
 

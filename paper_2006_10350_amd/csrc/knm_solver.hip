@@ -34,23 +34,26 @@ namespace {
 
 using namespace knm;
 
-// K[i, j] = exp(-|c_i - c_j|^2 / (2 sigma^2)) + jitter [i == j], fp64, direct differences.
+// Upper triangle (column-major, r <= c) of K[r, c] = exp(-|c_r - c_c|^2 / (2 sigma^2)) + jitter [r == c],
+// fp64, direct differences.  The factorisation reads nothing below the diagonal, which is
+// zeroed once the factor is there.
 __global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_t ldc, double inv2s2, double jitter,
                            double *__restrict__ K)
 {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t i = (int64_t)blockIdx.y * blockDim.y + threadIdx.y;
-    if (i >= M || j >= M) return;
-    const float *ci = C + i * ldc;
-    const float *cj = C + j * ldc;
+    if ((int64_t)blockIdx.x * blockDim.x > (int64_t)blockIdx.y * blockDim.y + (blockDim.y - 1)) return; // below
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.y * blockDim.y + threadIdx.y;
+    if (r > c || c >= M) return;
+    const float *cr = C + r * ldc;
+    const float *cc = C + c * ldc;
     double s = 0.0;
     for (int k = 0; k < d; ++k) {
-        double diff = (double)ci[k] - (double)cj[k];
+        double diff = (double)cr[k] - (double)cc[k];
         s += diff * diff;
     }
     double v = exp(-s * inv2s2);
-    if (i == j) v += jitter;
-    K[i * M + j] = v; // symmetric, so row- vs column-major does not matter
+    if (r == c) v += jitter;
+    K[r + c * M] = v;
 }
 
 // zero the strict lower triangle (column-major) and optionally add `shift` to the diagonal

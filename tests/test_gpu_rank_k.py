@@ -70,11 +70,12 @@ def test_triangular_operand_and_overwrite(knm, n):
     assert np.isnan(got[il]).all()
 
 
-def test_leading_dimensions_larger_than_the_matrix(knm):
+@pytest.mark.parametrize("k0", [100, 101])  # operand 16-byte aligned or not: wide and narrow loads
+def test_leading_dimensions_larger_than_the_matrix(knm, k0):
     """Operand and result as sub-blocks of larger allocations (how the factorisation calls it)."""
     rng = np.random.default_rng(7)
     big = rng.standard_normal((900, 900))        # column-major image below
-    k0, w_, r0 = 100, 64, 164                    # block row [k0, k0 + w_), trailing block from r0
+    w_, r0 = 64, 165                             # block row [k0, k0 + w_), trailing block from r0
     n = 900 - r0
     G = _colmajor(big)                           # G[j, i] = big[i, j]
     lib = knm.load_library()
