@@ -143,15 +143,26 @@ template <int FORM, int R, int VEC> struct Fetch {
                     if (k_of(r, e) >= k_left) v[r * VEC + e] = 0.0;
         }
     }
-    __device__ __forceinline__ void scale(const double *w_stage, int k_left)
+    // weights of the stage's k, fetched together with the operand (buffer loads: zero past K)
+    static constexpr int kW = FORM == 0 ? VEC : kLoads;
+    double wv[kW];
+    __device__ __forceinline__ void load_weights(const double *w_stage, int64_t w_left)
+    {
+        const unsigned records = ((uint64_t)w_left >> 29) != 0 ? 0xffffffffu : (unsigned)w_left * 8u;
+        const __amdgpu_buffer_rsrc_t rs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<double *>(w_stage), 0, (int)records, 0x00020000);
+#pragma unroll
+        for (int q = 0; q < kW; ++q) {
+            const int kk = FORM == 0 ? k + q : k + kStepK * q;
+            wv[q] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rs, kk * 8, 0, 0));
+        }
+    }
+    __device__ __forceinline__ void scale()
     {
 #pragma unroll
         for (int r = 0; r < kLoads; ++r)
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const int kk = k_of(r, e);
-                v[r * VEC + e] *= kk < k_left ? w_stage[kk] : 0.0;
-            }
+            for (int e = 0; e < VEC; ++e) v[r * VEC + e] *= wv[FORM == 0 ? e : r];
     }
     __device__ __forceinline__ void store(double *lds, int stride) const
     {
@@ -235,19 +246,26 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
                 fa.mask_tail(k_left);
                 fb.mask_tail(k_left);
             }
-            if (WEIGHTED) fb.scale(a.w + kbeg + (int64_t)s * kTK, k_left < kTK ? k_left : kTK);
+            if (WEIGHTED) fb.scale();
             fa.store(buf, kSA);
             fb.store(buf + kTK * kSA, kSB);
         };
 
-        double a0[4], b0[4], a1[4], b1[4];
-        fa.load();
-        fb.load();
-        commit(0, lds);
-        if (stages > 1) {
+        const double *w_stage = WEIGHTED ? a.w + kbeg : nullptr;
+        int64_t w_left = a.K - kbeg;
+        auto fetch = [&]() {
             fa.load();
             fb.load();
-        }
+            if (WEIGHTED) {
+                fb.load_weights(w_stage, w_left);
+                w_stage += kTK;
+                w_left -= kTK;
+            }
+        };
+        double a0[4], b0[4], a1[4], b1[4];
+        fetch();
+        commit(0, lds);
+        if (stages > 1) fetch();
         __syncthreads();
         read_ops(lds, 0, a0, b0);
         // Per stage: the operands of a k-step are read while the products of the one before
@@ -270,10 +288,7 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
             __builtin_amdgcn_sched_barrier(0);
             if (s + 1 < stages) {
                 commit(s + 1, nxt);
-                if (s + 2 < stages) {
-                    fa.load();
-                    fb.load();
-                }
+                if (s + 2 < stages) fetch();
             }
             read_ops(cur, 3, a1, b1);
             __builtin_amdgcn_sched_barrier(0);
