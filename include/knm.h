@@ -92,6 +92,11 @@ int precond_free(knm_precond *p);
 /* Copy the factors to HOST buffers of M*M doubles each (row-major, upper triangular,
  * strict lower triangle zero); either may be NULL.  For tests and inspection. */
 int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, double *A_host);
+/* Copy the block [row0, row0 + rows) x [col0, col0 + cols) of T (second == 0) or A (second != 0)
+ * to a HOST buffer of rows*cols doubles (row-major; entries below the factor's diagonal are
+ * zero).  For inspecting factors too large to copy whole. */
+int precond_get_block(knm_ctx *ctx, const knm_precond *p, int second, int64_t row0, int64_t col0, int64_t rows,
+                      int64_t cols, double *out_host);
 
 /* Preconditioned operator of Eq. 9 applied to beta (M x t, fp64 DEVICE pointers):
  *   out = A^-T ( T^-T K_nm^T K_nm T^-1 A^-1 beta + lambda n A^-1 beta ). */

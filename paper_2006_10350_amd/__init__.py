@@ -49,6 +49,7 @@ SIGNATURES = {
     "falkon_linop_weighted": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _vp, _int, _vp]),
     "precond_reweight": (_int, [_vp, _vp, _f64, _vp, ctypes.POINTER(_i64)]),
     "precond_solve": (_int, [_vp, _vp, _int, _vp, _int, _vp]),
+    "precond_get_block": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp]),
     "precond_rank_k_update": (_int, [_vp, _int, _i64, _i64, _f64, _vp, _i64, _vp, _int, _f64, _f64, _vp, _i64]),
     "falkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _int, _vp, _i64, _i64, _f32, _f64, _f64, _int,
                           _vp, _vp]),
@@ -257,6 +258,15 @@ class Preconditioner:
         A = np.empty((self.M, self.M), dtype=np.float64)
         self.ctx.check(load_library().precond_get_factors(self.ctx._h, self._h, T.ctypes.data, A.ctypes.data))
         return T, A
+
+    def block(self, second: bool, row0: int, col0: int, rows: int, cols: int):
+        """rows x cols block of T (second=False) or A (second=True) as a numpy array."""
+        import numpy as np
+
+        out = np.empty((rows, cols), dtype=np.float64)
+        self.ctx.check(load_library().precond_get_block(self.ctx._h, self._h, int(bool(second)), row0, col0, rows,
+                                                        cols, out.ctypes.data))
+        return out
 
     def reweight(self, lam: float, dw=None):
         """Rebuild A = chol(T diag(dw) T^T / M + lam I) in place (dw: float64 GPU tensor, M)."""

@@ -690,6 +690,27 @@ int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, doub
     return KNM_OK;
 }
 
+int precond_get_block(knm_ctx *ctx, const knm_precond *p, int second, int64_t row0, int64_t col0, int64_t rows,
+                      int64_t cols, double *out_host)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!p || !out_host || row0 < 0 || col0 < 0 || rows <= 0 || cols <= 0 || row0 + rows > p->M || col0 + cols > p->M)
+        return fail(ctx, KNM_INVALID_ARG, "bad factor block");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    const int64_t M = p->M;
+    const double *F = second ? p->A : p->T;
+    // the factor is column-major: column c of the block is contiguous, rows of `out_host` are strided
+    std::vector<double> tmp((size_t)rows * cols);
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess)
+        e = hipMemcpy2D(tmp.data(), sizeof(double) * rows, F + row0 + col0 * M, sizeof(double) * M,
+                        sizeof(double) * rows, (size_t)cols, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpy2D(factor block)", e);
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) out_host[r * cols + c] = (col0 + c >= row0 + r) ? tmp[r + c * rows] : 0.0;
+    return KNM_OK;
+}
+
 int falkon_linop_weighted(knm_ctx *ctx, const knm_precond *p, const float *X, int64_t n, int d, int64_t ldx,
                           const float *C, int64_t M, int64_t ldc, float sigma, double lambda, const float *dw_or_null,
                           const double *beta, int t, double *out)

@@ -102,3 +102,47 @@ def test_more_than_2_pow_31_elements(knm):
     uv = float((U.double() * v.double()).sum())
     ww = float((W.double() ** 2).sum())
     assert abs(uv - ww) <= 1e-4 * float(U.double().norm() * v.double().norm())
+
+
+def test_full_size_preconditioner_sampled_entries(knm):
+    """Both factors at M = 100k (80 GB each) against their defining identities on sampled index
+    pairs: T^T T = K_MM + jitter I entry by entry against the oracle's kernel values, and
+    A^T A = T T^T / M + lambda I with the right-hand side summed on the host from rows of T.
+    The blocked solves are checked through the adjoint identity c^T (T^-1 A^-1 b) = (A^-T T^-T c)^T b."""
+    w = synth.workload("mid")
+    jitter = 1e-8
+    inp = synth.make_inputs(w, device="cuda")
+    C = inp["C"]
+    M = w.M
+    print(f"building the preconditioner: M={M} d={w.d} lambda={w.lam}", flush=True)
+    pre = knm.precond_build(C, w.sigma, w.lam, jitter)
+    print("preconditioner built", flush=True)
+    Cn = C.cpu().numpy()
+    g = np.random.default_rng(11)
+    idx = np.concatenate([[0, 1, 127, 128, 2047, 2048, 4095, 4096, M - 4097, M - 2, M - 1], g.integers(0, M, 8)])
+    pairs = [(int(min(a, b)), int(max(a, b))) for a, b in zip(idx, g.permutation(idx))] + [(int(a), int(a)) for a in idx[:6]]
+    worst_t = worst_a = 0.0
+    for i, j in pairs:
+        ti = pre.block(False, 0, i, i + 1, 1)[:, 0]          # column i of T down to its diagonal
+        tj = pre.block(False, 0, j, i + 1, 1)[:, 0]          # column j of T, same rows
+        want = oracle.gauss(Cn[i], Cn[j], w.sigma) + (jitter if i == j else 0.0)
+        worst_t = max(worst_t, abs(float(ti @ tj) - want))
+        ai = pre.block(True, 0, i, i + 1, 1)[:, 0]
+        aj = pre.block(True, 0, j, i + 1, 1)[:, 0]
+        ri = pre.block(False, i, j, 1, M - j)[0]              # row i of T from column j on
+        rj = pre.block(False, j, j, 1, M - j)[0]              # row j of T from its diagonal on
+        want = float(ri @ rj) / M + (w.lam if i == j else 0.0)
+        worst_a = max(worst_a, abs(float(ai @ aj) - want))
+    print(f"worst |T^T T - K| = {worst_t:.3e}, worst |A^T A - (T T^T / M + lambda I)| = {worst_a:.3e}", flush=True)
+    assert worst_t < 1e-12  # entries of K are in [0, 1]; measured 2e-15
+    assert worst_a < 1e-12  # entries of T T^T / M are below max K_ii = 1; measured 3e-16
+
+    gt = torch.Generator().manual_seed(12)
+    b = torch.randn(M, generator=gt, dtype=torch.float64)
+    c = torch.randn(M, generator=gt, dtype=torch.float64)
+    x = pre.solve(b.cuda()).cpu()
+    y = pre.solve(c.cuda(), transpose=True).cpu()
+    lhs, rhs = float(c @ x), float(y @ b)
+    print(f"adjoint identity: {lhs:.12e} vs {rhs:.12e}", flush=True)
+    assert abs(lhs - rhs) <= 1e-8 * float(torch.linalg.norm(c) * torch.linalg.norm(x))
+    pre.close()
