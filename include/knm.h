@@ -120,6 +120,17 @@ int falkon_linop(knm_ctx *ctx, const knm_precond *p,
 int precond_rank_k_update(knm_ctx *ctx, int form_nt, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
                           const double *w_or_null, int triangular, double beta, double shift, double *C, int64_t ldc);
 
+/* General fp64 block product on the matrix cores, the building block of the first two steps of the
+ * block Cholesky column update (Sec. 4, block Cholesky paragraph: factor the diagonal tile, solve
+ * the block row against it) when they are carried out with products by inverted diagonal blocks:
+ *   C[i, j] = alpha sum_{q < k} a(i, q) b(j, q) + beta C[i, j],   i < ni, j < nj
+ *   a(i, q) = A[q + i lda] (a_nt == 0, A is k x ni) or A[i + q lda] (a_nt != 0, A is ni x k);  b(j, q) = B[q + j ldb]
+ * i.e. C = alpha A^T B + beta C or C = alpha A B + beta C for column-major A, B (k x nj), C (ni x nj).
+ * C must not overlap A or B; with beta == 0 C is not read.  All pointers DEVICE, asynchronous on
+ * the context's stream. */
+int precond_block_product(knm_ctx *ctx, int a_nt, int64_t ni, int64_t nj, int64_t k, double alpha, const double *A,
+                          int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc);
+
 /* The two triangular solves that take the preconditioned unknown to the coefficients (last
  * step of Alg. 1, alpha = T^-1 A^-1 beta) or a right-hand side into the preconditioned system
  * (its first step, A^-T T^-T r):

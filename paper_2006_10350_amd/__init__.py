@@ -49,6 +49,7 @@ SIGNATURES = {
     "falkon_linop_weighted": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _vp, _int, _vp]),
     "precond_reweight": (_int, [_vp, _vp, _f64, _vp, ctypes.POINTER(_i64)]),
     "precond_solve": (_int, [_vp, _vp, _int, _vp, _int, _vp]),
+    "precond_block_product": (_int, [_vp, _int, _i64, _i64, _i64, _f64, _vp, _i64, _vp, _i64, _f64, _vp, _i64]),
     "precond_get_block": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp]),
     "precond_rank_k_update": (_int, [_vp, _int, _i64, _i64, _f64, _vp, _i64, _vp, _int, _f64, _f64, _vp, _i64]),
     "falkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _int, _vp, _i64, _i64, _f32, _f64, _f64, _int,
@@ -335,6 +336,25 @@ def rank_k_update(A, C, alpha: float = 1.0, beta: float = 0.0, form_nt: bool = F
     ctx.check(load_library().precond_rank_k_update(ctx._h, int(bool(form_nt)), n, k, float(alpha), A.data_ptr(),
                                                    max(lda, 1), wp, int(bool(triangular)), float(beta), float(shift),
                                                    C.data_ptr(), max(n, 1)))
+
+
+def block_product(A, B, C, alpha: float = 1.0, beta: float = 0.0, a_nt: bool = False,
+                  ctx: Optional[Context] = None) -> None:
+    """C <- alpha op(A) B + beta C in place, fp64 on the matrix cores; op(A) = A^T, or A with a_nt.
+
+    All three are contiguous float64 GPU tensors read as COLUMN-major storage (a torch tensor of
+    shape (c, r) holds an r x c matrix): B is k x nj, C is ni x nj, A is k x ni (ni x k with a_nt)."""
+    ctx = ctx or default_context()
+    for x in (A, B, C):
+        if not (x.is_cuda and x.dtype == torch.float64 and x.dim() == 2 and x.is_contiguous()):
+            raise TypeError("A, B and C must be contiguous 2-D float64 GPU tensors")
+    nj, ni = C.shape
+    k = B.shape[1]
+    if B.shape[0] != nj or tuple(A.shape) != ((k, ni) if a_nt else (ni, k)):
+        raise ValueError("shapes do not match")
+    ctx.check(load_library().precond_block_product(ctx._h, int(bool(a_nt)), ni, nj, k, float(alpha), A.data_ptr(),
+                                                   max(A.shape[1], 1), B.data_ptr(), max(k, 1), float(beta),
+                                                   C.data_ptr(), max(ni, 1)))
 
 
 def precond_build(C, sigma: float, lam: float, jitter: float = 0.0, ctx: Optional[Context] = None) -> Preconditioner:

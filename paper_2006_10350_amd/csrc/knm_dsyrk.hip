@@ -58,16 +58,21 @@ constexpr int kPatchWgs = kPatchI * kPatchJ;
 constexpr int kXcds = 8;
 
 struct RankKArgs {
-    const double *A;
+    const double *A; // operand of the rows of C
     int64_t lda;
     int64_t extent;  // elements from A to one past the last one of the operand
+    const double *B; // operand of the columns of C (= A for the symmetric update)
+    int64_t ldb;
+    int64_t extent_b;
     const double *w; // weights along the contraction, or null
     double *C;
     int64_t ldc;
-    int64_t n, K;
+    int64_t n, nj, K; // C is n x nj (nj = n for the symmetric update)
     double alpha, beta, shift;
-    int tri;          // operand is upper triangular with explicit zeros below: tile column j0 starts at k = j0
-    int64_t n_patches; // upper-triangular patches in all
+    int tri;           // operand is upper triangular with explicit zeros below: tile column j0 starts at k = j0
+    int patch_i;       // general product: tiles of a patch along i (kPatchWgs / patch_i along j)
+    int64_t n_patch_i; // general product: patches along i
+    int64_t n_patches; // patches in all (symmetric update: the upper-triangular ones)
 };
 
 // Stage loader of one operand: a (kTK x R) tile, kPer elements per thread in kPer / VEC loads of
@@ -90,27 +95,27 @@ template <int FORM, int R, int VEC> struct Fetch {
     __device__ __forceinline__ int row_of(int r, int e) const { return FORM == 0 ? row + kPass * r : row + e; }
     __device__ __forceinline__ int k_of(int r, int e) const { return FORM == 0 ? k + e : k + kStepK * r; }
 
-    __device__ __forceinline__ void init(const RankKArgs &a, int64_t row0, int64_t kbeg)
+    __device__ __forceinline__ void init(const double *P, int64_t ld, int64_t extent, int64_t row0, int64_t kbeg)
     {
         const int tid = threadIdx.x;
         int64_t first;
         if (FORM == 0) {
             k = VEC * (tid % (kTK / VEC));
             row = tid / (kTK / VEC);
-            first = kbeg + row0 * a.lda;
+            first = kbeg + row0 * ld;
             stage = kTK;
         } else {
             row = VEC * (tid % (R / VEC));
             k = tid / (R / VEC);
-            first = row0 + kbeg * a.lda;
-            stage = kTK * a.lda;
+            first = row0 + kbeg * ld;
+            stage = kTK * ld;
         }
 #pragma unroll
         for (int r = 0; r < kLoads; ++r)
-            voff[r] = (unsigned)((FORM == 0 ? (int64_t)k_of(r, 0) + (int64_t)row_of(r, 0) * a.lda
-                                            : (int64_t)row_of(r, 0) + (int64_t)k_of(r, 0) * a.lda) * 8);
-        base = a.A + first;
-        left = a.extent - first;
+            voff[r] = (unsigned)((FORM == 0 ? (int64_t)k_of(r, 0) + (int64_t)row_of(r, 0) * ld
+                                            : (int64_t)row_of(r, 0) + (int64_t)k_of(r, 0) * ld) * 8);
+        base = P + first;
+        left = extent - first;
     }
     // issue the loads of the next stage; reads past the operand's last element return zero
     __device__ __forceinline__ void load()
@@ -181,7 +186,9 @@ template <int FORM, int R, int VEC> struct Fetch {
     }
 };
 
-template <int FORM, bool WEIGHTED, int VEC>
+// FA, FB: forms of the row and column operands; SYM: symmetric update (B = A, upper triangle of C
+// only, triangular patch enumeration); otherwise the general product C = alpha a b^T + beta C
+template <int FA, int FB, bool WEIGHTED, int VEC, bool SYM>
 __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
 {
     __shared__ double lds[2 * kStageDoubles];
@@ -191,20 +198,29 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
     const int64_t slot = g / kXcds;
     const int64_t q = (slot / kPatchWgs) * kXcds + g % kXcds;
     if (q >= a.n_patches) return;
-    // q = pj (pj + 1) / 2 + pi, pi <= pj
-    int64_t pj = (int64_t)((sqrt(8.0 * (double)q + 1.0) - 1.0) * 0.5);
-    while (pj * (pj + 1) / 2 > q) --pj;
-    while ((pj + 1) * (pj + 2) / 2 <= q) ++pj;
-    const int64_t pi = q - pj * (pj + 1) / 2;
     const int wq = (int)(slot % kPatchWgs);
-    const int64_t i0 = (pi * kPatchI + wq % kPatchI) * kTI;
-    const int64_t j0 = (pj * kPatchJ + wq / kPatchI) * kTJ;
-    if (i0 >= a.n || j0 >= a.n || i0 > j0 + (kTJ - 1)) return; // outside C or strictly below its diagonal
+    int64_t i0, j0;
+    if (SYM) {
+        // q = pj (pj + 1) / 2 + pi, pi <= pj
+        int64_t pj = (int64_t)((sqrt(8.0 * (double)q + 1.0) - 1.0) * 0.5);
+        while (pj * (pj + 1) / 2 > q) --pj;
+        while ((pj + 1) * (pj + 2) / 2 <= q) ++pj;
+        const int64_t pi = q - pj * (pj + 1) / 2;
+        i0 = (pi * kPatchI + wq % kPatchI) * kTI;
+        j0 = (pj * kPatchJ + wq / kPatchI) * kTJ;
+        if (i0 >= a.n || j0 >= a.n || i0 > j0 + (kTJ - 1)) return; // outside C or strictly below its diagonal
+    } else {
+        const int64_t pi = q % a.n_patch_i, pj = q / a.n_patch_i;
+        const int patch_j = kPatchWgs / a.patch_i;
+        i0 = (pi * a.patch_i + wq % a.patch_i) * kTI;
+        j0 = (pj * patch_j + wq / a.patch_i) * kTJ;
+        if (i0 >= a.n || j0 >= a.nj) return;
+    }
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wi = (wave % kWavesI) * 64, wj = (wave / kWavesI) * 64;
-    const int64_t kbeg = a.tri ? j0 : 0; // a multiple of kTK
+    const int64_t kbeg = (SYM && a.tri) ? j0 : 0; // a multiple of kTK
     const int64_t span = (a.K - kbeg + kTK - 1) / kTK;
     const int stages = span > 0x7fffffff ? 0x7fffffff : (int)span; // launch_rank_k_upper bounds K
 
@@ -215,17 +231,16 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
         for (int nn = 0; nn < 4; ++nn) acc[m][nn] = d4{0.0, 0.0, 0.0, 0.0};
 
     if (stages > 0) {
-        Fetch<FORM, kTI, VEC> fa;
-        Fetch<FORM, kTJ, VEC> fb;
-        fa.init(a, i0, kbeg);
-        fb.init(a, j0, kbeg);
+        Fetch<FA, kTI, VEC> fa;
+        Fetch<FB, kTJ, VEC> fb;
+        fa.init(a.A, a.lda, a.extent, i0, kbeg);
+        fb.init(a.B, a.ldb, a.extent_b, j0, kbeg);
         // operand registers of k-step ks of the stage in `buf`: lane l takes k = 4 ks + l / 16
         const int qk = lane >> 4, l15 = lane & 15;
         auto read_ops = [&](const double *buf, int ks, double (&av)[4], double (&bv)[4]) {
             const int krow = ks * 4 + qk;
-            const int col = FORM == 0 ? (l15 ^ krow) : l15;
-            const double *pa = buf + krow * kSA + wi + col;
-            const double *pb = buf + kTK * kSA + krow * kSB + wj + col;
+            const double *pa = buf + krow * kSA + wi + (FA == 0 ? (l15 ^ krow) : l15);
+            const double *pb = buf + kTK * kSA + krow * kSB + wj + (FB == 0 ? (l15 ^ krow) : l15);
 #pragma unroll
             for (int m = 0; m < 4; ++m) av[m] = pa[m * 16];
 #pragma unroll
@@ -313,15 +328,15 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
         for (int nn = 0; nn < 4; ++nn) {
             const int64_t j = j0 + wj + nn * 16 + (lane & 15);
             const int64_t ib = i0 + wi + m * 16 + (lane >> 4);
-            if (j >= a.n) continue;
+            if (j >= a.nj) continue;
             double *col = a.C + j * a.ldc;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int64_t i = ib + 4 * r;
-                if (i > j || i >= a.n) continue;
+                if ((SYM && i > j) || i >= a.n) continue;
                 double v = a.alpha * acc[m][nn][r];
                 if (a.beta != 0.0) v += a.beta * col[i];
-                if (i == j) v += a.shift;
+                if (SYM && i == j) v += a.shift;
                 col[i] = v;
             }
         }
@@ -335,20 +350,22 @@ hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, 
 {
     if (n <= 0) return hipSuccess;
     RankKArgs a;
-    a.A = A;
-    a.lda = lda;
+    a.A = a.B = A;
+    a.lda = a.ldb = lda;
     a.w = w;
     a.C = C;
     a.ldc = ldc;
-    a.n = n;
+    a.n = a.nj = n;
     a.K = K;
     a.alpha = alpha;
     a.beta = beta;
     a.shift = shift;
     a.tri = tri;
-    a.extent = K <= 0 ? 0 : (form_nt ? (K - 1) * lda + n : (n - 1) * lda + K);
+    a.extent = a.extent_b = K <= 0 ? 0 : (form_nt ? (K - 1) * lda + n : (n - 1) * lda + K);
     const int64_t patch = (int64_t)kPatchI * kTI; // = kPatchJ * kTJ
     const int64_t n_patch = (n + patch - 1) / patch;
+    a.patch_i = kPatchI;
+    a.n_patch_i = n_patch;
     a.n_patches = n_patch * (n_patch + 1) / 2;
     const int64_t groups = (a.n_patches + kXcds - 1) / kXcds;
     const int64_t wgs = groups * kXcds * kPatchWgs;
@@ -361,15 +378,66 @@ hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, 
     const bool vec2 = lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
     const int which = (form_nt ? 4 : 0) + (w ? 2 : 0) + (vec2 ? 1 : 0);
     switch (which) {
-    case 0: hipLaunchKernelGGL((rank_k_upper_kernel<0, false, 1>), grid, block, 0, stream, a); break;
-    case 1: hipLaunchKernelGGL((rank_k_upper_kernel<0, false, 2>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((rank_k_upper_kernel<0, true, 1>), grid, block, 0, stream, a); break;
-    case 3: hipLaunchKernelGGL((rank_k_upper_kernel<0, true, 2>), grid, block, 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((rank_k_upper_kernel<1, false, 1>), grid, block, 0, stream, a); break;
-    case 5: hipLaunchKernelGGL((rank_k_upper_kernel<1, false, 2>), grid, block, 0, stream, a); break;
-    case 6: hipLaunchKernelGGL((rank_k_upper_kernel<1, true, 1>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((rank_k_upper_kernel<1, true, 2>), grid, block, 0, stream, a); break;
+    case 0: hipLaunchKernelGGL((rank_k_upper_kernel<0, 0, false, 1, true>), grid, block, 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((rank_k_upper_kernel<0, 0, false, 2, true>), grid, block, 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((rank_k_upper_kernel<0, 0, true, 1, true>), grid, block, 0, stream, a); break;
+    case 3: hipLaunchKernelGGL((rank_k_upper_kernel<0, 0, true, 2, true>), grid, block, 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((rank_k_upper_kernel<1, 1, false, 1, true>), grid, block, 0, stream, a); break;
+    case 5: hipLaunchKernelGGL((rank_k_upper_kernel<1, 1, false, 2, true>), grid, block, 0, stream, a); break;
+    case 6: hipLaunchKernelGGL((rank_k_upper_kernel<1, 1, true, 1, true>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((rank_k_upper_kernel<1, 1, true, 2, true>), grid, block, 0, stream, a); break;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_f64(int a_nt, int64_t ni, int64_t nj, int64_t K, double alpha, const double *A, int64_t lda,
+                           const double *B, int64_t ldb, double beta, double *C, int64_t ldc, hipStream_t stream)
+{
+    if (ni <= 0 || nj <= 0) return hipSuccess;
+    RankKArgs a;
+    a.A = A;
+    a.lda = lda;
+    a.B = B;
+    a.ldb = ldb;
+    a.w = nullptr;
+    a.C = C;
+    a.ldc = ldc;
+    a.n = ni;
+    a.nj = nj;
+    a.K = K;
+    a.alpha = alpha;
+    a.beta = beta;
+    a.shift = 0.0;
+    a.tri = 0;
+    a.extent = K <= 0 ? 0 : (a_nt ? (K - 1) * lda + ni : (ni - 1) * lda + K);
+    a.extent_b = K <= 0 ? 0 : (nj - 1) * ldb + K;
+    // patches of 64 tiles, as square as the shape of C allows
+    const int64_t tiles_i = (ni + kTI - 1) / kTI;
+    int patch_i = 1;
+    while (patch_i < 8 && patch_i < tiles_i) patch_i *= 2;
+    const int patch_j = kPatchWgs / patch_i;
+    a.patch_i = patch_i;
+    a.n_patch_i = (tiles_i + patch_i - 1) / patch_i;
+    const int64_t tiles_j = (nj + kTJ - 1) / kTJ;
+    a.n_patches = a.n_patch_i * ((tiles_j + patch_j - 1) / patch_j);
+    const int64_t groups = (a.n_patches + kXcds - 1) / kXcds;
+    const int64_t wgs = groups * kXcds * kPatchWgs;
+    if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int64_t span_a = a_nt ? (int64_t)kTK * lda + kTI : (int64_t)kTI * lda + kTK;
+    const int64_t span_b = (int64_t)kTJ * ldb + kTK;
+    if (span_a * 8 >= 0xffffffffLL || span_b * 8 >= 0xffffffffLL || K >= (int64_t)0x7fffffff * kTK)
+        return hipErrorInvalidValue;
+    const dim3 grid((unsigned)wgs), block(kThreads);
+    const bool vec2 = lda % 2 == 0 && ldb % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0 &&
+                      reinterpret_cast<uintptr_t>(B) % 16 == 0;
+    if (a_nt && vec2)
+        hipLaunchKernelGGL((rank_k_upper_kernel<1, 0, false, 2, false>), grid, block, 0, stream, a);
+    else if (a_nt)
+        hipLaunchKernelGGL((rank_k_upper_kernel<1, 0, false, 1, false>), grid, block, 0, stream, a);
+    else if (vec2)
+        hipLaunchKernelGGL((rank_k_upper_kernel<0, 0, false, 2, false>), grid, block, 0, stream, a);
+    else
+        hipLaunchKernelGGL((rank_k_upper_kernel<0, 0, false, 1, false>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 

@@ -69,6 +69,12 @@ hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, 
                                const double *w, int tri, double beta, double shift, double *C, int64_t ldc,
                                hipStream_t stream);
 
+// general fp64 product on the same kernel: C (ni x nj) = alpha sum_{k < K} a(i, k) b(j, k) + beta C with
+// a(i, k) = A[k + i lda] (a_nt = 0) or A[i + k lda] (a_nt = 1) and b(j, k) = B[k + j ldb]; C must not
+// overlap A or B
+hipError_t launch_gemm_f64(int a_nt, int64_t ni, int64_t nj, int64_t K, double alpha, const double *A, int64_t lda,
+                           const double *B, int64_t ldb, double beta, double *C, int64_t ldc, hipStream_t stream);
+
 } // namespace knm
 
 struct knm_ctx {

@@ -761,6 +761,20 @@ int precond_rank_k_update(knm_ctx *ctx, int form_nt, int64_t n, int64_t k, doubl
     return KNM_OK;
 }
 
+int precond_block_product(knm_ctx *ctx, int a_nt, int64_t ni, int64_t nj, int64_t k, double alpha, const double *A,
+                          int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (ni < 0 || nj < 0 || k < 0 || !C || ldc < (ni > 1 ? ni : 1) || (ni > 0 && nj > 0 && k > 0 && (!A || !B)))
+        return fail(ctx, KNM_INVALID_ARG, "bad block product argument");
+    if (ni > 0 && nj > 0 && k > 0 && (lda < (a_nt ? ni : k) || ldb < k))
+        return fail(ctx, KNM_INVALID_ARG, "leading dimension too small");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    hipError_t e = launch_gemm_f64(a_nt, ni, nj, k, alpha, A, lda, B, ldb, beta, C, ldc, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "block product launch", e);
+    return KNM_OK;
+}
+
 int precond_solve(knm_ctx *ctx, const knm_precond *p, int transpose, const double *b, int t, double *out)
 {
     if (!ctx) return KNM_INVALID_ARG;

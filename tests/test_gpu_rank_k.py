@@ -102,3 +102,30 @@ def test_rank_k_update_rejects_bad_arguments(knm):
     assert lib.precond_rank_k_update(ctx._h, 0, 8, 4, 1.0, None, 4, None, 0, 0.0, 0.0, C.data_ptr(), 8) != 0
     # nothing to do is not an error
     assert lib.precond_rank_k_update(ctx._h, 0, 0, 4, 1.0, A.data_ptr(), 4, None, 0, 0.0, 0.0, C.data_ptr(), 1) == 0
+
+
+# general block product: ragged shapes around the 128 x 128 tile, the 16-deep stage and the patch shapes
+GEMM_SHAPES = [(1, 1, 1), (5, 7, 3), (128, 128, 128), (128, 1000, 48), (130, 257, 33), (300, 90, 129),
+               (1100, 700, 64), (64, 2100, 272), (2100, 64, 17)]
+
+
+@pytest.mark.parametrize("ni,nj,k", GEMM_SHAPES)
+@pytest.mark.parametrize("a_nt", [False, True])
+def test_block_product_matches_definition(knm, ni, nj, k, a_nt):
+    rng = np.random.default_rng(7 * ni + 3 * nj + k)
+    a = rng.standard_normal((ni, k))      # a(i, q)
+    b = rng.standard_normal((nj, k))      # b(j, q)
+    C0 = rng.standard_normal((ni, nj))
+    A = _colmajor(a) if a_nt else _colmajor(a.T)   # ni x k, or k x ni, column-major
+    B = _colmajor(b.T)                             # k x nj
+    C = _colmajor(C0)
+    knm.block_product(A, B, C, alpha=-0.5, beta=1.0, a_nt=a_nt)
+    torch.cuda.synchronize()
+    ref = -0.5 * a @ b.T + C0
+    assert np.abs(C.cpu().numpy().T - ref).max() <= 1e-13 * np.abs(ref).max() * max(k, 8)
+    # beta = 0 overwrites without reading
+    Cn = _colmajor(np.full((ni, nj), np.nan))
+    knm.block_product(A, B, Cn, alpha=2.0, beta=0.0, a_nt=a_nt)
+    torch.cuda.synchronize()
+    ref = 2.0 * a @ b.T
+    assert np.abs(Cn.cpu().numpy().T - ref).max() <= 1e-13 * np.abs(ref).max() * max(k, 8)
