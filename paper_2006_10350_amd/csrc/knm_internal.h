@@ -95,8 +95,8 @@ struct knm_ctx {
     bool ev_used[5] = {false, false, false, false, false};
     double fit_seconds[4] = {0.0, 0.0, 0.0, 0.0}; // last falkon_fit: preconditioner, rhs, iterations, tail
     std::string last_error;
-    // solver handles (created lazily by knm_solver.hip)
-    void *blas = nullptr;
+    // partial sums of the solver's fp64 reductions (allocated lazily by knm_solver.hip)
+    double *red_buf = nullptr;
 };
 
 namespace knm {

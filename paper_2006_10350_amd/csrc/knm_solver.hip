@@ -5,9 +5,6 @@
 // Factorisations and triangular solves use rocSOLVER / rocBLAS on column-major
 // storage: T and A are upper triangular with T^T T = K_MM + jitter I and
 // A^T A = T T^T / M + lambda I  (Eq. 7 with K_mm = T^T T).
-#include <rocblas/rocblas.h>
-#include <rocsolver/rocsolver.h>
-
 #include <chrono>
 #include <cmath>
 #include <new>
@@ -119,15 +116,6 @@ inline int solve_block_width(int64_t M)
     int64_t b = ((M + 15) / 16 + 255) / 256 * 256;
     if (b > 2048) b = 2048;
     return (int)b;
-}
-
-// every sb x sb block of S <- identity
-__global__ void identity_blocks_kernel(double *__restrict__ S, int sb, int64_t total)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
-    const int64_t in_block = i % ((int64_t)sb * sb);
-    S[i] = (in_block % sb == in_block / sb) ? 1.0 : 0.0;
 }
 
 // copy the upper triangle of every block onto its strict lower triangle
@@ -276,21 +264,218 @@ __global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__res
     }
 }
 
+// ---- leaf of the blocked factorisation --------------------------------------------------------
+// One workgroup factorises a diagonal block of order nb <= 128 in LDS (packed upper triangle,
+// right-looking, two barriers per pivot) and inverts the factor there.  Everything above the
+// leaf is products with these small inverses on the matrix cores.
+constexpr int kLeaf = 128;
+__device__ __forceinline__ int packed_upper(int i, int j) { return j * (j + 1) / 2 + i; } // i <= j, by columns
+
+constexpr int kLeafThreads = 512;
+// W (nb x nb, column-major, ldw; written whole, zeros below the diagonal) <- inverse of the upper
+// triangular factor R held packed by columns in P, whose reciprocal diagonal is in dinv.  Q is
+// scratch for the inverse packed by ROWS: (j, c), j <= c, at j nb - j (j - 1) / 2 + (c - j).
+// All rows are done in lockstep, last to first:  W[i, c] = -(sum_{i < j <= c} R[i, j] W[j, c]) / R[i, i],
+// so R[i, j] is a broadcast read and W[j, c] is contiguous across the columns c.  A column
+// belongs to four adjacent lanes, which split the sum over j.  kLeafThreads threads, all call.
+// One workgroup has a CU to itself, so the loops are unrolled by hand to keep several LDS
+// reads in flight.
+__device__ __forceinline__ void invert_packed_upper(const double *P, const double *dinv, double *Q, int nb,
+                                                    double *W, int64_t ldw)
+{
+    const int c = threadIdx.x >> 2, part = threadIdx.x & 3;
+    auto row_start = [nb](int j) { return j * nb - j * (j - 1) / 2; };
+    if (c < nb && part == 0) Q[row_start(c)] = dinv[c];
+    const bool live = c < nb;
+    for (int i = nb - 2; i >= 0; --i) {
+        double s0 = 0.0, s1 = 0.0;
+        int j = i + 1 + part;
+        int pr = packed_upper(i, j);       // R[i, j]
+        int pw = row_start(j) + (c - j);   // W[j, c]
+        // j advances by 4: R[i, j] moves by 4 j + 10 entries, W[j, c] by 4 nb - 4 j - 10
+        for (; j + 4 < nb; j += 8) {
+            const int pr1 = pr + 4 * j + 10, pw1 = pw + 4 * nb - 4 * j - 10;
+            const double a0 = (live && j <= c) ? P[pr] * Q[pw] : 0.0;
+            const double a1 = (live && j + 4 <= c) ? P[pr1] * Q[pw1] : 0.0;
+            s0 += a0;
+            s1 += a1;
+            pr = pr1 + 4 * (j + 4) + 10;
+            pw = pw1 + 4 * nb - 4 * (j + 4) - 10;
+        }
+        if (j < nb && live && j <= c) s0 += P[pr] * Q[pw];
+        double s = s0 + s1;
+        s += __shfl_xor(s, 1);
+        s += __shfl_xor(s, 2);
+        if (part == 0 && live && c > i) Q[row_start(i) + (c - i)] = -s * dinv[i];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < nb * nb; e += blockDim.x) {
+        const int i = e % nb, j = e / nb;
+        W[i + j * ldw] = (i <= j) ? Q[row_start(i) + (j - i)] : 0.0;
+    }
+}
+
+// Upper triangle of the nb x nb block at A (column-major, lda) <- its Cholesky factor R, R^T R = A;
+// W <- R^-1.  *bad <- min(*bad, pivot0 + k + 1) for a pivot k that is not a positive finite number
+// (the factorisation then goes on with 1 in its place; the caller discards the result).
+__global__ __launch_bounds__(kLeafThreads) void potrf_trtri_leaf_kernel(double *__restrict__ A, int64_t lda, int nb,
+                                                                       double *__restrict__ W, int64_t ldw,
+                                                                       int64_t pivot0, unsigned long long *bad)
+{
+    __shared__ double P[kLeaf * (kLeaf + 1) / 2];
+    __shared__ double Q[kLeaf * (kLeaf + 1) / 2];
+    __shared__ double rowk[kLeaf];
+    __shared__ double dinv[kLeaf];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < nb * nb; e += kLeafThreads) {
+        const int i = e % nb, j = e / nb;
+        if (i <= j) P[packed_upper(i, j)] = A[i + j * lda];
+    }
+    __syncthreads();
+    const int jc = tid & (kLeaf - 1), par = tid >> 7; // trailing update: column of this thread, rows par mod 4
+    for (int k = 0; k < nb; ++k) {
+        const double dkk = P[packed_upper(k, k)];
+        const bool ok = dkk > 0.0 && dkk < 1.0e300;
+        const double rinv = ok ? 1.0 / sqrt(dkk) : 1.0;
+        if (tid == 0) {
+            if (!ok) atomicMin(bad, (unsigned long long)(pivot0 + k + 1));
+            dinv[k] = rinv;
+        }
+        if (tid > k && tid < nb) { // row k, scaled; kept beside the packed copy for the update
+            const double v = P[packed_upper(k, tid)] * rinv;
+            P[packed_upper(k, tid)] = v;
+            rowk[tid] = v;
+        }
+        __syncthreads();
+        const int j = k + 1 + jc;
+        if (j < nb) {
+            const double rj = rowk[j];
+            double *col = P + packed_upper(0, j);
+            int i = k + 1 + par;
+            for (; i + 4 <= j; i += 8) {
+                const double u0 = rowk[i], u1 = rowk[i + 4];
+                const double c0 = col[i], c1 = col[i + 4];
+                col[i] = c0 - u0 * rj;
+                col[i + 4] = c1 - u1 * rj;
+            }
+            if (i <= j) col[i] -= rowk[i] * rj;
+        }
+        __syncthreads();
+    }
+    // the diagonal of R: P still holds the pivots before the square root
+    for (int k = tid; k < nb; k += kLeafThreads) P[packed_upper(k, k)] = 1.0 / dinv[k];
+    __syncthreads();
+    for (int e = tid; e < nb * nb; e += kLeafThreads) {
+        const int i = e % nb, j = e / nb;
+        if (i <= j) A[i + j * lda] = P[packed_upper(i, j)];
+    }
+    invert_packed_upper(P, dinv, Q, nb, W, ldw);
+}
+
+// W <- inverse of the upper triangular nb x nb block at R (one workgroup per diagonal block of a
+// factor: block g at R + g * step_r, its inverse at W + g * step_w)
+__global__ __launch_bounds__(kLeafThreads) void trtri_leaf_kernel(const double *__restrict__ R, int64_t ldr, int64_t M,
+                                                        int64_t step_w_block, int blocks_per_group, double *__restrict__ W,
+                                                        int64_t ldw)
+{
+    __shared__ double P[kLeaf * (kLeaf + 1) / 2];
+    __shared__ double Q[kLeaf * (kLeaf + 1) / 2];
+    __shared__ double dinv[kLeaf];
+    const int64_t g = blockIdx.x;
+    const int64_t r0 = g * kLeaf;
+    const int nb = (int)((M - r0 < kLeaf) ? M - r0 : kLeaf);
+    const double *Rb = R + r0 + r0 * ldr;
+    // leaf g sits on the diagonal of group g / blocks_per_group, at offset (g % blocks_per_group) * 128
+    const int64_t grp = g / blocks_per_group, off = (g % blocks_per_group) * kLeaf;
+    double *Wb = W + grp * step_w_block + off + off * ldw;
+    for (int e = threadIdx.x; e < nb * nb; e += kLeafThreads) {
+        const int i = e % nb, j = e / nb;
+        if (i <= j) P[packed_upper(i, j)] = Rb[i + j * ldr];
+        if (i == j) dinv[i] = 1.0 / Rb[i + j * ldr];
+    }
+    __syncthreads();
+    invert_packed_upper(P, dinv, Q, nb, Wb, ldw);
+}
+
 inline dim3 grid1(int64_t n, int threads = 256) { return dim3((unsigned)((n + threads - 1) / threads)); }
 
-int blas_handle(knm_ctx *ctx, rocblas_handle *h)
+// ---- fp64 vector work of the CG driver -----------------------------------------------------
+// Sums are taken in a fixed order (256 block partials, then one block), so a fit is
+// reproducible from run to run.
+constexpr int kRedBlocks = 256;
+
+__global__ __launch_bounds__(256) void dot_partial_kernel(const double *__restrict__ x, const double *__restrict__ y,
+                                                         int64_t n, double *__restrict__ part)
 {
-    if (!ctx->blas) {
-        rocblas_handle nh = nullptr;
-        if (rocblas_create_handle(&nh) != rocblas_status_success) return fail(ctx, KNM_HIP_ERROR, "rocblas_create_handle");
-        ctx->blas = nh;
+    __shared__ double sh[256];
+    double s = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        s += y ? x[i] * y[i] : x[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
     }
-    *h = static_cast<rocblas_handle>(ctx->blas);
-    if (rocblas_set_stream(*h, ctx->stream) != rocblas_status_success) return fail(ctx, KNM_HIP_ERROR, "rocblas_set_stream");
-    if (rocblas_set_pointer_mode(*h, rocblas_pointer_mode_host) != rocblas_status_success)
-        return fail(ctx, KNM_HIP_ERROR, "rocblas_set_pointer_mode");
+    if (threadIdx.x == 0) part[blockIdx.x] = sh[0];
+}
+
+__global__ __launch_bounds__(256) void dot_finish_kernel(const double *__restrict__ part, int count, double *__restrict__ out)
+{
+    __shared__ double sh[256];
+    sh[threadIdx.x] = ((int)threadIdx.x < count) ? part[threadIdx.x] : 0.0;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = sh[0];
+}
+
+__global__ void axpy_kernel(int64_t n, double a, const double *__restrict__ x, double *__restrict__ y)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) y[i] += a * x[i];
+}
+
+__global__ void scal_kernel(int64_t n, double b, double *__restrict__ y)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) y[i] *= b;
+}
+
+// *out_host <- sum_i x[i] y[i] (y null: sum_i x[i]); synchronises the stream
+int vec_dot(knm_ctx *ctx, int64_t n, const double *x, const double *y, double *out_host)
+{
+    if (!ctx->red_buf) {
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&ctx->red_buf), sizeof(double) * (kRedBlocks + 1));
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->red_buf = nullptr;
+            return fail(ctx, KNM_ALLOC, "hipMalloc(reduction buffer)", e);
+        }
+    }
+    hipLaunchKernelGGL(dot_partial_kernel, dim3(kRedBlocks), dim3(256), 0, ctx->stream, x, y, n, ctx->red_buf);
+    hipLaunchKernelGGL(dot_finish_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->red_buf, kRedBlocks,
+                       ctx->red_buf + kRedBlocks);
+    hipError_t e = hipMemcpyAsync(out_host, ctx->red_buf + kRedBlocks, sizeof(double), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "vector reduction", e);
     return KNM_OK;
 }
+
+int vec_axpy(knm_ctx *ctx, int64_t n, double a, const double *x, double *y)
+{
+    hipLaunchKernelGGL(axpy_kernel, grid1(n), dim3(256), 0, ctx->stream, n, a, x, y);
+    return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "axpy launch");
+}
+
+int vec_scal(knm_ctx *ctx, int64_t n, double b, double *y)
+{
+    hipLaunchKernelGGL(scal_kernel, grid1(n), dim3(256), 0, ctx->stream, n, b, y);
+    return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "scal launch");
+}
+
 
 // Logistic loss l(z, y) = log(1 + exp(-y z)), y = +-1 (Appendix "Logistic Falkon Algorithm",
 // Example 1a), evaluated in fp64 from fp32 predictions: first derivative g, second derivative
@@ -378,24 +563,38 @@ int tri_solve(knm_ctx *ctx, const knm_precond *p, const double *R, const double 
     return KNM_OK;
 }
 
-// S <- mirrored inverses of the diagonal blocks of the upper-triangular R: each block solves
-// R_kk X = I (TRSM on an identity, backward stable column by column), then the upper triangle
-// of X is copied onto the lower.
-int invert_diag_blocks(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, const double *R, double *S)
+// S <- mirrored inverses of the sb x sb diagonal blocks of the upper-triangular R.  The 128 x 128
+// diagonal blocks are inverted by the leaf kernel (one workgroup each); neighbouring inverses are
+// then merged level by level,  inv([R11 R12; 0 R22]) = [W11, -W11 R12 W22; 0, W22],  with two
+// block products per pair, until the blocks are sb wide; last the upper triangle of every
+// block is copied onto its lower.  `tmp` holds (sb / 2)^2 doubles.
+int invert_diag_blocks(knm_ctx *ctx, const knm_precond *p, const double *R, double *S, double *tmp)
 {
     const int64_t M = p->M;
     const int sb = p->sb;
     const int64_t nblk = (M + sb - 1) / sb;
-    const int64_t total = nblk * sb * sb;
-    hipLaunchKernelGGL(identity_blocks_kernel, grid1(total), dim3(256), 0, ctx->stream, S, sb, total);
-    const double one = 1.0;
-    for (int64_t k = 0; k < nblk; ++k) {
-        const int64_t k0 = k * sb;
-        const int64_t nbk = (M - k0 < sb) ? M - k0 : sb;
-        if (rocblas_dtrsm_64(h, rocblas_side_left, rocblas_fill_upper, rocblas_operation_none,
-                             rocblas_diagonal_non_unit, nbk, nbk, &one, R + k0 + (size_t)k0 * M, M,
-                             S + (size_t)k * sb * sb, sb) != rocblas_status_success)
-            return fail(ctx, KNM_HIP_ERROR, "rocblas_dtrsm");
+    const int64_t block = (int64_t)sb * sb;
+    hipError_t e = hipMemsetAsync(S, 0, sizeof(double) * nblk * block, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+    const int64_t leaves = (M + kLeaf - 1) / kLeaf;
+    hipLaunchKernelGGL(trtri_leaf_kernel, dim3((unsigned)leaves), dim3(kLeafThreads), 0, ctx->stream, R, M, M, block,
+                       sb / kLeaf, S, (int64_t)sb);
+    for (int64_t h = kLeaf; h < sb; h *= 2) {
+        for (int64_t k = 0; k < nblk; ++k) {
+            const int64_t k0 = k * sb;
+            const int64_t nbk = (M - k0 < sb) ? M - k0 : sb;
+            double *Sk = S + k * block;
+            for (int64_t off = 0; off + h < nbk; off += 2 * h) {
+                const int64_t h2 = (nbk - off - h < h) ? nbk - off - h : h; // order of the second block of the pair
+                const double *R12 = R + (k0 + off) + (size_t)(k0 + off + h) * M;
+                const double *W11 = Sk + off + off * sb;
+                const double *W22 = Sk + (off + h) + (off + h) * sb;
+                double *W12 = Sk + off + (off + h) * sb;
+                if (launch_gemm_f64(1, h, h2, h2, 1.0, R12, M, W22, sb, 0.0, tmp, h, ctx->stream) != hipSuccess ||
+                    launch_gemm_f64(1, h, h2, h, -1.0, W11, sb, tmp, h, 0.0, W12, sb, ctx->stream) != hipSuccess)
+                    return fail(ctx, KNM_HIP_ERROR, "inverse merge launch");
+            }
+        }
     }
     hipLaunchKernelGGL(mirror_upper_kernel, dim3((unsigned)((sb + 255) / 256), (unsigned)sb, (unsigned)nblk), dim3(256),
                        0, ctx->stream, S, sb);
@@ -417,7 +616,7 @@ struct LinopWork {
 
 // out <- A^-T ( T^-T K^T D K T^-1 A^-1 beta + lambda n A^-1 beta );  beta, out column-major, may not alias;
 // D = diag(wgt) over the rows of X, identity if wgt is null
-int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &wk, const float *X, int64_t n, int d,
+int linop_cols(knm_ctx *ctx, const knm_precond *p, LinopWork &wk, const float *X, int64_t n, int d,
                int64_t ldx, const float *C, int64_t M, int64_t ldc, float sigma, double lambda, const double *beta,
                int t, double *out, const float *wgt = nullptr)
 {
@@ -443,8 +642,8 @@ int linop_cols(knm_ctx *ctx, rocblas_handle h, const knm_precond *p, LinopWork &
     st = tri_solve(ctx, p, p->T, p->Tdinv, true, out, t); // T^-T c
     if (st) return st;
     const double ln = lambda * (double)n;
-    if (rocblas_daxpy(h, (rocblas_int)(M * t), &ln, v, 1, out, 1) != rocblas_status_success)
-        return fail(ctx, KNM_HIP_ERROR, "rocblas_daxpy");
+    if (vec_axpy(ctx, M * t, ln, v, out) != KNM_OK)
+        return KNM_HIP_ERROR;
     return tri_solve(ctx, p, p->A, p->Adinv, true, out, t); // A^-T (...)
 }
 
@@ -454,9 +653,9 @@ extern "C" {
 
 void knm_solver_release(knm_ctx *ctx)
 {
-    if (ctx && ctx->blas) {
-        (void)rocblas_destroy_handle(static_cast<rocblas_handle>(ctx->blas));
-        ctx->blas = nullptr;
+    if (ctx && ctx->red_buf) {
+        (void)hipFree(ctx->red_buf);
+        ctx->red_buf = nullptr;
     }
 }
 
@@ -473,46 +672,76 @@ int precond_free(knm_precond *p)
     return KNM_OK;
 }
 
-// Upper Cholesky factor in place, R^T R = A (column-major, leading dimension M), right-looking
-// with wide block rows: factor the diagonal block (rocSOLVER), solve the block row against it
-// (TRSM), downdate the trailing triangle (SYRK, which carries M^3 / 3 of the flop and runs
-// near the fp64 matrix peak at this width).  rocSOLVER's own blocking is much narrower and
-// reaches about half that rate on these sizes.  `info` holds one status word per block row
-// (filled asynchronously); first_bad receives the 1-based index of the first failing pivot, or 0.
-static int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t M, int64_t *info_dev, int64_t info_len,
-                       int64_t *first_bad)
+// Upper Cholesky factor in place, R^T R = A (column-major, leading dimension M): the three-step
+// column update of Sec. 4 (block Cholesky paragraph) on block rows of up to 4096.
+//   Steps 1 and 2 (factor the diagonal tile, solve the block row against it) are carried out
+//   together, left-looking over sub-panels of 512 rows and, inside them, steps of 128 rows: a
+//   row group, from its diagonal to the last column, first loses the products with the rows
+//   above it (one block product, contraction over the rows already done), then the diagonal
+//   block of a step is factorised and inverted by the leaf kernel, then the rest of its rows is
+//   multiplied by that inverse (in place: a 128-row tile of the block product reads exactly
+//   the columns it writes).
+//   Step 3 (trailing update, M^3 / 3 of the flop) is one rank-k launch per block row.
+// `W` is a 128 x 128 scratch block, `bad` a device word initialised by the caller to ~0;
+// first_bad receives the 1-based index of the first failing pivot, or 0.
+constexpr int64_t kSubPanel = 512;
+static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, unsigned long long *bad,
+                              int64_t *first_bad)
 {
     int64_t b = ((M + 7) / 8 + 255) / 256 * 256;
     if (b > 4096) b = 4096;
     const int64_t nb = (M + b - 1) / b;
-    if (nb > info_len) return fail(ctx, KNM_HIP_ERROR, "status buffer too small");
-    const double one = 1.0;
+    const unsigned long long none = ~0ull;
+    hipError_t e = hipMemcpyAsync(bad, &none, sizeof(none), hipMemcpyHostToDevice, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
     for (int64_t k = 0; k < nb; ++k) {
         const int64_t r0 = k * b;
         const int64_t w = (M - r0 < b) ? M - r0 : b;
+        for (int64_t S0 = 0; S0 < w; S0 += kSubPanel) {
+            // the sub-panel's rows lose the products with the block row's rows above them at once
+            // (four tile rows per launch); inside it the 128-row steps only reach back to its top
+            const int64_t sw = (w - S0 < kSubPanel) ? w - S0 : kSubPanel;
+            const int64_t prow = r0 + S0;
+            if (S0 > 0) {
+                const double *above = A + r0 + (size_t)prow * M; // rows r0 .. prow of the columns from `prow` on
+                if (launch_gemm_f64(0, sw, M - prow, S0, -1.0, above, M, above, M, 1.0, A + prow + (size_t)prow * M, M,
+                                    ctx->stream) != hipSuccess)
+                    return fail(ctx, KNM_HIP_ERROR, "block row update launch");
+            }
+            for (int64_t s0 = 0; s0 < sw; s0 += kLeaf) {
+                const int64_t row = prow + s0;
+                const int nbk = (int)((sw - s0 < kLeaf) ? sw - s0 : kLeaf);
+                const int64_t ncols = M - row;
+                double *Ass = A + row + (size_t)row * M;
+                if (s0 > 0) {
+                    const double *above = A + prow + (size_t)row * M;
+                    if (launch_gemm_f64(0, nbk, ncols, s0, -1.0, above, M, above, M, 1.0, Ass, M, ctx->stream) !=
+                        hipSuccess)
+                        return fail(ctx, KNM_HIP_ERROR, "block row update launch");
+                }
+                hipLaunchKernelGGL(potrf_trtri_leaf_kernel, dim3(1), dim3(kLeafThreads), 0, ctx->stream, Ass, M, nbk, W,
+                                   (int64_t)kLeaf, row, bad);
+                if (ncols > nbk) {
+                    double *right = A + row + (size_t)(row + nbk) * M;
+                    if (launch_gemm_f64(0, nbk, ncols - nbk, nbk, 1.0, W, kLeaf, right, M, 0.0, right, M,
+                                        ctx->stream) != hipSuccess)
+                        return fail(ctx, KNM_HIP_ERROR, "block row solve launch");
+                }
+            }
+        }
         const int64_t rest = M - r0 - w;
-        double *Akk = A + r0 + (size_t)r0 * M;
-        if (rocsolver_dpotrf_64(h, rocblas_fill_upper, w, Akk, M, info_dev + k) != rocblas_status_success)
-            return fail(ctx, KNM_HIP_ERROR, "rocsolver_dpotrf");
         if (rest == 0) break;
-        double *Akr = A + r0 + (size_t)(r0 + w) * M; // block row to the right of the diagonal block
-        if (rocblas_dtrsm_64(h, rocblas_side_left, rocblas_fill_upper, rocblas_operation_transpose,
-                             rocblas_diagonal_non_unit, w, rest, &one, Akk, M, Akr, M) != rocblas_status_success)
-            return fail(ctx, KNM_HIP_ERROR, "rocblas_dtrsm");
+        const double *Akr = A + r0 + (size_t)(r0 + w) * M; // block row to the right of the diagonal block
         double *Arr = A + (r0 + w) + (size_t)(r0 + w) * M;
         if (launch_rank_k_upper(0, rest, w, -1.0, Akr, M, nullptr, 0, 1.0, 0.0, Arr, M, ctx->stream) != hipSuccess)
             return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
     }
-    std::vector<int64_t> host(nb, 0);
-    hipError_t e = hipMemcpyAsync(host.data(), info_dev, sizeof(int64_t) * nb, hipMemcpyDeviceToHost, ctx->stream);
+    unsigned long long got = none;
+    e = hipMemcpyAsync(&got, bad, sizeof(got), hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "factorisation status copy", e);
-    *first_bad = 0;
-    for (int64_t k = 0; k < nb; ++k)
-        if (host[k] != 0) {
-            *first_bad = k * b + host[k];
-            break;
-        }
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "factorisation", e);
+    *first_bad = (got == none) ? 0 : (int64_t)got;
     return KNM_OK;
 }
 
@@ -520,14 +749,13 @@ static int chol_upper_blocked(knm_ctx *ctx, rocblas_handle h, double *A, int64_t
 // the inverses of its diagonal blocks.  T is upper triangular, so entry (i, j) of the product
 // only sums over k >= max(i, j): M^3 / 3 flop instead of the M^3 of a dense rank-M update,
 // in one launch of the rank-k kernel, which skips the vanishing part tile by tile.
-static int build_second_factor(knm_ctx *ctx, rocblas_handle h, knm_precond *p, double lambda, const double *dw,
+static int build_second_factor(knm_ctx *ctx, knm_precond *p, double lambda, const double *dw,
                                int64_t *bad_pivot)
 {
     const int64_t M = p->M;
     *bad_pivot = 0;
-    DevBuf info, badbuf;
-    const int64_t info_len = 64;
-    int st = info.alloc(ctx, sizeof(int64_t) * info_len);
+    DevBuf leaf, badbuf;
+    int st = leaf.alloc(ctx, sizeof(double) * kLeaf * kLeaf);
     if (!st) st = badbuf.alloc(ctx, sizeof(unsigned long long));
     if (st) return st;
     if (launch_rank_k_upper(1, M, M, 1.0 / (double)M, p->T, M, dw, 1, 0.0, lambda, p->A, M, ctx->stream) != hipSuccess)
@@ -535,7 +763,7 @@ static int build_second_factor(knm_ctx *ctx, rocblas_handle h, knm_precond *p, d
     const dim3 fb(32, 8);
     const dim3 fg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
     int64_t pivot = 0;
-    st = chol_upper_blocked(ctx, h, p->A, M, info.as<int64_t>(), info_len, &pivot);
+    st = chol_upper_blocked(ctx, p->A, M, leaf.as<double>(), badbuf.as<unsigned long long>(), &pivot);
     if (st) return st;
     if (pivot == 0) {
         const unsigned long long none = ~0ull;
@@ -555,8 +783,11 @@ static int build_second_factor(knm_ctx *ctx, rocblas_handle h, knm_precond *p, d
         return fail(ctx, KNM_NOT_PD, "T D T^T / M + lambda I is not positive definite");
     }
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, 0.0, 1);
-    st = invert_diag_blocks(ctx, h, p, p->A, p->Adinv);
+    DevBuf merge;
+    st = merge.alloc(ctx, sizeof(double) * (size_t)(p->sb / 2) * (size_t)(p->sb / 2));
+    if (!st) st = invert_diag_blocks(ctx, p, p->A, p->Adinv, merge.as<double>());
     if (st) return st;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "second factor"); // scratch is freed on return
     if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "preconditioner kernel launch");
     p->lambda = lambda;
     return KNM_OK;
@@ -573,9 +804,7 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
         return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
     if (M > 2000000000LL / 1) return fail(ctx, KNM_UNSUPPORTED, "M too large");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    rocblas_handle h;
-    int st = blas_handle(ctx, &h);
-    if (st) return st;
+    int st = KNM_OK;
 
     knm_precond *p = new (std::nothrow) knm_precond();
     if (!p) return fail(ctx, KNM_ALLOC, "host allocation");
@@ -592,9 +821,8 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Tdinv), dbytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Adinv), dbytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->xw), sizeof(double) * (size_t)M);
-    DevBuf info;
-    const int64_t info_len = 64; // status words: one per block row of the factorisation (at most 8 + M / 4096)
-    if (e != hipSuccess || info.alloc(ctx, sizeof(int64_t) * info_len)) {
+    DevBuf leaf;
+    if (e != hipSuccess || leaf.alloc(ctx, sizeof(double) * kLeaf * kLeaf)) {
         (void)hipGetLastError();
         precond_free(p);
         return fail(ctx, KNM_ALLOC, "hipMalloc(preconditioner)", e);
@@ -626,11 +854,9 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
         return err;
     };
 
-    // The 64-bit library interfaces are required throughout: M^2 exceeds 2^31 elements for
-    // M > 46340, which the 32-bit interfaces' internal element offsets cannot address.
     int64_t host_info = 0;
     {
-        int st2 = chol_upper_blocked(ctx, h, p->T, M, info.as<int64_t>(), info_len, &host_info);
+        int st2 = chol_upper_blocked(ctx, p->T, M, leaf.as<double>(), badbuf.as<unsigned long long>(), &host_info);
         if (st2) {
             precond_free(p);
             return st2;
@@ -647,14 +873,17 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
     hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->T, M, 0.0, 1);
 
     if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "preconditioner kernel launch");
-    st = invert_diag_blocks(ctx, h, p, p->T, p->Tdinv);
+    DevBuf merge;
+    st = merge.alloc(ctx, sizeof(double) * (size_t)(p->sb / 2) * (size_t)(p->sb / 2));
+    if (!st) st = invert_diag_blocks(ctx, p, p->T, p->Tdinv, merge.as<double>());
+    if (!st && hipStreamSynchronize(ctx->stream) != hipSuccess) st = fail(ctx, KNM_HIP_ERROR, "first factor");
     if (st) {
         precond_free(p);
         return st;
     }
     if (second_factor) {
         int64_t bad = 0;
-        st = build_second_factor(ctx, h, p, lambda, nullptr, &bad);
+        st = build_second_factor(ctx, p, lambda, nullptr, &bad);
         if (st) {
             if (bad_pivot_or_null) *bad_pivot_or_null = -bad;
             precond_free(p);
@@ -721,9 +950,7 @@ int falkon_linop_weighted(knm_ctx *ctx, const knm_precond *p, const float *X, in
         return fail(ctx, KNM_INVALID_ARG, "bad linop argument");
     if (d > knm_max_d() || t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "d or t above compiled maximum");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    rocblas_handle h;
-    int st = blas_handle(ctx, &h);
-    if (st) return st;
+    int st = KNM_OK;
     LinopWork wk;
     DevBuf bc, oc;
     st = wk.alloc(ctx, M, t);
@@ -731,7 +958,7 @@ int falkon_linop_weighted(knm_ctx *ctx, const knm_precond *p, const float *X, in
     if (!st) st = oc.alloc(ctx, sizeof(double) * M * t);
     if (st) return st;
     hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, beta, M, t, bc.as<double>(), 0);
-    st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, bc.as<double>(), t, oc.as<double>(),
+    st = linop_cols(ctx, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, bc.as<double>(), t, oc.as<double>(),
                     dw_or_null);
     if (st) return st;
     hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, oc.as<double>(), M, t, out, 1);
@@ -806,11 +1033,9 @@ int precond_reweight(knm_ctx *ctx, knm_precond *p, double lambda, const double *
     if (bad_pivot_or_null) *bad_pivot_or_null = 0;
     if (!p || !(lambda >= 0.0)) return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    rocblas_handle h;
-    int st = blas_handle(ctx, &h);
-    if (st) return st;
+    int st = KNM_OK;
     int64_t bad = 0;
-    st = build_second_factor(ctx, h, p, lambda, dw_or_null, &bad);
+    st = build_second_factor(ctx, p, lambda, dw_or_null, &bad);
     if (bad_pivot_or_null) *bad_pivot_or_null = -bad;
     return st;
 }
@@ -825,9 +1050,7 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
         return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
     if (d > knm_max_d() || t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "d or t above compiled maximum");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    rocblas_handle h;
-    int st = blas_handle(ctx, &h);
-    if (st) return st;
+    int st = KNM_OK;
 
     using clk = std::chrono::steady_clock;
     auto secs = [](clk::time_point a, clk::time_point b) { return std::chrono::duration<double>(b - a).count(); };
@@ -864,32 +1087,32 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
     if (e == hipSuccess) e = hipMemcpyAsync(dp, dr, sizeof(double) * len, hipMemcpyDeviceToDevice, ctx->stream);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "CG initialisation", e);
 
-    auto blas_ok = [&](rocblas_status s) { return s == rocblas_status_success; };
+    auto vec_ok = [&](int status) { return status == KNM_OK; };
     std::vector<double> rho(t), pq(t);
     for (int c = 0; c < t; ++c) {
-        if (!blas_ok(rocblas_ddot(h, (rocblas_int)M, dr + c * M, 1, dr + c * M, 1, &rho[c])))
-            return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
+        if (!vec_ok(vec_dot(ctx, M, dr + c * M, dr + c * M, &rho[c])))
+            return fail(ctx, KNM_HIP_ERROR, "vector reduction");
         if (resid_norms_or_null) resid_norms_or_null[c] = std::sqrt(rho[c]);
     }
     const clk::time_point t_rhs = clk::now(); // the host-pointer dot products above synchronise
     for (int it = 0; it < iters; ++it) {
-        st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, dp, t, dq);
+        st = linop_cols(ctx, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, dp, t, dq);
         if (st) return st;
         for (int c = 0; c < t; ++c) {
             double *pc = dp + c * M, *qc = dq + c * M, *rc = dr + c * M, *bc = db + c * M;
-            if (!blas_ok(rocblas_ddot(h, (rocblas_int)M, pc, 1, qc, 1, &pq[c]))) return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
+            if (!vec_ok(vec_dot(ctx, M, pc, qc, &pq[c]))) return fail(ctx, KNM_HIP_ERROR, "vector reduction");
             const double a = (pq[c] != 0.0) ? rho[c] / pq[c] : 0.0;
             const double ma = -a;
             double rn = 0.0;
-            if (!blas_ok(rocblas_daxpy(h, (rocblas_int)M, &a, pc, 1, bc, 1)) ||
-                !blas_ok(rocblas_daxpy(h, (rocblas_int)M, &ma, qc, 1, rc, 1)) ||
-                !blas_ok(rocblas_ddot(h, (rocblas_int)M, rc, 1, rc, 1, &rn)))
-                return fail(ctx, KNM_HIP_ERROR, "rocblas CG update");
+            if (!vec_ok(vec_axpy(ctx, M, a, pc, bc)) ||
+                !vec_ok(vec_axpy(ctx, M, ma, qc, rc)) ||
+                !vec_ok(vec_dot(ctx, M, rc, rc, &rn)))
+                return fail(ctx, KNM_HIP_ERROR, "CG vector update");
             const double b = (rho[c] != 0.0) ? rn / rho[c] : 0.0;
             const double one = 1.0;
-            if (!blas_ok(rocblas_dscal(h, (rocblas_int)M, &b, pc, 1)) ||
-                !blas_ok(rocblas_daxpy(h, (rocblas_int)M, &one, rc, 1, pc, 1)))
-                return fail(ctx, KNM_HIP_ERROR, "rocblas CG update");
+            if (!vec_ok(vec_scal(ctx, M, b, pc)) ||
+                !vec_ok(vec_axpy(ctx, M, one, rc, pc)))
+                return fail(ctx, KNM_HIP_ERROR, "CG vector update");
             rho[c] = rn;
             if (resid_norms_or_null) resid_norms_or_null[(int64_t)(it + 1) * t + c] = std::sqrt(rn);
         }
@@ -934,9 +1157,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         if (!(lambdas[k] >= 0.0) || iters[k] <= 0) return fail(ctx, KNM_INVALID_ARG, "bad Newton schedule");
     if (d > knm_max_d()) return fail(ctx, KNM_UNSUPPORTED, "d above compiled maximum");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    rocblas_handle h;
-    int st = blas_handle(ctx, &h);
-    if (st) return st;
+    int st = KNM_OK;
 
     // T depends on the centres only: built once; A is rebuilt per Newton step
     knm_precond *p = nullptr;
@@ -969,7 +1190,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
     hipError_t e = hipMemsetAsync(da, 0, sizeof(double) * M, ctx->stream);
     if (e == hipSuccess) e = hipMemsetAsync(a32.p, 0, sizeof(float) * M, ctx->stream);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
-    auto blas_ok = [&](rocblas_status s) { return s == rocblas_status_success; };
+    auto vec_ok = [&](int status) { return status == KNM_OK; };
     // predictions at the rows and at the centres for the current alpha, and the loss terms
     auto evaluate = [&](bool derivatives, double *mean_loss) -> int {
         int s2 = do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, a32.as<float>(), 1, z.as<float>());
@@ -983,8 +1204,8 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
             for (int64_t o = 0; o < n; o += (1 << 30)) {
                 const int64_t len = (n - o < (1 << 30)) ? n - o : (1 << 30);
                 double part = 0.0;
-                if (!blas_ok(rocblas_dasum(h, (rocblas_int)len, lossv.as<double>() + o, 1, &part)))
-                    return fail(ctx, KNM_HIP_ERROR, "rocblas_dasum");
+                if (!vec_ok(vec_dot(ctx, len, lossv.as<double>() + o, nullptr, &part)))
+                    return fail(ctx, KNM_HIP_ERROR, "loss reduction");
                 total += part;
             }
             *mean_loss = total / (double)n;
@@ -1002,7 +1223,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         hipLaunchKernelGGL(logistic_terms_kernel, grid1(M), dim3(256), 0, ctx->stream, zc.as<float>(), yC, M,
                            (float *)nullptr, (float *)nullptr, dm.as<double>(), (double *)nullptr);
         int64_t bad = 0;
-        st = build_second_factor(ctx, h, p, mu, dm.as<double>(), &bad);
+        st = build_second_factor(ctx, p, mu, dm.as<double>(), &bad);
         if (st) return st;
         // right-hand side  -P^T (K^T g + mu n (K_MM + eps I) alpha)
         st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, g.as<float>(), nullptr, 1, u32.as<float>());
@@ -1016,21 +1237,21 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         if (e == hipSuccess) e = hipMemcpyAsync(dp, dr, sizeof(double) * M, hipMemcpyDeviceToDevice, ctx->stream);
         if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "CG initialisation", e);
         double rho = 0.0;
-        if (!blas_ok(rocblas_ddot(h, (rocblas_int)M, dr, 1, dr, 1, &rho))) return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
+        if (!vec_ok(vec_dot(ctx, M, dr, dr, &rho))) return fail(ctx, KNM_HIP_ERROR, "vector reduction");
         for (int it = 0; it < iters[k]; ++it) {
-            st = linop_cols(ctx, h, p, wk, X, n, d, ldx, C, M, ldc, sigma, mu, dp, 1, dq, dw.as<float>());
+            st = linop_cols(ctx, p, wk, X, n, d, ldx, C, M, ldc, sigma, mu, dp, 1, dq, dw.as<float>());
             if (st) return st;
             double pq = 0.0, rn = 0.0;
-            if (!blas_ok(rocblas_ddot(h, (rocblas_int)M, dp, 1, dq, 1, &pq))) return fail(ctx, KNM_HIP_ERROR, "rocblas_ddot");
+            if (!vec_ok(vec_dot(ctx, M, dp, dq, &pq))) return fail(ctx, KNM_HIP_ERROR, "vector reduction");
             const double a = (pq != 0.0) ? rho / pq : 0.0, ma = -a, one = 1.0;
-            if (!blas_ok(rocblas_daxpy(h, (rocblas_int)M, &a, dp, 1, db, 1)) ||
-                !blas_ok(rocblas_daxpy(h, (rocblas_int)M, &ma, dq, 1, dr, 1)) ||
-                !blas_ok(rocblas_ddot(h, (rocblas_int)M, dr, 1, dr, 1, &rn)))
-                return fail(ctx, KNM_HIP_ERROR, "rocblas CG update");
+            if (!vec_ok(vec_axpy(ctx, M, a, dp, db)) ||
+                !vec_ok(vec_axpy(ctx, M, ma, dq, dr)) ||
+                !vec_ok(vec_dot(ctx, M, dr, dr, &rn)))
+                return fail(ctx, KNM_HIP_ERROR, "CG vector update");
             const double b = (rho != 0.0) ? rn / rho : 0.0;
-            if (!blas_ok(rocblas_dscal(h, (rocblas_int)M, &b, dp, 1)) ||
-                !blas_ok(rocblas_daxpy(h, (rocblas_int)M, &one, dr, 1, dp, 1)))
-                return fail(ctx, KNM_HIP_ERROR, "rocblas CG update");
+            if (!vec_ok(vec_scal(ctx, M, b, dp)) ||
+                !vec_ok(vec_axpy(ctx, M, one, dr, dp)))
+                return fail(ctx, KNM_HIP_ERROR, "CG vector update");
             rho = rn;
         }
         // alpha += T^-1 A^-1 beta
@@ -1038,7 +1259,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         if (!st) st = tri_solve(ctx, p, p->T, p->Tdinv, false, db, 1);
         if (st) return st;
         const double one = 1.0;
-        if (!blas_ok(rocblas_daxpy(h, (rocblas_int)M, &one, db, 1, da, 1))) return fail(ctx, KNM_HIP_ERROR, "rocblas_daxpy");
+        if (!vec_ok(vec_axpy(ctx, M, one, db, da))) return fail(ctx, KNM_HIP_ERROR, "vector update");
         hipLaunchKernelGGL(f64_to_f32_kernel, grid1(M), dim3(256), 0, ctx->stream, da, M, a32.as<float>());
     }
     if (loss_or_null) {
