@@ -97,6 +97,8 @@ struct knm_ctx {
     std::string last_error;
     // partial sums of the solver's fp64 reductions (allocated lazily by knm_solver.hip)
     double *red_buf = nullptr;
+    // second stream for the look-ahead of the blocked factorisation (created lazily by knm_solver.hip)
+    hipStream_t aux_stream = nullptr;
 };
 
 namespace knm {

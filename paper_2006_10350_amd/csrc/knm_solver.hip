@@ -265,53 +265,73 @@ __global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__res
 }
 
 // ---- leaf of the blocked factorisation --------------------------------------------------------
-// One workgroup factorises a diagonal block of order nb <= 128 in LDS (packed upper triangle,
-// right-looking, two barriers per pivot) and inverts the factor there.  Everything above the
-// leaf is products with these small inverses on the matrix cores.
+// One workgroup factorises a diagonal block of order nb <= 128 in LDS (upper triangle packed by
+// rows, right-looking, two barriers per pivot) and inverts the factor in place there.
+// Everything above the leaf is products with these small inverses on the matrix cores.
+// The kernel keeps to 70 KB of LDS so that it can share a CU with a workgroup of the rank-k
+// kernel: during the factorisation's look-ahead it runs beside the trailing update.
 constexpr int kLeaf = 128;
-__device__ __forceinline__ int packed_upper(int i, int j) { return j * (j + 1) / 2 + i; } // i <= j, by columns
-
 constexpr int kLeafThreads = 512;
-// W (nb x nb, column-major, ldw; written whole, zeros below the diagonal) <- inverse of the upper
-// triangular factor R held packed by columns in P, whose reciprocal diagonal is in dinv.  Q is
-// scratch for the inverse packed by ROWS: (j, c), j <= c, at j nb - j (j - 1) / 2 + (c - j).
-// All rows are done in lockstep, last to first:  W[i, c] = -(sum_{i < j <= c} R[i, j] W[j, c]) / R[i, i],
-// so R[i, j] is a broadcast read and W[j, c] is contiguous across the columns c.  A column
-// belongs to four adjacent lanes, which split the sum over j.  kLeafThreads threads, all call.
-// One workgroup has a CU to itself, so the loops are unrolled by hand to keep several LDS
-// reads in flight.
-__device__ __forceinline__ void invert_packed_upper(const double *P, const double *dinv, double *Q, int nb,
-                                                    double *W, int64_t ldw)
+constexpr int kLeafPacked = kLeaf * (kLeaf + 1) / 2;
+
+struct LeafShared {
+    double P[kLeafPacked]; // (i, j), i <= j, at i nb - i (i - 1) / 2 + (j - i)
+    double rowk[kLeaf];
+    double dinv[kLeaf];
+    double rrow[2][kLeaf];
+};
+
+__device__ __forceinline__ int leaf_row_start(int i, int nb) { return i * nb - i * (i - 1) / 2; }
+
+__device__ __forceinline__ void leaf_load(LeafShared &sh, const double *A, int64_t lda, int nb)
 {
-    const int c = threadIdx.x >> 2, part = threadIdx.x & 3;
-    auto row_start = [nb](int j) { return j * nb - j * (j - 1) / 2; };
-    if (c < nb && part == 0) Q[row_start(c)] = dinv[c];
+    for (int e = threadIdx.x; e < nb * kLeaf; e += kLeafThreads) {
+        const int i = e & (kLeaf - 1), j = e >> 7; // column j of the block, row i
+        if (i <= j && i < nb) sh.P[leaf_row_start(i, nb) + (j - i)] = A[i + j * lda];
+    }
+}
+
+// W (nb x nb, column-major, ldw; written whole, zeros below the diagonal) <- inverse of the upper
+// triangular factor R packed in sh.P, whose reciprocal diagonal is in sh.dinv; sh.P is overwritten
+// by the inverse.  Rows are done in lockstep, last to first:
+//   W[i, c] = -(sum_{i < j <= c} R[i, j] W[j, c]) / R[i, i],
+// with row i of R first copied aside (its storage then takes row i of W), so R[i, j] is a
+// broadcast read and W[j, c] is contiguous across the columns c.  A column belongs to four
+// adjacent lanes, which split the sum over j.  One workgroup has its CU nearly to itself, so
+// the loops are unrolled by hand to keep several LDS reads in flight.
+__device__ __forceinline__ void leaf_invert(LeafShared &sh, int nb, double *W, int64_t ldw)
+{
+    const int tid = threadIdx.x;
+    const int c = tid >> 2, part = tid & 3;
     const bool live = c < nb;
+    if (tid == 0) sh.P[leaf_row_start(nb - 1, nb)] = sh.dinv[nb - 1];
     for (int i = nb - 2; i >= 0; --i) {
+        double *rr = sh.rrow[i & 1];
+        const int ri = leaf_row_start(i, nb);
+        if (tid > i && tid < nb) rr[tid] = sh.P[ri + (tid - i)];
+        __syncthreads(); // row i of R is aside, row i + 1 of W is complete
         double s0 = 0.0, s1 = 0.0;
         int j = i + 1 + part;
-        int pr = packed_upper(i, j);       // R[i, j]
-        int pw = row_start(j) + (c - j);   // W[j, c]
-        // j advances by 4: R[i, j] moves by 4 j + 10 entries, W[j, c] by 4 nb - 4 j - 10
+        int pw = leaf_row_start(j, nb) + (c - j); // W[j, c]; four rows on it moves by 4 nb - 4 j - 10
         for (; j + 4 < nb; j += 8) {
-            const int pr1 = pr + 4 * j + 10, pw1 = pw + 4 * nb - 4 * j - 10;
-            const double a0 = (live && j <= c) ? P[pr] * Q[pw] : 0.0;
-            const double a1 = (live && j + 4 <= c) ? P[pr1] * Q[pw1] : 0.0;
+            const int pw1 = pw + 4 * nb - 4 * j - 10;
+            const double a0 = (live && j <= c) ? rr[j] * sh.P[pw] : 0.0;
+            const double a1 = (live && j + 4 <= c) ? rr[j + 4] * sh.P[pw1] : 0.0;
             s0 += a0;
             s1 += a1;
-            pr = pr1 + 4 * (j + 4) + 10;
             pw = pw1 + 4 * nb - 4 * (j + 4) - 10;
         }
-        if (j < nb && live && j <= c) s0 += P[pr] * Q[pw];
+        if (j < nb && live && j <= c) s0 += rr[j] * sh.P[pw];
         double s = s0 + s1;
         s += __shfl_xor(s, 1);
         s += __shfl_xor(s, 2);
-        if (part == 0 && live && c > i) Q[row_start(i) + (c - i)] = -s * dinv[i];
+        if (part == 0 && live && c > i) sh.P[ri + (c - i)] = -s * sh.dinv[i];
+        if (tid == 0) sh.P[ri] = sh.dinv[i];
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < nb * nb; e += blockDim.x) {
-        const int i = e % nb, j = e / nb;
-        W[i + j * ldw] = (i <= j) ? Q[row_start(i) + (j - i)] : 0.0;
+    for (int e = tid; e < nb * kLeaf; e += kLeafThreads) {
+        const int i = e & (kLeaf - 1), j = e >> 7;
+        if (i < nb) W[i + j * ldw] = (i <= j) ? sh.P[leaf_row_start(i, nb) + (j - i)] : 0.0;
     }
 }
 
@@ -322,79 +342,69 @@ __global__ __launch_bounds__(kLeafThreads) void potrf_trtri_leaf_kernel(double *
                                                                        double *__restrict__ W, int64_t ldw,
                                                                        int64_t pivot0, unsigned long long *bad)
 {
-    __shared__ double P[kLeaf * (kLeaf + 1) / 2];
-    __shared__ double Q[kLeaf * (kLeaf + 1) / 2];
-    __shared__ double rowk[kLeaf];
-    __shared__ double dinv[kLeaf];
+    __shared__ LeafShared sh;
     const int tid = threadIdx.x;
-    for (int e = tid; e < nb * nb; e += kLeafThreads) {
-        const int i = e % nb, j = e / nb;
-        if (i <= j) P[packed_upper(i, j)] = A[i + j * lda];
-    }
+    leaf_load(sh, A, lda, nb);
     __syncthreads();
     const int jc = tid & (kLeaf - 1), par = tid >> 7; // trailing update: column of this thread, rows par mod 4
     for (int k = 0; k < nb; ++k) {
-        const double dkk = P[packed_upper(k, k)];
+        const int rk = leaf_row_start(k, nb);
+        const double dkk = sh.P[rk];
         const bool ok = dkk > 0.0 && dkk < 1.0e300;
         const double rinv = ok ? 1.0 / sqrt(dkk) : 1.0;
         if (tid == 0) {
             if (!ok) atomicMin(bad, (unsigned long long)(pivot0 + k + 1));
-            dinv[k] = rinv;
+            sh.dinv[k] = rinv;
         }
         if (tid > k && tid < nb) { // row k, scaled; kept beside the packed copy for the update
-            const double v = P[packed_upper(k, tid)] * rinv;
-            P[packed_upper(k, tid)] = v;
-            rowk[tid] = v;
+            const double v = sh.P[rk + (tid - k)] * rinv;
+            sh.P[rk + (tid - k)] = v;
+            sh.rowk[tid] = v;
         }
         __syncthreads();
         const int j = k + 1 + jc;
         if (j < nb) {
-            const double rj = rowk[j];
-            double *col = P + packed_upper(0, j);
+            const double rj = sh.rowk[j];
             int i = k + 1 + par;
+            int pa = leaf_row_start(i, nb) + (j - i); // (i, j); four rows on it moves by 4 nb - 4 i - 10
             for (; i + 4 <= j; i += 8) {
-                const double u0 = rowk[i], u1 = rowk[i + 4];
-                const double c0 = col[i], c1 = col[i + 4];
-                col[i] = c0 - u0 * rj;
-                col[i + 4] = c1 - u1 * rj;
+                const int pa1 = pa + 4 * nb - 4 * i - 10;
+                const double u0 = sh.rowk[i], u1 = sh.rowk[i + 4];
+                const double c0 = sh.P[pa], c1 = sh.P[pa1];
+                sh.P[pa] = c0 - u0 * rj;
+                sh.P[pa1] = c1 - u1 * rj;
+                pa = pa1 + 4 * nb - 4 * (i + 4) - 10;
             }
-            if (i <= j) col[i] -= rowk[i] * rj;
+            if (i <= j) sh.P[pa] -= sh.rowk[i] * rj;
         }
         __syncthreads();
     }
-    // the diagonal of R: P still holds the pivots before the square root
-    for (int k = tid; k < nb; k += kLeafThreads) P[packed_upper(k, k)] = 1.0 / dinv[k];
-    __syncthreads();
-    for (int e = tid; e < nb * nb; e += kLeafThreads) {
-        const int i = e % nb, j = e / nb;
-        if (i <= j) A[i + j * lda] = P[packed_upper(i, j)];
+    // back to A, with the diagonal of R: sh.P still holds the pivots before the square root
+    for (int e = tid; e < nb * kLeaf; e += kLeafThreads) {
+        const int i = e & (kLeaf - 1), j = e >> 7;
+        if (i <= j && i < nb) A[i + j * lda] = (i == j) ? 1.0 / sh.dinv[i] : sh.P[leaf_row_start(i, nb) + (j - i)];
     }
-    invert_packed_upper(P, dinv, Q, nb, W, ldw);
+    __syncthreads();
+    leaf_invert(sh, nb, W, ldw);
 }
 
-// W <- inverse of the upper triangular nb x nb block at R (one workgroup per diagonal block of a
-// factor: block g at R + g * step_r, its inverse at W + g * step_w)
+// W <- inverse of the upper triangular nb x nb diagonal blocks of a factor R (one workgroup per
+// block): leaf g sits on the diagonal of group g / blocks_per_group, at offset (g % blocks_per_group) * 128
 __global__ __launch_bounds__(kLeafThreads) void trtri_leaf_kernel(const double *__restrict__ R, int64_t ldr, int64_t M,
-                                                        int64_t step_w_block, int blocks_per_group, double *__restrict__ W,
-                                                        int64_t ldw)
+                                                                 int64_t step_w_block, int blocks_per_group,
+                                                                 double *__restrict__ W, int64_t ldw)
 {
-    __shared__ double P[kLeaf * (kLeaf + 1) / 2];
-    __shared__ double Q[kLeaf * (kLeaf + 1) / 2];
-    __shared__ double dinv[kLeaf];
+    __shared__ LeafShared sh;
     const int64_t g = blockIdx.x;
     const int64_t r0 = g * kLeaf;
     const int nb = (int)((M - r0 < kLeaf) ? M - r0 : kLeaf);
     const double *Rb = R + r0 + r0 * ldr;
-    // leaf g sits on the diagonal of group g / blocks_per_group, at offset (g % blocks_per_group) * 128
     const int64_t grp = g / blocks_per_group, off = (g % blocks_per_group) * kLeaf;
     double *Wb = W + grp * step_w_block + off + off * ldw;
-    for (int e = threadIdx.x; e < nb * nb; e += kLeafThreads) {
-        const int i = e % nb, j = e / nb;
-        if (i <= j) P[packed_upper(i, j)] = Rb[i + j * ldr];
-        if (i == j) dinv[i] = 1.0 / Rb[i + j * ldr];
-    }
+    leaf_load(sh, Rb, ldr, nb);
+    for (int k = threadIdx.x; k < nb; k += kLeafThreads) sh.dinv[k] = 1.0 / Rb[k + k * ldr];
     __syncthreads();
-    invert_packed_upper(P, dinv, Q, nb, Wb, ldw);
+    leaf_invert(sh, nb, Wb, ldw);
 }
 
 inline dim3 grid1(int64_t n, int threads = 256) { return dim3((unsigned)((n + threads - 1) / threads)); }
@@ -657,6 +667,10 @@ void knm_solver_release(knm_ctx *ctx)
         (void)hipFree(ctx->red_buf);
         ctx->red_buf = nullptr;
     }
+    if (ctx && ctx->aux_stream) {
+        (void)hipStreamDestroy(ctx->aux_stream);
+        ctx->aux_stream = nullptr;
+    }
 }
 
 int precond_free(knm_precond *p)
@@ -685,6 +699,39 @@ int precond_free(knm_precond *p)
 // `W` is a 128 x 128 scratch block, `bad` a device word initialised by the caller to ~0;
 // first_bad receives the 1-based index of the first failing pivot, or 0.
 constexpr int64_t kSubPanel = 512;
+
+// events without timing, destroyed with the set
+struct EventSet {
+    std::vector<hipEvent_t> ev;
+    ~EventSet()
+    {
+        for (hipEvent_t e : ev)
+            if (e) (void)hipEventDestroy(e);
+    }
+    bool create(int64_t count)
+    {
+        ev.assign((size_t)count, nullptr);
+        for (auto &e : ev)
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return false;
+        return true;
+    }
+    hipEvent_t operator[](int64_t i) const { return ev[(size_t)i]; }
+};
+
+// second stream of the context (default priority, no implicit ordering with the legacy default
+// stream: every dependency is an event), created on first use
+static int aux_stream(knm_ctx *ctx, hipStream_t *out)
+{
+    if (!ctx->aux_stream) {
+        hipStream_t s = nullptr;
+        hipError_t e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipStreamCreateWithFlags", e);
+        ctx->aux_stream = s;
+    }
+    *out = ctx->aux_stream;
+    return KNM_OK;
+}
+
 static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, unsigned long long *bad,
                               int64_t *first_bad)
 {
@@ -694,6 +741,12 @@ static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, uns
     const unsigned long long none = ~0ull;
     hipError_t e = hipMemcpyAsync(bad, &none, sizeof(none), hipMemcpyHostToDevice, ctx->stream);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
+    hipStream_t aux = nullptr;
+    int st = aux_stream(ctx, &aux);
+    if (st) return st;
+    EventSet ev_rows, ev_rest;
+    if (!ev_rows.create(nb) || !ev_rest.create(nb)) return fail(ctx, KNM_HIP_ERROR, "hipEventCreate");
+    std::vector<char> have_rest(nb, 0);
     for (int64_t k = 0; k < nb; ++k) {
         const int64_t r0 = k * b;
         const int64_t w = (M - r0 < b) ? M - r0 : b;
@@ -731,11 +784,38 @@ static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, uns
         }
         const int64_t rest = M - r0 - w;
         if (rest == 0) break;
+        // Step 3 with one block row of look-ahead.  The part of the trailing matrix that the next
+        // block row needs (its own rows) is updated on the main stream, which then goes on to
+        // steps 1 and 2 of that block row; the remainder (most of the flop) runs on the second
+        // stream meanwhile and fills the chip, which those short dependent launches cannot.
+        const int64_t w2 = (rest < b) ? rest : b;
         const double *Akr = A + r0 + (size_t)(r0 + w) * M; // block row to the right of the diagonal block
         double *Arr = A + (r0 + w) + (size_t)(r0 + w) * M;
-        if (launch_rank_k_upper(0, rest, w, -1.0, Akr, M, nullptr, 0, 1.0, 0.0, Arr, M, ctx->stream) != hipSuccess)
+        if (hipEventRecord(ev_rows[k], ctx->stream) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipEventRecord");
+        if (k > 0 && have_rest[k - 1] && hipStreamWaitEvent(ctx->stream, ev_rest[k - 1], 0) != hipSuccess)
+            return fail(ctx, KNM_HIP_ERROR, "hipStreamWaitEvent");
+        if (launch_rank_k_upper(0, w2, w, -1.0, Akr, M, nullptr, 0, 1.0, 0.0, Arr, M, ctx->stream) != hipSuccess)
             return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
+        if (rest > w2) {
+            const double *Akr2 = Akr + (size_t)w2 * M;
+            if (launch_gemm_f64(0, w2, rest - w2, w, -1.0, Akr, M, Akr2, M, 1.0, Arr + (size_t)w2 * M, M, ctx->stream) !=
+                hipSuccess)
+                return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
+            if (hipStreamWaitEvent(aux, ev_rows[k], 0) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipStreamWaitEvent");
+            if (launch_rank_k_upper(0, rest - w2, w, -1.0, Akr2, M, nullptr, 0, 1.0, 0.0, Arr + w2 + (size_t)w2 * M, M,
+                                    aux) != hipSuccess)
+                return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
+            if (hipEventRecord(ev_rest[k], aux) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipEventRecord");
+            have_rest[k] = 1;
+        }
     }
+    // the second stream's last update (its stream order makes it the last of all) before anything else
+    for (int64_t k = nb - 1; k >= 0; --k)
+        if (have_rest[k]) {
+            if (hipStreamWaitEvent(ctx->stream, ev_rest[k], 0) != hipSuccess)
+                return fail(ctx, KNM_HIP_ERROR, "hipStreamWaitEvent");
+            break;
+        }
     unsigned long long got = none;
     e = hipMemcpyAsync(&got, bad, sizeof(got), hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
