@@ -35,7 +35,7 @@ typedef enum {
     KNM_INVALID_ARG = -1, /* null pointer, non-positive size, sigma <= 0, lambda < 0, ld < d */
     KNM_UNSUPPORTED = -2, /* shape outside what the kernels were compiled for (see knm_max_*) */
     KNM_ALLOC = -3,       /* workspace allocation failed */
-    KNM_HIP_ERROR = -4,   /* a HIP / rocBLAS / rocSOLVER call failed; text via knm_last_error */
+    KNM_HIP_ERROR = -4,   /* a HIP runtime call or kernel launch failed; text via knm_last_error */
     KNM_NOT_PD = -5       /* a Cholesky factorisation met a non-positive pivot */
 } knm_status;
 

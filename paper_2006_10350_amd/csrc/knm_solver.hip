@@ -1,10 +1,11 @@
 // Preconditioner, preconditioned operator, conjugate gradient and predictor (Alg. 1).
 //
 // Everything here is fp64 and runs once per fit or is O(M^2) per iteration; the
-// O(n M) work of every iteration is the fp32 kernel product of knm_tile.hip.
-// Factorisations and triangular solves use rocSOLVER / rocBLAS on column-major
-// storage: T and A are upper triangular with T^T T = K_MM + jitter I and
-// A^T A = T T^T / M + lambda I  (Eq. 7 with K_mm = T^T T).
+// O(n M) work of every iteration is the fp32 kernel product of the sweep engines.
+// Storage is column-major: T and A are upper triangular with T^T T = K_MM + jitter I and
+// A^T A = T T^T / M + lambda I  (Eq. 7 with K_mm = T^T T).  The factorisations are the block
+// column update of Sec. 4 on the fp64 matrix-core products of knm_dsyrk.hip and a leaf
+// kernel; the triangular solves, vector updates and reductions are kernels of this file.
 #include <chrono>
 #include <cmath>
 #include <new>
