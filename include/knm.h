@@ -75,6 +75,20 @@ int knm_prod_weighted(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ld
                       const float *C, int64_t M, int64_t ldc, float sigma,
                       const float *dw, const float *V, int t, float *U);
 
+/* The same product for sparse inputs (Sec. 4, "Dealing with sparse datasets"): X (n rows) and C
+ * (M rows) in CSR form over d features, d < 2^31 - 1.
+ *   x_indptr[n + 1], c_indptr[M + 1]: row pointers, starting at 0 and non-decreasing;
+ *   x_indices, c_indices: feature of every stored entry, in [0, d) and strictly increasing
+ *   within a row (canonical CSR: every feature at most once per row); x_values, c_values: fp32.
+ * V (M x t), W_or_null (n x t), U (M x t) as for knm_prod.  The structure is checked on the device before it is used
+ * (KNM_INVALID_ARG).  Only pairs of points that share a feature are visited: the rest of the
+ * kernel matrix is a rank-one matrix and is summed in closed form.  U is accumulated with float
+ * atomics, so its last bits can differ from run to run.  All pointers DEVICE; the call
+ * returns after the product is complete. */
+int knm_prod_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
+                 const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M, int64_t d,
+                 float sigma, const float *V, int t, float *W_or_null, float *U);
+
 /* R[M x t] = K_nm^T Y, the right-hand side of the Nystrom system (Eq. 5; line
  * "R <- ..." of Alg. 1 read as k(X_m, X) y). */
 int knm_t_y(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,

@@ -49,6 +49,7 @@ SIGNATURES = {
     "falkon_linop_weighted": (_int, [_vp, _vp] + _PTS + [_f64, _vp, _vp, _int, _vp]),
     "precond_reweight": (_int, [_vp, _vp, _f64, _vp, ctypes.POINTER(_i64)]),
     "precond_solve": (_int, [_vp, _vp, _int, _vp, _int, _vp]),
+    "knm_prod_csr": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _i64, _f32, _vp, _int, _vp, _vp]),
     "precond_block_product": (_int, [_vp, _int, _i64, _i64, _i64, _f64, _vp, _i64, _vp, _i64, _f64, _vp, _i64]),
     "precond_get_block": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp]),
     "precond_rank_k_update": (_int, [_vp, _int, _i64, _i64, _f64, _vp, _i64, _vp, _int, _f64, _f64, _vp, _i64]),
@@ -234,6 +235,36 @@ def knm_t_y(X, C, sigma: float, Y, ctx: Optional[Context] = None) -> torch.Tenso
     ctx.check(load_library().knm_t_y(ctx._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc, float(sigma),
                                      Y.data_ptr(), t, R.data_ptr()))
     return R[:, 0] if sq else R
+
+
+def _csr_parts(A, name: str):
+    if not (isinstance(A, torch.Tensor) and A.layout == torch.sparse_csr and A.is_cuda and A.dim() == 2):
+        raise TypeError(f"{name} must be a 2-D sparse CSR tensor on the GPU")
+    crow, col, val = A.crow_indices(), A.col_indices(), A.values()
+    if crow.dtype != torch.int64 or col.dtype != torch.int64 or val.dtype != torch.float32:
+        raise TypeError(f"{name} must have int64 indices and float32 values")
+    return crow.contiguous(), col.contiguous(), val.contiguous()
+
+
+def knm_prod_csr(X, C, sigma: float, V, return_w: bool = False, ctx: Optional[Context] = None):
+    """U = K^T (K V) for sparse CSR X (n x d) and C (M x d) (float32 values, int64 indices)."""
+    ctx = ctx or default_context()
+    xr, xc, xv = _csr_parts(X, "X")
+    cr, cc, cv = _csr_parts(C, "C")
+    n, d = X.shape
+    M = C.shape[0]
+    if C.shape[1] != d:
+        raise ValueError("X and C must have the same number of features")
+    V, t, sq = _cols(V, M, "V")
+    U = torch.empty(M, t, device=V.device, dtype=torch.float32)
+    W = torch.empty(n, t, device=V.device, dtype=torch.float32) if return_w else None
+    ctx.check(load_library().knm_prod_csr(ctx._h, xr.data_ptr(), xc.data_ptr(), xv.data_ptr(), n, cr.data_ptr(),
+                                          cc.data_ptr(), cv.data_ptr(), M, d, float(sigma), V.data_ptr(), t,
+                                          W.data_ptr() if return_w else None, U.data_ptr()))
+    if sq:
+        U = U[:, 0]
+        W = W[:, 0] if return_w else None
+    return (U, W) if return_w else U
 
 
 class Preconditioner:

@@ -1,0 +1,417 @@
+// Kernel product for sparse inputs (Sec. 4, "Dealing with sparse datasets"): X and C in CSR
+// form with a feature dimension far beyond what a dense row can hold.
+//
+// The kernel matrix of sparse points is still dense, but most of it is a rank-one matrix:
+// with a_i = exp(-|x_i|^2 / 2 sigma^2), b_j = exp(-|c_j|^2 / 2 sigma^2) and g_ij = x_i . c_j,
+//   K_ij = a_i b_j exp(g_ij / sigma^2),
+// and g_ij = 0 unless the two points share a feature.  So
+//   (K v)_i   = a_i sum_j b_j v_j  +  sum_{j : g_ij != 0} (K_ij - a_i b_j) v_j
+//   (K^T w)_j = b_j sum_i a_i w_i  +  sum_{i : g_ij != 0} (K_ij - a_i b_j) w_i,
+// exactly (up to rounding order), and only the pairs that share a feature are ever visited:
+// no dense n x M sweep, no dense tile of the cross term.  The paper forms the dense kernel
+// blocks from a sparse matrix product; this is the same result with the all-ones part of
+// exp(g / sigma^2) summed in closed form.
+//
+// One wavefront owns a row of X at a time and a private dense accumulator over the M centres
+// (in HBM / L2): it walks the row's features, and for each feature the list of centres that
+// have it (C transposed to CSC once per call), adding x_if c_jf into the accumulator; a second
+// walk takes every touched entry out again (atomic exchange with zero, so a centre reached
+// through several features is consumed once), turns it into K_ij - a_i b_j and adds it to the
+// row's sum (row sweep) or scatters it into U (column sweep, float atomics: the summation
+// order, hence the last bits, vary from run to run).  Long centre lists are walked by the whole
+// wavefront, short ones by the lane that owns the feature.
+#include "knm_internal.h"
+
+namespace knm {
+namespace {
+
+constexpr int kSpThreads = 256;
+constexpr int kSpWaves = kSpThreads / 64;
+constexpr int kLongList = 32;     // centre lists at least this long are walked by the whole wavefront
+constexpr int kScanChunk = 4096;  // elements per workgroup of the prefix sum
+
+// flag |= 1 if the CSR structure is not usable: indptr not starting at 0, decreasing, running
+// past nnz, or the column indices of a row not strictly increasing inside [0, d)
+__global__ void csr_check_kernel(const int64_t *__restrict__ indptr, const int64_t *__restrict__ indices, int64_t rows,
+                                 int64_t nnz, int64_t d, int *flag)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= rows) return;
+    const int64_t p0 = indptr[r], p1 = indptr[r + 1];
+    bool bad = (r == 0 && p0 != 0) || p0 < 0 || p1 < p0 || p1 > nnz;
+    if (!bad) {
+        int64_t prev = -1;
+        for (int64_t p = p0; p < p1; ++p) {
+            const int64_t c = indices[p];
+            if (c <= prev || c >= d) bad = true; // strictly increasing: every feature at most once in a row
+            prev = c;
+        }
+    }
+    if (bad) atomicOr(flag, 1);
+}
+
+__global__ void row_norms_kernel(const int64_t *__restrict__ indptr, const float *__restrict__ values, int64_t rows,
+                                 float *__restrict__ norms)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= rows) return;
+    double s = 0.0;
+    for (int64_t p = indptr[r]; p < indptr[r + 1]; ++p) s += (double)values[p] * (double)values[p];
+    norms[r] = (float)s;
+}
+
+__global__ void col_count_kernel(const int64_t *__restrict__ indices, int64_t nnz, int *__restrict__ count)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < nnz) atomicAdd(&count[indices[p]], 1);
+}
+
+// exclusive prefix sum of `in` (len entries) in three passes; out may alias in
+__global__ __launch_bounds__(256) void scan_local_kernel(const int *__restrict__ in, int64_t len, int *__restrict__ out,
+                                                        int *__restrict__ sums)
+{
+    __shared__ int sh[256];
+    constexpr int kPer = kScanChunk / 256;
+    const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kPer;
+    int v[kPer];
+    int tot = 0;
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+        v[e] = (base + e < len) ? in[base + e] : 0;
+        tot += v[e];
+    }
+    sh[threadIdx.x] = tot;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        const int add = ((int)threadIdx.x >= off) ? sh[threadIdx.x - off] : 0;
+        __syncthreads();
+        sh[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int run = sh[threadIdx.x] - tot; // exclusive prefix of this thread inside the workgroup
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+        if (base + e < len) out[base + e] = run;
+        run += v[e];
+    }
+    if (threadIdx.x == 255) sums[blockIdx.x] = sh[255];
+}
+
+__global__ __launch_bounds__(256) void scan_sums_kernel(int *__restrict__ sums, int64_t count)
+{
+    __shared__ int sh[256];
+    const int64_t per = (count + 255) / 256;
+    const int64_t b0 = (int64_t)threadIdx.x * per;
+    int tot = 0;
+    for (int64_t i = b0; i < b0 + per && i < count; ++i) tot += sums[i];
+    sh[threadIdx.x] = tot;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        const int add = ((int)threadIdx.x >= off) ? sh[threadIdx.x - off] : 0;
+        __syncthreads();
+        sh[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int run = sh[threadIdx.x] - tot;
+    for (int64_t i = b0; i < b0 + per && i < count; ++i) {
+        const int v = sums[i];
+        sums[i] = run;
+        run += v;
+    }
+}
+
+__global__ void scan_add_kernel(int *__restrict__ out, int64_t len, const int *__restrict__ sums)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < len) out[i] += sums[i / kScanChunk];
+}
+
+// scatter the entries of C (CSR) into its CSC image; cursor starts as a copy of col_ptr
+__global__ void csc_fill_kernel(const int64_t *__restrict__ indptr, const int64_t *__restrict__ indices,
+                                const float *__restrict__ values, int64_t rows, int *__restrict__ cursor,
+                                int *__restrict__ csc_row, float *__restrict__ csc_val)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= rows) return;
+    for (int64_t p = indptr[r]; p < indptr[r + 1]; ++p) {
+        const int pos = atomicAdd(&cursor[indices[p]], 1);
+        csc_row[pos] = (int)r;
+        csc_val[pos] = values[p];
+    }
+}
+
+// e[r] = exp(-norm[r] / 2 sigma^2)
+__global__ void norm_factor_kernel(const float *__restrict__ norms, int64_t rows, float inv2s2, float *__restrict__ e)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows) e[r] = expf(-norms[r] * inv2s2);
+}
+
+// partial sums of e[r] * vec[r * ldv] in fp64, fixed order: one partial per workgroup
+__global__ __launch_bounds__(256) void weighted_sum_kernel(const float *__restrict__ e, const float *__restrict__ vec,
+                                                          int64_t ldv, int64_t rows, double *__restrict__ part)
+{
+    __shared__ double sh[256];
+    double s = 0.0;
+    for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < rows; r += (int64_t)gridDim.x * 256)
+        s += (double)e[r] * (double)vec[r * ldv];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) part[blockIdx.x] = sh[0];
+}
+
+// out[j * ldo] = e[j] * s  (the rank-one part of the column sweep, which the scatter then adds to)
+__global__ void rank_one_init_kernel(const float *__restrict__ e, int64_t rows, double s, float *__restrict__ out,
+                                     int64_t ldo)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows) out[r * ldo] = (float)((double)e[r] * s);
+}
+
+struct SparseArgs {
+    const int64_t *x_indptr, *x_indices;
+    const float *x_values;
+    int64_t n, M;
+    const int *col_ptr, *csc_row;
+    const float *csc_val;
+    const float *xn, *cn; // squared norms
+    const float *xa;      // a_i
+    const float *vec;     // row sweep: v over the centres; column sweep: w over the rows
+    int64_t ldv;
+    float *out;           // row sweep: W over the rows; column sweep: U over the centres (pre-set to the rank-one part)
+    int64_t ldo;
+    float *acc;           // one dense accumulator of M floats per wavefront of the grid, all zero
+    float inv2s2, inv_s2;
+    double s_rank_one;    // row sweep: sum_j b_j v_j
+};
+
+// K_ij - a_i b_j from the dot product g and the squared norms
+__device__ __forceinline__ float pair_excess(float g, float xn, float cn, float inv2s2, float inv_s2)
+{
+    const float e0 = (xn + cn) * inv2s2;
+    if (e0 < 80.0f) return expf(-e0) * expm1f(g * inv_s2);
+    return expf(g * inv_s2 - e0); // a_i b_j has underflowed: the excess is K_ij itself
+}
+
+template <int COLUMN_SWEEP>
+__global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * kSpWaves + (threadIdx.x >> 6);
+    const int64_t waves = (int64_t)gridDim.x * kSpWaves;
+    float *acc = a.acc + wave * a.M;
+    for (int64_t row = wave; row < a.n; row += waves) {
+        const int64_t p0 = a.x_indptr[row], p1 = a.x_indptr[row + 1];
+        const float xn = a.xn[row];
+        const float wrow = COLUMN_SWEEP ? a.vec[row * a.ldv] : 0.0f;
+        float sum = 0.0f;
+        // pass 0 adds x_if c_jf into the accumulator; pass 1 takes every touched entry out again
+        for (int pass = 0; pass < 2; ++pass) {
+            for (int64_t p = p0; p < p1; p += 64) {
+                const bool mine = p + lane < p1;
+                int q0 = 0, q1 = 0;
+                float xv = 0.0f;
+                if (mine) {
+                    const int64_t col = a.x_indices[p + lane];
+                    xv = a.x_values[p + lane];
+                    q0 = a.col_ptr[col];
+                    q1 = a.col_ptr[col + 1];
+                }
+                const int len = q1 - q0;
+                unsigned long long longs = __ballot(len >= kLongList);
+                while (longs) {
+                    const int src = __ffsll((long long)longs) - 1;
+                    longs &= longs - 1;
+                    const int b0 = __shfl(q0, src), b1 = __shfl(q1, src);
+                    const float bx = __shfl(xv, src);
+                    for (int q = b0 + lane; q < b1; q += 64) {
+                        const int j = a.csc_row[q];
+                        if (pass == 0) {
+                            atomicAdd(&acc[j], bx * a.csc_val[q]);
+                        } else {
+                            const float g = atomicExch(&acc[j], 0.0f);
+                            if (g != 0.0f) {
+                                const float ex = pair_excess(g, xn, a.cn[j], a.inv2s2, a.inv_s2);
+                                if (COLUMN_SWEEP) atomicAdd(&a.out[j * a.ldo], ex * wrow);
+                                else sum += ex * a.vec[j * a.ldv];
+                            }
+                        }
+                    }
+                }
+                if (len < kLongList)
+                    for (int q = q0; q < q1; ++q) {
+                        const int j = a.csc_row[q];
+                        if (pass == 0) {
+                            atomicAdd(&acc[j], xv * a.csc_val[q]);
+                        } else {
+                            const float g = atomicExch(&acc[j], 0.0f);
+                            if (g != 0.0f) {
+                                const float ex = pair_excess(g, xn, a.cn[j], a.inv2s2, a.inv_s2);
+                                if (COLUMN_SWEEP) atomicAdd(&a.out[j * a.ldo], ex * wrow);
+                                else sum += ex * a.vec[j * a.ldv];
+                            }
+                        }
+                    }
+            }
+            __threadfence(); // every lane's updates of the accumulator are done before the next pass or row
+        }
+        if (!COLUMN_SWEEP) {
+            sum += __shfl_xor(sum, 32);
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 8);
+            sum += __shfl_xor(sum, 4);
+            sum += __shfl_xor(sum, 2);
+            sum += __shfl_xor(sum, 1);
+            if (lane == 0) a.out[row * a.ldo] = (float)((double)a.xa[row] * a.s_rank_one) + sum;
+        }
+    }
+}
+
+inline dim3 grid_for(int64_t n, int threads = 256) { return dim3((unsigned)((n + threads - 1) / threads)); }
+
+struct DevMem {
+    void *p = nullptr;
+    ~DevMem() { if (p) (void)hipFree(p); }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 1); }
+    template <class T> T *as() { return static_cast<T *>(p); }
+};
+
+} // namespace
+
+// W (n x t, ldw = t) = K V and U (M x t) = K^T W for CSR X (n rows) and C (M rows) over d features.
+// W_or_null may be null (a workspace is used).  Validates the CSR structure on the device first.
+int sparse_prod(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
+                const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M, int64_t d,
+                float sigma, const float *V, int t, float *W_or_null, float *U)
+{
+    hipStream_t st = ctx->stream;
+    int64_t nnz_x = 0, nnz_c = 0;
+    hipError_t e = hipMemcpyAsync(&nnz_x, x_indptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(&nnz_c, c_indptr + M, sizeof(int64_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "reading the CSR sizes", e);
+    if (nnz_x < 0 || nnz_c < 0 || nnz_c >= 0x7fffffffLL) return fail(ctx, KNM_INVALID_ARG, "bad CSR size");
+
+    // grid: enough wavefronts to fill the chip, each with a private accumulator over the centres
+    int64_t wgs = (n + kSpWaves - 1) / kSpWaves;
+    if (wgs > 1024) wgs = 1024;
+    const int64_t waves = wgs * kSpWaves;
+
+    DevMem flag, xn, cn, xa, cb, col_ptr, cursor, sums, csc_row, csc_val, acc, part, wtmp;
+    const int64_t scan_blocks = (d + 1 + kScanChunk - 1) / kScanChunk;
+    if (flag.alloc(sizeof(int)) != hipSuccess || xn.alloc(sizeof(float) * n) != hipSuccess ||
+        cn.alloc(sizeof(float) * M) != hipSuccess || xa.alloc(sizeof(float) * n) != hipSuccess ||
+        cb.alloc(sizeof(float) * M) != hipSuccess || col_ptr.alloc(sizeof(int) * (d + 1)) != hipSuccess ||
+        cursor.alloc(sizeof(int) * (d + 1)) != hipSuccess || sums.alloc(sizeof(int) * scan_blocks) != hipSuccess ||
+        csc_row.alloc(sizeof(int) * nnz_c) != hipSuccess || csc_val.alloc(sizeof(float) * nnz_c) != hipSuccess ||
+        acc.alloc(sizeof(float) * waves * M) != hipSuccess || part.alloc(sizeof(double) * 257) != hipSuccess ||
+        (!W_or_null && wtmp.alloc(sizeof(float) * n * t) != hipSuccess)) {
+        (void)hipGetLastError();
+        return fail(ctx, KNM_ALLOC, "hipMalloc(sparse workspace)");
+    }
+    float *W = W_or_null ? W_or_null : wtmp.as<float>();
+
+    // structure check before anything indexes with the caller's numbers
+    int bad = 0;
+    e = hipMemsetAsync(flag.p, 0, sizeof(int), st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+    hipLaunchKernelGGL(csr_check_kernel, grid_for(n), dim3(256), 0, st, x_indptr, x_indices, n, nnz_x, d, flag.as<int>());
+    hipLaunchKernelGGL(csr_check_kernel, grid_for(M), dim3(256), 0, st, c_indptr, c_indices, M, nnz_c, d, flag.as<int>());
+    e = hipMemcpyAsync(&bad, flag.p, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "CSR check", e);
+    if (bad) return fail(ctx, KNM_INVALID_ARG, "CSR structure: row pointers not monotone from 0, or feature ids of a row not strictly increasing in [0, d)");
+
+    const float inv2s2 = 1.0f / (2.0f * sigma * sigma), inv_s2 = 1.0f / (sigma * sigma);
+    hipLaunchKernelGGL(row_norms_kernel, grid_for(n), dim3(256), 0, st, x_indptr, x_values, n, xn.as<float>());
+    hipLaunchKernelGGL(row_norms_kernel, grid_for(M), dim3(256), 0, st, c_indptr, c_values, M, cn.as<float>());
+    hipLaunchKernelGGL(norm_factor_kernel, grid_for(n), dim3(256), 0, st, xn.as<float>(), n, inv2s2, xa.as<float>());
+    hipLaunchKernelGGL(norm_factor_kernel, grid_for(M), dim3(256), 0, st, cn.as<float>(), M, inv2s2, cb.as<float>());
+
+    // C transposed: centre lists per feature
+    e = hipMemsetAsync(col_ptr.p, 0, sizeof(int) * (d + 1), st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+    if (nnz_c > 0)
+        hipLaunchKernelGGL(col_count_kernel, grid_for(nnz_c), dim3(256), 0, st, c_indices, nnz_c, col_ptr.as<int>());
+    hipLaunchKernelGGL(scan_local_kernel, dim3((unsigned)scan_blocks), dim3(256), 0, st, col_ptr.as<int>(), d + 1,
+                       col_ptr.as<int>(), sums.as<int>());
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, st, sums.as<int>(), scan_blocks);
+    hipLaunchKernelGGL(scan_add_kernel, grid_for(d + 1), dim3(256), 0, st, col_ptr.as<int>(), d + 1, sums.as<int>());
+    e = hipMemcpyAsync(cursor.p, col_ptr.p, sizeof(int) * (d + 1), hipMemcpyDeviceToDevice, st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
+    hipLaunchKernelGGL(csc_fill_kernel, grid_for(M), dim3(256), 0, st, c_indptr, c_indices, c_values, M, cursor.as<int>(),
+                       csc_row.as<int>(), csc_val.as<float>());
+    e = hipMemsetAsync(acc.p, 0, sizeof(float) * waves * M, st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+
+    SparseArgs a;
+    a.x_indptr = x_indptr;
+    a.x_indices = x_indices;
+    a.x_values = x_values;
+    a.n = n;
+    a.M = M;
+    a.col_ptr = col_ptr.as<int>();
+    a.csc_row = csc_row.as<int>();
+    a.csc_val = csc_val.as<float>();
+    a.xn = xn.as<float>();
+    a.cn = cn.as<float>();
+    a.xa = xa.as<float>();
+    a.acc = acc.as<float>();
+    a.inv2s2 = inv2s2;
+    a.inv_s2 = inv_s2;
+    // fixed-order fp64 sum of 256 partials, finished on the host
+    auto rank_one_sum = [&](const float *ev, const float *vec, int64_t ldv, int64_t rows, double *out) -> int {
+        double host[256];
+        hipLaunchKernelGGL(weighted_sum_kernel, dim3(256), dim3(256), 0, st, ev, vec, ldv, rows, part.as<double>());
+        hipError_t err = hipMemcpyAsync(host, part.p, sizeof(double) * 256, hipMemcpyDeviceToHost, st);
+        if (err == hipSuccess) err = hipStreamSynchronize(st);
+        if (err != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "rank-one sum", err);
+        double s = 0.0;
+        for (int i = 0; i < 256; ++i) s += host[i];
+        *out = s;
+        return KNM_OK;
+    };
+    for (int c = 0; c < t; ++c) {
+        double s = 0.0;
+        int stat = rank_one_sum(cb.as<float>(), V + c, t, M, &s);
+        if (stat) return stat;
+        a.vec = V + c;
+        a.ldv = t;
+        a.out = W + c;
+        a.ldo = t;
+        a.s_rank_one = s;
+        hipLaunchKernelGGL(sparse_sweep_kernel<0>, dim3((unsigned)wgs), dim3(kSpThreads), 0, st, a);
+        stat = rank_one_sum(xa.as<float>(), W + c, t, n, &s);
+        if (stat) return stat;
+        hipLaunchKernelGGL(rank_one_init_kernel, grid_for(M), dim3(256), 0, st, cb.as<float>(), M, s, U + c, (int64_t)t);
+        a.vec = W + c;
+        a.out = U + c;
+        a.s_rank_one = 0.0;
+        hipLaunchKernelGGL(sparse_sweep_kernel<1>, dim3((unsigned)wgs), dim3(kSpThreads), 0, st, a);
+    }
+    e = hipStreamSynchronize(st); // the workspace is freed on return
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "sparse product", e);
+    return KNM_OK;
+}
+
+} // namespace knm
+
+extern "C" int knm_prod_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values,
+                            int64_t n, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values,
+                            int64_t M, int64_t d, float sigma, const float *V, int t, float *W_or_null, float *U)
+{
+    using namespace knm;
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!x_indptr || !c_indptr || !V || !U || n <= 0 || M <= 0 || d <= 0 || t <= 0 || !(sigma > 0.0f))
+        return fail(ctx, KNM_INVALID_ARG, "bad shape or pointer");
+    if (d >= 0x7fffffffLL || M >= 0x7fffffffLL) return fail(ctx, KNM_UNSUPPORTED, "d or M beyond 2^31 - 2");
+    if (t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "t above compiled maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    return sparse_prod(ctx, x_indptr, x_indices, x_values, n, c_indptr, c_indices, c_values, M, d, sigma, V, t,
+                       W_or_null, U);
+}

@@ -177,3 +177,38 @@ def probe_vector(M: int, t: int, kind: str = "normal", device="cpu", seed: int =
         v[j % M, :] = 1.0
         return v
     raise KeyError(kind)
+
+
+def sparse_inputs(n: int, M: int, d: int, nnz_per_row: float = 40.0, skew: float = 5.0, seed: int = 77,
+                  device="cpu") -> dict:
+    """Sparse rows shaped like n-gram count vectors (the paper's sparse text workload: about 1e6
+    reviews over about 1e7 3-gram features): row lengths lognormal around `nnz_per_row`, feature
+    ids with a heavy head (id = floor(d u^skew), u uniform: a few features occur in a large
+    share of the rows, most in almost none), small integer counts as values, feature ids
+    strictly increasing within a row.  The M centres are rows of X.
+    Returns CSR pieces (int64 row pointers and feature ids, float32 values) for X and C."""
+    device = torch.device(device)
+    g = _gen(device, seed)
+    lengths = torch.exp(math.log(nnz_per_row) + 0.5 * torch.randn(n, generator=g, device=device)).round().clamp(min=0)
+    lengths = lengths.to(torch.int64)
+    lengths[::97] = 0  # some empty rows
+    draws = int(lengths.sum())
+    u = torch.rand(draws, generator=g, device=device, dtype=torch.float64)
+    col = (d * u.pow(skew)).to(torch.int64).clamp(max=d - 1)
+    cnt = torch.randint(1, 4, (draws,), generator=g, device=device).to(torch.float32)
+    row = torch.arange(n, device=device).repeat_interleave(lengths)
+    # canonical CSR: a feature drawn several times in a row becomes one entry with the counts added
+    key, inverse = torch.unique(row * d + col, sorted=True, return_inverse=True)
+    val = torch.zeros(key.numel(), device=device, dtype=torch.float32).index_add_(0, inverse, cnt)
+    row, col = key // d, key % d
+    lengths = torch.bincount(row, minlength=n)
+    crow = torch.zeros(n + 1, dtype=torch.int64, device=device)
+    crow[1:] = torch.cumsum(lengths, 0)
+    pick = torch.randperm(n, generator=g, device=device)[:M].sort().values
+    len_c = lengths[pick]
+    crow_c = torch.zeros(M + 1, dtype=torch.int64, device=device)
+    crow_c[1:] = torch.cumsum(len_c, 0)
+    nnz_c = int(crow_c[-1])
+    src = crow[pick].repeat_interleave(len_c) + (torch.arange(nnz_c, device=device) - crow_c[:-1].repeat_interleave(len_c))
+    return {"x_indptr": crow, "x_indices": col, "x_values": val, "c_indptr": crow_c, "c_indices": col[src],
+            "c_values": val[src], "n": n, "M": M, "d": d, "centre_rows": pick}

@@ -1,0 +1,109 @@
+"""Sparse-input product (CSR X and C) against the oracle's dense definition on the densified inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def rel_l2(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def _dense(indptr, indices, values, rows, d):
+    out = np.zeros((rows, d), dtype=np.float32)
+    r = np.repeat(np.arange(rows), np.diff(indptr))
+    out[r, indices] = values
+    return out
+
+
+def _csr(indptr, indices, values, rows, d):
+    return torch.sparse_csr_tensor(indptr.cuda(), indices.cuda(), values.cuda(), size=(rows, d), check_invariants=False)
+
+
+def _case(n, M, d, nnz, seed):
+    s = synth.sparse_inputs(n, M, d, nnz_per_row=nnz, seed=seed)
+    Xd = _dense(s["x_indptr"].numpy(), s["x_indices"].numpy(), s["x_values"].numpy(), n, d)
+    Cd = _dense(s["c_indptr"].numpy(), s["c_indices"].numpy(), s["c_values"].numpy(), M, d)
+    X = _csr(s["x_indptr"], s["x_indices"], s["x_values"], n, d)
+    C = _csr(s["c_indptr"], s["c_indices"], s["c_values"], M, d)
+    return s, X, C, Xd, Cd
+
+
+# sigma = 8: typical |x|^2 / 2 sigma^2 around 1 (the rank-one part matters); sigma = 1: a_i b_j underflows
+# and only the pairs that share features survive (a centre against its own row gives exactly 1)
+@pytest.mark.parametrize("n,M,d,nnz,sigma", [(3000, 400, 5000, 30.0, 8.0), (1500, 300, 800, 12.0, 3.0),
+                                             (2000, 256, 3000, 40.0, 1.0), (130, 7, 64, 5.0, 4.0)])
+def test_sparse_product_matches_dense_oracle(knm, n, M, d, nnz, sigma):
+    s, X, C, Xd, Cd = _case(n, M, d, nnz, seed=n + M)
+    v = synth.probe_vector(M, 1, "normal", device="cuda")
+    U, W = knm.knm_prod_csr(X, C, sigma, v, return_w=True)
+    Uo, Wo = oracle.knm_prod(Xd, Cd, sigma, v.cpu().numpy(), return_w=True)
+    assert rel_l2(W.cpu().numpy(), Wo) < 1e-5
+    assert rel_l2(U.cpu().numpy(), Uo) < 1e-5
+
+
+def test_sparse_product_several_columns_and_no_w(knm):
+    n, M, d, sigma = 1200, 200, 2000, 6.0
+    s, X, C, Xd, Cd = _case(n, M, d, 25.0, seed=5)
+    V = synth.probe_vector(M, 3, "normal", device="cuda")
+    U = knm.knm_prod_csr(X, C, sigma, V)
+    Uo = oracle.knm_prod(Xd, Cd, sigma, V.cpu().numpy())
+    assert U.shape == (M, 3)
+    assert rel_l2(U.cpu().numpy(), Uo) < 1e-5
+
+
+def test_feature_ids_spread_over_fifty_million_columns(knm):
+    """The same problem with its features renamed injectively into [0, 5e7): the kernel only sees
+    which features two points share, so the product must not change (the dense oracle cannot
+    hold 5e7 columns; it evaluates the compact problem)."""
+    n, M, d, sigma = 2000, 300, 4000, 7.0
+    s, X, C, Xd, Cd = _case(n, M, d, 30.0, seed=9)
+    big = 50_000_000
+    rename = torch.from_numpy(np.sort(np.random.default_rng(3).choice(big, size=d, replace=False))).to(torch.int64)
+    Xb = _csr(s["x_indptr"], rename[s["x_indices"]], s["x_values"], n, big)
+    Cb = _csr(s["c_indptr"], rename[s["c_indices"]], s["c_values"], M, big)
+    v = synth.probe_vector(M, 1, "normal", device="cuda")
+    U, W = knm.knm_prod_csr(Xb, Cb, sigma, v, return_w=True)
+    Uo, Wo = oracle.knm_prod(Xd, Cd, sigma, v.cpu().numpy(), return_w=True)
+    assert rel_l2(W.cpu().numpy(), Wo) < 1e-5
+    assert rel_l2(U.cpu().numpy(), Uo) < 1e-5
+
+
+def test_all_rows_empty_is_the_rank_one_matrix(knm):
+    """No stored entry anywhere: every point is the origin, K is all ones."""
+    n, M, d = 70, 9, 1000
+    X = _csr(torch.zeros(n + 1, dtype=torch.int64), torch.zeros(0, dtype=torch.int64), torch.zeros(0), n, d)
+    C = _csr(torch.zeros(M + 1, dtype=torch.int64), torch.zeros(0, dtype=torch.int64), torch.zeros(0), M, d)
+    v = synth.probe_vector(M, 1, "normal", device="cuda")
+    U, W = knm.knm_prod_csr(X, C, 2.0, v, return_w=True)
+    sv = float(v.sum())
+    assert np.allclose(W.cpu().numpy(), sv, rtol=1e-6, atol=1e-6)
+    assert np.allclose(U.cpu().numpy(), n * sv, rtol=1e-6, atol=1e-5)
+
+
+def test_sparse_product_rejects_bad_structure(knm):
+    n, M, d = 50, 8, 100
+    s = synth.sparse_inputs(n, M, d, nnz_per_row=6.0, seed=2)
+    C = _csr(s["c_indptr"], s["c_indices"], s["c_values"], M, d)
+    v = synth.probe_vector(M, 1, "normal", device="cuda")
+    bad_col = s["x_indices"].clone()
+    bad_col[3] = d  # one past the last feature
+    with pytest.raises(knm.KnmError):
+        knm.knm_prod_csr(_csr(s["x_indptr"], bad_col, s["x_values"], n, d), C, 2.0, v)
+    twice = s["x_indices"].clone()
+    first = int(s["x_indptr"][1])  # row 1 has entries (row 0 is empty by construction)
+    twice[first + 1] = twice[first]  # the same feature twice in a row
+    with pytest.raises(knm.KnmError):
+        knm.knm_prod_csr(_csr(s["x_indptr"], twice, s["x_values"], n, d), C, 2.0, v)
+    bad_ptr = s["x_indptr"].clone()
+    bad_ptr[5] = bad_ptr[6] + 1  # decreasing
+    with pytest.raises(knm.KnmError):
+        knm.knm_prod_csr(_csr(bad_ptr, s["x_indices"], s["x_values"], n, d), C, 2.0, v)
+    with pytest.raises(TypeError):
+        knm.knm_prod_csr(torch.zeros(n, d, device="cuda"), C, 2.0, v)
