@@ -19,7 +19,10 @@
 // through several features is consumed once), turns it into K_ij - a_i b_j and adds it to the
 // row's sum (row sweep) or scatters it into U (column sweep, float atomics: the summation
 // order, hence the last bits, vary from run to run).  Long centre lists are walked by the whole
-// wavefront, short ones by the lane that owns the feature.
+// wavefront, short ones by the lane that owns the feature.  The additions are the hardware's
+// fp32 atomic add (the accumulators and U live in ordinary device memory).
+#include <vector>
+
 #include "knm_internal.h"
 
 namespace knm {
@@ -29,6 +32,7 @@ constexpr int kSpThreads = 256;
 constexpr int kSpWaves = kSpThreads / 64;
 constexpr int kLongList = 32;     // centre lists at least this long are walked by the whole wavefront
 constexpr int kScanChunk = 4096;  // elements per workgroup of the prefix sum
+constexpr int64_t kFillGroup = 128; // rows of C per launch of the CSC fill
 
 // flag |= 1 if the CSR structure is not usable: indptr not starting at 0, decreasing, running
 // past nnz, or the column indices of a row not strictly increasing inside [0, d)
@@ -126,18 +130,25 @@ __global__ void scan_add_kernel(int *__restrict__ out, int64_t len, const int *_
     if (i < len) out[i] += sums[i / kScanChunk];
 }
 
-// scatter the entries of C (CSR) into its CSC image; cursor starts as a copy of col_ptr
+// scatter the entries of rows [row0, row1) of C (CSR) into its CSC image; cursor starts as a copy
+// of col_ptr.  Launched for one group of rows after the other, so that a feature's centre list
+// comes out ordered by group: neighbouring list entries then update neighbouring accumulator
+// entries (the same cache lines) when the whole wavefront walks a long list.
 __global__ void csc_fill_kernel(const int64_t *__restrict__ indptr, const int64_t *__restrict__ indices,
-                                const float *__restrict__ values, int64_t rows, int *__restrict__ cursor,
-                                int *__restrict__ csc_row, float *__restrict__ csc_val)
+                                const float *__restrict__ values, int64_t row0, int64_t row1, int64_t p0, int64_t p1,
+                                int *__restrict__ cursor, int *__restrict__ csc_row, float *__restrict__ csc_val)
 {
-    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= rows) return;
-    for (int64_t p = indptr[r]; p < indptr[r + 1]; ++p) {
-        const int pos = atomicAdd(&cursor[indices[p]], 1);
-        csc_row[pos] = (int)r;
-        csc_val[pos] = values[p];
+    const int64_t p = p0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; // one stored entry of the group
+    if (p >= p1) return;
+    int64_t lo = row0, hi = row1; // its row: the last r in [row0, row1) with indptr[r] <= p
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (indptr[mid] <= p) lo = mid;
+        else hi = mid;
     }
+    const int pos = atomicAdd(&cursor[indices[p]], 1);
+    csc_row[pos] = (int)lo;
+    csc_val[pos] = values[p];
 }
 
 // e[r] = exp(-norm[r] / 2 sigma^2)
@@ -231,12 +242,12 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
                     for (int q = b0 + lane; q < b1; q += 64) {
                         const int j = a.csc_row[q];
                         if (pass == 0) {
-                            atomicAdd(&acc[j], bx * a.csc_val[q]);
+                            unsafeAtomicAdd(&acc[j], bx * a.csc_val[q]);
                         } else {
                             const float g = atomicExch(&acc[j], 0.0f);
                             if (g != 0.0f) {
                                 const float ex = pair_excess(g, xn, a.cn[j], a.inv2s2, a.inv_s2);
-                                if (COLUMN_SWEEP) atomicAdd(&a.out[j * a.ldo], ex * wrow);
+                                if (COLUMN_SWEEP) unsafeAtomicAdd(&a.out[j * a.ldo], ex * wrow);
                                 else sum += ex * a.vec[j * a.ldv];
                             }
                         }
@@ -246,12 +257,12 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
                     for (int q = q0; q < q1; ++q) {
                         const int j = a.csc_row[q];
                         if (pass == 0) {
-                            atomicAdd(&acc[j], xv * a.csc_val[q]);
+                            unsafeAtomicAdd(&acc[j], xv * a.csc_val[q]);
                         } else {
                             const float g = atomicExch(&acc[j], 0.0f);
                             if (g != 0.0f) {
                                 const float ex = pair_excess(g, xn, a.cn[j], a.inv2s2, a.inv_s2);
-                                if (COLUMN_SWEEP) atomicAdd(&a.out[j * a.ldo], ex * wrow);
+                                if (COLUMN_SWEEP) unsafeAtomicAdd(&a.out[j * a.ldo], ex * wrow);
                                 else sum += ex * a.vec[j * a.ldv];
                             }
                         }
@@ -298,7 +309,7 @@ int sparse_prod(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices,
 
     // grid: enough wavefronts to fill the chip, each with a private accumulator over the centres
     int64_t wgs = (n + kSpWaves - 1) / kSpWaves;
-    if (wgs > 1024) wgs = 1024;
+    if (wgs > 2048) wgs = 2048; // 8 workgroups per CU: the sweep is bound by memory latency
     const int64_t waves = wgs * kSpWaves;
 
     DevMem flag, xn, cn, xa, cb, col_ptr, cursor, sums, csc_row, csc_val, acc, part, wtmp;
@@ -343,8 +354,17 @@ int sparse_prod(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices,
     hipLaunchKernelGGL(scan_add_kernel, grid_for(d + 1), dim3(256), 0, st, col_ptr.as<int>(), d + 1, sums.as<int>());
     e = hipMemcpyAsync(cursor.p, col_ptr.p, sizeof(int) * (d + 1), hipMemcpyDeviceToDevice, st);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
-    hipLaunchKernelGGL(csc_fill_kernel, grid_for(M), dim3(256), 0, st, c_indptr, c_indices, c_values, M, cursor.as<int>(),
-                       csc_row.as<int>(), csc_val.as<float>());
+    std::vector<int64_t> c_ptr_host((size_t)M + 1);
+    e = hipMemcpyAsync(c_ptr_host.data(), c_indptr, sizeof(int64_t) * (M + 1), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "reading the row pointers of C", e);
+    for (int64_t r0 = 0; r0 < M; r0 += kFillGroup) {
+        const int64_t r1 = (r0 + kFillGroup < M) ? r0 + kFillGroup : M;
+        const int64_t q0 = c_ptr_host[(size_t)r0], q1 = c_ptr_host[(size_t)r1]; // checked: monotone, within nnz
+        if (q1 > q0)
+            hipLaunchKernelGGL(csc_fill_kernel, grid_for(q1 - q0), dim3(256), 0, st, c_indptr, c_indices, c_values, r0, r1,
+                               q0, q1, cursor.as<int>(), csc_row.as<int>(), csc_val.as<float>());
+    }
     e = hipMemsetAsync(acc.p, 0, sizeof(float) * waves * M, st);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
 
