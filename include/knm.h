@@ -89,6 +89,12 @@ int knm_prod_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices
                  const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M, int64_t d,
                  float sigma, const float *V, int t, float *W_or_null, float *U);
 
+/* W[n x t] = k(X, C) V for CSR X and C (the predictor of Eq. 4 on sparse points); arguments as
+ * for knm_prod_csr. */
+int knm_v_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
+              const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M, int64_t d,
+              float sigma, const float *V, int t, float *W);
+
 /* R[M x t] = K_nm^T Y, the right-hand side of the Nystrom system (Eq. 5; line
  * "R <- ..." of Alg. 1 read as k(X_m, X) y). */
 int knm_t_y(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
@@ -103,6 +109,11 @@ int knm_t_y(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
 int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma,
                   double lambda, double jitter, knm_precond **out, int64_t *bad_pivot_or_null);
 int precond_free(knm_precond *p);
+/* The same preconditioner for CSR centres (M rows over d features, as for knm_prod_csr): k(C, C) is
+ * formed in fp64 from the squared norms and the sparse dot products of the centres. */
+int precond_build_csr(knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values,
+                      int64_t M, int64_t d, float sigma, double lambda, double jitter, knm_precond **out,
+                      int64_t *bad_pivot_or_null);
 /* Copy the factors to HOST buffers of M*M doubles each (row-major, upper triangular,
  * strict lower triangle zero); either may be NULL.  For tests and inspection. */
 int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, double *A_host);
@@ -179,6 +190,13 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
                const float *Y, int t, const float *C, int64_t M, int64_t ldc,
                float sigma, double lambda, double jitter, int iters,
                float *alpha, double *resid_norms_or_null);
+
+/* falkon_fit for CSR X (n rows) and CSR centres (M rows) over d features (Sec. 4, "Dealing with
+ * sparse datasets"); CSR arguments as for knm_prod_csr, everything else as for falkon_fit. */
+int falkon_fit_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
+                   const float *Y, int t, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values,
+                   int64_t M, int64_t d, float sigma, double lambda, double jitter, int iters, float *alpha,
+                   double *resid_norms_or_null);
 
 /* Approximate Newton method for the logistic loss l(z, y) = log(1 + exp(-y z)), y = +-1
  * (Appendix "Logistic Falkon Algorithm", Alg. 2).  The schedule of regularisers is not given in

@@ -50,6 +50,11 @@ SIGNATURES = {
     "precond_reweight": (_int, [_vp, _vp, _f64, _vp, ctypes.POINTER(_i64)]),
     "precond_solve": (_int, [_vp, _vp, _int, _vp, _int, _vp]),
     "knm_prod_csr": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _i64, _f32, _vp, _int, _vp, _vp]),
+    "knm_v_csr": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _i64, _f32, _vp, _int, _vp]),
+    "precond_build_csr": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _f32, _f64, _f64, ctypes.POINTER(_vp),
+                                 ctypes.POINTER(_i64)]),
+    "falkon_fit_csr": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _int, _vp, _vp, _vp, _i64, _i64, _f32, _f64, _f64, _int,
+                              _vp, _vp]),
     "precond_block_product": (_int, [_vp, _int, _i64, _i64, _i64, _f64, _vp, _i64, _vp, _i64, _f64, _vp, _i64]),
     "precond_get_block": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp]),
     "precond_rank_k_update": (_int, [_vp, _int, _i64, _i64, _f64, _vp, _i64, _vp, _int, _f64, _f64, _vp, _i64]),
@@ -265,6 +270,44 @@ def knm_prod_csr(X, C, sigma: float, V, return_w: bool = False, ctx: Optional[Co
         U = U[:, 0]
         W = W[:, 0] if return_w else None
     return (U, W) if return_w else U
+
+
+def knm_v_csr(X, C, sigma: float, V, ctx: Optional[Context] = None) -> torch.Tensor:
+    """W = K V for sparse CSR X and C (also the predictor: V = alpha)."""
+    ctx = ctx or default_context()
+    xr, xc, xv = _csr_parts(X, "X")
+    cr, cc, cv = _csr_parts(C, "C")
+    n, d = X.shape
+    M = C.shape[0]
+    if C.shape[1] != d:
+        raise ValueError("X and C must have the same number of features")
+    V, t, sq = _cols(V, M, "V")
+    W = torch.empty(n, t, device=V.device, dtype=torch.float32)
+    ctx.check(load_library().knm_v_csr(ctx._h, xr.data_ptr(), xc.data_ptr(), xv.data_ptr(), n, cr.data_ptr(),
+                                       cc.data_ptr(), cv.data_ptr(), M, d, float(sigma), V.data_ptr(), t, W.data_ptr()))
+    return W[:, 0] if sq else W
+
+
+def falkon_fit_csr(X, Y, C, sigma: float, lam: float, iters: int, jitter: float = 0.0, return_resid: bool = False,
+                   ctx: Optional[Context] = None):
+    """falkon_fit for sparse CSR X and C."""
+    import numpy as np
+
+    ctx = ctx or default_context()
+    xr, xc, xv = _csr_parts(X, "X")
+    cr, cc, cv = _csr_parts(C, "C")
+    n, d = X.shape
+    M = C.shape[0]
+    if C.shape[1] != d:
+        raise ValueError("X and C must have the same number of features")
+    Y, t, sq = _cols(Y, n, "Y")
+    alpha = torch.empty(M, t, device=Y.device, dtype=torch.float32)
+    resid = np.zeros((iters + 1, t), dtype=np.float64)
+    ctx.check(load_library().falkon_fit_csr(ctx._h, xr.data_ptr(), xc.data_ptr(), xv.data_ptr(), n, Y.data_ptr(), t,
+                                            cr.data_ptr(), cc.data_ptr(), cv.data_ptr(), M, d, float(sigma), float(lam),
+                                            float(jitter), int(iters), alpha.data_ptr(), resid.ctypes.data))
+    out = alpha[:, 0] if sq else alpha
+    return (out, resid) if return_resid else out
 
 
 class Preconditioner:

@@ -75,6 +75,25 @@ hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, 
 hipError_t launch_gemm_f64(int a_nt, int64_t ni, int64_t nj, int64_t K, double alpha, const double *A, int64_t lda,
                            const double *B, int64_t ldb, double beta, double *C, int64_t ldc, hipStream_t stream);
 
+// Sparse inputs (knm_sparse.hip): the two sweeps of one (X, C, sigma) for CSR X and C, prepared once
+// (structure check, norms, centre lists per feature, accumulators) and then applied any number
+// of times; and the fp64 kernel matrix of CSR centres for the preconditioner.
+struct SparseProducts {
+    struct Impl;
+    Impl *impl;
+    SparseProducts();
+    ~SparseProducts();
+    SparseProducts(const SparseProducts &) = delete;
+    SparseProducts &operator=(const SparseProducts &) = delete;
+    int prepare(struct ::knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
+                const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M, int64_t d,
+                float sigma);
+    int v(const float *V, int t, float *W);                       // W (n x t) = K V
+    int t_w(const float *W, const float *wgt, int t, float *U);   // U (M x t) = K^T (wgt .* W)
+};
+int sparse_kmm(struct ::knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M,
+               int64_t d, float sigma, double jitter, double *K);
+
 } // namespace knm
 
 struct knm_ctx {

@@ -8,6 +8,7 @@
 // kernel; the triangular solves, vector updates and reductions are kernels of this file.
 #include <chrono>
 #include <cmath>
+#include <functional>
 #include <new>
 #include <vector>
 
@@ -625,12 +626,33 @@ struct LinopWork {
     }
 };
 
+// The two sweeps of one (X, C, sigma), whatever the storage of the points: W (n x t) = K V and
+// U (M x t) = K^T (wgt .* W) (wgt over the rows of X, or null)
+struct KernelOps {
+    int64_t n = 0, M = 0;
+    std::function<int(const float *V, int t, float *W)> v;
+    std::function<int(const float *W, const float *wgt, int t, float *U)> t_w;
+};
+
+KernelOps dense_ops(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M, int64_t ldc,
+                    float sigma)
+{
+    KernelOps ops;
+    ops.n = n;
+    ops.M = M;
+    ops.v = [=](const float *V, int t, float *W) { return do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, V, t, W); };
+    ops.t_w = [=](const float *W, const float *wgt, int t, float *U) {
+        return do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, W, wgt, t, U);
+    };
+    return ops;
+}
+
 // out <- A^-T ( T^-T K^T D K T^-1 A^-1 beta + lambda n A^-1 beta );  beta, out column-major, may not alias;
 // D = diag(wgt) over the rows of X, identity if wgt is null
-int linop_cols(knm_ctx *ctx, const knm_precond *p, LinopWork &wk, const float *X, int64_t n, int d,
-               int64_t ldx, const float *C, int64_t M, int64_t ldc, float sigma, double lambda, const double *beta,
-               int t, double *out, const float *wgt = nullptr)
+int linop_cols(knm_ctx *ctx, const knm_precond *p, LinopWork &wk, const KernelOps &ops, double lambda,
+               const double *beta, int t, double *out, const float *wgt = nullptr)
 {
+    const int64_t n = ops.n, M = ops.M;
     const size_t bytes = sizeof(double) * M * t;
     double *v = wk.v.as<double>();
     hipError_t e = hipMemcpyAsync(v, beta, bytes, hipMemcpyDeviceToDevice, ctx->stream);
@@ -645,9 +667,9 @@ int linop_cols(knm_ctx *ctx, const knm_precond *p, LinopWork &wk, const float *X
     // c = K_nm^T (K_nm z), the O(n M) step
     st = ensure(ctx, &ctx->w_buf, &ctx->w_bytes, sizeof(float) * (size_t)n * t);
     if (st) return st;
-    st = do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, wk.z32.as<float>(), t, ctx->w_buf);
+    st = ops.v(wk.z32.as<float>(), t, ctx->w_buf);
     if (st) return st;
-    st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, ctx->w_buf, wgt, t, wk.u32.as<float>());
+    st = ops.t_w(ctx->w_buf, wgt, t, wk.u32.as<float>());
     if (st) return st;
     hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(M * t), dim3(256), 0, ctx->stream, wk.u32.as<float>(), M, t, out);
     st = tri_solve(ctx, p, p->T, p->Tdinv, true, out, t); // T^-T c
@@ -874,15 +896,15 @@ static int build_second_factor(knm_ctx *ctx, knm_precond *p, double lambda, cons
     return KNM_OK;
 }
 
-static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma, double lambda,
+// fill_kmm writes the upper triangle of K_MM + jitter I (column-major, leading dimension M) into its argument
+static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(double *)> &fill_kmm, double lambda,
                               double jitter, bool second_factor, knm_precond **out, int64_t *bad_pivot_or_null)
 {
     if (!ctx) return KNM_INVALID_ARG;
     if (!out) return fail(ctx, KNM_INVALID_ARG, "null output");
     *out = nullptr;
     if (bad_pivot_or_null) *bad_pivot_or_null = 0;
-    if (!C || M <= 0 || d <= 0 || ldc < d || !(sigma > 0.0f) || !(lambda >= 0.0) || !(jitter >= 0.0))
-        return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
+    if (M <= 0 || !(lambda >= 0.0) || !(jitter >= 0.0)) return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
     if (M > 2000000000LL / 1) return fail(ctx, KNM_UNSUPPORTED, "M too large");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
     int st = KNM_OK;
@@ -913,11 +935,11 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
         return fail(ctx, status, what);
     };
 
-    const dim3 tb(32, 8);
-    const dim3 tg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
-    const double inv2s2 = 1.0 / (2.0 * (double)sigma * (double)sigma);
-    hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, inv2s2, jitter, p->T);
-    if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "kmm_kernel launch");
+    st = fill_kmm(p->T);
+    if (st) {
+        precond_free(p);
+        return st;
+    }
 
     DevBuf badbuf;
     if (badbuf.alloc(ctx, sizeof(unsigned long long))) return bail(KNM_ALLOC, "hipMalloc");
@@ -975,10 +997,37 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
     return KNM_OK;
 }
 
+static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma, double lambda,
+                              double jitter, bool second_factor, knm_precond **out, int64_t *bad_pivot_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!C || M <= 0 || d <= 0 || ldc < d || !(sigma > 0.0f))
+        return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
+    auto fill = [=](double *K) {
+        const dim3 tb(32, 8);
+        const dim3 tg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
+        const double inv2s2 = 1.0 / (2.0 * (double)sigma * (double)sigma);
+        hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, inv2s2, jitter, K);
+        return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "kmm_kernel launch");
+    };
+    return precond_build_from(ctx, M, fill, lambda, jitter, second_factor, out, bad_pivot_or_null);
+}
+
 int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma, double lambda,
                   double jitter, knm_precond **out, int64_t *bad_pivot_or_null)
 {
     return precond_build_impl(ctx, C, M, d, ldc, sigma, lambda, jitter, true, out, bad_pivot_or_null);
+}
+
+int precond_build_csr(knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M,
+                      int64_t d, float sigma, double lambda, double jitter, knm_precond **out,
+                      int64_t *bad_pivot_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!c_indptr || M <= 0 || d <= 0 || d >= 0x7fffffffLL || !(sigma > 0.0f))
+        return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
+    auto fill = [=](double *K) { return sparse_kmm(ctx, c_indptr, c_indices, c_values, M, d, sigma, jitter, K); };
+    return precond_build_from(ctx, M, fill, lambda, jitter, true, out, bad_pivot_or_null);
 }
 
 int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, double *A_host)
@@ -1039,7 +1088,7 @@ int falkon_linop_weighted(knm_ctx *ctx, const knm_precond *p, const float *X, in
     if (!st) st = oc.alloc(ctx, sizeof(double) * M * t);
     if (st) return st;
     hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, beta, M, t, bc.as<double>(), 0);
-    st = linop_cols(ctx, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, bc.as<double>(), t, oc.as<double>(),
+    st = linop_cols(ctx, p, wk, dense_ops(ctx, X, n, d, ldx, C, M, ldc, sigma), lambda, bc.as<double>(), t, oc.as<double>(),
                     dw_or_null);
     if (st) return st;
     hipLaunchKernelGGL(f64_rows_to_cols, grid1(M * t), dim3(256), 0, ctx->stream, oc.as<double>(), M, t, out, 1);
@@ -1121,29 +1170,20 @@ int precond_reweight(knm_ctx *ctx, knm_precond *p, double lambda, const double *
     return st;
 }
 
-int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *Y, int t, const float *C,
-               int64_t M, int64_t ldc, float sigma, double lambda, double jitter, int iters, float *alpha,
-               double *resid_norms_or_null)
+// Alg. 1 from the right-hand side on, with the preconditioner built: exactly `iters` steps of
+// preconditioned CG on the operator of Eq. 9, then alpha = T^-1 A^-1 beta.  Takes ownership of p.
+static int fit_core(knm_ctx *ctx, const KernelOps &ops, knm_precond *p, const float *Y, int t, double lambda, int iters,
+                    float *alpha, double *resid_norms_or_null, std::chrono::steady_clock::time_point t_start)
 {
-    if (!ctx) return KNM_INVALID_ARG;
-    if (!X || !Y || !C || !alpha || n <= 0 || M <= 0 || d <= 0 || t <= 0 || iters <= 0 || ldx < d || ldc < d ||
-        !(sigma > 0.0f) || !(lambda >= 0.0) || !(jitter >= 0.0))
-        return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
-    if (d > knm_max_d() || t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "d or t above compiled maximum");
-    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    int st = KNM_OK;
-
     using clk = std::chrono::steady_clock;
     auto secs = [](clk::time_point a, clk::time_point b) { return std::chrono::duration<double>(b - a).count(); };
-    const clk::time_point t_start = clk::now();
-    knm_precond *p = nullptr;
-    st = precond_build(ctx, C, M, d, ldc, sigma, lambda, jitter, &p, nullptr); // synchronises
-    if (st) return st;
     const clk::time_point t_precond = clk::now();
     struct Guard {
         knm_precond *p;
         ~Guard() { precond_free(p); }
     } guard{p};
+    const int64_t M = ops.M;
+    int st = KNM_OK;
 
     const int64_t len = M * t;
     LinopWork wk;
@@ -1158,7 +1198,7 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
     double *db = beta.as<double>(), *dr = r.as<double>(), *dp = pv.as<double>(), *dq = q.as<double>();
 
     // rhs = A^-T T^-T K_nm^T Y
-    st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, Y, nullptr, t, r32.as<float>());
+    st = ops.t_w(Y, nullptr, t, r32.as<float>());
     if (st) return st;
     hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(len), dim3(256), 0, ctx->stream, r32.as<float>(), M, t, dr);
     st = tri_solve(ctx, p, p->T, p->Tdinv, true, dr, t);
@@ -1177,7 +1217,7 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
     }
     const clk::time_point t_rhs = clk::now(); // the host-pointer dot products above synchronise
     for (int it = 0; it < iters; ++it) {
-        st = linop_cols(ctx, p, wk, X, n, d, ldx, C, M, ldc, sigma, lambda, dp, t, dq);
+        st = linop_cols(ctx, p, wk, ops, lambda, dp, t, dq);
         if (st) return st;
         for (int c = 0; c < t; ++c) {
             double *pc = dp + c * M, *qc = dq + c * M, *rc = dr + c * M, *bc = db + c * M;
@@ -1210,6 +1250,70 @@ int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
     ctx->fit_seconds[1] = secs(t_precond, t_rhs);
     ctx->fit_seconds[2] = secs(t_rhs, t_iters);
     ctx->fit_seconds[3] = secs(t_iters, clk::now());
+    return KNM_OK;
+}
+
+int falkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *Y, int t, const float *C,
+               int64_t M, int64_t ldc, float sigma, double lambda, double jitter, int iters, float *alpha,
+               double *resid_norms_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!X || !Y || !C || !alpha || n <= 0 || M <= 0 || d <= 0 || t <= 0 || iters <= 0 || ldx < d || ldc < d ||
+        !(sigma > 0.0f) || !(lambda >= 0.0) || !(jitter >= 0.0))
+        return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
+    if (d > knm_max_d() || t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "d or t above compiled maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    const std::chrono::steady_clock::time_point t_start = std::chrono::steady_clock::now();
+    knm_precond *p = nullptr;
+    int st = precond_build(ctx, C, M, d, ldc, sigma, lambda, jitter, &p, nullptr); // synchronises
+    if (st) return st;
+    return fit_core(ctx, dense_ops(ctx, X, n, d, ldx, C, M, ldc, sigma), p, Y, t, lambda, iters, alpha,
+                    resid_norms_or_null, t_start);
+}
+
+int falkon_fit_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
+                   const float *Y, int t, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values,
+                   int64_t M, int64_t d, float sigma, double lambda, double jitter, int iters, float *alpha,
+                   double *resid_norms_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!x_indptr || !c_indptr || !Y || !alpha || n <= 0 || M <= 0 || d <= 0 || t <= 0 || iters <= 0 ||
+        !(sigma > 0.0f) || !(lambda >= 0.0) || !(jitter >= 0.0))
+        return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
+    if (d >= 0x7fffffffLL || M >= 0x7fffffffLL || t > knm_max_t())
+        return fail(ctx, KNM_UNSUPPORTED, "d, M or t above the supported maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    const std::chrono::steady_clock::time_point t_start = std::chrono::steady_clock::now();
+    SparseProducts sp; // outlives the fit: the sweeps use its workspace
+    int st = sp.prepare(ctx, x_indptr, x_indices, x_values, n, c_indptr, c_indices, c_values, M, d, sigma);
+    if (st) return st;
+    knm_precond *p = nullptr;
+    st = precond_build_csr(ctx, c_indptr, c_indices, c_values, M, d, sigma, lambda, jitter, &p, nullptr);
+    if (st) return st;
+    KernelOps ops;
+    ops.n = n;
+    ops.M = M;
+    ops.v = [&sp](const float *V, int tt, float *W) { return sp.v(V, tt, W); };
+    ops.t_w = [&sp](const float *W, const float *wgt, int tt, float *U) { return sp.t_w(W, wgt, tt, U); };
+    return fit_core(ctx, ops, p, Y, t, lambda, iters, alpha, resid_norms_or_null, t_start);
+}
+
+int knm_v_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
+              const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M, int64_t d,
+              float sigma, const float *V, int t, float *W)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!x_indptr || !c_indptr || !V || !W || n <= 0 || M <= 0 || d <= 0 || t <= 0 || !(sigma > 0.0f))
+        return fail(ctx, KNM_INVALID_ARG, "bad shape or pointer");
+    if (d >= 0x7fffffffLL || M >= 0x7fffffffLL || t > knm_max_t())
+        return fail(ctx, KNM_UNSUPPORTED, "d, M or t above the supported maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    SparseProducts sp;
+    int st = sp.prepare(ctx, x_indptr, x_indices, x_values, n, c_indptr, c_indices, c_values, M, d, sigma);
+    if (!st) st = sp.v(V, t, W);
+    if (st) return st;
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "knm_v_csr", e);
     return KNM_OK;
 }
 
@@ -1320,7 +1424,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         double rho = 0.0;
         if (!vec_ok(vec_dot(ctx, M, dr, dr, &rho))) return fail(ctx, KNM_HIP_ERROR, "vector reduction");
         for (int it = 0; it < iters[k]; ++it) {
-            st = linop_cols(ctx, p, wk, X, n, d, ldx, C, M, ldc, sigma, mu, dp, 1, dq, dw.as<float>());
+            st = linop_cols(ctx, p, wk, dense_ops(ctx, X, n, d, ldx, C, M, ldc, sigma), mu, dp, 1, dq, dw.as<float>());
             if (st) return st;
             double pq = 0.0, rn = 0.0;
             if (!vec_ok(vec_dot(ctx, M, dp, dq, &pq))) return fail(ctx, KNM_HIP_ERROR, "vector reduction");

@@ -284,6 +284,78 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
 
 inline dim3 grid_for(int64_t n, int threads = 256) { return dim3((unsigned)((n + threads - 1) / threads)); }
 
+// fp64 entries of the centres' kernel matrix, for the preconditioner: row i of the upper triangle
+// (column-major K, leading dimension M) = exp(-(|c_i|^2 + |c_j|^2 - 2 g_ij) / 2 sigma^2) + jitter [i == j],
+// j >= i, with g_ij accumulated in a private fp64 accumulator exactly as in the sweeps (every
+// entry of the accumulator is read and cleared when the row is written out).
+__global__ __launch_bounds__(kSpThreads) void sparse_kmm_kernel(const int64_t *__restrict__ c_indptr,
+                                                               const int64_t *__restrict__ c_indices,
+                                                               const float *__restrict__ c_values, int64_t M,
+                                                               const int *__restrict__ col_ptr,
+                                                               const int *__restrict__ csc_row,
+                                                               const float *__restrict__ csc_val,
+                                                               const double *__restrict__ cn, double inv2s2,
+                                                               double jitter, double *__restrict__ acc_all,
+                                                               double *__restrict__ K)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * kSpWaves + (threadIdx.x >> 6);
+    const int64_t waves = (int64_t)gridDim.x * kSpWaves;
+    double *acc = acc_all + wave * M;
+    for (int64_t row = wave; row < M; row += waves) {
+        const int64_t p0 = c_indptr[row], p1 = c_indptr[row + 1];
+        for (int64_t p = p0; p < p1; p += 64) {
+            const bool mine = p + lane < p1;
+            int q0 = 0, q1 = 0;
+            double xv = 0.0;
+            if (mine) {
+                const int64_t col = c_indices[p + lane];
+                xv = (double)c_values[p + lane];
+                q0 = col_ptr[col];
+                q1 = col_ptr[col + 1];
+            }
+            const int len = q1 - q0;
+            unsigned long long longs = __ballot(len >= kLongList);
+            while (longs) {
+                const int src = __ffsll((long long)longs) - 1;
+                longs &= longs - 1;
+                const int b0 = __shfl(q0, src), b1 = __shfl(q1, src);
+                const double bx = __shfl(xv, src);
+                for (int q = b0 + lane; q < b1; q += 64) unsafeAtomicAdd(&acc[csc_row[q]], bx * (double)csc_val[q]);
+            }
+            if (len < kLongList)
+                for (int q = q0; q < q1; ++q) unsafeAtomicAdd(&acc[csc_row[q]], xv * (double)csc_val[q]);
+        }
+        __threadfence();
+        const double ci = cn[row];
+        for (int64_t j = lane; j < M; j += 64) {
+            // written by atomics (at the L2): read and cleared there too, past the first-level cache
+            const double g = __hip_atomic_load(&acc[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (g != 0.0) __hip_atomic_store(&acc[j], 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (j >= row) K[row + j * M] = exp(-(ci + cn[j] - 2.0 * g) * inv2s2) + (j == row ? jitter : 0.0);
+        }
+        __threadfence();
+    }
+}
+
+__global__ void row_norms_f64_kernel(const int64_t *__restrict__ indptr, const float *__restrict__ values, int64_t rows,
+                                     double *__restrict__ norms)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= rows) return;
+    double s = 0.0;
+    for (int64_t p = indptr[r]; p < indptr[r + 1]; ++p) s += (double)values[p] * (double)values[p];
+    norms[r] = s;
+}
+
+// out[r] = w[r] * x[r * ldx]
+__global__ void weigh_kernel(const float *__restrict__ x, int64_t ldx, const float *__restrict__ w, int64_t rows,
+                             float *__restrict__ out)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows) out[r] = w[r] * x[r * ldx];
+}
+
 struct DevMem {
     void *p = nullptr;
     ~DevMem() { if (p) (void)hipFree(p); }
@@ -291,101 +363,93 @@ struct DevMem {
     template <class T> T *as() { return static_cast<T *>(p); }
 };
 
-} // namespace
-
-// W (n x t, ldw = t) = K V and U (M x t) = K^T W for CSR X (n rows) and C (M rows) over d features.
-// W_or_null may be null (a workspace is used).  Validates the CSR structure on the device first.
-int sparse_prod(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
-                const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M, int64_t d,
-                float sigma, const float *V, int t, float *W_or_null, float *U)
+// structure check of one CSR matrix before anything indexes with the caller's numbers; *nnz_out
+// receives indptr[rows]
+int check_csr(knm_ctx *ctx, const int64_t *indptr, const int64_t *indices, int64_t rows, int64_t d, int64_t *nnz_out)
 {
     hipStream_t st = ctx->stream;
-    int64_t nnz_x = 0, nnz_c = 0;
-    hipError_t e = hipMemcpyAsync(&nnz_x, x_indptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipMemcpyAsync(&nnz_c, c_indptr + M, sizeof(int64_t), hipMemcpyDeviceToHost, st);
+    int64_t nnz = 0;
+    hipError_t e = hipMemcpyAsync(&nnz, indptr + rows, sizeof(int64_t), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "reading the CSR sizes", e);
-    if (nnz_x < 0 || nnz_c < 0 || nnz_c >= 0x7fffffffLL) return fail(ctx, KNM_INVALID_ARG, "bad CSR size");
-
-    // grid: enough wavefronts to fill the chip, each with a private accumulator over the centres
-    int64_t wgs = (n + kSpWaves - 1) / kSpWaves;
-    if (wgs > 2048) wgs = 2048; // 8 workgroups per CU: the sweep is bound by memory latency
-    const int64_t waves = wgs * kSpWaves;
-
-    DevMem flag, xn, cn, xa, cb, col_ptr, cursor, sums, csc_row, csc_val, acc, part, wtmp;
-    const int64_t scan_blocks = (d + 1 + kScanChunk - 1) / kScanChunk;
-    if (flag.alloc(sizeof(int)) != hipSuccess || xn.alloc(sizeof(float) * n) != hipSuccess ||
-        cn.alloc(sizeof(float) * M) != hipSuccess || xa.alloc(sizeof(float) * n) != hipSuccess ||
-        cb.alloc(sizeof(float) * M) != hipSuccess || col_ptr.alloc(sizeof(int) * (d + 1)) != hipSuccess ||
-        cursor.alloc(sizeof(int) * (d + 1)) != hipSuccess || sums.alloc(sizeof(int) * scan_blocks) != hipSuccess ||
-        csc_row.alloc(sizeof(int) * nnz_c) != hipSuccess || csc_val.alloc(sizeof(float) * nnz_c) != hipSuccess ||
-        acc.alloc(sizeof(float) * waves * M) != hipSuccess || part.alloc(sizeof(double) * 257) != hipSuccess ||
-        (!W_or_null && wtmp.alloc(sizeof(float) * n * t) != hipSuccess)) {
-        (void)hipGetLastError();
-        return fail(ctx, KNM_ALLOC, "hipMalloc(sparse workspace)");
-    }
-    float *W = W_or_null ? W_or_null : wtmp.as<float>();
-
-    // structure check before anything indexes with the caller's numbers
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "reading the CSR size", e);
+    if (nnz < 0 || nnz >= 0x7fffffffLL * 64) return fail(ctx, KNM_INVALID_ARG, "bad CSR size");
+    DevMem flag;
+    if (flag.alloc(sizeof(int)) != hipSuccess) return fail(ctx, KNM_ALLOC, "hipMalloc");
     int bad = 0;
     e = hipMemsetAsync(flag.p, 0, sizeof(int), st);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
-    hipLaunchKernelGGL(csr_check_kernel, grid_for(n), dim3(256), 0, st, x_indptr, x_indices, n, nnz_x, d, flag.as<int>());
-    hipLaunchKernelGGL(csr_check_kernel, grid_for(M), dim3(256), 0, st, c_indptr, c_indices, M, nnz_c, d, flag.as<int>());
+    hipLaunchKernelGGL(csr_check_kernel, grid_for(rows), dim3(256), 0, st, indptr, indices, rows, nnz, d, flag.as<int>());
     e = hipMemcpyAsync(&bad, flag.p, sizeof(int), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "CSR check", e);
-    if (bad) return fail(ctx, KNM_INVALID_ARG, "CSR structure: row pointers not monotone from 0, or feature ids of a row not strictly increasing in [0, d)");
+    if (bad)
+        return fail(ctx, KNM_INVALID_ARG,
+                    "CSR structure: row pointers not monotone from 0, or feature ids of a row not strictly increasing in [0, d)");
+    *nnz_out = nnz;
+    return KNM_OK;
+}
 
-    const float inv2s2 = 1.0f / (2.0f * sigma * sigma), inv_s2 = 1.0f / (sigma * sigma);
-    hipLaunchKernelGGL(row_norms_kernel, grid_for(n), dim3(256), 0, st, x_indptr, x_values, n, xn.as<float>());
-    hipLaunchKernelGGL(row_norms_kernel, grid_for(M), dim3(256), 0, st, c_indptr, c_values, M, cn.as<float>());
-    hipLaunchKernelGGL(norm_factor_kernel, grid_for(n), dim3(256), 0, st, xn.as<float>(), n, inv2s2, xa.as<float>());
-    hipLaunchKernelGGL(norm_factor_kernel, grid_for(M), dim3(256), 0, st, cn.as<float>(), M, inv2s2, cb.as<float>());
-
-    // C transposed: centre lists per feature
-    e = hipMemsetAsync(col_ptr.p, 0, sizeof(int) * (d + 1), st);
-    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
-    if (nnz_c > 0)
-        hipLaunchKernelGGL(col_count_kernel, grid_for(nnz_c), dim3(256), 0, st, c_indices, nnz_c, col_ptr.as<int>());
-    hipLaunchKernelGGL(scan_local_kernel, dim3((unsigned)scan_blocks), dim3(256), 0, st, col_ptr.as<int>(), d + 1,
-                       col_ptr.as<int>(), sums.as<int>());
-    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, st, sums.as<int>(), scan_blocks);
-    hipLaunchKernelGGL(scan_add_kernel, grid_for(d + 1), dim3(256), 0, st, col_ptr.as<int>(), d + 1, sums.as<int>());
-    e = hipMemcpyAsync(cursor.p, col_ptr.p, sizeof(int) * (d + 1), hipMemcpyDeviceToDevice, st);
-    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
-    std::vector<int64_t> c_ptr_host((size_t)M + 1);
-    e = hipMemcpyAsync(c_ptr_host.data(), c_indptr, sizeof(int64_t) * (M + 1), hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "reading the row pointers of C", e);
-    for (int64_t r0 = 0; r0 < M; r0 += kFillGroup) {
-        const int64_t r1 = (r0 + kFillGroup < M) ? r0 + kFillGroup : M;
-        const int64_t q0 = c_ptr_host[(size_t)r0], q1 = c_ptr_host[(size_t)r1]; // checked: monotone, within nnz
-        if (q1 > q0)
-            hipLaunchKernelGGL(csc_fill_kernel, grid_for(q1 - q0), dim3(256), 0, st, c_indptr, c_indices, c_values, r0, r1,
-                               q0, q1, cursor.as<int>(), csc_row.as<int>(), csc_val.as<float>());
+// CSC image of the centres: col_ptr (d + 1), csc_row / csc_val (nnz_c)
+struct CentreLists {
+    DevMem col_ptr, csc_row, csc_val;
+    int build(knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M,
+              int64_t d, int64_t nnz_c)
+    {
+        hipStream_t st = ctx->stream;
+        if (nnz_c >= 0x7fffffffLL) return fail(ctx, KNM_UNSUPPORTED, "more than 2^31 - 2 stored entries in C");
+        DevMem cursor, sums;
+        const int64_t scan_blocks = (d + 1 + kScanChunk - 1) / kScanChunk;
+        if (col_ptr.alloc(sizeof(int) * (d + 1)) != hipSuccess || cursor.alloc(sizeof(int) * (d + 1)) != hipSuccess ||
+            sums.alloc(sizeof(int) * scan_blocks) != hipSuccess || csc_row.alloc(sizeof(int) * nnz_c) != hipSuccess ||
+            csc_val.alloc(sizeof(float) * nnz_c) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, KNM_ALLOC, "hipMalloc(centre lists)");
+        }
+        hipError_t e = hipMemsetAsync(col_ptr.p, 0, sizeof(int) * (d + 1), st);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+        if (nnz_c > 0)
+            hipLaunchKernelGGL(col_count_kernel, grid_for(nnz_c), dim3(256), 0, st, c_indices, nnz_c, col_ptr.as<int>());
+        hipLaunchKernelGGL(scan_local_kernel, dim3((unsigned)scan_blocks), dim3(256), 0, st, col_ptr.as<int>(), d + 1,
+                           col_ptr.as<int>(), sums.as<int>());
+        hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, st, sums.as<int>(), scan_blocks);
+        hipLaunchKernelGGL(scan_add_kernel, grid_for(d + 1), dim3(256), 0, st, col_ptr.as<int>(), d + 1, sums.as<int>());
+        e = hipMemcpyAsync(cursor.p, col_ptr.p, sizeof(int) * (d + 1), hipMemcpyDeviceToDevice, st);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpyAsync", e);
+        std::vector<int64_t> c_ptr_host((size_t)M + 1);
+        e = hipMemcpyAsync(c_ptr_host.data(), c_indptr, sizeof(int64_t) * (M + 1), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "reading the row pointers of C", e);
+        for (int64_t r0 = 0; r0 < M; r0 += kFillGroup) {
+            const int64_t r1 = (r0 + kFillGroup < M) ? r0 + kFillGroup : M;
+            const int64_t q0 = c_ptr_host[(size_t)r0], q1 = c_ptr_host[(size_t)r1]; // checked: monotone, within nnz
+            if (q1 > q0)
+                hipLaunchKernelGGL(csc_fill_kernel, grid_for(q1 - q0), dim3(256), 0, st, c_indptr, c_indices, c_values, r0,
+                                   r1, q0, q1, cursor.as<int>(), csc_row.as<int>(), csc_val.as<float>());
+        }
+        e = hipStreamSynchronize(st); // cursor and sums are freed on return
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "centre lists", e);
+        return KNM_OK;
     }
-    e = hipMemsetAsync(acc.p, 0, sizeof(float) * waves * M, st);
-    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+};
 
-    SparseArgs a;
-    a.x_indptr = x_indptr;
-    a.x_indices = x_indices;
-    a.x_values = x_values;
-    a.n = n;
-    a.M = M;
-    a.col_ptr = col_ptr.as<int>();
-    a.csc_row = csc_row.as<int>();
-    a.csc_val = csc_val.as<float>();
-    a.xn = xn.as<float>();
-    a.cn = cn.as<float>();
-    a.xa = xa.as<float>();
-    a.acc = acc.as<float>();
-    a.inv2s2 = inv2s2;
-    a.inv_s2 = inv_s2;
-    // fixed-order fp64 sum of 256 partials, finished on the host
-    auto rank_one_sum = [&](const float *ev, const float *vec, int64_t ldv, int64_t rows, double *out) -> int {
+} // namespace
+
+// Everything the two sweeps of one (X, C, sigma) need, prepared once: validated structure, norms,
+// centre lists, accumulators.
+struct SparseProducts::Impl {
+    knm_ctx *ctx = nullptr;
+    const int64_t *x_indptr = nullptr, *x_indices = nullptr;
+    const float *x_values = nullptr;
+    int64_t n = 0, M = 0;
+    float inv2s2 = 0.0f, inv_s2 = 0.0f;
+    int64_t wgs = 0;
+    CentreLists lists;
+    DevMem xn, cn, xa, cb, acc, part, tmp;
+
+    int rank_one_sum(const float *ev, const float *vec, int64_t ldv, int64_t rows, double *out)
+    {
         double host[256];
+        hipStream_t st = ctx->stream;
         hipLaunchKernelGGL(weighted_sum_kernel, dim3(256), dim3(256), 0, st, ev, vec, ldv, rows, part.as<double>());
         hipError_t err = hipMemcpyAsync(host, part.p, sizeof(double) * 256, hipMemcpyDeviceToHost, st);
         if (err == hipSuccess) err = hipStreamSynchronize(st);
@@ -394,28 +458,150 @@ int sparse_prod(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices,
         for (int i = 0; i < 256; ++i) s += host[i];
         *out = s;
         return KNM_OK;
-    };
+    }
+    SparseArgs args()
+    {
+        SparseArgs a;
+        a.x_indptr = x_indptr;
+        a.x_indices = x_indices;
+        a.x_values = x_values;
+        a.n = n;
+        a.M = M;
+        a.col_ptr = lists.col_ptr.as<int>();
+        a.csc_row = lists.csc_row.as<int>();
+        a.csc_val = lists.csc_val.as<float>();
+        a.xn = xn.as<float>();
+        a.cn = cn.as<float>();
+        a.xa = xa.as<float>();
+        a.acc = acc.as<float>();
+        a.inv2s2 = inv2s2;
+        a.inv_s2 = inv_s2;
+        return a;
+    }
+};
+
+SparseProducts::SparseProducts() : impl(new Impl()) {}
+SparseProducts::~SparseProducts()
+{
+    if (impl && impl->ctx) (void)hipStreamSynchronize(impl->ctx->stream); // kernels may still use the workspace
+    delete impl;
+}
+
+int SparseProducts::prepare(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values,
+                            int64_t n, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values,
+                            int64_t M, int64_t d, float sigma)
+{
+    Impl &s = *impl;
+    s.ctx = ctx;
+    s.x_indptr = x_indptr;
+    s.x_indices = x_indices;
+    s.x_values = x_values;
+    s.n = n;
+    s.M = M;
+    s.inv2s2 = 1.0f / (2.0f * sigma * sigma);
+    s.inv_s2 = 1.0f / (sigma * sigma);
+    hipStream_t st = ctx->stream;
+    int64_t nnz_x = 0, nnz_c = 0;
+    int stat = check_csr(ctx, x_indptr, x_indices, n, d, &nnz_x);
+    if (!stat) stat = check_csr(ctx, c_indptr, c_indices, M, d, &nnz_c);
+    if (stat) return stat;
+    // grid: enough wavefronts to fill the chip, each with a private accumulator over the centres
+    s.wgs = (n + kSpWaves - 1) / kSpWaves;
+    if (s.wgs > 2048) s.wgs = 2048; // 8 workgroups per CU: the sweep is bound by memory latency
+    const int64_t waves = s.wgs * kSpWaves;
+    if (s.xn.alloc(sizeof(float) * n) != hipSuccess || s.cn.alloc(sizeof(float) * M) != hipSuccess ||
+        s.xa.alloc(sizeof(float) * n) != hipSuccess || s.cb.alloc(sizeof(float) * M) != hipSuccess ||
+        s.acc.alloc(sizeof(float) * waves * M) != hipSuccess || s.part.alloc(sizeof(double) * 256) != hipSuccess ||
+        s.tmp.alloc(sizeof(float) * n) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, KNM_ALLOC, "hipMalloc(sparse workspace)");
+    }
+    hipLaunchKernelGGL(row_norms_kernel, grid_for(n), dim3(256), 0, st, x_indptr, x_values, n, s.xn.as<float>());
+    hipLaunchKernelGGL(row_norms_kernel, grid_for(M), dim3(256), 0, st, c_indptr, c_values, M, s.cn.as<float>());
+    hipLaunchKernelGGL(norm_factor_kernel, grid_for(n), dim3(256), 0, st, s.xn.as<float>(), n, s.inv2s2, s.xa.as<float>());
+    hipLaunchKernelGGL(norm_factor_kernel, grid_for(M), dim3(256), 0, st, s.cn.as<float>(), M, s.inv2s2, s.cb.as<float>());
+    stat = s.lists.build(ctx, c_indptr, c_indices, c_values, M, d, nnz_c);
+    if (stat) return stat;
+    hipError_t e = hipMemsetAsync(s.acc.p, 0, sizeof(float) * waves * M, st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+    return KNM_OK;
+}
+
+// W (n x t, row-major) = K V
+int SparseProducts::v(const float *V, int t, float *W)
+{
+    Impl &s = *impl;
     for (int c = 0; c < t; ++c) {
-        double s = 0.0;
-        int stat = rank_one_sum(cb.as<float>(), V + c, t, M, &s);
+        double sum = 0.0;
+        int stat = s.rank_one_sum(s.cb.as<float>(), V + c, t, s.M, &sum);
         if (stat) return stat;
+        SparseArgs a = s.args();
         a.vec = V + c;
         a.ldv = t;
         a.out = W + c;
         a.ldo = t;
-        a.s_rank_one = s;
-        hipLaunchKernelGGL(sparse_sweep_kernel<0>, dim3((unsigned)wgs), dim3(kSpThreads), 0, st, a);
-        stat = rank_one_sum(xa.as<float>(), W + c, t, n, &s);
-        if (stat) return stat;
-        hipLaunchKernelGGL(rank_one_init_kernel, grid_for(M), dim3(256), 0, st, cb.as<float>(), M, s, U + c, (int64_t)t);
-        a.vec = W + c;
-        a.out = U + c;
-        a.s_rank_one = 0.0;
-        hipLaunchKernelGGL(sparse_sweep_kernel<1>, dim3((unsigned)wgs), dim3(kSpThreads), 0, st, a);
+        a.s_rank_one = sum;
+        hipLaunchKernelGGL(sparse_sweep_kernel<0>, dim3((unsigned)s.wgs), dim3(kSpThreads), 0, s.ctx->stream, a);
     }
+    return hipGetLastError() == hipSuccess ? KNM_OK : fail(s.ctx, KNM_HIP_ERROR, "sparse row sweep launch");
+}
+
+// U (M x t, row-major) = K^T (wgt .* W), wgt over the rows of X or null
+int SparseProducts::t_w(const float *W, const float *wgt, int t, float *U)
+{
+    Impl &s = *impl;
+    hipStream_t st = s.ctx->stream;
+    for (int c = 0; c < t; ++c) {
+        const float *w = W + c;
+        int64_t ldw = t;
+        if (wgt) {
+            hipLaunchKernelGGL(weigh_kernel, grid_for(s.n), dim3(256), 0, st, W + c, (int64_t)t, wgt, s.n, s.tmp.as<float>());
+            w = s.tmp.as<float>();
+            ldw = 1;
+        }
+        double sum = 0.0;
+        int stat = s.rank_one_sum(s.xa.as<float>(), w, ldw, s.n, &sum);
+        if (stat) return stat;
+        hipLaunchKernelGGL(rank_one_init_kernel, grid_for(s.M), dim3(256), 0, st, s.cb.as<float>(), s.M, sum, U + c, (int64_t)t);
+        SparseArgs a = s.args();
+        a.vec = w;
+        a.ldv = ldw;
+        a.out = U + c;
+        a.ldo = t;
+        a.s_rank_one = 0.0;
+        hipLaunchKernelGGL(sparse_sweep_kernel<1>, dim3((unsigned)s.wgs), dim3(kSpThreads), 0, st, a);
+    }
+    return hipGetLastError() == hipSuccess ? KNM_OK : fail(s.ctx, KNM_HIP_ERROR, "sparse column sweep launch");
+}
+
+// Upper triangle of K (M x M, column-major, fp64) = k(C, C) + jitter I for CSR centres
+int sparse_kmm(knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M,
+               int64_t d, float sigma, double jitter, double *K)
+{
+    hipStream_t st = ctx->stream;
+    int64_t nnz_c = 0;
+    int stat = check_csr(ctx, c_indptr, c_indices, M, d, &nnz_c);
+    if (stat) return stat;
+    CentreLists lists;
+    stat = lists.build(ctx, c_indptr, c_indices, c_values, M, d, nnz_c);
+    if (stat) return stat;
+    int64_t wgs = (M + kSpWaves - 1) / kSpWaves;
+    if (wgs > 1024) wgs = 1024;
+    const int64_t waves = wgs * kSpWaves;
+    DevMem cn, acc;
+    if (cn.alloc(sizeof(double) * M) != hipSuccess || acc.alloc(sizeof(double) * waves * M) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, KNM_ALLOC, "hipMalloc(sparse K_MM workspace)");
+    }
+    hipLaunchKernelGGL(row_norms_f64_kernel, grid_for(M), dim3(256), 0, st, c_indptr, c_values, M, cn.as<double>());
+    hipError_t e = hipMemsetAsync(acc.p, 0, sizeof(double) * waves * M, st);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+    hipLaunchKernelGGL(sparse_kmm_kernel, dim3((unsigned)wgs), dim3(kSpThreads), 0, st, c_indptr, c_indices, c_values, M,
+                       lists.col_ptr.as<int>(), lists.csc_row.as<int>(), lists.csc_val.as<float>(), cn.as<double>(),
+                       1.0 / (2.0 * (double)sigma * (double)sigma), jitter, acc.as<double>(), K);
     e = hipStreamSynchronize(st); // the workspace is freed on return
     if (e == hipSuccess) e = hipGetLastError();
-    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "sparse product", e);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "sparse K_MM", e);
     return KNM_OK;
 }
 
@@ -432,6 +618,20 @@ extern "C" int knm_prod_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t
     if (d >= 0x7fffffffLL || M >= 0x7fffffffLL) return fail(ctx, KNM_UNSUPPORTED, "d or M beyond 2^31 - 2");
     if (t > knm_max_t()) return fail(ctx, KNM_UNSUPPORTED, "t above compiled maximum");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    return sparse_prod(ctx, x_indptr, x_indices, x_values, n, c_indptr, c_indices, c_values, M, d, sigma, V, t,
-                       W_or_null, U);
+    SparseProducts ops;
+    int st = ops.prepare(ctx, x_indptr, x_indices, x_values, n, c_indptr, c_indices, c_values, M, d, sigma);
+    if (st) return st;
+    float *W = W_or_null;
+    if (!W) {
+        st = ensure(ctx, &ctx->w_buf, &ctx->w_bytes, sizeof(float) * (size_t)n * t);
+        if (st) return st;
+        W = ctx->w_buf;
+    }
+    st = ops.v(V, t, W);
+    if (!st) st = ops.t_w(W, nullptr, t, U);
+    if (st) return st;
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "sparse product", e);
+    return KNM_OK;
 }

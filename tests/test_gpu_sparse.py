@@ -107,3 +107,47 @@ def test_sparse_product_rejects_bad_structure(knm):
         knm.knm_prod_csr(_csr(bad_ptr, s["x_indices"], s["x_values"], n, d), C, 2.0, v)
     with pytest.raises(TypeError):
         knm.knm_prod_csr(torch.zeros(n, d, device="cuda"), C, 2.0, v)
+
+
+def test_sparse_fit_and_predict_match_the_dense_oracle(knm):
+    """Alg. 1 on CSR inputs against the oracle's fit on the densified inputs: same centres, same
+    iteration count; predictions on the training rows and on held-out sparse rows at the end-to-end
+    bar (the coefficients themselves are ill-determined at this lambda, as in the dense fits)."""
+    # lambda = 1e-3: with 1e-5 this problem amplifies the fp32 noise of the products tenfold per
+    # iteration (the dense GPU fit leaves the fp64 oracle's trajectory at the same point), and the
+    # sparse sweeps' atomics make that noise differ from run to run
+    n, M, d, sigma, lam, jitter, iters = 2500, 200, 1500, 5.0, 1e-3, 1e-6, 6
+    s, X, C, Xd, Cd = _case(n, M, d, 15.0, seed=21)
+    g = torch.Generator().manual_seed(4)
+    wtrue = torch.randn(d, generator=g)
+    Y = torch.tanh(0.05 * torch.from_numpy(Xd) @ wtrue) + 0.05 * torch.randn(n, generator=g)
+    alpha, resid = knm.falkon_fit_csr(X, Y.cuda(), C, sigma, lam, iters, jitter, return_resid=True)
+    ao, ro = oracle.falkon_fit(Xd, Y.numpy(), Cd, sigma, lam, iters, jitter, return_resid=True)
+    assert np.allclose(np.ravel(resid), np.ravel(ro), rtol=1e-3)
+    fit = knm.knm_v_csr(X, C, sigma, alpha)
+    assert rel_l2(fit.cpu().numpy(), oracle.falkon_predict(Xd, Cd, sigma, ao)) < 1e-3
+    st, Xt, _, Xtd, _ = _case(400, 8, d, 15.0, seed=22)
+    pred = knm.knm_v_csr(Xt, C, sigma, alpha)
+    po = oracle.falkon_predict(Xtd, Cd, sigma, ao)
+    assert rel_l2(pred.cpu().numpy(), po) < 1e-3
+
+
+def test_sparse_preconditioner_factors_match_oracle(knm):
+    M, d, sigma, lam, jitter = 300, 900, 4.0, 1e-4, 1e-8
+    s, X, C, Xd, Cd = _case(600, M, d, 12.0, seed=31)
+    lib = knm.load_library()
+    import ctypes
+
+    ctx = knm.default_context()
+    cr, cc, cv = C.crow_indices().contiguous(), C.col_indices().contiguous(), C.values().contiguous()
+    h = ctypes.c_void_p()
+    bad = ctypes.c_int64(0)
+    ctx.check(lib.precond_build_csr(ctx._h, cr.data_ptr(), cc.data_ptr(), cv.data_ptr(), M, d, sigma, lam, jitter,
+                                    ctypes.byref(h), ctypes.byref(bad)))
+    T = np.empty((M, M))
+    A = np.empty((M, M))
+    ctx.check(lib.precond_get_factors(ctx._h, h, T.ctypes.data, A.ctypes.data))
+    lib.precond_free(h)
+    To, Ao = oracle.precond(Cd, sigma, lam, jitter)
+    assert np.abs(T - To).max() < 1e-9 * max(1.0, np.abs(To).max())
+    assert np.abs(A - Ao).max() < 1e-9 * max(1.0, np.abs(Ao).max())
