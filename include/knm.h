@@ -241,6 +241,19 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
 typedef enum { KNM_CROSS_F32 = 0, KNM_CROSS_F16X3 = 1 } knm_cross_term;
 int knm_set_cross_term(knm_ctx *ctx, int mode);
 
+/* Kernel function of the dense entry points (a second kernel family on the same engines; the
+ * paper's experiments use the Gaussian kernel throughout):
+ *   KNM_KERNEL_GAUSSIAN (default)  k(x, c) = exp(-|x - c|^2 / (2 sigma^2))
+ *   KNM_KERNEL_LAPLACIAN           k(x, c) = exp(-|x - c| / sigma)
+ * The Laplacian kernel runs on the K-loop engines for every shape: the matrix cores accumulate
+ * -(log2(e) |x - c| / sigma)^2 from the norm expansion, then one square root and one exp2 per
+ * entry.  The distance of (nearly) coincident points comes out of a cancellation, so such an
+ * entry carries an absolute error of about 1e-3 (split-fp16) or 3e-4 (fp32) times |x| / sigma
+ * instead of the usual 1e-6; the preconditioner's k(C, C) is formed from fp64 differences and
+ * does not.  The sparse (CSR) entry points support the Gaussian kernel only. */
+typedef enum { KNM_KERNEL_GAUSSIAN = 0, KNM_KERNEL_LAPLACIAN = 1 } knm_kernel_kind;
+int knm_set_kernel(knm_ctx *ctx, int kind);
+
 /* Cap, in bytes, on the library-owned workspace that holds the converted operands of the
  * split-fp16 engines (0 restores the defaults: 2 GiB, or 8 GiB for the K-loop engine).  Operands
  * that do not fit are converted and swept slab by slab; results do not depend on the cap.  The

@@ -9,6 +9,7 @@ GPU sees); vectors are float64, shaped (rows, t) or (rows,) for t = 1.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
 import subprocess
@@ -44,6 +45,9 @@ def _load():
         lib.orc_num_threads.restype = _int
         lib.orc_gauss.restype = _dbl
         lib.orc_gauss.argtypes = [_f32p, _f32p, _int, _dbl]
+        lib.orc_set_kernel.argtypes = [_int]
+        lib.orc_set_kernel.restype = _int
+        lib.orc_get_kernel.restype = _int
         lib.orc_kernel_matrix.argtypes = pts + [_f64p]
         lib.orc_knm_v.argtypes = pts + [_f64p, _int, _f64p]
         lib.orc_knm_t_w.argtypes = pts + [_f64p, _int, _f64p]
@@ -96,7 +100,26 @@ def num_threads() -> int:
     return int(_load().orc_num_threads())
 
 
+KERNELS = {"gaussian": 0, "laplacian": 1}
+
+
+@contextlib.contextmanager
+def kernel(name: str):
+    """Evaluate everything inside the block with the named kernel: "gaussian" (the paper's,
+    Section 2: exp(-|x - c|^2 / (2 sigma^2))) or "laplacian" (exp(-|x - c| / sigma), textbook form;
+    the paper's method takes any positive-definite kernel but writes out only the Gaussian one)."""
+    lib = _load()
+    before = lib.orc_get_kernel()
+    if lib.orc_set_kernel(KERNELS[name]) != 0:
+        raise ValueError(name)
+    try:
+        yield
+    finally:
+        lib.orc_set_kernel(before)
+
+
 def gauss(x, c, sigma: float) -> float:
+    """k(x, c) of the kernel in force (Gaussian unless inside `kernel("laplacian")`)."""
     x = np.ascontiguousarray(x, dtype=np.float32).ravel()
     c = np.ascontiguousarray(c, dtype=np.float32).ravel()
     return float(_load().orc_gauss(_p32(x), _p32(c), x.size, float(sigma)))

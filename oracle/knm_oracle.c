@@ -40,7 +40,24 @@ int orc_num_threads(void)
 #endif
 }
 
-/* Gaussian kernel, Section 2: k(x, c) = exp(-||x - c||^2 / (2 sigma^2)). */
+/* Kernel function.  The paper works with the Gaussian kernel of a single length-scale throughout
+ * (Section 2 for the estimator, Section 5 for the experiments):
+ *     k(x, c) = exp(-||x - c||^2 / (2 sigma^2)).
+ * Its method holds for any positive-definite kernel; as a second one this oracle has the Laplacian
+ * (exponential) kernel in its textbook form, which the paper does not spell out:
+ *     k(x, c) = exp(-||x - c|| / sigma).
+ * The choice is a process-wide setting (test infrastructure: one thread of control). */
+static int g_kind = 0; /* 0 Gaussian, 1 Laplacian */
+
+int orc_set_kernel(int kind)
+{
+    if (kind != 0 && kind != 1) return -1;
+    g_kind = kind;
+    return 0;
+}
+
+int orc_get_kernel(void) { return g_kind; }
+
 static double gauss(const float *x, const float *c, int d, double sigma)
 {
     double s = 0.0;
@@ -48,6 +65,7 @@ static double gauss(const float *x, const float *c, int d, double sigma)
         double diff = (double)x[k] - (double)c[k];
         s += diff * diff;
     }
+    if (g_kind == 1) return exp(-sqrt(s) / sigma);
     return exp(-s / (2.0 * sigma * sigma));
 }
 

@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libknm.so")
 
 KNM_OK = 0
+KNM_INVALID_ARG, KNM_UNSUPPORTED, KNM_ALLOC, KNM_HIP_ERROR, KNM_NOT_PD = -1, -2, -3, -4, -5
 STATUS_NAMES = {0: "KNM_OK", -1: "KNM_INVALID_ARG", -2: "KNM_UNSUPPORTED", -3: "KNM_ALLOC",
                 -4: "KNM_HIP_ERROR", -5: "KNM_NOT_PD"}
 
@@ -65,6 +66,7 @@ SIGNATURES = {
     "knm_get_fit_timing": (_int, [_vp, ctypes.POINTER(_f64)]),
     "falkon_predict": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
     "knm_set_cross_term": (_int, [_vp, _int]),
+    "knm_set_kernel": (_int, [_vp, _int]),
     "knm_set_pack_limit": (_int, [_vp, ctypes.c_size_t]),
     "knm_set_timing": (_int, [_vp, _int]),
     "knm_get_timing": (_int, [_vp, ctypes.POINTER(_f32)]),
@@ -153,6 +155,11 @@ class Context:
         """'f16x3' (split-fp16 products on the f16 matrix cores, default) or 'f32' (fp32 MFMA)."""
         code = {"f32": 0, "f16x3": 1}[mode] if isinstance(mode, str) else int(mode)
         self.check(load_library().knm_set_cross_term(self._h, code))
+
+    def set_kernel(self, kind):
+        """'gaussian' (default) or 'laplacian' (exp(-|x - c| / sigma); dense entry points only)."""
+        code = {"gaussian": 0, "laplacian": 1}[kind] if isinstance(kind, str) else int(kind)
+        self.check(load_library().knm_set_kernel(self._h, code))
 
     def set_pack_limit(self, nbytes: int):
         """Cap on the workspace of the split-fp16 engines' converted operands (0: defaults)."""

@@ -41,17 +41,17 @@ int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need)
 
 // K-loop engine for several columns or for d beyond what the register-resident engine of the
 // selected arithmetic holds (44 features for the split-fp16 one, 64 for fp32)
-bool use_gemm_engine(int d, int t, int cross_term)
+bool use_gemm_engine(int d, int t, int cross_term, int kind)
 {
-    return t > 1 || d > (cross_term == KNM_CROSS_F16X3 ? f16_max_d() : small_max_d());
+    return kind != KNM_KERNEL_GAUSSIAN || t > 1 || d > (cross_term == KNM_CROSS_F16X3 ? f16_max_d() : small_max_d());
 }
 
 // Chunking of the stream dimension.  More chunks = more workgroups (needed when there
 // are few fixed blocks) and shorter fp32 running sums; each chunk costs one partial
 // vector that the merge pass adds up in fp64.
-int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int cross_term, int64_t *chunk_len)
+int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int cross_term, int kind, int64_t *chunk_len)
 {
-    const bool gemm = use_gemm_engine(d, t, cross_term);
+    const bool gemm = use_gemm_engine(d, t, cross_term, kind);
     const int64_t stage = gemm ? gemm_stage_points() : stage_points();
     const int64_t per_block = gemm ? gemm_fixed_per_block() : fixed_per_block(d);
     const int64_t blocks = (nF + per_block - 1) / per_block;
@@ -83,7 +83,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
                  int d, float sigma, const float *vec, const float *wgt, int t, float *out, hipEvent_t after_sweep)
 {
     int64_t chunk_len = 0;
-    const int64_t chunks = choose_chunks(nF, nS, d, t, ctx->cross_term, &chunk_len);
+    const int64_t chunks = choose_chunks(nF, nS, d, t, ctx->cross_term, ctx->kernel_kind, &chunk_len);
     if (chunks > 65535) return fail(ctx, KNM_UNSUPPORTED, "too many stream chunks");
     float *part = nullptr;
     if (chunks > 1) {
@@ -91,7 +91,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         if (st) return st;
         part = ctx->part_buf;
     }
-    const bool gemm = use_gemm_engine(d, t, ctx->cross_term);
+    const bool gemm = use_gemm_engine(d, t, ctx->cross_term, ctx->kernel_kind);
     // columns per launch
     const int group = !gemm ? 1 : (ctx->cross_term == KNM_CROSS_F16X3 ? gemm_f16_max_t() : gemm_max_t());
     for (int c = 0; c < t; c += group) {
@@ -107,7 +107,10 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.chunk_stride = nF * t;
         a.chunk_len = chunk_len;
         a.n_chunks = chunks;
-        a.sigma = sigma;
+        // Laplacian: with sigma / sqrt(2 log2 e) in place of sigma the engines' accumulators hold
+        // -(log2(e) |x - c| / sigma)^2, whose root the kernel takes before the exp2
+        a.kind = ctx->kernel_kind;
+        a.sigma = (a.kind == KNM_KERNEL_LAPLACIAN) ? sigma / sqrtf(2.0f * 1.4426950408889634f) : sigma;
         const bool f16 = !gemm && ctx->cross_term == KNM_CROSS_F16X3 && d <= f16_max_d();
         hipError_t e;
         if (gemm && ctx->cross_term == KNM_CROSS_F16X3) {
@@ -245,9 +248,9 @@ size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
     size_t bytes = sizeof(float) * (size_t)n * t; // W
     // the larger of the two arithmetic modes' needs (they may cut the stream differently)
     size_t part = 0;
-    for (int mode = 0; mode < 2; ++mode) {
-        const int64_t c1 = choose_chunks(n, M, d, t, mode, &len);
-        const int64_t c2 = choose_chunks(M, n, d, t, mode, &len);
+    for (int mode = 0; mode < 4; ++mode) { // both cross-term modes of both kernel families
+        const int64_t c1 = choose_chunks(n, M, d, t, mode & 1, mode >> 1, &len);
+        const int64_t c2 = choose_chunks(M, n, d, t, mode & 1, mode >> 1, &len);
         const size_t p1 = c1 > 1 ? sizeof(float) * (size_t)c1 * n * t : 0;
         const size_t p2 = c2 > 1 ? sizeof(float) * (size_t)c2 * M * t : 0;
         if (p1 > part) part = p1;
@@ -335,6 +338,14 @@ int knm_set_cross_term(knm_ctx *ctx, int mode)
     if (!ctx) return KNM_INVALID_ARG;
     if (mode != KNM_CROSS_F32 && mode != KNM_CROSS_F16X3) return fail(ctx, KNM_INVALID_ARG, "unknown cross-term mode");
     ctx->cross_term = mode;
+    return KNM_OK;
+}
+
+int knm_set_kernel(knm_ctx *ctx, int kind)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (kind != KNM_KERNEL_GAUSSIAN && kind != KNM_KERNEL_LAPLACIAN) return fail(ctx, KNM_INVALID_ARG, "unknown kernel");
+    ctx->kernel_kind = kind;
     return KNM_OK;
 }
 

@@ -12,6 +12,11 @@
 //   form TN:  a(i, k) = A[k + i * lda]   (block row of the factor: contraction index contiguous)
 //   form NT:  a(i, k) = A[i + k * lda]   (columns of the triangular factor: row index contiguous)
 //
+// and, with the triangle test and the patch enumeration switched off, the general product
+//   C[i, j] = alpha * sum_k a(i, k) * b(j, k) + beta * C[i, j]   over a rectangular C with its own
+// column operand b (always TN), which carries the first two steps of the column update (products
+// with the rows above and with inverted diagonal blocks) and the merging of block inverses.
+//
 // A workgroup of 4 wavefronts owns a 128 x 128 tile of C, each wavefront a 64 x 64 piece as
 // 4 x 4 accumulators of v_mfma_f64_16x16x4_f64.  Operand tiles (16 deep) are staged through
 // LDS, double buffered, with the global loads issued a stage and a half ahead.  Two

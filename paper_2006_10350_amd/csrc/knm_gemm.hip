@@ -53,14 +53,21 @@ __device__ __forceinline__ void mfma_acc(f32x16 &acc, float a, float b)
     asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
-// exp2 of an accumulator element with the clamp modifier (kernel value in [0, 1]).  Volatile and
-// reading the accumulation register itself: the compiler does not look inside inline assembly,
+// exp2 of an accumulator element with the clamp modifier (Gaussian kernel value in [0, 1]).  Volatile
+// and reading the accumulation register itself: the compiler does not look inside inline assembly,
 // so it must neither move this read up towards the MFMA that produces the element nor be
 // relied on for the wait state a transcendental result needs before its first use.
 __device__ __forceinline__ float exp2_clamped(const float &x)
 {
     float p;
     asm volatile("v_accvgpr_read_b32 %0, %1\n\tv_exp_f32_e64 %0, %0 clamp\n\ts_nop 0" : "=v"(p) : "a"(x));
+    return p;
+}
+// the accumulator element itself, for code the compiler schedules (same ordering argument)
+__device__ __forceinline__ float acc_read(const float &x)
+{
+    float p;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(p) : "a"(x));
     return p;
 }
 
@@ -72,7 +79,7 @@ __device__ __forceinline__ void mfma_results_ready()
 
 // TP: number of vector columns, padded to a multiple of 4.  VW: 4 if rows can be read
 // with aligned 16-byte loads, else 1.
-template <int TP, int VW>
+template <int TP, int VW, int KIND>
 __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
 {
     __shared__ __attribute__((aligned(16))) float img[2][kBlocks * kBlockFloats]; // 2 x 24 KB
@@ -241,6 +248,33 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
 
         // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block
         mfma_results_ready();
+        // Laplacian: per fixed point of this lane, the row and the |exponent| below which a pair is
+        // taken again from differences (never for a padding row).  The unrolled pass leaves such
+        // pairs out (kernel value 0) and only notes that there are some; the rare second pass
+        // finds them again and adds their terms.
+        const float *frow[2] = {nullptr, nullptr};
+        float near[2] = {0.0f, 0.0f};
+        bool any_near = false;
+        if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb) {
+                const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
+                const bool in = idx < a.nF;
+                frow[fb] = a.F + (in ? idx : 0) * a.ldf;
+                near[fb] = in ? near_pair_threshold(aug[(wave * 2 + fb) * 64 + (lane & 31)], d) : -INFINITY;
+            }
+        }
+        auto kernel_value = [&](int fb, int sb, int r) -> float {
+            if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+                const float x = acc_read(acc[fb][sb][r]);
+                const bool nr = x > -near[fb];
+                any_near |= nr;
+                return nr ? 0.0f : laplacian_from_exponent(x);
+            } else {
+                // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
+                return exp2_clamped(acc[fb][sb][r]);
+            }
+        };
 #pragma unroll
         for (int sb = 0; sb < 4; ++sb)
 #pragma unroll
@@ -254,12 +288,41 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
                 }
 #pragma unroll
                 for (int fb = 0; fb < 2; ++fb) {
-                    // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
-                    const float p = exp2_clamped(acc[fb][sb][r]);
+                    const float p = kernel_value(fb, sb, r);
 #pragma unroll
                     for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[c], sum[fb][c]);
                 }
             }
+        if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+            if (__builtin_amdgcn_ballot_w64(any_near) != 0) {
+#pragma unroll
+                for (int fb = 0; fb < 2; ++fb) {
+                    // bit 16 (sb % 2) + r of word sb / 2: register r of stream block sb is a near pair
+                    uint32_t m[2] = {0u, 0u};
+#pragma unroll
+                    for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (acc_read(acc[fb][sb][r]) > -near[fb]) m[sb >> 1] |= 1u << ((sb & 1) * 16 + r);
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        uint32_t mm = m[half];
+                        while (mm != 0u) {
+                            const int b = __builtin_ctz(mm);
+                            mm &= mm - 1u;
+                            const int sb = half * 2 + (b >> 4), r = b & 15;
+                            const int jl = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                            const int64_t j = stream0 + jl;
+                            if (j < chunk_end) { // a padding row has zero vectors
+                                const float p = laplacian_from_exponent(exact_exponent(frow[fb], a.S + j * a.lds, d, s2));
+#pragma unroll
+                                for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vimg[jl * TP + c], sum[fb][c]);
+                            }
+                        }
+                    }
+                }
+            }
+        }
         __syncthreads(); // aug / vimg / img are rewritten by the next tile
     }
 
@@ -284,10 +347,15 @@ hipError_t launch_tp(const SweepArgs &a, hipStream_t stream)
     dim3 grid((unsigned)blocks, (unsigned)a.n_chunks);
     const bool a16 = (a.d % 4 == 0) && (a.lds % 4 == 0) && (a.ldf % 4 == 0) &&
                      ((reinterpret_cast<uintptr_t>(a.S) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.F) & 15) == 0);
-    if (a16)
-        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 4>), grid, dim3(kThreads), 0, stream, a);
+    const bool lap = a.kind == KNM_KERNEL_LAPLACIAN;
+    if (a16 && !lap)
+        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 4, KNM_KERNEL_GAUSSIAN>), grid, dim3(kThreads), 0, stream, a);
+    else if (!lap)
+        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 1, KNM_KERNEL_GAUSSIAN>), grid, dim3(kThreads), 0, stream, a);
+    else if (a16)
+        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 4, KNM_KERNEL_LAPLACIAN>), grid, dim3(kThreads), 0, stream, a);
     else
-        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 1>), grid, dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 1, KNM_KERNEL_LAPLACIAN>), grid, dim3(kThreads), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -300,6 +368,7 @@ int64_t gemm_fixed_per_block() { return kFixed; }
 hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream)
 {
     if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > gemm_max_t()) return hipErrorInvalidValue;
+    if (a.kind != KNM_KERNEL_GAUSSIAN && a.kind != KNM_KERNEL_LAPLACIAN) return hipErrorInvalidValue;
     if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
     if (a.t <= 4) return launch_tp<4>(a, stream);

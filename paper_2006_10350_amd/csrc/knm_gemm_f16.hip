@@ -182,15 +182,21 @@ __device__ __forceinline__ void mfma_acc(f32x16 &acc, const f16x8 &a, const f16x
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
-// exp2 of an accumulator element with the clamp modifier (kernel value in [0, 1]).  Volatile and
-// reading the accumulation register itself: the compiler does not look inside inline assembly,
+// exp2 of an accumulator element with the clamp modifier (Gaussian kernel value in [0, 1]).  Volatile
+// and reading the accumulation register itself: the compiler does not look inside inline assembly,
 // so it must neither move this read up towards the MFMA that produces the element (it knows
-// nothing of that instruction's latency) nor be relied on for the wait state a transcendental
-// result needs before its first use.
+// nothing of that instruction's latency) nor be relied on for the wait state a transcendental result needs before its first use.
 __device__ __forceinline__ float exp2_clamped(const float &x)
 {
     float p;
     asm volatile("v_accvgpr_read_b32 %0, %1\n\tv_exp_f32_e64 %0, %0 clamp\n\ts_nop 0" : "=v"(p) : "a"(x));
+    return p;
+}
+// the accumulator element itself, for code the compiler schedules (same ordering argument)
+__device__ __forceinline__ float acc_read(const float &x)
+{
+    float p;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(p) : "a"(x));
     return p;
 }
 
@@ -236,7 +242,7 @@ struct PatchMap {
 // Simg: image of the stream chunks [chunk0, chunk0 + n_chunks).
 // TP: number of vector columns, padded to a multiple of 2 (vector-ALU reduction).  MV: reduce
 // on the matrix cores instead (up to 32 columns; TP unused); colmax[c] = bits of max |vec[:, c]|.
-template <int TP, bool MV>
+template <int TP, bool MV, int KIND>
 __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
                                                                      const f16x8 *__restrict__ Simg,
                                                                      int64_t fixed_row0, int64_t chunk0, int n_kc,
@@ -263,6 +269,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     const int h = lane >> 5;
     const int t = a.t;
     const int n_st = n_kc + 1; // stages per tile: the feature chunks, then the norm slots
+    const float s2 = kLog2e / (2.0f * a.sigma * a.sigma); // exponent per squared distance (Laplacian refinement)
 
     const int64_t fixed0 = fixed_row0 + fblk * kFixed;
     const int64_t chunk = chunk0 + cblk;
@@ -419,6 +426,58 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
 
         // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block
         mfma_results_ready();
+        // Laplacian: per fixed point of this lane, the row and the |exponent| below which a pair is
+        // taken again from differences (never for a padding row).  The norm term is read back from
+        // the two leading digits of the fixed point's norm slot (lanes 0..31 hold them).  The unrolled
+        // pass leaves such pairs out (kernel value 0) and only notes that there are some; the rare
+        // second pass finds them again and adds their terms.
+        const float *frow[2] = {nullptr, nullptr};
+        float near[2] = {0.0f, 0.0f};
+        bool any_near = false;
+        if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+            const f16x8 *ib = img[(stage - 1) & 1];
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb) {
+                const f16x8 fx = ib[(wave * 2 + fb) * kUnits + (lane & 31)];
+                const float nf = kC1 * (float)fx[0] + kC2 * (float)fx[1];
+                const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
+                const bool in = idx < a.nF;
+                frow[fb] = a.F + (in ? idx : 0) * a.ldf;
+                near[fb] = in ? near_pair_threshold(nf, a.d) : -INFINITY;
+            }
+        }
+        auto kernel_value = [&](int fb, int sb, int r) -> float {
+            if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+                const float x = acc_read(acc[fb][sb][r]);
+                const bool nr = x > -near[fb];
+                any_near |= nr;
+                return nr ? 0.0f : laplacian_from_exponent(x);
+            } else {
+                // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
+                return exp2_clamped(acc[fb][sb][r]);
+            }
+        };
+        // second pass, per fixed block: the near pairs of this lane as bit 16 (sb % 2) + r of word sb / 2
+        auto near_pairs = [&](int fb, uint32_t (&m)[2]) {
+            m[0] = m[1] = 0u;
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (acc_read(acc[fb][sb][r]) > -near[fb]) m[sb >> 1] |= 1u << ((sb & 1) * 16 + r);
+        };
+        // takes the lowest pair off the mask: its stream row within the tile and its kernel value
+        // (0 for a padding row, whose vectors are zero)
+        auto pop_pair = [&](int fb, uint32_t (&m)[2], int &jl) -> float {
+            const int half = m[0] != 0u ? 0 : 1;
+            const int b = __builtin_ctz(m[half]);
+            m[half] &= m[half] - 1u;
+            const int sb = half * 2 + (b >> 4), r = b & 15;
+            jl = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+            const int64_t j = stream0 + jl;
+            if (j >= chunk_end) return 0.0f;
+            return laplacian_from_exponent(exact_exponent(frow[fb], a.S + j * a.lds, a.d, s2));
+        };
         if constexpr (MV) {
 #pragma unroll
             for (int sb = 0; sb < 4; ++sb)
@@ -433,8 +492,8 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                         u32x4 ph, pl;
 #pragma unroll
                         for (int e = 0; e < 8; e += 2) {
-                            const float p0 = exp2_clamped(acc[fb][sb][8 * q + e]);
-                            const float p1 = exp2_clamped(acc[fb][sb][8 * q + e + 1]);
+                            const float p0 = kernel_value(fb, sb, 8 * q + e);
+                            const float p1 = kernel_value(fb, sb, 8 * q + e + 1);
                             const f16x2 h2 = __builtin_amdgcn_cvt_pkrtz(p0, p1);
                             const f16x2 l2 = __builtin_amdgcn_cvt_pkrtz(p0 - (float)h2[0], p1 - (float)h2[1]);
                             ph[e / 2] = __builtin_bit_cast(uint32_t, h2);
@@ -446,6 +505,37 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                         mfma_accv(dacc[fb], vl, bh);
                     }
                 }
+            if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+                if (__builtin_amdgcn_ballot_w64(any_near) != 0) {
+                    // The 32 columns of a fixed point are spread over its two lanes (one per
+                    // half-wave), so the two exchange their pairs and each adds both to its own
+                    // columns, scaled like the vector image.
+                    auto add_pair = [&](int fb, float p, int jl) {
+                        if (p == 0.0f) return;
+                        const int64_t j = stream0 + jl;
+                        const float w = a.wgt != nullptr ? a.wgt[j] : 1.0f;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int c = 8 * (r / 4) + 4 * h + (r % 4);
+                            if (c < t) dacc[fb][r] = fmaf(p * w * column_scale(colmax[c], false), a.vec[j * a.ldv + c], dacc[fb][r]);
+                        }
+                    };
+#pragma unroll
+                    for (int fb = 0; fb < 2; ++fb) {
+                        uint32_t m[2];
+                        near_pairs(fb, m);
+                        while (__builtin_amdgcn_ballot_w64((m[0] | m[1]) != 0u) != 0) {
+                            int jl = 0;
+                            float p = 0.0f;
+                            if ((m[0] | m[1]) != 0u) p = pop_pair(fb, m, jl);
+                            const float p_other = __shfl_xor(p, 32);
+                            const int jl_other = __shfl_xor(jl, 32);
+                            add_pair(fb, p, jl);
+                            add_pair(fb, p_other, jl_other);
+                        }
+                    }
+                }
+            }
         } else {
             // the vector row of the next register is read from LDS while this one is used
             float vr[2][TP];
@@ -465,10 +555,24 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                 if (it + 1 < 64) load_row(vr[cur ^ 1], it + 1);
 #pragma unroll
                 for (int fb = 0; fb < 2; ++fb) {
-                    // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
-                    const float p = exp2_clamped(acc[fb][it >> 4][it & 15]);
+                    const float p = kernel_value(fb, it >> 4, it & 15);
 #pragma unroll
                     for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[cur][c], sum[fb][c]);
+                }
+            }
+            if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+                if (__builtin_amdgcn_ballot_w64(any_near) != 0) {
+#pragma unroll
+                    for (int fb = 0; fb < 2; ++fb) {
+                        uint32_t m[2];
+                        near_pairs(fb, m);
+                        while ((m[0] | m[1]) != 0u) {
+                            int jl = 0;
+                            const float p = pop_pair(fb, m, jl);
+#pragma unroll
+                            for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vimg[jl * TP + c], sum[fb][c]);
+                        }
+                    }
                 }
             }
         }
@@ -548,8 +652,12 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
     const int64_t n_patch_c = (chunks + pm.pc - 1) / pm.pc;
     const int64_t patches = (pm.n_patch_f * n_patch_c + 7) / 8 * 8;
     const dim3 grid((unsigned)(patches * kPatch));
-    hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP, MV>), grid, dim3(kThreads), 0, stream, a, Fimg, Simg, fixed_row0,
-                       chunk0, n_kc, pm, colmax);
+    if (a.kind == KNM_KERNEL_LAPLACIAN)
+        hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP, MV, KNM_KERNEL_LAPLACIAN>), grid, dim3(kThreads), 0, stream, a,
+                           Fimg, Simg, fixed_row0, chunk0, n_kc, pm, colmax);
+    else
+        hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP, MV, KNM_KERNEL_GAUSSIAN>), grid, dim3(kThreads), 0, stream, a,
+                           Fimg, Simg, fixed_row0, chunk0, n_kc, pm, colmax);
 }
 
 } // namespace
@@ -570,6 +678,7 @@ int gemm_f16_max_t() { return 32; }
 hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
     if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > gemm_f16_max_t()) return hipErrorInvalidValue;
+    if (a.kind != KNM_KERNEL_GAUSSIAN && a.kind != KNM_KERNEL_LAPLACIAN) return hipErrorInvalidValue;
     if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
     const int n_kc = (a.d + kChunk - 1) / kChunk;

@@ -33,8 +33,39 @@ struct SweepArgs {
     int64_t ldo, chunk_stride;
     int64_t chunk_len; // stream points per chunk (multiple of the stage size)
     int64_t n_chunks;
-    float sigma;
+    float sigma;      // length scale the engines work with (for the Laplacian kernel the caller's, rescaled)
+    int kind;         // KNM_KERNEL_GAUSSIAN or KNM_KERNEL_LAPLACIAN (K-loop engines only)
 };
+
+// ---- Laplacian kernel on the K-loop engines ------------------------------------------
+//
+// The engines' accumulators hold x = -s2 |f - s|^2 (s2 = log2(e) / (2 sigma^2) of the rescaled
+// sigma), formed as norms minus cross term; the kernel value is 2^-sqrt(|x|).  The cancellation
+// leaves an absolute error of about 1e-7 sqrt(d) N in x (N = s2 |f|^2, the norm in the same units),
+// which the square root turns into error / (2 sqrt(|x|)): harmless for ordinary pairs, but 1e-4 to
+// 1e-3 for coincident or nearly coincident ones, and every Nystrom centre coincides with a data
+// row.  Pairs whose |x| lies below the threshold at which that error reaches 1e-5 get their
+// exponent again from fp32 differences of the two rows (exact for coincident rows, relative
+// rounding error otherwise).  Such pairs are rare, so the branch is almost never taken.
+__device__ __forceinline__ float near_pair_threshold(float norm_term, int d)
+{
+    const float N = fabsf(norm_term);
+    return fmaxf(2.5e-5f * (float)d * N * N, 1.0e-12f);
+}
+__device__ __forceinline__ float exact_exponent(const float *__restrict__ f, const float *__restrict__ s, int d,
+                                                float s2)
+{
+    float q = 0.0f;
+    for (int k = 0; k < d; ++k) {
+        const float diff = f[k] - s[k];
+        q = fmaf(diff, diff, q);
+    }
+    return -s2 * q;
+}
+__device__ __forceinline__ float laplacian_from_exponent(float x)
+{
+    return __builtin_amdgcn_exp2f(-__builtin_amdgcn_sqrtf(fabsf(x)));
+}
 
 // register-resident engine (knm_tile.hip): d <= small_max_d(), one column per launch
 int small_max_d();
@@ -108,6 +139,7 @@ struct knm_ctx {
     size_t pack_bytes = 0;
     size_t pack_limit = 0;     // cap on the image workspace chosen by the caller; 0 = engine defaults
     int cross_term = KNM_CROSS_F16X3;
+    int kernel_kind = KNM_KERNEL_GAUSSIAN;
     // timing
     bool timing = false;
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
@@ -124,9 +156,9 @@ namespace knm {
 int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need);
 int fail(knm_ctx *ctx, int status, const char *what, hipError_t e = hipSuccess);
 // true if (d, t) runs on the K-loop engine, false for the register-resident one
-bool use_gemm_engine(int d, int t, int cross_term);
+bool use_gemm_engine(int d, int t, int cross_term, int kind);
 // number of stream chunks for a sweep over nS stream points against nF fixed points
-int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int cross_term, int64_t *chunk_len);
+int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int cross_term, int kind, int64_t *chunk_len);
 int do_knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
              int64_t ldc, float sigma, const float *V, int t, float *W);
 int do_knm_t_w(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,

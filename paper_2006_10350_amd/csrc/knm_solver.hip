@@ -33,11 +33,12 @@ namespace {
 
 using namespace knm;
 
-// Upper triangle (column-major, r <= c) of K[r, c] = exp(-|c_r - c_c|^2 / (2 sigma^2)) + jitter [r == c],
-// fp64, direct differences.  The factorisation reads nothing below the diagonal, which is
+// Upper triangle (column-major, r <= c) of K[r, c] = k(c_r, c_c) + jitter [r == c], fp64, direct
+// differences: k = exp(-|c_r - c_c|^2 scale) with scale = 1 / (2 sigma^2) for the Gaussian kernel,
+// exp(-|c_r - c_c| scale) with scale = 1 / sigma for the Laplacian one.  The factorisation reads nothing below the diagonal, which is
 // zeroed once the factor is there.
-__global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_t ldc, double inv2s2, double jitter,
-                           double *__restrict__ K)
+__global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_t ldc, int kind, double scale,
+                           double jitter, double *__restrict__ K)
 {
     if ((int64_t)blockIdx.x * blockDim.x > (int64_t)blockIdx.y * blockDim.y + (blockDim.y - 1)) return; // below
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -50,7 +51,7 @@ __global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_
         double diff = (double)cr[k] - (double)cc[k];
         s += diff * diff;
     }
-    double v = exp(-s * inv2s2);
+    double v = exp(-(kind == KNM_KERNEL_LAPLACIAN ? sqrt(s) : s) * scale);
     if (r == c) v += jitter;
     K[r + c * M] = v;
 }
@@ -1006,8 +1007,10 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
     auto fill = [=](double *K) {
         const dim3 tb(32, 8);
         const dim3 tg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
-        const double inv2s2 = 1.0 / (2.0 * (double)sigma * (double)sigma);
-        hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, inv2s2, jitter, K);
+        const int kind = ctx->kernel_kind;
+        const double scale =
+            kind == KNM_KERNEL_LAPLACIAN ? 1.0 / (double)sigma : 1.0 / (2.0 * (double)sigma * (double)sigma);
+        hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, kind, scale, jitter, K);
         return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "kmm_kernel launch");
     };
     return precond_build_from(ctx, M, fill, lambda, jitter, second_factor, out, bad_pivot_or_null);

@@ -491,6 +491,9 @@ int SparseProducts::prepare(knm_ctx *ctx, const int64_t *x_indptr, const int64_t
                             int64_t n, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values,
                             int64_t M, int64_t d, float sigma)
 {
+    // the closed form of the rank-one part belongs to the Gaussian kernel
+    if (ctx->kernel_kind != KNM_KERNEL_GAUSSIAN)
+        return fail(ctx, KNM_UNSUPPORTED, "sparse inputs: Gaussian kernel only");
     Impl &s = *impl;
     s.ctx = ctx;
     s.x_indptr = x_indptr;
@@ -578,6 +581,8 @@ int SparseProducts::t_w(const float *W, const float *wgt, int t, float *U)
 int sparse_kmm(knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M,
                int64_t d, float sigma, double jitter, double *K)
 {
+    if (ctx->kernel_kind != KNM_KERNEL_GAUSSIAN)
+        return fail(ctx, KNM_UNSUPPORTED, "sparse inputs: Gaussian kernel only");
     hipStream_t st = ctx->stream;
     int64_t nnz_c = 0;
     int stat = check_csr(ctx, c_indptr, c_indices, M, d, &nnz_c);

@@ -22,10 +22,22 @@ def rel_l2(got, ref):
     return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-@pytest.mark.parametrize("name,n_rows,n_cols", [("mid", 503, 6), ("lowdim", 503, 6), ("highdim", 120, 2)])
-def test_full_size_sampled_outputs(knm, name, n_rows, n_cols):
+@pytest.fixture
+def kernel_kind(request, knm):
+    """Sets the kernel function on the default context and in the oracle for one test."""
+    kind = getattr(request, "param", "gaussian")
+    knm.default_context().set_kernel(kind)
+    with oracle.kernel(kind):
+        yield kind
+    knm.default_context().set_kernel("gaussian")
+
+
+@pytest.mark.parametrize("name,n_rows,n_cols,kernel_kind",
+                         [("mid", 503, 6, "gaussian"), ("lowdim", 503, 6, "gaussian"), ("highdim", 120, 2, "gaussian"),
+                          ("mid", 503, 6, "laplacian")], indirect=["kernel_kind"])
+def test_full_size_sampled_outputs(knm, name, n_rows, n_cols, kernel_kind):
     w = synth.workload(name)
-    print(f"workload {name}: n={w.n} d={w.d} M={w.M}", flush=True)
+    print(f"workload {name}: n={w.n} d={w.d} M={w.M} kernel={kernel_kind}", flush=True)
     inp = synth.make_inputs(w, device="cuda", with_targets=True)
     X, C, Y = inp["X"], inp["C"], inp["Y"]
     v = synth.probe_vector(w.M, w.t, "normal", device="cuda")

@@ -312,3 +312,44 @@ def test_fit_few_iterations_match_library_cg_iterates():
         r = rn
     alpha = oracle.falkon_fit(X, y, C, sigma, lam, iters=k)
     np.testing.assert_allclose(Knm @ alpha, Knm @ (Bm @ x), rtol=1e-6, atol=1e-8)
+
+
+# ---------------------------------------------------------------- second kernel family (Laplacian)
+
+def test_laplacian_hand_values_and_library():
+    from scipy.spatial.distance import cdist
+
+    with oracle.kernel("laplacian"):
+        assert oracle.gauss([0.0], [0.0], 1.0) == 1.0
+        # 3-4-5 triangle, sigma = 2.5: exp(-5 / 2.5); the Gaussian value would be exp(-2) too only for
+        # sigma^2 = 6.25, so a second point with another distance separates the two forms
+        assert oracle.gauss([1.0, -2.0], [4.0, 2.0], 2.5) == pytest.approx(math.exp(-2.0), rel=1e-15)
+        assert oracle.gauss([0.0], [3.0], 2.0) == pytest.approx(math.exp(-1.5), rel=1e-15)
+        X, C = _pts(57, 9), _pts(23, 9)
+        D = cdist(X.astype(np.float64), C.astype(np.float64), metric="euclidean")
+        assert np.allclose(oracle.kernel_matrix(X, C, 1.7), np.exp(-D / 1.7), rtol=1e-13, atol=0)
+    # the setting ends with the block
+    assert oracle.gauss([0.0], [3.0], 2.0) == pytest.approx(math.exp(-9.0 / 8.0), rel=1e-15)
+
+
+def test_laplacian_setting_reaches_every_product_and_the_fit():
+    from scipy.spatial.distance import cdist
+
+    n, M, d, t, sigma, lam = 300, 40, 5, 2, 2.0, 1e-3
+    X = _pts(n, d)
+    C = X[RNG.choice(n, M, replace=False)].copy()
+    V = RNG.standard_normal((M, t))
+    Y = RNG.standard_normal((n, t))
+    K = np.exp(-cdist(X.astype(np.float64), C.astype(np.float64)) / sigma)
+    Kmm = np.exp(-cdist(C.astype(np.float64), C.astype(np.float64)) / sigma)
+    with oracle.kernel("laplacian"):
+        assert np.allclose(oracle.knm_v(X, C, sigma, V), K @ V, rtol=1e-12, atol=1e-12)
+        assert np.allclose(oracle.knm_t_w(X, C, sigma, Y), K.T @ Y, rtol=1e-12, atol=1e-12)
+        assert np.allclose(oracle.knm_prod(X, C, sigma, V), K.T @ (K @ V), rtol=1e-12, atol=1e-10)
+        T, A = oracle.precond(C, sigma, lam)
+        assert np.allclose(T.T @ T, Kmm, rtol=1e-10, atol=1e-12)
+        # converged fit = dense Nystrom solution of Eq. 5-6 with the same kernel
+        alpha = oracle.falkon_fit(X, Y, C, sigma, lam, 40)
+        H = K.T @ K + lam * n * Kmm
+        ref = sla.solve(H, K.T @ Y, assume_a="sym")
+        assert np.linalg.norm(K @ alpha - K @ ref) <= 1e-6 * np.linalg.norm(K @ ref)
