@@ -16,6 +16,10 @@
  *  - Work is enqueued on the context's HIP stream.  Calls return without synchronising
  *    unless a host value is needed (Cholesky status, CG scalars, timing queries).
  *  - Outputs are overwritten, never accumulated into.
+ *  - The product entry points (knm_v, knm_prod, knm_prod_weighted, knm_t_y, falkon_predict) allocate
+ *    only when the library-owned workspace has to grow; a repeated call with the same shapes only
+ *    enqueues kernels (no memset or copy nodes, no synchronisation), so it can be captured into a
+ *    HIP graph on the context's stream.  The solver entry points allocate and synchronise.
  *  - Return value: KNM_OK (0) or a negative knm_status.  No exception crosses the ABI.
  *  - Indices are 64-bit; n * d and n * M may exceed 2^32.
  *  - Results are deterministic: partial sums are merged in a fixed order (no atomics).

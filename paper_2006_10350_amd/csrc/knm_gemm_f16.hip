@@ -606,6 +606,9 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     }
 }
 
+// zeroes the head of the workspace (one thread per word)
+__global__ void clear_head_kernel(uint32_t *__restrict__ head) { head[threadIdx.x] = 0u; }
+
 // bits of max_i |vec[i, c] wgt[i]| per column (non-negative floats order like their bit patterns)
 __global__ void col_absmax_kernel(const float *__restrict__ vec, int64_t ldv, const float *__restrict__ wgt, int64_t n,
                                   int t, uint32_t *__restrict__ out)
@@ -706,7 +709,9 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
     const bool mv = a.t > 16 || (a.t >= kMvMinT && 4 * (3 + a.t) >= 3 * n_kc + 1);
     if (mv) {
         // largest magnitude of every vector column: the power-of-two scale into the fp16 range
-        hipError_t e = hipMemsetAsync(colmax, 0, kHeadBytes, stream);
+        // cleared by a kernel, not a memset node: the product entry points may be captured into a graph
+        hipLaunchKernelGGL(clear_head_kernel, dim3(1), dim3(kHeadBytes / sizeof(uint32_t)), 0, stream, colmax);
+        hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         int64_t blocks = (a.nS + 7) / 8;
         if (blocks > 4096) blocks = 4096;

@@ -274,3 +274,39 @@ def test_workload_shaped_sample(knm, cross, name, n_sub, M_sub):
     v = synth.probe_vector(w.M, 1, "normal")
     U = knm.knm_prod(X.cuda(), C.cuda(), w.sigma, v.cuda()).cpu().numpy()
     assert rel_l2(U, oracle.knm_prod(X.numpy(), C.numpy(), w.sigma, v.numpy())) < TOL
+
+
+@pytest.mark.parametrize("n,M,d,t,sigma", [(3000, 700, 28, 1, 4.0), (2100, 600, 100, 12, 7.0), (1500, 400, 9, 3, 2.0)])
+def test_product_replays_in_a_graph(knm, n, M, d, t, sigma):
+    """Once the workspace exists (one eager call with the same shapes) a product only enqueues kernels
+    on the context's stream, so it can be captured into a graph.  Every replay, with new inputs and
+    eager work in between, must give the eager result bit for bit."""
+    side = torch.cuda.Stream()
+    X, C, V = _rand(n, d, 70).cuda(), _rand(M, d, 71).cuda(), _rand(M, t, 72).cuda()
+    U = torch.empty(M, t, device="cuda", dtype=torch.float32)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        ctx = knm.Context()  # bound to the side stream
+        knm.knm_prod(X, C, sigma, V, out=U, ctx=ctx)  # allocates the workspace
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            knm.knm_prod(X, C, sigma, V, out=U, ctx=ctx)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        print(f"replay {rep}", flush=True)
+        X.copy_(_rand(n, d, 80 + rep).cuda())
+        V.copy_(_rand(M, t, 90 + rep).cuda())
+        if rep == 2:
+            V[:, 0] = 0.0
+        U.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = U.clone()
+        want = knm.knm_prod(X, C, sigma, V)  # eager, default context and stream
+        torch.cuda.synchronize()
+        assert torch.equal(got, want.reshape(M, t)), rep
+        assert rel_l2(got.cpu().numpy(), oracle.knm_prod(X.cpu().numpy(), C.cpu().numpy(), sigma, V.cpu().numpy())) < TIGHT
+    del graph
+    ctx.close()
