@@ -220,6 +220,15 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
                   const double *lambdas, const int *iters, int n_steps, double jitter,
                   float *alpha, double *loss_or_null);
 
+/* logfalkon_fit for CSR X (n rows) and CSR centres (M rows) over d features: the same Newton
+ * iteration on the sparse sweeps (Alg. 2 with the products of Sec. 4, "Dealing with sparse
+ * datasets"); CSR arguments as for knm_prod_csr, everything else as for logfalkon_fit. */
+int logfalkon_fit_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values,
+                      int64_t n, const float *y, const int64_t *c_indptr, const int64_t *c_indices,
+                      const float *c_values, int64_t M, int64_t d, const float *yC, float sigma,
+                      const double *lambdas, const int *iters, int n_steps, double jitter, float *alpha,
+                      double *loss_or_null);
+
 /* Wall-clock seconds of the phases of the most recent successful falkon_fit on this context,
  * written to the HOST array seconds[4]: [0] preconditioner, [1] right-hand side
  * (K_nm^T Y and two solves), [2] all conjugate-gradient iterations, [3] final solves. */

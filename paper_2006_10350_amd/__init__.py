@@ -63,6 +63,8 @@ SIGNATURES = {
                           _vp, _vp]),
     "logfalkon_fit": (_int, [_vp, _vp, _i64, _int, _i64, _vp, _vp, _i64, _i64, _vp, _f32, _vp, _vp, _int, _f64,
                              _vp, _vp]),
+    "logfalkon_fit_csr": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _f32, _vp, _vp, _int,
+                                 _f64, _vp, _vp]),
     "knm_get_fit_timing": (_int, [_vp, ctypes.POINTER(_f64)]),
     "falkon_predict": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
     "knm_set_cross_term": (_int, [_vp, _int]),
@@ -501,6 +503,33 @@ def logfalkon_fit(X, y, C, yC, sigma: float, lambdas, iters, jitter: float = 0.0
     ctx.check(load_library().logfalkon_fit(ctx._h, X.data_ptr(), n, d, ldx, y.data_ptr(), C.data_ptr(), M, ldc,
                                            yC.data_ptr(), float(sigma), lam.ctypes.data, its.ctypes.data,
                                            int(lam.size), float(jitter), alpha.data_ptr(), loss.ctypes.data))
+    return (alpha, loss) if return_loss else alpha
+
+
+def logfalkon_fit_csr(X, y, C, yC, sigma: float, lambdas, iters, jitter: float = 0.0, return_loss: bool = False,
+                      ctx: Optional[Context] = None):
+    """logfalkon_fit for sparse CSR X and C."""
+    import numpy as np
+
+    ctx = ctx or default_context()
+    xr, xc, xv = _csr_parts(X, "X")
+    cr, cc, cv = _csr_parts(C, "C")
+    n, d = X.shape
+    M = C.shape[0]
+    if C.shape[1] != d:
+        raise ValueError("X and C must have the same number of features")
+    y, _, _ = _cols(y, n, "y")
+    yC, _, _ = _cols(yC, M, "yC")
+    lam = np.ascontiguousarray(lambdas, dtype=np.float64)
+    its = np.ascontiguousarray(iters, dtype=np.int32)
+    if lam.ndim != 1 or lam.shape != its.shape or lam.size == 0:
+        raise ValueError("lambdas and iters must be equally long, non-empty sequences")
+    alpha = torch.empty(M, device=xv.device, dtype=torch.float32)
+    loss = np.zeros(lam.size + 1, dtype=np.float64)
+    ctx.check(load_library().logfalkon_fit_csr(ctx._h, xr.data_ptr(), xc.data_ptr(), xv.data_ptr(), n, y.data_ptr(),
+                                               cr.data_ptr(), cc.data_ptr(), cv.data_ptr(), M, d, yC.data_ptr(),
+                                               float(sigma), lam.ctypes.data, its.ctypes.data, int(lam.size),
+                                               float(jitter), alpha.data_ptr(), loss.ctypes.data))
     return (alpha, loss) if return_loss else alpha
 
 

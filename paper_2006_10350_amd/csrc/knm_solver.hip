@@ -1333,24 +1333,15 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
     return knm_v(ctx, Xtest, ntest, d, ldx, C, M, ldc, sigma, alpha, t, out);
 }
 
-int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *y, const float *C, int64_t M,
-                  int64_t ldc, const float *yC, float sigma, const double *lambdas, const int *iters, int n_steps,
-                  double jitter, float *alpha, double *loss_or_null)
+// Newton iteration of the logistic fit (Alg. 2) on whatever storage the points have: `ops` are the
+// two sweeps of k(X, C), `centres_v` gives k(C, C) a (M floats); p holds T (its second factor is
+// rebuilt at every step) and is freed on return.
+static int logfalkon_core(knm_ctx *ctx, const KernelOps &ops, const std::function<int(const float *, float *)> &centres_v,
+                          knm_precond *p, const float *y, const float *yC, const double *lambdas, const int *iters,
+                          int n_steps, double jitter, float *alpha, double *loss_or_null)
 {
-    if (!ctx) return KNM_INVALID_ARG;
-    if (!X || !y || !C || !yC || !alpha || !lambdas || !iters || n <= 0 || M <= 0 || d <= 0 || n_steps <= 0 ||
-        ldx < d || ldc < d || !(sigma > 0.0f) || !(jitter >= 0.0))
-        return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
-    for (int k = 0; k < n_steps; ++k)
-        if (!(lambdas[k] >= 0.0) || iters[k] <= 0) return fail(ctx, KNM_INVALID_ARG, "bad Newton schedule");
-    if (d > knm_max_d()) return fail(ctx, KNM_UNSUPPORTED, "d above compiled maximum");
-    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    const int64_t n = ops.n, M = ops.M;
     int st = KNM_OK;
-
-    // T depends on the centres only: built once; A is rebuilt per Newton step
-    knm_precond *p = nullptr;
-    st = precond_build_impl(ctx, C, M, d, ldc, sigma, lambdas[0], jitter, false, &p, nullptr);
-    if (st) return st;
     struct Guard {
         knm_precond *p;
         ~Guard() { precond_free(p); }
@@ -1381,7 +1372,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
     auto vec_ok = [&](int status) { return status == KNM_OK; };
     // predictions at the rows and at the centres for the current alpha, and the loss terms
     auto evaluate = [&](bool derivatives, double *mean_loss) -> int {
-        int s2 = do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, a32.as<float>(), 1, z.as<float>());
+        int s2 = ops.v(a32.as<float>(), 1, z.as<float>());
         if (s2) return s2;
         hipLaunchKernelGGL(logistic_terms_kernel, grid1(n), dim3(256), 0, ctx->stream, z.as<float>(), y, n,
                            derivatives ? g.as<float>() : nullptr, derivatives ? dw.as<float>() : nullptr,
@@ -1406,7 +1397,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         st = evaluate(true, loss_or_null ? loss_or_null + k : nullptr);
         if (st) return st;
         // weights at the centres -> second factor of the preconditioner for this step
-        st = do_knm_v(ctx, C, M, d, ldc, C, M, ldc, sigma, a32.as<float>(), 1, zc.as<float>());
+        st = centres_v(a32.as<float>(), zc.as<float>());
         if (st) return st;
         hipLaunchKernelGGL(logistic_terms_kernel, grid1(M), dim3(256), 0, ctx->stream, zc.as<float>(), yC, M,
                            (float *)nullptr, (float *)nullptr, dm.as<double>(), (double *)nullptr);
@@ -1414,7 +1405,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         st = build_second_factor(ctx, p, mu, dm.as<double>(), &bad);
         if (st) return st;
         // right-hand side  -P^T (K^T g + mu n (K_MM + eps I) alpha)
-        st = do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, g.as<float>(), nullptr, 1, u32.as<float>());
+        st = ops.t_w(g.as<float>(), nullptr, 1, u32.as<float>());
         if (st) return st;
         hipLaunchKernelGGL(newton_rhs_kernel, grid1(M), dim3(256), 0, ctx->stream, u32.as<float>(), zc.as<float>(), da,
                            mu * (double)n, jitter, M, dr);
@@ -1427,7 +1418,7 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
         double rho = 0.0;
         if (!vec_ok(vec_dot(ctx, M, dr, dr, &rho))) return fail(ctx, KNM_HIP_ERROR, "vector reduction");
         for (int it = 0; it < iters[k]; ++it) {
-            st = linop_cols(ctx, p, wk, dense_ops(ctx, X, n, d, ldx, C, M, ldc, sigma), mu, dp, 1, dq, dw.as<float>());
+            st = linop_cols(ctx, p, wk, ops, mu, dp, 1, dq, dw.as<float>());
             if (st) return st;
             double pq = 0.0, rn = 0.0;
             if (!vec_ok(vec_dot(ctx, M, dp, dq, &pq))) return fail(ctx, KNM_HIP_ERROR, "vector reduction");
@@ -1458,6 +1449,60 @@ int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, c
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream); // temporaries are freed on return
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "logfalkon_fit", e);
     return KNM_OK;
+}
+
+
+int logfalkon_fit(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *y, const float *C, int64_t M,
+                  int64_t ldc, const float *yC, float sigma, const double *lambdas, const int *iters, int n_steps,
+                  double jitter, float *alpha, double *loss_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!X || !y || !C || !yC || !alpha || !lambdas || !iters || n <= 0 || M <= 0 || d <= 0 || n_steps <= 0 ||
+        ldx < d || ldc < d || !(sigma > 0.0f) || !(jitter >= 0.0))
+        return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
+    for (int k = 0; k < n_steps; ++k)
+        if (!(lambdas[k] >= 0.0) || iters[k] <= 0) return fail(ctx, KNM_INVALID_ARG, "bad Newton schedule");
+    if (d > knm_max_d()) return fail(ctx, KNM_UNSUPPORTED, "d above compiled maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    int st = KNM_OK;
+    // T depends on the centres only: built once; A is rebuilt per Newton step
+    knm_precond *p = nullptr;
+    st = precond_build_impl(ctx, C, M, d, ldc, sigma, lambdas[0], jitter, false, &p, nullptr);
+    if (st) return st;
+    const KernelOps ops = dense_ops(ctx, X, n, d, ldx, C, M, ldc, sigma);
+    auto centres_v = [=](const float *a, float *zc) { return do_knm_v(ctx, C, M, d, ldc, C, M, ldc, sigma, a, 1, zc); };
+    return logfalkon_core(ctx, ops, centres_v, p, y, yC, lambdas, iters, n_steps, jitter, alpha, loss_or_null);
+}
+
+int logfalkon_fit_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_indices, const float *x_values, int64_t n,
+                      const float *y, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M,
+                      int64_t d, const float *yC, float sigma, const double *lambdas, const int *iters, int n_steps,
+                      double jitter, float *alpha, double *loss_or_null)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!x_indptr || !c_indptr || !y || !yC || !alpha || !lambdas || !iters || n <= 0 || M <= 0 || d <= 0 ||
+        n_steps <= 0 || !(sigma > 0.0f) || !(jitter >= 0.0))
+        return fail(ctx, KNM_INVALID_ARG, "bad fit argument");
+    for (int k = 0; k < n_steps; ++k)
+        if (!(lambdas[k] >= 0.0) || iters[k] <= 0) return fail(ctx, KNM_INVALID_ARG, "bad Newton schedule");
+    if (d >= 0x7fffffffLL || M >= 0x7fffffffLL) return fail(ctx, KNM_UNSUPPORTED, "d or M above the supported maximum");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    // the sweeps of k(X, C) and of k(C, C); both outlive the fit, which uses their workspaces
+    SparseProducts sp, spc;
+    int st = sp.prepare(ctx, x_indptr, x_indices, x_values, n, c_indptr, c_indices, c_values, M, d, sigma);
+    if (!st) st = spc.prepare(ctx, c_indptr, c_indices, c_values, M, c_indptr, c_indices, c_values, M, d, sigma);
+    if (st) return st;
+    knm_precond *p = nullptr;
+    auto fill = [=](double *K) { return sparse_kmm(ctx, c_indptr, c_indices, c_values, M, d, sigma, jitter, K); };
+    st = precond_build_from(ctx, M, fill, lambdas[0], jitter, false, &p, nullptr);
+    if (st) return st;
+    KernelOps ops;
+    ops.n = n;
+    ops.M = M;
+    ops.v = [&sp](const float *V, int tt, float *W) { return sp.v(V, tt, W); };
+    ops.t_w = [&sp](const float *W, const float *wgt, int tt, float *U) { return sp.t_w(W, wgt, tt, U); };
+    auto centres_v = [&spc](const float *a, float *zc) { return spc.v(a, 1, zc); };
+    return logfalkon_core(ctx, ops, centres_v, p, y, yC, lambdas, iters, n_steps, jitter, alpha, loss_or_null);
 }
 
 } // extern "C"

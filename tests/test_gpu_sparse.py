@@ -132,6 +132,32 @@ def test_sparse_fit_and_predict_match_the_dense_oracle(knm):
     assert rel_l2(pred.cpu().numpy(), po) < 1e-3
 
 
+def test_sparse_logistic_fit_matches_the_dense_oracle(knm):
+    """Alg. 2 on CSR inputs against the oracle's Newton iteration on the densified inputs: the loss
+    after every step and the predictions on training and held-out rows."""
+    n, M, d, sigma, jitter = 3000, 200, 1200, 5.0, 1e-6
+    s, X, C, Xd, Cd = _case(n, M, d, 15.0, seed=41)
+    g = torch.Generator().manual_seed(5)
+    wtrue = torch.randn(d, generator=g)
+    score = 0.08 * torch.from_numpy(Xd) @ wtrue + 0.3 * torch.randn(n, generator=g)
+    y = torch.where(score >= score.median(), 1.0, -1.0).to(torch.float32)
+    yC = y[s["centre_rows"]].clone()
+    lambdas, iters = [1e-2, 1e-3, 1e-3], [4, 5, 5]
+    alpha, loss = knm.logfalkon_fit_csr(X, y.cuda(), C, yC.cuda(), sigma, lambdas, iters, jitter, return_loss=True)
+    ao, lo = oracle.logfalkon_fit(Xd, y.numpy(), Cd, yC.numpy(), sigma, lambdas, iters, jitter, return_loss=True)
+    print(f"losses gpu {loss} oracle {lo}", flush=True)
+    assert np.allclose(loss, lo, rtol=1e-4, atol=1e-6)
+    assert loss[0] == pytest.approx(np.log(2.0), rel=1e-6) and np.all(np.diff(loss) < 0)
+    fit = knm.knm_v_csr(X, C, sigma, alpha).cpu().numpy()
+    assert rel_l2(fit, oracle.falkon_predict(Xd, Cd, sigma, ao)) < 1e-3
+    st, Xt, _, Xtd, _ = _case(400, 8, d, 15.0, seed=42)
+    pred = knm.knm_v_csr(Xt, C, sigma, alpha).cpu().numpy()
+    assert rel_l2(pred, oracle.falkon_predict(Xtd, Cd, sigma, ao)) < 1e-3
+    assert float((np.sign(fit) == y.numpy()).mean()) > 0.7
+    with pytest.raises(knm.KnmError):
+        knm.logfalkon_fit_csr(X, y.cuda(), C, yC.cuda(), sigma, [1e-2, -1.0], [3, 3], jitter)
+
+
 def test_sparse_preconditioner_factors_match_oracle(knm):
     M, d, sigma, lam, jitter = 300, 900, 4.0, 1e-4, 1e-8
     s, X, C, Xd, Cd = _case(600, M, d, 12.0, seed=31)
