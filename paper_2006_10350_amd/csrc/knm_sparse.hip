@@ -183,11 +183,61 @@ __global__ void rank_one_init_kernel(const float *__restrict__ e, int64_t rows, 
     if (r < rows) out[r * ldo] = (float)((double)e[r] * s);
 }
 
+// Orders a wavefront's accesses to its private accumulator: everything it has issued (atomics
+// without a return value included) has been performed at the L2, where all accesses to the
+// accumulator take place, before anything that follows.  A workgroup-scope fence is that wait and
+// nothing else; a device-scope one would also write back and invalidate the XCD's whole L2 at every
+// row, which evicts the accumulator lines the next pass is about to hit.
+__device__ __forceinline__ void accumulator_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
+
+// Work list of X (see SparseArgs): one wavefront per row looks every entry's feature up in the
+// centre lists once, so that the sweeps stream (start, length, value) instead of reading the
+// d + 1 list pointers at random for every entry, pass and sweep; entries whose feature occurs in no
+// centre drop out.
+__global__ __launch_bounds__(kSpThreads) void build_work_kernel(const int64_t *__restrict__ x_indptr,
+                                                               const int64_t *__restrict__ x_indices,
+                                                               const float *__restrict__ x_values, int64_t n,
+                                                               const int *__restrict__ col_ptr, int *__restrict__ work_count,
+                                                               int *__restrict__ work_q0, int *__restrict__ work_len,
+                                                               float *__restrict__ work_val)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * kSpWaves + (threadIdx.x >> 6);
+    const int64_t waves = (int64_t)gridDim.x * kSpWaves;
+    for (int64_t row = wave; row < n; row += waves) {
+        const int64_t p0 = x_indptr[row], p1 = x_indptr[row + 1];
+        int64_t kept = 0;
+        for (int64_t p = p0; p < p1; p += 64) {
+            int q0 = 0, len = 0;
+            float xv = 0.0f;
+            if (p + lane < p1) {
+                const int64_t col = x_indices[p + lane];
+                xv = x_values[p + lane];
+                q0 = col_ptr[col];
+                len = col_ptr[col + 1] - q0;
+            }
+            const unsigned long long keep = __ballot(len > 0);
+            if (len > 0) {
+                const int64_t at = p0 + kept + __popcll(keep & ((1ull << lane) - 1ull));
+                work_q0[at] = q0;
+                work_len[at] = len;
+                work_val[at] = xv;
+            }
+            kept += __popcll(keep);
+        }
+        if (lane == 0) work_count[row] = (int)kept;
+    }
+}
+
 struct SparseArgs {
-    const int64_t *x_indptr, *x_indices;
-    const float *x_values;
+    const int64_t *x_indptr;
+    // work list of X: per row the entries whose feature occurs in some centre, packed to the front
+    // of the row's own range [x_indptr[r], x_indptr[r] + work_count[r]): start and length of the
+    // feature's centre list and the entry's value
+    const int *work_count, *work_q0, *work_len;
+    const float *work_val;
     int64_t n, M;
-    const int *col_ptr, *csc_row;
+    const int *csc_row;
     const float *csc_val;
     const float *xn, *cn; // squared norms
     const float *xa;      // a_i
@@ -216,7 +266,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
     const int64_t waves = (int64_t)gridDim.x * kSpWaves;
     float *acc = a.acc + wave * a.M;
     for (int64_t row = wave; row < a.n; row += waves) {
-        const int64_t p0 = a.x_indptr[row], p1 = a.x_indptr[row + 1];
+        const int64_t p0 = a.x_indptr[row], p1 = p0 + a.work_count[row];
         const float xn = a.xn[row];
         const float wrow = COLUMN_SWEEP ? a.vec[row * a.ldv] : 0.0f;
         float sum = 0.0f;
@@ -227,10 +277,9 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
                 int q0 = 0, q1 = 0;
                 float xv = 0.0f;
                 if (mine) {
-                    const int64_t col = a.x_indices[p + lane];
-                    xv = a.x_values[p + lane];
-                    q0 = a.col_ptr[col];
-                    q1 = a.col_ptr[col + 1];
+                    q0 = a.work_q0[p + lane];
+                    q1 = q0 + a.work_len[p + lane];
+                    xv = a.work_val[p + lane];
                 }
                 const int len = q1 - q0;
                 unsigned long long longs = __ballot(len >= kLongList);
@@ -268,7 +317,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
                         }
                     }
             }
-            __threadfence(); // every lane's updates of the accumulator are done before the next pass or row
+            accumulator_fence(); // every lane's updates are done before the next pass or row
         }
         if (!COLUMN_SWEEP) {
             sum += __shfl_xor(sum, 32);
@@ -326,7 +375,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_kmm_kernel(const int64_t *_
             if (len < kLongList)
                 for (int q = q0; q < q1; ++q) unsafeAtomicAdd(&acc[csc_row[q]], xv * (double)csc_val[q]);
         }
-        __threadfence();
+        accumulator_fence();
         const double ci = cn[row];
         for (int64_t j = lane; j < M; j += 64) {
             // written by atomics (at the L2): read and cleared there too, past the first-level cache
@@ -334,7 +383,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_kmm_kernel(const int64_t *_
             if (g != 0.0) __hip_atomic_store(&acc[j], 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (j >= row) K[row + j * M] = exp(-(ci + cn[j] - 2.0 * g) * inv2s2) + (j == row ? jitter : 0.0);
         }
-        __threadfence();
+        accumulator_fence();
     }
 }
 
@@ -444,7 +493,7 @@ struct SparseProducts::Impl {
     float inv2s2 = 0.0f, inv_s2 = 0.0f;
     int64_t wgs = 0;
     CentreLists lists;
-    DevMem xn, cn, xa, cb, acc, part, tmp;
+    DevMem xn, cn, xa, cb, acc, part, tmp, work_count, work_q0, work_len, work_val;
 
     int rank_one_sum(const float *ev, const float *vec, int64_t ldv, int64_t rows, double *out)
     {
@@ -463,11 +512,12 @@ struct SparseProducts::Impl {
     {
         SparseArgs a;
         a.x_indptr = x_indptr;
-        a.x_indices = x_indices;
-        a.x_values = x_values;
+        a.work_count = work_count.as<int>();
+        a.work_q0 = work_q0.as<int>();
+        a.work_len = work_len.as<int>();
+        a.work_val = work_val.as<float>();
         a.n = n;
         a.M = M;
-        a.col_ptr = lists.col_ptr.as<int>();
         a.csc_row = lists.csc_row.as<int>();
         a.csc_val = lists.csc_val.as<float>();
         a.xn = xn.as<float>();
@@ -525,6 +575,16 @@ int SparseProducts::prepare(knm_ctx *ctx, const int64_t *x_indptr, const int64_t
     hipLaunchKernelGGL(norm_factor_kernel, grid_for(M), dim3(256), 0, st, s.cn.as<float>(), M, s.inv2s2, s.cb.as<float>());
     stat = s.lists.build(ctx, c_indptr, c_indices, c_values, M, d, nnz_c);
     if (stat) return stat;
+    const size_t work = (size_t)(nnz_x > 0 ? nnz_x : 1);
+    if (s.work_count.alloc(sizeof(int) * n) != hipSuccess || s.work_q0.alloc(sizeof(int) * work) != hipSuccess ||
+        s.work_len.alloc(sizeof(int) * work) != hipSuccess || s.work_val.alloc(sizeof(float) * work) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, KNM_ALLOC, "hipMalloc(sparse work list)");
+    }
+    hipLaunchKernelGGL(build_work_kernel, dim3((unsigned)s.wgs), dim3(kSpThreads), 0, st, x_indptr, x_indices, x_values, n,
+                       s.lists.col_ptr.as<int>(), s.work_count.as<int>(), s.work_q0.as<int>(), s.work_len.as<int>(),
+                       s.work_val.as<float>());
+    if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "work list launch");
     hipError_t e = hipMemsetAsync(s.acc.p, 0, sizeof(float) * waves * M, st);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
     return KNM_OK;
