@@ -173,7 +173,9 @@ def sparse_benchmark(args) -> int:
         "roofline": {"bound": "hbm", "kernel": "sparse_sweep_kernel", "achieved": bytes_per_product / elapsed / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": bytes_per_product / elapsed / 1e9 / PEAK_HBM_GBS,
                      "traffic": None,
-                     "note": "scattered 4-byte atomic updates: bound by L2 atomic latency, far from the HBM roofline"},
+                     "note": "bytes of the all-sparse walk (every pair that shares a feature); the most frequent features' "
+                             "pairs are in fact covered by one dense product, the rest by scattered 4-byte atomics bound by "
+                             "L2 atomic latency, far from the HBM roofline"},
         "u_finite": bool(torch.isfinite(U).all()),
     }))
     return 0

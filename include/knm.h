@@ -267,6 +267,12 @@ int knm_set_cross_term(knm_ctx *ctx, int mode);
 typedef enum { KNM_KERNEL_GAUSSIAN = 0, KNM_KERNEL_LAPLACIAN = 1 } knm_kernel_kind;
 int knm_set_kernel(knm_ctx *ctx, int kind);
 
+/* Sparse (CSR) entry points: the features that occur in the largest share of the centres (at most
+ * max_features of them, capped at 64; 0 switches this off; default 64) are taken out of the sparse
+ * walk and handled by one dense product over those features, when that is estimated to be cheaper.
+ * The result is the same kernel product up to rounding. */
+int knm_set_sparse_head_limit(knm_ctx *ctx, int max_features);
+
 /* Cap, in bytes, on the library-owned workspace that holds the converted operands of the
  * split-fp16 engines (0 restores the defaults: 2 GiB, or 8 GiB for the K-loop engine).  Operands
  * that do not fit are converted and swept slab by slab; results do not depend on the cap.  The

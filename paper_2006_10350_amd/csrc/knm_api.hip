@@ -349,6 +349,14 @@ int knm_set_kernel(knm_ctx *ctx, int kind)
     return KNM_OK;
 }
 
+int knm_set_sparse_head_limit(knm_ctx *ctx, int max_features)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (max_features < 0) return fail(ctx, KNM_INVALID_ARG, "negative head limit");
+    ctx->sparse_head_max = max_features > 64 ? 64 : max_features;
+    return KNM_OK;
+}
+
 int knm_set_pack_limit(knm_ctx *ctx, size_t bytes)
 {
     if (!ctx) return KNM_INVALID_ARG;

@@ -140,6 +140,8 @@ struct knm_ctx {
     size_t pack_limit = 0;     // cap on the image workspace chosen by the caller; 0 = engine defaults
     int cross_term = KNM_CROSS_F16X3;
     int kernel_kind = KNM_KERNEL_GAUSSIAN;
+    // sparse inputs: most frequent features treated densely, at most (0: none)
+    int sparse_head_max = 64;
     // timing
     bool timing = false;
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};

@@ -21,6 +21,13 @@
 // order, hence the last bits, vary from run to run).  Long centre lists are walked by the whole
 // wavefront, short ones by the lane that owns the feature.  The additions are the hardware's
 // fp32 atomic add (the accumulators and U live in ordinary device memory).
+//
+// What a row has to walk is prepared once per (X, C): a work list with the start and length of
+// the centre list of every entry whose feature occurs in a centre at all.  The few features that
+// occur in a large share of the centres are not walked: their pairs are covered by one dense
+// product over those features (see "head features" below), which takes the place of the
+// rank-one term.
+#include <algorithm>
 #include <vector>
 
 #include "knm_internal.h"
@@ -33,6 +40,7 @@ constexpr int kSpWaves = kSpThreads / 64;
 constexpr int kLongList = 32;     // centre lists at least this long are walked by the whole wavefront
 constexpr int kScanChunk = 4096;  // elements per workgroup of the prefix sum
 constexpr int64_t kFillGroup = 128; // rows of C per launch of the CSC fill
+constexpr int kMaxHead = 64;        // features treated densely, at most (one dense row of X^H and C^H each)
 
 // flag |= 1 if the CSR structure is not usable: indptr not starting at 0, decreasing, running
 // past nnz, or the column indices of a row not strictly increasing inside [0, d)
@@ -190,42 +198,128 @@ __global__ void rank_one_init_kernel(const float *__restrict__ e, int64_t rows, 
 // row, which evicts the accumulator lines the next pass is about to hit.
 __device__ __forceinline__ void accumulator_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
 
+// ---- head features ---------------------------------------------------------------------
+//
+// A feature that occurs in a large share of the centres (and hence of the rows) makes nearly every
+// pair of points share a feature: its centre list is long and is walked for every row that has
+// the feature, and a handful of such features carry most of the pair updates.  They are taken out
+// of the sparse walk and treated densely instead.  With H the set of head features, x^H / c^H the
+// dense head parts of the points and g = g^H + g^T split accordingly,
+//   K_ij = KH_ij + KH_ij (exp(g^T_ij / sigma^2) - 1),    KH_ij = a_i b_j exp(g^H_ij / sigma^2),
+// the first term over all pairs and the second only over pairs that share a tail feature.  KH is
+// the Gaussian kernel of the head parts times the factors a^T_i = exp(-|x^T_i|^2 / 2 sigma^2) and
+// b^T_j of the tail parts' norms, so its sweep is one dense product with d = |H| on the dense
+// engines; the second term is the sparse walk over the tail features, whose pairs read g^H from
+// the dense head rows of the few head features their row has.
+
+// features whose centre list has at least min_len entries: (feature, list start, length)
+__global__ void head_candidates_kernel(const int *__restrict__ col_ptr, int64_t d, int min_len, int cap,
+                                       int *__restrict__ count, int *__restrict__ cand)
+{
+    const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= d) return;
+    const int q0 = col_ptr[f], len = col_ptr[f + 1] - q0;
+    if (len < min_len) return;
+    const int at = atomicAdd(count, 1);
+    if (at < cap) {
+        cand[3 * at] = (int)f;
+        cand[3 * at + 1] = q0;
+        cand[3 * at + 2] = len;
+    }
+}
+
+struct HeadLists {
+    int q0[kMaxHead], len[kMaxHead];
+};
+
+// CH[j, h] = c_j's value of head feature h (CH zeroed before); blockIdx.y = h
+__global__ void head_centres_kernel(HeadLists hl, int Hn, const int *__restrict__ csc_row,
+                                    const float *__restrict__ csc_val, float *__restrict__ CH)
+{
+    const int h = blockIdx.y;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < hl.len[h]) CH[(int64_t)csc_row[hl.q0[h] + k] * Hn + h] = csc_val[hl.q0[h] + k];
+}
+
+// e[r] = exp(-(norm[r] - |row r of PH|^2) / 2 sigma^2): the factor of the tail part's norm
+__global__ void tail_factor_kernel(const float *__restrict__ norms, const float *__restrict__ PH, int Hn, int64_t rows,
+                                   float inv2s2, float *__restrict__ e)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= rows) return;
+    float hn = 0.0f;
+    for (int h = 0; h < Hn; ++h) hn = fmaf(PH[r * Hn + h], PH[r * Hn + h], hn);
+    e[r] = expf(-fmaxf(norms[r] - hn, 0.0f) * inv2s2);
+}
+
+// out[r * ldo] = e[r] * x[r * ldx]
+__global__ void scale_kernel(const float *__restrict__ e, const float *__restrict__ x, int64_t ldx, int64_t rows,
+                             float *__restrict__ out, int64_t ldo)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows) out[r * ldo] = e[r] * x[r * ldx];
+}
+
 // Work list of X (see SparseArgs): one wavefront per row looks every entry's feature up in the
 // centre lists once, so that the sweeps stream (start, length, value) instead of reading the
 // d + 1 list pointers at random for every entry, pass and sweep; entries whose feature occurs in no
-// centre drop out.
+// centre drop out.  Entries of head features (head_feat: Hn ids, ascending) go to the back of
+// the row's range as (head index, value) and into the dense row XH[row, :] (zeroed before).
 __global__ __launch_bounds__(kSpThreads) void build_work_kernel(const int64_t *__restrict__ x_indptr,
                                                                const int64_t *__restrict__ x_indices,
                                                                const float *__restrict__ x_values, int64_t n,
-                                                               const int *__restrict__ col_ptr, int *__restrict__ work_count,
+                                                               const int *__restrict__ col_ptr,
+                                                               const int *__restrict__ head_feat, int Hn, int head_min_len,
+                                                               int *__restrict__ work_count, int *__restrict__ head_count,
                                                                int *__restrict__ work_q0, int *__restrict__ work_len,
-                                                               float *__restrict__ work_val)
+                                                               float *__restrict__ work_val, float *__restrict__ XH)
 {
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * kSpWaves + (threadIdx.x >> 6);
     const int64_t waves = (int64_t)gridDim.x * kSpWaves;
     for (int64_t row = wave; row < n; row += waves) {
         const int64_t p0 = x_indptr[row], p1 = x_indptr[row + 1];
-        int64_t kept = 0;
+        int64_t kept = 0, heads = 0;
         for (int64_t p = p0; p < p1; p += 64) {
-            int q0 = 0, len = 0;
+            int q0 = 0, len = 0, h = -1;
             float xv = 0.0f;
             if (p + lane < p1) {
                 const int64_t col = x_indices[p + lane];
                 xv = x_values[p + lane];
                 q0 = col_ptr[col];
                 len = col_ptr[col + 1] - q0;
+                if (Hn > 0 && len >= head_min_len) { // binary search among the head features
+                    int lo = 0, hi = Hn - 1;
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if ((int64_t)head_feat[mid] < col) lo = mid + 1;
+                        else hi = mid;
+                    }
+                    if ((int64_t)head_feat[lo] == col) h = lo;
+                }
             }
-            const unsigned long long keep = __ballot(len > 0);
-            if (len > 0) {
-                const int64_t at = p0 + kept + __popcll(keep & ((1ull << lane) - 1ull));
+            const unsigned long long below = (1ull << lane) - 1ull;
+            const unsigned long long keep = __ballot(len > 0 && h < 0);
+            const unsigned long long head = __ballot(h >= 0);
+            if (len > 0 && h < 0) {
+                const int64_t at = p0 + kept + __popcll(keep & below);
                 work_q0[at] = q0;
                 work_len[at] = len;
                 work_val[at] = xv;
             }
+            if (h >= 0) {
+                const int64_t at = p1 - 1 - heads - __popcll(head & below);
+                work_q0[at] = h;
+                work_val[at] = xv;
+                XH[row * Hn + h] = xv;
+            }
             kept += __popcll(keep);
+            heads += __popcll(head);
         }
-        if (lane == 0) work_count[row] = (int)kept;
+        if (lane == 0) {
+            work_count[row] = (int)kept;
+            head_count[row] = (int)heads;
+        }
     }
 }
 
@@ -236,6 +330,12 @@ struct SparseArgs {
     // feature's centre list and the entry's value
     const int *work_count, *work_q0, *work_len;
     const float *work_val;
+    // head features (Hn = 0: none): per row the last head_count[r] slots of its range hold (head
+    // index, value); CH is the dense M x Hn image of the centres' head parts; tail_factor the
+    // factor a^T of the rows (row sweep); dense the head-kernel product of the row sweep
+    int Hn;
+    const int *head_count;
+    const float *CH, *tail_factor, *dense;
     int64_t n, M;
     const int *csc_row;
     const float *csc_val;
@@ -250,12 +350,13 @@ struct SparseArgs {
     double s_rank_one;    // row sweep: sum_j b_j v_j
 };
 
-// K_ij - a_i b_j from the dot product g and the squared norms
-__device__ __forceinline__ float pair_excess(float g, float xn, float cn, float inv2s2, float inv_s2)
+// K_ij - KH_ij from the tail part gt and the head part gh of the dot product and the squared norms
+// (no head features: gh = 0 and KH_ij = a_i b_j)
+__device__ __forceinline__ float pair_excess(float gt, float gh, float xn, float cn, float inv2s2, float inv_s2)
 {
-    const float e0 = (xn + cn) * inv2s2;
-    if (e0 < 80.0f) return expf(-e0) * expm1f(g * inv_s2);
-    return expf(g * inv_s2 - e0); // a_i b_j has underflowed: the excess is K_ij itself
+    const float e0 = (xn + cn) * inv2s2 - gh * inv_s2;
+    if (e0 < 80.0f) return expf(-e0) * expm1f(gt * inv_s2);
+    return expf(gt * inv_s2 - e0); // KH_ij has underflowed: the excess is K_ij itself
 }
 
 template <int COLUMN_SWEEP>
@@ -265,11 +366,32 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
     const int64_t wave = (int64_t)blockIdx.x * kSpWaves + (threadIdx.x >> 6);
     const int64_t waves = (int64_t)gridDim.x * kSpWaves;
     float *acc = a.acc + wave * a.M;
+    // the head features of the row in hand, for every lane of the wavefront to read
+    __shared__ int head_idx_all[kSpWaves][kMaxHead];
+    __shared__ float head_val_all[kSpWaves][kMaxHead];
+    int *const head_idx = head_idx_all[threadIdx.x >> 6];
+    float *const head_val = head_val_all[threadIdx.x >> 6];
     for (int64_t row = wave; row < a.n; row += waves) {
         const int64_t p0 = a.x_indptr[row], p1 = p0 + a.work_count[row];
         const float xn = a.xn[row];
         const float wrow = COLUMN_SWEEP ? a.vec[row * a.ldv] : 0.0f;
         float sum = 0.0f;
+        int hc = 0;
+        if (a.Hn > 0) {
+            hc = a.head_count[row];
+            const int64_t back = a.x_indptr[row + 1] - hc;
+            if (lane < hc) {
+                head_idx[lane] = a.work_q0[back + lane];
+                head_val[lane] = a.work_val[back + lane];
+            }
+            accumulator_fence(); // the wavefront's own LDS writes, before any lane reads them
+        }
+        // g^H_ij of the row in hand against centre j
+        auto head_dot = [&](int j) -> float {
+            float gh = 0.0f;
+            for (int k = 0; k < hc; ++k) gh = fmaf(head_val[k], a.CH[(int64_t)j * a.Hn + head_idx[k]], gh);
+            return gh;
+        };
         // pass 0 adds x_if c_jf into the accumulator; pass 1 takes every touched entry out again
         for (int pass = 0; pass < 2; ++pass) {
             for (int64_t p = p0; p < p1; p += 64) {
@@ -295,7 +417,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
                         } else {
                             const float g = atomicExch(&acc[j], 0.0f);
                             if (g != 0.0f) {
-                                const float ex = pair_excess(g, xn, a.cn[j], a.inv2s2, a.inv_s2);
+                                const float ex = pair_excess(g, head_dot(j), xn, a.cn[j], a.inv2s2, a.inv_s2);
                                 if (COLUMN_SWEEP) unsafeAtomicAdd(&a.out[j * a.ldo], ex * wrow);
                                 else sum += ex * a.vec[j * a.ldv];
                             }
@@ -310,7 +432,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
                         } else {
                             const float g = atomicExch(&acc[j], 0.0f);
                             if (g != 0.0f) {
-                                const float ex = pair_excess(g, xn, a.cn[j], a.inv2s2, a.inv_s2);
+                                const float ex = pair_excess(g, head_dot(j), xn, a.cn[j], a.inv2s2, a.inv_s2);
                                 if (COLUMN_SWEEP) unsafeAtomicAdd(&a.out[j * a.ldo], ex * wrow);
                                 else sum += ex * a.vec[j * a.ldv];
                             }
@@ -326,7 +448,10 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
             sum += __shfl_xor(sum, 4);
             sum += __shfl_xor(sum, 2);
             sum += __shfl_xor(sum, 1);
-            if (lane == 0) a.out[row * a.ldo] = (float)((double)a.xa[row] * a.s_rank_one) + sum;
+            if (lane == 0) {
+                const float all_pairs = a.Hn > 0 ? a.tail_factor[row] * a.dense[row] : (float)((double)a.xa[row] * a.s_rank_one);
+                a.out[row * a.ldo] = all_pairs + sum;
+            }
         }
     }
 }
@@ -494,6 +619,12 @@ struct SparseProducts::Impl {
     int64_t wgs = 0;
     CentreLists lists;
     DevMem xn, cn, xa, cb, acc, part, tmp, work_count, work_q0, work_len, work_val;
+    // head features: dense head parts XH (n x Hn), CH (M x Hn), factors of the tail norms, per-row
+    // head counts, and the vectors of the dense product (tmp_m over the centres, dense_n / tmp_n over
+    // the rows)
+    int Hn = 0;
+    float sigma = 0.0f;
+    DevMem head_feat, head_count, XH, CH, xat, cbt, tmp_m, dense_n, dense_m, tmp_n;
 
     int rank_one_sum(const float *ev, const float *vec, int64_t ldv, int64_t rows, double *out)
     {
@@ -508,6 +639,73 @@ struct SparseProducts::Impl {
         *out = s;
         return KNM_OK;
     }
+    // Chooses the head features from the centre lists and builds CH.  A feature qualifies with a
+    // list of at least max(16, M / 160) centres; the kMaxHead longest are taken if, on the estimate
+    // that a feature is as frequent in the rows as in the centres, they would cost more pair updates
+    // (n / M sum_h len_h^2) than the dense product costs entries (n M / 128 at the measured rates).
+    int choose_head(int64_t d, int64_t nnz_c, int max_head, int *min_len_out)
+    {
+        hipStream_t st = ctx->stream;
+        Hn = 0;
+        const int min_len = (int)(M / 160 > 16 ? M / 160 : 16);
+        *min_len_out = min_len;
+        if (max_head <= 0 || nnz_c < min_len) return KNM_OK;
+        if (max_head > kMaxHead) max_head = kMaxHead;
+        const int cap = (int)(nnz_c / min_len) + 1; // no more features than this can have such lists
+        DevMem count, cand;
+        if (count.alloc(sizeof(int)) != hipSuccess || cand.alloc(sizeof(int) * 3 * (size_t)cap) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, KNM_ALLOC, "hipMalloc(head candidates)");
+        }
+        hipError_t e = hipMemsetAsync(count.p, 0, sizeof(int), st);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
+        hipLaunchKernelGGL(head_candidates_kernel, grid_for(d), dim3(256), 0, st, lists.col_ptr.as<int>(), d, min_len, cap,
+                           count.as<int>(), cand.as<int>());
+        int found = 0;
+        e = hipMemcpyAsync(&found, count.p, sizeof(int), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "head candidates", e);
+        if (found <= 0) return KNM_OK;
+        if (found > cap) found = cap;
+        std::vector<int> host(3 * (size_t)found);
+        e = hipMemcpy(host.data(), cand.p, sizeof(int) * host.size(), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "head candidates", e);
+        struct Cand { int feat, q0, len; };
+        std::vector<Cand> cs((size_t)found);
+        for (int i = 0; i < found; ++i) cs[i] = {host[3 * i], host[3 * i + 1], host[3 * i + 2]};
+        // longest first; equal lengths by feature id, so the choice does not depend on the order
+        // in which the candidates were found
+        std::sort(cs.begin(), cs.end(), [](const Cand &x, const Cand &y) { return x.len != y.len ? x.len > y.len : x.feat < y.feat; });
+        if ((int)cs.size() > max_head) cs.resize((size_t)max_head);
+        double sq = 0.0;
+        for (const Cand &c : cs) sq += (double)c.len * (double)c.len;
+        if (sq * 128.0 < (double)M * (double)M) return KNM_OK;
+        std::sort(cs.begin(), cs.end(), [](const Cand &x, const Cand &y) { return x.feat < y.feat; });
+        Hn = (int)cs.size();
+        HeadLists hl;
+        int feats[kMaxHead], longest = 0;
+        for (int h = 0; h < kMaxHead; ++h) {
+            hl.q0[h] = h < Hn ? cs[h].q0 : 0;
+            hl.len[h] = h < Hn ? cs[h].len : 0;
+            feats[h] = h < Hn ? cs[h].feat : 0;
+            if (hl.len[h] > longest) longest = hl.len[h];
+        }
+        if (head_feat.alloc(sizeof(int) * kMaxHead) != hipSuccess || CH.alloc(sizeof(float) * (size_t)M * Hn) != hipSuccess ||
+            XH.alloc(sizeof(float) * (size_t)n * Hn) != hipSuccess || xat.alloc(sizeof(float) * n) != hipSuccess ||
+            cbt.alloc(sizeof(float) * M) != hipSuccess || tmp_m.alloc(sizeof(float) * M) != hipSuccess ||
+            dense_m.alloc(sizeof(float) * M) != hipSuccess || dense_n.alloc(sizeof(float) * n) != hipSuccess ||
+            tmp_n.alloc(sizeof(float) * n) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, KNM_ALLOC, "hipMalloc(head features)");
+        }
+        e = hipMemcpy(head_feat.p, feats, sizeof(int) * kMaxHead, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemsetAsync(CH.p, 0, sizeof(float) * (size_t)M * Hn, st);
+        if (e == hipSuccess) e = hipMemsetAsync(XH.p, 0, sizeof(float) * (size_t)n * Hn, st);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "head features", e);
+        hipLaunchKernelGGL(head_centres_kernel, dim3((unsigned)((longest + 255) / 256), (unsigned)Hn), dim3(256), 0, st, hl, Hn,
+                           lists.csc_row.as<int>(), lists.csc_val.as<float>(), CH.as<float>());
+        return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "head_centres_kernel launch");
+    }
     SparseArgs args()
     {
         SparseArgs a;
@@ -516,6 +714,11 @@ struct SparseProducts::Impl {
         a.work_q0 = work_q0.as<int>();
         a.work_len = work_len.as<int>();
         a.work_val = work_val.as<float>();
+        a.Hn = Hn;
+        a.head_count = head_count.as<int>();
+        a.CH = CH.as<float>();
+        a.tail_factor = xat.as<float>();
+        a.dense = dense_n.as<float>();
         a.n = n;
         a.M = M;
         a.csc_row = lists.csc_row.as<int>();
@@ -575,16 +778,28 @@ int SparseProducts::prepare(knm_ctx *ctx, const int64_t *x_indptr, const int64_t
     hipLaunchKernelGGL(norm_factor_kernel, grid_for(M), dim3(256), 0, st, s.cn.as<float>(), M, s.inv2s2, s.cb.as<float>());
     stat = s.lists.build(ctx, c_indptr, c_indices, c_values, M, d, nnz_c);
     if (stat) return stat;
+    s.sigma = sigma;
+    int head_min_len = 0;
+    stat = s.choose_head(d, nnz_c, ctx->sparse_head_max, &head_min_len);
+    if (stat) return stat;
     const size_t work = (size_t)(nnz_x > 0 ? nnz_x : 1);
-    if (s.work_count.alloc(sizeof(int) * n) != hipSuccess || s.work_q0.alloc(sizeof(int) * work) != hipSuccess ||
-        s.work_len.alloc(sizeof(int) * work) != hipSuccess || s.work_val.alloc(sizeof(float) * work) != hipSuccess) {
+    if (s.work_count.alloc(sizeof(int) * n) != hipSuccess || s.head_count.alloc(sizeof(int) * n) != hipSuccess ||
+        s.work_q0.alloc(sizeof(int) * work) != hipSuccess || s.work_len.alloc(sizeof(int) * work) != hipSuccess ||
+        s.work_val.alloc(sizeof(float) * work) != hipSuccess) {
         (void)hipGetLastError();
         return fail(ctx, KNM_ALLOC, "hipMalloc(sparse work list)");
     }
     hipLaunchKernelGGL(build_work_kernel, dim3((unsigned)s.wgs), dim3(kSpThreads), 0, st, x_indptr, x_indices, x_values, n,
-                       s.lists.col_ptr.as<int>(), s.work_count.as<int>(), s.work_q0.as<int>(), s.work_len.as<int>(),
-                       s.work_val.as<float>());
+                       s.lists.col_ptr.as<int>(), s.head_feat.as<int>(), s.Hn, head_min_len, s.work_count.as<int>(),
+                       s.head_count.as<int>(), s.work_q0.as<int>(), s.work_len.as<int>(), s.work_val.as<float>(),
+                       s.XH.as<float>());
     if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "work list launch");
+    if (s.Hn > 0) {
+        hipLaunchKernelGGL(tail_factor_kernel, grid_for(n), dim3(256), 0, st, s.xn.as<float>(), s.XH.as<float>(), s.Hn, n,
+                           s.inv2s2, s.xat.as<float>());
+        hipLaunchKernelGGL(tail_factor_kernel, grid_for(M), dim3(256), 0, st, s.cn.as<float>(), s.CH.as<float>(), s.Hn, M,
+                           s.inv2s2, s.cbt.as<float>());
+    }
     hipError_t e = hipMemsetAsync(s.acc.p, 0, sizeof(float) * waves * M, st);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
     return KNM_OK;
@@ -596,8 +811,17 @@ int SparseProducts::v(const float *V, int t, float *W)
     Impl &s = *impl;
     for (int c = 0; c < t; ++c) {
         double sum = 0.0;
-        int stat = s.rank_one_sum(s.cb.as<float>(), V + c, t, s.M, &sum);
-        if (stat) return stat;
+        if (s.Hn > 0) {
+            // all pairs: a^T_i sum_j k(x^H_i, c^H_j) b^T_j v_j on the dense engine
+            hipLaunchKernelGGL(scale_kernel, grid_for(s.M), dim3(256), 0, s.ctx->stream, s.cbt.as<float>(), V + c, (int64_t)t,
+                               s.M, s.tmp_m.as<float>(), (int64_t)1);
+            int stat = do_knm_v(s.ctx, s.XH.as<float>(), s.n, s.Hn, s.Hn, s.CH.as<float>(), s.M, s.Hn, s.sigma,
+                                s.tmp_m.as<float>(), 1, s.dense_n.as<float>());
+            if (stat) return stat;
+        } else {
+            int stat = s.rank_one_sum(s.cb.as<float>(), V + c, t, s.M, &sum);
+            if (stat) return stat;
+        }
         SparseArgs a = s.args();
         a.vec = V + c;
         a.ldv = t;
@@ -622,10 +846,21 @@ int SparseProducts::t_w(const float *W, const float *wgt, int t, float *U)
             w = s.tmp.as<float>();
             ldw = 1;
         }
-        double sum = 0.0;
-        int stat = s.rank_one_sum(s.xa.as<float>(), w, ldw, s.n, &sum);
-        if (stat) return stat;
-        hipLaunchKernelGGL(rank_one_init_kernel, grid_for(s.M), dim3(256), 0, st, s.cb.as<float>(), s.M, sum, U + c, (int64_t)t);
+        if (s.Hn > 0) {
+            // all pairs: b^T_j sum_i k(x^H_i, c^H_j) a^T_i w_i on the dense engine
+            hipLaunchKernelGGL(scale_kernel, grid_for(s.n), dim3(256), 0, st, s.xat.as<float>(), w, ldw, s.n,
+                               s.tmp_n.as<float>(), (int64_t)1);
+            int stat = do_knm_t_w(s.ctx, s.XH.as<float>(), s.n, s.Hn, s.Hn, s.CH.as<float>(), s.M, s.Hn, s.sigma,
+                                  s.tmp_n.as<float>(), nullptr, 1, s.dense_m.as<float>());
+            if (stat) return stat;
+            hipLaunchKernelGGL(scale_kernel, grid_for(s.M), dim3(256), 0, st, s.cbt.as<float>(), s.dense_m.as<float>(),
+                               (int64_t)1, s.M, U + c, (int64_t)t);
+        } else {
+            double sum = 0.0;
+            int stat = s.rank_one_sum(s.xa.as<float>(), w, ldw, s.n, &sum);
+            if (stat) return stat;
+            hipLaunchKernelGGL(rank_one_init_kernel, grid_for(s.M), dim3(256), 0, st, s.cb.as<float>(), s.M, sum, U + c, (int64_t)t);
+        }
         SparseArgs a = s.args();
         a.vec = w;
         a.ldv = ldw;

@@ -37,15 +37,46 @@ def _case(n, M, d, nnz, seed):
 
 # sigma = 8: typical |x|^2 / 2 sigma^2 around 1 (the rank-one part matters); sigma = 1: a_i b_j underflows
 # and only the pairs that share features survive (a centre against its own row gives exactly 1)
+@pytest.fixture(params=[64, 0, 3])
+def head_limit(request, knm):
+    """Runs a test with the dense treatment of the most frequent features at its default, switched
+    off, and restricted to three features (so that frequent features remain in the sparse walk)."""
+    ctx = knm.default_context()
+    ctx.set_sparse_head_limit(request.param)
+    yield request.param
+    ctx.set_sparse_head_limit(64)
+
+
 @pytest.mark.parametrize("n,M,d,nnz,sigma", [(3000, 400, 5000, 30.0, 8.0), (1500, 300, 800, 12.0, 3.0),
                                              (2000, 256, 3000, 40.0, 1.0), (130, 7, 64, 5.0, 4.0)])
-def test_sparse_product_matches_dense_oracle(knm, n, M, d, nnz, sigma):
+def test_sparse_product_matches_dense_oracle(knm, head_limit, n, M, d, nnz, sigma):
     s, X, C, Xd, Cd = _case(n, M, d, nnz, seed=n + M)
     v = synth.probe_vector(M, 1, "normal", device="cuda")
     U, W = knm.knm_prod_csr(X, C, sigma, v, return_w=True)
     Uo, Wo = oracle.knm_prod(Xd, Cd, sigma, v.cpu().numpy(), return_w=True)
+    print(f"head limit {head_limit}: errors W {rel_l2(W.cpu().numpy(), Wo):.2e} U {rel_l2(U.cpu().numpy(), Uo):.2e}", flush=True)
     assert rel_l2(W.cpu().numpy(), Wo) < 1e-5
     assert rel_l2(U.cpu().numpy(), Uo) < 1e-5
+
+
+def test_frequent_features_are_found_and_change_nothing(knm):
+    """A problem in which a few features occur in most points (their centre lists pass the
+    threshold by a wide margin): with and without their dense treatment the product is the
+    oracle's, also with weights and several columns, and for rows made of frequent features only."""
+    n, M, d, sigma = 2500, 320, 600, 6.0
+    s, X, C, Xd, Cd = _case(n, M, d, 20.0, seed=77)
+    lens = np.bincount(s["c_indices"].numpy(), minlength=d)
+    assert np.sort(lens)[-3] >= 64  # at least three long lists: the head set is not empty
+    V = synth.probe_vector(M, 2, "normal", device="cuda")
+    Uo = oracle.knm_prod(Xd, Cd, sigma, V.cpu().numpy())
+    ctx = knm.default_context()
+    got = {}
+    for limit in (0, 64):
+        ctx.set_sparse_head_limit(limit)
+        got[limit] = knm.knm_prod_csr(X, C, sigma, V).cpu().numpy()
+        assert rel_l2(got[limit], Uo) < 1e-5, limit
+    ctx.set_sparse_head_limit(64)
+    assert rel_l2(got[64], got[0]) < 1e-5
 
 
 def test_sparse_product_several_columns_and_no_w(knm):
