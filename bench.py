@@ -141,6 +141,34 @@ def sparse_benchmark(args) -> int:
     s = synth.sparse_inputs(n, M, d, nnz_per_row=100.0, skew=args.sparse_skew, seed=6, device="cuda")
     X = torch.sparse_csr_tensor(s["x_indptr"], s["x_indices"], s["x_values"], size=(n, d), check_invariants=False)
     C = torch.sparse_csr_tensor(s["c_indptr"], s["c_indices"], s["c_values"], size=(M, d), check_invariants=False)
+    if args.fit:
+        # falkon_fit_csr end to end: labels from a sparse linear score, squashed
+        iters = args.iters or 10
+        g = torch.Generator(device="cuda").manual_seed(7)
+        wtrue = torch.randn(d, device="cuda", generator=g)
+        rows = torch.repeat_interleave(torch.arange(n, device="cuda"), torch.diff(s["x_indptr"]))
+        score = torch.zeros(n, device="cuda").index_add_(0, rows, s["x_values"] * wtrue[s["x_indices"]])
+        Y = torch.tanh(0.05 * score).reshape(n, 1).contiguous()
+        del wtrue, rows, score
+        ctx = knm.default_context()
+        lam = 1e-6
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        alpha, resid = knm.falkon_fit_csr(X, Y, C, sigma, lam, iters, args.jitter, return_resid=True, ctx=ctx)
+        torch.cuda.synchronize()
+        total = time.perf_counter() - t0
+        ft = ctx.get_fit_timing()
+        print(json.dumps({
+            "metric": "s per CG iteration (falkon_fit_csr)", "value": ft["iterations_s"] / iters, "unit": "s",
+            "higher_is_better": False, "n_gpus": 1,
+            "config": {"workload": "sparse-text-like", "n": n, "d": d, "M": M, "t": 1, "sigma": sigma, "lambda": lam,
+                       "iters": iters, "jitter": args.jitter, "feature_skew": args.sparse_skew,
+                       "nnz_x": int(s["x_indptr"][-1]), "nnz_c": int(s["c_indptr"][-1])},
+            "fit_total_s": total, "precond_s": ft["precond_s"], "rhs_s": ft["rhs_s"], "iterations_s": ft["iterations_s"],
+            "residual_first_last": [float(resid[0].max()), float(resid[-1].max())],
+            "alpha_finite": bool(torch.isfinite(alpha).all()),
+        }))
+        return 0
     v = synth.probe_vector(M, 1, "normal", device="cuda")
     # work of one sweep: for every stored entry of X, the centres that have its feature
     counts = torch.bincount(s["c_indices"])
