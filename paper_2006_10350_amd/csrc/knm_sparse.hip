@@ -23,7 +23,8 @@
 // fp32 atomic add (the accumulators and U live in ordinary device memory).
 //
 // What a row has to walk is prepared once per (X, C): a work list with the start and length of
-// the centre list of every entry whose feature occurs in a centre at all.  The few features that
+// the centre list of every entry whose feature occurs in a centre at all.  A row with few pair
+// updates accumulates in a small table in LDS instead of the accumulator in device memory.  The few features that
 // occur in a large share of the centres are not walked: their pairs are covered by one dense
 // product over those features (see "head features" below), which takes the place of the
 // rank-one term.
@@ -40,6 +41,9 @@ constexpr int kSpWaves = kSpThreads / 64;
 constexpr int kLongList = 32;     // centre lists at least this long are walked by the whole wavefront
 constexpr int kScanChunk = 4096;  // elements per workgroup of the prefix sum
 constexpr int64_t kFillGroup = 128; // rows of C per launch of the CSC fill
+constexpr int kHashBits = 9;        // slots (2^9) of a wavefront's accumulator table in LDS
+constexpr int kHashSlots = 1 << kHashBits;
+constexpr int kHashMaxPairs = 320; // a row with at most this many pair updates uses the table (load <= 5/8)
 constexpr int kMaxHead = 64;        // features treated densely, at most (one dense row of X^H and C^H each)
 
 // flag |= 1 if the CSR structure is not usable: indptr not starting at 0, decreasing, running
@@ -270,7 +274,8 @@ __global__ __launch_bounds__(kSpThreads) void build_work_kernel(const int64_t *_
                                                                const float *__restrict__ x_values, int64_t n,
                                                                const int *__restrict__ col_ptr,
                                                                const int *__restrict__ head_feat, int Hn, int head_min_len,
-                                                               int *__restrict__ work_count, int *__restrict__ head_count,
+                                                               int *__restrict__ work_count, int *__restrict__ work_pairs,
+                                                               int *__restrict__ head_count,
                                                                int *__restrict__ work_q0, int *__restrict__ work_len,
                                                                float *__restrict__ work_val, float *__restrict__ XH)
 {
@@ -279,7 +284,7 @@ __global__ __launch_bounds__(kSpThreads) void build_work_kernel(const int64_t *_
     const int64_t waves = (int64_t)gridDim.x * kSpWaves;
     for (int64_t row = wave; row < n; row += waves) {
         const int64_t p0 = x_indptr[row], p1 = x_indptr[row + 1];
-        int64_t kept = 0, heads = 0;
+        int64_t kept = 0, heads = 0, pairs = 0;
         for (int64_t p = p0; p < p1; p += 64) {
             int q0 = 0, len = 0, h = -1;
             float xv = 0.0f;
@@ -315,9 +320,12 @@ __global__ __launch_bounds__(kSpThreads) void build_work_kernel(const int64_t *_
             }
             kept += __popcll(keep);
             heads += __popcll(head);
+            pairs += (len > 0 && h < 0) ? len : 0;
         }
+        for (int w = 32; w > 0; w >>= 1) pairs += __shfl_xor(pairs, w);
         if (lane == 0) {
             work_count[row] = (int)kept;
+            work_pairs[row] = (int)(pairs < 0x7fffffffLL ? pairs : 0x7fffffffLL);
             head_count[row] = (int)heads;
         }
     }
@@ -330,6 +338,7 @@ struct SparseArgs {
     // feature's centre list and the entry's value
     const int *work_count, *work_q0, *work_len;
     const float *work_val;
+    const int *work_pairs; // per row: sum of the list lengths of its work list (saturating)
     // head features (Hn = 0: none): per row the last head_count[r] slots of its range hold (head
     // index, value); CH is the dense M x Hn image of the centres' head parts; tail_factor the
     // factor a^T of the rows (row sweep); dense the head-kernel product of the row sweep
@@ -359,6 +368,21 @@ __device__ __forceinline__ float pair_excess(float gt, float gh, float xn, float
     return expf(gt * inv_s2 - e0); // KH_ij has underflowed: the excess is K_ij itself
 }
 
+// Adds v to the entry of key j of a wavefront's table (open addressing, linear probing; the
+// table never holds more than kHashMaxPairs keys, so a free slot is always found)
+__device__ __forceinline__ void table_add(int *keys, float *vals, int j, float v)
+{
+    unsigned slot = ((unsigned)j * 2654435761u) >> (32 - kHashBits);
+    for (;;) {
+        const int prev = atomicCAS(&keys[slot], -1, j);
+        if (prev == -1 || prev == j) {
+            unsafeAtomicAdd(&vals[slot], v);
+            return;
+        }
+        slot = (slot + 1) & (kHashSlots - 1);
+    }
+}
+
 template <int COLUMN_SWEEP>
 __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
 {
@@ -371,10 +395,22 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
     __shared__ float head_val_all[kSpWaves][kMaxHead];
     int *const head_idx = head_idx_all[threadIdx.x >> 6];
     float *const head_val = head_val_all[threadIdx.x >> 6];
+    // Rows with few pair updates accumulate in a table in LDS instead of the dense accumulator in
+    // device memory: (centre, sum) pairs, all slots empty (key -1, sum 0) between rows.
+    __shared__ int keys_all[kSpWaves][kHashSlots];
+    __shared__ float vals_all[kSpWaves][kHashSlots];
+    int *const keys = keys_all[threadIdx.x >> 6];
+    float *const vals = vals_all[threadIdx.x >> 6];
+    for (int k = lane; k < kHashSlots; k += 64) {
+        keys[k] = -1;
+        vals[k] = 0.0f;
+    }
+    accumulator_fence();
     for (int64_t row = wave; row < a.n; row += waves) {
         const int64_t p0 = a.x_indptr[row], p1 = p0 + a.work_count[row];
         const float xn = a.xn[row];
         const float wrow = COLUMN_SWEEP ? a.vec[row * a.ldv] : 0.0f;
+        const bool in_lds = a.work_pairs[row] <= kHashMaxPairs; // same for the whole wavefront
         float sum = 0.0f;
         int hc = 0;
         if (a.Hn > 0) {
@@ -392,8 +428,22 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
             for (int k = 0; k < hc; ++k) gh = fmaf(head_val[k], a.CH[(int64_t)j * a.Hn + head_idx[k]], gh);
             return gh;
         };
-        // pass 0 adds x_if c_jf into the accumulator; pass 1 takes every touched entry out again
-        for (int pass = 0; pass < 2; ++pass) {
+        // one term x_if c_jf of g^T_ij
+        auto add = [&](int j, float v) {
+            if (in_lds) table_add(keys, vals, j, v);
+            else unsafeAtomicAdd(&acc[j], v);
+        };
+        // the finished g^T_ij of a pair that shares a tail feature
+        auto consume = [&](int j, float g) {
+            if (g == 0.0f) return; // nothing beyond KH_ij (or, in device memory, taken out before)
+            const float ex = pair_excess(g, head_dot(j), xn, a.cn[j], a.inv2s2, a.inv_s2);
+            if (COLUMN_SWEEP) unsafeAtomicAdd(&a.out[j * a.ldo], ex * wrow);
+            else sum += ex * a.vec[j * a.ldv];
+        };
+        // pass 0 adds x_if c_jf into the accumulator; pass 1 takes every touched entry out again:
+        // in device memory by walking the lists a second time (atomic exchange with zero, so a
+        // centre reached through several features is consumed once), in LDS by a sweep over the table
+        for (int pass = 0; pass < (in_lds ? 1 : 2); ++pass) {
             for (int64_t p = p0; p < p1; p += 64) {
                 const bool mine = p + lane < p1;
                 int q0 = 0, q1 = 0;
@@ -412,34 +462,30 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
                     const float bx = __shfl(xv, src);
                     for (int q = b0 + lane; q < b1; q += 64) {
                         const int j = a.csc_row[q];
-                        if (pass == 0) {
-                            unsafeAtomicAdd(&acc[j], bx * a.csc_val[q]);
-                        } else {
-                            const float g = atomicExch(&acc[j], 0.0f);
-                            if (g != 0.0f) {
-                                const float ex = pair_excess(g, head_dot(j), xn, a.cn[j], a.inv2s2, a.inv_s2);
-                                if (COLUMN_SWEEP) unsafeAtomicAdd(&a.out[j * a.ldo], ex * wrow);
-                                else sum += ex * a.vec[j * a.ldv];
-                            }
-                        }
+                        if (pass == 0) add(j, bx * a.csc_val[q]);
+                        else consume(j, atomicExch(&acc[j], 0.0f));
                     }
                 }
                 if (len < kLongList)
                     for (int q = q0; q < q1; ++q) {
                         const int j = a.csc_row[q];
-                        if (pass == 0) {
-                            unsafeAtomicAdd(&acc[j], xv * a.csc_val[q]);
-                        } else {
-                            const float g = atomicExch(&acc[j], 0.0f);
-                            if (g != 0.0f) {
-                                const float ex = pair_excess(g, head_dot(j), xn, a.cn[j], a.inv2s2, a.inv_s2);
-                                if (COLUMN_SWEEP) unsafeAtomicAdd(&a.out[j * a.ldo], ex * wrow);
-                                else sum += ex * a.vec[j * a.ldv];
-                            }
-                        }
+                        if (pass == 0) add(j, xv * a.csc_val[q]);
+                        else consume(j, atomicExch(&acc[j], 0.0f));
                     }
             }
             accumulator_fence(); // every lane's updates are done before the next pass or row
+        }
+        if (in_lds) {
+            for (int k = lane; k < kHashSlots; k += 64) {
+                const int j = keys[k];
+                if (j >= 0) {
+                    const float g = vals[k];
+                    keys[k] = -1;
+                    vals[k] = 0.0f;
+                    consume(j, g);
+                }
+            }
+            accumulator_fence();
         }
         if (!COLUMN_SWEEP) {
             sum += __shfl_xor(sum, 32);
@@ -618,7 +664,7 @@ struct SparseProducts::Impl {
     float inv2s2 = 0.0f, inv_s2 = 0.0f;
     int64_t wgs = 0;
     CentreLists lists;
-    DevMem xn, cn, xa, cb, acc, part, tmp, work_count, work_q0, work_len, work_val;
+    DevMem xn, cn, xa, cb, acc, part, tmp, work_count, work_pairs, work_q0, work_len, work_val;
     // head features: dense head parts XH (n x Hn), CH (M x Hn), factors of the tail norms, per-row
     // head counts, and the vectors of the dense product (tmp_m over the centres, dense_n / tmp_n over
     // the rows)
@@ -714,6 +760,7 @@ struct SparseProducts::Impl {
         a.work_q0 = work_q0.as<int>();
         a.work_len = work_len.as<int>();
         a.work_val = work_val.as<float>();
+        a.work_pairs = work_pairs.as<int>();
         a.Hn = Hn;
         a.head_count = head_count.as<int>();
         a.CH = CH.as<float>();
@@ -784,6 +831,7 @@ int SparseProducts::prepare(knm_ctx *ctx, const int64_t *x_indptr, const int64_t
     if (stat) return stat;
     const size_t work = (size_t)(nnz_x > 0 ? nnz_x : 1);
     if (s.work_count.alloc(sizeof(int) * n) != hipSuccess || s.head_count.alloc(sizeof(int) * n) != hipSuccess ||
+        s.work_pairs.alloc(sizeof(int) * n) != hipSuccess ||
         s.work_q0.alloc(sizeof(int) * work) != hipSuccess || s.work_len.alloc(sizeof(int) * work) != hipSuccess ||
         s.work_val.alloc(sizeof(float) * work) != hipSuccess) {
         (void)hipGetLastError();
@@ -791,7 +839,7 @@ int SparseProducts::prepare(knm_ctx *ctx, const int64_t *x_indptr, const int64_t
     }
     hipLaunchKernelGGL(build_work_kernel, dim3((unsigned)s.wgs), dim3(kSpThreads), 0, st, x_indptr, x_indices, x_values, n,
                        s.lists.col_ptr.as<int>(), s.head_feat.as<int>(), s.Hn, head_min_len, s.work_count.as<int>(),
-                       s.head_count.as<int>(), s.work_q0.as<int>(), s.work_len.as<int>(), s.work_val.as<float>(),
+                       s.work_pairs.as<int>(), s.head_count.as<int>(), s.work_q0.as<int>(), s.work_len.as<int>(), s.work_val.as<float>(),
                        s.XH.as<float>());
     if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "work list launch");
     if (s.Hn > 0) {
