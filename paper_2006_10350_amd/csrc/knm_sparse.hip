@@ -17,8 +17,8 @@
 // have it (C transposed to CSC once per call), adding x_if c_jf into the accumulator; a second
 // walk takes every touched entry out again (atomic exchange with zero, so a centre reached
 // through several features is consumed once), turns it into K_ij - a_i b_j and adds it to the
-// row's sum (row sweep) or scatters it into U (column sweep, float atomics: the summation
-// order, hence the last bits, vary from run to run).  Long centre lists are walked by the whole
+// row's sum (row sweep) or scatters it into a fp64 image of U (column sweep, fp64 atomics: the
+// summation order varies from run to run, which the rounding to fp32 at the end mostly hides).  Long centre lists are walked by the whole
 // wavefront, short ones by the lane that owns the feature.  The additions are the hardware's
 // fp32 atomic add (the accumulators and U live in ordinary device memory).
 //
@@ -187,12 +187,23 @@ __global__ __launch_bounds__(256) void weighted_sum_kernel(const float *__restri
     if (threadIdx.x == 0) part[blockIdx.x] = sh[0];
 }
 
-// out[j * ldo] = e[j] * s  (the rank-one part of the column sweep, which the scatter then adds to)
-__global__ void rank_one_init_kernel(const float *__restrict__ e, int64_t rows, double s, float *__restrict__ out,
-                                     int64_t ldo)
+// Column sweep: the all-pairs part of U in fp64, base[j] = e[j] * s (rank-one form, x null) or
+// e[j] * x[j] (dense head product).  The sparse walk scatters its terms into a separate fp64
+// buffer and the two are added at the end: float atomics onto the all-pairs part, which is
+// orders of magnitude larger than a single term, would lose the terms' low bits at every add.
+__global__ void column_base_kernel(const float *__restrict__ e, const float *__restrict__ x, double s, int64_t rows,
+                                   double *__restrict__ base)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r < rows) out[r * ldo] = (float)((double)e[r] * s);
+    if (r < rows) base[r] = (double)e[r] * (x ? (double)x[r] : s);
+}
+
+// out[j * ldo] = base[j] + scattered[j]
+__global__ void column_finish_kernel(const double *__restrict__ base, const double *__restrict__ scattered, int64_t rows,
+                                     float *__restrict__ out, int64_t ldo)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows) out[r * ldo] = (float)(base[r] + scattered[r]);
 }
 
 // Orders a wavefront's accesses to its private accumulator: everything it has issued (atomics
@@ -352,7 +363,8 @@ struct SparseArgs {
     const float *xa;      // a_i
     const float *vec;     // row sweep: v over the centres; column sweep: w over the rows
     int64_t ldv;
-    float *out;           // row sweep: W over the rows; column sweep: U over the centres (pre-set to the rank-one part)
+    float *out;           // row sweep: W over the rows
+    double *scattered;    // column sweep: the walk's terms of U over the centres (zero before)
     int64_t ldo;
     float *acc;           // one dense accumulator of M floats per wavefront of the grid, all zero
     float inv2s2, inv_s2;
@@ -437,7 +449,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
         auto consume = [&](int j, float g) {
             if (g == 0.0f) return; // nothing beyond KH_ij (or, in device memory, taken out before)
             const float ex = pair_excess(g, head_dot(j), xn, a.cn[j], a.inv2s2, a.inv_s2);
-            if (COLUMN_SWEEP) unsafeAtomicAdd(&a.out[j * a.ldo], ex * wrow);
+            if (COLUMN_SWEEP) unsafeAtomicAdd(&a.scattered[j], (double)ex * (double)wrow);
             else sum += ex * a.vec[j * a.ldv];
         };
         // pass 0 adds x_if c_jf into the accumulator; pass 1 takes every touched entry out again:
@@ -671,6 +683,7 @@ struct SparseProducts::Impl {
     int Hn = 0;
     float sigma = 0.0f;
     DevMem head_feat, head_count, XH, CH, xat, cbt, tmp_m, dense_n, dense_m, tmp_n;
+    DevMem col_base, col_scattered; // column sweep: all-pairs part and scattered terms, fp64 over the centres
 
     int rank_one_sum(const float *ev, const float *vec, int64_t ldv, int64_t rows, double *out)
     {
@@ -761,6 +774,7 @@ struct SparseProducts::Impl {
         a.work_len = work_len.as<int>();
         a.work_val = work_val.as<float>();
         a.work_pairs = work_pairs.as<int>();
+        a.scattered = nullptr;
         a.Hn = Hn;
         a.head_count = head_count.as<int>();
         a.CH = CH.as<float>();
@@ -815,7 +829,8 @@ int SparseProducts::prepare(knm_ctx *ctx, const int64_t *x_indptr, const int64_t
     if (s.xn.alloc(sizeof(float) * n) != hipSuccess || s.cn.alloc(sizeof(float) * M) != hipSuccess ||
         s.xa.alloc(sizeof(float) * n) != hipSuccess || s.cb.alloc(sizeof(float) * M) != hipSuccess ||
         s.acc.alloc(sizeof(float) * waves * M) != hipSuccess || s.part.alloc(sizeof(double) * 256) != hipSuccess ||
-        s.tmp.alloc(sizeof(float) * n) != hipSuccess) {
+        s.tmp.alloc(sizeof(float) * n) != hipSuccess || s.col_base.alloc(sizeof(double) * M) != hipSuccess ||
+        s.col_scattered.alloc(sizeof(double) * M) != hipSuccess) {
         (void)hipGetLastError();
         return fail(ctx, KNM_ALLOC, "hipMalloc(sparse workspace)");
     }
@@ -901,21 +916,27 @@ int SparseProducts::t_w(const float *W, const float *wgt, int t, float *U)
             int stat = do_knm_t_w(s.ctx, s.XH.as<float>(), s.n, s.Hn, s.Hn, s.CH.as<float>(), s.M, s.Hn, s.sigma,
                                   s.tmp_n.as<float>(), nullptr, 1, s.dense_m.as<float>());
             if (stat) return stat;
-            hipLaunchKernelGGL(scale_kernel, grid_for(s.M), dim3(256), 0, st, s.cbt.as<float>(), s.dense_m.as<float>(),
-                               (int64_t)1, s.M, U + c, (int64_t)t);
+            hipLaunchKernelGGL(column_base_kernel, grid_for(s.M), dim3(256), 0, st, s.cbt.as<float>(), s.dense_m.as<float>(), 0.0,
+                               s.M, s.col_base.as<double>());
         } else {
             double sum = 0.0;
             int stat = s.rank_one_sum(s.xa.as<float>(), w, ldw, s.n, &sum);
             if (stat) return stat;
-            hipLaunchKernelGGL(rank_one_init_kernel, grid_for(s.M), dim3(256), 0, st, s.cb.as<float>(), s.M, sum, U + c, (int64_t)t);
+            hipLaunchKernelGGL(column_base_kernel, grid_for(s.M), dim3(256), 0, st, s.cb.as<float>(), (const float *)nullptr, sum,
+                               s.M, s.col_base.as<double>());
         }
+        hipError_t e = hipMemsetAsync(s.col_scattered.p, 0, sizeof(double) * s.M, st);
+        if (e != hipSuccess) return fail(s.ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
         SparseArgs a = s.args();
         a.vec = w;
         a.ldv = ldw;
-        a.out = U + c;
-        a.ldo = t;
+        a.out = nullptr;
+        a.ldo = 0;
+        a.scattered = s.col_scattered.as<double>();
         a.s_rank_one = 0.0;
         hipLaunchKernelGGL(sparse_sweep_kernel<1>, dim3((unsigned)s.wgs), dim3(kSpThreads), 0, st, a);
+        hipLaunchKernelGGL(column_finish_kernel, grid_for(s.M), dim3(256), 0, st, s.col_base.as<double>(),
+                           s.col_scattered.as<double>(), s.M, U + c, (int64_t)t);
     }
     return hipGetLastError() == hipSuccess ? KNM_OK : fail(s.ctx, KNM_HIP_ERROR, "sparse column sweep launch");
 }

@@ -158,3 +158,78 @@ def test_full_size_preconditioner_sampled_entries(knm):
     print(f"adjoint identity: {lhs:.12e} vs {rhs:.12e}", flush=True)
     assert abs(lhs - rhs) <= 1e-8 * float(torch.linalg.norm(c) * torch.linalg.norm(x))
     pre.close()
+
+
+def test_full_size_sparse_sampled_outputs(knm):
+    """The sparse product at the benchmark's size (n = 1.5M rows, d = 6.5e7 features, M = 50k
+    centres), with and without the dense treatment of the most frequent features.  The dense
+    oracle cannot hold 6.5e7 columns, so a sampled output is checked on the features of the one
+    point it belongs to: with S the features of x_r, k(x_r, c_j) is the oracle's kernel of the
+    parts in S times exp(-(|c_j|^2 - |c_j restricted to S|^2) / 2 sigma^2), a factor computed here in
+    fp64 and folded into the vector; likewise for a column of U with S the features of c_j."""
+    n, M, d, sigma = 1_500_000, 50_000, 65_000_000, 20.0
+    s = synth.sparse_inputs(n, M, d, nnz_per_row=100.0, skew=2.5, seed=6, device="cuda")
+    X = torch.sparse_csr_tensor(s["x_indptr"], s["x_indices"], s["x_values"], size=(n, d), check_invariants=False)
+    C = torch.sparse_csr_tensor(s["c_indptr"], s["c_indices"], s["c_values"], size=(M, d), check_invariants=False)
+    v = synth.probe_vector(M, 1, "normal", device="cuda")
+    ctx = knm.default_context()
+
+    def parts(prefix, rows):
+        ip, ix, val = s[prefix + "_indptr"], s[prefix + "_indices"], s[prefix + "_values"]
+        owner = torch.repeat_interleave(torch.arange(rows, device="cuda"), torch.diff(ip))
+        norms = torch.zeros(rows, dtype=torch.float64, device="cuda").index_add_(0, owner, val.double() ** 2)
+        return ip, ix, val, owner, norms
+
+    def restricted(prefix, rows, S):
+        """Dense (rows x |S|) image of the matrix's entries in the sorted feature set S, and the
+        fp64 factor of every row's remaining squared norm."""
+        ip, ix, val, owner, norms = parts(prefix, rows)
+        keep = torch.isin(ix, S)
+        dense = torch.zeros(rows, max(int(S.numel()), 1), dtype=torch.float32, device="cuda")
+        dense[owner[keep], torch.searchsorted(S, ix[keep])] = val[keep]
+        rest = (norms - (dense.double() ** 2).sum(1)).clamp_min(0.0)
+        return dense.cpu().numpy(), torch.exp(-rest / (2.0 * sigma * sigma)).cpu().numpy()
+
+    def check(v, label):
+        results = {}
+        for limit in (64, 0):
+            ctx.set_sparse_head_limit(limit)
+            U, W = knm.knm_prod_csr(X, C, sigma, v, return_w=True)
+            torch.cuda.synchronize()
+            results[limit] = (U, W)
+            print(f"{label}, head limit {limit}: product done", flush=True)
+        ctx.set_sparse_head_limit(64)
+        vn = v.cpu().numpy().astype(np.float64).reshape(M)
+
+        centre_rows = s["centre_rows"].cpu().numpy()
+        sample_rows = [0, 1, 97, int(centre_rows[0]), int(centre_rows[-1]), n - 1, 123_457, 1_000_003]  # 0 and 97 are empty rows
+        for r in sample_rows:
+            p0, p1 = int(s["x_indptr"][r]), int(s["x_indptr"][r + 1])
+            S = s["x_indices"][p0:p1]
+            x_r = s["x_values"][p0:p1].reshape(1, -1).cpu().numpy() if p1 > p0 else np.zeros((1, 1), dtype=np.float32)
+            Cs, factor = restricted("c", M, S)
+            ref = float(oracle.knm_v(x_r, Cs, sigma, factor * vn).ravel()[0])
+            for limit, (U, W) in results.items():
+                got = float(W.reshape(n)[r])
+                assert abs(got - ref) <= 1e-4 * abs(ref) + 1e-6, (r, limit, got, ref)
+        print("row samples ok", flush=True)
+
+        for j in (0, 17, M - 1):
+            p0, p1 = int(s["c_indptr"][j]), int(s["c_indptr"][j + 1])
+            S = s["c_indices"][p0:p1]
+            c_j = s["c_values"][p0:p1].reshape(1, -1).cpu().numpy() if p1 > p0 else np.zeros((1, 1), dtype=np.float32)
+            Xs, factor = restricted("x", n, S)
+            for limit, (U, W) in results.items():
+                Wn = W.reshape(n).cpu().numpy().astype(np.float64)  # the GPU's own W as the oracle's input
+                ref = float(oracle.knm_t_y(Xs, c_j, sigma, factor * Wn).ravel()[0])
+                got = float(U.reshape(M)[j])
+                print(f"column {j}, head limit {limit}: relative error {abs(got - ref) / abs(ref):.2e}", flush=True)
+                assert abs(got - ref) <= 1e-4 * abs(ref), (j, limit, got, ref)
+        # the two formulations agree with each other over all outputs
+        assert rel_l2(results[64][0].cpu().numpy(), results[0][0].cpu().numpy()) < 2e-5
+        assert rel_l2(results[64][1].cpu().numpy(), results[0][1].cpu().numpy()) < 2e-5
+
+    check(v, "mixed signs")
+    # all terms of one sign: the all-pairs part of every output is orders of magnitude above a
+    # single term of the sparse walk, the case in which accumulating the two together loses bits
+    check(v.abs(), "positive vector")
