@@ -268,7 +268,7 @@ typedef enum { KNM_KERNEL_GAUSSIAN = 0, KNM_KERNEL_LAPLACIAN = 1 } knm_kernel_ki
 int knm_set_kernel(knm_ctx *ctx, int kind);
 
 /* Sparse (CSR) entry points: the features that occur in the largest share of the centres (at most
- * max_features of them, capped at 64; 0 switches this off; default 64) are taken out of the sparse
+ * max_features of them, capped at 128; 0 switches this off; default 128) are taken out of the sparse
  * walk and handled by one dense product over those features, when that is estimated to be cheaper.
  * The result is the same kernel product up to rounding. */
 int knm_set_sparse_head_limit(knm_ctx *ctx, int max_features);

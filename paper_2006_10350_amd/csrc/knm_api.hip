@@ -353,7 +353,7 @@ int knm_set_sparse_head_limit(knm_ctx *ctx, int max_features)
 {
     if (!ctx) return KNM_INVALID_ARG;
     if (max_features < 0) return fail(ctx, KNM_INVALID_ARG, "negative head limit");
-    ctx->sparse_head_max = max_features > 64 ? 64 : max_features;
+    ctx->sparse_head_max = max_features > 128 ? 128 : max_features;
     return KNM_OK;
 }
 

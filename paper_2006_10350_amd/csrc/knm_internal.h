@@ -141,7 +141,7 @@ struct knm_ctx {
     int cross_term = KNM_CROSS_F16X3;
     int kernel_kind = KNM_KERNEL_GAUSSIAN;
     // sparse inputs: most frequent features treated densely, at most (0: none)
-    int sparse_head_max = 64;
+    int sparse_head_max = 128;
     // timing
     bool timing = false;
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};

@@ -44,7 +44,7 @@ constexpr int64_t kFillGroup = 128; // rows of C per launch of the CSC fill
 constexpr int kHashBits = 9;        // slots (2^9) of a wavefront's accumulator table in LDS
 constexpr int kHashSlots = 1 << kHashBits;
 constexpr int kHashMaxPairs = 320; // a row with at most this many pair updates uses the table (load <= 5/8)
-constexpr int kMaxHead = 64;        // features treated densely, at most (one dense row of X^H and C^H each)
+constexpr int kMaxHead = 128;       // features treated densely, at most (one dense row of X^H and C^H each)
 
 // flag |= 1 if the CSR structure is not usable: indptr not starting at 0, decreasing, running
 // past nnz, or the column indices of a row not strictly increasing inside [0, d)

@@ -192,13 +192,13 @@ def test_full_size_sparse_sampled_outputs(knm):
 
     def check(v, label):
         results = {}
-        for limit in (64, 0):
+        for limit in (128, 0):
             ctx.set_sparse_head_limit(limit)
             U, W = knm.knm_prod_csr(X, C, sigma, v, return_w=True)
             torch.cuda.synchronize()
             results[limit] = (U, W)
             print(f"{label}, head limit {limit}: product done", flush=True)
-        ctx.set_sparse_head_limit(64)
+        ctx.set_sparse_head_limit(128)
         vn = v.cpu().numpy().astype(np.float64).reshape(M)
 
         centre_rows = s["centre_rows"].cpu().numpy()
@@ -226,8 +226,8 @@ def test_full_size_sparse_sampled_outputs(knm):
                 print(f"column {j}, head limit {limit}: relative error {abs(got - ref) / abs(ref):.2e}", flush=True)
                 assert abs(got - ref) <= 1e-4 * abs(ref), (j, limit, got, ref)
         # the two formulations agree with each other over all outputs
-        assert rel_l2(results[64][0].cpu().numpy(), results[0][0].cpu().numpy()) < 2e-5
-        assert rel_l2(results[64][1].cpu().numpy(), results[0][1].cpu().numpy()) < 2e-5
+        assert rel_l2(results[128][0].cpu().numpy(), results[0][0].cpu().numpy()) < 2e-5
+        assert rel_l2(results[128][1].cpu().numpy(), results[0][1].cpu().numpy()) < 2e-5
 
     check(v, "mixed signs")
     # all terms of one sign: the all-pairs part of every output is orders of magnitude above a

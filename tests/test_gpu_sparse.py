@@ -37,14 +37,14 @@ def _case(n, M, d, nnz, seed):
 
 # sigma = 8: typical |x|^2 / 2 sigma^2 around 1 (the rank-one part matters); sigma = 1: a_i b_j underflows
 # and only the pairs that share features survive (a centre against its own row gives exactly 1)
-@pytest.fixture(params=[64, 0, 3])
+@pytest.fixture(params=[128, 0, 3])
 def head_limit(request, knm):
     """Runs a test with the dense treatment of the most frequent features at its default, switched
     off, and restricted to three features (so that frequent features remain in the sparse walk)."""
     ctx = knm.default_context()
     ctx.set_sparse_head_limit(request.param)
     yield request.param
-    ctx.set_sparse_head_limit(64)
+    ctx.set_sparse_head_limit(128)
 
 
 @pytest.mark.parametrize("n,M,d,nnz,sigma", [(3000, 400, 5000, 30.0, 8.0), (1500, 300, 800, 12.0, 3.0),
@@ -71,12 +71,12 @@ def test_frequent_features_are_found_and_change_nothing(knm):
     Uo = oracle.knm_prod(Xd, Cd, sigma, V.cpu().numpy())
     ctx = knm.default_context()
     got = {}
-    for limit in (0, 64):
+    for limit in (0, 128):
         ctx.set_sparse_head_limit(limit)
         got[limit] = knm.knm_prod_csr(X, C, sigma, V).cpu().numpy()
         assert rel_l2(got[limit], Uo) < 1e-5, limit
-    ctx.set_sparse_head_limit(64)
-    assert rel_l2(got[64], got[0]) < 1e-5
+    ctx.set_sparse_head_limit(128)
+    assert rel_l2(got[128], got[0]) < 1e-5
 
 
 def test_sparse_product_several_columns_and_no_w(knm):
