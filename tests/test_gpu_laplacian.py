@@ -93,6 +93,26 @@ def test_laplacian_weighted_product(knm, lap):
     assert rel_l2(U, oracle.knm_prod_weighted(X.numpy(), C.numpy(), sigma, dw.numpy(), V.numpy())) < TOL
 
 
+def test_laplacian_large_norms_and_near_duplicates(knm, lap):
+    """Points far from the origin (the norm expansion cancels seven digits), centres that are data
+    rows, and centres that are data rows moved by 1e-3: the pairs below the refinement threshold
+    are taken from differences, the others keep the accuracy of the expansion (the bar of the
+    Gaussian kernel on the same data)."""
+    n, M, d, sigma = 2000, 256, 8, 1.0
+    X = 11.0 + 0.5 * _rand(n, d, 18)
+    C = _centres(X, M, 19)
+    C[::2] += 1e-3 * _rand(M // 2, d, 20)
+    V = torch.ones(M, 1)
+    W = knm.knm_v(X.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
+    Wo = oracle.knm_v(X.numpy(), C.numpy(), sigma, V.numpy())
+    err = rel_l2(W, Wo)
+    print(f"large norms: {err:.2e}", flush=True)
+    assert err < 1e-3
+    # the rows that are centres (or next to one) carry a kernel value near 1: each within 1e-3 of it
+    idx = torch.randperm(n, generator=torch.Generator().manual_seed(19))[:M].numpy()
+    assert np.abs(W.ravel()[idx] - np.asarray(Wo).ravel()[idx]).max() < 1e-3
+
+
 def test_laplacian_preconditioner_factors(knm, lap):
     M, d, sigma, lam, jitter = 700, 5, 1.5, 1e-4, 1e-9
     C = _rand(M, d, 31)
