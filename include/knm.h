@@ -260,10 +260,14 @@ int knm_set_cross_term(knm_ctx *ctx, int mode);
  *   KNM_KERNEL_LAPLACIAN           k(x, c) = exp(-|x - c| / sigma)
  * The Laplacian kernel runs on the K-loop engines for every shape: the matrix cores accumulate
  * -(log2(e) |x - c| / sigma)^2 from the norm expansion, then one square root and one exp2 per
- * entry.  The distance of (nearly) coincident points comes out of a cancellation, so such an
- * entry carries an absolute error of about 1e-3 (split-fp16) or 3e-4 (fp32) times |x| / sigma
- * instead of the usual 1e-6; the preconditioner's k(C, C) is formed from fp64 differences and
- * does not.  The sparse (CSR) entry points support the Gaussian kernel only. */
+ * entry.  The root magnifies the cancellation error of the expansion for close pairs (every
+ * Nystrom centre coincides with a data row), so pairs closer than a threshold derived from the
+ * points' norms are evaluated again from fp32 differences of the two rows: the result keeps
+ * the accuracy of the Gaussian kernel.  That second evaluation is rare for centred data; for data
+ * whose distance from the origin is many times sigma, most pairs take it and the sweep slows down
+ * accordingly (centre such data first: the kernel depends on differences only).  The
+ * preconditioner's k(C, C) is formed from fp64 differences.  The sparse (CSR) entry points support
+ * the Gaussian kernel only and return KNM_UNSUPPORTED otherwise. */
 typedef enum { KNM_KERNEL_GAUSSIAN = 0, KNM_KERNEL_LAPLACIAN = 1 } knm_kernel_kind;
 int knm_set_kernel(knm_ctx *ctx, int kind);
 
