@@ -56,8 +56,12 @@ const char *knm_last_error(const knm_ctx *ctx);
 /* Largest d and t the compiled kernels accept. */
 int knm_max_d(void);
 int knm_max_t(void);
-/* Device bytes of library-owned workspace knm_prod will hold for this shape. */
+/* Upper bound on the device bytes of library-owned workspace that the product entry points hold
+ * for this shape with the default settings (any arithmetic mode, either kernel function): W when the
+ * caller passes none, the partial results of the stream chunks, and the converted operands of the
+ * split-fp16 engines.  knm_workspace_held: what the context holds now. */
 size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t);
+size_t knm_workspace_held(const knm_ctx *ctx);
 
 /* W[n x t] = k(X, C) V  -- the kernel-matrix-vector product k(X1, X2) v of the
  * matrix-vector comparison in the appendix on performance, and the predictor

@@ -70,6 +70,7 @@ SIGNATURES = {
     "knm_set_cross_term": (_int, [_vp, _int]),
     "knm_set_kernel": (_int, [_vp, _int]),
     "knm_set_sparse_head_limit": (_int, [_vp, _int]),
+    "knm_workspace_held": (ctypes.c_size_t, [_vp]),
     "knm_set_pack_limit": (_int, [_vp, ctypes.c_size_t]),
     "knm_set_timing": (_int, [_vp, _int]),
     "knm_get_timing": (_int, [_vp, ctypes.POINTER(_f32)]),
@@ -163,6 +164,10 @@ class Context:
         """'gaussian' (default) or 'laplacian' (exp(-|x - c| / sigma); dense entry points only)."""
         code = {"gaussian": 0, "laplacian": 1}[kind] if isinstance(kind, str) else int(kind)
         self.check(load_library().knm_set_kernel(self._h, code))
+
+    def workspace_held(self) -> int:
+        """Device bytes of workspace this context holds now."""
+        return int(load_library().knm_workspace_held(self._h))
 
     def set_sparse_head_limit(self, max_features: int):
         """Sparse inputs: how many of the most frequent features may be handled densely (0: none)."""

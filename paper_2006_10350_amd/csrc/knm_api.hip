@@ -78,6 +78,31 @@ static bool bad_geom(const void *X, int64_t n, int d, int64_t ldx, const void *C
     return !X || !C || n <= 0 || M <= 0 || d <= 0 || t <= 0 || ldx < d || ldc < d || !(sigma > 0.0f);
 }
 
+// Bytes of the packed-operand workspace one sweep asks for in the split-fp16 modes (0 in the
+// fp32-MFMA mode): the same rule for the sweep itself and for knm_workspace_bytes.  `limit` = the
+// caller's cap, 0 for the defaults.
+static size_t pack_bytes_wanted(int64_t nF, int d, int t, int kind, size_t limit, int64_t chunks, int64_t chunk_len)
+{
+    if (use_gemm_engine(d, t, KNM_CROSS_F16X3, kind)) {
+        // packed images of both operands: whole if they fit 8 GiB, else the smaller one
+        // whole and the other in slabs
+        const size_t per_point = gemm_f16_pack_bytes_per_point(d);
+        const int64_t nFp = (nF + gemm_fixed_per_block() - 1) / gemm_fixed_per_block() * gemm_fixed_per_block();
+        size_t want = 256 + per_point * (size_t)(nFp + chunks * chunk_len); // head + both images
+        const size_t cap = limit ? limit : (size_t)8 << 30;
+        const size_t least = gemm_f16_min_pack_bytes(nF, chunks * chunk_len, chunk_len, d);
+        if (want > cap) want = cap;
+        if (want < least) want = least;
+        return want;
+    }
+    // packed image of the stream points: all of it, or slabs of at most 2 GiB
+    const size_t per_point = f16_pack_bytes_per_point(d);
+    size_t want = per_point * (size_t)(chunks * chunk_len);
+    const size_t cap = limit ? limit : (size_t)2 << 30;
+    if (want > cap) want = (cap / (per_point * chunk_len) + 1) * per_point * chunk_len;
+    return want;
+}
+
 // out[f, c] = sum_s k(F_f, S_s) vec[s, c] wgt[s]  for c < t (all arrays leading dimension t)
 static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const float *S, int64_t nS, int64_t lds,
                  int d, float sigma, const float *vec, const float *wgt, int t, float *out, hipEvent_t after_sweep)
@@ -114,26 +139,14 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         const bool f16 = !gemm && ctx->cross_term == KNM_CROSS_F16X3 && d <= f16_max_d();
         hipError_t e;
         if (gemm && ctx->cross_term == KNM_CROSS_F16X3) {
-            // packed images of both operands: whole if they fit 8 GiB, else the smaller one
-            // whole and the other in slabs
-            const size_t per_point = gemm_f16_pack_bytes_per_point(d);
-            const int64_t nFp = (nF + gemm_fixed_per_block() - 1) / gemm_fixed_per_block() * gemm_fixed_per_block();
-            size_t want = 256 + per_point * (size_t)(nFp + chunks * chunk_len); // head + both images
-            const size_t cap = ctx->pack_limit ? ctx->pack_limit : (size_t)8 << 30;
-            const size_t least = gemm_f16_min_pack_bytes(nF, chunks * chunk_len, chunk_len, d);
-            if (want > cap) want = cap;
-            if (want < least) want = least;
+            const size_t want = pack_bytes_wanted(nF, d, t, ctx->kernel_kind, ctx->pack_limit, chunks, chunk_len);
             int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
             if (st) return st;
             e = launch_sweep_gemm_f16(a, ctx->pack_buf, want, ctx->stream);
         } else if (gemm) {
             e = launch_sweep_gemm(a, ctx->stream);
         } else if (f16) {
-            // packed image of the stream points: all of it, or slabs of at most 2 GiB
-            const size_t per_point = f16_pack_bytes_per_point(d);
-            size_t want = per_point * (size_t)(chunks * chunk_len);
-            const size_t cap = ctx->pack_limit ? ctx->pack_limit : (size_t)2 << 30;
-            if (want > cap) want = (cap / (per_point * chunk_len) + 1) * per_point * chunk_len;
+            const size_t want = pack_bytes_wanted(nF, d, t, ctx->kernel_kind, ctx->pack_limit, chunks, chunk_len);
             int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
             if (st) return st;
             e = launch_sweep_f16(a, ctx->pack_buf, want, ctx->stream);
@@ -245,18 +258,34 @@ size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
 {
     if (n <= 0 || M <= 0 || d <= 0 || t <= 0) return 0;
     int64_t len = 0;
-    size_t bytes = sizeof(float) * (size_t)n * t; // W
-    // the larger of the two arithmetic modes' needs (they may cut the stream differently)
-    size_t part = 0;
-    for (int mode = 0; mode < 4; ++mode) { // both cross-term modes of both kernel families
-        const int64_t c1 = choose_chunks(n, M, d, t, mode & 1, mode >> 1, &len);
-        const int64_t c2 = choose_chunks(M, n, d, t, mode & 1, mode >> 1, &len);
+    const size_t bytes = sizeof(float) * (size_t)n * t; // W
+    // the largest needs over the arithmetic modes and kernel functions (they may cut the stream
+    // differently): chunk partials, and the packed operands of the split-fp16 modes
+    size_t part = 0, pack = 0;
+    for (int mode = 0; mode < 4; ++mode) {
+        const int cross = mode & 1, kind = mode >> 1;
+        const int64_t c1 = choose_chunks(n, M, d, t, cross, kind, &len);
+        const int64_t l1 = len;
+        const int64_t c2 = choose_chunks(M, n, d, t, cross, kind, &len);
+        const int64_t l2 = len;
         const size_t p1 = c1 > 1 ? sizeof(float) * (size_t)c1 * n * t : 0;
         const size_t p2 = c2 > 1 ? sizeof(float) * (size_t)c2 * M * t : 0;
         if (p1 > part) part = p1;
         if (p2 > part) part = p2;
+        if (cross == KNM_CROSS_F16X3) {
+            const bool packs = use_gemm_engine(d, t, cross, kind) || d <= f16_max_d();
+            const size_t k1 = packs ? pack_bytes_wanted(n, d, t, kind, 0, c1, l1) : 0;
+            const size_t k2 = packs ? pack_bytes_wanted(M, d, t, kind, 0, c2, l2) : 0;
+            if (k1 > pack) pack = k1;
+            if (k2 > pack) pack = k2;
+        }
     }
-    return bytes + part;
+    return bytes + part + pack;
+}
+
+size_t knm_workspace_held(const knm_ctx *ctx)
+{
+    return ctx ? ctx->w_bytes + ctx->part_bytes + ctx->pack_bytes : 0;
 }
 
 static int check_common(knm_ctx *ctx, const void *X, int64_t n, int d, int64_t ldx, const void *C, int64_t M,

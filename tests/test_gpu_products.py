@@ -310,3 +310,23 @@ def test_product_replays_in_a_graph(knm, n, M, d, t, sigma):
         assert rel_l2(got.cpu().numpy(), oracle.knm_prod(X.cpu().numpy(), C.cpu().numpy(), sigma, V.cpu().numpy())) < TIGHT
     del graph
     ctx.close()
+
+
+@pytest.mark.parametrize("n,M,d,t", [(30000, 2000, 8, 1), (9000, 1500, 100, 3), (5000, 700, 28, 12)])
+def test_workspace_held_stays_within_the_announced_bound(knm, n, M, d, t):
+    """knm_workspace_bytes is an upper bound on what a context holds after the products of that
+    shape, in every arithmetic mode and for both kernel functions."""
+    X, C, V, Y = _rand(n, d, 60).cuda(), _rand(M, d, 61).cuda(), _rand(M, t, 62).cuda(), _rand(n, t, 63).cuda()
+    bound = int(knm.load_library().knm_workspace_bytes(n, M, d, t))
+    for mode in ("f16x3", "f32"):
+        for kind in ("gaussian", "laplacian"):
+            ctx = knm.Context()
+            ctx.set_cross_term(mode)
+            ctx.set_kernel(kind)
+            assert ctx.workspace_held() == 0
+            knm.knm_prod(X, C, 3.0, V, ctx=ctx)
+            knm.knm_t_y(X, C, 3.0, Y, ctx=ctx)
+            held = ctx.workspace_held()
+            print(f"{mode} {kind}: held {held} of {bound}", flush=True)
+            assert 0 < held <= bound
+            ctx.close()
