@@ -147,6 +147,28 @@ def test_laplacian_fit_and_predict(knm, lap):
     assert np.mean((pred[:, 0] - clean) ** 2) < 0.5 * np.var(clean)
 
 
+def test_laplacian_logistic_fit(knm, lap):
+    """The Newton iteration for the logistic loss (Alg. 2) is kernel-agnostic: losses after every step
+    and predictions against the oracle's iteration with the same kernel."""
+    n, M, d, sigma, jitter = 5000, 250, 6, 3.0, 1e-7
+    g = torch.Generator().manual_seed(9)
+    X = torch.randn(n, d, generator=g)
+    y = torch.sign(X @ torch.randn(d, generator=g) + 0.4 * torch.randn(n, generator=g))
+    y[y == 0] = 1.0
+    idx = torch.randperm(n, generator=g)[:M]
+    C, yC = X[idx].contiguous(), y[idx].contiguous()
+    lambdas, iters = [1e-2, 1e-3, 1e-4], [4, 4, 6]
+    alpha, loss = knm.logfalkon_fit(X.cuda(), y.cuda(), C.cuda(), yC.cuda(), sigma, lambdas, iters, jitter,
+                                    return_loss=True)
+    ao, lo = oracle.logfalkon_fit(X.numpy(), y.numpy(), C.numpy(), yC.numpy(), sigma, lambdas, iters, jitter,
+                                  return_loss=True)
+    assert np.allclose(loss, lo, rtol=1e-4, atol=1e-6)
+    assert np.all(np.diff(loss) < 0)
+    Xt = _rand(1000, d, 10)
+    pred = knm.falkon_predict(Xt.cuda(), C.cuda(), sigma, alpha).cpu().numpy()
+    assert rel_l2(pred, oracle.falkon_predict(Xt.numpy(), C.numpy(), sigma, ao)) < 1e-3
+
+
 def test_kernel_setting_is_per_context_and_validated(knm):
     n, M, d, sigma = 600, 200, 7, 2.0
     X = _rand(n, d, 50)
