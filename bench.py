@@ -222,7 +222,7 @@ def main() -> int:
     ap.add_argument("--cross", default="f16x3", choices=["f32", "f16x3"],
                     help="arithmetic of the cross term (d <= 44, t = 1): three split-fp16 MFMA products (library "
                          "default) or fp32 MFMA")
-    ap.add_argument("--kernel", default="gaussian", choices=["gaussian", "laplacian"],
+    ap.add_argument("--kernel", default="gaussian", choices=["gaussian", "laplacian", "matern32", "matern52"],
                     help="kernel function of the product (the headline metric is quoted on the Gaussian one)")
     ap.add_argument("--fit", action="store_true",
                     help="instead of the product benchmark, run falkon_fit end to end on the workload and "
@@ -304,8 +304,8 @@ def main() -> int:
     # per launch) or d beyond the register-resident engine's limit (44 features with the split-fp16
     # cross term, the default; 64 with fp32 MFMA); otherwise the register-resident engine.  Two sweeps
     # per step.
-    # The Laplacian kernel always runs on the K-loop engine.
-    k_loop = args.kernel == "laplacian" or w.t > 1 or w.d > (44 if args.cross == "f16x3" else 64)
+    # The kernels of the distance (Laplacian, Matern) always run on the K-loop engine.
+    k_loop = args.kernel != "gaussian" or w.t > 1 or w.d > (44 if args.cross == "f16x3" else 64)
     f16 = (not k_loop) and args.cross == "f16x3" and w.d <= 44
     k_loop_f16 = k_loop and args.cross == "f16x3"
     kernel_name = (("gauss_gemm_f16_kernel" if k_loop_f16 else "gauss_gemm_kernel") if k_loop

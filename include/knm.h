@@ -258,21 +258,29 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
 typedef enum { KNM_CROSS_F32 = 0, KNM_CROSS_F16X3 = 1 } knm_cross_term;
 int knm_set_cross_term(knm_ctx *ctx, int mode);
 
-/* Kernel function of the dense entry points (a second kernel family on the same engines; the
- * paper's experiments use the Gaussian kernel throughout):
- *   KNM_KERNEL_GAUSSIAN (default)  k(x, c) = exp(-|x - c|^2 / (2 sigma^2))
- *   KNM_KERNEL_LAPLACIAN           k(x, c) = exp(-|x - c| / sigma)
- * The Laplacian kernel runs on the K-loop engines for every shape: the matrix cores accumulate
- * -(log2(e) |x - c| / sigma)^2 from the norm expansion, then one square root and one exp2 per
- * entry.  The root magnifies the cancellation error of the expansion for close pairs (every
- * Nystrom centre coincides with a data row), so pairs closer than a threshold derived from the
- * points' norms are evaluated again from fp32 differences of the two rows: the result keeps
- * the accuracy of the Gaussian kernel.  That second evaluation is rare for centred data; for data
- * whose distance from the origin is many times sigma, most pairs take it and the sweep slows down
- * accordingly (centre such data first: the kernel depends on differences only).  The
- * preconditioner's k(C, C) is formed from fp64 differences.  The sparse (CSR) entry points support
- * the Gaussian kernel only and return KNM_UNSUPPORTED otherwise. */
-typedef enum { KNM_KERNEL_GAUSSIAN = 0, KNM_KERNEL_LAPLACIAN = 1 } knm_kernel_kind;
+/* Kernel function of the dense entry points (further kernel families on the same engines; the
+ * paper's experiments use the Gaussian kernel throughout), with r = |x - c|:
+ *   KNM_KERNEL_GAUSSIAN (default)  k = exp(-r^2 / (2 sigma^2))
+ *   KNM_KERNEL_LAPLACIAN           k = exp(-r / sigma)
+ *   KNM_KERNEL_MATERN32            k = (1 + u) exp(-u),            u = sqrt(3) r / sigma
+ *   KNM_KERNEL_MATERN52            k = (1 + u + u^2 / 3) exp(-u),  u = sqrt(5) r / sigma
+ * The kernels of r (all but the Gaussian) run on the K-loop engines for every shape: the matrix
+ * cores accumulate -(log2(e) u)^2 from the norm expansion (u = r / sigma for the Laplacian kernel),
+ * then one square root, one exp2 and the polynomial per entry.  The root magnifies the
+ * cancellation error of the expansion for close pairs (every Nystrom centre coincides with a data
+ * row), so pairs closer than a threshold derived from the points' norms are evaluated again from
+ * fp32 differences of the two rows: the result keeps the accuracy of the Gaussian kernel.  That
+ * second evaluation is rare for centred data; for data whose distance from the origin is many
+ * times sigma, most pairs take it and the sweep slows down accordingly (centre such data first:
+ * the kernel depends on differences only).  The preconditioner's k(C, C) is formed from fp64
+ * differences.  The sparse (CSR) entry points support the Gaussian kernel only and return
+ * KNM_UNSUPPORTED otherwise. */
+typedef enum {
+    KNM_KERNEL_GAUSSIAN = 0,
+    KNM_KERNEL_LAPLACIAN = 1,
+    KNM_KERNEL_MATERN32 = 2,
+    KNM_KERNEL_MATERN52 = 3
+} knm_kernel_kind;
 int knm_set_kernel(knm_ctx *ctx, int kind);
 
 /* Sparse (CSR) entry points: the features that occur in the largest share of the centres (at most

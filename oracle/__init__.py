@@ -100,14 +100,16 @@ def num_threads() -> int:
     return int(_load().orc_num_threads())
 
 
-KERNELS = {"gaussian": 0, "laplacian": 1}
+KERNELS = {"gaussian": 0, "laplacian": 1, "matern32": 2, "matern52": 3}
 
 
 @contextlib.contextmanager
 def kernel(name: str):
     """Evaluate everything inside the block with the named kernel: "gaussian" (the paper's,
-    Section 2: exp(-|x - c|^2 / (2 sigma^2))) or "laplacian" (exp(-|x - c| / sigma), textbook form;
-    the paper's method takes any positive-definite kernel but writes out only the Gaussian one)."""
+    Section 2: exp(-|x - c|^2 / (2 sigma^2))), or one of the kernels of r = |x - c| in textbook form
+    (the paper's method takes any positive-definite kernel but writes out only the Gaussian one):
+    "laplacian" exp(-r / sigma); "matern32" (1 + u) exp(-u), u = sqrt(3) r / sigma; "matern52"
+    (1 + u + u^2 / 3) exp(-u), u = sqrt(5) r / sigma."""
     lib = _load()
     before = lib.orc_get_kernel()
     if lib.orc_set_kernel(KERNELS[name]) != 0:

@@ -43,15 +43,17 @@ int orc_num_threads(void)
 /* Kernel function.  The paper works with the Gaussian kernel of a single length-scale throughout
  * (Section 2 for the estimator, Section 5 for the experiments):
  *     k(x, c) = exp(-||x - c||^2 / (2 sigma^2)).
- * Its method holds for any positive-definite kernel; as a second one this oracle has the Laplacian
- * (exponential) kernel in its textbook form, which the paper does not spell out:
- *     k(x, c) = exp(-||x - c|| / sigma).
+ * Its method holds for any positive-definite kernel; beyond it this oracle has three kernels of the
+ * distance r = ||x - c|| in their textbook forms, which the paper does not spell out:
+ *     Laplacian     k = exp(-r / sigma)
+ *     Matern 3/2    k = (1 + u) exp(-u),            u = sqrt(3) r / sigma
+ *     Matern 5/2    k = (1 + u + u^2 / 3) exp(-u),  u = sqrt(5) r / sigma
  * The choice is a process-wide setting (test infrastructure: one thread of control). */
-static int g_kind = 0; /* 0 Gaussian, 1 Laplacian */
+static int g_kind = 0; /* 0 Gaussian, 1 Laplacian, 2 Matern 3/2, 3 Matern 5/2 */
 
 int orc_set_kernel(int kind)
 {
-    if (kind != 0 && kind != 1) return -1;
+    if (kind < 0 || kind > 3) return -1;
     g_kind = kind;
     return 0;
 }
@@ -66,6 +68,14 @@ static double gauss(const float *x, const float *c, int d, double sigma)
         s += diff * diff;
     }
     if (g_kind == 1) return exp(-sqrt(s) / sigma);
+    if (g_kind == 2) {
+        double u = sqrt(3.0) * sqrt(s) / sigma;
+        return (1.0 + u) * exp(-u);
+    }
+    if (g_kind == 3) {
+        double u = sqrt(5.0) * sqrt(s) / sigma;
+        return (1.0 + u + u * u / 3.0) * exp(-u);
+    }
     return exp(-s / (2.0 * sigma * sigma));
 }
 

@@ -161,8 +161,8 @@ class Context:
         self.check(load_library().knm_set_cross_term(self._h, code))
 
     def set_kernel(self, kind):
-        """'gaussian' (default) or 'laplacian' (exp(-|x - c| / sigma); dense entry points only)."""
-        code = {"gaussian": 0, "laplacian": 1}[kind] if isinstance(kind, str) else int(kind)
+        """'gaussian' (default), 'laplacian', 'matern32' or 'matern52' (dense entry points only)."""
+        code = {"gaussian": 0, "laplacian": 1, "matern32": 2, "matern52": 3}[kind] if isinstance(kind, str) else int(kind)
         self.check(load_library().knm_set_kernel(self._h, code))
 
     def workspace_held(self) -> int:

@@ -132,10 +132,13 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.chunk_stride = nF * t;
         a.chunk_len = chunk_len;
         a.n_chunks = chunks;
-        // Laplacian: with sigma / sqrt(2 log2 e) in place of sigma the engines' accumulators hold
-        // -(log2(e) |x - c| / sigma)^2, whose root the kernel takes before the exp2
+        // Kernels of r = |x - c|: with sigma / (c sqrt(2 log2 e)) in place of sigma the engines'
+        // accumulators hold -(log2(e) c r / sigma)^2, whose root the kernel takes before the exp2
+        // (c = 1 Laplacian, sqrt(3) and sqrt(5) for the two Matern kernels)
         a.kind = ctx->kernel_kind;
-        a.sigma = (a.kind == KNM_KERNEL_LAPLACIAN) ? sigma / sqrtf(2.0f * 1.4426950408889634f) : sigma;
+        const float c_kind = a.kind == KNM_KERNEL_MATERN32 ? 1.7320508075688772f
+                             : a.kind == KNM_KERNEL_MATERN52 ? 2.23606797749979f : 1.0f;
+        a.sigma = (a.kind == KNM_KERNEL_GAUSSIAN) ? sigma : sigma / (c_kind * sqrtf(2.0f * 1.4426950408889634f));
         const bool f16 = !gemm && ctx->cross_term == KNM_CROSS_F16X3 && d <= f16_max_d();
         hipError_t e;
         if (gemm && ctx->cross_term == KNM_CROSS_F16X3) {
@@ -373,7 +376,7 @@ int knm_set_cross_term(knm_ctx *ctx, int mode)
 int knm_set_kernel(knm_ctx *ctx, int kind)
 {
     if (!ctx) return KNM_INVALID_ARG;
-    if (kind != KNM_KERNEL_GAUSSIAN && kind != KNM_KERNEL_LAPLACIAN) return fail(ctx, KNM_INVALID_ARG, "unknown kernel");
+    if (kind < KNM_KERNEL_GAUSSIAN || kind > KNM_KERNEL_MATERN52) return fail(ctx, KNM_INVALID_ARG, "unknown kernel");
     ctx->kernel_kind = kind;
     return KNM_OK;
 }

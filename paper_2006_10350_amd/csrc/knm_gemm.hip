@@ -20,6 +20,8 @@
 // with the vector rows read from LDS as broadcasts.  The two half-waves hold different
 // stream rows of the same fixed point and are added once, when the workgroup finishes.
 
+#include <type_traits>
+
 #include "knm_internal.h"
 
 namespace knm {
@@ -255,7 +257,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
         const float *frow[2] = {nullptr, nullptr};
         float near[2] = {0.0f, 0.0f};
         bool any_near = false;
-        if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+        if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
 #pragma unroll
             for (int fb = 0; fb < 2; ++fb) {
                 const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
@@ -265,11 +267,11 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
             }
         }
         auto kernel_value = [&](int fb, int sb, int r) -> float {
-            if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+            if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
                 const float x = acc_read(acc[fb][sb][r]);
                 const bool nr = x > -near[fb];
                 any_near |= nr;
-                return nr ? 0.0f : laplacian_from_exponent(x);
+                return nr ? 0.0f : radial_from_exponent<KIND>(x);
             } else {
                 // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
                 return exp2_clamped(acc[fb][sb][r]);
@@ -293,7 +295,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
                     for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[c], sum[fb][c]);
                 }
             }
-        if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+        if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
             if (__builtin_amdgcn_ballot_w64(any_near) != 0) {
 #pragma unroll
                 for (int fb = 0; fb < 2; ++fb) {
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
                             const int jl = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
                             const int64_t j = stream0 + jl;
                             if (j < chunk_end) { // a padding row has zero vectors
-                                const float p = laplacian_from_exponent(exact_exponent(frow[fb], a.S + j * a.lds, d, s2));
+                                const float p = radial_from_exponent<KIND>(exact_exponent(frow[fb], a.S + j * a.lds, d, s2));
 #pragma unroll
                                 for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vimg[jl * TP + c], sum[fb][c]);
                             }
@@ -347,15 +349,17 @@ hipError_t launch_tp(const SweepArgs &a, hipStream_t stream)
     dim3 grid((unsigned)blocks, (unsigned)a.n_chunks);
     const bool a16 = (a.d % 4 == 0) && (a.lds % 4 == 0) && (a.ldf % 4 == 0) &&
                      ((reinterpret_cast<uintptr_t>(a.S) & 15) == 0) && ((reinterpret_cast<uintptr_t>(a.F) & 15) == 0);
-    const bool lap = a.kind == KNM_KERNEL_LAPLACIAN;
-    if (a16 && !lap)
-        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 4, KNM_KERNEL_GAUSSIAN>), grid, dim3(kThreads), 0, stream, a);
-    else if (!lap)
-        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 1, KNM_KERNEL_GAUSSIAN>), grid, dim3(kThreads), 0, stream, a);
-    else if (a16)
-        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 4, KNM_KERNEL_LAPLACIAN>), grid, dim3(kThreads), 0, stream, a);
-    else
-        hipLaunchKernelGGL((gauss_gemm_kernel<TP, 1, KNM_KERNEL_LAPLACIAN>), grid, dim3(kThreads), 0, stream, a);
+    auto launch = [&](auto kind) {
+        constexpr int K = decltype(kind)::value;
+        if (a16) hipLaunchKernelGGL((gauss_gemm_kernel<TP, 4, K>), grid, dim3(kThreads), 0, stream, a);
+        else hipLaunchKernelGGL((gauss_gemm_kernel<TP, 1, K>), grid, dim3(kThreads), 0, stream, a);
+    };
+    switch (a.kind) {
+    case KNM_KERNEL_LAPLACIAN: launch(std::integral_constant<int, KNM_KERNEL_LAPLACIAN>{}); break;
+    case KNM_KERNEL_MATERN32: launch(std::integral_constant<int, KNM_KERNEL_MATERN32>{}); break;
+    case KNM_KERNEL_MATERN52: launch(std::integral_constant<int, KNM_KERNEL_MATERN52>{}); break;
+    default: launch(std::integral_constant<int, KNM_KERNEL_GAUSSIAN>{}); break;
+    }
     return hipGetLastError();
 }
 
@@ -368,7 +372,7 @@ int64_t gemm_fixed_per_block() { return kFixed; }
 hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream)
 {
     if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > gemm_max_t()) return hipErrorInvalidValue;
-    if (a.kind != KNM_KERNEL_GAUSSIAN && a.kind != KNM_KERNEL_LAPLACIAN) return hipErrorInvalidValue;
+    if (a.kind < KNM_KERNEL_GAUSSIAN || a.kind > KNM_KERNEL_MATERN52) return hipErrorInvalidValue;
     if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
     if (a.t <= 4) return launch_tp<4>(a, stream);

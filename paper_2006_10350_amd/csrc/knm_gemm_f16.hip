@@ -434,7 +434,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         const float *frow[2] = {nullptr, nullptr};
         float near[2] = {0.0f, 0.0f};
         bool any_near = false;
-        if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+        if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
             const f16x8 *ib = img[(stage - 1) & 1];
 #pragma unroll
             for (int fb = 0; fb < 2; ++fb) {
@@ -447,11 +447,11 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
             }
         }
         auto kernel_value = [&](int fb, int sb, int r) -> float {
-            if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+            if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
                 const float x = acc_read(acc[fb][sb][r]);
                 const bool nr = x > -near[fb];
                 any_near |= nr;
-                return nr ? 0.0f : laplacian_from_exponent(x);
+                return nr ? 0.0f : radial_from_exponent<KIND>(x);
             } else {
                 // exponent <= 0 up to rounding; the clamp modifier keeps the kernel value in [0, 1]
                 return exp2_clamped(acc[fb][sb][r]);
@@ -476,7 +476,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
             jl = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
             const int64_t j = stream0 + jl;
             if (j >= chunk_end) return 0.0f;
-            return laplacian_from_exponent(exact_exponent(frow[fb], a.S + j * a.lds, a.d, s2));
+            return radial_from_exponent<KIND>(exact_exponent(frow[fb], a.S + j * a.lds, a.d, s2));
         };
         if constexpr (MV) {
 #pragma unroll
@@ -505,7 +505,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                         mfma_accv(dacc[fb], vl, bh);
                     }
                 }
-            if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+            if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
                 if (__builtin_amdgcn_ballot_w64(any_near) != 0) {
                     // The 32 columns of a fixed point are spread over its two lanes (one per
                     // half-wave), so the two exchange their pairs and each adds both to its own
@@ -560,7 +560,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                     for (int c = 0; c < TP; ++c) sum[fb][c] = fmaf(p, vr[cur][c], sum[fb][c]);
                 }
             }
-            if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+            if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
                 if (__builtin_amdgcn_ballot_w64(any_near) != 0) {
 #pragma unroll
                     for (int fb = 0; fb < 2; ++fb) {
@@ -655,12 +655,16 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
     const int64_t n_patch_c = (chunks + pm.pc - 1) / pm.pc;
     const int64_t patches = (pm.n_patch_f * n_patch_c + 7) / 8 * 8;
     const dim3 grid((unsigned)(patches * kPatch));
-    if (a.kind == KNM_KERNEL_LAPLACIAN)
-        hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP, MV, KNM_KERNEL_LAPLACIAN>), grid, dim3(kThreads), 0, stream, a,
-                           Fimg, Simg, fixed_row0, chunk0, n_kc, pm, colmax);
-    else
-        hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP, MV, KNM_KERNEL_GAUSSIAN>), grid, dim3(kThreads), 0, stream, a,
-                           Fimg, Simg, fixed_row0, chunk0, n_kc, pm, colmax);
+    auto launch = [&](auto kind) {
+        hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP, MV, decltype(kind)::value>), grid, dim3(kThreads), 0, stream, a, Fimg,
+                           Simg, fixed_row0, chunk0, n_kc, pm, colmax);
+    };
+    switch (a.kind) {
+    case KNM_KERNEL_LAPLACIAN: launch(std::integral_constant<int, KNM_KERNEL_LAPLACIAN>{}); break;
+    case KNM_KERNEL_MATERN32: launch(std::integral_constant<int, KNM_KERNEL_MATERN32>{}); break;
+    case KNM_KERNEL_MATERN52: launch(std::integral_constant<int, KNM_KERNEL_MATERN52>{}); break;
+    default: launch(std::integral_constant<int, KNM_KERNEL_GAUSSIAN>{}); break;
+    }
 }
 
 } // namespace
@@ -681,7 +685,7 @@ int gemm_f16_max_t() { return 32; }
 hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
     if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > gemm_f16_max_t()) return hipErrorInvalidValue;
-    if (a.kind != KNM_KERNEL_GAUSSIAN && a.kind != KNM_KERNEL_LAPLACIAN) return hipErrorInvalidValue;
+    if (a.kind < KNM_KERNEL_GAUSSIAN || a.kind > KNM_KERNEL_MATERN52) return hipErrorInvalidValue;
     if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
     const int n_kc = (a.d + kChunk - 1) / kChunk;

@@ -34,10 +34,10 @@ struct SweepArgs {
     int64_t chunk_len; // stream points per chunk (multiple of the stage size)
     int64_t n_chunks;
     float sigma;      // length scale the engines work with (for the Laplacian kernel the caller's, rescaled)
-    int kind;         // KNM_KERNEL_GAUSSIAN or KNM_KERNEL_LAPLACIAN (K-loop engines only)
+    int kind;         // knm_kernel_kind (the kernels of r = |x - c|: K-loop engines only)
 };
 
-// ---- Laplacian kernel on the K-loop engines ------------------------------------------
+// ---- kernels of r = |x - c| (Laplacian, Matern) on the K-loop engines ---------------------
 //
 // The engines' accumulators hold x = -s2 |f - s|^2 (s2 = log2(e) / (2 sigma^2) of the rescaled
 // sigma), formed as norms minus cross term; the kernel value is 2^-sqrt(|x|).  The cancellation
@@ -62,9 +62,16 @@ __device__ __forceinline__ float exact_exponent(const float *__restrict__ f, con
     }
     return -s2 * q;
 }
-__device__ __forceinline__ float laplacian_from_exponent(float x)
+// kernel value from the exponent x = -(log2(e) u)^2 held by the accumulators
+template <int KIND>
+__device__ __forceinline__ float radial_from_exponent(float x)
 {
-    return __builtin_amdgcn_exp2f(-__builtin_amdgcn_sqrtf(fabsf(x)));
+    const float y = __builtin_amdgcn_sqrtf(fabsf(x)); // log2(e) u
+    const float e = __builtin_amdgcn_exp2f(-y);
+    if constexpr (KIND == KNM_KERNEL_LAPLACIAN) return e;
+    const float u = y * 0.6931471805599453f;
+    if constexpr (KIND == KNM_KERNEL_MATERN32) return fmaf(u, e, e);
+    return e * fmaf(u, fmaf(u, 1.0f / 3.0f, 1.0f), 1.0f); // KNM_KERNEL_MATERN52
 }
 
 // register-resident engine (knm_tile.hip): d <= small_max_d(), one column per launch

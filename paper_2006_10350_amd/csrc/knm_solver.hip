@@ -34,8 +34,9 @@ namespace {
 using namespace knm;
 
 // Upper triangle (column-major, r <= c) of K[r, c] = k(c_r, c_c) + jitter [r == c], fp64, direct
-// differences: k = exp(-|c_r - c_c|^2 scale) with scale = 1 / (2 sigma^2) for the Gaussian kernel,
-// exp(-|c_r - c_c| scale) with scale = 1 / sigma for the Laplacian one.  The factorisation reads nothing below the diagonal, which is
+// differences: k = exp(-|c_r - c_c|^2 scale) with scale = 1 / (2 sigma^2) for the Gaussian kernel; for the
+// kernels of r = |c_r - c_c|, with u = r scale: exp(-u), scale = 1 / sigma (Laplacian);
+// (1 + u) exp(-u), scale = sqrt(3) / sigma; (1 + u + u^2 / 3) exp(-u), scale = sqrt(5) / sigma (Matern).  The factorisation reads nothing below the diagonal, which is
 // zeroed once the factor is there.
 __global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_t ldc, int kind, double scale,
                            double jitter, double *__restrict__ K)
@@ -51,7 +52,14 @@ __global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_
         double diff = (double)cr[k] - (double)cc[k];
         s += diff * diff;
     }
-    double v = exp(-(kind == KNM_KERNEL_LAPLACIAN ? sqrt(s) : s) * scale);
+    double v;
+    if (kind == KNM_KERNEL_GAUSSIAN) {
+        v = exp(-s * scale);
+    } else {
+        const double u = sqrt(s) * scale;
+        const double poly = kind == KNM_KERNEL_MATERN32 ? 1.0 + u : kind == KNM_KERNEL_MATERN52 ? 1.0 + u + u * u / 3.0 : 1.0;
+        v = poly * exp(-u);
+    }
     if (r == c) v += jitter;
     K[r + c * M] = v;
 }
@@ -1008,8 +1016,10 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
         const dim3 tb(32, 8);
         const dim3 tg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
         const int kind = ctx->kernel_kind;
-        const double scale =
-            kind == KNM_KERNEL_LAPLACIAN ? 1.0 / (double)sigma : 1.0 / (2.0 * (double)sigma * (double)sigma);
+        const double scale = kind == KNM_KERNEL_GAUSSIAN   ? 1.0 / (2.0 * (double)sigma * (double)sigma)
+                             : kind == KNM_KERNEL_MATERN32 ? sqrt(3.0) / (double)sigma
+                             : kind == KNM_KERNEL_MATERN52 ? sqrt(5.0) / (double)sigma
+                                                           : 1.0 / (double)sigma;
         hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, kind, scale, jitter, K);
         return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "kmm_kernel launch");
     };

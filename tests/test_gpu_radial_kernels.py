@@ -1,6 +1,6 @@
-"""GPU parity for the second kernel family, the Laplacian kernel k(x, c) = exp(-|x - c| / sigma):
-products, preconditioner and a small fit against the fp64 CPU oracle run with the same kernel,
-through the C ABI.
+"""GPU parity for the kernels of the distance r = |x - c| -- Laplacian exp(-r / sigma) and the
+Matern kernels with nu = 3/2 and 5/2: products, preconditioner and small fits against the fp64 CPU
+oracle run with the same kernel, through the C ABI.
 
 Bar: relative L2 error <= 1e-4 per product, <= 1e-3 for end-to-end predictions.  The centres are
 rows of the data (Nystrom centres, Section 2), so every case holds exactly coincident pairs, whose
@@ -34,14 +34,17 @@ def _centres(X, M, seed):
     return X[idx].clone()
 
 
-@pytest.fixture(params=["f32", "f16x3"])
+@pytest.fixture(params=[("laplacian", "f32"), ("laplacian", "f16x3"), ("matern32", "f16x3"), ("matern52", "f32"),
+                        ("matern52", "f16x3")], ids=lambda p: f"{p[0]}-{p[1]}")
 def lap(request, knm):
-    """Laplacian kernel on the default context and in the oracle, once per cross-term arithmetic."""
+    """One of the kernels of r on the default context and in the oracle, with one of the two
+    cross-term arithmetics."""
+    kind, cross = request.param
     ctx = knm.default_context()
-    ctx.set_cross_term(request.param)
-    ctx.set_kernel("laplacian")
-    with oracle.kernel("laplacian"):
-        yield request.param
+    ctx.set_cross_term(cross)
+    ctx.set_kernel(kind)
+    with oracle.kernel(kind):
+        yield f"{kind}/{cross}"
     ctx.set_kernel("gaussian")
     ctx.set_cross_term("f16x3")
 
@@ -63,7 +66,7 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("n,M,d,t,sigma", SHAPES)
-def test_laplacian_products_match_oracle(knm, lap, n, M, d, t, sigma):
+def test_radial_products_match_oracle(knm, lap, n, M, d, t, sigma):
     print(f"case n={n} M={M} d={d} t={t} cross={lap}", flush=True)
     X = _rand(n, d, 1)
     C = _centres(X, M, 2)
@@ -84,7 +87,7 @@ def test_laplacian_products_match_oracle(knm, lap, n, M, d, t, sigma):
         assert rel_l2(U.reshape(M, t)[:, c], np.asarray(Uo).reshape(M, t)[:, c]) < TOL
 
 
-def test_laplacian_weighted_product(knm, lap):
+def test_radial_weighted_product(knm, lap):
     n, M, d, t, sigma = 2500, 300, 9, 2, 3.0
     X = _rand(n, d, 7)
     C, V = _centres(X, M, 8), _rand(M, t, 9)
@@ -93,7 +96,7 @@ def test_laplacian_weighted_product(knm, lap):
     assert rel_l2(U, oracle.knm_prod_weighted(X.numpy(), C.numpy(), sigma, dw.numpy(), V.numpy())) < TOL
 
 
-def test_laplacian_large_norms_and_near_duplicates(knm, lap):
+def test_radial_large_norms_and_near_duplicates(knm, lap):
     """Points far from the origin (the norm expansion cancels seven digits), centres that are data
     rows, and centres that are data rows moved by 1e-3: the pairs below the refinement threshold
     are taken from differences, the others keep the accuracy of the expansion (the bar of the
@@ -113,7 +116,7 @@ def test_laplacian_large_norms_and_near_duplicates(knm, lap):
     assert np.abs(W.ravel()[idx] - np.asarray(Wo).ravel()[idx]).max() < 1e-3
 
 
-def test_laplacian_preconditioner_factors(knm, lap):
+def test_radial_preconditioner_factors(knm, lap):
     M, d, sigma, lam, jitter = 700, 5, 1.5, 1e-4, 1e-9
     C = _rand(M, d, 31)
     pre = knm.precond_build(C.cuda(), sigma, lam, jitter)
@@ -126,7 +129,7 @@ def test_laplacian_preconditioner_factors(knm, lap):
     pre.close()
 
 
-def test_laplacian_fit_and_predict(knm, lap):
+def test_radial_fit_and_predict(knm, lap):
     n, M, d, t, sigma, lam, iters, jitter = 6000, 400, 6, 2, 3.0, 1e-5, 10, 1e-9
     X = _rand(n, d, 37)
     C = _centres(X, M, 38)
@@ -147,7 +150,7 @@ def test_laplacian_fit_and_predict(knm, lap):
     assert np.mean((pred[:, 0] - clean) ** 2) < 0.5 * np.var(clean)
 
 
-def test_laplacian_logistic_fit(knm, lap):
+def test_radial_logistic_fit(knm, lap):
     """The Newton iteration for the logistic loss (Alg. 2) is kernel-agnostic: losses after every step
     and predictions against the oracle's iteration with the same kernel."""
     n, M, d, sigma, jitter = 5000, 250, 6, 3.0, 1e-7

@@ -353,3 +353,22 @@ def test_laplacian_setting_reaches_every_product_and_the_fit():
         H = K.T @ K + lam * n * Kmm
         ref = sla.solve(H, K.T @ Y, assume_a="sym")
         assert np.linalg.norm(K @ alpha - K @ ref) <= 1e-6 * np.linalg.norm(K @ ref)
+
+
+@pytest.mark.parametrize("name,nu", [("matern32", 1.5), ("matern52", 2.5)])
+def test_matern_hand_values_and_library(name, nu):
+    from sklearn.gaussian_process.kernels import Matern
+
+    with oracle.kernel(name):
+        assert oracle.gauss([0.0], [0.0], 1.0) == 1.0
+        # r = sigma: u = sqrt(2 nu)
+        u = math.sqrt(2.0 * nu)
+        want = (1.0 + u) * math.exp(-u) if nu == 1.5 else (1.0 + u + u * u / 3.0) * math.exp(-u)
+        assert oracle.gauss([1.0, -2.0], [4.0, 2.0], 5.0) == pytest.approx(want, rel=1e-15)
+        X, C = _pts(41, 6), _pts(17, 6)
+        lib = Matern(length_scale=1.3, nu=nu)(X.astype(np.float64), C.astype(np.float64))
+        assert np.allclose(oracle.kernel_matrix(X, C, 1.3), lib, rtol=1e-12, atol=0)
+        # the setting reaches the products
+        V = RNG.standard_normal((17, 2))
+        assert np.allclose(oracle.knm_prod(X, C, 1.3, V), lib.T @ (lib @ V), rtol=1e-12, atol=1e-12)
+    assert oracle.gauss([0.0], [3.0], 2.0) == pytest.approx(math.exp(-9.0 / 8.0), rel=1e-15)
