@@ -428,7 +428,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         mfma_results_ready();
         // Laplacian: per fixed point of this lane, the row and the |exponent| below which a pair is
         // taken again from differences (never for a padding row).  The norm term is read back from
-        // the two leading digits of the fixed point's norm slot (lanes 0..31 hold them).  The unrolled
+        // the digits of the fixed point's norm slot (lanes 0..31 hold them).  The unrolled
         // pass leaves such pairs out (kernel value 0) and only notes that there are some; the rare
         // second pass finds them again and adds their terms.
         const float *frow[2] = {nullptr, nullptr};
@@ -439,7 +439,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
 #pragma unroll
             for (int fb = 0; fb < 2; ++fb) {
                 const f16x8 fx = ib[(wave * 2 + fb) * kUnits + (lane & 31)];
-                const float nf = kC1 * (float)fx[0] + kC2 * (float)fx[1];
+                const float nf = kC1 * (float)fx[0] + kC2 * (float)fx[1] + kC3 * (float)fx[2] + kC4 * (float)fx[3];
                 const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
                 const bool in = idx < a.nF;
                 frow[fb] = a.F + (in ? idx : 0) * a.ldf;

@@ -44,13 +44,16 @@ struct SweepArgs {
 // leaves an absolute error of about 1e-7 sqrt(d) N in x (N = s2 |f|^2, the norm in the same units),
 // which the square root turns into error / (2 sqrt(|x|)): harmless for ordinary pairs, but 1e-4 to
 // 1e-3 for coincident or nearly coincident ones, and every Nystrom centre coincides with a data
-// row.  Pairs whose |x| lies below the threshold at which that error reaches 1e-5 get their
+// row.  Pairs whose |x| lies below the threshold at which that error reaches about 1e-5 get their
 // exponent again from fp32 differences of the two rows (exact for coincident rows, relative
 // rounding error otherwise).  Such pairs are rare, so the branch is almost never taken.
 __device__ __forceinline__ float near_pair_threshold(float norm_term, int d)
 {
+    // relative part: 1e-7 sqrt(d) N of rounding in the fp32 accumulation, at least the 2.4e-7 N that
+    // the split-fp16 product leaves out; absolute part: the 2^-24 to which that engine's norm slots
+    // are rounded
     const float N = fabsf(norm_term);
-    return fmaxf(2.5e-5f * (float)d * N * N, 1.0e-12f);
+    return fmaxf(fmaxf(2.5e-5f * (float)d, 2.5e-4f) * N * N, 1.0e-5f);
 }
 __device__ __forceinline__ float exact_exponent(const float *__restrict__ f, const float *__restrict__ s, int d,
                                                 float s2)
