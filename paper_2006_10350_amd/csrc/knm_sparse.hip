@@ -29,6 +29,7 @@
 // product over those features (see "head features" below), which takes the place of the
 // rank-one term.
 #include <algorithm>
+#include <cstring>
 #include <vector>
 
 #include "knm_internal.h"
@@ -256,15 +257,17 @@ __global__ void head_centres_kernel(HeadLists hl, int Hn, const int *__restrict_
     if (k < hl.len[h]) CH[(int64_t)csc_row[hl.q0[h] + k] * Hn + h] = csc_val[hl.q0[h] + k];
 }
 
-// e[r] = exp(-(norm[r] - |row r of PH|^2) / 2 sigma^2): the factor of the tail part's norm
+// e[r] = exp(-(norm[r] - |row r of PH|^2) / 2 sigma^2): the factor of the tail part's norm; *worst =
+// bits of the largest |row of PH|^2 / 2 sigma^2 (non-negative floats order like their bit patterns)
 __global__ void tail_factor_kernel(const float *__restrict__ norms, const float *__restrict__ PH, int Hn, int64_t rows,
-                                   float inv2s2, float *__restrict__ e)
+                                   float inv2s2, float *__restrict__ e, unsigned *__restrict__ worst)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= rows) return;
     float hn = 0.0f;
     for (int h = 0; h < Hn; ++h) hn = fmaf(PH[r * Hn + h], PH[r * Hn + h], hn);
     e[r] = expf(-fmaxf(norms[r] - hn, 0.0f) * inv2s2);
+    atomicMax(worst, __float_as_uint(hn * inv2s2));
 }
 
 // out[r * ldo] = e[r] * x[r * ldx]
@@ -372,12 +375,15 @@ struct SparseArgs {
 };
 
 // K_ij - KH_ij from the tail part gt and the head part gh of the dot product and the squared norms
-// (no head features: gh = 0 and KH_ij = a_i b_j)
+// (no head features: gh = 0 and KH_ij = a_i b_j).  With e0 = -log KH_ij >= 0 and a = gt / sigma^2 the
+// excess is exp(a - e0) - exp(-e0), where a - e0 = log K_ij <= 0: neither term can overflow.  For
+// small a the difference is taken as exp(-e0) expm1(a), which keeps its leading digits.
 __device__ __forceinline__ float pair_excess(float gt, float gh, float xn, float cn, float inv2s2, float inv_s2)
 {
     const float e0 = (xn + cn) * inv2s2 - gh * inv_s2;
-    if (e0 < 80.0f) return expf(-e0) * expm1f(gt * inv_s2);
-    return expf(gt * inv_s2 - e0); // KH_ij has underflowed: the excess is K_ij itself
+    const float a = gt * inv_s2;
+    if (a < 1.0f) return expf(-e0) * expm1f(a);
+    return expf(a - e0) - expf(-e0);
 }
 
 // Adds v to the entry of key j of a wavefront's table (open addressing, linear probing; the
@@ -428,9 +434,9 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
         if (a.Hn > 0) {
             hc = a.head_count[row];
             const int64_t back = a.x_indptr[row + 1] - hc;
-            if (lane < hc) {
-                head_idx[lane] = a.work_q0[back + lane];
-                head_val[lane] = a.work_val[back + lane];
+            for (int k = lane; k < hc; k += 64) { // hc <= Hn <= kMaxHead, which may exceed the 64 lanes
+                head_idx[k] = a.work_q0[back + k];
+                head_val[k] = a.work_val[back + k];
             }
             accumulator_fence(); // the wavefront's own LDS writes, before any lane reads them
         }
@@ -852,16 +858,36 @@ int SparseProducts::prepare(knm_ctx *ctx, const int64_t *x_indptr, const int64_t
         (void)hipGetLastError();
         return fail(ctx, KNM_ALLOC, "hipMalloc(sparse work list)");
     }
-    hipLaunchKernelGGL(build_work_kernel, dim3((unsigned)s.wgs), dim3(kSpThreads), 0, st, x_indptr, x_indices, x_values, n,
-                       s.lists.col_ptr.as<int>(), s.head_feat.as<int>(), s.Hn, head_min_len, s.work_count.as<int>(),
-                       s.work_pairs.as<int>(), s.head_count.as<int>(), s.work_q0.as<int>(), s.work_len.as<int>(), s.work_val.as<float>(),
-                       s.XH.as<float>());
-    if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "work list launch");
+    auto build_work = [&]() {
+        hipLaunchKernelGGL(build_work_kernel, dim3((unsigned)s.wgs), dim3(kSpThreads), 0, st, x_indptr, x_indices, x_values, n,
+                           s.lists.col_ptr.as<int>(), s.head_feat.as<int>(), s.Hn, head_min_len, s.work_count.as<int>(),
+                           s.work_pairs.as<int>(), s.head_count.as<int>(), s.work_q0.as<int>(), s.work_len.as<int>(),
+                           s.work_val.as<float>(), s.XH.as<float>());
+        return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "work list launch");
+    };
+    stat = build_work();
+    if (stat) return stat;
     if (s.Hn > 0) {
+        // The dense product forms its exponent from the norm expansion, whose rounding error grows
+        // with the head parts' norm terms |x^H|^2 / 2 sigma^2 (about 1e-7 of them): beyond 50 the
+        // head features go back into the sparse walk, which has no such cancellation.
+        unsigned worst_bits = 0;
+        hipError_t e = hipMemsetAsync(s.part.p, 0, sizeof(unsigned), st);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
         hipLaunchKernelGGL(tail_factor_kernel, grid_for(n), dim3(256), 0, st, s.xn.as<float>(), s.XH.as<float>(), s.Hn, n,
-                           s.inv2s2, s.xat.as<float>());
+                           s.inv2s2, s.xat.as<float>(), s.part.as<unsigned>());
         hipLaunchKernelGGL(tail_factor_kernel, grid_for(M), dim3(256), 0, st, s.cn.as<float>(), s.CH.as<float>(), s.Hn, M,
-                           s.inv2s2, s.cbt.as<float>());
+                           s.inv2s2, s.cbt.as<float>(), s.part.as<unsigned>());
+        e = hipMemcpyAsync(&worst_bits, s.part.p, sizeof(unsigned), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "head norm terms", e);
+        float worst = 0.0f;
+        memcpy(&worst, &worst_bits, sizeof(float));
+        if (!(worst <= 50.0f)) {
+            s.Hn = 0;
+            stat = build_work();
+            if (stat) return stat;
+        }
     }
     hipError_t e = hipMemsetAsync(s.acc.p, 0, sizeof(float) * waves * M, st);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);

@@ -208,3 +208,58 @@ def test_sparse_preconditioner_factors_match_oracle(knm):
     To, Ao = oracle.precond(Cd, sigma, lam, jitter)
     assert np.abs(T - To).max() < 1e-9 * max(1.0, np.abs(To).max())
     assert np.abs(A - Ao).max() < 1e-9 * max(1.0, np.abs(Ao).max())
+
+
+def _check_product(knm, n, M, d, nnz, skew, sigma, t, seed, tol=1e-5):
+    s = synth.sparse_inputs(n, M, d, nnz_per_row=nnz, skew=skew, seed=seed)
+    Xd = _dense(s["x_indptr"].numpy(), s["x_indices"].numpy(), s["x_values"].numpy(), n, d)
+    Cd = _dense(s["c_indptr"].numpy(), s["c_indices"].numpy(), s["c_values"].numpy(), M, d)
+    X = _csr(s["x_indptr"], s["x_indices"], s["x_values"], n, d)
+    C = _csr(s["c_indptr"], s["c_indices"], s["c_values"], M, d)
+    V = torch.randn(M, t, generator=torch.Generator().manual_seed(seed))
+    if seed % 3 == 0:
+        V = V.abs()
+    U, W = knm.knm_prod_csr(X, C, sigma, V.cuda(), return_w=True)
+    Uo, Wo = oracle.knm_prod(Xd, Cd, sigma, V.numpy(), return_w=True)
+    errs = (rel_l2(U.cpu().numpy(), Uo), rel_l2(W.cpu().numpy(), Wo))
+    assert max(errs) < tol, (n, M, d, nnz, skew, sigma, t, seed, errs)
+
+
+def test_rows_with_more_frequent_features_than_lanes(knm):
+    """Dense-ish rows over few features: nearly every feature is frequent, the head set is full
+    (128 features) and single rows hold more than 64 of them."""
+    n = M = 100
+    s = synth.sparse_inputs(n, M, 300, nnz_per_row=80.0, skew=1.0, seed=150)
+    lens = np.bincount(s["c_indices"].numpy(), minlength=300)
+    assert (lens >= 16).sum() >= 128
+    _check_product(knm, n, M, 300, 80.0, 1.0, 20.0, 1, seed=150)
+
+
+def test_small_length_scale_sends_the_frequent_features_back_to_the_sparse_walk(knm):
+    """sigma far below the norms of the frequent features' parts: a dense product over them would
+    form its exponent from a cancellation of terms in the thousands; the library must notice and
+    keep the exact sparse walk (also: no overflow where the shared part of two rows is large)."""
+    _check_product(knm, 1500, 64, 1000, 80.0, 8.0, 0.7, 2, seed=141)
+    _check_product(knm, 64, 64, 1000, 10.0, 5.0, 0.7, 1, seed=139)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_sparse_draws_match_dense_oracle(knm, block):
+    ctx = knm.default_context()
+    try:
+        for case in range(10):
+            seed = 700 + 10 * block + case
+            rng = np.random.default_rng(seed)
+            M = int(rng.choice([1, 3, 17, 64, 100, 257, 400, 900]))
+            n = int(max(M, rng.choice([1, 5, 63, 130, 500, 1500, 4000])))
+            d = int(rng.choice([8, 64, 300, 1000, 5000]))
+            nnz = min(float(rng.choice([1.0, 3.0, 10.0, 30.0, 80.0])), d / 2)
+            skew = float(rng.choice([1.0, 2.5, 5.0, 8.0]))
+            sigma = float(rng.choice([0.7, 2.0, 6.0, 20.0]))
+            t = int(rng.choice([1, 1, 2, 3]))
+            limit = int(rng.choice([128, 128, 0, 2, 7]))
+            print(f"seed {seed}: n={n} M={M} d={d} nnz={nnz} skew={skew} sigma={sigma} t={t} head limit {limit}", flush=True)
+            ctx.set_sparse_head_limit(limit)
+            _check_product(knm, n, M, d, nnz, skew, sigma, t, seed)
+    finally:
+        ctx.set_sparse_head_limit(128)
