@@ -226,3 +226,28 @@ def test_fit_rejects_bad_arguments(knm):
     with pytest.raises(knm.KnmError) as e:
         knm.falkon_fit(X, Y, C, 1.0, 1e-3, 0)
     assert e.value.status == -1
+
+
+@pytest.mark.parametrize("M", [1, 2, 17, 127, 128, 129, 255, 257, 513, 640, 2049])
+def test_preconditioner_at_block_boundaries(knm, M):
+    """Sizes around the leaf (128), sub-panel (512) and solve-block (256, 2048) widths: the defining
+    identities of both factors and the two solves against a library's triangular solves."""
+    import scipy.linalg as sla
+
+    d, sigma, lam, jitter, t = 3, 0.75, 1e-4, 1e-7, 2
+    g = torch.Generator().manual_seed(1000 + M)
+    C = torch.randn(M, d, generator=g)
+    pre = knm.precond_build(C.cuda(), sigma, lam, jitter)
+    T, A = pre.factors()
+    K = oracle.kernel_matrix(C.numpy(), C.numpy(), sigma) + jitter * np.eye(M)
+    assert np.array_equal(np.tril(T, -1), np.zeros_like(T)) and np.array_equal(np.tril(A, -1), np.zeros_like(A))
+    assert np.abs(T.T @ T - K).max() < 1e-12
+    assert np.abs(A.T @ A - (T @ T.T / M + lam * np.eye(M))).max() < 1e-12
+    B = torch.randn(M, t, generator=g, dtype=torch.float64)
+    got = pre.solve(B.cuda()).cpu().numpy()
+    ref = sla.solve_triangular(T, sla.solve_triangular(A, B.numpy(), lower=False), lower=False)
+    assert rel_l2(got, ref) < 1e-9
+    got = pre.solve(B.cuda(), transpose=True).cpu().numpy()
+    ref = sla.solve_triangular(A, sla.solve_triangular(T, B.numpy(), lower=False, trans="T"), lower=False, trans="T")
+    assert rel_l2(got, ref) < 1e-9
+    pre.close()
