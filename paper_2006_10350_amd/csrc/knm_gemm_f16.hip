@@ -62,6 +62,7 @@ constexpr int kChunk = 16;                     // features per K-chunk = one MFM
 constexpr int kUnits = 128;                    // 16-byte units per block and chunk (2 planes x 64 lanes)
 constexpr int kLoads = kBlocks * kUnits / kThreads; // units copied per thread and stage (6)
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kPScale = 16384.0f; // matrix-core reduction: kernel values are split into fp16 halves after this scale
 constexpr float kC1 = 1024.0f, kC2 = 0.5f, kC3 = 0.000244140625f, kC4 = 1.1920928955078125e-07f; // 2^10 2^-1 2^-12 2^-23
 
 static_assert(kLoads * kThreads == kBlocks * kUnits, "staging must divide evenly");
@@ -492,8 +493,10 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                         u32x4 ph, pl;
 #pragma unroll
                         for (int e = 0; e < 8; e += 2) {
-                            const float p0 = kernel_value(fb, sb, 8 * q + e);
-                            const float p1 = kernel_value(fb, sb, 8 * q + e + 1);
+                            // kernel values in [0, 1] times 2^14: the halves then resolve values
+                            // down to 4e-9 (instead of fp16's 6e-5) relative to themselves
+                            const float p0 = kPScale * kernel_value(fb, sb, 8 * q + e);
+                            const float p1 = kPScale * kernel_value(fb, sb, 8 * q + e + 1);
                             const f16x2 h2 = __builtin_amdgcn_cvt_pkrtz(p0, p1);
                             const f16x2 l2 = __builtin_amdgcn_cvt_pkrtz(p0 - (float)h2[0], p1 - (float)h2[1]);
                             ph[e / 2] = __builtin_bit_cast(uint32_t, h2);
@@ -517,7 +520,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int c = 8 * (r / 4) + 4 * h + (r % 4);
-                            if (c < t) dacc[fb][r] = fmaf(p * w * column_scale(colmax[c], false), a.vec[j * a.ldv + c], dacc[fb][r]);
+                            if (c < t) dacc[fb][r] = fmaf(kPScale * p * w * column_scale(colmax[c], false), a.vec[j * a.ldv + c], dacc[fb][r]);
                         }
                     };
 #pragma unroll
@@ -588,7 +591,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int c = 8 * (r / 4) + 4 * h + (r % 4);
-                if (idx < a.nF && c < t) out[idx * a.ldo + c] = dacc[fb][r] * column_scale(colmax[c], true);
+                if (idx < a.nF && c < t) out[idx * a.ldo + c] = (dacc[fb][r] * (1.0f / kPScale)) * column_scale(colmax[c], true);
             }
         }
     } else {

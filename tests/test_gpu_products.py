@@ -330,3 +330,19 @@ def test_workspace_held_stays_within_the_announced_bound(knm, n, M, d, t):
             print(f"{mode} {kind}: held {held} of {bound}", flush=True)
             assert 0 < held <= bound
             ctx.close()
+
+
+@pytest.mark.parametrize("t", [9, 20])
+def test_matrix_core_reduction_keeps_small_kernel_values(knm, t):
+    """Data and centres in two clusters far apart: the kernel values lie around and below fp16's
+    normal range (6e-5), most of them by orders of magnitude.  With 8 or more columns the kernel values go through
+    fp16 halves, which must still resolve them relative to themselves."""
+    n, M, d = 600, 300, 28
+    X, C, V = _rand(n, d, 101), _rand(M, d, 102) + 3.0, _rand(M, t, 103)
+    knm.default_context().set_cross_term("f16x3")
+    for sigma in (3.1, 2.7):  # kernel values up to 5e-4 and up to 5e-5 (median 1e-7 and 1e-9)
+        assert oracle.kernel_matrix(X.numpy(), C.numpy(), sigma).max() < 1e-3
+        Wo = oracle.knm_v(X.numpy(), C.numpy(), sigma, V.numpy())
+        W = knm.knm_v(X.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
+        print(f"sigma {sigma}: |W| {np.linalg.norm(Wo):.2e} error {rel_l2(W, Wo):.2e}", flush=True)
+        assert rel_l2(W, Wo) < TOL
