@@ -270,9 +270,9 @@ int knm_set_cross_term(knm_ctx *ctx, int mode);
  * cancellation error of the expansion for close pairs (every Nystrom centre coincides with a data
  * row), so pairs closer than a threshold derived from the points' norms are evaluated again from
  * fp32 differences of the two rows: the result keeps the accuracy of the Gaussian kernel.  That
- * second evaluation is rare for centred data; for data whose distance from the origin is many
- * times sigma, most pairs take it and the sweep slows down accordingly (centre such data first:
- * the kernel depends on differences only).  The preconditioner's k(C, C) is formed from fp64
+ * second evaluation is rare as long as the points' distances from the mean of the centres (the
+ * engines expand around it) are not many times sigma; where they are, most pairs take it and the
+ * sweep slows down accordingly.  The preconditioner's k(C, C) is formed from fp64
  * differences.  The sparse (CSR) entry points support the Gaussian kernel only and return
  * KNM_UNSUPPORTED otherwise. */
 typedef enum {

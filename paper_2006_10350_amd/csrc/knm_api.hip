@@ -78,6 +78,27 @@ static bool bad_geom(const void *X, int64_t n, int d, int64_t ldx, const void *C
     return !X || !C || n <= 0 || M <= 0 || d <= 0 || t <= 0 || ldx < d || ldc < d || !(sigma > 0.0f);
 }
 
+// mu[k] = mean of feature k over the first `rows` rows of P: the common shift of a sweep's two
+// point sets.  One workgroup per 32 features, 8 row lanes per feature, fp64 sums in a fixed order.
+__global__ __launch_bounds__(256) void column_mean_kernel(const float *__restrict__ P, int64_t rows, int64_t ld, int d,
+                                                         float *__restrict__ mu)
+{
+    __shared__ double part[8][32];
+    const int f = threadIdx.x & 31, lane8 = threadIdx.x >> 5;
+    const int k = blockIdx.x * 32 + f;
+    double s = 0.0;
+    if (k < d)
+        for (int64_t r = lane8; r < rows; r += 8) s += (double)P[r * ld + k];
+    part[lane8][f] = s;
+    __syncthreads();
+    if (lane8 == 0 && k < d) {
+        double total = 0.0;
+        for (int i = 0; i < 8; ++i) total += part[i][f];
+        const float m = (float)(total / (double)rows);
+        mu[k] = (m == m && fabsf(m) < 3.0e38f) ? m : 0.0f; // a NaN or Inf in the data must not spread to every point
+    }
+}
+
 // Bytes of the packed-operand workspace one sweep asks for in the split-fp16 modes (0 in the
 // fp32-MFMA mode): the same rule for the sweep itself and for knm_workspace_bytes.  `limit` = the
 // caller's cap, 0 for the defaults.
@@ -116,6 +137,16 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         if (st) return st;
         part = ctx->part_buf;
     }
+    // common shift: feature means of (the first rows of) the smaller point set
+    {
+        int st = ensure(ctx, &ctx->mu_buf, &ctx->mu_bytes, sizeof(float) * (size_t)d);
+        if (st) return st;
+        const bool from_f = nF <= nS;
+        const int64_t rows = from_f ? nF : nS;
+        hipLaunchKernelGGL(column_mean_kernel, dim3((unsigned)((d + 31) / 32)), dim3(256), 0, ctx->stream, from_f ? F : S,
+                           rows < 65536 ? rows : 65536, from_f ? ldf : lds, d, ctx->mu_buf);
+        if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "column_mean_kernel launch");
+    }
     const bool gemm = use_gemm_engine(d, t, ctx->cross_term, ctx->kernel_kind);
     // columns per launch
     const int group = !gemm ? 1 : (ctx->cross_term == KNM_CROSS_F16X3 ? gemm_f16_max_t() : gemm_max_t());
@@ -124,6 +155,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.F = F; a.nF = nF; a.ldf = ldf;
         a.S = S; a.nS = nS; a.lds = lds;
         a.d = d;
+        a.mu = ctx->mu_buf;
         a.vec = vec + c; a.ldv = t;
         a.t = (t - c < group) ? t - c : group;
         a.wgt = wgt;
@@ -231,6 +263,7 @@ int knm_destroy(knm_ctx *ctx)
     if (ctx->w_buf) (void)hipFree(ctx->w_buf);
     if (ctx->part_buf) (void)hipFree(ctx->part_buf);
     if (ctx->pack_buf) (void)hipFree(ctx->pack_buf);
+    if (ctx->mu_buf) (void)hipFree(ctx->mu_buf);
     for (int i = 0; i < 5; ++i)
         if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     extern void knm_solver_release(knm_ctx *);
@@ -283,12 +316,12 @@ size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
             if (k2 > pack) pack = k2;
         }
     }
-    return bytes + part + pack;
+    return bytes + part + pack + sizeof(float) * (size_t)d;
 }
 
 size_t knm_workspace_held(const knm_ctx *ctx)
 {
-    return ctx ? ctx->w_bytes + ctx->part_bytes + ctx->pack_bytes : 0;
+    return ctx ? ctx->w_bytes + ctx->part_bytes + ctx->pack_bytes + ctx->mu_bytes : 0;
 }
 
 static int check_common(knm_ctx *ctx, const void *X, int64_t n, int d, int64_t ldx, const void *C, int64_t M,

@@ -146,19 +146,23 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
         f32x4 pre[kLoads];
         auto fetch = [&](int kc) {
             const int f0 = kc * kChunk + sq * 4;
+            // the common shift of this thread's four features (the same for all its points)
+            f32x4 m4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) m4[e] = a.mu[f0 + e < d ? f0 + e : 0];
 #pragma unroll
             for (int i = 0; i < kLoads; ++i) {
                 if constexpr (VW == 4) {
                     const bool in = valid[i] && (f0 < d); // d % 4 == 0 in this mode
                     const f32x4 v = *reinterpret_cast<const f32x4 *>(rowp(i) + (in ? f0 : 0));
-                    pre[i][0] = in ? v[0] : 0.0f; pre[i][1] = in ? v[1] : 0.0f;
-                    pre[i][2] = in ? v[2] : 0.0f; pre[i][3] = in ? v[3] : 0.0f;
+                    pre[i][0] = in ? v[0] - m4[0] : 0.0f; pre[i][1] = in ? v[1] - m4[1] : 0.0f;
+                    pre[i][2] = in ? v[2] - m4[2] : 0.0f; pre[i][3] = in ? v[3] - m4[3] : 0.0f;
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const bool in = valid[i] && (f0 + e < d);
                         const float v = rowp(i)[in ? f0 + e : 0];
-                        pre[i][e] = in ? v : 0.0f;
+                        pre[i][e] = in ? v - m4[e] : 0.0f;
                     }
                 }
             }

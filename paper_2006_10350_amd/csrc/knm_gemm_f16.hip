@@ -100,8 +100,8 @@ __device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
 // chunks (64 features) per pass over the row.
 template <int VW>
 __global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__restrict__ P, int64_t nP, int64_t ld,
-                                                               int d, float sigma, int64_t row0, int n_kc,
-                                                               f16x8 *__restrict__ img)
+                                                               const float *__restrict__ mu, int d, float sigma,
+                                                               int64_t row0, int n_kc, f16x8 *__restrict__ img)
 {
     const int tid = threadIdx.x;
     const int u = tid & 7;
@@ -123,15 +123,16 @@ __global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__re
             for (int k = 0; k < 8; k += 4) {
                 const bool in = valid && (f0 + k < d); // d % 4 == 0 in this mode
                 const f32x4 v = *reinterpret_cast<const f32x4 *>(row + (in ? f0 + k : 0));
-                z[k] = in ? v[0] : 0.0f; z[k + 1] = in ? v[1] : 0.0f;
-                z[k + 2] = in ? v[2] : 0.0f; z[k + 3] = in ? v[3] : 0.0f;
+                const f32x4 m = *reinterpret_cast<const f32x4 *>(mu + (in ? f0 + k : 0));
+                z[k] = in ? v[0] - m[0] : 0.0f; z[k + 1] = in ? v[1] - m[1] : 0.0f;
+                z[k + 2] = in ? v[2] - m[2] : 0.0f; z[k + 3] = in ? v[3] - m[3] : 0.0f;
             }
         } else {
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const bool in = valid && (f0 + k < d);
                 const float v = row[in ? f0 + k : 0];
-                z[k] = in ? v : 0.0f;
+                z[k] = in ? v - mu[in ? f0 + k : 0] : 0.0f;
             }
         }
         f16x8 hi, lo;
@@ -627,15 +628,15 @@ __global__ void col_absmax_kernel(const float *__restrict__ vec, int64_t ldv, co
     if (c < t && m > 0.0f) atomicMax(out + c, __float_as_uint(m));
 }
 
-hipError_t pack_points(const float *P, int64_t nP, int64_t ld, int d, float sigma, int64_t row0, int64_t rows,
-                       int n_kc, f16x8 *img, hipStream_t stream)
+hipError_t pack_points(const float *P, int64_t nP, int64_t ld, const float *mu, int d, float sigma, int64_t row0,
+                       int64_t rows, int n_kc, f16x8 *img, hipStream_t stream)
 {
     const dim3 grid((unsigned)(rows / 32));
     const bool a16 = (d % 4 == 0) && (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(P) & 15) == 0);
     if (a16)
-        hipLaunchKernelGGL((pack_points_kernel<4>), grid, dim3(kThreads), 0, stream, P, nP, ld, d, sigma, row0, n_kc, img);
+        hipLaunchKernelGGL((pack_points_kernel<4>), grid, dim3(kThreads), 0, stream, P, nP, ld, mu, d, sigma, row0, n_kc, img);
     else
-        hipLaunchKernelGGL((pack_points_kernel<1>), grid, dim3(kThreads), 0, stream, P, nP, ld, d, sigma, row0, n_kc, img);
+        hipLaunchKernelGGL((pack_points_kernel<1>), grid, dim3(kThreads), 0, stream, P, nP, ld, mu, d, sigma, row0, n_kc, img);
     return hipGetLastError();
 }
 
@@ -728,12 +729,12 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
 
     for (int64_t f0 = 0; f0 < nFp; f0 += f_slab) {
         const int64_t f_rows = (nFp - f0 < f_slab) ? nFp - f0 : f_slab;
-        hipError_t e = pack_points(a.F, a.nF, a.ldf, a.d, a.sigma, f0, f_rows, n_kc, Fimg, stream);
+        hipError_t e = pack_points(a.F, a.nF, a.ldf, a.mu, a.d, a.sigma, f0, f_rows, n_kc, Fimg, stream);
         if (e != hipSuccess) return e;
         for (int64_t c0 = 0; c0 < a.n_chunks; c0 += s_slab) {
             const int64_t nc = (a.n_chunks - c0 < s_slab) ? a.n_chunks - c0 : s_slab;
             if (f0 == 0 || s_slab < a.n_chunks) { // a whole stream image is built once
-                e = pack_points(a.S, a.nS, a.lds, a.d, a.sigma, c0 * a.chunk_len, nc * a.chunk_len, n_kc, Simg, stream);
+                e = pack_points(a.S, a.nS, a.lds, a.mu, a.d, a.sigma, c0 * a.chunk_len, nc * a.chunk_len, n_kc, Simg, stream);
                 if (e != hipSuccess) return e;
             }
             const int64_t fb = f_rows / kFixed;

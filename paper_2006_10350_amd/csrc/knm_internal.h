@@ -25,6 +25,10 @@ struct SweepArgs {
     const float *S;   // stream points, nS x d, leading dimension lds
     int64_t nS, lds;
     int d;
+    // common shift of both point sets, d floats: the engines work with F - mu and S - mu (the kernels
+    // depend on differences only), which keeps the norm terms of the expansion small for data that
+    // is not centred
+    const float *mu;
     const float *vec; // stream-side vectors: column c of stream point i is vec[i * ldv + c]
     int64_t ldv;
     int t;            // columns handled by this launch (1 for the register-resident engine)
@@ -145,6 +149,8 @@ struct knm_ctx {
     size_t w_bytes = 0;
     float *part_buf = nullptr;
     size_t part_bytes = 0;
+    float *mu_buf = nullptr;   // common shift of the two point sets of a sweep (d floats)
+    size_t mu_bytes = 0;
     float *pack_buf = nullptr; // packed operand images of the split-fp16 engines
     size_t pack_bytes = 0;
     size_t pack_limit = 0;     // cap on the image workspace chosen by the caller; 0 = engine defaults

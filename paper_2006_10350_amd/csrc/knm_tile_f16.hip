@@ -94,29 +94,32 @@ __device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
 
 // branch-free row loads (see knm_tile.hip): virtual features [base, base + N), zero beyond d
 template <int N, int VW>
-__device__ __forceinline__ void load_features(const float *__restrict__ row, int base, int d, bool valid,
-                                              float (&x)[N])
+__device__ __forceinline__ void load_features(const float *__restrict__ row, const float *__restrict__ mu, int base,
+                                              int d, bool valid, float (&x)[N])
 {
     if constexpr (VW == 4) {
 #pragma unroll
         for (int k = 0; k < N; k += 4) {
             const bool in = valid && (base + k < d); // d % 4 == 0 in this mode
             const f32x4 v = *reinterpret_cast<const f32x4 *>(row + (in ? base + k : 0));
-            x[k] = in ? v[0] : 0.0f; x[k + 1] = in ? v[1] : 0.0f; x[k + 2] = in ? v[2] : 0.0f; x[k + 3] = in ? v[3] : 0.0f;
+            const f32x4 m = *reinterpret_cast<const f32x4 *>(mu + (in ? base + k : 0));
+            x[k] = in ? v[0] - m[0] : 0.0f; x[k + 1] = in ? v[1] - m[1] : 0.0f;
+            x[k + 2] = in ? v[2] - m[2] : 0.0f; x[k + 3] = in ? v[3] - m[3] : 0.0f;
         }
     } else if constexpr (VW == 2) {
 #pragma unroll
         for (int k = 0; k < N; k += 2) {
             const bool in = valid && (base + k < d); // d % 2 == 0 in this mode
             const f32x2 v = *reinterpret_cast<const f32x2 *>(row + (in ? base + k : 0));
-            x[k] = in ? v[0] : 0.0f; x[k + 1] = in ? v[1] : 0.0f;
+            const f32x2 m = *reinterpret_cast<const f32x2 *>(mu + (in ? base + k : 0));
+            x[k] = in ? v[0] - m[0] : 0.0f; x[k + 1] = in ? v[1] - m[1] : 0.0f;
         }
     } else {
 #pragma unroll
         for (int k = 0; k < N; ++k) {
             const bool in = valid && (base + k < d);
             const float v = row[in ? base + k : 0];
-            x[k] = in ? v : 0.0f;
+            x[k] = in ? v - mu[in ? base + k : 0] : 0.0f;
         }
     }
 }
@@ -209,8 +212,8 @@ __device__ __forceinline__ void block_tile(f32x16 &acc, const f16x8 (&fh)[HU], c
 // tile g of the slab occupies 2 * HU * 64 units at packed + g * 2 * HU * 64.
 template <int NU, int VW>
 __global__ __launch_bounds__(kThreads) void pack_stream_kernel(const float *__restrict__ S, int64_t nS, int64_t lds,
-                                                               int d, float sigma, int64_t row0, int64_t rows,
-                                                               f16x8 *__restrict__ packed)
+                                                               const float *__restrict__ mu, int d, float sigma,
+                                                               int64_t row0, int64_t rows, f16x8 *__restrict__ packed)
 {
     constexpr int HU = NU / 2;
     constexpr int FPT = 8 * HU;
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(kThreads) void pack_stream_kernel(const float *__re
     const bool valid = idx < nS;
     const float gamma = sqrtf(kLog2e) / sigma;
     float xs[FPT];
-    load_features<FPT, VW>(S + (valid ? idx : 0) * lds, part * FPT, d, valid, xs);
+    load_features<FPT, VW>(S + (valid ? idx : 0) * lds, mu, part * FPT, d, valid, xs);
     float nrm = 0.0f;
 #pragma unroll
     for (int k = 0; k < FPT; ++k) {
@@ -290,7 +293,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int k = 8 * (2 * m + h) + e;
-                const float z = (valid && k < d) ? gamma * p[k] : 0.0f;
+                const float z = (valid && k < d) ? gamma * (p[k] - a.mu[k < d ? k : 0]) : 0.0f;
                 nrm = fmaf(z, z, nrm);
                 _Float16 zh, zl;
                 split_half(z, zh, zl);
@@ -429,13 +432,13 @@ hipError_t launch_nu(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipS
         const int64_t row0 = c0 * a.chunk_len, rows = nc * a.chunk_len;
         const dim3 pgrid((unsigned)((rows + kThreads / 2 - 1) / (kThreads / 2)));
         if (a16)
-            hipLaunchKernelGGL((pack_stream_kernel<NU, 4>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.d,
+            hipLaunchKernelGGL((pack_stream_kernel<NU, 4>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.mu, a.d,
                                a.sigma, row0, rows, packed);
         else if (a8)
-            hipLaunchKernelGGL((pack_stream_kernel<NU, 2>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.d,
+            hipLaunchKernelGGL((pack_stream_kernel<NU, 2>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.mu, a.d,
                                a.sigma, row0, rows, packed);
         else
-            hipLaunchKernelGGL((pack_stream_kernel<NU, 1>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.d,
+            hipLaunchKernelGGL((pack_stream_kernel<NU, 1>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.mu, a.d,
                                a.sigma, row0, rows, packed);
         const dim3 grid((unsigned)blocks, (unsigned)nc);
         hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU>), grid, dim3(kThreads), 0, stream, a, packed, c0);

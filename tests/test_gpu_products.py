@@ -184,15 +184,24 @@ def test_degenerate_sizes(knm, cross):
 
 
 def test_large_norm_close_pairs(knm, cross):
-    # the cancellation hazard of the norm expansion: large |x|, small distances.
-    # With |x|^2 ~ 1e3 the fp32 expansion keeps ~1e-4 absolute accuracy on the exponent.
+    """Data far from the origin (|x|^2 ~ 1000 sigma^2) with small mutual distances: the norm expansion
+    alone would keep only ~1e-4 of the exponent; the engines expand around the centres' mean, so the
+    accuracy is that of centred data.  A second case moves single points far away from that mean."""
     n, M, d, sigma = 2000, 256, 8, 1.0
-    base = _rand(1, d, 17) * 0.0 + 11.0
-    X = base + 0.5 * _rand(n, d, 18)
-    C = base + 0.5 * _rand(M, d, 19)
+    X = 11.0 + 0.5 * _rand(n, d, 18)
+    C = 11.0 + 0.5 * _rand(M, d, 19)
     V = torch.ones(M, 1)
     W = knm.knm_v(X.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
-    assert rel_l2(W, oracle.knm_v(X.numpy(), C.numpy(), sigma, V.numpy())) < 1e-3
+    err = rel_l2(W, oracle.knm_v(X.numpy(), C.numpy(), sigma, V.numpy()))
+    print(f"offset data: {err:.2e}", flush=True)
+    assert err < TIGHT
+    U = knm.knm_t_y(X.cuda(), C.cuda(), sigma, torch.ones(n, 1).cuda()).cpu().numpy()
+    assert rel_l2(U, oracle.knm_t_y(X.numpy(), C.numpy(), sigma, np.ones((n, 1)))) < TIGHT
+    # outliers in the data (not among the centres): their rows are far from everything, the rest is unaffected
+    X2 = X.clone()
+    X2[::97] += 40.0
+    W2 = knm.knm_v(X2.cuda(), C.cuda(), sigma, V.cuda()).cpu().numpy()
+    assert rel_l2(W2, oracle.knm_v(X2.numpy(), C.numpy(), sigma, V.numpy())) < TIGHT
 
 
 def test_split_half_range_limits(knm):
@@ -212,9 +221,10 @@ def test_split_half_range_limits(knm):
         assert np.all(np.isfinite(W))
         keep = np.ones(n, dtype=bool)
         keep[11] = False
-        keep[7] = False       # its twin centre: |x|^2 ~ 1e5 cancels to 0, fp32 keeps ~1e-2 of the exponent
+        keep[7] = False       # its twin centre: |x|^2 ~ 1e5 cancels to 0; the split halves leave out 2.4e-7 of it,
+                              # about 0.02 in the exponent (unless 300 minus the common shift happens to be a half)
         assert rel_l2(W[keep], Wo[keep]) < 1e-4
-        assert W[7, 0] == pytest.approx(Wo[7, 0], rel=2e-2) and Wo[7, 0] >= 1.0  # sees its twin centre
+        assert W[7, 0] == pytest.approx(Wo[7, 0], rel=5e-2) and Wo[7, 0] >= 1.0  # sees its twin centre
         assert abs(W[11, 0]) < 1e-6
     finally:
         ctx.set_cross_term("f16x3")
