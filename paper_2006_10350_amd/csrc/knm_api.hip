@@ -99,6 +99,27 @@ __global__ __launch_bounds__(256) void column_mean_kernel(const float *__restric
     }
 }
 
+// Keeps the shift only where it pays: if the mean itself is within sigma of the origin
+// (|mu|^2 / 2 sigma^2 <= 0.5) the norm terms are small anyway, and mu is set to zero, which leaves the
+// points exactly as they are (data with many exact zeros keeps them: the matrix cores draw less
+// power on such operands, and the sweep runs measurably faster).  One workgroup.
+__global__ __launch_bounds__(256) void shift_decide_kernel(float *__restrict__ mu, int d, float inv2s2)
+{
+    __shared__ float part[256];
+    float s = 0.0f;
+    for (int k = threadIdx.x; k < d; k += 256) s = fmaf(mu[k], mu[k], s);
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    const bool keep = part[0] * inv2s2 > 0.5f;
+    if (!keep)
+        for (int k = threadIdx.x; k < d; k += 256) mu[k] = 0.0f;
+    if (threadIdx.x == 0) mu[d] = keep ? 1.0f : 0.0f; // lets the hot loops skip the loads of an all-zero shift
+}
+
 // Bytes of the packed-operand workspace one sweep asks for in the split-fp16 modes (0 in the
 // fp32-MFMA mode): the same rule for the sweep itself and for knm_workspace_bytes.  `limit` = the
 // caller's cap, 0 for the defaults.
@@ -139,12 +160,14 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
     }
     // common shift: feature means of (the first rows of) the smaller point set
     {
-        int st = ensure(ctx, &ctx->mu_buf, &ctx->mu_bytes, sizeof(float) * (size_t)d);
+        int st = ensure(ctx, &ctx->mu_buf, &ctx->mu_bytes, sizeof(float) * ((size_t)d + 1)); // + the "shifted" flag
         if (st) return st;
         const bool from_f = nF <= nS;
         const int64_t rows = from_f ? nF : nS;
         hipLaunchKernelGGL(column_mean_kernel, dim3((unsigned)((d + 31) / 32)), dim3(256), 0, ctx->stream, from_f ? F : S,
                            rows < 65536 ? rows : 65536, from_f ? ldf : lds, d, ctx->mu_buf);
+        hipLaunchKernelGGL(shift_decide_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->mu_buf, d,
+                           1.0f / (2.0f * sigma * sigma));
         if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "column_mean_kernel launch");
     }
     const bool gemm = use_gemm_engine(d, t, ctx->cross_term, ctx->kernel_kind);
@@ -316,7 +339,7 @@ size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
             if (k2 > pack) pack = k2;
         }
     }
-    return bytes + part + pack + sizeof(float) * (size_t)d;
+    return bytes + part + pack + sizeof(float) * ((size_t)d + 1);
 }
 
 size_t knm_workspace_held(const knm_ctx *ctx)

@@ -96,6 +96,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
     const int d = a.d;
     const float s2 = kLog2e / (2.0f * a.sigma * a.sigma);
     const int n_kc = (d + kChunk - 1) / kChunk;
+    const bool shifted = a.mu[d] != 0.0f; // same for every thread of the grid
 
     const int64_t fixed0 = (int64_t)blockIdx.x * kFixed;
     const int64_t chunk_begin = (int64_t)blockIdx.y * a.chunk_len;
@@ -147,9 +148,11 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
         auto fetch = [&](int kc) {
             const int f0 = kc * kChunk + sq * 4;
             // the common shift of this thread's four features (the same for all its points)
-            f32x4 m4;
+            f32x4 m4 = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (shifted) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) m4[e] = a.mu[f0 + e < d ? f0 + e : 0];
+                for (int e = 0; e < 4; ++e) m4[e] = a.mu[f0 + e < d ? f0 + e : 0];
+            }
 #pragma unroll
             for (int i = 0; i < kLoads; ++i) {
                 if constexpr (VW == 4) {

@@ -27,7 +27,7 @@ struct SweepArgs {
     int d;
     // common shift of both point sets, d floats: the engines work with F - mu and S - mu (the kernels
     // depend on differences only), which keeps the norm terms of the expansion small for data that
-    // is not centred
+    // is not centred; mu[d] != 0 says that the shift is not all zero
     const float *mu;
     const float *vec; // stream-side vectors: column c of stream point i is vec[i * ldv + c]
     int64_t ldv;

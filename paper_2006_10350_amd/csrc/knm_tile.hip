@@ -68,15 +68,16 @@ __host__ __device__ constexpr int ks_for_d(int d)
 // elements and are zeroed by a select, so all loads issue back to back and their latency
 // is hidden behind a whole stage of MFMA work.  `row` must point at a readable row.
 template <int N, int VW>
-__device__ __forceinline__ void load_features(const float *__restrict__ row, const float *__restrict__ mu, int base,
-                                              int d, bool valid, float (&x)[N])
+__device__ __forceinline__ void load_features(const float *__restrict__ row, const float *__restrict__ mu, bool shifted,
+                                              int base, int d, bool valid, float (&x)[N])
 {
     if constexpr (VW == 4) {
 #pragma unroll
         for (int k = 0; k < N; k += 4) {
             const bool in = valid && (base + k < d); // d % 4 == 0 in this mode
             const f32x4 v = *reinterpret_cast<const f32x4 *>(row + (in ? base + k : 0));
-            const f32x4 m = *reinterpret_cast<const f32x4 *>(mu + (in ? base + k : 0));
+            f32x4 m = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (shifted) m = *reinterpret_cast<const f32x4 *>(mu + (in ? base + k : 0));
             x[k] = in ? v[0] - m[0] : 0.0f; x[k + 1] = in ? v[1] - m[1] : 0.0f;
             x[k + 2] = in ? v[2] - m[2] : 0.0f; x[k + 3] = in ? v[3] - m[3] : 0.0f;
         }
@@ -85,7 +86,8 @@ __device__ __forceinline__ void load_features(const float *__restrict__ row, con
         for (int k = 0; k < N; k += 2) {
             const bool in = valid && (base + k < d); // d % 2 == 0 in this mode
             const f32x2 v = *reinterpret_cast<const f32x2 *>(row + (in ? base + k : 0));
-            const f32x2 m = *reinterpret_cast<const f32x2 *>(mu + (in ? base + k : 0));
+            f32x2 m = {0.0f, 0.0f};
+            if (shifted) m = *reinterpret_cast<const f32x2 *>(mu + (in ? base + k : 0));
             x[k] = in ? v[0] - m[0] : 0.0f; x[k + 1] = in ? v[1] - m[1] : 0.0f;
         }
     } else {
@@ -93,7 +95,7 @@ __device__ __forceinline__ void load_features(const float *__restrict__ row, con
         for (int k = 0; k < N; ++k) {
             const bool in = valid && (base + k < d);
             const float v = row[in ? base + k : 0];
-            x[k] = in ? v - mu[in ? base + k : 0] : 0.0f;
+            x[k] = in ? v - (shifted ? mu[in ? base + k : 0] : 0.0f) : 0.0f;
         }
     }
 }
@@ -179,6 +181,7 @@ __global__ __launch_bounds__(kThreads, (KS <= 15 ? 3 : 1)) void gauss_sweep_kern
     const int h = lane >> 5;
     const float s2 = kLog2e / (2.0f * a.sigma * a.sigma);
     const int d = a.d;
+    const bool shifted = a.mu[d] != 0.0f; // same for every thread of the grid
 
     // ---- fixed operand: R blocks of 32 points per wavefront, in registers -------------
     const int64_t fixed0 = ((int64_t)blockIdx.x * kWaves + wave) * (32 * R);
@@ -220,7 +223,7 @@ __global__ __launch_bounds__(kThreads, (KS <= 15 ? 3 : 1)) void gauss_sweep_kern
         const int64_t idx = chunk_begin + (int64_t)stage * kStage + sp;
         const bool valid = idx < chunk_end;
         const float *p = a.S + (valid ? idx : 0) * a.lds;
-        load_features<VPT, VW>(p, a.mu, part * VPT, d, valid, xs);
+        load_features<VPT, VW>(p, a.mu, shifted, part * VPT, d, valid, xs);
         const int64_t vi = valid ? idx : 0;
         const float vraw = a.vec[vi * a.ldv];
         const float wraw = (a.wgt != nullptr) ? a.wgt[vi] : 1.0f;
