@@ -145,16 +145,23 @@ static size_t pack_bytes_wanted(int64_t nF, int d, int t, int kind, size_t limit
     return want;
 }
 
-// out[f, c] = sum_s k(F_f, S_s) vec[s, c] wgt[s]  for c < t (all arrays leading dimension t)
+// out[f, c] = sum_s k(F_f, S_s) vec[s, c] wgt[s]  for c < t (all arrays leading dimension t); the
+// result goes to `out` (fp32) or, if that is null, to `out64`: then the chunk partials of the K-loop
+// engines stay in fp64 from the kernels' running sums to the merged result
 static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const float *S, int64_t nS, int64_t lds,
-                 int d, float sigma, const float *vec, const float *wgt, int t, float *out, hipEvent_t after_sweep)
+                 int d, float sigma, const float *vec, const float *wgt, int t, float *out, double *out64,
+                 hipEvent_t after_sweep)
 {
     int64_t chunk_len = 0;
     const int64_t chunks = choose_chunks(nF, nS, d, t, ctx->cross_term, ctx->kernel_kind, &chunk_len);
     if (chunks > 65535) return fail(ctx, KNM_UNSUPPORTED, "too many stream chunks");
+    const bool gemm = use_gemm_engine(d, t, ctx->cross_term, ctx->kernel_kind);
+    const bool part_is_64 = out64 != nullptr && gemm;
+    const bool merged = chunks > 1 || out64 != nullptr; // an fp64 result is always written by the merge pass
     float *part = nullptr;
-    if (chunks > 1) {
-        int st = ensure(ctx, &ctx->part_buf, &ctx->part_bytes, sizeof(float) * (size_t)chunks * nF * t);
+    if (merged) {
+        int st = ensure(ctx, &ctx->part_buf, &ctx->part_bytes,
+                        (part_is_64 ? sizeof(double) : sizeof(float)) * (size_t)chunks * nF * t);
         if (st) return st;
         part = ctx->part_buf;
     }
@@ -170,7 +177,6 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
                            1.0f / (2.0f * sigma * sigma));
         if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "column_mean_kernel launch");
     }
-    const bool gemm = use_gemm_engine(d, t, ctx->cross_term, ctx->kernel_kind);
     // columns per launch
     const int group = !gemm ? 1 : (ctx->cross_term == KNM_CROSS_F16X3 ? gemm_f16_max_t() : gemm_max_t());
     for (int c = 0; c < t; c += group) {
@@ -182,7 +188,8 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.vec = vec + c; a.ldv = t;
         a.t = (t - c < group) ? t - c : group;
         a.wgt = wgt;
-        a.out = (chunks > 1) ? part + c : out + c;
+        a.out = merged ? part + c : out + c;
+        a.out64 = part_is_64 ? reinterpret_cast<double *>(part) + c : nullptr;
         a.ldo = t;
         a.chunk_stride = nF * t;
         a.chunk_len = chunk_len;
@@ -214,8 +221,9 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "launch_sweep", e);
     }
     if (after_sweep) (void)hipEventRecord(after_sweep, ctx->stream);
-    if (chunks > 1) {
-        hipError_t e = launch_merge(part, chunks, nF * t, 1, out, 1, nF * t, ctx->stream);
+    if (merged) {
+        hipError_t e = launch_merge(part_is_64 ? nullptr : part, part_is_64 ? reinterpret_cast<double *>(part) : nullptr,
+                                    chunks, nF * t, 1, out64 != nullptr ? nullptr : out, out64, 1, nF * t, ctx->stream);
         if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "launch_merge", e);
     }
     return KNM_OK;
@@ -238,18 +246,18 @@ static void begin_timing(knm_ctx *ctx)
 int do_knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
              int64_t ldc, float sigma, const float *V, int t, float *W)
 {
-    return sweep(ctx, X, n, ldx, C, M, ldc, d, sigma, V, nullptr, t, W, nullptr);
+    return sweep(ctx, X, n, ldx, C, M, ldc, d, sigma, V, nullptr, t, W, nullptr, nullptr);
 }
 
 int do_knm_t_w(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
-               int64_t ldc, float sigma, const float *Wv, const float *wgt, int t, float *U)
+               int64_t ldc, float sigma, const float *Wv, const float *wgt, int t, float *U, double *U64)
 {
     hipEvent_t ev = nullptr;
     if (ctx->timing) {
         ev = ctx->ev[2];
         ctx->ev_used[2] = true;
     }
-    return sweep(ctx, C, M, ldc, X, n, ldx, d, sigma, Wv, wgt, t, U, ev);
+    return sweep(ctx, C, M, ldc, X, n, ldx, d, sigma, Wv, wgt, t, U64 != nullptr ? nullptr : U, U64, ev);
 }
 
 } // namespace knm

@@ -109,11 +109,20 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
     const int sq = tid & 3;
     const int sp0 = tid >> 2;
 
+    // Two levels of summation: the terms of one tile (64 per lane and fixed point) in fp32 from zero,
+    // the tile sums into fp64 running sums, so that the rounding of a long sum of same-sign terms
+    // does not grow with the chunk (with 16 columns the registers hold only the fp32 sums, which
+    // then run through the chunk).
+    constexpr bool kWide = TP <= 12;
     float sum[2][TP];
+    double wide[2][kWide ? TP : 1];
 #pragma unroll
     for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
-        for (int c = 0; c < TP; ++c) sum[fb][c] = 0.0f;
+        for (int c = 0; c < TP; ++c) {
+            sum[fb][c] = 0.0f;
+            if constexpr (kWide) wide[fb][c] = 0.0;
+        }
 
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int64_t stream0 = chunk_begin + (int64_t)tile * kStream;
@@ -332,19 +341,37 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_kernel(SweepArgs a)
                 }
             }
         }
+        if constexpr (kWide) {
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+                for (int c = 0; c < TP; ++c) {
+                    wide[fb][c] += (double)sum[fb][c];
+                    sum[fb][c] = 0.0f;
+                }
+        }
         __syncthreads(); // aug / vimg / img are rewritten by the next tile
     }
 
     // the two half-waves hold different stream rows of the same fixed point
-    float *out = a.out + (int64_t)blockIdx.y * a.chunk_stride;
+    // partials in fp64 if asked for (a uniform choice: one base address, two element sizes)
+    const bool wide_out = a.out64 != nullptr;
+    char *const obase = wide_out ? reinterpret_cast<char *>(a.out64 + (int64_t)blockIdx.y * a.chunk_stride)
+                                 : reinterpret_cast<char *>(a.out + (int64_t)blockIdx.y * a.chunk_stride);
 #pragma unroll
     for (int fb = 0; fb < 2; ++fb) {
         const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
 #pragma unroll
         for (int c = 0; c < TP; ++c) {
-            float v = sum[fb][c];
+            double v;
+            if constexpr (kWide) v = wide[fb][c];
+            else v = (double)sum[fb][c];
             v += __shfl_xor(v, 32);
-            if (h == 0 && idx < a.nF && c < t) out[idx * a.ldo + c] = v;
+            if (h == 0 && idx < a.nF && c < t) {
+                const int64_t at = idx * a.ldo + c;
+                if (wide_out) *reinterpret_cast<double *>(obase + at * 8) = v;
+                else *reinterpret_cast<float *>(obase + at * 4) = (float)v;
+            }
         }
     }
 }

@@ -288,11 +288,21 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     const f16x8 *const fbase = Fimg + fblk * (kFixed / 32) * blk_units;
     const f16x8 *const sbase = Simg + cblk * (a.chunk_len / 32) * blk_units;
 
+    // Vector-ALU reduction, two levels: the terms of one tile (64 per lane and fixed point) are summed
+    // in fp32 from zero, and the tile sums are added into fp64 running sums, so that the rounding of a
+    // long sum of same-sign terms does not grow with the length of the chunk (a plain fp32 running sum
+    // over some thousand terms loses 2-3 digits of what the solver's T^-T amplifies).  With more than 10
+    // columns (8 for the kernels of r) the registers do not hold a second set of sums and the fp32 sums run through the chunk.
+    constexpr bool kWide = !MV && TP <= (KIND == KNM_KERNEL_GAUSSIAN ? 10 : 8);
     float sum[2][TP];
+    double wide[2][kWide ? TP : 1];
 #pragma unroll
     for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
-        for (int c = 0; c < TP; ++c) sum[fb][c] = 0.0f;
+        for (int c = 0; c < TP; ++c) {
+            sum[fb][c] = 0.0f;
+            if constexpr (kWide) wide[fb][c] = 0.0;
+        }
     // MV: output tile [column][fixed point] of each fixed block, and this thread's column scale
     f32x16 dacc[2];
 #pragma unroll
@@ -579,10 +589,26 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                     }
                 }
             }
+            if constexpr (kWide) {
+#pragma unroll
+                for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+                    for (int c = 0; c < TP; ++c) {
+                        wide[fb][c] += (double)sum[fb][c];
+                        sum[fb][c] = 0.0f;
+                    }
+            }
         }
     }
 
-    float *out = a.out + chunk * a.chunk_stride;
+    // partials in fp64 if asked for (a uniform choice: one base address, two element sizes)
+    const bool wide_out = a.out64 != nullptr;
+    char *const obase = wide_out ? reinterpret_cast<char *>(a.out64 + chunk * a.chunk_stride)
+                                 : reinterpret_cast<char *>(a.out + chunk * a.chunk_stride);
+    auto store = [&](int64_t at, double v) {
+        if (wide_out) *reinterpret_cast<double *>(obase + at * 8) = v;
+        else *reinterpret_cast<float *>(obase + at * 4) = (float)v;
+    };
     mfma_results_ready();
     if constexpr (MV) {
         // register r of a lane: column 8 (r / 4) + 4 h + r % 4 of fixed point lane % 32; undo the scale
@@ -592,7 +618,8 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int c = 8 * (r / 4) + 4 * h + (r % 4);
-                if (idx < a.nF && c < t) out[idx * a.ldo + c] = (dacc[fb][r] * (1.0f / kPScale)) * column_scale(colmax[c], true);
+                if (idx < a.nF && c < t)
+                    store(idx * a.ldo + c, (double)((dacc[fb][r] * (1.0f / kPScale)) * column_scale(colmax[c], true)));
             }
         }
     } else {
@@ -602,9 +629,11 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
             const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
 #pragma unroll
             for (int c = 0; c < TP; ++c) {
-                float v = sum[fb][c];
+                double v;
+                if constexpr (kWide) v = wide[fb][c];
+                else v = (double)sum[fb][c];
                 v += __shfl_xor(v, 32);
-                if (h == 0 && idx < a.nF && c < t) out[idx * a.ldo + c] = v;
+                if (h == 0 && idx < a.nF && c < t) store(idx * a.ldo + c, v);
             }
         }
     }

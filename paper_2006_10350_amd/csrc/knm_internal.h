@@ -34,6 +34,9 @@ struct SweepArgs {
     int t;            // columns handled by this launch (1 for the register-resident engine)
     const float *wgt; // optional per-stream-point weight multiplied into vec (may be null)
     float *out;       // out[chunk * chunk_stride + f * ldo + c]
+    // K-loop engines only: if not null the results go here instead, same indexing, in fp64 (the
+    // register-resident engines ignore it and must be given `out`)
+    double *out64 = nullptr;
     int64_t ldo, chunk_stride;
     int64_t chunk_len; // stream points per chunk (multiple of the stage size)
     int64_t n_chunks;
@@ -102,9 +105,10 @@ size_t gemm_f16_pack_bytes_per_point(int d);
 int gemm_f16_max_t(); // columns per launch
 size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len, int d);
 hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream);
-// out[j * ldo] = sum over chunks of part[chunk * chunk_stride + j * ldp], summed in fp64
-hipError_t launch_merge(const float *part, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
-                        float *out, int64_t ldo, int64_t count, hipStream_t stream);
+// out[j * ldo] = sum over chunks of part[chunk * chunk_stride + j * ldp], summed in fp64 in a fixed
+// order; the partials are fp32 or (part64) fp64, the result goes to `out` or, if not null, to `out64`
+hipError_t launch_merge(const float *part, const double *part64, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
+                        float *out, double *out64, int64_t ldo, int64_t count, hipStream_t stream);
 
 // fp64 rank-k update of the upper triangle of C on the matrix cores (knm_dsyrk.hip):
 //   C[i, j] = alpha sum_{k < K} w[k] a(i, k) a(j, k) + beta C[i, j] + shift [i == j],  i <= j < n,
@@ -179,6 +183,8 @@ bool use_gemm_engine(int d, int t, int cross_term, int kind);
 int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int cross_term, int kind, int64_t *chunk_len);
 int do_knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
              int64_t ldc, float sigma, const float *V, int t, float *W);
+// U = K^T (wgt .* W) as fp32 rows (U) or, if U64 is not null, as fp64 rows (M x t, row-major) that
+// never pass through fp32 after the merge of the chunk partials
 int do_knm_t_w(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
-               int64_t ldc, float sigma, const float *Wv, const float *wgt, int t, float *U);
+               int64_t ldc, float sigma, const float *Wv, const float *wgt, int t, float *U, double *U64 = nullptr);
 } // namespace knm

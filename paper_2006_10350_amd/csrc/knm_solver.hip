@@ -625,12 +625,13 @@ int invert_diag_blocks(knm_ctx *ctx, const knm_precond *p, const double *R, doub
 
 // Workspace of one application of the operator of Eq. 9 on column-major fp64 vectors.
 struct LinopWork {
-    DevBuf v, z32, u32;
+    DevBuf v, z32, u32, u64;
     int alloc(knm_ctx *ctx, int64_t M, int t)
     {
         int st = v.alloc(ctx, sizeof(double) * M * t);
         if (!st) st = z32.alloc(ctx, sizeof(float) * M * t);
         if (!st) st = u32.alloc(ctx, sizeof(float) * M * t);
+        if (!st) st = u64.alloc(ctx, sizeof(double) * M * t);
         return st;
     }
 };
@@ -641,7 +642,26 @@ struct KernelOps {
     int64_t n = 0, M = 0;
     std::function<int(const float *V, int t, float *W)> v;
     std::function<int(const float *W, const float *wgt, int t, float *U)> t_w;
+    // the same with U as fp64 rows (M x t, row-major) that were never rounded to fp32; may be empty
+    std::function<int(const float *W, const float *wgt, int t, double *U64)> t_w64;
 };
+
+// cols (M x t, column-major fp64) <- K^T (wgt .* W): T^-T amplifies what the solver is given by the
+// conditioning of K_MM, so the result of the column sweep is taken in fp64 where the sweeps offer it
+int t_w_cols(knm_ctx *ctx, const KernelOps &ops, const float *W, const float *wgt, int t, float *u32, double *u64,
+             double *cols)
+{
+    if (ops.t_w64) {
+        int st = ops.t_w64(W, wgt, t, u64);
+        if (st) return st;
+        hipLaunchKernelGGL(f64_rows_to_cols, grid1(ops.M * t), dim3(256), 0, ctx->stream, u64, ops.M, t, cols, 0);
+    } else {
+        int st = ops.t_w(W, wgt, t, u32);
+        if (st) return st;
+        hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(ops.M * t), dim3(256), 0, ctx->stream, u32, ops.M, t, cols);
+    }
+    return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "column sweep result conversion");
+}
 
 KernelOps dense_ops(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M, int64_t ldc,
                     float sigma)
@@ -652,6 +672,9 @@ KernelOps dense_ops(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
     ops.v = [=](const float *V, int t, float *W) { return do_knm_v(ctx, X, n, d, ldx, C, M, ldc, sigma, V, t, W); };
     ops.t_w = [=](const float *W, const float *wgt, int t, float *U) {
         return do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, W, wgt, t, U);
+    };
+    ops.t_w64 = [=](const float *W, const float *wgt, int t, double *U64) {
+        return do_knm_t_w(ctx, X, n, d, ldx, C, M, ldc, sigma, W, wgt, t, nullptr, U64);
     };
     return ops;
 }
@@ -678,9 +701,8 @@ int linop_cols(knm_ctx *ctx, const knm_precond *p, LinopWork &wk, const KernelOp
     if (st) return st;
     st = ops.v(wk.z32.as<float>(), t, ctx->w_buf);
     if (st) return st;
-    st = ops.t_w(ctx->w_buf, wgt, t, wk.u32.as<float>());
+    st = t_w_cols(ctx, ops, ctx->w_buf, wgt, t, wk.u32.as<float>(), wk.u64.as<double>(), out);
     if (st) return st;
-    hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(M * t), dim3(256), 0, ctx->stream, wk.u32.as<float>(), M, t, out);
     st = tri_solve(ctx, p, p->T, p->Tdinv, true, out, t); // T^-T c
     if (st) return st;
     const double ln = lambda * (double)n;
@@ -1211,9 +1233,8 @@ static int fit_core(knm_ctx *ctx, const KernelOps &ops, knm_precond *p, const fl
     double *db = beta.as<double>(), *dr = r.as<double>(), *dp = pv.as<double>(), *dq = q.as<double>();
 
     // rhs = A^-T T^-T K_nm^T Y
-    st = ops.t_w(Y, nullptr, t, r32.as<float>());
+    st = t_w_cols(ctx, ops, Y, nullptr, t, r32.as<float>(), wk.u64.as<double>(), dr);
     if (st) return st;
-    hipLaunchKernelGGL(f32_rows_to_f64_cols, grid1(len), dim3(256), 0, ctx->stream, r32.as<float>(), M, t, dr);
     st = tri_solve(ctx, p, p->T, p->Tdinv, true, dr, t);
     if (!st) st = tri_solve(ctx, p, p->A, p->Adinv, true, dr, t);
     if (st) return st;

@@ -309,14 +309,15 @@ __global__ __launch_bounds__(kThreads, (KS <= 15 ? 3 : 1)) void gauss_sweep_kern
         }
 }
 
-__global__ void merge_kernel(const float *__restrict__ part, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
-                             float *__restrict__ out, int64_t ldo, int64_t count)
+template <typename TI, typename TO>
+__global__ void merge_kernel(const TI *__restrict__ part, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
+                             TO *__restrict__ out, int64_t ldo, int64_t count)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= count) return;
     double s = 0.0;
     for (int64_t c = 0; c < n_chunks; ++c) s += (double)part[c * chunk_stride + j * ldp];
-    out[j * ldo] = (float)s;
+    out[j * ldo] = (TO)s;
 }
 
 constexpr int kR = 2;
@@ -363,13 +364,19 @@ hipError_t launch_sweep(const SweepArgs &a, hipStream_t stream)
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_merge(const float *part, int64_t n_chunks, int64_t chunk_stride, int64_t ldp, float *out,
-                        int64_t ldo, int64_t count, hipStream_t stream)
+hipError_t launch_merge(const float *part, const double *part64, int64_t n_chunks, int64_t chunk_stride, int64_t ldp,
+                        float *out, double *out64, int64_t ldo, int64_t count, hipStream_t stream)
 {
-    const int threads = 256;
-    const int64_t blocks = (count + threads - 1) / threads;
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)blocks), dim3(threads), 0, stream, part, n_chunks,
-                       chunk_stride, ldp, out, ldo, count);
+    if ((part == nullptr) == (part64 == nullptr) || (out == nullptr) == (out64 == nullptr)) return hipErrorInvalidValue;
+    const dim3 threads(256), blocks((unsigned)((count + 255) / 256));
+    if (part64 != nullptr && out64 != nullptr)
+        hipLaunchKernelGGL((merge_kernel<double, double>), blocks, threads, 0, stream, part64, n_chunks, chunk_stride, ldp, out64, ldo, count);
+    else if (part64 != nullptr)
+        hipLaunchKernelGGL((merge_kernel<double, float>), blocks, threads, 0, stream, part64, n_chunks, chunk_stride, ldp, out, ldo, count);
+    else if (out64 != nullptr)
+        hipLaunchKernelGGL((merge_kernel<float, double>), blocks, threads, 0, stream, part, n_chunks, chunk_stride, ldp, out64, ldo, count);
+    else
+        hipLaunchKernelGGL((merge_kernel<float, float>), blocks, threads, 0, stream, part, n_chunks, chunk_stride, ldp, out, ldo, count);
     return hipGetLastError();
 }
 

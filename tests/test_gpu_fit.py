@@ -157,26 +157,31 @@ def test_multi_output_fit(knm):
         assert rel_l2(pred[:, c], po[:, c]) < 1e-3
 
 
-@pytest.mark.parametrize("name,n,M,iters,sigma", [("mid", 60000, 1500, 8, None), ("highdim", 8000, 600, 5, 8.0),
-                                                  ("lowdim", 60000, 1500, 8, None)])
-def test_workload_shaped_fit(knm, name, n, M, iters, sigma):
+@pytest.mark.parametrize("name,n,M,iters,cross_term", [("mid", 60000, 1500, 8, "f16x3"), ("lowdim", 60000, 1500, 8, "f16x3"),
+                                                       ("highdim", 8000, 600, 5, "f16x3"), ("highdim", 8000, 600, 5, "f32")])
+def test_workload_shaped_fit(knm, name, n, M, iters, cross_term):
     """End-to-end fit on reduced copies of the benchmark workloads (their distributions, number of
-    outputs; every tile engine), predictions against the oracle.  The image-like workload runs with
-    sigma = 8 here: at its own sigma = 24 every kernel value lies within 8 % of 1, K_MM is close to
-    a rank-one matrix and fp32 products limit the predictions to 2e-3 (measured, the same with the
-    fp32-MFMA cross term): the single-precision limit the paper discusses, not a property of a kernel."""
+    outputs, length-scale and regulariser; every tile engine), predictions against the oracle.  The
+    jitter on K_MM is not part of the workloads: 1e-7 on both sides.  At the image-like workload's
+    sigma = 24 every kernel value lies within 8 % of 1 and K_MM is close to a rank-one matrix: the
+    case that needs the two-level sums of the K-loop engines and the fp64 hand-over of K^T w to the
+    solver (2e-3 without them)."""
     w = synth.workload(name, n=n, M=M)
-    if sigma is not None:
-        w = w._replace(sigma=sigma) if hasattr(w, "_replace") else __import__("dataclasses").replace(w, sigma=sigma)
     inp = synth.make_inputs(w, device="cpu", n_test=1000)
     X, Y, C, Xt = inp["X"], inp["Y"], inp["C"], inp["Xtest"]
-    lam, jitter = 1e-6, 1e-7
-    alpha, resid = knm.falkon_fit(X.cuda(), Y.cuda(), C.cuda(), w.sigma, lam, iters, jitter, return_resid=True)
+    lam, jitter = w.lam, 1e-7
+    ctx = knm.default_context()
+    ctx.set_cross_term(cross_term)
+    try:
+        alpha, resid = knm.falkon_fit(X.cuda(), Y.cuda(), C.cuda(), w.sigma, lam, iters, jitter, return_resid=True)
+        pred = knm.falkon_predict(Xt.cuda(), C.cuda(), w.sigma, alpha).cpu().numpy()
+    finally:
+        ctx.set_cross_term("f16x3")
     ao, ro = oracle.falkon_fit(X.numpy(), Y.numpy(), C.numpy(), w.sigma, lam, iters, jitter, return_resid=True)
-    pred = knm.falkon_predict(Xt.cuda(), C.cuda(), w.sigma, alpha).cpu().numpy()
     po = oracle.falkon_predict(Xt.numpy(), C.numpy(), w.sigma, ao)
     err = rel_l2(pred, po)
-    print(f"\n  {name}-shaped fit (n={n}, M={M}, d={w.d}, t={w.t}): prediction error {err:.2e}", flush=True)
+    print(f"\n  {name}-shaped fit (n={n}, M={M}, d={w.d}, t={w.t}, sigma={w.sigma}, lambda={lam}, {cross_term}): "
+          f"prediction error {err:.2e}", flush=True)
     assert err < 1e-3
     assert np.all(np.isfinite(resid)) and np.all(np.asarray(resid)[-1] < np.asarray(resid)[0])
 
@@ -196,14 +201,23 @@ def test_all_points_as_centres_reaches_exact_krr(knm):
 
 def test_product_parity_on_a_cg_shaped_vector(knm, capsys):
     """The vectors the product sees inside CG are v = T^-1 A^-1 p: huge dynamic range and sign
-    alternation (T^-1 amplifies by ~ sqrt(cond K_MM)), so K^T K v cancels heavily and fp32 rounding
-    of the entries is amplified.  The error is reported; the assertion is only a sanity bound."""
+    alternation (T^-1 amplifies by ~ sqrt(cond K_MM)), so K v cancels heavily: here
+    kappa = |K|_2 |v| / |K v| is about 8000.  Every fp32 kernel value carries a relative error
+    eps_K of about 3e-7 (half an ulp of an exponent of size 4 to 8 is 2.4e-7 to 4.8e-7 in the
+    kernel value, plus one ulp of the hardware exp2), independent from entry to entry, so the
+    product's relative error is a fraction of kappa eps_K = 2.4e-3 (measured: 0.07 to 0.09 of it;
+    emulating fp32 kernel values on the CPU gives the same figure).  The 1e-4 bar of the product
+    is for vectors without such cancellation; this one is held to 5e-4, and end to end the fit
+    is held to its own bar (test_workload_shaped_fit)."""
     n, M, d, sigma, lam, jitter = 6000, 400, 6, 1.5, 1e-6, 1e-7
     X, C = _rand(n, d, 71), _rand(M, d, 72)
     T, A = oracle.precond(C.numpy(), sigma, lam, jitter)
     p = _rand(M, 1, 73).numpy().astype(np.float64)
     v = oracle.solve_upper(T, oracle.solve_upper(A, p))
     v32 = torch.from_numpy(v.astype(np.float32))
+    K = oracle.kernel_matrix(X.numpy(), C.numpy(), sigma)
+    kappa = np.linalg.norm(K, 2) * np.linalg.norm(v32.numpy()) / np.linalg.norm(K @ v32.numpy().astype(np.float64))
+    ref = oracle.knm_prod(X.numpy(), C.numpy(), sigma, v32.numpy())
     for mode in ("f16x3", "f32"):
         ctx = knm.default_context()
         ctx.set_cross_term(mode)
@@ -211,11 +225,12 @@ def test_product_parity_on_a_cg_shaped_vector(knm, capsys):
             U = knm.knm_prod(X.cuda(), C.cuda(), sigma, v32.cuda()).cpu().numpy()
         finally:
             ctx.set_cross_term("f16x3")
-        err = rel_l2(U, oracle.knm_prod(X.numpy(), C.numpy(), sigma, v32.numpy()))
+        err = rel_l2(U, ref)
         with capsys.disabled():
-            print(f"\n  CG-shaped v ({mode}): max|v|/rms = {np.abs(v).max() / np.sqrt((v ** 2).mean()):.1f}, "
-                  f"|v| = {np.linalg.norm(v):.3e}, rel L2 error of K^T K v = {err:.2e}", flush=True)
-        assert err < 1e-2
+            print(f"\n  CG-shaped v ({mode}): kappa = {kappa:.0f}, |v| = {np.linalg.norm(v):.3e}, "
+                  f"rel L2 error of K^T K v = {err:.2e} = {err / (kappa * 3e-7):.2f} kappa eps_K", flush=True)
+        assert err < 5e-4
+        assert err < 0.25 * kappa * 3e-7
 
 
 def test_fit_rejects_bad_arguments(knm):
