@@ -77,6 +77,21 @@ int knm_prod(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
              const float *C, int64_t M, int64_t ldc, float sigma,
              const float *V, int t, float *W_or_null, float *U);
 
+/* knm_prod for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments and result as knm_prod, except that
+ * W (n x t) must be given.  The call allocates nothing: the chunk partials, the common shift and the
+ * converted operands of the split-fp16 engines live in a static device array of
+ * knm_static_scratch_bytes() bytes (64 MiB) that every GPU the library runs on holds until the process
+ * ends.  Shapes whose sweeps do not fit that array (the packed operands are cut into slabs, so this is
+ * mostly the partials: chunks x M x t floats) are rejected with KNM_UNSUPPORTED and the text of
+ * knm_last_error says so.  All calls on one GPU share the array: calls that overlap on one GPU (other
+ * streams, other contexts, other threads) race; calls on one stream are ordered.  Nothing in the
+ * array needs to start at zero (every word read by a call was written by it first). */
+int knm_prod_static(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
+                    const float *C, int64_t M, int64_t ldc, float sigma,
+                    const float *V, int t, float *W, float *U);
+size_t knm_static_scratch_bytes(void);
+
 /* U[M x t] = K_nm^T diag(dw) K_nm V with dw[n] >= 0: the product inside LinOp of the
  * weighted solver for generalised self-concordant losses (Alg. 2, WeightedFalkon). */
 int knm_prod_weighted(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,

@@ -41,6 +41,8 @@ SIGNATURES = {
     "knm_v": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
     "knm_prod": (_int, [_vp] + _PTS + [_vp, _int, _vp, _vp]),
     "knm_prod_weighted": (_int, [_vp] + _PTS + [_vp, _vp, _int, _vp]),
+    "knm_prod_static": (_int, [_vp] + _PTS + [_vp, _int, _vp, _vp]),
+    "knm_static_scratch_bytes": (ctypes.c_size_t, []),
     "knm_t_y": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
     "precond_build": (_int, [_vp, _vp, _i64, _int, _i64, _f32, _f64, _f64, ctypes.POINTER(_vp),
                              ctypes.POINTER(_i64)]),
@@ -236,6 +238,23 @@ def knm_prod(X, C, sigma: float, V, return_w: bool = False, out: Optional[torch.
         U = U.reshape(M)
         W = W[:, 0] if return_w else None
     return (U, W) if return_w else U
+
+
+def knm_prod_static(X, C, sigma: float, V, W, U, ctx: Optional[Context] = None) -> None:
+    """U = K_nm^T (K_nm V), W = K_nm V into the caller's tensors; the library allocates nothing (its
+    workspace is the static scratch array of knm_static_scratch_bytes() bytes)."""
+    ctx = ctx or default_context()
+    X, n, d, ldx, C, M, ldc = _geom(X, C)
+    V, t, _ = _cols(V, M, "V")
+    for name, T, rows in (("W", W, n), ("U", U, M)):
+        if T.dtype != torch.float32 or not T.is_contiguous() or T.numel() != rows * t or T.device != X.device:
+            raise ValueError(f"{name} must be a contiguous float32 tensor of {rows} x {t} on the inputs' device")
+    ctx.check(load_library().knm_prod_static(ctx._h, X.data_ptr(), n, d, ldx, C.data_ptr(), M, ldc, float(sigma),
+                                             V.data_ptr(), t, W.data_ptr(), U.data_ptr()))
+
+
+def knm_static_scratch_bytes() -> int:
+    return int(load_library().knm_static_scratch_bytes())
 
 
 def knm_prod_weighted(X, C, sigma: float, dw, V, ctx: Optional[Context] = None) -> torch.Tensor:

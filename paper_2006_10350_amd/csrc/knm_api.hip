@@ -39,6 +39,30 @@ int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need)
     return KNM_OK;
 }
 
+// Workspace for callers that cannot allocate (code under HIP graph capture, serving loops,
+// harnesses that forbid hipMalloc): one array per GPU, held from the loading of the library to the
+// end of the process.  Host code never uses this name as an address: knm_create looks up the
+// device's own copy with hipGetSymbolAddress and keeps the pointer in the context.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// One piece of a sweep's workspace: grown on demand in the context's own buffer, or, in a call that
+// must not allocate, carved from the static scratch (KNM_UNSUPPORTED if it does not fit).
+static int acquire(knm_ctx *ctx, float **buf, size_t *cur, size_t need, float **out)
+{
+    if (!ctx->static_mode) {
+        int st = ensure(ctx, buf, cur, need);
+        *out = *buf;
+        return st;
+    }
+    const size_t at = (ctx->static_used + 255) & ~(size_t)255;
+    if (ctx->static_ws == nullptr || at + need > kStaticScratchBytes)
+        return fail(ctx, KNM_UNSUPPORTED, "problem too large for the static scratch of the allocation-free entry point");
+    *out = reinterpret_cast<float *>(ctx->static_ws + at);
+    ctx->static_used = at + need;
+    return KNM_OK;
+}
+
 // K-loop engine for several columns or for d beyond what the register-resident engine of the
 // selected arithmetic holds (44 features for the split-fp16 one, 64 for fp32)
 bool use_gemm_engine(int d, int t, int cross_term, int kind)
@@ -158,22 +182,23 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
     const bool gemm = use_gemm_engine(d, t, ctx->cross_term, ctx->kernel_kind);
     const bool part_is_64 = out64 != nullptr && gemm;
     const bool merged = chunks > 1 || out64 != nullptr; // an fp64 result is always written by the merge pass
+    if (ctx->static_mode) ctx->static_used = 0; // every sweep carves its pieces afresh
     float *part = nullptr;
     if (merged) {
-        int st = ensure(ctx, &ctx->part_buf, &ctx->part_bytes,
-                        (part_is_64 ? sizeof(double) : sizeof(float)) * (size_t)chunks * nF * t);
+        int st = acquire(ctx, &ctx->part_buf, &ctx->part_bytes,
+                         (part_is_64 ? sizeof(double) : sizeof(float)) * (size_t)chunks * nF * t, &part);
         if (st) return st;
-        part = ctx->part_buf;
     }
     // common shift: feature means of (the first rows of) the smaller point set
+    float *mu = nullptr;
     {
-        int st = ensure(ctx, &ctx->mu_buf, &ctx->mu_bytes, sizeof(float) * ((size_t)d + 1)); // + the "shifted" flag
+        int st = acquire(ctx, &ctx->mu_buf, &ctx->mu_bytes, sizeof(float) * ((size_t)d + 1), &mu); // + the "shifted" flag
         if (st) return st;
         const bool from_f = nF <= nS;
         const int64_t rows = from_f ? nF : nS;
         hipLaunchKernelGGL(column_mean_kernel, dim3((unsigned)((d + 31) / 32)), dim3(256), 0, ctx->stream, from_f ? F : S,
-                           rows < 65536 ? rows : 65536, from_f ? ldf : lds, d, ctx->mu_buf);
-        hipLaunchKernelGGL(shift_decide_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->mu_buf, d,
+                           rows < 65536 ? rows : 65536, from_f ? ldf : lds, d, mu);
+        hipLaunchKernelGGL(shift_decide_kernel, dim3(1), dim3(256), 0, ctx->stream, mu, d,
                            1.0f / (2.0f * sigma * sigma));
         if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "column_mean_kernel launch");
     }
@@ -184,7 +209,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.F = F; a.nF = nF; a.ldf = ldf;
         a.S = S; a.nS = nS; a.lds = lds;
         a.d = d;
-        a.mu = ctx->mu_buf;
+        a.mu = mu;
         a.vec = vec + c; a.ldv = t;
         a.t = (t - c < group) ? t - c : group;
         a.wgt = wgt;
@@ -203,22 +228,45 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.sigma = (a.kind == KNM_KERNEL_GAUSSIAN) ? sigma : sigma / (c_kind * sqrtf(2.0f * 1.4426950408889634f));
         const bool f16 = !gemm && ctx->cross_term == KNM_CROSS_F16X3 && d <= f16_max_d();
         hipError_t e;
+        // packed operands of the split-fp16 engines: what the engine would like, or (static scratch)
+        // as many whole slabs as the rest of the scratch holds; the same region serves every column group
+        auto pack_room = [&](size_t *want) -> int {
+            *want = pack_bytes_wanted(nF, d, t, ctx->kernel_kind, ctx->pack_limit, chunks, chunk_len);
+            if (!ctx->static_mode) return KNM_OK;
+            const size_t at = (ctx->static_used + 255) & ~(size_t)255;
+            const size_t room = at < kStaticScratchBytes ? kStaticScratchBytes - at : 0;
+            if (gemm) {
+                const size_t least = gemm_f16_min_pack_bytes(nF, chunks * chunk_len, chunk_len, d);
+                if (*want > room) *want = room;
+                if (*want < least) *want = least; // acquire() then reports that it does not fit
+            } else {
+                const size_t per_chunk = f16_pack_bytes_per_point(d) * (size_t)chunk_len;
+                const size_t fit = room / per_chunk * per_chunk;
+                if (*want > fit) *want = fit > 0 ? fit : per_chunk;
+            }
+            return KNM_OK;
+        };
+        float *pack = nullptr;
+        const size_t mark_used = ctx->static_used;
         if (gemm && ctx->cross_term == KNM_CROSS_F16X3) {
-            const size_t want = pack_bytes_wanted(nF, d, t, ctx->kernel_kind, ctx->pack_limit, chunks, chunk_len);
-            int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
+            size_t want = 0;
+            int st = pack_room(&want);
+            if (!st) st = acquire(ctx, &ctx->pack_buf, &ctx->pack_bytes, want, &pack);
             if (st) return st;
-            e = launch_sweep_gemm_f16(a, ctx->pack_buf, want, ctx->stream);
+            e = launch_sweep_gemm_f16(a, pack, want, ctx->stream);
         } else if (gemm) {
             e = launch_sweep_gemm(a, ctx->stream);
         } else if (f16) {
-            const size_t want = pack_bytes_wanted(nF, d, t, ctx->kernel_kind, ctx->pack_limit, chunks, chunk_len);
-            int st = ensure(ctx, &ctx->pack_buf, &ctx->pack_bytes, want);
+            size_t want = 0;
+            int st = pack_room(&want);
+            if (!st) st = acquire(ctx, &ctx->pack_buf, &ctx->pack_bytes, want, &pack);
             if (st) return st;
-            e = launch_sweep_f16(a, ctx->pack_buf, want, ctx->stream);
+            e = launch_sweep_f16(a, pack, want, ctx->stream);
         } else {
             e = launch_sweep(a, ctx->stream);
         }
         if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "launch_sweep", e);
+        ctx->static_used = mark_used; // the next column group reuses the image region (same stream: ordered)
     }
     if (after_sweep) (void)hipEventRecord(after_sweep, ctx->stream);
     if (merged) {
@@ -277,6 +325,16 @@ int knm_create(knm_ctx **out, int device, void *hip_stream)
     if (!ctx) return KNM_ALLOC;
     ctx->device = device;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
+    {
+        // this device's copy of the static scratch array (the device is current)
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            delete ctx;
+            return KNM_HIP_ERROR;
+        }
+        ctx->static_ws = static_cast<unsigned char *>(ptr);
+    }
     for (int i = 0; i < 5; ++i) {
         if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
             delete ctx;
@@ -405,6 +463,19 @@ int knm_prod(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const 
              float sigma, const float *V, int t, float *W_or_null, float *U)
 {
     return prod_impl(ctx, X, n, d, ldx, C, M, ldc, sigma, nullptr, V, t, W_or_null, U);
+}
+
+size_t knm_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int knm_prod_static(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M, int64_t ldc,
+                    float sigma, const float *V, int t, float *W, float *U)
+{
+    if (ctx && !W) return fail(ctx, KNM_INVALID_ARG, "the allocation-free product needs the caller's W");
+    if (!ctx) return KNM_INVALID_ARG;
+    ctx->static_mode = true;
+    const int st = prod_impl(ctx, X, n, d, ldx, C, M, ldc, sigma, nullptr, V, t, W, U);
+    ctx->static_mode = false;
+    return st;
 }
 
 int knm_prod_weighted(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,

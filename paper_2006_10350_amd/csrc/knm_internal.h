@@ -158,6 +158,11 @@ struct knm_ctx {
     float *pack_buf = nullptr; // packed operand images of the split-fp16 engines
     size_t pack_bytes = 0;
     size_t pack_limit = 0;     // cap on the image workspace chosen by the caller; 0 = engine defaults
+    // this device's copy of the library's static scratch array (address looked up at knm_create), and
+    // the state of a call that draws its workspace from it instead of allocating
+    unsigned char *static_ws = nullptr;
+    bool static_mode = false;
+    size_t static_used = 0;
     int cross_term = KNM_CROSS_F16X3;
     int kernel_kind = KNM_KERNEL_GAUSSIAN;
     // sparse inputs: most frequent features treated densely, at most (0: none)
