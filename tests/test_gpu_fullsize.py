@@ -32,12 +32,22 @@ def kernel_kind(request, knm):
     knm.default_context().set_kernel("gaussian")
 
 
-@pytest.mark.parametrize("name,n_rows,n_cols,kernel_kind",
-                         [("mid", 503, 6, "gaussian"), ("lowdim", 503, 6, "gaussian"), ("highdim", 120, 2, "gaussian"),
-                          ("mid", 503, 6, "laplacian")], indirect=["kernel_kind"])
-def test_full_size_sampled_outputs(knm, name, n_rows, n_cols, kernel_kind):
+@pytest.fixture
+def cross_term(request, knm):
+    """Sets the arithmetic of the cross term on the default context for one test."""
+    mode = getattr(request, "param", "f16x3")
+    knm.default_context().set_cross_term(mode)
+    yield mode
+    knm.default_context().set_cross_term("f16x3")
+
+
+@pytest.mark.parametrize("name,n_rows,n_cols,kernel_kind,cross_term",
+                         [("mid", 503, 6, "gaussian", "f16x3"), ("mid", 503, 6, "gaussian", "f32"),
+                          ("lowdim", 503, 6, "gaussian", "f16x3"), ("highdim", 120, 2, "gaussian", "f16x3"),
+                          ("mid", 503, 6, "laplacian", "f16x3")], indirect=["kernel_kind", "cross_term"])
+def test_full_size_sampled_outputs(knm, name, n_rows, n_cols, kernel_kind, cross_term):
     w = synth.workload(name)
-    print(f"workload {name}: n={w.n} d={w.d} M={w.M} kernel={kernel_kind}", flush=True)
+    print(f"workload {name}: n={w.n} d={w.d} M={w.M} kernel={kernel_kind} cross term={cross_term}", flush=True)
     inp = synth.make_inputs(w, device="cuda", with_targets=True)
     X, C, Y = inp["X"], inp["C"], inp["Y"]
     v = synth.probe_vector(w.M, w.t, "normal", device="cuda")
@@ -111,6 +121,52 @@ def test_more_than_2_pow_31_elements(knm):
     assert rel_l2(Ut[torch.from_numpy(cols).cuda()].cpu().numpy(), Uo) < 1e-4
     Uh = knm.knm_t_y(X[: w.n - tail], C, w.sigma, W[: w.n - tail])
     assert rel_l2((Uh.double() + Ut.double()).cpu().numpy(), U.double().cpu().numpy()) < 1e-5
+    uv = float((U.double() * v.double()).sum())
+    ww = float((W.double() ** 2).sum())
+    assert abs(uv - ww) <= 1e-4 * float(U.double().norm() * v.double().norm())
+
+
+def test_billion_point_workload_sampled_outputs(knm):
+    """The billion-point workload at its own size (n = 1e9, d = 9: 9e9 elements of X, past 2^32;
+    36 GB resident), both sweeps launched over all n rows.  Rows of W = K V at both ends of the array
+    and at random places against the oracle.  For the column sweep the oracle cannot sum 1e9 rows,
+    so the sweep runs on a vector that is W on the last million rows and on scattered single rows
+    (some past element 2^32, some before) and zero elsewhere: its result is a sum over those rows
+    only, which the oracle computes from the gathered rows, while the kernel still indexes all of X."""
+    w = synth.workload("billion")
+    assert w.n * w.d > 2 ** 32
+    inp = synth.make_inputs(w, device="cuda", with_targets=False)
+    X, C = inp["X"], inp["C"]
+    v = synth.probe_vector(w.M, 1, "normal", device="cuda")
+    W = knm.knm_v(X, C, w.sigma, v)
+    torch.cuda.synchronize()
+    print("row sweep done", flush=True)
+    Cn, vn = C.cpu().numpy(), v.cpu().numpy()
+    g = np.random.default_rng(13)
+    first_past = 2 ** 32 // w.d  # first row with an element past 2^32
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, first_past - 1, first_past, first_past + 1], w.n - 1 - np.arange(300),
+                                     g.integers(0, w.n, 200)]))
+    ridx = torch.from_numpy(rows).cuda()
+    Wo = oracle.knm_v(X[ridx].cpu().numpy(), Cn, w.sigma, vn)
+    Wg = W[ridx].cpu().numpy()
+    assert rel_l2(Wg, Wo) < 1e-4
+    assert np.max(np.abs(Wg - Wo)) < 1e-4 * np.max(np.abs(Wo)) + 1e-6
+    print("row samples ok", flush=True)
+
+    tail = 1_000_000
+    single = np.unique(np.concatenate([[0, 1, 4095, first_past - 1, first_past, first_past + 4097],
+                                       g.integers(0, w.n - tail, 2000)]))
+    keep = torch.cat([torch.from_numpy(single).cuda(), torch.arange(w.n - tail, w.n, device="cuda")])
+    Wm = torch.zeros_like(W)
+    Wm[keep] = W[keep]
+    Um = knm.knm_t_y(X, C, w.sigma, Wm)
+    torch.cuda.synchronize()
+    print("column sweep done", flush=True)
+    cols = np.array([0, 31, 32, 4097, w.M - 1])
+    Uo = oracle.knm_t_y(X[keep].cpu().numpy(), Cn[cols], w.sigma, W[keep].cpu().numpy())
+    assert rel_l2(Um[torch.from_numpy(cols).cuda()].cpu().numpy(), Uo) < 1e-4
+    # and the full product's identity v^T K^T K v = |K v|^2 over all 1e9 rows
+    U = knm.knm_t_y(X, C, w.sigma, W)
     uv = float((U.double() * v.double()).sum())
     ww = float((W.double() ** 2).sum())
     assert abs(uv - ww) <= 1e-4 * float(U.double().norm() * v.double().norm())
