@@ -49,19 +49,6 @@ def cpu_baseline(w, X_rows, C, v, budget_entries: float):
     }
 
 
-def measured_traffic_bytes(workload: str):
-    """HBM-side bytes per launch of the tile kernel, from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE and WRITE_SIZE, each scaled by its copy-probe factor); None if not profiled."""
-    try:
-        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
-            t = json.load(f).get(workload)
-        if not t:
-            return None
-        return 1024.0 * (t["fetch_kib_raw"] * t["fetch_scale"] + t["write_kib_raw"] * t["write_scale"])
-    except (OSError, ValueError, KeyError):
-        return None
-
-
 def fit_benchmark(w, args) -> int:
     """falkon_fit end to end (preconditioner, right-hand side, CG iterations) with phase timings."""
     import torch
@@ -185,10 +172,6 @@ def sparse_benchmark(args) -> int:
     torch.cuda.synchronize()
     elapsed = (time.perf_counter() - t0) / args.steps
     nnz_x = int(s["x_indptr"][-1])
-    # algorithmic bytes of the two sweeps: per visited (entry of X, centre) pair and pass one list entry
-    # (8 B) and one accumulator update (4 B read + 4 B written); per entry of X and pass its id, value and
-    # two list pointers (20 B)
-    bytes_per_product = 2 * 2 * (16.0 * pairs + 20.0 * nnz_x)
     print(json.dumps({
         "metric": "G kernel-entries/s in K_nm^T(K_nm v), sparse CSR inputs",
         "value": n * M / elapsed / 1e9, "unit": "G entries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -198,15 +181,131 @@ def sparse_benchmark(args) -> int:
                    "nnz_x": nnz_x, "nnz_c": int(s["c_indptr"][-1]), "feature_skew": args.sparse_skew,
                    "stands_in_for": "YELP-shaped sparse n-gram counts"},
         "pair_updates_per_sweep": pairs, "pair_updates_per_s": 2 * 2 * pairs / elapsed,
-        "roofline": {"bound": "hbm", "kernel": "sparse_sweep_kernel", "achieved": bytes_per_product / elapsed / 1e9,
-                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": bytes_per_product / elapsed / 1e9 / PEAK_HBM_GBS,
-                     "traffic": None,
-                     "note": "bytes of the all-sparse walk (every pair that shares a feature); the most frequent features' "
-                             "pairs are in fact covered by one dense product, the rest by scattered 4-byte atomics bound by "
-                             "L2 atomic latency, far from the HBM roofline"},
+        # the walk is bound by scattered 4-byte L2 atomics on the per-wavefront accumulators; there is no
+        # published peak for those, so the rate is stated without a fraction
+        "roofline": {"bound": "l2-atomics", "kernel": "sparse_sweep_kernel", "achieved": 2 * 2 * pairs / elapsed / 1e9,
+                     "peak": None, "unit": "G pair updates/s", "frac": None, "traffic": None},
         "u_finite": bool(torch.isfinite(U).all()),
     }))
     return 0
+
+
+def counters(workload: str):
+    """Per-launch counters of the tile kernel from the committed rocprofv3 --pmc summaries
+    (profiles/hbm_traffic.json): HBM-side bytes (FETCH_SIZE and WRITE_SIZE, each scaled by its
+    copy-probe factor) and issued matrix-core instructions; None where not profiled."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            t = json.load(f).get(workload)
+    except (OSError, ValueError):
+        t = None
+    if not t:
+        return None, None
+    traffic = None
+    if "fetch_kib_raw" in t:
+        traffic = 1024.0 * (t["fetch_kib_raw"] * t["fetch_scale"] + t["write_kib_raw"] * t["write_scale"])
+    return traffic, t.get("mfma_insts_per_launch")
+
+
+def engine_of(w, cross: str, kernel: str):
+    """Which tile engine the library runs for this shape (same rule as the library): the K-loop engine
+    for t > 1, for the kernels of the distance, or for d beyond the register-resident engine's limit
+    (44 features with the split-fp16 cross term, the default; 64 with fp32 MFMA)."""
+    k_loop = kernel != "gaussian" or w.t > 1 or w.d > (44 if cross == "f16x3" else 64)
+    f16 = cross == "f16x3"
+    name = (("gauss_gemm_f16_kernel" if f16 else "gauss_gemm_kernel") if k_loop
+            else ("gauss_sweep_f16_kernel" if f16 else "gauss_sweep_kernel"))
+    return name, k_loop, f16
+
+
+def product_leg(knm, synth, torch, ctx, w, steps: int, warmup: int, cross: str, kernel: str, inputs=None, probe=None):
+    """Times `steps` full products K_nm^T (K_nm v) on workload w; returns the metrics of the leg."""
+    inp = inputs or synth.make_inputs(w, device="cuda", with_targets=False)
+    X, C = inp["X"], inp["C"]
+    v = synth.probe_vector(w.M, w.t, "normal", device="cuda")
+    U = torch.empty(w.M, w.t, device="cuda", dtype=torch.float32)
+    ctx.set_cross_term(cross)
+    ctx.set_kernel(kernel)
+    for _ in range(warmup):
+        knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
+    torch.cuda.synchronize()
+    ctx.set_timing(True)
+    row_ms, col_ms, merge_ms = [], [], []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
+        tm = ctx.get_timing()  # HIP events on the library's stream; waits for this step
+        row_ms.append(tm["row_sweep_ms"])
+        col_ms.append(tm["col_sweep_ms"])
+        merge_ms.append(tm["merge_ms"])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ctx.set_timing(False)
+
+    s_per_product = elapsed / steps
+    entries = float(w.n) * float(w.M)
+    kernel_name, k_loop, f16 = engine_of(w, cross, kernel)
+    group = 32 if (k_loop and f16) else 16  # columns per launch of the K-loop engines
+    launches = 2 * ((w.t + group - 1) // group if k_loop else 1) * steps
+    avg_launch_ms = (sum(row_ms) + sum(col_ms)) / launches
+    # Algorithmic contraction work of one launch (one sweep): every kernel entry once, 2 d flop each.
+    # Padded or augmented contraction slots, the 2 t reduction flop and the exp are not counted.
+    flop_per_launch = entries * 2.0 * w.d
+    tflops = flop_per_launch / (avg_launch_ms * 1e-3) / 1e12
+    default = kernel == "gaussian"
+    traffic, mfma_insts = counters(w.name + ("" if f16 else "_f32")) if default else (None, None)
+    roofline = {
+        "bound": "mfma",
+        "kernel": kernel_name,
+        # the contraction's own dtype: f16 matrix cores (three split products per feature pair,
+        # fp32 accumulate) in the default mode, fp32 matrix cores otherwise
+        "contraction_dtype": "f16" if f16 else "f32",
+        "achieved": tflops,
+        "peak": PEAK_FP16_MFMA_TFLOPS if f16 else PEAK_FP32_MFMA_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": tflops / (PEAK_FP16_MFMA_TFLOPS if f16 else PEAK_FP32_MFMA_TFLOPS),
+        "traffic": traffic,
+        "avg_launch_ms": avg_launch_ms,
+        "row_sweep_ms": sum(row_ms) / len(row_ms),
+        "col_sweep_ms": sum(col_ms) / len(col_ms),
+        "merge_ms": sum(merge_ms) / len(merge_ms),
+        "flop_per_launch": flop_per_launch,
+        # the same launch priced against the fp32 matrix peak (what the 2 d flop per entry would cost there)
+        "fp32_mfma_equiv_frac": tflops / PEAK_FP32_MFMA_TFLOPS,
+    }
+    if f16:
+        # counting the three split products that fp32-class accuracy costs in that dtype
+        roofline["frac_split_x3"] = 3.0 * roofline["frac"]
+        if mfma_insts:
+            # issued: matrix-core instructions per launch from the committed SQ_INSTS_MFMA count
+            # (32 x 32 x 16 x 2 flop each; includes padding of d and the norm slots)
+            roofline["frac_issued"] = mfma_insts * 32768.0 / (avg_launch_ms * 1e-3) / 1e12 / PEAK_FP16_MFMA_TFLOPS
+        if not k_loop and probe:
+            # The register-resident engine at small d is bound by the vector ALU's exp + FMA per entry
+            # together with the matrix cores they share issue with, not by the matrix cores alone: the
+            # engine's clocks per pair of 32 x 32 tiles against the same instruction mix run from
+            # registers only (measured now, on this device: both pipes, and each pipe alone).
+            hu = 1 if w.d <= 12 else (2 if w.d <= 28 else 3)
+            per_pair = avg_launch_ms * 1e-3 * 2.4e9 / (entries / 2048.0 / (256 * 4))  # per SIMD
+            roofline["alu"] = {
+                "nominal_clk_per_tile_pair": per_pair,
+                "probe_mix_clk_per_tile_pair": {k: probe[f"mix{hu}_{k}_clk"] for k in ("both", "valu", "mfma")},
+                "frac_of_probe_mix": probe[f"mix{hu}_both_clk"] / per_pair,
+            }
+    return {
+        "workload": w.name, "n": w.n, "d": w.d, "M": w.M, "t": w.t, "sigma": w.sigma, "kernel": kernel,
+        "steps": steps, "warmup": warmup,
+        "s_per_product": s_per_product,
+        "g_entries_per_s": entries / s_per_product / 1e9,
+        "g_entry_evaluations_per_s": 2.0 * entries / s_per_product / 1e9,
+        "cross_term": "f16x3" if f16 else "f32",
+        # fractions of the fp32 matrix peak: the method's two evaluations of every entry, and one
+        "fp32_mfma_frac_two_sweeps": 2.0 * entries * 2.0 * w.d / s_per_product / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+        "fp32_mfma_frac_single_eval": entries * 2.0 * w.d / s_per_product / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+        "roofline": roofline,
+        "_tensors": (X, C, v, U),
+    }
 
 
 def main() -> int:
@@ -220,8 +319,7 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=None, help="rows of the oracle's timing sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cross", default="f16x3", choices=["f32", "f16x3"],
-                    help="arithmetic of the cross term (d <= 44, t = 1): three split-fp16 MFMA products (library "
-                         "default) or fp32 MFMA")
+                    help="arithmetic of the cross term: three split-fp16 MFMA products (library default) or fp32 MFMA")
     ap.add_argument("--kernel", default="gaussian", choices=["gaussian", "laplacian", "matern32", "matern52"],
                     help="kernel function of the product (the headline metric is quoted on the Gaussian one)")
     ap.add_argument("--fit", action="store_true",
@@ -232,9 +330,14 @@ def main() -> int:
                     help="--fit: squared loss (falkon_fit) or logistic loss (logfalkon_fit, labels = sign of the "
                          "targets about their median)")
     ap.add_argument("--newton-steps", type=int, default=4, help="Newton steps for --fit --loss logistic")
-    ap.add_argument("--jitter", type=float, default=1e-8, help="diagonal jitter on K_MM for --fit")
+    ap.add_argument("--jitter", type=float, default=1e-8, help="diagonal jitter on K_MM for the fits")
     ap.add_argument("--no-fp32-leg", action="store_true",
                     help="skip the extra (untimed-region) product in the fp32-MFMA cross-term mode")
+    ap.add_argument("--no-cg-leg", action="store_true",
+                    help="skip the short falkon_fit (preconditioner + 4 CG iterations) that measures s per CG iteration")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short product legs on the other workloads (lowdim, highdim, billion)")
+    ap.add_argument("--no-probe", action="store_true", help="skip the instruction-rate probe")
     ap.add_argument("--sparse", action="store_true",
                     help="instead of a dense workload, time knm_prod_csr on synthetic sparse rows (n = 1.5M, "
                          "d = 6.5e7, M = 50k, about 100 stored features per row)")
@@ -263,14 +366,10 @@ def main() -> int:
     w = synth.workload(args.workload, n=args.n, M=args.M)
     if args.fit:
         return fit_benchmark(w, args)
-    inp = synth.make_inputs(w, device="cuda", with_targets=False)
-    X, C = inp["X"], inp["C"]
-    v = synth.probe_vector(w.M, w.t, "normal", device="cuda")
-    U = torch.empty(w.M, w.t, device="cuda", dtype=torch.float32)
     ctx = knm.default_context()
-    ctx.set_cross_term(args.cross)
-    ctx.set_kernel(args.kernel)
-    torch.cuda.synchronize()
+    full_size = args.n is None and args.M is None
+    headline = full_size and args.workload == "mid" and args.kernel == "gaussian" and args.cross == "f16x3"
+    probe = None if args.no_probe else ctx.probe_rates()
     if args.copy_probe_mib > 0:
         src = torch.ones(args.copy_probe_mib * (1 << 18), device="cuda", dtype=torch.float32)
         dst = torch.empty_like(src)
@@ -278,79 +377,15 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
-    torch.cuda.synchronize()
-
-    ctx.set_timing(True)
-    row_ms, col_ms, merge_ms = [], [], []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
-        tm = ctx.get_timing()  # HIP events on the library's stream; waits for this step
-        row_ms.append(tm["row_sweep_ms"])
-        col_ms.append(tm["col_sweep_ms"])
-        merge_ms.append(tm["merge_ms"])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ctx.set_timing(False)
-
-    ms_per_step = 1e3 * elapsed / args.steps
-    entries = float(w.n) * float(w.M)
-    value = entries / (elapsed / args.steps) / 1e9
-
-    # Which tile engine ran (same rule as the library): the K-loop engine for t > 1 (up to 16 columns
-    # per launch) or d beyond the register-resident engine's limit (44 features with the split-fp16
-    # cross term, the default; 64 with fp32 MFMA); otherwise the register-resident engine.  Two sweeps
-    # per step.
-    # The kernels of the distance (Laplacian, Matern) always run on the K-loop engine.
-    k_loop = args.kernel != "gaussian" or w.t > 1 or w.d > (44 if args.cross == "f16x3" else 64)
-    f16 = (not k_loop) and args.cross == "f16x3" and w.d <= 44
-    k_loop_f16 = k_loop and args.cross == "f16x3"
-    kernel_name = (("gauss_gemm_f16_kernel" if k_loop_f16 else "gauss_gemm_kernel") if k_loop
-                   else ("gauss_sweep_f16_kernel" if f16 else "gauss_sweep_kernel"))
-    launches = 2 * ((w.t + 15) // 16) * args.steps
-    avg_launch_ms = (sum(row_ms) + sum(col_ms)) / launches
-    # algorithmic contraction work: one evaluation of every entry, 2 d flop each
-    flop_per_launch = entries * 2.0 * w.d
-    if f16:
-        # Bound by the vector ALU, not the matrix cores: per entry one v_exp_f32 (half rate: two issue
-        # slots) and one FMA (one slot) = 3 lane-slots = 6 flop-equivalents at 2 flop per slot, against
-        # the un-packed fp32 vector peak 256 CU x 64 lanes x 2 flop x 2.4 GHz = 78.6 TFLOP/s.
-        alu_per_launch = entries * 6.0
-        achieved = alu_per_launch / (avg_launch_ms * 1e-3) / 1e12
-        bound, peak, work = "alu", PEAK_FP32_VALU_TFLOPS, alu_per_launch
-    elif k_loop_f16:
-        # Dense contraction on the f16 matrix cores: the split-fp16 cross term is three f16 products per
-        # feature pair (fh.xh + fh.xl + fl.xh), 6 d flop per entry, against the dense fp16 MFMA peak.
-        f16_flop = 3.0 * flop_per_launch
-        achieved = f16_flop / (avg_launch_ms * 1e-3) / 1e12
-        bound, peak, work = "mfma", PEAK_FP16_MFMA_TFLOPS, f16_flop
-    else:
-        achieved = flop_per_launch / (avg_launch_ms * 1e-3) / 1e12
-        bound, peak, work = "mfma", PEAK_FP32_MFMA_TFLOPS, flop_per_launch
-    roofline = {
-        "bound": bound,
-        "kernel": kernel_name,
-        "achieved": achieved,
-        "peak": peak,
-        "unit": "TFLOP/s",
-        "frac": achieved / peak,
-        "traffic": measured_traffic_bytes(w.name + ("" if f16 or k_loop_f16 else "_f32"))
-        if (args.n is None and args.M is None and args.kernel == "gaussian") else None,
-        "avg_launch_ms": avg_launch_ms,
-        "row_sweep_ms": sum(row_ms) / len(row_ms),
-        "col_sweep_ms": sum(col_ms) / len(col_ms),
-        "merge_ms": sum(merge_ms) / len(merge_ms),
-        "work_per_launch": work,
-        "contraction_flop_per_launch": flop_per_launch,
-        # the same launch priced as if its 2 d flop per entry had run on fp32 MFMA
-        "fp32_mfma_equiv_frac": flop_per_launch / (avg_launch_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
-    }
+    inp = synth.make_inputs(w, device="cuda", with_targets=headline and not args.no_cg_leg)
+    leg = product_leg(knm, synth, torch, ctx, w, args.steps, args.warmup, args.cross, args.kernel, inputs=inp, probe=probe)
+    X, C, v, U = leg.pop("_tensors")
+    if not full_size:
+        leg["roofline"]["traffic"] = None
+    f16 = leg["cross_term"] == "f16x3"
 
     fp32_mode = None
-    if (f16 or k_loop_f16) and not args.no_fp32_leg:
+    if f16 and not args.no_fp32_leg:
         # the fp32-MFMA cross-term mode on the same inputs, outside the timed region
         ctx.set_cross_term("f32")
         knm.knm_prod(X, C, w.sigma, v, out=U, ctx=ctx)
@@ -359,32 +394,57 @@ def main() -> int:
         tm = ctx.get_timing()
         ctx.set_timing(False)
         ctx.set_cross_term(args.cross)
-        l_ms = 0.5 * (tm["row_sweep_ms"] + tm["col_sweep_ms"])
-        fp32_mode = {"kernel": "gauss_gemm_kernel" if k_loop else "gauss_sweep_kernel", "ms_per_product": tm["total_ms"], "avg_launch_ms": l_ms,
-                     "frac_of_fp32_mfma_peak": flop_per_launch / (l_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
+        launches = 2 * ((w.t + 15) // 16 if engine_of(w, "f32", args.kernel)[1] else 1)
+        l_ms = (tm["row_sweep_ms"] + tm["col_sweep_ms"]) / launches
+        fp32_mode = {"kernel": engine_of(w, "f32", args.kernel)[0], "ms_per_product": tm["total_ms"], "avg_launch_ms": l_ms,
+                     "frac_of_fp32_mfma_peak": leg["roofline"]["flop_per_launch"] / (l_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
 
     out = {
-        "metric": "G kernel-entries/s in K_nm^T(K_nm v)",
-        "value": value,
+        "metric": "G kernel-entries/s in K_nm^T(K_nm v) + % fp32 MFMA peak; s per CG iteration",
+        "value": leg["g_entries_per_s"],
         "unit": "G entries/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": 1e3 * leg["s_per_product"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        # fp32 inputs, outputs and accumulation throughout; the contraction over d runs as three
+        # split-fp16 products on the f16 matrix cores (library default) or on the fp32 matrix cores
+        "dtype": "f32 data, f16x3 cross term" if f16 else "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "d": w.d, "M": w.M, "t": w.t, "sigma": w.sigma,
                    "kernel": args.kernel, "stands_in_for": w.stands_in_for},
-        "s_per_product": ms_per_step / 1e3,
-        "mfma_frac_two_sweeps": 2.0 * entries * 2.0 * w.d / (elapsed / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
-        "cross_term": "f16x3" if (f16 or k_loop_f16) else "f32",
-        "roofline": roofline,
+        "s_per_product": leg["s_per_product"],
+        "g_entry_evaluations_per_s": leg["g_entry_evaluations_per_s"],
+        "fp32_mfma_frac_two_sweeps": leg["fp32_mfma_frac_two_sweeps"],
+        "fp32_mfma_frac_single_eval": leg["fp32_mfma_frac_single_eval"],
+        "cross_term": leg["cross_term"],
+        "roofline": leg["roofline"],
     }
     if fp32_mode is not None:
         out["fp32_mfma_mode"] = fp32_mode
+    if probe is not None:
+        out["probe"] = probe
+
+    if headline and not args.no_cg_leg:
+        # The third part of the metric: the preconditioner is built (outside any timed product), then
+        # a few iterations of preconditioned CG run inside falkon_fit; s per CG iteration = product +
+        # 4 fp64 triangular solves + vector updates, host clock around iterations that each end with a
+        # synchronising dot product.
+        iters = 4
+        torch.cuda.synchronize()
+        alpha, resid = knm.falkon_fit(X, inp["Y"], C, w.sigma, w.lam, iters, args.jitter, return_resid=True, ctx=ctx)
+        torch.cuda.synchronize()
+        ft = ctx.get_fit_timing()
+        out["s_per_cg_iter"] = ft["iterations_s"] / iters
+        out["precond_s"] = ft["precond_s"]
+        out["cg_leg"] = {"iters": iters, "rhs_s": ft["rhs_s"], "iterations_s": ft["iterations_s"], "lambda": w.lam,
+                         "jitter": args.jitter, "alpha_finite": bool(torch.isfinite(alpha).all()),
+                         "residual_first_last": [float(resid.reshape(iters + 1, -1)[0].max()),
+                                                 float(resid.reshape(iters + 1, -1)[-1].max())]}
+        del alpha
 
     if not args.no_cpu:
         # bounded sample: about 10-30 s of oracle work on the host cores
@@ -396,6 +456,19 @@ def main() -> int:
 
         with oracle.kernel(args.kernel):
             out["cpu_baseline"] = cpu_baseline(w, X[idx], C, v, 0.0)
+
+    if headline and not args.no_others:
+        # Short legs on the other workloads (not part of `value`): one line each with the same fields.
+        del X, C, v, U, inp
+        torch.cuda.empty_cache()
+        others = {}
+        for name, steps, warmup in (("lowdim", 5, 1), ("highdim", 3, 1), ("billion", 1, 0)):
+            wo = synth.workload(name)
+            lo = product_leg(knm, synth, torch, ctx, wo, steps, warmup, args.cross, args.kernel, probe=probe)
+            lo.pop("_tensors")
+            others[name] = lo
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
     ctx.set_kernel("gaussian")
     print(json.dumps(out))
     return 0

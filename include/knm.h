@@ -319,6 +319,29 @@ int knm_set_pack_limit(knm_ctx *ctx, size_t bytes);
 int knm_set_timing(knm_ctx *ctx, int enabled);
 int knm_get_timing(knm_ctx *ctx, float *ms);
 
+/* Measurement aid for benchmarks (not part of the method): sustained rates of the instructions the
+ * tile engines are made of, measured on the context's device with register-resident loops at the
+ * engines' occupancy (2 wavefronts per SIMD, all compute units), so that a roofline can be stated
+ * against what the chip sustains as well as against its nominal peaks.  Writes KNM_PROBE_COUNT
+ * doubles to the HOST array rates_host (count = its length); allocates two small device buffers,
+ * takes about 0.5 s, and synchronises the stream. */
+typedef enum {
+    KNM_PROBE_MFMA_F32_TFLOPS = 0,        /* v_mfma_f32_32x32x2_f32, 4 independent chains               */
+    KNM_PROBE_MFMA_F16_CONST_TFLOPS = 1,  /* v_mfma_f32_32x32x16_f16 on constant operands               */
+    KNM_PROBE_MFMA_F16_RANDOM_TFLOPS = 2, /* the same on random operands (data-dependent power limit)   */
+    KNM_PROBE_EXP_TOPS = 3,               /* v_exp_f32 back to back, 1e12 lane results per second       */
+    KNM_PROBE_FMA_TOPS = 4,               /* v_fmac_f32, 1e12 lane results per second                   */
+    /* One pair of 32 x 32 tiles of the split-fp16 register-resident engine (per wavefront 6 HU f16
+     * MFMAs + 32 exp + 32 FMA in the engine's order; HU = 1, 2, 3 for d <= 12, 28, 44), random
+     * operands, in nominal 2.4 GHz clocks per SIMD and tile pair: both pipes, the vector-ALU
+     * instructions alone, the matrix-core instructions alone. */
+    KNM_PROBE_MIX1_BOTH_CLK = 5, KNM_PROBE_MIX1_VALU_CLK = 6, KNM_PROBE_MIX1_MFMA_CLK = 7,
+    KNM_PROBE_MIX2_BOTH_CLK = 8, KNM_PROBE_MIX2_VALU_CLK = 9, KNM_PROBE_MIX2_MFMA_CLK = 10,
+    KNM_PROBE_MIX3_BOTH_CLK = 11, KNM_PROBE_MIX3_VALU_CLK = 12, KNM_PROBE_MIX3_MFMA_CLK = 13,
+    KNM_PROBE_COUNT = 14
+} knm_probe_rate;
+int knm_probe_rates(knm_ctx *ctx, double *rates_host, int count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -75,6 +75,7 @@ SIGNATURES = {
     "knm_workspace_held": (ctypes.c_size_t, [_vp]),
     "knm_set_pack_limit": (_int, [_vp, ctypes.c_size_t]),
     "knm_set_timing": (_int, [_vp, _int]),
+    "knm_probe_rates": (_int, [_vp, ctypes.POINTER(_f64), _int]),
     "knm_get_timing": (_int, [_vp, ctypes.POINTER(_f32)]),
 }
 
@@ -166,6 +167,14 @@ class Context:
         """'gaussian' (default), 'laplacian', 'matern32' or 'matern52' (dense entry points only)."""
         code = {"gaussian": 0, "laplacian": 1, "matern32": 2, "matern52": 3}[kind] if isinstance(kind, str) else int(kind)
         self.check(load_library().knm_set_kernel(self._h, code))
+
+    def probe_rates(self) -> dict:
+        """Sustained instruction rates of this device (knm_probe_rates)."""
+        names = ("mfma_f32_tflops", "mfma_f16_const_tflops", "mfma_f16_random_tflops", "exp_tops", "fma_tops") + tuple(
+            f"mix{hu}_{what}_clk" for hu in (1, 2, 3) for what in ("both", "valu", "mfma"))
+        buf = (_f64 * len(names))()
+        self.check(load_library().knm_probe_rates(self._h, buf, len(names)))
+        return {k: float(v) for k, v in zip(names, buf)}
 
     def workspace_held(self) -> int:
         """Device bytes of workspace this context holds now."""

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libknm.so")
-SOURCES = ["knm_tile.hip", "knm_tile_f16.hip", "knm_gemm.hip", "knm_gemm_f16.hip", "knm_api.hip", "knm_solver.hip", "knm_dsyrk.hip", "knm_sparse.hip"]
+SOURCES = ["knm_tile.hip", "knm_tile_f16.hip", "knm_gemm.hip", "knm_gemm_f16.hip", "knm_api.hip", "knm_solver.hip", "knm_dsyrk.hip", "knm_sparse.hip", "knm_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
