@@ -272,6 +272,7 @@ int falkon_predict(knm_ctx *ctx, const float *Xtest, int64_t ntest, int d, int64
  *                   (fp32 MFMA and the exp/FMA work share the vector ALU's issue). */
 typedef enum { KNM_CROSS_F32 = 0, KNM_CROSS_F16X3 = 1 } knm_cross_term;
 int knm_set_cross_term(knm_ctx *ctx, int mode);
+int knm_get_cross_term(const knm_ctx *ctx); /* the mode now selected, or KNM_INVALID_ARG */
 
 /* Kernel function of the dense entry points (further kernel families on the same engines; the
  * paper's experiments use the Gaussian kernel throughout), with r = |x - c|:
@@ -310,6 +311,20 @@ int knm_set_sparse_head_limit(knm_ctx *ctx, int max_features);
  * workspace never shrinks below what one slab needs (one stream chunk, plus the whole smaller
  * operand for the K-loop engine). */
 int knm_set_pack_limit(knm_ctx *ctx, size_t bytes);
+
+/* Range check of the split-fp16 cross term (KNM_CROSS_F16X3, the default).  Its operands hold scaled
+ * features z = (x - shift) sqrt(log2 e) / sigma up to |z| = 65000 and norm terms |z|^2 / 2 below 2^21 (a
+ * point about 1700 sigma from the bulk of the data); beyond that, and for features that are not finite,
+ * the conversion clamps, and the kernel values of such a point are wrong wherever they are not zero
+ * anyway.  Every clamped conversion of a point is counted on the device.  knm_range_exceeded waits for
+ * the stream, writes the count since the last reset to the HOST pointer (several sweeps may convert
+ * the same point, so only zero or non-zero is meaningful: 0 means no operand was clamped), and
+ * clears it if reset != 0.  The product entry points do not synchronise and therefore cannot report
+ * it themselves: check here, and repeat with knm_set_cross_term(KNM_CROSS_F32), which clamps nothing
+ * and lets NaNs through (its exponent still carries about 1e-7 of the norm terms as rounding error, so
+ * pairs of close points that far out are inaccurate in either mode).  falkon_fit, falkon_fit_csr and the logistic fits check after their first sweep and run the
+ * whole fit with the fp32-MFMA cross term if anything was clamped. */
+int knm_range_exceeded(knm_ctx *ctx, int64_t *count_host, int reset);
 
 /* Timing aid for benchmarks: when enabled, knm_v / knm_prod / knm_t_y bracket their
  * kernels with HIP events on the context's stream.  knm_get_timing synchronises the

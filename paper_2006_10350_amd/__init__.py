@@ -70,11 +70,13 @@ SIGNATURES = {
     "knm_get_fit_timing": (_int, [_vp, ctypes.POINTER(_f64)]),
     "falkon_predict": (_int, [_vp] + _PTS + [_vp, _int, _vp]),
     "knm_set_cross_term": (_int, [_vp, _int]),
+    "knm_get_cross_term": (_int, [_vp]),
     "knm_set_kernel": (_int, [_vp, _int]),
     "knm_set_sparse_head_limit": (_int, [_vp, _int]),
     "knm_workspace_held": (ctypes.c_size_t, [_vp]),
     "knm_set_pack_limit": (_int, [_vp, ctypes.c_size_t]),
     "knm_set_timing": (_int, [_vp, _int]),
+    "knm_range_exceeded": (_int, [_vp, ctypes.POINTER(_i64), _int]),
     "knm_probe_rates": (_int, [_vp, ctypes.POINTER(_f64), _int]),
     "knm_get_timing": (_int, [_vp, ctypes.POINTER(_f32)]),
 }
@@ -163,6 +165,10 @@ class Context:
         code = {"f32": 0, "f16x3": 1}[mode] if isinstance(mode, str) else int(mode)
         self.check(load_library().knm_set_cross_term(self._h, code))
 
+    @property
+    def cross_term(self) -> str:
+        return {0: "f32", 1: "f16x3"}[load_library().knm_get_cross_term(self._h)]
+
     def set_kernel(self, kind):
         """'gaussian' (default), 'laplacian', 'matern32' or 'matern52' (dense entry points only)."""
         code = {"gaussian": 0, "laplacian": 1, "matern32": 2, "matern52": 3}[kind] if isinstance(kind, str) else int(kind)
@@ -175,6 +181,12 @@ class Context:
         buf = (_f64 * len(names))()
         self.check(load_library().knm_probe_rates(self._h, buf, len(names)))
         return {k: float(v) for k, v in zip(names, buf)}
+
+    def range_exceeded(self, reset: bool = True) -> int:
+        """Operand conversions the split-fp16 cross term had to clamp since the last reset (waits for the stream)."""
+        c = _i64(0)
+        self.check(load_library().knm_range_exceeded(self._h, ctypes.byref(c), 1 if reset else 0))
+        return int(c.value)
 
     def workspace_held(self) -> int:
         """Device bytes of workspace this context holds now."""

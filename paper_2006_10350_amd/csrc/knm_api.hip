@@ -210,6 +210,7 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         a.S = S; a.nS = nS; a.lds = lds;
         a.d = d;
         a.mu = mu;
+        a.range_count = ctx->range_count;
         a.vec = vec + c; a.ldv = t;
         a.t = (t - c < group) ? t - c : group;
         a.wgt = wgt;
@@ -337,9 +338,21 @@ int knm_create(knm_ctx **out, int device, void *hip_stream)
     }
     for (int i = 0; i < 5; ++i) {
         if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
-            delete ctx;
+            (void)knm_destroy(ctx);
             return KNM_HIP_ERROR;
         }
+    }
+    {
+        // the word the split-fp16 engines count clamped operands in (allocated here so that the
+        // products themselves never allocate for it)
+        void *w = nullptr;
+        if (hipMalloc(&w, 256) != hipSuccess || hipMemset(w, 0, 256) != hipSuccess) {
+            (void)hipGetLastError();
+            if (w) (void)hipFree(w);
+            (void)knm_destroy(ctx);
+            return KNM_ALLOC;
+        }
+        ctx->range_count = static_cast<unsigned int *>(w);
     }
     *out = ctx;
     return KNM_OK;
@@ -353,6 +366,7 @@ int knm_destroy(knm_ctx *ctx)
     if (ctx->part_buf) (void)hipFree(ctx->part_buf);
     if (ctx->pack_buf) (void)hipFree(ctx->pack_buf);
     if (ctx->mu_buf) (void)hipFree(ctx->mu_buf);
+    if (ctx->range_count) (void)hipFree(ctx->range_count);
     for (int i = 0; i < 5; ++i)
         if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     extern void knm_solver_release(knm_ctx *);
@@ -500,6 +514,20 @@ int knm_t_y(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const f
     return KNM_OK;
 }
 
+int knm_range_exceeded(knm_ctx *ctx, int64_t *count_host, int reset)
+{
+    if (!ctx) return KNM_INVALID_ARG;
+    if (!count_host) return fail(ctx, KNM_INVALID_ARG, "null count");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
+    unsigned int c = 0;
+    hipError_t e = hipMemcpyAsync(&c, ctx->range_count, sizeof(c), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess && reset) e = hipMemsetAsync(ctx->range_count, 0, sizeof(c), ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "knm_range_exceeded", e);
+    *count_host = (int64_t)c;
+    return KNM_OK;
+}
+
 int knm_set_cross_term(knm_ctx *ctx, int mode)
 {
     if (!ctx) return KNM_INVALID_ARG;
@@ -507,6 +535,8 @@ int knm_set_cross_term(knm_ctx *ctx, int mode)
     ctx->cross_term = mode;
     return KNM_OK;
 }
+
+int knm_get_cross_term(const knm_ctx *ctx) { return ctx ? ctx->cross_term : KNM_INVALID_ARG; }
 
 int knm_set_kernel(knm_ctx *ctx, int kind)
 {

@@ -64,6 +64,8 @@ constexpr int kLoads = kBlocks * kUnits / kThreads; // units copied per thread a
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kPScale = 16384.0f; // matrix-core reduction: kernel values are split into fp16 halves after this scale
 constexpr float kC1 = 1024.0f, kC2 = 0.5f, kC3 = 0.000244140625f, kC4 = 1.1920928955078125e-07f; // 2^10 2^-1 2^-12 2^-23
+constexpr float kHalfMax = 65000.0f;   // scaled features are clamped to +-this before the split
+constexpr float kNormMax = 2097151.0f; // norm terms are clamped to this (four digits of 11 bits)
 
 static_assert(kLoads * kThreads == kBlocks * kUnits, "staging must divide evenly");
 
@@ -72,8 +74,8 @@ static_assert(kLoads * kThreads == kBlocks * kUnits, "staging must divide evenly
 __device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 &lo)
 {
     f32x2 z;
-    z[0] = fminf(fmaxf(z0, -65000.0f), 65000.0f);
-    z[1] = fminf(fmaxf(z1, -65000.0f), 65000.0f);
+    z[0] = fminf(fmaxf(z0, -kHalfMax), kHalfMax);
+    z[1] = fminf(fmaxf(z1, -kHalfMax), kHalfMax);
     hi = __builtin_convertvector(z, f16x2);
     f32x2 rem;
     rem[0] = z[0] - (float)hi[0];
@@ -84,7 +86,7 @@ __device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 
 // -n as four fixed-point digits; n >= 0
 __device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
 {
-    n = fminf(n, 2097151.0f);
+    n = fminf(n, kNormMax);
     const float q1 = floorf(n * (1.0f / 1024.0f));
     float r = fmaf(-q1, 1024.0f, n);
     const float q2 = floorf(r * 2.0f);
@@ -101,7 +103,8 @@ __device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
 template <int VW>
 __global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__restrict__ P, int64_t nP, int64_t ld,
                                                                const float *__restrict__ mu, int d, float sigma,
-                                                               int64_t row0, int n_kc, f16x8 *__restrict__ img)
+                                                               int64_t row0, int n_kc, f16x8 *__restrict__ img,
+                                                               unsigned int *__restrict__ range_count)
 {
     const int tid = threadIdx.x;
     const int u = tid & 7;
@@ -114,6 +117,7 @@ __global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__re
     f16x8 *blk = img + (int64_t)blockIdx.x * (n_kc + 1) * kUnits;
 
     float nrm = 0.0f;
+    bool clamped = false;
     for (int g = 0; 4 * g < n_kc; ++g) {
         const int kc = 4 * g + (u >> 1);
         const int f0 = kChunk * kc + 8 * h;
@@ -141,6 +145,7 @@ __global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__re
             const float z0 = gamma * z[e], z1 = gamma * z[e + 1];
             nrm = fmaf(z0, z0, nrm);
             nrm = fmaf(z1, z1, nrm);
+            clamped |= !(fabsf(z0) <= kHalfMax) || !(fabsf(z1) <= kHalfMax); // also true for a NaN
             f16x2 ph, pl;
             split_pair(z0, z1, ph, pl);
             hi[e] = (_Float16)ph[0]; hi[e + 1] = (_Float16)ph[1];
@@ -155,6 +160,10 @@ __global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__re
     nrm += __shfl_xor(nrm, 1);
     nrm += __shfl_xor(nrm, 2);
     nrm += __shfl_xor(nrm, 4);
+    clamped |= !(0.5f * nrm <= kNormMax);
+    const unsigned long long any = __builtin_amdgcn_ballot_w64(clamped);
+    // the 8 threads of a point are 8 consecutive lanes: one count per clamped point (rare)
+    if (valid && u == 0 && ((any >> ((threadIdx.x & 63) & ~7)) & 0xffull) != 0) atomicAdd(range_count, 1u);
     f16x8 *c = blk + (int64_t)n_kc * kUnits;
     if (u == 0) {
         _Float16 q[4];
@@ -658,14 +667,14 @@ __global__ void col_absmax_kernel(const float *__restrict__ vec, int64_t ldv, co
 }
 
 hipError_t pack_points(const float *P, int64_t nP, int64_t ld, const float *mu, int d, float sigma, int64_t row0,
-                       int64_t rows, int n_kc, f16x8 *img, hipStream_t stream)
+                       int64_t rows, int n_kc, f16x8 *img, unsigned int *range_count, hipStream_t stream)
 {
     const dim3 grid((unsigned)(rows / 32));
     const bool a16 = (d % 4 == 0) && (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(P) & 15) == 0);
     if (a16)
-        hipLaunchKernelGGL((pack_points_kernel<4>), grid, dim3(kThreads), 0, stream, P, nP, ld, mu, d, sigma, row0, n_kc, img);
+        hipLaunchKernelGGL((pack_points_kernel<4>), grid, dim3(kThreads), 0, stream, P, nP, ld, mu, d, sigma, row0, n_kc, img, range_count);
     else
-        hipLaunchKernelGGL((pack_points_kernel<1>), grid, dim3(kThreads), 0, stream, P, nP, ld, mu, d, sigma, row0, n_kc, img);
+        hipLaunchKernelGGL((pack_points_kernel<1>), grid, dim3(kThreads), 0, stream, P, nP, ld, mu, d, sigma, row0, n_kc, img, range_count);
     return hipGetLastError();
 }
 
@@ -758,12 +767,12 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
 
     for (int64_t f0 = 0; f0 < nFp; f0 += f_slab) {
         const int64_t f_rows = (nFp - f0 < f_slab) ? nFp - f0 : f_slab;
-        hipError_t e = pack_points(a.F, a.nF, a.ldf, a.mu, a.d, a.sigma, f0, f_rows, n_kc, Fimg, stream);
+        hipError_t e = pack_points(a.F, a.nF, a.ldf, a.mu, a.d, a.sigma, f0, f_rows, n_kc, Fimg, a.range_count, stream);
         if (e != hipSuccess) return e;
         for (int64_t c0 = 0; c0 < a.n_chunks; c0 += s_slab) {
             const int64_t nc = (a.n_chunks - c0 < s_slab) ? a.n_chunks - c0 : s_slab;
             if (f0 == 0 || s_slab < a.n_chunks) { // a whole stream image is built once
-                e = pack_points(a.S, a.nS, a.lds, a.mu, a.d, a.sigma, c0 * a.chunk_len, nc * a.chunk_len, n_kc, Simg, stream);
+                e = pack_points(a.S, a.nS, a.lds, a.mu, a.d, a.sigma, c0 * a.chunk_len, nc * a.chunk_len, n_kc, Simg, a.range_count, stream);
                 if (e != hipSuccess) return e;
             }
             const int64_t fb = f_rows / kFixed;

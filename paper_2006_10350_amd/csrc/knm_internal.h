@@ -40,6 +40,10 @@ struct SweepArgs {
     int64_t ldo, chunk_stride;
     int64_t chunk_len; // stream points per chunk (multiple of the stage size)
     int64_t n_chunks;
+    // split-fp16 engines: incremented once per converted point whose scaled features or norm term lie
+    // outside what the fp16 operands represent (|z| > 65000, |z|^2 / 2 >= 2^21, or not finite) and
+    // were clamped; never null
+    unsigned int *range_count;
     float sigma;      // length scale the engines work with (for the Laplacian kernel the caller's, rescaled)
     int kind;         // knm_kernel_kind (the kernels of r = |x - c|: K-loop engines only)
 };
@@ -158,6 +162,7 @@ struct knm_ctx {
     float *pack_buf = nullptr; // packed operand images of the split-fp16 engines
     size_t pack_bytes = 0;
     size_t pack_limit = 0;     // cap on the image workspace chosen by the caller; 0 = engine defaults
+    unsigned int *range_count = nullptr; // device word: operands the split-fp16 engines had to clamp (see SweepArgs)
     // this device's copy of the library's static scratch array (address looked up at knm_create), and
     // the state of a call that draws its workspace from it instead of allocating
     unsigned char *static_ws = nullptr;

@@ -646,6 +646,40 @@ struct KernelOps {
     std::function<int(const float *W, const float *wgt, int t, double *U64)> t_w64;
 };
 
+// Operand conversions the split-fp16 engines have clamped so far (waits for the stream).
+int read_range_count(knm_ctx *ctx, unsigned int *count)
+{
+    hipError_t e = hipMemcpyAsync(count, ctx->range_count, sizeof(*count), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    return e == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "range counter", e);
+}
+
+// A fit runs with the context's cross-term mode unless its first sweep had to clamp operands (points
+// outside the range of the split-fp16 engines): then the whole fit runs on the fp32 matrix cores,
+// which have no such limits, and the context's mode comes back when the fit returns.
+struct CrossTermScope {
+    knm_ctx *ctx;
+    int saved;
+    unsigned int before = 0;
+    explicit CrossTermScope(knm_ctx *c) : ctx(c), saved(c->cross_term) {}
+    ~CrossTermScope() { ctx->cross_term = saved; }
+    int begin() { return read_range_count(ctx, &before); }
+    // after the first sweep: true if it must be repeated in the fp32 mode (now selected)
+    int check(bool *repeat)
+    {
+        *repeat = false;
+        if (ctx->cross_term != KNM_CROSS_F16X3) return KNM_OK;
+        unsigned int now = 0;
+        int st = read_range_count(ctx, &now);
+        if (st) return st;
+        if (now != before) {
+            ctx->cross_term = KNM_CROSS_F32;
+            *repeat = true;
+        }
+        return KNM_OK;
+    }
+};
+
 // cols (M x t, column-major fp64) <- K^T (wgt .* W): T^-T amplifies what the solver is given by the
 // conditioning of K_MM, so the result of the column sweep is taken in fp64 where the sweeps offer it
 int t_w_cols(knm_ctx *ctx, const KernelOps &ops, const float *W, const float *wgt, int t, float *u32, double *u64,
@@ -1233,7 +1267,14 @@ static int fit_core(knm_ctx *ctx, const KernelOps &ops, knm_precond *p, const fl
     double *db = beta.as<double>(), *dr = r.as<double>(), *dp = pv.as<double>(), *dq = q.as<double>();
 
     // rhs = A^-T T^-T K_nm^T Y
+    CrossTermScope cross(ctx);
+    st = cross.begin();
+    if (st) return st;
     st = t_w_cols(ctx, ops, Y, nullptr, t, r32.as<float>(), wk.u64.as<double>(), dr);
+    if (st) return st;
+    bool repeat = false;
+    st = cross.check(&repeat);
+    if (!st && repeat) st = t_w_cols(ctx, ops, Y, nullptr, t, r32.as<float>(), wk.u64.as<double>(), dr);
     if (st) return st;
     st = tri_solve(ctx, p, p->T, p->Tdinv, true, dr, t);
     if (!st) st = tri_solve(ctx, p, p->A, p->Adinv, true, dr, t);
@@ -1423,10 +1464,19 @@ static int logfalkon_core(knm_ctx *ctx, const KernelOps &ops, const std::functio
         return KNM_OK;
     };
 
+    CrossTermScope cross(ctx);
+    st = cross.begin();
+    if (st) return st;
     for (int k = 0; k < n_steps; ++k) {
         const double mu = lambdas[k];
         st = evaluate(true, loss_or_null ? loss_or_null + k : nullptr);
         if (st) return st;
+        if (k == 0) {
+            bool repeat = false;
+            st = cross.check(&repeat);
+            if (!st && repeat) st = evaluate(true, loss_or_null ? loss_or_null : nullptr);
+            if (st) return st;
+        }
         // weights at the centres -> second factor of the preconditioner for this step
         st = centres_v(a32.as<float>(), zc.as<float>());
         if (st) return st;

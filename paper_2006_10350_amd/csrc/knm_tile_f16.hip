@@ -55,10 +55,12 @@ constexpr int kStage = 128; // stream points per LDS stage (2 threads per point)
 constexpr int kTilesPerStage = kStage / 32;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kC1 = 1024.0f, kC2 = 0.5f, kC3 = 0.000244140625f, kC4 = 1.1920928955078125e-07f; // 2^10 2^-1 2^-12 2^-23
+constexpr float kHalfMax = 65000.0f;   // scaled features are clamped to +-this before the split
+constexpr float kNormMax = 2097151.0f; // norm terms are clamped to this (four digits of 11 bits)
 
 __device__ __forceinline__ void split_half(float z, _Float16 &hi, _Float16 &lo)
 {
-    z = fminf(fmaxf(z, -65000.0f), 65000.0f);
+    z = fminf(fmaxf(z, -kHalfMax), kHalfMax);
     hi = (_Float16)z;
     lo = (_Float16)(z - (float)hi);
 }
@@ -69,8 +71,8 @@ typedef __fp16 f16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 &lo)
 {
     f32x2 z;
-    z[0] = fminf(fmaxf(z0, -65000.0f), 65000.0f);
-    z[1] = fminf(fmaxf(z1, -65000.0f), 65000.0f);
+    z[0] = fminf(fmaxf(z0, -kHalfMax), kHalfMax);
+    z[1] = fminf(fmaxf(z1, -kHalfMax), kHalfMax);
     hi = __builtin_convertvector(z, f16x2);
     f32x2 rem;
     rem[0] = z[0] - (float)hi[0];
@@ -81,7 +83,7 @@ __device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 
 // -n as four fixed-point digits (see the header comment); n >= 0
 __device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
 {
-    n = fminf(n, 2097151.0f);
+    n = fminf(n, kNormMax);
     const float q1 = floorf(n * (1.0f / 1024.0f));
     float r = fmaf(-q1, 1024.0f, n);
     const float q2 = floorf(r * 2.0f);
@@ -213,7 +215,8 @@ __device__ __forceinline__ void block_tile(f32x16 &acc, const f16x8 (&fh)[HU], c
 template <int NU, int VW>
 __global__ __launch_bounds__(kThreads) void pack_stream_kernel(const float *__restrict__ S, int64_t nS, int64_t lds,
                                                                const float *__restrict__ mu, int d, float sigma,
-                                                               int64_t row0, int64_t rows, f16x8 *__restrict__ packed)
+                                                               int64_t row0, int64_t rows, f16x8 *__restrict__ packed,
+                                                               unsigned int *__restrict__ range_count)
 {
     constexpr int HU = NU / 2;
     constexpr int FPT = 8 * HU;
@@ -227,12 +230,17 @@ __global__ __launch_bounds__(kThreads) void pack_stream_kernel(const float *__re
     float xs[FPT];
     load_features<FPT, VW>(S + (valid ? idx : 0) * lds, mu, part * FPT, d, valid, xs);
     float nrm = 0.0f;
+    bool clamped = false;
 #pragma unroll
     for (int k = 0; k < FPT; ++k) {
         xs[k] *= gamma;
         nrm = fmaf(xs[k], xs[k], nrm);
+        clamped |= !(fabsf(xs[k]) <= kHalfMax); // also true for a NaN
     }
     nrm += __shfl_xor(nrm, 1);
+    clamped |= !(0.5f * nrm <= kNormMax);
+    clamped |= (__shfl_xor((int)clamped, 1) != 0); // the two threads of a point
+    if (clamped && valid && part == 0) atomicAdd(range_count, 1u); // rare: one count per point
     _Float16 q[4];
     norm_digits(0.5f * nrm, q);
     f16x8 *tile = packed + (rel >> 5) * (2 * HU * 64);
@@ -288,6 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         const bool valid = idx < a.nF;
         const float *p = a.F + (valid ? idx : 0) * a.ldf;
         float nrm = 0.0f;
+        bool clamped = false;
 #pragma unroll
         for (int m = 0; m < HU; ++m) {
 #pragma unroll
@@ -295,6 +304,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
                 const int k = 8 * (2 * m + h) + e;
                 const float z = (valid && k < d) ? gamma * (p[k] - a.mu[k < d ? k : 0]) : 0.0f;
                 nrm = fmaf(z, z, nrm);
+                clamped |= !(fabsf(z) <= kHalfMax); // also true for a NaN
                 _Float16 zh, zl;
                 split_half(z, zh, zl);
                 fh[rb][m][e] = zh;
@@ -302,6 +312,11 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
             }
         }
         nrm += __shfl_xor(nrm, 32);
+        clamped |= !(0.5f * nrm <= kNormMax);
+        clamped |= (__shfl_xor((int)clamped, 32) != 0); // the two lanes of a point
+        // one count per point and sweep: the workgroups of the first chunk report (every chunk's
+        // workgroups convert the same fixed points)
+        if (clamped && valid && h == 0 && blockIdx.y == 0 && chunk0 == 0) atomicAdd(a.range_count, 1u);
         _Float16 q[4];
         norm_digits(valid ? 0.5f * nrm : 0.0f, q);
         fhv[rb] = fh[rb][HU - 1];
@@ -433,13 +448,13 @@ hipError_t launch_nu(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipS
         const dim3 pgrid((unsigned)((rows + kThreads / 2 - 1) / (kThreads / 2)));
         if (a16)
             hipLaunchKernelGGL((pack_stream_kernel<NU, 4>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.mu, a.d,
-                               a.sigma, row0, rows, packed);
+                               a.sigma, row0, rows, packed, a.range_count);
         else if (a8)
             hipLaunchKernelGGL((pack_stream_kernel<NU, 2>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.mu, a.d,
-                               a.sigma, row0, rows, packed);
+                               a.sigma, row0, rows, packed, a.range_count);
         else
             hipLaunchKernelGGL((pack_stream_kernel<NU, 1>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.mu, a.d,
-                               a.sigma, row0, rows, packed);
+                               a.sigma, row0, rows, packed, a.range_count);
         const dim3 grid((unsigned)blocks, (unsigned)nc);
         hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU>), grid, dim3(kThreads), 0, stream, a, packed, c0);
         hipError_t e = hipGetLastError();

@@ -186,6 +186,25 @@ def test_workload_shaped_fit(knm, name, n, M, iters, cross_term):
     assert np.all(np.isfinite(resid)) and np.all(np.asarray(resid)[-1] < np.asarray(resid)[0])
 
 
+def test_fit_falls_back_to_fp32_when_operands_are_clamped(knm):
+    """A data row far outside the range of the split-fp16 operands (its kernel values against every
+    centre are zero either way): the fit notices the clamped conversion in its first sweep, runs in
+    the fp32-MFMA mode, matches the oracle and leaves the context's mode as it was."""
+    w = synth.workload("tiny", n=6000, M=300)
+    inp = synth.make_inputs(w, device="cpu", n_test=500)
+    X, Y, C, Xt = inp["X"].clone(), inp["Y"], inp["C"], inp["Xtest"]
+    far = int(np.setdiff1d(np.arange(w.n), inp["centre_rows"].numpy())[0])
+    X[far, 2] = 5.0e5
+    ctx = knm.default_context()
+    ctx.range_exceeded()
+    alpha = knm.falkon_fit(X.cuda(), Y.cuda(), C.cuda(), w.sigma, w.lam, 5, 1e-9)
+    assert ctx.range_exceeded() >= 1
+    assert ctx.cross_term == "f16x3"
+    pred = knm.falkon_predict(Xt.cuda(), C.cuda(), w.sigma, alpha).cpu().numpy()
+    ao = oracle.falkon_fit(X.numpy(), Y.numpy(), C.numpy(), w.sigma, w.lam, 5, 1e-9)
+    assert rel_l2(pred, oracle.falkon_predict(Xt.numpy(), C.numpy(), w.sigma, ao)) < 1e-3
+
+
 def test_all_points_as_centres_reaches_exact_krr(knm):
     # M = n, C = X: the preconditioned operator is n I, one CG step gives (K + n lam I)^-1 y
     # (moderately conditioned K, as above: the fp32 products are amplified by T^-1)

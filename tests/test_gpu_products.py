@@ -226,8 +226,38 @@ def test_split_half_range_limits(knm):
         assert rel_l2(W[keep], Wo[keep]) < 1e-4
         assert W[7, 0] == pytest.approx(Wo[7, 0], rel=5e-2) and Wo[7, 0] >= 1.0  # sees its twin centre
         assert abs(W[11, 0]) < 1e-6
+        # the clamped conversion of row 11 is reported, and only that one
+        assert ctx.range_exceeded() >= 1
+        assert ctx.range_exceeded() == 0  # the query resets the count
+        X[11, 0] = 1.0
+        knm.knm_v(X.cuda(), C.cuda(), sigma, V.cuda())
+        assert ctx.range_exceeded() == 0
     finally:
         ctx.set_cross_term("f16x3")
+
+
+@pytest.mark.parametrize("d,t", [(9, 1), (28, 1), (60, 1), (12, 3)])  # every packing kernel and the fixed-point prologue
+def test_clamped_and_non_finite_operands_are_counted(knm, d, t):
+    """Scaled features beyond +-65000, norm terms beyond 2^21 and NaNs are clamped by the split-fp16
+    conversion: the device counter reports them, whichever operand role the point has, and the
+    fp32-MFMA mode counts nothing."""
+    ctx = knm.default_context()
+    n, M, sigma = 700, 300, 2.0
+    X, C, V = _rand(n, d, 52), _rand(M, d, 53), _rand(M, t, 54)
+    ctx.range_exceeded()
+    knm.knm_prod(X.cuda(), C.cuda(), sigma, V.cuda())
+    assert ctx.range_exceeded() == 0
+    for where, row, value in (("X", 650, 4.0e5), ("X", 3, float("nan")), ("C", 299, 7000.0), ("C", 0, float("inf"))):
+        Xb, Cb = X.clone(), C.clone()
+        (Xb if where == "X" else Cb)[row, d - 1] = value  # 7000 / sigma: norm term 9e6 > 2^21, feature in range
+        knm.knm_prod(Xb.cuda(), Cb.cuda(), sigma, V.cuda())
+        assert ctx.range_exceeded() >= 1, (where, row, value)
+        ctx.set_cross_term("f32")
+        try:
+            knm.knm_prod(Xb.cuda(), Cb.cuda(), sigma, V.cuda())
+            assert ctx.range_exceeded() == 0
+        finally:
+            ctx.set_cross_term("f16x3")
 
 
 @pytest.mark.parametrize("d,t,limit", [(28, 1, 300 << 10), (9, 1, 200 << 10), (130, 1, 4 << 20), (16, 5, 1 << 20)])
