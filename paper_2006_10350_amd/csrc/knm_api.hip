@@ -102,17 +102,19 @@ static bool bad_geom(const void *X, int64_t n, int d, int64_t ldx, const void *C
     return !X || !C || n <= 0 || M <= 0 || d <= 0 || t <= 0 || ldx < d || ldc < d || !(sigma > 0.0f);
 }
 
-// mu[k] = mean of feature k over the first `rows` rows of P: the common shift of a sweep's two
-// point sets.  One workgroup per 32 features, 8 row lanes per feature, fp64 sums in a fixed order.
-__global__ __launch_bounds__(256) void column_mean_kernel(const float *__restrict__ P, int64_t rows, int64_t ld, int d,
-                                                         float *__restrict__ mu)
+// mu[k] = mean of feature k over `rows` rows of P taken `stride` rows apart (a sample spread over the
+// whole set, so that data stored in some order still gives a representative centre): the common shift
+// of a sweep's two point sets.  One workgroup per 32 features, 8 row lanes per feature, fp64 sums in a
+// fixed order.
+__global__ __launch_bounds__(256) void column_mean_kernel(const float *__restrict__ P, int64_t rows, int64_t stride,
+                                                         int64_t ld, int d, float *__restrict__ mu)
 {
     __shared__ double part[8][32];
     const int f = threadIdx.x & 31, lane8 = threadIdx.x >> 5;
     const int k = blockIdx.x * 32 + f;
     double s = 0.0;
     if (k < d)
-        for (int64_t r = lane8; r < rows; r += 8) s += (double)P[r * ld + k];
+        for (int64_t r = lane8; r < rows; r += 8) s += (double)P[r * stride * ld + k];
     part[lane8][f] = s;
     __syncthreads();
     if (lane8 == 0 && k < d) {
@@ -180,6 +182,8 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
     const int64_t chunks = choose_chunks(nF, nS, d, t, ctx->cross_term, ctx->kernel_kind, &chunk_len);
     if (chunks > 65535) return fail(ctx, KNM_UNSUPPORTED, "too many stream chunks");
     const bool gemm = use_gemm_engine(d, t, ctx->cross_term, ctx->kernel_kind);
+    if (gemm && ctx->cross_term == KNM_CROSS_F32 && (!gemm_leading_dimension_ok(ldf) || !gemm_leading_dimension_ok(lds)))
+        return fail(ctx, KNM_UNSUPPORTED, "leading dimension above 5.5 million elements in the fp32-MFMA K-loop engine");
     const bool part_is_64 = out64 != nullptr && gemm;
     const bool merged = chunks > 1 || out64 != nullptr; // an fp64 result is always written by the merge pass
     if (ctx->static_mode) ctx->static_used = 0; // every sweep carves its pieces afresh
@@ -189,15 +193,16 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
                          (part_is_64 ? sizeof(double) : sizeof(float)) * (size_t)chunks * nF * t, &part);
         if (st) return st;
     }
-    // common shift: feature means of (the first rows of) the smaller point set
+    // common shift: feature means of (a strided sample of at most 65536 rows of) the smaller point set
     float *mu = nullptr;
     {
         int st = acquire(ctx, &ctx->mu_buf, &ctx->mu_bytes, sizeof(float) * ((size_t)d + 1), &mu); // + the "shifted" flag
         if (st) return st;
         const bool from_f = nF <= nS;
         const int64_t rows = from_f ? nF : nS;
+        const int64_t stride = (rows + 65535) / 65536; // every stride-th row: at most 65536 of them, spread over the set
         hipLaunchKernelGGL(column_mean_kernel, dim3((unsigned)((d + 31) / 32)), dim3(256), 0, ctx->stream, from_f ? F : S,
-                           rows < 65536 ? rows : 65536, from_f ? ldf : lds, d, mu);
+                           (rows + stride - 1) / stride, stride, from_f ? ldf : lds, d, mu);
         hipLaunchKernelGGL(shift_decide_kernel, dim3(1), dim3(256), 0, ctx->stream, mu, d,
                            1.0f / (2.0f * sigma * sigma));
         if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "column_mean_kernel launch");

@@ -23,13 +23,11 @@
 #include <type_traits>
 
 #include "knm_internal.h"
+#include "knm_operands.h"
 
 namespace knm {
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int kFixed = 256;            // fixed points per workgroup
@@ -38,7 +36,6 @@ constexpr int kPts = kFixed + kStream; // points staged per K-chunk
 constexpr int kBlocks = kPts / 32;     // 32-point blocks in LDS: 8 fixed then 4 stream
 constexpr int kChunk = 16;             // features per K-chunk = 8 K-steps
 constexpr int kLoads = kPts * (kChunk / 4) / kThreads; // float4 loads per thread and chunk (6)
-constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kBlockFloats = 2 * 64 * 4; // one block, one chunk: 2 units x 64 lanes x 4 K-steps
 
 static_assert(kLoads * kThreads == kPts * (kChunk / 4), "staging must divide evenly");
@@ -71,12 +68,6 @@ __device__ __forceinline__ float acc_read(const float &x)
     float p;
     asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(p) : "a"(x));
     return p;
-}
-
-// Wait states between the last MFMA written in inline assembly and the first read of its result.
-__device__ __forceinline__ void mfma_results_ready()
-{
-    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory");
 }
 
 // TP: number of vector columns, padded to a multiple of 4.  VW: 4 if rows can be read
@@ -400,6 +391,8 @@ hipError_t launch_tp(const SweepArgs &a, hipStream_t stream)
 } // namespace
 
 int gemm_max_t() { return 16; }
+// the stagers form row offsets within a block of 256 fixed + 128 stream points in 32 bits
+bool gemm_leading_dimension_ok(int64_t ld) { return ld <= (int64_t)0x7fffffff / 384; }
 int64_t gemm_stage_points() { return kStream; }
 int64_t gemm_fixed_per_block() { return kFixed; }
 
@@ -409,6 +402,7 @@ hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream)
     if (a.kind < KNM_KERNEL_GAUSSIAN || a.kind > KNM_KERNEL_MATERN52) return hipErrorInvalidValue;
     if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
+    if (!gemm_leading_dimension_ok(a.ldf) || !gemm_leading_dimension_ok(a.lds)) return hipErrorInvalidValue;
     if (a.t <= 4) return launch_tp<4>(a, stream);
     if (a.t <= 8) return launch_tp<8>(a, stream);
     if (a.t <= 12) return launch_tp<12>(a, stream);

@@ -43,15 +43,11 @@
 #include <type_traits>
 
 #include "knm_internal.h"
+#include "knm_operands.h"
 
 namespace knm {
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __fp16 f16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
@@ -61,42 +57,7 @@ constexpr int kBlocks = (kFixed + kStream) / 32; // 32-point blocks per stage: 8
 constexpr int kChunk = 16;                     // features per K-chunk = one MFMA K
 constexpr int kUnits = 128;                    // 16-byte units per block and chunk (2 planes x 64 lanes)
 constexpr int kLoads = kBlocks * kUnits / kThreads; // units copied per thread and stage (6)
-constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kPScale = 16384.0f; // matrix-core reduction: kernel values are split into fp16 halves after this scale
-constexpr float kC1 = 1024.0f, kC2 = 0.5f, kC3 = 0.000244140625f, kC4 = 1.1920928955078125e-07f; // 2^10 2^-1 2^-12 2^-23
-constexpr float kHalfMax = 65000.0f;   // scaled features are clamped to +-this before the split
-constexpr float kNormMax = 2097151.0f; // norm terms are clamped to this (four digits of 11 bits)
-
-static_assert(kLoads * kThreads == kBlocks * kUnits, "staging must divide evenly");
-
-// hi = nearest half of z (clamped to the finite range first), lo = nearest half of the exact
-// remainder z - hi; hi + lo carries 22-23 significant bits of z
-__device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 &lo)
-{
-    f32x2 z;
-    z[0] = fminf(fmaxf(z0, -kHalfMax), kHalfMax);
-    z[1] = fminf(fmaxf(z1, -kHalfMax), kHalfMax);
-    hi = __builtin_convertvector(z, f16x2);
-    f32x2 rem;
-    rem[0] = z[0] - (float)hi[0];
-    rem[1] = z[1] - (float)hi[1];
-    lo = __builtin_convertvector(rem, f16x2);
-}
-
-// -n as four fixed-point digits; n >= 0
-__device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
-{
-    n = fminf(n, kNormMax);
-    const float q1 = floorf(n * (1.0f / 1024.0f));
-    float r = fmaf(-q1, 1024.0f, n);
-    const float q2 = floorf(r * 2.0f);
-    r = fmaf(-q2, 0.5f, r);
-    const float q3 = floorf(r * 4096.0f);
-    r = fmaf(-q3, kC3, r);
-    const float q4 = rintf(r * 8388608.0f);
-    q[0] = (_Float16)(-q1); q[1] = (_Float16)(-q2); q[2] = (_Float16)(-q3); q[3] = (_Float16)(-q4);
-}
-
 // Image of points [row0, row0 + 32 gridDim.x) of P (points at or beyond nP become zero
 // points).  One workgroup per 32-point block; thread = (point, 8-feature unit), four
 // chunks (64 features) per pass over the row.
@@ -145,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__re
             const float z0 = gamma * z[e], z1 = gamma * z[e + 1];
             nrm = fmaf(z0, z0, nrm);
             nrm = fmaf(z1, z1, nrm);
-            clamped |= !(fabsf(z0) <= kHalfMax) || !(fabsf(z1) <= kHalfMax); // also true for a NaN
+            clamped |= out_of_half_range(z0) || out_of_half_range(z1);
             f16x2 ph, pl;
             split_pair(z0, z1, ph, pl);
             hi[e] = (_Float16)ph[0]; hi[e + 1] = (_Float16)ph[1];
@@ -209,13 +170,6 @@ __device__ __forceinline__ float acc_read(const float &x)
     float p;
     asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(p) : "a"(x));
     return p;
-}
-
-// Wait states between the last MFMA written in inline assembly and the first read of its result
-// by other instructions (the compiler cannot insert them for instructions it does not see).
-__device__ __forceinline__ void mfma_results_ready()
-{
-    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory");
 }
 
 // The second contraction uses the compiler's MFMA builtin, not inline assembly: its operands are

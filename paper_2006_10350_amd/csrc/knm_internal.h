@@ -100,6 +100,7 @@ size_t f16_pack_bytes_per_point(int d);
 hipError_t launch_sweep_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream);
 // K-loop engine (knm_gemm.hip): any d, up to gemm_max_t() columns per launch
 int gemm_max_t();
+bool gemm_leading_dimension_ok(int64_t ld); // leading dimensions the fp32 K-loop engine can index
 int64_t gemm_stage_points();
 int64_t gemm_fixed_per_block();
 hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream);

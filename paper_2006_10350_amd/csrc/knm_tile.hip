@@ -30,19 +30,16 @@
 // and LDS accesses 8 or 16 bytes wide.
 
 #include "knm_internal.h"
+#include "knm_operands.h"
 
 namespace knm {
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kStage = 128; // stream points per LDS stage (2 threads per point)
 constexpr int kTilesPerStage = kStage / 32;
-constexpr float kLog2e = 1.4426950408889634f;
 
 template <int KS>
 struct Geo {
@@ -63,43 +60,6 @@ __host__ __device__ constexpr int ks_for_d(int d)
     return ks;
 }
 
-// Loads virtual features [base, base + N) of one point into registers (zero beyond d or
-// when the point is padding).  Branch-free: out-of-range pieces re-read the row's first
-// elements and are zeroed by a select, so all loads issue back to back and their latency
-// is hidden behind a whole stage of MFMA work.  `row` must point at a readable row.
-template <int N, int VW>
-__device__ __forceinline__ void load_features(const float *__restrict__ row, const float *__restrict__ mu, bool shifted,
-                                              int base, int d, bool valid, float (&x)[N])
-{
-    if constexpr (VW == 4) {
-#pragma unroll
-        for (int k = 0; k < N; k += 4) {
-            const bool in = valid && (base + k < d); // d % 4 == 0 in this mode
-            const f32x4 v = *reinterpret_cast<const f32x4 *>(row + (in ? base + k : 0));
-            f32x4 m = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (shifted) m = *reinterpret_cast<const f32x4 *>(mu + (in ? base + k : 0));
-            x[k] = in ? v[0] - m[0] : 0.0f; x[k + 1] = in ? v[1] - m[1] : 0.0f;
-            x[k + 2] = in ? v[2] - m[2] : 0.0f; x[k + 3] = in ? v[3] - m[3] : 0.0f;
-        }
-    } else if constexpr (VW == 2) {
-#pragma unroll
-        for (int k = 0; k < N; k += 2) {
-            const bool in = valid && (base + k < d); // d % 2 == 0 in this mode
-            const f32x2 v = *reinterpret_cast<const f32x2 *>(row + (in ? base + k : 0));
-            f32x2 m = {0.0f, 0.0f};
-            if (shifted) m = *reinterpret_cast<const f32x2 *>(mu + (in ? base + k : 0));
-            x[k] = in ? v[0] - m[0] : 0.0f; x[k + 1] = in ? v[1] - m[1] : 0.0f;
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < N; ++k) {
-            const bool in = valid && (base + k < d);
-            const float v = row[in ? base + k : 0];
-            x[k] = in ? v - (shifted ? mu[in ? base + k : 0] : 0.0f) : 0.0f;
-        }
-    }
-}
-
 // The hot instructions are issued through volatile inline assembly: the compiler keeps
 // volatile statements in program order, which is what the schedule below relies on.
 //
@@ -113,55 +73,61 @@ __device__ __forceinline__ void load_features(const float *__restrict__ row, con
 // by three instructions (a transcendental result needs one idle issue slot).
 // acc = sum_{s < KS} a[s] (x) b[s] as one dependent chain of 32x32x2 fp32 MFMAs, emitted in
 // assembly blocks of up to four instructions (operand-count limit of an asm statement).
+// `guard` is the accumulator of another block whose MFMA chain may still be in flight: naming it as
+// an operand of every statement keeps the compiler from placing a copy or spill of it (a read the
+// hardware does not interlock) between these statements.
 template <int KS, int S0>
-__device__ __forceinline__ void mfma_chain_from(f32x16 &acc, const float *a, const float *b)
+__device__ __forceinline__ void mfma_chain_from(f32x16 &acc, const float *a, const float *b, f32x16 &guard)
 {
     constexpr int n = KS - S0 >= 4 ? 4 : KS - S0;
     if constexpr (n == 4)
-        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0\n\t"
-                     "v_mfma_f32_32x32x2_f32 %0, %3, %4, %0\n\t"
-                     "v_mfma_f32_32x32x2_f32 %0, %5, %6, %0\n\t"
-                     "v_mfma_f32_32x32x2_f32 %0, %7, %8, %0"
-                     : "+v"(acc)
-                     : "v"(a[S0]), "v"(b[S0]), "v"(a[S0 + 1]), "v"(b[S0 + 1]), "v"(a[S0 + 2]), "v"(b[S0 + 2]),
-                       "v"(a[S0 + 3]), "v"(b[S0 + 3]));
+        asm volatile("v_mfma_f32_32x32x2_f32 %[c], %[a0], %[b0], %[c]\n\t"
+                     "v_mfma_f32_32x32x2_f32 %[c], %[a1], %[b1], %[c]\n\t"
+                     "v_mfma_f32_32x32x2_f32 %[c], %[a2], %[b2], %[c]\n\t"
+                     "v_mfma_f32_32x32x2_f32 %[c], %[a3], %[b3], %[c]"
+                     : [c] "+v"(acc), "+v"(guard)
+                     : [a0] "v"(a[S0]), [b0] "v"(b[S0]), [a1] "v"(a[S0 + 1]), [b1] "v"(b[S0 + 1]), [a2] "v"(a[S0 + 2]),
+                       [b2] "v"(b[S0 + 2]), [a3] "v"(a[S0 + 3]), [b3] "v"(b[S0 + 3]));
     else if constexpr (n == 3)
-        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0\n\t"
-                     "v_mfma_f32_32x32x2_f32 %0, %3, %4, %0\n\t"
-                     "v_mfma_f32_32x32x2_f32 %0, %5, %6, %0"
-                     : "+v"(acc)
-                     : "v"(a[S0]), "v"(b[S0]), "v"(a[S0 + 1]), "v"(b[S0 + 1]), "v"(a[S0 + 2]), "v"(b[S0 + 2]));
+        asm volatile("v_mfma_f32_32x32x2_f32 %[c], %[a0], %[b0], %[c]\n\t"
+                     "v_mfma_f32_32x32x2_f32 %[c], %[a1], %[b1], %[c]\n\t"
+                     "v_mfma_f32_32x32x2_f32 %[c], %[a2], %[b2], %[c]"
+                     : [c] "+v"(acc), "+v"(guard)
+                     : [a0] "v"(a[S0]), [b0] "v"(b[S0]), [a1] "v"(a[S0 + 1]), [b1] "v"(b[S0 + 1]), [a2] "v"(a[S0 + 2]),
+                       [b2] "v"(b[S0 + 2]));
     else if constexpr (n == 2)
-        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0\n\t"
-                     "v_mfma_f32_32x32x2_f32 %0, %3, %4, %0"
-                     : "+v"(acc)
-                     : "v"(a[S0]), "v"(b[S0]), "v"(a[S0 + 1]), "v"(b[S0 + 1]));
+        asm volatile("v_mfma_f32_32x32x2_f32 %[c], %[a0], %[b0], %[c]\n\t"
+                     "v_mfma_f32_32x32x2_f32 %[c], %[a1], %[b1], %[c]"
+                     : [c] "+v"(acc), "+v"(guard)
+                     : [a0] "v"(a[S0]), [b0] "v"(b[S0]), [a1] "v"(a[S0 + 1]), [b1] "v"(b[S0 + 1]));
     else if constexpr (n == 1)
-        asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a[S0]), "v"(b[S0]));
-    if constexpr (S0 + n < KS) mfma_chain_from<KS, S0 + n>(acc, a, b);
+        asm volatile("v_mfma_f32_32x32x2_f32 %[c], %[a0], %[b0], %[c]" : [c] "+v"(acc), "+v"(guard) : [a0] "v"(a[S0]), [b0] "v"(b[S0]));
+    if constexpr (S0 + n < KS) mfma_chain_from<KS, S0 + n>(acc, a, b, guard);
 }
 template <int KS>
-__device__ __forceinline__ void mfma_chain(f32x16 &acc, const float *a, const float *b)
+__device__ __forceinline__ void mfma_chain(f32x16 &acc, const float *a, const float *b, f32x16 &guard)
 {
     // first instruction takes the literal 0 as its C operand
-    asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, 0" : "=&v"(acc) : "v"(a[0]), "v"(b[0]));
-    if constexpr (KS > 1) mfma_chain_from<KS, 1>(acc, a, b);
+    asm volatile("v_mfma_f32_32x32x2_f32 %0, %2, %3, 0" : "=&v"(acc), "+v"(guard) : "v"(a[0]), "v"(b[0]));
+    if constexpr (KS > 1) mfma_chain_from<KS, 1>(acc, a, b, guard);
 }
 // s_i += min(max(2^x_i, 0), 1) * vl for four entries; the clamp keeps kernel values in [0, 1]
+// (`guard`: see mfma_chain_from)
 __device__ __forceinline__ void exp_fma4(float x0, float x1, float x2, float x3, float vl, float &s0, float &s1,
-                                         float &s2, float &s3)
+                                         float &s2, float &s3, f32x16 &guard)
 {
     float p0, p1, p2, p3;
-    asm volatile("v_exp_f32_e64 %0, %8 clamp\n\t"
-                 "v_exp_f32_e64 %1, %9 clamp\n\t"
-                 "v_exp_f32_e64 %2, %10 clamp\n\t"
-                 "v_exp_f32_e64 %3, %11 clamp\n\t"
-                 "v_fmac_f32_e32 %4, %0, %12\n\t"
-                 "v_fmac_f32_e32 %5, %1, %12\n\t"
-                 "v_fmac_f32_e32 %6, %2, %12\n\t"
-                 "v_fmac_f32_e32 %7, %3, %12"
-                 : "=&v"(p0), "=&v"(p1), "=&v"(p2), "=&v"(p3), "+v"(s0), "+v"(s1), "+v"(s2), "+v"(s3)
-                 : "v"(x0), "v"(x1), "v"(x2), "v"(x3), "v"(vl));
+    asm volatile("v_exp_f32_e64 %[p0], %[x0] clamp\n\t"
+                 "v_exp_f32_e64 %[p1], %[x1] clamp\n\t"
+                 "v_exp_f32_e64 %[p2], %[x2] clamp\n\t"
+                 "v_exp_f32_e64 %[p3], %[x3] clamp\n\t"
+                 "v_fmac_f32_e32 %[s0], %[p0], %[vl]\n\t"
+                 "v_fmac_f32_e32 %[s1], %[p1], %[vl]\n\t"
+                 "v_fmac_f32_e32 %[s2], %[p2], %[vl]\n\t"
+                 "v_fmac_f32_e32 %[s3], %[p3], %[vl]"
+                 : [p0] "=&v"(p0), [p1] "=&v"(p1), [p2] "=&v"(p2), [p3] "=&v"(p3), [s0] "+v"(s0), [s1] "+v"(s1),
+                   [s2] "+v"(s2), [s3] "+v"(s3), "+v"(guard)
+                 : [x0] "v"(x0), [x1] "v"(x1), [x2] "v"(x2), [x3] "v"(x3), [vl] "v"(vl));
 }
 
 template <int KS, int R, int VW>
@@ -279,17 +245,18 @@ __global__ __launch_bounds__(kThreads, (KS <= 15 ? 3 : 1)) void gauss_sweep_kern
         for (int tile = 0; tile < kTilesPerStage; ++tile) {
             const int cur = tile & 1;
             if (tile + 1 < kTilesPerStage) read_tile(tile + 1, cur ^ 1);
+            // chain(0), chain(1), finish(0), finish(1): every statement that runs while the other
+            // block's chain may be in flight names that block's accumulator as its guard
+            static_assert(R == 2, "the order of chains and finishes below is written for two blocks");
             f32x16 acc[R];
-#pragma unroll
-            for (int rb = 0; rb < R; ++rb) {
-                mfma_chain<KS>(acc[rb], af[rb], b[cur]);
-            }
+            mfma_chain<KS>(acc[0], af[0], b[cur], acc[1]); // acc[1]: not yet written, a harmless guard
+            mfma_chain<KS>(acc[1], af[1], b[cur], acc[0]);
 #pragma unroll
             for (int rb = 0; rb < R; ++rb)
 #pragma unroll
                 for (int r = 0; r < 16; r += 4)
                     exp_fma4(acc[rb][r], acc[rb][r + 1], acc[rb][r + 2], acc[rb][r + 3], vl[cur], sum[rb][r],
-                             sum[rb][r + 1], sum[rb][r + 2], sum[rb][r + 3]);
+                             sum[rb][r + 1], sum[rb][r + 2], sum[rb][r + 3], acc[rb ^ 1]);
         }
     }
     // ---- reduce over the 32 stream lanes of each half-wave and store ----------------------

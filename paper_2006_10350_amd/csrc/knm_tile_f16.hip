@@ -40,92 +40,15 @@
 // tile after it was issued, and no exp result by the instruction right after it.
 
 #include "knm_internal.h"
+#include "knm_operands.h"
 
 namespace knm {
 namespace {
-
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kStage = 128; // stream points per LDS stage (2 threads per point)
 constexpr int kTilesPerStage = kStage / 32;
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kC1 = 1024.0f, kC2 = 0.5f, kC3 = 0.000244140625f, kC4 = 1.1920928955078125e-07f; // 2^10 2^-1 2^-12 2^-23
-constexpr float kHalfMax = 65000.0f;   // scaled features are clamped to +-this before the split
-constexpr float kNormMax = 2097151.0f; // norm terms are clamped to this (four digits of 11 bits)
-
-__device__ __forceinline__ void split_half(float z, _Float16 &hi, _Float16 &lo)
-{
-    z = fminf(fmaxf(z, -kHalfMax), kHalfMax);
-    hi = (_Float16)z;
-    lo = (_Float16)(z - (float)hi);
-}
-
-typedef __fp16 f16x2 __attribute__((ext_vector_type(2)));
-// Two features at once: hi = nearest half of z (clamped to the finite range first), lo = nearest
-// half of the exact remainder z - hi; hi + lo carries 22-23 significant bits of z.
-__device__ __forceinline__ void split_pair(float z0, float z1, f16x2 &hi, f16x2 &lo)
-{
-    f32x2 z;
-    z[0] = fminf(fmaxf(z0, -kHalfMax), kHalfMax);
-    z[1] = fminf(fmaxf(z1, -kHalfMax), kHalfMax);
-    hi = __builtin_convertvector(z, f16x2);
-    f32x2 rem;
-    rem[0] = z[0] - (float)hi[0];
-    rem[1] = z[1] - (float)hi[1];
-    lo = __builtin_convertvector(rem, f16x2);
-}
-
-// -n as four fixed-point digits (see the header comment); n >= 0
-__device__ __forceinline__ void norm_digits(float n, _Float16 (&q)[4])
-{
-    n = fminf(n, kNormMax);
-    const float q1 = floorf(n * (1.0f / 1024.0f));
-    float r = fmaf(-q1, 1024.0f, n);
-    const float q2 = floorf(r * 2.0f);
-    r = fmaf(-q2, 0.5f, r);
-    const float q3 = floorf(r * 4096.0f);
-    r = fmaf(-q3, kC3, r);
-    const float q4 = rintf(r * 8388608.0f);
-    q[0] = (_Float16)(-q1); q[1] = (_Float16)(-q2); q[2] = (_Float16)(-q3); q[3] = (_Float16)(-q4);
-}
-
-// branch-free row loads (see knm_tile.hip): virtual features [base, base + N), zero beyond d
-template <int N, int VW>
-__device__ __forceinline__ void load_features(const float *__restrict__ row, const float *__restrict__ mu, int base,
-                                              int d, bool valid, float (&x)[N])
-{
-    if constexpr (VW == 4) {
-#pragma unroll
-        for (int k = 0; k < N; k += 4) {
-            const bool in = valid && (base + k < d); // d % 4 == 0 in this mode
-            const f32x4 v = *reinterpret_cast<const f32x4 *>(row + (in ? base + k : 0));
-            const f32x4 m = *reinterpret_cast<const f32x4 *>(mu + (in ? base + k : 0));
-            x[k] = in ? v[0] - m[0] : 0.0f; x[k + 1] = in ? v[1] - m[1] : 0.0f;
-            x[k + 2] = in ? v[2] - m[2] : 0.0f; x[k + 3] = in ? v[3] - m[3] : 0.0f;
-        }
-    } else if constexpr (VW == 2) {
-#pragma unroll
-        for (int k = 0; k < N; k += 2) {
-            const bool in = valid && (base + k < d); // d % 2 == 0 in this mode
-            const f32x2 v = *reinterpret_cast<const f32x2 *>(row + (in ? base + k : 0));
-            const f32x2 m = *reinterpret_cast<const f32x2 *>(mu + (in ? base + k : 0));
-            x[k] = in ? v[0] - m[0] : 0.0f; x[k + 1] = in ? v[1] - m[1] : 0.0f;
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < N; ++k) {
-            const bool in = valid && (base + k < d);
-            const float v = row[in ? base + k : 0];
-            x[k] = in ? v - mu[in ? base + k : 0] : 0.0f;
-        }
-    }
-}
-
 // ---- one MFMA followed by G (exp, FMA) pairs of the previous tile -------------------------
 #define KNM_MFMA_FIRST "v_mfma_f32_32x32x16_f16 %[acc], %[a], %[b], 0\n\t"
 #define KNM_MFMA_NEXT "v_mfma_f32_32x32x16_f16 %[acc], %[a], %[b], %[acc]\n\t"
@@ -228,14 +151,14 @@ __global__ __launch_bounds__(kThreads) void pack_stream_kernel(const float *__re
     const bool valid = idx < nS;
     const float gamma = sqrtf(kLog2e) / sigma;
     float xs[FPT];
-    load_features<FPT, VW>(S + (valid ? idx : 0) * lds, mu, part * FPT, d, valid, xs);
+    load_features<FPT, VW>(S + (valid ? idx : 0) * lds, mu, true, part * FPT, d, valid, xs);
     float nrm = 0.0f;
     bool clamped = false;
 #pragma unroll
     for (int k = 0; k < FPT; ++k) {
         xs[k] *= gamma;
         nrm = fmaf(xs[k], xs[k], nrm);
-        clamped |= !(fabsf(xs[k]) <= kHalfMax); // also true for a NaN
+        clamped |= out_of_half_range(xs[k]);
     }
     nrm += __shfl_xor(nrm, 1);
     clamped |= !(0.5f * nrm <= kNormMax);
@@ -304,7 +227,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
                 const int k = 8 * (2 * m + h) + e;
                 const float z = (valid && k < d) ? gamma * (p[k] - a.mu[k < d ? k : 0]) : 0.0f;
                 nrm = fmaf(z, z, nrm);
-                clamped |= !(fabsf(z) <= kHalfMax); // also true for a NaN
+                clamped |= out_of_half_range(z);
                 _Float16 zh, zl;
                 split_half(z, zh, zl);
                 fh[rb][m][e] = zh;
