@@ -126,8 +126,11 @@ int knm_t_y(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx,
 
 /* Preconditioner of Alg. 1 / Eq. 7, all in fp64 on the device:
  *   T = chol_upper(k(C, C) + jitter I),   A = chol_upper(T T^T / M + lambda I),
- * with T^T T = K_MM and A^T A = T T^T / M + lambda I.  *out owns 2 M^2 doubles of
- * device memory until precond_free.  On KNM_NOT_PD, *bad_pivot_or_null (HOST pointer)
+ * with T^T T = K_MM and A^T A = T T^T / M + lambda I.  The two factors share one array, as in the
+ * paper's in-place preconditioner (Sec. 3.1, the paragraph and figure on its memory): T in the
+ * upper triangle, the transpose of A two rows below the diagonal (so that neither diagonal is
+ * lost); *out owns (M + 3) M doubles of device memory at most, plus M^2 / 8 or so for the
+ * inverted diagonal blocks of the blocked solves, until precond_free.  On KNM_NOT_PD, *bad_pivot_or_null (HOST pointer)
  * receives the 1-based failing pivot, negative if it was the second factorisation. */
 int precond_build(knm_ctx *ctx, const float *C, int64_t M, int d, int64_t ldc, float sigma,
                   double lambda, double jitter, knm_precond **out, int64_t *bad_pivot_or_null);
@@ -161,8 +164,8 @@ int falkon_linop(knm_ctx *ctx, const knm_precond *p,
  *   C[i, j] = alpha sum_{q < k} w[q] a(i, q) a(j, q) + beta C[i, j] + shift [i == j],   i <= j < n
  *   form_nt == 0:  a(i, q) = A[q + i lda]  (A is k x n)      form_nt != 0:  a(i, q) = A[i + q lda]  (A is n x k)
  * w_or_null: k weights or NULL (all one).  triangular != 0 (form_nt only): A is upper
- * triangular with zeros stored below its diagonal (a(i, q) = 0 for q < i), and the part of
- * the sum that those zeros make vanish is skipped.  The strict lower triangle of C is neither read nor written; with
+ * triangular (a(i, q) is taken as 0 for q < i, whatever is stored there), and the part of
+ * the sum that vanishes is skipped.  The strict lower triangle of C is neither read nor written; with
  * beta == 0 C is not read.  A must not overlap the upper triangle of C.  All pointers DEVICE,
  * the call is asynchronous on the context's stream. */
 int precond_rank_k_update(knm_ctx *ctx, int form_nt, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,

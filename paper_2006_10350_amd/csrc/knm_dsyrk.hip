@@ -12,6 +12,11 @@
 //   form TN:  a(i, k) = A[k + i * lda]   (block row of the factor: contraction index contiguous)
 //   form NT:  a(i, k) = A[i + k * lda]   (columns of the triangular factor: row index contiguous)
 //
+// The result goes to the upper triangle of C, or (trans_c) mirrored to C[j + i * ldc], i <= j: the lower
+// triangle of the same array.  The two factors of the preconditioner share one array that way (the
+// first in the upper triangle, the transpose of the second two rows below it), and a triangular operand
+// is masked below its diagonal while it is staged, because what lies there belongs to the other factor.
+//
 // and, with the triangle test and the patch enumeration switched off, the general product
 //   C[i, j] = alpha * sum_k a(i, k) * b(j, k) + beta * C[i, j]   over a rectangular C with its own
 // column operand b (always TN), which carries the first two steps of the column update (products
@@ -74,7 +79,8 @@ struct RankKArgs {
     int64_t ldc;
     int64_t n, nj, K; // C is n x nj (nj = n for the symmetric update)
     double alpha, beta, shift;
-    int tri;           // operand is upper triangular with explicit zeros below: tile column j0 starts at k = j0
+    int tri;           // operand is upper triangular (what is stored below its diagonal is ignored): tile column j0 starts at k = j0
+    int trans_c;       // store entry (i, j) at C[j + i * ldc]
     int patch_i;       // general product: tiles of a patch along i (kPatchWgs / patch_i along j)
     int64_t n_patch_i; // general product: patches along i
     int64_t n_patches; // patches in all (symmetric update: the upper-triangular ones)
@@ -152,6 +158,16 @@ template <int FORM, int R, int VEC> struct Fetch {
                 for (int e = 0; e < VEC; ++e)
                     if (k_of(r, e) >= k_left) v[r * VEC + e] = 0.0;
         }
+    }
+    // upper-triangular operand: zero the elements below the diagonal, row > k + delta in tile-relative
+    // terms (delta = global k of the stage's first element minus global row of the tile's first row)
+    __device__ __forceinline__ void mask_lower(int delta)
+    {
+#pragma unroll
+        for (int r = 0; r < kLoads; ++r)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+                if (row_of(r, e) > k_of(r, e) + delta) v[r * VEC + e] = 0.0;
     }
     // weights of the stage's k, fetched together with the operand (buffer loads: zero past K)
     static constexpr int kW = FORM == 0 ? VEC : kLoads;
@@ -266,6 +282,12 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
                 fa.mask_tail(k_left);
                 fb.mask_tail(k_left);
             }
+            if (SYM && a.tri) {
+                // stages that still overlap the diagonal band of a tile's rows (the first few of a tile)
+                const int64_t kk0 = kbeg + (int64_t)s * kTK;
+                if (kk0 < i0 + kTI) fa.mask_lower((int)(kk0 - i0));
+                if (kk0 < j0 + kTJ) fb.mask_lower((int)(kk0 - j0));
+            }
             if (WEIGHTED) fb.scale();
             fa.store(buf, kSA);
             fb.store(buf + kTK * kSA, kSB);
@@ -334,15 +356,15 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
             const int64_t j = j0 + wj + nn * 16 + (lane & 15);
             const int64_t ib = i0 + wi + m * 16 + (lane >> 4);
             if (j >= a.nj) continue;
-            double *col = a.C + j * a.ldc;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int64_t i = ib + 4 * r;
                 if ((SYM && i > j) || i >= a.n) continue;
+                double *dst = a.trans_c ? a.C + j + i * a.ldc : a.C + i + j * a.ldc;
                 double v = a.alpha * acc[m][nn][r];
-                if (a.beta != 0.0) v += a.beta * col[i];
+                if (a.beta != 0.0) v += a.beta * *dst;
                 if (SYM && i == j) v += a.shift;
-                col[i] = v;
+                *dst = v;
             }
         }
 }
@@ -351,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void rank_k_upper_kernel(RankKArgs a)
 
 hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, const double *A, int64_t lda,
                                const double *w, int tri, double beta, double shift, double *C, int64_t ldc,
-                               hipStream_t stream)
+                               hipStream_t stream, int trans_c)
 {
     if (n <= 0) return hipSuccess;
     RankKArgs a;
@@ -366,6 +388,7 @@ hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, 
     a.beta = beta;
     a.shift = shift;
     a.tri = tri;
+    a.trans_c = trans_c;
     a.extent = a.extent_b = K <= 0 ? 0 : (form_nt ? (K - 1) * lda + n : (n - 1) * lda + K);
     const int64_t patch = (int64_t)kPatchI * kTI; // = kPatchJ * kTJ
     const int64_t n_patch = (n + patch - 1) / patch;
@@ -396,8 +419,9 @@ hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, 
 }
 
 hipError_t launch_gemm_f64(int a_nt, int64_t ni, int64_t nj, int64_t K, double alpha, const double *A, int64_t lda,
-                           const double *B, int64_t ldb, double beta, double *C, int64_t ldc, hipStream_t stream)
+                           const double *B, int64_t ldb, double beta, double *C, int64_t ldc, hipStream_t stream, int b_nt)
 {
+    if (b_nt && !a_nt) return hipErrorInvalidValue; // not instantiated
     if (ni <= 0 || nj <= 0) return hipSuccess;
     RankKArgs a;
     a.A = A;
@@ -414,8 +438,9 @@ hipError_t launch_gemm_f64(int a_nt, int64_t ni, int64_t nj, int64_t K, double a
     a.beta = beta;
     a.shift = 0.0;
     a.tri = 0;
+    a.trans_c = 0;
     a.extent = K <= 0 ? 0 : (a_nt ? (K - 1) * lda + ni : (ni - 1) * lda + K);
-    a.extent_b = K <= 0 ? 0 : (nj - 1) * ldb + K;
+    a.extent_b = K <= 0 ? 0 : (b_nt ? (K - 1) * ldb + nj : (nj - 1) * ldb + K);
     // patches of 64 tiles, as square as the shape of C allows
     const int64_t tiles_i = (ni + kTI - 1) / kTI;
     int patch_i = 1;
@@ -429,13 +454,17 @@ hipError_t launch_gemm_f64(int a_nt, int64_t ni, int64_t nj, int64_t K, double a
     const int64_t wgs = groups * kXcds * kPatchWgs;
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     const int64_t span_a = a_nt ? (int64_t)kTK * lda + kTI : (int64_t)kTI * lda + kTK;
-    const int64_t span_b = (int64_t)kTJ * ldb + kTK;
+    const int64_t span_b = b_nt ? (int64_t)kTK * ldb + kTJ : (int64_t)kTJ * ldb + kTK;
     if (span_a * 8 >= 0xffffffffLL || span_b * 8 >= 0xffffffffLL || K >= (int64_t)0x7fffffff * kTK)
         return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs), block(kThreads);
     const bool vec2 = lda % 2 == 0 && ldb % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0 &&
                       reinterpret_cast<uintptr_t>(B) % 16 == 0;
-    if (a_nt && vec2)
+    if (b_nt && vec2)
+        hipLaunchKernelGGL((rank_k_upper_kernel<1, 1, false, 2, false>), grid, block, 0, stream, a);
+    else if (b_nt)
+        hipLaunchKernelGGL((rank_k_upper_kernel<1, 1, false, 1, false>), grid, block, 0, stream, a);
+    else if (a_nt && vec2)
         hipLaunchKernelGGL((rank_k_upper_kernel<1, 0, false, 2, false>), grid, block, 0, stream, a);
     else if (a_nt)
         hipLaunchKernelGGL((rank_k_upper_kernel<1, 0, false, 1, false>), grid, block, 0, stream, a);

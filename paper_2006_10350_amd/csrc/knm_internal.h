@@ -118,16 +118,19 @@ hipError_t launch_merge(const float *part, const double *part64, int64_t n_chunk
 // fp64 rank-k update of the upper triangle of C on the matrix cores (knm_dsyrk.hip):
 //   C[i, j] = alpha sum_{k < K} w[k] a(i, k) a(j, k) + beta C[i, j] + shift [i == j],  i <= j < n,
 // a(i, k) = A[k + i lda] (form_nt = 0) or A[i + k lda] (form_nt = 1); w may be null; with tri the
-// operand is upper triangular (a(i, k) = 0 for k < i) and the zero part of the contraction is skipped
+// operand is upper triangular (a(i, k) taken as 0 for k < i whatever is stored there) and the zero part
+// of the contraction is skipped; with trans_c entry (i, j) goes to C[j + i ldc] (the lower triangle)
 hipError_t launch_rank_k_upper(int form_nt, int64_t n, int64_t K, double alpha, const double *A, int64_t lda,
                                const double *w, int tri, double beta, double shift, double *C, int64_t ldc,
-                               hipStream_t stream);
+                               hipStream_t stream, int trans_c = 0);
 
 // general fp64 product on the same kernel: C (ni x nj) = alpha sum_{k < K} a(i, k) b(j, k) + beta C with
-// a(i, k) = A[k + i lda] (a_nt = 0) or A[i + k lda] (a_nt = 1) and b(j, k) = B[k + j ldb]; C must not
-// overlap A or B
+// a(i, k) = A[k + i lda] (a_nt = 0) or A[i + k lda] (a_nt = 1) and b(j, k) = B[k + j ldb] (b_nt = 0) or
+// B[j + k ldb] (b_nt = 1, only with a_nt = 1); C must not overlap A or B, except that a tile of C may be
+// exactly the operand rows it reads
 hipError_t launch_gemm_f64(int a_nt, int64_t ni, int64_t nj, int64_t K, double alpha, const double *A, int64_t lda,
-                           const double *B, int64_t ldb, double beta, double *C, int64_t ldc, hipStream_t stream);
+                           const double *B, int64_t ldb, double beta, double *C, int64_t ldc, hipStream_t stream,
+                           int b_nt = 0);
 
 // Sparse inputs (knm_sparse.hip): the two sweeps of one (X, C, sigma) for CSR X and C, prepared once
 // (structure check, norms, centre lists per feature, accumulators) and then applied any number
@@ -146,7 +149,7 @@ struct SparseProducts {
     int t_w(const float *W, const float *wgt, int t, float *U);   // U (M x t) = K^T (wgt .* W)
 };
 int sparse_kmm(struct ::knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M,
-               int64_t d, float sigma, double jitter, double *K);
+               int64_t d, float sigma, double jitter, double *K, int64_t ldk);
 
 } // namespace knm
 

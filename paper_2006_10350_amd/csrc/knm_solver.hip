@@ -2,8 +2,14 @@
 //
 // Everything here is fp64 and runs once per fit or is O(M^2) per iteration; the
 // O(n M) work of every iteration is the fp32 kernel product of the sweep engines.
-// Storage is column-major: T and A are upper triangular with T^T T = K_MM + jitter I and
-// A^T A = T T^T / M + lambda I  (Eq. 7 with K_mm = T^T T).  The factorisations are the block
+// T and A are upper triangular with T^T T = K_MM + jitter I and A^T A = T T^T / M + lambda I
+// (Eq. 7 with K_mm = T^T T).  Both live in ONE column-major array of leading dimension ld = M + 2
+// (M + 3 for odd M), as in the paper's in-place preconditioner (Sec. 3.1, the figure of the memory
+// layout): T in the upper triangle, T(r, c) at r + c ld, and the transpose of A two rows below the
+// diagonal, A(r, c) at 2 + c + r ld (a lower triangle; the two rows keep both diagonals and leave
+// every column 16-byte aligned).  Code that works on either factor addresses entry (r, c), r <= c,
+// of an upper factor R as base[r + c ld] ("upper storage") or base[c + r ld] ("lower storage").
+// The factorisations are the block
 // column update of Sec. 4 on the fp64 matrix-core products of knm_dsyrk.hip and a leaf
 // kernel; the triangular solves, vector updates and reductions are kernels of this file.
 #include <chrono>
@@ -18,8 +24,10 @@ struct knm_precond {
     int device = 0;
     int64_t M = 0;
     double lambda = 0.0, jitter = 0.0;
-    double *T = nullptr; // column-major M x M, upper triangle valid, strict lower zero
-    double *A = nullptr;
+    double *buf = nullptr; // the shared array, ld x M doubles
+    int64_t ld = 0;
+    double *T = nullptr;   // = buf: upper storage
+    double *A = nullptr;   // = buf + 2: lower storage (what is in memory is A^T, a lower triangle)
     // inverses of the sb x sb diagonal blocks of T and A (column-major blocks, each mirrored onto
     // its lower triangle, the last one padded with the identity), used by the blocked
     // triangular solves; xw (M entries) stages the solved blocks
@@ -33,13 +41,12 @@ namespace {
 
 using namespace knm;
 
-// Upper triangle (column-major, r <= c) of K[r, c] = k(c_r, c_c) + jitter [r == c], fp64, direct
+// Upper triangle (column-major with leading dimension ldk, r <= c) of K[r, c] = k(c_r, c_c) + jitter [r == c], fp64, direct
 // differences: k = exp(-|c_r - c_c|^2 scale) with scale = 1 / (2 sigma^2) for the Gaussian kernel; for the
 // kernels of r = |c_r - c_c|, with u = r scale: exp(-u), scale = 1 / sigma (Laplacian);
-// (1 + u) exp(-u), scale = sqrt(3) / sigma; (1 + u + u^2 / 3) exp(-u), scale = sqrt(5) / sigma (Matern).  The factorisation reads nothing below the diagonal, which is
-// zeroed once the factor is there.
+// (1 + u) exp(-u), scale = sqrt(3) / sigma; (1 + u + u^2 / 3) exp(-u), scale = sqrt(5) / sigma (Matern).  The factorisation reads nothing below the diagonal.
 __global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_t ldc, int kind, double scale,
-                           double jitter, double *__restrict__ K)
+                           double jitter, double *__restrict__ K, int64_t ldk)
 {
     if ((int64_t)blockIdx.x * blockDim.x > (int64_t)blockIdx.y * blockDim.y + (blockDim.y - 1)) return; // below
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -61,26 +68,16 @@ __global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_
         v = poly * exp(-u);
     }
     if (r == c) v += jitter;
-    K[r + c * M] = v;
-}
-
-// zero the strict lower triangle (column-major) and optionally add `shift` to the diagonal
-__global__ void tri_fix_kernel(double *A, int64_t M, double shift, int zero_lower)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; // row
-    const int64_t j = (int64_t)blockIdx.y * blockDim.y + threadIdx.y; // column
-    if (i >= M || j >= M) return;
-    if (i > j && zero_lower) A[i + j * M] = 0.0;
-    if (i == j && shift != 0.0) A[i + j * M] += shift;
+    K[r + c * ldk] = v;
 }
 
 // first (1-based) index whose diagonal entry is not a positive finite number, else unchanged;
 // catches NaN/Inf pivots, which a "pivot <= 0" test inside the factorisation lets through
-__global__ void diag_check_kernel(const double *__restrict__ A, int64_t M, unsigned long long *bad)
+__global__ void diag_check_kernel(const double *__restrict__ A, int64_t lda, int64_t M, unsigned long long *bad)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= M) return;
-    const double v = A[i + i * M];
+    const double v = A[i + i * lda]; // the diagonal sits at the same place in upper and lower storage
     if (!(v > 0.0) || !(v < 1.0e300)) atomicMin(bad, (unsigned long long)(i + 1));
 }
 
@@ -177,25 +174,27 @@ constexpr int kPanelWaves = 8;  // wavefronts of a panel_update_n workgroup, sha
 constexpr int kPanelRows = 64;  // rows of a panel_update_n workgroup, one per lane
 constexpr int kPanelCols = 4;   // columns of one panel_update_t wavefront
 
-// b[r] -= sum_j R[r, k0 + j] x[j] for r in [0, k0)  (x = the solved block, nbk entries).
-// Workgroups past the row range copy x into b[k0 : k0 + nbk].
+// b[r] -= sum_j P[r + (k0 + j) ld] x[j] for r in [r_lo, r_hi)  (x = the solved block, nbk entries): the
+// rows above the block of an upper-storage factor in its plain solve, the rows below the block of a
+// lower-storage factor in its transposed solve.  Workgroups past the row range copy x into
+// b[k0 : k0 + nbk].
 __global__ __launch_bounds__(kPanelWaves * 64) void panel_update_n_kernel(const double *__restrict__ R, int64_t M,
-                                                                         int64_t k0, int nbk,
-                                                                         const double *__restrict__ x,
+                                                                         int64_t k0, int nbk, int64_t r_lo,
+                                                                         int64_t r_hi, const double *__restrict__ x,
                                                                          double *__restrict__ b)
 {
     __shared__ double part[kPanelWaves][kPanelRows];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t row_groups = (k0 + kPanelRows - 1) / kPanelRows;
+    const int64_t row_groups = (r_hi - r_lo + kPanelRows - 1) / kPanelRows;
     if ((int64_t)blockIdx.x >= row_groups) {
         const int64_t i = ((int64_t)blockIdx.x - row_groups) * blockDim.x + threadIdx.x;
         if (i < nbk) b[k0 + i] = x[i];
         return;
     }
-    const int64_t r = (int64_t)blockIdx.x * kPanelRows + lane;
-    const bool live = r < k0;
-    const double *p = R + (live ? r : 0) + k0 * M;
+    const int64_t r = r_lo + (int64_t)blockIdx.x * kPanelRows + lane;
+    const bool live = r < r_hi;
+    const double *p = R + (live ? r : r_lo) + k0 * M;
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
     int j = w;
     for (; j + 7 * kPanelWaves < nbk; j += 8 * kPanelWaves) {
@@ -226,15 +225,16 @@ __global__ __launch_bounds__(kPanelWaves * 64) void panel_update_n_kernel(const 
     }
 }
 
-// b[j] -= sum_i R[k0 + i, j] x[i] for j in [j0, M)  (x = the solved block, nbk entries): one
-// wavefront per kPanelCols columns, lanes along the rows.  Workgroups past the column range copy
-// x into b[k0 : k0 + nbk].
+// b[j] -= sum_i P[(k0 + i) + j ld] x[i] for j in [j0, j1)  (x = the solved block, nbk entries): the
+// columns right of the block of an upper-storage factor in its transposed solve, the columns left of
+// the block of a lower-storage factor in its plain solve.  One wavefront per kPanelCols columns, lanes
+// along the rows.  Workgroups past the column range copy x into b[k0 : k0 + nbk].
 __global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__restrict__ R, int64_t M, int64_t k0,
-                                                            int nbk, int64_t j0, const double *__restrict__ x,
-                                                            double *__restrict__ b)
+                                                            int nbk, int64_t j0, int64_t j1,
+                                                            const double *__restrict__ x, double *__restrict__ b)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t col_groups = (M - j0 + 4 * kPanelCols - 1) / (4 * kPanelCols);
+    const int64_t col_groups = (j1 - j0 + 4 * kPanelCols - 1) / (4 * kPanelCols);
     if ((int64_t)blockIdx.x >= col_groups) {
         const int64_t i = ((int64_t)blockIdx.x - col_groups) * blockDim.x + threadIdx.x;
         if (i < nbk) b[k0 + i] = x[i];
@@ -242,12 +242,12 @@ __global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__res
     }
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t jb = j0 + wave * kPanelCols;
-    if (jb >= M) return;
+    if (jb >= j1) return;
     const double *p[kPanelCols];
     double s[kPanelCols];
 #pragma unroll
     for (int c = 0; c < kPanelCols; ++c) {
-        const int64_t j = (jb + c < M) ? jb + c : M - 1; // a clamped column is computed and dropped
+        const int64_t j = (jb + c < j1) ? jb + c : j1 - 1; // a clamped column is computed and dropped
         p[c] = R + k0 + j * M;
         s[c] = 0.0;
     }
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__res
 #pragma unroll
     for (int c = 0; c < kPanelCols; ++c) {
         const double tot = wave_sum(s[c]);
-        if (lane == 0 && jb + c < M) b[jb + c] -= tot;
+        if (lane == 0 && jb + c < j1) b[jb + c] -= tot;
     }
 }
 
@@ -294,11 +294,14 @@ struct LeafShared {
 
 __device__ __forceinline__ int leaf_row_start(int i, int nb) { return i * nb - i * (i - 1) / 2; }
 
-__device__ __forceinline__ void leaf_load(LeafShared &sh, const double *A, int64_t lda, int nb)
+// entry (i, j), i <= j, of the block at A: A[i + j lda] (upper storage) or A[j + i lda] (lower)
+__device__ __forceinline__ void leaf_load(LeafShared &sh, const double *A, int64_t lda, int nb, int lower)
 {
     for (int e = threadIdx.x; e < nb * kLeaf; e += kLeafThreads) {
-        const int i = e & (kLeaf - 1), j = e >> 7; // column j of the block, row i
-        if (i <= j && i < nb) sh.P[leaf_row_start(i, nb) + (j - i)] = A[i + j * lda];
+        // upper storage: column j of the block, row i contiguous; lower: row i, column j contiguous
+        const int u = e & (kLeaf - 1), w = e >> 7;
+        const int i = lower ? w : u, j = lower ? u : w;
+        if (i <= j && j < nb) sh.P[leaf_row_start(i, nb) + (j - i)] = A[u + w * lda];
     }
 }
 
@@ -346,16 +349,17 @@ __device__ __forceinline__ void leaf_invert(LeafShared &sh, int nb, double *W, i
     }
 }
 
-// Upper triangle of the nb x nb block at A (column-major, lda) <- its Cholesky factor R, R^T R = A;
-// W <- R^-1.  *bad <- min(*bad, pivot0 + k + 1) for a pivot k that is not a positive finite number
+// Triangle of the nb x nb block at A (upper or lower storage, lda) <- its upper Cholesky factor R,
+// R^T R = A, in the same storage; W <- R^-1 (always column-major, upper).  *bad <- min(*bad, pivot0 + k + 1) for a pivot k that is not a positive finite number
 // (the factorisation then goes on with 1 in its place; the caller discards the result).
 __global__ __launch_bounds__(kLeafThreads) void potrf_trtri_leaf_kernel(double *__restrict__ A, int64_t lda, int nb,
                                                                        double *__restrict__ W, int64_t ldw,
-                                                                       int64_t pivot0, unsigned long long *bad)
+                                                                       int64_t pivot0, unsigned long long *bad,
+                                                                       int lower)
 {
     __shared__ LeafShared sh;
     const int tid = threadIdx.x;
-    leaf_load(sh, A, lda, nb);
+    leaf_load(sh, A, lda, nb, lower);
     __syncthreads();
     const int jc = tid & (kLeaf - 1), par = tid >> 7; // trailing update: column of this thread, rows par mod 4
     for (int k = 0; k < nb; ++k) {
@@ -392,8 +396,9 @@ __global__ __launch_bounds__(kLeafThreads) void potrf_trtri_leaf_kernel(double *
     }
     // back to A, with the diagonal of R: sh.P still holds the pivots before the square root
     for (int e = tid; e < nb * kLeaf; e += kLeafThreads) {
-        const int i = e & (kLeaf - 1), j = e >> 7;
-        if (i <= j && i < nb) A[i + j * lda] = (i == j) ? 1.0 / sh.dinv[i] : sh.P[leaf_row_start(i, nb) + (j - i)];
+        const int u = e & (kLeaf - 1), w = e >> 7;
+        const int i = lower ? w : u, j = lower ? u : w;
+        if (i <= j && j < nb) A[u + w * lda] = (i == j) ? 1.0 / sh.dinv[i] : sh.P[leaf_row_start(i, nb) + (j - i)];
     }
     __syncthreads();
     leaf_invert(sh, nb, W, ldw);
@@ -403,7 +408,7 @@ __global__ __launch_bounds__(kLeafThreads) void potrf_trtri_leaf_kernel(double *
 // block): leaf g sits on the diagonal of group g / blocks_per_group, at offset (g % blocks_per_group) * 128
 __global__ __launch_bounds__(kLeafThreads) void trtri_leaf_kernel(const double *__restrict__ R, int64_t ldr, int64_t M,
                                                                  int64_t step_w_block, int blocks_per_group,
-                                                                 double *__restrict__ W, int64_t ldw)
+                                                                 double *__restrict__ W, int64_t ldw, int lower)
 {
     __shared__ LeafShared sh;
     const int64_t g = blockIdx.x;
@@ -412,7 +417,7 @@ __global__ __launch_bounds__(kLeafThreads) void trtri_leaf_kernel(const double *
     const double *Rb = R + r0 + r0 * ldr;
     const int64_t grp = g / blocks_per_group, off = (g % blocks_per_group) * kLeaf;
     double *Wb = W + grp * step_w_block + off + off * ldw;
-    leaf_load(sh, Rb, ldr, nb);
+    leaf_load(sh, Rb, ldr, nb, lower);
     for (int k = threadIdx.x; k < nb; k += kLeafThreads) sh.dinv[k] = 1.0 / Rb[k + k * ldr];
     __syncthreads();
     leaf_invert(sh, nb, Wb, ldw);
@@ -550,10 +555,13 @@ struct DevBuf {
 };
 
 // B <- op(R)^-1 B for column-major B (M x t); S = mirrored inverses of the diagonal blocks of R
-// (R = p->T or p->A).  p->xw stages each solved block; solves on one context are stream-ordered.
+// (R = p->T, upper storage, or p->A, lower storage).  p->xw stages each solved block; solves on one
+// context are stream-ordered.  Either storage streams its panels along contiguous columns of the
+// array: what is a row update for one is a column update for the other.
 int tri_solve(knm_ctx *ctx, const knm_precond *p, const double *R, const double *S, bool trans, double *B, int t)
 {
-    const int64_t M = p->M;
+    const int64_t M = p->M, ld = p->ld;
+    const bool lower = (R == p->A);
     const int sb = p->sb;
     const int64_t nblk = (M + sb - 1) / sb;
     for (int c = 0; c < t; ++c) {
@@ -565,17 +573,18 @@ int tri_solve(knm_ctx *ctx, const knm_precond *p, const double *R, const double 
             double *x = p->xw + k0;
             hipLaunchKernelGGL(diag_apply_kernel, dim3((unsigned)((nbk + 3) / 4)), dim3(256), 0, ctx->stream,
                                S + k * sb * sb, sb, nbk, trans ? 0 : 1, b + k0, x);
-            if (!trans) {
-                const int64_t groups = (k0 + kPanelRows - 1) / kPanelRows;
+            // the entries of b still to be solved: before the block (plain) or after it (transposed)
+            const int64_t lo = trans ? k0 + nbk : 0, hi = trans ? M : k0;
+            if (trans == lower) { // panel entries R(r, k0 + j) or R(k0 + j, r) contiguous in r
+                const int64_t groups = (hi - lo + kPanelRows - 1) / kPanelRows;
                 const int64_t copy = (nbk + kPanelWaves * 64 - 1) / (kPanelWaves * 64);
                 hipLaunchKernelGGL(panel_update_n_kernel, dim3((unsigned)(groups + copy)), dim3(kPanelWaves * 64), 0,
-                                   ctx->stream, R, M, k0, nbk, x, b);
-            } else {
-                const int64_t j0 = k0 + nbk;
-                const int64_t groups = (M - j0 + 4 * kPanelCols - 1) / (4 * kPanelCols);
+                                   ctx->stream, R, ld, k0, nbk, lo, hi, x, b);
+            } else {              // contiguous in the block's own index
+                const int64_t groups = (hi - lo + 4 * kPanelCols - 1) / (4 * kPanelCols);
                 const int64_t copy = (nbk + 255) / 256;
                 hipLaunchKernelGGL(panel_update_t_kernel, dim3((unsigned)(groups + copy)), dim3(256), 0, ctx->stream,
-                                   R, M, k0, nbk, j0, x, b);
+                                   R, ld, k0, nbk, lo, hi, x, b);
             }
         }
     }
@@ -584,22 +593,23 @@ int tri_solve(knm_ctx *ctx, const knm_precond *p, const double *R, const double 
     return KNM_OK;
 }
 
-// S <- mirrored inverses of the sb x sb diagonal blocks of the upper-triangular R.  The 128 x 128
+// S <- mirrored inverses of the sb x sb diagonal blocks of the upper-triangular R (p->T or p->A).  The 128 x 128
 // diagonal blocks are inverted by the leaf kernel (one workgroup each); neighbouring inverses are
 // then merged level by level,  inv([R11 R12; 0 R22]) = [W11, -W11 R12 W22; 0, W22],  with two
 // block products per pair, until the blocks are sb wide; last the upper triangle of every
 // block is copied onto its lower.  `tmp` holds (sb / 2)^2 doubles.
 int invert_diag_blocks(knm_ctx *ctx, const knm_precond *p, const double *R, double *S, double *tmp)
 {
-    const int64_t M = p->M;
+    const int64_t M = p->M, ld = p->ld;
+    const int lower = (R == p->A) ? 1 : 0;
     const int sb = p->sb;
     const int64_t nblk = (M + sb - 1) / sb;
     const int64_t block = (int64_t)sb * sb;
     hipError_t e = hipMemsetAsync(S, 0, sizeof(double) * nblk * block, ctx->stream);
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
     const int64_t leaves = (M + kLeaf - 1) / kLeaf;
-    hipLaunchKernelGGL(trtri_leaf_kernel, dim3((unsigned)leaves), dim3(kLeafThreads), 0, ctx->stream, R, M, M, block,
-                       sb / kLeaf, S, (int64_t)sb);
+    hipLaunchKernelGGL(trtri_leaf_kernel, dim3((unsigned)leaves), dim3(kLeafThreads), 0, ctx->stream, R, ld, M, block,
+                       sb / kLeaf, S, (int64_t)sb, lower);
     for (int64_t h = kLeaf; h < sb; h *= 2) {
         for (int64_t k = 0; k < nblk; ++k) {
             const int64_t k0 = k * sb;
@@ -607,11 +617,13 @@ int invert_diag_blocks(knm_ctx *ctx, const knm_precond *p, const double *R, doub
             double *Sk = S + k * block;
             for (int64_t off = 0; off + h < nbk; off += 2 * h) {
                 const int64_t h2 = (nbk - off - h < h) ? nbk - off - h : h; // order of the second block of the pair
-                const double *R12 = R + (k0 + off) + (size_t)(k0 + off + h) * M;
+                // R12 (h x h2): entry (i, k) at R12[i + k ld] in upper storage, R12[k + i ld] in lower
+                const double *R12 = lower ? R + (k0 + off + h) + (size_t)(k0 + off) * ld
+                                          : R + (k0 + off) + (size_t)(k0 + off + h) * ld;
                 const double *W11 = Sk + off + off * sb;
                 const double *W22 = Sk + (off + h) + (off + h) * sb;
                 double *W12 = Sk + off + (off + h) * sb;
-                if (launch_gemm_f64(1, h, h2, h2, 1.0, R12, M, W22, sb, 0.0, tmp, h, ctx->stream) != hipSuccess ||
+                if (launch_gemm_f64(lower ? 0 : 1, h, h2, h2, 1.0, R12, ld, W22, sb, 0.0, tmp, h, ctx->stream) != hipSuccess ||
                     launch_gemm_f64(1, h, h2, h, -1.0, W11, sb, tmp, h, 0.0, W12, sb, ctx->stream) != hipSuccess)
                     return fail(ctx, KNM_HIP_ERROR, "inverse merge launch");
             }
@@ -765,8 +777,7 @@ int precond_free(knm_precond *p)
 {
     if (!p) return KNM_INVALID_ARG;
     (void)hipSetDevice(p->device);
-    if (p->T) (void)hipFree(p->T);
-    if (p->A) (void)hipFree(p->A);
+    if (p->buf) (void)hipFree(p->buf);
     if (p->Tdinv) (void)hipFree(p->Tdinv);
     if (p->Adinv) (void)hipFree(p->Adinv);
     if (p->xw) (void)hipFree(p->xw);
@@ -774,7 +785,7 @@ int precond_free(knm_precond *p)
     return KNM_OK;
 }
 
-// Upper Cholesky factor in place, R^T R = A (column-major, leading dimension M): the three-step
+// Upper Cholesky factor in place, R^T R = A (upper or lower storage, leading dimension ld): the three-step
 // column update of Sec. 4 (block Cholesky paragraph) on block rows of up to 4096.
 //   Steps 1 and 2 (factor the diagonal tile, solve the block row against it) are carried out
 //   together, left-looking over sub-panels of 512 rows and, inside them, steps of 128 rows: a
@@ -820,8 +831,12 @@ static int aux_stream(knm_ctx *ctx, hipStream_t *out)
     return KNM_OK;
 }
 
-static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, unsigned long long *bad,
-                              int64_t *first_bad)
+// `lower`: the factor and the matrix it replaces are in lower storage (entry (r, c), r <= c, at
+// A[c + r ld]); every product below then has its two index roles exchanged, and the pieces of a
+// block row that straddle the diagonal are split into a symmetric update (which writes one triangle
+// only) and a rectangle, because the other triangle belongs to the other factor.
+static int chol_blocked(knm_ctx *ctx, double *A, int64_t ld, int64_t M, bool lower, double *W, unsigned long long *bad,
+                        int64_t *first_bad)
 {
     int64_t b = ((M + 7) / 8 + 255) / 256 * 256;
     if (b > 4096) b = 4096;
@@ -835,6 +850,22 @@ static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, uns
     EventSet ev_rows, ev_rest;
     if (!ev_rows.create(nb) || !ev_rest.create(nb)) return fail(ctx, KNM_HIP_ERROR, "hipEventCreate");
     std::vector<char> have_rest(nb, 0);
+    // entry (r, c) of the matrix, r <= c
+    auto at = [&](int64_t r, int64_t c) { return lower ? A + c + (size_t)r * ld : A + r + (size_t)c * ld; };
+    // rows [row, row + nr) of the columns from `col` on lose the products with rows [top, top + K)
+    // of the same columns: R(row + i, col + j) -= sum_k R(top + k, row + i) R(top + k, col + j).
+    // Here col == row: the nr x nr block on the diagonal and the rectangle to its right.
+    auto update_rows = [&](int64_t top, int64_t K, int64_t row, int64_t nr) -> bool {
+        const int64_t ncols = M - row;
+        if (!lower) // upper storage: one product; what it writes below the diagonal block's diagonal is unused space
+            return launch_gemm_f64(0, nr, ncols, K, -1.0, at(top, row), ld, at(top, row), ld, 1.0, at(row, row), ld,
+                                   ctx->stream) == hipSuccess;
+        const double *P = at(top, row); // element (top + k, row + x) at P[x + k ld]
+        if (launch_rank_k_upper(1, nr, K, -1.0, P, ld, nullptr, 0, 1.0, 0.0, at(row, row), ld, ctx->stream, 1) != hipSuccess)
+            return false;
+        return ncols == nr || launch_gemm_f64(1, ncols - nr, nr, K, -1.0, P + nr, ld, P, ld, 1.0, at(row, row + nr), ld,
+                                              ctx->stream, 1) == hipSuccess;
+    };
     for (int64_t k = 0; k < nb; ++k) {
         const int64_t r0 = k * b;
         const int64_t w = (M - r0 < b) ? M - r0 : b;
@@ -843,30 +874,21 @@ static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, uns
             // (four tile rows per launch); inside it the 128-row steps only reach back to its top
             const int64_t sw = (w - S0 < kSubPanel) ? w - S0 : kSubPanel;
             const int64_t prow = r0 + S0;
-            if (S0 > 0) {
-                const double *above = A + r0 + (size_t)prow * M; // rows r0 .. prow of the columns from `prow` on
-                if (launch_gemm_f64(0, sw, M - prow, S0, -1.0, above, M, above, M, 1.0, A + prow + (size_t)prow * M, M,
-                                    ctx->stream) != hipSuccess)
-                    return fail(ctx, KNM_HIP_ERROR, "block row update launch");
-            }
+            if (S0 > 0 && !update_rows(r0, S0, prow, sw)) return fail(ctx, KNM_HIP_ERROR, "block row update launch");
             for (int64_t s0 = 0; s0 < sw; s0 += kLeaf) {
                 const int64_t row = prow + s0;
                 const int nbk = (int)((sw - s0 < kLeaf) ? sw - s0 : kLeaf);
                 const int64_t ncols = M - row;
-                double *Ass = A + row + (size_t)row * M;
-                if (s0 > 0) {
-                    const double *above = A + prow + (size_t)row * M;
-                    if (launch_gemm_f64(0, nbk, ncols, s0, -1.0, above, M, above, M, 1.0, Ass, M, ctx->stream) !=
-                        hipSuccess)
-                        return fail(ctx, KNM_HIP_ERROR, "block row update launch");
-                }
-                hipLaunchKernelGGL(potrf_trtri_leaf_kernel, dim3(1), dim3(kLeafThreads), 0, ctx->stream, Ass, M, nbk, W,
-                                   (int64_t)kLeaf, row, bad);
+                if (s0 > 0 && !update_rows(prow, s0, row, nbk)) return fail(ctx, KNM_HIP_ERROR, "block row update launch");
+                hipLaunchKernelGGL(potrf_trtri_leaf_kernel, dim3(1), dim3(kLeafThreads), 0, ctx->stream, at(row, row), ld, nbk,
+                                   W, (int64_t)kLeaf, row, bad, lower ? 1 : 0);
                 if (ncols > nbk) {
-                    double *right = A + row + (size_t)(row + nbk) * M;
-                    if (launch_gemm_f64(0, nbk, ncols - nbk, nbk, 1.0, W, kLeaf, right, M, 0.0, right, M,
-                                        ctx->stream) != hipSuccess)
-                        return fail(ctx, KNM_HIP_ERROR, "block row solve launch");
+                    // the rest of the rows times the inverse: R(row + i, c) <- sum_k W(k, i) R(row + k, c)
+                    double *right = at(row, row + nbk);
+                    const hipError_t le =
+                        lower ? launch_gemm_f64(1, ncols - nbk, nbk, nbk, 1.0, right, ld, W, kLeaf, 0.0, right, ld, ctx->stream)
+                              : launch_gemm_f64(0, nbk, ncols - nbk, nbk, 1.0, W, kLeaf, right, ld, 0.0, right, ld, ctx->stream);
+                    if (le != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "block row solve launch");
                 }
             }
         }
@@ -877,21 +899,24 @@ static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, uns
         // steps 1 and 2 of that block row; the remainder (most of the flop) runs on the second
         // stream meanwhile and fills the chip, which those short dependent launches cannot.
         const int64_t w2 = (rest < b) ? rest : b;
-        const double *Akr = A + r0 + (size_t)(r0 + w) * M; // block row to the right of the diagonal block
-        double *Arr = A + (r0 + w) + (size_t)(r0 + w) * M;
+        const int64_t c0 = r0 + w;                 // first trailing row and column
+        const double *Akr = at(r0, c0);            // block row to the right of the diagonal block
+        const double *Akr2 = at(r0, c0 + w2);
+        const int form = lower ? 1 : 0, tc = lower ? 1 : 0;
         if (hipEventRecord(ev_rows[k], ctx->stream) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipEventRecord");
         if (k > 0 && have_rest[k - 1] && hipStreamWaitEvent(ctx->stream, ev_rest[k - 1], 0) != hipSuccess)
             return fail(ctx, KNM_HIP_ERROR, "hipStreamWaitEvent");
-        if (launch_rank_k_upper(0, w2, w, -1.0, Akr, M, nullptr, 0, 1.0, 0.0, Arr, M, ctx->stream) != hipSuccess)
+        if (launch_rank_k_upper(form, w2, w, -1.0, Akr, ld, nullptr, 0, 1.0, 0.0, at(c0, c0), ld, ctx->stream, tc) != hipSuccess)
             return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
         if (rest > w2) {
-            const double *Akr2 = Akr + (size_t)w2 * M;
-            if (launch_gemm_f64(0, w2, rest - w2, w, -1.0, Akr, M, Akr2, M, 1.0, Arr + (size_t)w2 * M, M, ctx->stream) !=
-                hipSuccess)
-                return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
+            // R(c0 + i, c0 + w2 + j) -= sum_k R(r0 + k, c0 + i) R(r0 + k, c0 + w2 + j)
+            const hipError_t le =
+                lower ? launch_gemm_f64(1, rest - w2, w2, w, -1.0, Akr2, ld, Akr, ld, 1.0, at(c0, c0 + w2), ld, ctx->stream, 1)
+                      : launch_gemm_f64(0, w2, rest - w2, w, -1.0, Akr, ld, Akr2, ld, 1.0, at(c0, c0 + w2), ld, ctx->stream);
+            if (le != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
             if (hipStreamWaitEvent(aux, ev_rows[k], 0) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipStreamWaitEvent");
-            if (launch_rank_k_upper(0, rest - w2, w, -1.0, Akr2, M, nullptr, 0, 1.0, 0.0, Arr + w2 + (size_t)w2 * M, M,
-                                    aux) != hipSuccess)
+            if (launch_rank_k_upper(form, rest - w2, w, -1.0, Akr2, ld, nullptr, 0, 1.0, 0.0, at(c0 + w2, c0 + w2), ld, aux,
+                                    tc) != hipSuccess)
                 return fail(ctx, KNM_HIP_ERROR, "trailing update launch");
             if (hipEventRecord(ev_rest[k], aux) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipEventRecord");
             have_rest[k] = 1;
@@ -916,7 +941,8 @@ static int chol_upper_blocked(knm_ctx *ctx, double *A, int64_t M, double *W, uns
 // A <- upper Cholesky factor of T D T^T / M + lambda I, D = diag(dw) (identity if dw is null), and
 // the inverses of its diagonal blocks.  T is upper triangular, so entry (i, j) of the product
 // only sums over k >= max(i, j): M^3 / 3 flop instead of the M^3 of a dense rank-M update,
-// in one launch of the rank-k kernel, which skips the vanishing part tile by tile.
+// in one launch of the rank-k kernel, which skips the vanishing part tile by tile.  The product is
+// written mirrored, into the lower storage of A beside T, and factorised there in place.
 static int build_second_factor(knm_ctx *ctx, knm_precond *p, double lambda, const double *dw,
                                int64_t *bad_pivot)
 {
@@ -926,19 +952,18 @@ static int build_second_factor(knm_ctx *ctx, knm_precond *p, double lambda, cons
     int st = leaf.alloc(ctx, sizeof(double) * kLeaf * kLeaf);
     if (!st) st = badbuf.alloc(ctx, sizeof(unsigned long long));
     if (st) return st;
-    if (launch_rank_k_upper(1, M, M, 1.0 / (double)M, p->T, M, dw, 1, 0.0, lambda, p->A, M, ctx->stream) != hipSuccess)
+    if (launch_rank_k_upper(1, M, M, 1.0 / (double)M, p->T, p->ld, dw, 1, 0.0, lambda, p->A, p->ld, ctx->stream, 1) !=
+        hipSuccess)
         return fail(ctx, KNM_HIP_ERROR, "triangular product launch");
-    const dim3 fb(32, 8);
-    const dim3 fg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
     int64_t pivot = 0;
-    st = chol_upper_blocked(ctx, p->A, M, leaf.as<double>(), badbuf.as<unsigned long long>(), &pivot);
+    st = chol_blocked(ctx, p->A, p->ld, M, true, leaf.as<double>(), badbuf.as<unsigned long long>(), &pivot);
     if (st) return st;
     if (pivot == 0) {
         const unsigned long long none = ~0ull;
         unsigned long long got = none;
         hipError_t err = hipMemcpyAsync(badbuf.p, &none, sizeof(none), hipMemcpyHostToDevice, ctx->stream);
         if (err == hipSuccess) {
-            hipLaunchKernelGGL(diag_check_kernel, grid1(M), dim3(256), 0, ctx->stream, p->A, M,
+            hipLaunchKernelGGL(diag_check_kernel, grid1(M), dim3(256), 0, ctx->stream, p->A, p->ld, M,
                                badbuf.as<unsigned long long>());
             err = hipMemcpyAsync(&got, badbuf.p, sizeof(got), hipMemcpyDeviceToHost, ctx->stream);
         }
@@ -950,7 +975,6 @@ static int build_second_factor(knm_ctx *ctx, knm_precond *p, double lambda, cons
         *bad_pivot = pivot;
         return fail(ctx, KNM_NOT_PD, "T D T^T / M + lambda I is not positive definite");
     }
-    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->A, M, 0.0, 1);
     DevBuf merge;
     st = merge.alloc(ctx, sizeof(double) * (size_t)(p->sb / 2) * (size_t)(p->sb / 2));
     if (!st) st = invert_diag_blocks(ctx, p, p->A, p->Adinv, merge.as<double>());
@@ -961,8 +985,8 @@ static int build_second_factor(knm_ctx *ctx, knm_precond *p, double lambda, cons
     return KNM_OK;
 }
 
-// fill_kmm writes the upper triangle of K_MM + jitter I (column-major, leading dimension M) into its argument
-static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(double *)> &fill_kmm, double lambda,
+// fill_kmm(K, ldk) writes the upper triangle of K_MM + jitter I (column-major, leading dimension ldk)
+static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(double *, int64_t)> &fill_kmm, double lambda,
                               double jitter, bool second_factor, knm_precond **out, int64_t *bad_pivot_or_null)
 {
     if (!ctx) return KNM_INVALID_ARG;
@@ -980,9 +1004,11 @@ static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(d
     p->M = M;
     p->lambda = lambda;
     p->jitter = jitter;
-    const size_t bytes = sizeof(double) * (size_t)M * (size_t)M;
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(&p->T), bytes);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->A), bytes);
+    p->ld = M + 2 + (M & 1); // even: every column of either factor starts 16-byte aligned
+    const size_t bytes = sizeof(double) * (size_t)p->ld * (size_t)M;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&p->buf), bytes);
+    p->T = p->buf;
+    p->A = p->buf ? p->buf + 2 : nullptr;
     p->sb = solve_block_width(M);
     const int64_t nblk = (M + p->sb - 1) / p->sb;
     const size_t dbytes = sizeof(double) * (size_t)nblk * p->sb * p->sb;
@@ -1000,7 +1026,7 @@ static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(d
         return fail(ctx, status, what);
     };
 
-    st = fill_kmm(p->T);
+    st = fill_kmm(p->T, p->ld);
     if (st) {
         precond_free(p);
         return st;
@@ -1014,7 +1040,7 @@ static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(d
         unsigned long long got = none;
         hipError_t err = hipMemcpyAsync(badbuf.p, &none, sizeof(none), hipMemcpyHostToDevice, ctx->stream);
         if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(diag_check_kernel, grid1(M), dim3(256), 0, ctx->stream, F, M,
+        hipLaunchKernelGGL(diag_check_kernel, grid1(M), dim3(256), 0, ctx->stream, F, p->ld, M,
                            badbuf.as<unsigned long long>());
         err = hipMemcpyAsync(&got, badbuf.p, sizeof(got), hipMemcpyDeviceToHost, ctx->stream);
         if (err == hipSuccess) err = hipStreamSynchronize(ctx->stream);
@@ -1024,7 +1050,7 @@ static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(d
 
     int64_t host_info = 0;
     {
-        int st2 = chol_upper_blocked(ctx, p->T, M, leaf.as<double>(), badbuf.as<unsigned long long>(), &host_info);
+        int st2 = chol_blocked(ctx, p->T, p->ld, M, false, leaf.as<double>(), badbuf.as<unsigned long long>(), &host_info);
         if (st2) {
             precond_free(p);
             return st2;
@@ -1036,10 +1062,6 @@ static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(d
         if (bad_pivot_or_null) *bad_pivot_or_null = pivot;
         return bail(KNM_NOT_PD, "K_MM + jitter I is not positive definite");
     }
-    const dim3 fb(32, 8);
-    const dim3 fg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
-    hipLaunchKernelGGL(tri_fix_kernel, fg, fb, 0, ctx->stream, p->T, M, 0.0, 1);
-
     if (hipGetLastError() != hipSuccess) return bail(KNM_HIP_ERROR, "preconditioner kernel launch");
     DevBuf merge;
     st = merge.alloc(ctx, sizeof(double) * (size_t)(p->sb / 2) * (size_t)(p->sb / 2));
@@ -1068,7 +1090,7 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
     if (!ctx) return KNM_INVALID_ARG;
     if (!C || M <= 0 || d <= 0 || ldc < d || !(sigma > 0.0f))
         return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
-    auto fill = [=](double *K) {
+    auto fill = [=](double *K, int64_t ldk) {
         const dim3 tb(32, 8);
         const dim3 tg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
         const int kind = ctx->kernel_kind;
@@ -1076,7 +1098,7 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
                              : kind == KNM_KERNEL_MATERN32 ? sqrt(3.0) / (double)sigma
                              : kind == KNM_KERNEL_MATERN52 ? sqrt(5.0) / (double)sigma
                                                            : 1.0 / (double)sigma;
-        hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, kind, scale, jitter, K);
+        hipLaunchKernelGGL(kmm_kernel, tg, tb, 0, ctx->stream, C, M, d, ldc, kind, scale, jitter, K, ldk);
         return hipGetLastError() == hipSuccess ? KNM_OK : fail(ctx, KNM_HIP_ERROR, "kmm_kernel launch");
     };
     return precond_build_from(ctx, M, fill, lambda, jitter, second_factor, out, bad_pivot_or_null);
@@ -1095,7 +1117,9 @@ int precond_build_csr(knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_in
     if (!ctx) return KNM_INVALID_ARG;
     if (!c_indptr || M <= 0 || d <= 0 || d >= 0x7fffffffLL || !(sigma > 0.0f))
         return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
-    auto fill = [=](double *K) { return sparse_kmm(ctx, c_indptr, c_indices, c_values, M, d, sigma, jitter, K); };
+    auto fill = [=](double *K, int64_t ldk) {
+        return sparse_kmm(ctx, c_indptr, c_indices, c_values, M, d, sigma, jitter, K, ldk);
+    };
     return precond_build_from(ctx, M, fill, lambda, jitter, true, out, bad_pivot_or_null);
 }
 
@@ -1110,10 +1134,13 @@ int precond_get_factors(knm_ctx *ctx, const knm_precond *p, double *T_host, doub
     for (int k = 0; k < 2; ++k) {
         if (!dst[k]) continue;
         hipError_t e = hipStreamSynchronize(ctx->stream);
-        if (e == hipSuccess) e = hipMemcpy(tmp.data(), src[k], sizeof(double) * M * M, hipMemcpyDeviceToHost);
+        if (e == hipSuccess)
+            e = hipMemcpy2D(tmp.data(), sizeof(double) * M, src[k], sizeof(double) * p->ld, sizeof(double) * M, (size_t)M,
+                            hipMemcpyDeviceToHost);
         if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpy(factor)", e);
+        // T: upper storage, entry (i, j) at i + j M of the copy; A: lower storage, at j + i M
         for (int64_t i = 0; i < M; ++i)
-            for (int64_t j = 0; j < M; ++j) dst[k][i * M + j] = (j >= i) ? tmp[i + j * M] : 0.0;
+            for (int64_t j = 0; j < M; ++j) dst[k][i * M + j] = (j >= i) ? (k == 0 ? tmp[i + j * M] : tmp[j + i * M]) : 0.0;
     }
     return KNM_OK;
 }
@@ -1125,17 +1152,25 @@ int precond_get_block(knm_ctx *ctx, const knm_precond *p, int second, int64_t ro
     if (!p || !out_host || row0 < 0 || col0 < 0 || rows <= 0 || cols <= 0 || row0 + rows > p->M || col0 + cols > p->M)
         return fail(ctx, KNM_INVALID_ARG, "bad factor block");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    const int64_t M = p->M;
-    const double *F = second ? p->A : p->T;
-    // the factor is column-major: column c of the block is contiguous, rows of `out_host` are strided
     std::vector<double> tmp((size_t)rows * cols);
     hipError_t e = hipStreamSynchronize(ctx->stream);
-    if (e == hipSuccess)
-        e = hipMemcpy2D(tmp.data(), sizeof(double) * rows, F + row0 + col0 * M, sizeof(double) * M,
-                        sizeof(double) * rows, (size_t)cols, hipMemcpyDeviceToHost);
-    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpy2D(factor block)", e);
-    for (int64_t r = 0; r < rows; ++r)
-        for (int64_t c = 0; c < cols; ++c) out_host[r * cols + c] = (col0 + c >= row0 + r) ? tmp[r + c * rows] : 0.0;
+    if (!second) {
+        // upper storage: column c of the block is contiguous, rows of `out_host` are strided
+        if (e == hipSuccess)
+            e = hipMemcpy2D(tmp.data(), sizeof(double) * rows, p->T + row0 + col0 * p->ld, sizeof(double) * p->ld,
+                            sizeof(double) * rows, (size_t)cols, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpy2D(factor block)", e);
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t c = 0; c < cols; ++c) out_host[r * cols + c] = (col0 + c >= row0 + r) ? tmp[r + c * rows] : 0.0;
+    } else {
+        // lower storage: row r of the block is contiguous
+        if (e == hipSuccess)
+            e = hipMemcpy2D(tmp.data(), sizeof(double) * cols, p->A + col0 + row0 * p->ld, sizeof(double) * p->ld,
+                            sizeof(double) * cols, (size_t)rows, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpy2D(factor block)", e);
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t c = 0; c < cols; ++c) out_host[r * cols + c] = (col0 + c >= row0 + r) ? tmp[c + r * cols] : 0.0;
+    }
     return KNM_OK;
 }
 
@@ -1574,7 +1609,9 @@ int logfalkon_fit_csr(knm_ctx *ctx, const int64_t *x_indptr, const int64_t *x_in
     if (!st) st = spc.prepare(ctx, c_indptr, c_indices, c_values, M, c_indptr, c_indices, c_values, M, d, sigma);
     if (st) return st;
     knm_precond *p = nullptr;
-    auto fill = [=](double *K) { return sparse_kmm(ctx, c_indptr, c_indices, c_values, M, d, sigma, jitter, K); };
+    auto fill = [=](double *K, int64_t ldk) {
+        return sparse_kmm(ctx, c_indptr, c_indices, c_values, M, d, sigma, jitter, K, ldk);
+    };
     st = precond_build_from(ctx, M, fill, lambdas[0], jitter, false, &p, nullptr);
     if (st) return st;
     KernelOps ops;

@@ -523,7 +523,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_sweep_kernel(SparseArgs a)
 inline dim3 grid_for(int64_t n, int threads = 256) { return dim3((unsigned)((n + threads - 1) / threads)); }
 
 // fp64 entries of the centres' kernel matrix, for the preconditioner: row i of the upper triangle
-// (column-major K, leading dimension M) = exp(-(|c_i|^2 + |c_j|^2 - 2 g_ij) / 2 sigma^2) + jitter [i == j],
+// (column-major K, leading dimension ldk) = exp(-(|c_i|^2 + |c_j|^2 - 2 g_ij) / 2 sigma^2) + jitter [i == j],
 // j >= i, with g_ij accumulated in a private fp64 accumulator exactly as in the sweeps (every
 // entry of the accumulator is read and cleared when the row is written out).
 __global__ __launch_bounds__(kSpThreads) void sparse_kmm_kernel(const int64_t *__restrict__ c_indptr,
@@ -534,7 +534,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_kmm_kernel(const int64_t *_
                                                                const float *__restrict__ csc_val,
                                                                const double *__restrict__ cn, double inv2s2,
                                                                double jitter, double *__restrict__ acc_all,
-                                                               double *__restrict__ K)
+                                                               double *__restrict__ K, int64_t ldk)
 {
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * kSpWaves + (threadIdx.x >> 6);
@@ -570,7 +570,7 @@ __global__ __launch_bounds__(kSpThreads) void sparse_kmm_kernel(const int64_t *_
             // written by atomics (at the L2): read and cleared there too, past the first-level cache
             const double g = __hip_atomic_load(&acc[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (g != 0.0) __hip_atomic_store(&acc[j], 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (j >= row) K[row + j * M] = exp(-(ci + cn[j] - 2.0 * g) * inv2s2) + (j == row ? jitter : 0.0);
+            if (j >= row) K[row + j * ldk] = exp(-(ci + cn[j] - 2.0 * g) * inv2s2) + (j == row ? jitter : 0.0);
         }
         accumulator_fence();
     }
@@ -967,9 +967,9 @@ int SparseProducts::t_w(const float *W, const float *wgt, int t, float *U)
     return hipGetLastError() == hipSuccess ? KNM_OK : fail(s.ctx, KNM_HIP_ERROR, "sparse column sweep launch");
 }
 
-// Upper triangle of K (M x M, column-major, fp64) = k(C, C) + jitter I for CSR centres
+// Upper triangle of K (M x M, column-major with leading dimension ldk, fp64) = k(C, C) + jitter I for CSR centres
 int sparse_kmm(knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, const float *c_values, int64_t M,
-               int64_t d, float sigma, double jitter, double *K)
+               int64_t d, float sigma, double jitter, double *K, int64_t ldk)
 {
     if (ctx->kernel_kind != KNM_KERNEL_GAUSSIAN)
         return fail(ctx, KNM_UNSUPPORTED, "sparse inputs: Gaussian kernel only");
@@ -993,7 +993,7 @@ int sparse_kmm(knm_ctx *ctx, const int64_t *c_indptr, const int64_t *c_indices, 
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemsetAsync", e);
     hipLaunchKernelGGL(sparse_kmm_kernel, dim3((unsigned)wgs), dim3(kSpThreads), 0, st, c_indptr, c_indices, c_values, M,
                        lists.col_ptr.as<int>(), lists.csc_row.as<int>(), lists.csc_val.as<float>(), cn.as<double>(),
-                       1.0 / (2.0 * (double)sigma * (double)sigma), jitter, acc.as<double>(), K);
+                       1.0 / (2.0 * (double)sigma * (double)sigma), jitter, acc.as<double>(), K, ldk);
     e = hipStreamSynchronize(st); // the workspace is freed on return
     if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "sparse K_MM", e);

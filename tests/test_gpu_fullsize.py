@@ -172,22 +172,30 @@ def test_billion_point_workload_sampled_outputs(knm):
     assert abs(uv - ww) <= 1e-4 * float(U.double().norm() * v.double().norm())
 
 
-def test_full_size_preconditioner_sampled_entries(knm):
-    """Both factors at M = 100k (80 GB each) against their defining identities on sampled index
+@pytest.mark.parametrize("M", [100_000, 140_001])
+def test_full_size_preconditioner_sampled_entries(knm, M):
+    """Both factors at M = 100k (80 GB in one shared array) and at an odd M = 140001 (157 GB; two
+    separate arrays of that order would not fit the GPU) against their defining identities on sampled index
     pairs: T^T T = K_MM + jitter I entry by entry against the oracle's kernel values, and
     A^T A = T T^T / M + lambda I with the right-hand side summed on the host from rows of T.
     The blocked solves are checked through the adjoint identity c^T (T^-1 A^-1 b) = (A^-T T^-T c)^T b."""
-    w = synth.workload("mid")
+    w = synth.workload("mid", n=1_000_000, M=M)
     jitter = 1e-8
-    inp = synth.make_inputs(w, device="cuda")
+    inp = synth.make_inputs(w, device="cuda", with_targets=False)
     C = inp["C"]
-    M = w.M
+    del inp
     print(f"building the preconditioner: M={M} d={w.d} lambda={w.lam}", flush=True)
+    free0 = torch.cuda.mem_get_info()[0]
     pre = knm.precond_build(C, w.sigma, w.lam, jitter)
-    print("preconditioner built", flush=True)
+    held = free0 - torch.cuda.mem_get_info()[0]
+    print(f"preconditioner built, holds {held / 1e9:.1f} GB", flush=True)
+    assert held < 1.06 * 8.0 * M * M  # one shared array (+ the inverted diagonal blocks), not two
     Cn = C.cpu().numpy()
     g = np.random.default_rng(11)
+    # (rows of a factor are strided in memory and slow to copy out: fewer samples at the larger size)
     idx = np.concatenate([[0, 1, 127, 128, 2047, 2048, 4095, 4096, M - 4097, M - 2, M - 1], g.integers(0, M, 8)])
+    if M > 100_000:
+        idx = np.concatenate([[0, 128, 4095, 4096, M - 4097, M - 1], g.integers(0, M, 2)])
     pairs = [(int(min(a, b)), int(max(a, b))) for a, b in zip(idx, g.permutation(idx))] + [(int(a), int(a)) for a in idx[:6]]
     worst_t = worst_a = 0.0
     for i, j in pairs:

@@ -68,6 +68,12 @@ def test_triangular_operand_and_overwrite(knm, n):
     assert np.abs(got[iu] - ref[iu]).max() <= 1e-13 * np.abs(ref).max() * n
     il = np.tril_indices(n, -1)
     assert np.isnan(got[il]).all()
+    # what is stored below the operand's diagonal is ignored (in the preconditioner's shared array
+    # it belongs to the other factor): NaN there must not reach the result
+    Tn = T.copy()
+    Tn[il] = np.nan
+    got2 = _run(knm, Tn, C0, True, alpha=1.0 / n, beta=0.0, w=w, triangular=True, shift=1e-3)
+    assert np.array_equal(got2[iu], got[iu])
 
 
 @pytest.mark.parametrize("k0", [100, 101])  # operand 16-byte aligned or not: wide and narrow loads
