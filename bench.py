@@ -209,9 +209,9 @@ def counters(workload: str):
 
 def engine_of(w, cross: str, kernel: str):
     """Which tile engine the library runs for this shape (same rule as the library): the K-loop engine
-    for t > 1, for the kernels of the distance, or for d beyond the register-resident engine's limit
-    (44 features with the split-fp16 cross term, the default; 64 with fp32 MFMA)."""
-    k_loop = kernel != "gaussian" or w.t > 1 or w.d > (44 if cross == "f16x3" else 64)
+    for t > 1 or for d beyond the register-resident engine's limit (44 features with the split-fp16
+    cross term, the default, 28 for the kernels of the distance; 64 with fp32 MFMA, Gaussian only)."""
+    k_loop = w.t > 1 or w.d > (44 if cross == "f16x3" else 64) or (kernel != "gaussian" and (cross != "f16x3" or w.d > 28))
     f16 = cross == "f16x3"
     name = (("gauss_gemm_f16_kernel" if f16 else "gauss_gemm_kernel") if k_loop
             else ("gauss_sweep_f16_kernel" if f16 else "gauss_sweep_kernel"))

@@ -67,7 +67,10 @@ static int acquire(knm_ctx *ctx, float **buf, size_t *cur, size_t need, float **
 // selected arithmetic holds (44 features for the split-fp16 one, 64 for fp32)
 bool use_gemm_engine(int d, int t, int cross_term, int kind)
 {
-    return kind != KNM_KERNEL_GAUSSIAN || t > 1 || d > (cross_term == KNM_CROSS_F16X3 ? f16_max_d() : small_max_d());
+    // (the kernels of r = |x - c| run on the register-resident engine only with the split-fp16 cross
+    // term, and up to the d its two smaller layouts hold without register spills)
+    if (kind != KNM_KERNEL_GAUSSIAN && (cross_term != KNM_CROSS_F16X3 || d > f16_radial_max_d())) return true;
+    return t > 1 || d > (cross_term == KNM_CROSS_F16X3 ? f16_max_d() : small_max_d());
 }
 
 // Chunking of the stream dimension.  More chunks = more workgroups (needed when there

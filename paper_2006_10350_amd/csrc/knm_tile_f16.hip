@@ -39,6 +39,8 @@
 // assembly so this order survives the compiler; no MFMA result is read until a whole
 // tile after it was issued, and no exp result by the instruction right after it.
 
+#include <type_traits>
+
 #include "knm_internal.h"
 #include "knm_operands.h"
 
@@ -114,12 +116,74 @@ __device__ __forceinline__ void mfma_step(f32x16 &acc, const f16x8 &a, const f16
     }
 }
 
-// The 3 HU MFMAs of one fixed block on one stream tile, with the 16 (exp, FMA) pairs that
-// finish the same block's accumulator of the previous tile (`pa`, weight `vl_prev`).
-template <int HU, int I = 0>
+// ---- kernels of r = |f - x| (Laplacian, Matern): one MFMA followed by the finish of G entries ----
+// The accumulator holds x = -(log2(e) u)^2; the kernel value is 2^-sqrt(|x|) (times a polynomial in u
+// for the Matern kernels).  Entries whose |x| lies below the lane's threshold `thr` (pairs so close
+// that the cancellation error of the norm expansion would show after the square root) get the
+// value 0 here and are noted in `near` (a wave mask); the caller evaluates them again from
+// differences.  Every instruction is its own volatile statement, in program order; a transcendental
+// result is never read by the instruction right after it.
+struct RadialConsts {
+    float big;   // replaces the exponent of a near pair: 2^-sqrt(big) = 0
+    float ln2;   // u = y ln 2 for y = log2(e) u
+    float third; // Matern 5/2
+};
+
+template <int KIND, int G, int R0>
+__device__ __forceinline__ void radial_group(const f32x16 &pa, float thr, float vl, const RadialConsts &rc, float (&s)[16],
+                                             uint64_t &near)
+{
+    float p[G], q[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i)
+        asm volatile("v_cmp_lt_f32_e64 vcc, |%2|, %3\n\t"
+                     "s_or_b64 %1, %1, vcc\n\t"
+                     "v_cndmask_b32_e32 %0, %2, %4, vcc"
+                     : "=&v"(p[i]), "+s"(near)
+                     : "v"(pa[R0 + i]), "v"(thr), "v"(rc.big)
+                     : "vcc");
+#pragma unroll
+    for (int i = 0; i < G; ++i) asm volatile("v_sqrt_f32_e64 %0, |%1|" : "=v"(q[i]) : "v"(p[i]));
+    if constexpr (G == 1) asm volatile("s_nop 0");
+#pragma unroll
+    for (int i = 0; i < G; ++i) asm volatile("v_exp_f32_e64 %0, -%1" : "=v"(p[i]) : "v"(q[i]));
+    if constexpr (KIND == KNM_KERNEL_LAPLACIAN) {
+        if constexpr (G == 1) asm volatile("s_nop 0");
+    } else {
+#pragma unroll
+        for (int i = 0; i < G; ++i) asm volatile("v_mul_f32_e32 %0, %1, %0" : "+v"(q[i]) : "v"(rc.ln2)); // u
+        if constexpr (KIND == KNM_KERNEL_MATERN32) {
+#pragma unroll
+            for (int i = 0; i < G; ++i) asm volatile("v_fmac_f32_e32 %0, %1, %0" : "+v"(p[i]) : "v"(q[i])); // e + u e
+        } else {
+            float w[G];
+#pragma unroll
+            for (int i = 0; i < G; ++i) asm volatile("v_fma_f32 %0, %1, %2, 1.0" : "=v"(w[i]) : "v"(q[i]), "v"(rc.third));
+#pragma unroll
+            for (int i = 0; i < G; ++i) asm volatile("v_fma_f32 %0, %1, %0, 1.0" : "+v"(w[i]) : "v"(q[i])); // 1 + u + u^2 / 3
+#pragma unroll
+            for (int i = 0; i < G; ++i) asm volatile("v_mul_f32_e32 %0, %0, %1" : "+v"(p[i]) : "v"(w[i]));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < G; ++i) asm volatile("v_fmac_f32_e32 %0, %1, %2" : "+v"(s[R0 + i]) : "v"(p[i]), "v"(vl));
+}
+
+template <bool FIRST>
+__device__ __forceinline__ void mfma_only(f32x16 &acc, const f16x8 &a, const f16x8 &b)
+{
+    if constexpr (FIRST) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
+// The 3 HU MFMAs of one fixed block on one stream tile, with the finish of the 16 entries of the
+// same block's accumulator of the previous tile (`pa`, weight `vl_prev`; for the kernels of r also
+// that tile's threshold `thr_prev`) spread behind them.
+template <int HU, int KIND, int I = 0>
 __device__ __forceinline__ void block_tile(f32x16 &acc, const f16x8 (&fh)[HU], const f16x8 &fhv,
                                            const f16x8 (&fl)[HU], const f16x8 (&bh)[HU], const f16x8 (&bl)[HU],
-                                           const f32x16 &pa, float vl_prev, float (&s)[16])
+                                           const f32x16 &pa, float vl_prev, float thr_prev, const RadialConsts &rc,
+                                           float (&s)[16], uint64_t &near)
 {
     constexpr int NM = 3 * HU;
     if constexpr (I < NM) {
@@ -128,8 +192,13 @@ __device__ __forceinline__ void block_tile(f32x16 &acc, const f16x8 (&fh)[HU], c
         constexpr int plane = I / HU, m = I % HU;
         const f16x8 &a = plane == 0 ? fh[m] : (plane == 1 ? (m == HU - 1 ? fhv : fh[m]) : fl[m]);
         const f16x8 &b = plane == 1 ? bl[m] : bh[m];
-        mfma_step<I == 0, G, R0>(acc, a, b, pa, vl_prev, s);
-        block_tile<HU, I + 1>(acc, fh, fhv, fl, bh, bl, pa, vl_prev, s);
+        if constexpr (KIND == KNM_KERNEL_GAUSSIAN) {
+            mfma_step<I == 0, G, R0>(acc, a, b, pa, vl_prev, s);
+        } else {
+            mfma_only<I == 0>(acc, a, b);
+            radial_group<KIND, G, R0>(pa, thr_prev, vl_prev, rc, s, near);
+        }
+        block_tile<HU, KIND, I + 1>(acc, fh, fhv, fl, bh, bl, pa, vl_prev, thr_prev, rc, s, near);
     }
 }
 
@@ -190,10 +259,11 @@ __global__ __launch_bounds__(kThreads) void pack_stream_kernel(const float *__re
 
 // `packed` is the image of the stream chunks [chunk0, chunk0 + gridDim.y) built by
 // pack_stream_kernel; blockIdx.y counts chunks within that slab.
-template <int NU>
+template <int NU, int KIND>
 __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs a, const f16x8 *__restrict__ packed,
                                                                       int64_t chunk0)
 {
+    constexpr bool kRadial = KIND != KNM_KERNEL_GAUSSIAN;
     constexpr int HU = NU / 2;                      // MFMAs per plane
     constexpr int UPS = kTilesPerStage * 2 * HU * 64; // 16-byte units per stage
     constexpr int UPT = UPS / kThreads;             // units copied per thread and stage
@@ -201,6 +271,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
 
     __shared__ f16x8 img[2][kTilesPerStage][2][HU][64]; // [buffer][tile][plane xh/xl][mfma][lane]
     __shared__ float vv[2][kStage];
+    __shared__ float tt[kRadial ? 2 : 1][kRadial ? kStage : 1]; // per stream point: threshold of a near pair
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -265,21 +336,36 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
 
     f16x8 xs[UPT];
     float vs = 0.0f;
+    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+    f16x4 digits = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
     auto fetch = [&](int stage) {
 #pragma unroll
         for (int k = 0; k < UPT; ++k) xs[k] = src[(int64_t)stage * UPS + k * kThreads];
-        const int64_t idx = chunk_begin + (int64_t)stage * kStage + (tid & (kStage - 1));
+        const int sp = tid & (kStage - 1); // stream point of the stage this thread brings the vector entry of
+        const int64_t idx = chunk_begin + (int64_t)stage * kStage + sp;
         const bool valid = idx < chunk_end;
         const int64_t vi = valid ? idx : 0;
         const float vraw = a.vec[vi * a.ldv];
         const float wraw = (a.wgt != nullptr) ? a.wgt[vi] : 1.0f;
         vs = valid ? vraw * wraw : 0.0f;
+        if constexpr (kRadial) {
+            // the point's norm term, as the four digits the packing kernel left in the last unit of
+            // the lo plane (half-wave 1, slots 4..7): unit (tile, plane 1, MFMA HU - 1, lane 32 + row)
+            const f16x8 *unit = src - tid + (int64_t)stage * UPS + ((sp >> 5) * 2 * HU + HU + (HU - 1)) * 64 + 32 + (sp & 31);
+            digits = reinterpret_cast<const f16x4 *>(unit)[1];
+        }
     };
     auto commit = [&](int buf) {
         f16x8 *dst = &img[buf][0][0][0][0];
 #pragma unroll
         for (int k = 0; k < UPT; ++k) dst[k * kThreads + tid] = xs[k];
         if (tid < kStage) vv[buf][tid] = vs;
+        if constexpr (kRadial) {
+            // the digits hold -n; a near pair has nearly equal norms, so the stream point's own
+            // norm stands for both
+            const float nrm = -(kC1 * (float)digits[0] + kC2 * (float)digits[1] + kC3 * (float)digits[2] + kC4 * (float)digits[3]);
+            if (tid < kStage) tt[buf][tid] = near_pair_threshold(nrm, d);
+        }
     };
 
     // accumulators of the tile in flight (cur) and of the tile being finished (prev)
@@ -289,6 +375,41 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
 #pragma unroll
         for (int r = 0; r < 16; ++r) { accA[rb][r] = 0.0f; accB[rb][r] = 0.0f; }
     float vl_prev = 0.0f; // zero weight: the first "previous tile" contributes nothing
+    // kernels of r: threshold and stream point of the tile being finished (no entry of the first
+    // "previous tile" lies below a zero threshold), the wave's mask of near pairs seen, constants
+    float thr_prev = 0.0f;
+    int64_t j_prev = 0;
+    uint64_t near = 0;
+    RadialConsts rc;
+    rc.big = 1.0e30f;
+    rc.ln2 = 0.6931471805599453f;
+    rc.third = 1.0f / 3.0f;
+    const float s2 = kLog2e / (2.0f * a.sigma * a.sigma); // exponent per squared distance, for the second evaluation
+    // Second evaluation of the near pairs of one finished tile (rare: behind a wave-uniform branch):
+    // their exponents again from fp32 differences of the two rows, exact for coincident rows.
+    auto refine = [&](const f32x16 (&acc)[2], float thr_t, float vl_t, int64_t j) {
+        const bool in = j < chunk_end; // a padding point has a zero vector entry
+        const float *srow = a.S + (in ? j : 0) * a.lds;
+        uint32_t m = 0; // bit 16 rb + r: entry r of block rb is a near pair of this lane
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (fabsf(acc[rb][r]) < thr_t) m |= 1u << (16 * rb + r);
+        if (!in) m = 0;
+        while (__builtin_amdgcn_ballot_w64(m != 0) != 0) {
+            int b = -1;
+            float term = 0.0f;
+            if (m != 0) {
+                b = __builtin_ctz(m);
+                m &= m - 1;
+                const int64_t fi = fixed0 + (b >> 4) * 32 + 8 * ((b & 15) >> 2) + 4 * h + (b & 3);
+                if (fi < a.nF) term = radial_from_exponent<KIND>(exact_exponent(a.F + fi * a.ldf, srow, d, s2)) * vl_t;
+            }
+#pragma unroll
+            for (int k = 0; k < 32; ++k) sum[k >> 4][k & 15] += (b == k) ? term : 0.0f;
+        }
+    };
 
     if (n_stages > 0) fetch(0);
     for (int st = 0; st < n_stages; ++st) {
@@ -298,7 +419,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         if (st + 1 < n_stages) fetch(st + 1);
 
         f16x8 bh[2][HU], bl[2][HU];
-        float vl[2];
+        float vl[2], th[2] = {0.0f, 0.0f};
         auto read_tile = [&](int tile, int slot) {
 #pragma unroll
             for (int m = 0; m < HU; ++m) {
@@ -306,6 +427,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
                 bl[slot][m] = img[buf][tile][1][m][lane];
             }
             vl[slot] = vv[buf][tile * 32 + row];
+            if constexpr (kRadial) th[slot] = tt[buf][tile * 32 + row];
         };
         read_tile(0, 0);
 #pragma unroll
@@ -313,11 +435,20 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
             const int cur = tile & 1;
             if (tile + 1 < kTilesPerStage) read_tile(tile + 1, cur ^ 1);
             if (cur == 0) {
-                block_tile<HU>(accA[0], fh[0], fhv[0], fl[0], bh[cur], bl[cur], accB[0], vl_prev, sum[0]);
-                block_tile<HU>(accA[1], fh[1], fhv[1], fl[1], bh[cur], bl[cur], accB[1], vl_prev, sum[1]);
+                block_tile<HU, KIND>(accA[0], fh[0], fhv[0], fl[0], bh[cur], bl[cur], accB[0], vl_prev, thr_prev, rc, sum[0], near);
+                block_tile<HU, KIND>(accA[1], fh[1], fhv[1], fl[1], bh[cur], bl[cur], accB[1], vl_prev, thr_prev, rc, sum[1], near);
             } else {
-                block_tile<HU>(accB[0], fh[0], fhv[0], fl[0], bh[cur], bl[cur], accA[0], vl_prev, sum[0]);
-                block_tile<HU>(accB[1], fh[1], fhv[1], fl[1], bh[cur], bl[cur], accA[1], vl_prev, sum[1]);
+                block_tile<HU, KIND>(accB[0], fh[0], fhv[0], fl[0], bh[cur], bl[cur], accA[0], vl_prev, thr_prev, rc, sum[0], near);
+                block_tile<HU, KIND>(accB[1], fh[1], fhv[1], fl[1], bh[cur], bl[cur], accA[1], vl_prev, thr_prev, rc, sum[1], near);
+            }
+            if constexpr (kRadial) {
+                if (near != 0) { // the finished tile (the set this tile's MFMAs do not write) had near pairs
+                    if (cur == 0) refine(accB, thr_prev, vl_prev, j_prev);
+                    else refine(accA, thr_prev, vl_prev, j_prev);
+                    near = 0;
+                }
+                thr_prev = th[cur];
+                j_prev = chunk_begin + (int64_t)st * kStage + tile * 32 + row;
             }
             vl_prev = vl[cur];
         }
@@ -327,13 +458,24 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
     // does not know that the inline assembly above contains MFMAs
     static_assert(kTilesPerStage % 2 == 0, "accumulator sets alternate per tile");
     asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+v"(accB[0]), "+v"(accB[1]));
+    bool any_near = false;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(accB[rb][r]), 0.0f, 1.0f);
+            float p;
+            if constexpr (kRadial) {
+                const bool nr = fabsf(accB[rb][r]) < thr_prev;
+                any_near |= nr;
+                p = nr ? 0.0f : radial_from_exponent<KIND>(accB[rb][r]);
+            } else {
+                p = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(accB[rb][r]), 0.0f, 1.0f);
+            }
             sum[rb][r] = fmaf(p, vl_prev, sum[rb][r]);
         }
+    if constexpr (kRadial) {
+        if (__builtin_amdgcn_ballot_w64(any_near) != 0) refine(accB, thr_prev, vl_prev, j_prev);
+    }
 
     // ---- reduce over the 32 stream lanes of each half-wave and store ----------------------
     float *out = a.out + chunk * a.chunk_stride;
@@ -352,7 +494,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         }
 }
 
-template <int NU>
+template <int NU, int KIND>
 hipError_t launch_nu(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
     constexpr int HU = NU / 2;
@@ -379,7 +521,7 @@ hipError_t launch_nu(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipS
             hipLaunchKernelGGL((pack_stream_kernel<NU, 1>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.mu, a.d,
                                a.sigma, row0, rows, packed, a.range_count);
         const dim3 grid((unsigned)blocks, (unsigned)nc);
-        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU>), grid, dim3(kThreads), 0, stream, a, packed, c0);
+        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, KIND>), grid, dim3(kThreads), 0, stream, a, packed, c0);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -389,6 +531,7 @@ hipError_t launch_nu(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipS
 } // namespace
 
 int f16_max_d() { return 44; } // 6 units of 8 features; larger images exceed 64 KB of static LDS
+int f16_radial_max_d() { return 28; } // the kernels of r need more registers per entry: 4 units
 
 // bytes of packed image per stream point for this d
 size_t f16_pack_bytes_per_point(int d) { return d <= 12 ? 64 : (d <= 28 ? 128 : 192); }
@@ -396,12 +539,23 @@ size_t f16_pack_bytes_per_point(int d) { return d <= 12 ? 64 : (d <= 28 ? 128 : 
 hipError_t launch_sweep_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
     if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t != 1 || a.d > f16_max_d()) return hipErrorInvalidValue;
+    if (a.kind != KNM_KERNEL_GAUSSIAN && a.d > f16_radial_max_d()) return hipErrorInvalidValue;
     if (a.chunk_len % kStage != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
+    if (a.kind < KNM_KERNEL_GAUSSIAN || a.kind > KNM_KERNEL_MATERN52) return hipErrorInvalidValue;
     // units of 8 features; the last unit keeps 4 slots for the norm digits
-    if (a.d <= 12) return launch_nu<2>(a, pack_buf, pack_bytes, stream);
-    if (a.d <= 28) return launch_nu<4>(a, pack_buf, pack_bytes, stream);
-    return launch_nu<6>(a, pack_buf, pack_bytes, stream);
+    auto launch = [&](auto kind) {
+        constexpr int K = decltype(kind)::value;
+        if (a.d <= 12) return launch_nu<2, K>(a, pack_buf, pack_bytes, stream);
+        if (a.d <= 28) return launch_nu<4, K>(a, pack_buf, pack_bytes, stream);
+        return launch_nu<6, K>(a, pack_buf, pack_bytes, stream);
+    };
+    switch (a.kind) {
+    case KNM_KERNEL_LAPLACIAN: return launch(std::integral_constant<int, KNM_KERNEL_LAPLACIAN>{});
+    case KNM_KERNEL_MATERN32: return launch(std::integral_constant<int, KNM_KERNEL_MATERN32>{});
+    case KNM_KERNEL_MATERN52: return launch(std::integral_constant<int, KNM_KERNEL_MATERN52>{});
+    default: return launch(std::integral_constant<int, KNM_KERNEL_GAUSSIAN>{});
+    }
 }
 
 } // namespace knm
