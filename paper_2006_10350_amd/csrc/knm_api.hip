@@ -1,11 +1,56 @@
 // C ABI of libknm: context, workspace and the kernel-matrix-vector products.
+#include <dlfcn.h>
+
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "knm_internal.h"
 
 namespace knm {
+
+namespace {
+struct MarkerApi {
+    int (*push)(const char *) = nullptr;
+    int (*pop)() = nullptr;
+};
+const MarkerApi &marker_api()
+{
+    static MarkerApi api;
+    static std::once_flag once;
+    std::call_once(once, [] {
+        const char *want = std::getenv("KNM_MARKERS");
+        if (!want || !*want || std::strcmp(want, "0") == 0) return;
+        for (const char *lib : {"librocprofiler-sdk-roctx.so", "libroctx64.so"}) {
+            void *h = dlopen(lib, RTLD_NOW | RTLD_GLOBAL);
+            if (!h) continue;
+            auto push = reinterpret_cast<int (*)(const char *)>(dlsym(h, "roctxRangePushA"));
+            auto pop = reinterpret_cast<int (*)()>(dlsym(h, "roctxRangePop"));
+            if (push && pop) {
+                api.push = push;
+                api.pop = pop;
+                return;
+            }
+        }
+    });
+    return api;
+}
+} // namespace
+
+TraceRange::TraceRange(const char *name) : open(false)
+{
+    const MarkerApi &api = marker_api();
+    if (api.push) {
+        (void)api.push(name);
+        open = true;
+    }
+}
+TraceRange::~TraceRange()
+{
+    if (open) (void)marker_api().pop();
+}
 
 int fail(knm_ctx *ctx, int status, const char *what, hipError_t e)
 {
@@ -107,22 +152,37 @@ static bool bad_geom(const void *X, int64_t n, int d, int64_t ldx, const void *C
 
 // mu[k] = mean of feature k over `rows` rows of P taken `stride` rows apart (a sample spread over the
 // whole set, so that data stored in some order still gives a representative centre): the common shift
-// of a sweep's two point sets.  One workgroup per 32 features, 8 row lanes per feature, fp64 sums in a
-// fixed order.
-__global__ __launch_bounds__(256) void column_mean_kernel(const float *__restrict__ P, int64_t rows, int64_t stride,
-                                                         int64_t ld, int d, float *__restrict__ mu)
+// of a sweep's two point sets.  One workgroup per 32 features, 32 row lanes per feature with four
+// loads in flight each, fp64 sums in a fixed order.
+constexpr int kMeanRowLanes = 32;
+constexpr int64_t kMeanSample = 16384; // rows of the sample at most
+__global__ __launch_bounds__(32 * kMeanRowLanes) void column_mean_kernel(const float *__restrict__ P, int64_t rows,
+                                                                        int64_t stride, int64_t ld, int d,
+                                                                        float *__restrict__ mu)
 {
-    __shared__ double part[8][32];
-    const int f = threadIdx.x & 31, lane8 = threadIdx.x >> 5;
+    __shared__ double part[kMeanRowLanes][32];
+    const int f = threadIdx.x & 31, rl = threadIdx.x >> 5;
     const int k = blockIdx.x * 32 + f;
-    double s = 0.0;
-    if (k < d)
-        for (int64_t r = lane8; r < rows; r += 8) s += (double)P[r * stride * ld + k];
-    part[lane8][f] = s;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    if (k < d) {
+        const float *col = P + k;
+        const int64_t step = stride * ld;
+        int64_t r = rl;
+        for (; r + 3 * kMeanRowLanes < rows; r += 4 * kMeanRowLanes) {
+            const float a0 = col[r * step], a1 = col[(r + kMeanRowLanes) * step];
+            const float a2 = col[(r + 2 * kMeanRowLanes) * step], a3 = col[(r + 3 * kMeanRowLanes) * step];
+            s0 += (double)a0;
+            s1 += (double)a1;
+            s2 += (double)a2;
+            s3 += (double)a3;
+        }
+        for (; r < rows; r += kMeanRowLanes) s0 += (double)col[r * step];
+    }
+    part[rl][f] = (s0 + s1) + (s2 + s3);
     __syncthreads();
-    if (lane8 == 0 && k < d) {
+    if (rl == 0 && k < d) {
         double total = 0.0;
-        for (int i = 0; i < 8; ++i) total += part[i][f];
+        for (int i = 0; i < kMeanRowLanes; ++i) total += part[i][f];
         const float m = (float)(total / (double)rows);
         mu[k] = (m == m && fabsf(m) < 3.0e38f) ? m : 0.0f; // a NaN or Inf in the data must not spread to every point
     }
@@ -196,16 +256,16 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
                          (part_is_64 ? sizeof(double) : sizeof(float)) * (size_t)chunks * nF * t, &part);
         if (st) return st;
     }
-    // common shift: feature means of (a strided sample of at most 65536 rows of) the smaller point set
+    // common shift: feature means of (a strided sample of at most 16384 rows of) the smaller point set
     float *mu = nullptr;
     {
         int st = acquire(ctx, &ctx->mu_buf, &ctx->mu_bytes, sizeof(float) * ((size_t)d + 1), &mu); // + the "shifted" flag
         if (st) return st;
         const bool from_f = nF <= nS;
         const int64_t rows = from_f ? nF : nS;
-        const int64_t stride = (rows + 65535) / 65536; // every stride-th row: at most 65536 of them, spread over the set
-        hipLaunchKernelGGL(column_mean_kernel, dim3((unsigned)((d + 31) / 32)), dim3(256), 0, ctx->stream, from_f ? F : S,
-                           (rows + stride - 1) / stride, stride, from_f ? ldf : lds, d, mu);
+        const int64_t stride = (rows + kMeanSample - 1) / kMeanSample; // every stride-th row, spread over the set
+        hipLaunchKernelGGL(column_mean_kernel, dim3((unsigned)((d + 31) / 32)), dim3(32 * kMeanRowLanes), 0, ctx->stream,
+                           from_f ? F : S, (rows + stride - 1) / stride, stride, from_f ? ldf : lds, d, mu);
         hipLaunchKernelGGL(shift_decide_kernel, dim3(1), dim3(256), 0, ctx->stream, mu, d,
                            1.0f / (2.0f * sigma * sigma));
         if (hipGetLastError() != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "column_mean_kernel launch");
@@ -303,6 +363,7 @@ static void begin_timing(knm_ctx *ctx)
 int do_knm_v(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, const float *C, int64_t M,
              int64_t ldc, float sigma, const float *V, int t, float *W)
 {
+    TraceRange range("knm row sweep W = K V");
     return sweep(ctx, X, n, ldx, C, M, ldc, d, sigma, V, nullptr, t, W, nullptr, nullptr);
 }
 
@@ -314,6 +375,7 @@ int do_knm_t_w(knm_ctx *ctx, const float *X, int64_t n, int d, int64_t ldx, cons
         ev = ctx->ev[2];
         ctx->ev_used[2] = true;
     }
+    TraceRange range("knm column sweep U = K^T W");
     return sweep(ctx, C, M, ldc, X, n, ldx, d, sigma, Wv, wgt, t, U64 != nullptr ? nullptr : U, U64, ev);
 }
 

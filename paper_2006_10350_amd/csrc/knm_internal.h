@@ -190,6 +190,17 @@ struct knm_ctx {
 };
 
 namespace knm {
+// Named range for profilers (rocprofv3 --marker-trace): the phases of a product or fit.  The marker
+// library (librocprofiler-sdk-roctx.so, or libroctx64.so) is looked up at run time the first time a
+// range opens, and only if the environment variable KNM_MARKERS is set to a non-empty value other
+// than 0: libknm itself links the HIP runtime only, and a range costs nothing otherwise.
+struct TraceRange {
+    explicit TraceRange(const char *name);
+    ~TraceRange();
+    TraceRange(const TraceRange &) = delete;
+    TraceRange &operator=(const TraceRange &) = delete;
+    bool open;
+};
 int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need);
 int fail(knm_ctx *ctx, int status, const char *what, hipError_t e = hipSuccess);
 // true if (d, t) runs on the K-loop engine, false for the register-resident one

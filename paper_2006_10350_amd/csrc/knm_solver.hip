@@ -560,6 +560,7 @@ struct DevBuf {
 // array: what is a row update for one is a column update for the other.
 int tri_solve(knm_ctx *ctx, const knm_precond *p, const double *R, const double *S, bool trans, double *B, int t)
 {
+    TraceRange range(R == p->A ? (trans ? "knm solve A^-T" : "knm solve A^-1") : (trans ? "knm solve T^-T" : "knm solve T^-1"));
     const int64_t M = p->M, ld = p->ld;
     const bool lower = (R == p->A);
     const int sb = p->sb;
@@ -838,6 +839,7 @@ static int aux_stream(knm_ctx *ctx, hipStream_t *out)
 static int chol_blocked(knm_ctx *ctx, double *A, int64_t ld, int64_t M, bool lower, double *W, unsigned long long *bad,
                         int64_t *first_bad)
 {
+    TraceRange range(lower ? "knm Cholesky of T D T^T / M + lambda I" : "knm Cholesky of K_MM");
     int64_t b = ((M + 7) / 8 + 255) / 256 * 256;
     if (b > 4096) b = 4096;
     const int64_t nb = (M + b - 1) / b;
@@ -952,9 +954,12 @@ static int build_second_factor(knm_ctx *ctx, knm_precond *p, double lambda, cons
     int st = leaf.alloc(ctx, sizeof(double) * kLeaf * kLeaf);
     if (!st) st = badbuf.alloc(ctx, sizeof(unsigned long long));
     if (st) return st;
-    if (launch_rank_k_upper(1, M, M, 1.0 / (double)M, p->T, p->ld, dw, 1, 0.0, lambda, p->A, p->ld, ctx->stream, 1) !=
-        hipSuccess)
-        return fail(ctx, KNM_HIP_ERROR, "triangular product launch");
+    {
+        TraceRange range("knm triangular product T D T^T");
+        if (launch_rank_k_upper(1, M, M, 1.0 / (double)M, p->T, p->ld, dw, 1, 0.0, lambda, p->A, p->ld, ctx->stream, 1) !=
+            hipSuccess)
+            return fail(ctx, KNM_HIP_ERROR, "triangular product launch");
+    }
     int64_t pivot = 0;
     st = chol_blocked(ctx, p->A, p->ld, M, true, leaf.as<double>(), badbuf.as<unsigned long long>(), &pivot);
     if (st) return st;
@@ -1327,6 +1332,7 @@ static int fit_core(knm_ctx *ctx, const KernelOps &ops, knm_precond *p, const fl
     }
     const clk::time_point t_rhs = clk::now(); // the host-pointer dot products above synchronise
     for (int it = 0; it < iters; ++it) {
+        TraceRange range("knm CG iteration");
         st = linop_cols(ctx, p, wk, ops, lambda, dp, t, dq);
         if (st) return st;
         for (int c = 0; c < t; ++c) {
