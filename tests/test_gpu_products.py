@@ -82,6 +82,11 @@ def test_products_match_oracle(knm, cross, n, M, d, t, sigma):
     Uo, Wo = oracle.knm_prod(Xn, Cn, sigma, V.numpy(), return_w=True)
     assert rel_l2(U.cpu().numpy(), Uo) < TIGHT
     assert rel_l2(W2.cpu().numpy(), Wo) < TIGHT
+    # element by element as well: no single output may hide behind the norm of the others
+    for got, ref in ((W, oracle.knm_v(Xn, Cn, sigma, V.numpy())), (R, oracle.knm_t_y(Xn, Cn, sigma, Y.numpy())),
+                     (U.cpu().numpy(), Uo)):
+        ref = np.asarray(ref).reshape(got.shape)
+        assert np.max(np.abs(got - ref)) < TOL * np.max(np.abs(ref))
     for c in range(t):  # per column as well as Frobenius
         assert rel_l2(U.cpu().numpy().reshape(M, t)[:, c], np.asarray(Uo).reshape(M, t)[:, c]) < TOL
     # without the W output the library uses its own workspace: same result bit for bit
