@@ -108,6 +108,17 @@ __global__ void f64_rows_to_cols(const double *__restrict__ src, int64_t rows, i
     else dst[r + (int64_t)c * rows] = src[i];
 }
 
+// dst[r * cols + c] = entry (row0 + r, col0 + c) of an upper factor stored at F (upper or lower storage,
+// leading dimension ld), zero below the diagonal: a block of a factor gathered into row-major order
+__global__ void gather_block_kernel(const double *__restrict__ F, int64_t ld, int lower, int64_t row0, int64_t col0,
+                                    int64_t rows, int64_t cols, double *__restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * cols) return;
+    const int64_t r = row0 + i / cols, c = col0 + i % cols;
+    dst[i] = (c >= r) ? (lower ? F[c + r * ld] : F[r + c * ld]) : 0.0;
+}
+
 // ---- blocked triangular solves -----------------------------------------------------------------
 // R (upper, column-major, leading dimension M) is cut into block columns of width sb.  A solve
 // walks the diagonal blocks in dependency order; each step multiplies a right-hand-side block
@@ -1157,25 +1168,16 @@ int precond_get_block(knm_ctx *ctx, const knm_precond *p, int second, int64_t ro
     if (!p || !out_host || row0 < 0 || col0 < 0 || rows <= 0 || cols <= 0 || row0 + rows > p->M || col0 + cols > p->M)
         return fail(ctx, KNM_INVALID_ARG, "bad factor block");
     if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipSetDevice");
-    std::vector<double> tmp((size_t)rows * cols);
-    hipError_t e = hipStreamSynchronize(ctx->stream);
-    if (!second) {
-        // upper storage: column c of the block is contiguous, rows of `out_host` are strided
-        if (e == hipSuccess)
-            e = hipMemcpy2D(tmp.data(), sizeof(double) * rows, p->T + row0 + col0 * p->ld, sizeof(double) * p->ld,
-                            sizeof(double) * rows, (size_t)cols, hipMemcpyDeviceToHost);
-        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpy2D(factor block)", e);
-        for (int64_t r = 0; r < rows; ++r)
-            for (int64_t c = 0; c < cols; ++c) out_host[r * cols + c] = (col0 + c >= row0 + r) ? tmp[r + c * rows] : 0.0;
-    } else {
-        // lower storage: row r of the block is contiguous
-        if (e == hipSuccess)
-            e = hipMemcpy2D(tmp.data(), sizeof(double) * cols, p->A + col0 + row0 * p->ld, sizeof(double) * p->ld,
-                            sizeof(double) * cols, (size_t)rows, hipMemcpyDeviceToHost);
-        if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "hipMemcpy2D(factor block)", e);
-        for (int64_t r = 0; r < rows; ++r)
-            for (int64_t c = 0; c < cols; ++c) out_host[r * cols + c] = (col0 + c >= row0 + r) ? tmp[c + r * cols] : 0.0;
-    }
+    // gathered on the device (a row of an upper-storage factor is strided in memory), then one copy
+    DevBuf tmp;
+    int st = tmp.alloc(ctx, sizeof(double) * (size_t)rows * (size_t)cols);
+    if (st) return st;
+    hipLaunchKernelGGL(gather_block_kernel, grid1(rows * cols), dim3(256), 0, ctx->stream, second ? p->A : p->T, p->ld,
+                       second ? 1 : 0, row0, col0, rows, cols, tmp.as<double>());
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess) e = hipMemcpy(out_host, tmp.p, sizeof(double) * (size_t)rows * (size_t)cols, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "factor block copy", e);
     return KNM_OK;
 }
 
