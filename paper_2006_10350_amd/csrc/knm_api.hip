@@ -124,11 +124,12 @@ bool use_gemm_engine(int d, int t, int cross_term, int kind)
 int64_t choose_chunks(int64_t nF, int64_t nS, int d, int t, int cross_term, int kind, int64_t *chunk_len)
 {
     const bool gemm = use_gemm_engine(d, t, cross_term, kind);
-    const int64_t stage = gemm ? gemm_stage_points() : stage_points();
+    const int64_t stage = gemm ? gemm_stage_points()
+                               : (cross_term == KNM_CROSS_F16X3 ? f16_stage_points(d, kind) : stage_points());
     const int64_t per_block = gemm ? gemm_fixed_per_block() : fixed_per_block(d);
     const int64_t blocks = (nF + per_block - 1) / per_block;
     const int64_t target_wgs = 4096;       // several waves of workgroups over 256 CUs
-    const int64_t min_len = 16 * stage;    // amortise the per-workgroup prologue/epilogue
+    const int64_t min_len = gemm ? 16 * stage : 2048; // amortise the per-workgroup prologue/epilogue
     const int64_t max_len = (int64_t)1 << 18; // bound the length of a per-lane fp32 running sum
     int64_t chunks = (target_wgs + blocks - 1) / blocks;
     if (gemm && chunks < 16) chunks = 16;  // the K-loop engine tiles (fixed blocks x chunks) over each XCD's L2

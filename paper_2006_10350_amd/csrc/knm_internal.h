@@ -96,6 +96,7 @@ hipError_t launch_sweep(const SweepArgs &a, hipStream_t stream);
 // same shapes with the cross term as three f16 MFMA products (knm_tile_f16.hip): d <= f16_max_d()
 int f16_max_d();
 int f16_radial_max_d(); // the same for the kernels of r = |x - c|
+int64_t f16_stage_points(int d, int kind); // stream points staged per LDS buffer by that engine
 size_t f16_pack_bytes_per_point(int d);
 // pack_buf: device workspace for the packed stream image, at least one chunk's worth
 hipError_t launch_sweep_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream);

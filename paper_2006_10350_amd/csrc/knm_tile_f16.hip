@@ -49,8 +49,10 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kStage = 128; // stream points per LDS stage (2 threads per point)
-constexpr int kTilesPerStage = kStage / 32;
+// stream points per LDS stage: 256 (eight tiles between barriers) while two workgroups' double buffers
+// still fit a CU's LDS and the registers hold the stage's vector entries without spills: up to four units
+// for the Gaussian kernel, two for the kernels of r
+constexpr int stage_of(int nu, int kind) { return nu <= (kind == KNM_KERNEL_GAUSSIAN ? 4 : 2) ? 256 : 128; }
 // ---- one MFMA followed by G (exp, FMA) pairs of the previous tile -------------------------
 #define KNM_MFMA_FIRST "v_mfma_f32_32x32x16_f16 %[acc], %[a], %[b], 0\n\t"
 #define KNM_MFMA_NEXT "v_mfma_f32_32x32x16_f16 %[acc], %[a], %[b], %[acc]\n\t"
@@ -265,6 +267,8 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
 {
     constexpr bool kRadial = KIND != KNM_KERNEL_GAUSSIAN;
     constexpr int HU = NU / 2;                      // MFMAs per plane
+    constexpr int kStage = stage_of(NU, KIND);
+    constexpr int kTilesPerStage = kStage / 32;
     constexpr int UPS = kTilesPerStage * 2 * HU * 64; // 16-byte units per stage
     constexpr int UPT = UPS / kThreads;             // units copied per thread and stage
     static_assert(NU % 2 == 0 && NU >= 2, "an MFMA takes two units");
@@ -531,6 +535,7 @@ hipError_t launch_nu(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipS
 } // namespace
 
 int f16_max_d() { return 44; } // 6 units of 8 features; larger images exceed 64 KB of static LDS
+int64_t f16_stage_points(int d, int kind) { return stage_of(d <= 12 ? 2 : (d <= 28 ? 4 : 6), kind); }
 int f16_radial_max_d() { return 28; } // the kernels of r need more registers per entry: 4 units
 
 // bytes of packed image per stream point for this d
@@ -540,7 +545,7 @@ hipError_t launch_sweep_f16(const SweepArgs &a, void *pack_buf, size_t pack_byte
 {
     if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t != 1 || a.d > f16_max_d()) return hipErrorInvalidValue;
     if (a.kind != KNM_KERNEL_GAUSSIAN && a.d > f16_radial_max_d()) return hipErrorInvalidValue;
-    if (a.chunk_len % kStage != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
+    if (a.chunk_len % f16_stage_points(a.d, a.kind) != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
     if (a.kind < KNM_KERNEL_GAUSSIAN || a.kind > KNM_KERNEL_MATERN52) return hipErrorInvalidValue;
     // units of 8 features; the last unit keeps 4 slots for the norm digits
