@@ -12,7 +12,8 @@
 // against the constants 2^10, 2^-1, 2^-12, 2^-23 on the other operand.
 //
 // Packed images.  Both operands are converted once per sweep (`pack_points_kernel`) into
-// images laid out exactly as the LDS stage, so staging is a 16-byte copy and the
+// images laid out exactly as the LDS stage, so staging is a 16-byte copy (done by loads that
+// write LDS directly, into a ring of stages that keeps two stages of loads in flight) and the
 // conversion cost (scale, split, norms) is not repeated by every workgroup that visits a
 // point.  Per block of 32 points the image holds n_kc + 1 chunks of 2 KB:
 //     chunk kc < n_kc : [plane hi | lo][lane = 32 h + point] units of 8 halves = features
@@ -57,6 +58,10 @@ constexpr int kBlocks = (kFixed + kStream) / 32; // 32-point blocks per stage: 8
 constexpr int kChunk = 16;                     // features per K-chunk = one MFMA K
 constexpr int kUnits = 128;                    // 16-byte units per block and chunk (2 planes x 64 lanes)
 constexpr int kLoads = kBlocks * kUnits / kThreads; // units copied per thread and stage (6)
+constexpr int kStageUnits = kBlocks * kUnits;       // 16-byte units of one LDS stage (24 KB)
+// Stages in the LDS ring: 3 (two stages of loads in flight) where two workgroups' rings and vector rows
+// fit a CU's 160 KB, 2 for the matrix-core reduction with its 16 KB of vector halves
+constexpr int ring_depth(bool mv) { return mv ? 2 : 3; }
 constexpr float kPScale = 16384.0f; // matrix-core reduction: kernel values are split into fp16 halves after this scale
 // Image of points [row0, row0 + 32 gridDim.x) of P (points at or beyond nP become zero
 // points).  One workgroup per 32-point block; thread = (point, 8-feature unit), four
@@ -221,11 +226,13 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     const int64_t cblk = (patch / pm.n_patch_f) * pm.pc + within / pm.pf;
     if (fblk >= pm.n_fblocks || cblk >= pm.n_chunks) return; // whole workgroup, before any barrier
 
-    __shared__ f16x8 img[2][kBlocks * kUnits]; // 2 x 24 KB
-    // vector rows of a tile: fp32 [stream point][column], or for MV split halves in A-operand
-    // layout [stream block][K-step][plane hi/lo][lane]
-    constexpr int kVecUnits = MV ? 4 * 2 * 2 * 64 : (kStream * TP * 4 + 15) / 16;
-    __shared__ f16x8 vstore[kVecUnits];
+    // Ring of operand stages (24 KB each) in dynamic LDS, filled by loads that write LDS directly, and
+    // behind it the vector rows of a tile: fp32 [stream point][column], or for MV split halves in
+    // A-operand layout [stream block][K-step][plane hi/lo][lane]
+    constexpr int kRing = ring_depth(MV);
+    extern __shared__ __align__(16) unsigned char lds_dyn[];
+    f16x8 *const img = reinterpret_cast<f16x8 *>(lds_dyn);
+    f16x8 *const vstore = img + kRing * kStageUnits;
     float *const vimg = reinterpret_cast<float *>(vstore);
 
     const int tid = threadIdx.x;
@@ -254,9 +261,9 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     // Vector-ALU reduction, two levels: the terms of one tile (64 per lane and fixed point) are summed
     // in fp32 from zero, and the tile sums are added into fp64 running sums, so that the rounding of a
     // long sum of same-sign terms does not grow with the length of the chunk (a plain fp32 running sum
-    // over some thousand terms loses 2-3 digits of what the solver's T^-T amplifies).  With more than 10
-    // columns (8 for the kernels of r) the registers do not hold a second set of sums and the fp32 sums run through the chunk.
-    constexpr bool kWide = !MV && TP <= (KIND == KNM_KERNEL_GAUSSIAN ? 10 : 8);
+    // over some thousand terms loses 2-3 digits of what the solver's T^-T amplifies).  With more than 12
+    // columns (10 for the kernels of r) the registers do not hold a second set of sums and the fp32 sums run through the chunk.
+    constexpr bool kWide = !MV && TP <= (KIND == KNM_KERNEL_GAUSSIAN ? 12 : 10);
     float sum[2][TP];
     double wide[2][kWide ? TP : 1];
 #pragma unroll
@@ -275,22 +282,75 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     float vscale = 1.0f;
     if constexpr (MV) vscale = column_scale(colmax[lane & 31], false);
 
-    f16x8 pre[kLoads];
-    auto fetch = [&](int tile, int st) {
+    // Staging.  The images are laid out as the LDS stage, so a stage is 6 loads of 16 bytes per thread
+    // that go from memory into LDS without passing through registers: a wavefront's 64 units land in
+    // 1 KB starting at the address in M0.  The loads of a stage are started kRing - 1 stages before it
+    // is used; vmcnt counts them, and the compiler (which does not look inside inline assembly) knows
+    // nothing of them, so the waits are written here as well.  Bases are uniform, the thread's own
+    // byte offsets fit 32 bits.
+    const unsigned lds_wave =
+        __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_dyn +
+                                       (unsigned)wave * 1024u);
+    unsigned off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) off[i] = (toff + (unsigned)(2 * i) * (unsigned)blk_units) * 16u;
+    auto issue = [&](int tile, int st, int buf) {
         const f16x8 *const fs = fbase + (int64_t)st * kUnits;
         const f16x8 *const ss = sbase + (int64_t)tile * (kStream / 32) * blk_units + (int64_t)st * kUnits;
-        // the offset is made opaque here so that the six 64-bit addresses are formed where they are
-        // used instead of being kept (and spilled) across the whole tile loop
-        unsigned o = toff;
-        asm volatile("" : "+v"(o));
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pre[i] = (fs + 2 * i * blk_units)[o];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) pre[4 + i] = (ss + 2 * i * blk_units)[o];
+        const unsigned l = lds_wave + (unsigned)buf * (unsigned)(kStageUnits * 16);
+        unsigned m0_saved;
+        // (one wait state between a scalar write of M0 and the load that reads it)
+        asm volatile("s_mov_b32 %[keep], m0\n\t"
+                     "s_mov_b32 m0, %[l]\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %[o0], %[fs]\n\t"
+                     "s_add_u32 m0, m0, 0x1000\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %[o1], %[fs]\n\t"
+                     "s_add_u32 m0, m0, 0x1000\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %[o2], %[fs]\n\t"
+                     "s_add_u32 m0, m0, 0x1000\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %[o3], %[fs]\n\t"
+                     "s_add_u32 m0, m0, 0x1000\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %[o0], %[ss]\n\t"
+                     "s_add_u32 m0, m0, 0x1000\n\t"
+                     "s_nop 0\n\t"
+                     "global_load_lds_dwordx4 %[o1], %[ss]\n\t"
+                     "s_mov_b32 m0, %[keep]"
+                     : [keep] "=&s"(m0_saved)
+                     : [l] "s"(l), [o0] "v"(off[0]), [o1] "v"(off[1]), [o2] "v"(off[2]), [o3] "v"(off[3]), [fs] "s"(fs),
+                       [ss] "s"(ss)
+                     : "memory", "scc");
     };
-    auto commit = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < kLoads; ++i) img[buf][tid + kThreads * i] = pre[i];
+    const int total = n_tiles * n_st; // stages of this workgroup
+    int issued = 0, itile = 0, ist = 0, ibuf = 0; // the next stage to start, and its ring slot
+    auto issue_next = [&]() {
+        if (issued < total) {
+            issue(itile, ist, ibuf);
+            ++issued;
+            ibuf = ibuf + 1 == kRing ? 0 : ibuf + 1;
+            if (++ist == n_st) {
+                ist = 0;
+                ++itile;
+            }
+        }
+    };
+    // Start of stage g (ring slot `buf`): this thread's loads of the stage have landed when at most the
+    // loads of the kRing - 2 stages started after it are outstanding; after the barrier everyone's have,
+    // and everyone is done reading the slot of stage g - 1, which the stage kRing - 1 ahead takes over.
+    int g = 0, buf = 0;
+    auto stage_begin = [&]() {
+        if (kRing > 2 && g + kRing - 2 < total) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads * (kRing - 2)) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        issue_next();
+    };
+    auto stage_end = [&]() {
+        ++g;
+        buf = buf + 1 == kRing ? 0 : buf + 1;
     };
 
     f32x16 acc[2][4];
@@ -320,29 +380,24 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         }
     };
 
-    int stage = 0; // running stage counter: buffer parity
-    if (n_tiles > 0) fetch(0, 0);
+    for (int i = 0; i < kRing - 1; ++i) issue_next();
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int64_t stream0 = chunk_begin + (int64_t)tile * kStream;
 
         // first feature chunk: starts the accumulators
-        commit(stage & 1);
-        __syncthreads();
-        fetch(tile, 1); // n_st >= 2
-        feature_stage(img[stage & 1], std::true_type{});
-        ++stage;
+        stage_begin();
+        feature_stage(img + buf * kStageUnits, std::true_type{});
+        stage_end();
 
-        for (int st = 1; st < n_kc; ++st, ++stage) {
-            commit(stage & 1);
-            __syncthreads();
-            fetch(tile, st + 1);
-            feature_stage(img[stage & 1], std::false_type{});
+        for (int st = 1; st < n_kc; ++st) {
+            stage_begin();
+            feature_stage(img + buf * kStageUnits, std::false_type{});
+            stage_end();
         }
 
         // last stage: the norm slots, stream role (plane 1) against fixed role (plane 0);
         // the vectors of this tile are staged with it (every wavefront has passed this
         // tile's first barrier, so it is done with the previous tile's vectors)
-        commit(stage & 1);
         if constexpr (MV) {
             // combination id = tid + 256 i: stream block id / 128, K-step (id / 64) % 2, lane id % 64
             // = (column c, half hh); slot e of that lane is stream row 8 (2 q + e / 4) + 4 hh + e % 4
@@ -383,10 +438,10 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                 vimg[k] = in ? v : 0.0f;
             }
         }
-        __syncthreads();
-        if (tile + 1 < n_tiles) fetch(tile + 1, 0);
+        stage_begin();
+        const f16x8 *const norm_img = img + buf * kStageUnits;
         {
-            const f16x8 *ib = img[stage & 1];
+            const f16x8 *ib = norm_img;
             f16x8 bf[2];
 #pragma unroll
             for (int fb = 0; fb < 2; ++fb) bf[fb] = ib[(wave * 2 + fb) * kUnits + lane];
@@ -397,7 +452,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                 mfma_acc(acc[1][sb], as, bf[1]);
             }
         }
-        ++stage;
+        stage_end();
 
         // finish: register r of a lane is stream row 8 (r / 4) + 4 h + r % 4 of its block
         mfma_results_ready();
@@ -410,7 +465,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         float near[2] = {0.0f, 0.0f};
         bool any_near = false;
         if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
-            const f16x8 *ib = img[(stage - 1) & 1];
+            const f16x8 *ib = norm_img;
 #pragma unroll
             for (int fb = 0; fb < 2; ++fb) {
                 const f16x8 fx = ib[(wave * 2 + fb) * kUnits + (lane & 31)];
@@ -651,9 +706,17 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
     const int64_t n_patch_c = (chunks + pm.pc - 1) / pm.pc;
     const int64_t patches = (pm.n_patch_f * n_patch_c + 7) / 8 * 8;
     const dim3 grid((unsigned)(patches * kPatch));
+    // dynamic LDS: the ring of stages and the vector rows of a tile (more than the 64 KB a kernel gets
+    // without asking)
+    constexpr int kVecUnits = MV ? 4 * 2 * 2 * 64 : (kStream * TP * 4 + 15) / 16;
+    constexpr size_t lds_bytes = (size_t)(ring_depth(MV) * kStageUnits + kVecUnits) * sizeof(f16x8);
     auto launch = [&](auto kind) {
-        hipLaunchKernelGGL((gauss_gemm_f16_kernel<TP, MV, decltype(kind)::value>), grid, dim3(kThreads), 0, stream, a, Fimg,
-                           Simg, fixed_row0, chunk0, n_kc, pm, colmax);
+        auto *const kernel = gauss_gemm_f16_kernel<TP, MV, decltype(kind)::value>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes) != hipSuccess)
+            return;
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, stream, a, Fimg, Simg, fixed_row0, chunk0, n_kc, pm,
+                           colmax);
     };
     switch (a.kind) {
     case KNM_KERNEL_LAPLACIAN: launch(std::integral_constant<int, KNM_KERNEL_LAPLACIAN>{}); break;
