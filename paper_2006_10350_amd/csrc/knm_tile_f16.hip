@@ -50,9 +50,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 // stream points per LDS stage: 256 (eight tiles between barriers) while two workgroups' double buffers
-// still fit a CU's LDS and the registers hold the stage's vector entries without spills: up to four units
-// for the Gaussian kernel, two for the kernels of r
-constexpr int stage_of(int nu, int kind) { return nu <= (kind == KNM_KERNEL_GAUSSIAN ? 4 : 2) ? 256 : 128; }
+// still fit a CU's LDS, 128 for the six-unit layout
+constexpr int stage_of(int nu, int /*kind*/) { return nu <= 4 ? 256 : 128; }
 // ---- one MFMA followed by G (exp, FMA) pairs of the previous tile -------------------------
 #define KNM_MFMA_FIRST "v_mfma_f32_32x32x16_f16 %[acc], %[a], %[b], 0\n\t"
 #define KNM_MFMA_NEXT "v_mfma_f32_32x32x16_f16 %[acc], %[a], %[b], %[acc]\n\t"
@@ -338,13 +337,49 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
     const int n_stages = (int)((chunk_end - chunk_begin + kStage - 1) / kStage);
     const f16x8 *src = packed + ((int64_t)blockIdx.y * a.chunk_len / kStage) * UPS + tid;
 
-    f16x8 xs[UPT];
+    // The image goes from memory into LDS by loads that write LDS directly (a wavefront's 64 units land in
+    // the 1 KB at the address in M0), started one stage ahead; vmcnt counts them, and since the compiler
+    // does not look inside inline assembly the wait for them is written out where a stage begins.
+    const unsigned lds_wave = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) f16x8 *)&img[0][0][0][0][0] + (unsigned)wave * 1024u);
+    const unsigned src_off = (unsigned)tid * 16u;
+    auto issue = [&](int stage, int buf) {
+        const f16x8 *const b = src - tid + (int64_t)stage * UPS; // uniform
+        const unsigned l = lds_wave + (unsigned)buf * (unsigned)(UPS * 16);
+        unsigned m0_saved;
+        static_assert(UPT == 4 || UPT == 6 || UPT == 8, "one block of inline assembly per count");
+        // (one wait state between a scalar write of M0 and the load that reads it)
+#define KNM_DMA_FIRST "s_mov_b32 %[keep], m0\n\ts_mov_b32 m0, %[l]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[o], %[b0]\n\t"
+#define KNM_DMA_NEXT(k) "s_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[o], %[b" #k "]\n\t"
+#define KNM_DMA_LAST "s_mov_b32 m0, %[keep]"
+        if constexpr (UPT == 4)
+            asm volatile(KNM_DMA_FIRST KNM_DMA_NEXT(1) KNM_DMA_NEXT(2) KNM_DMA_NEXT(3) KNM_DMA_LAST
+                         : [keep] "=&s"(m0_saved)
+                         : [l] "s"(l), [o] "v"(src_off), [b0] "s"(b), [b1] "s"(b + kThreads), [b2] "s"(b + 2 * kThreads),
+                           [b3] "s"(b + 3 * kThreads)
+                         : "memory", "scc");
+        else if constexpr (UPT == 6)
+            asm volatile(KNM_DMA_FIRST KNM_DMA_NEXT(1) KNM_DMA_NEXT(2) KNM_DMA_NEXT(3) KNM_DMA_NEXT(4) KNM_DMA_NEXT(5) KNM_DMA_LAST
+                         : [keep] "=&s"(m0_saved)
+                         : [l] "s"(l), [o] "v"(src_off), [b0] "s"(b), [b1] "s"(b + kThreads), [b2] "s"(b + 2 * kThreads),
+                           [b3] "s"(b + 3 * kThreads), [b4] "s"(b + 4 * kThreads), [b5] "s"(b + 5 * kThreads)
+                         : "memory", "scc");
+        else
+            asm volatile(KNM_DMA_FIRST KNM_DMA_NEXT(1) KNM_DMA_NEXT(2) KNM_DMA_NEXT(3) KNM_DMA_NEXT(4) KNM_DMA_NEXT(5)
+                             KNM_DMA_NEXT(6) KNM_DMA_NEXT(7) KNM_DMA_LAST
+                         : [keep] "=&s"(m0_saved)
+                         : [l] "s"(l), [o] "v"(src_off), [b0] "s"(b), [b1] "s"(b + kThreads), [b2] "s"(b + 2 * kThreads),
+                           [b3] "s"(b + 3 * kThreads), [b4] "s"(b + 4 * kThreads), [b5] "s"(b + 5 * kThreads),
+                           [b6] "s"(b + 6 * kThreads), [b7] "s"(b + 7 * kThreads)
+                         : "memory", "scc");
+#undef KNM_DMA_FIRST
+#undef KNM_DMA_NEXT
+#undef KNM_DMA_LAST
+    };
     float vs = 0.0f;
     typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
     f16x4 digits = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
     auto fetch = [&](int stage) {
-#pragma unroll
-        for (int k = 0; k < UPT; ++k) xs[k] = src[(int64_t)stage * UPS + k * kThreads];
         const int sp = tid & (kStage - 1); // stream point of the stage this thread brings the vector entry of
         const int64_t idx = chunk_begin + (int64_t)stage * kStage + sp;
         const bool valid = idx < chunk_end;
@@ -360,9 +395,6 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         }
     };
     auto commit = [&](int buf) {
-        f16x8 *dst = &img[buf][0][0][0][0];
-#pragma unroll
-        for (int k = 0; k < UPT; ++k) dst[k * kThreads + tid] = xs[k];
         if (tid < kStage) vv[buf][tid] = vs;
         if constexpr (kRadial) {
             // the digits hold -n; a near pair has nearly equal norms, so the stream point's own
@@ -415,12 +447,19 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         }
     };
 
-    if (n_stages > 0) fetch(0);
+    if (n_stages > 0) {
+        issue(0, 0);
+        fetch(0);
+    }
     for (int st = 0; st < n_stages; ++st) {
         const int buf = st & 1;
         commit(buf);
-        __syncthreads();
-        if (st + 1 < n_stages) fetch(st + 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this thread's share of the stage has landed
+        __syncthreads();                                 // everyone's has, and the other buffer is free
+        if (st + 1 < n_stages) {
+            issue(st + 1, buf ^ 1);
+            fetch(st + 1);
+        }
 
         f16x8 bh[2][HU], bl[2][HU];
         float vl[2], th[2] = {0.0f, 0.0f};
