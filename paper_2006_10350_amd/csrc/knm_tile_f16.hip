@@ -30,8 +30,9 @@
 // points.  A small pre-pass (`pack_stream_kernel`) therefore converts the stream points
 // once into a packed image in device memory, laid out exactly as the LDS stage (per
 // 32-point tile: [plane xh/xl][MFMA][lane] units of 8 halves); the sweep's staging is then
-// a straight 16-byte copy.  The image is built slab by slab (bounded workspace) and the
-// sweep is launched once per slab.
+// a straight 16-byte copy, done by loads that write LDS directly (no staging registers, no
+// LDS write instructions), one stage ahead.  The image is built slab by slab (bounded
+// workspace) and the sweep is launched once per slab.
 //
 // Schedule.  Accumulators are double-buffered across stream tiles: while the matrix
 // cores run the 3 NU MFMAs of tile k (two fixed blocks), the VALU finishes tile k-1
