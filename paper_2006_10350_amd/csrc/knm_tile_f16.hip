@@ -259,12 +259,27 @@ __global__ __launch_bounds__(kThreads) void pack_stream_kernel(const float *__re
     }
 }
 
-// `packed` is the image of the stream chunks [chunk0, chunk0 + gridDim.y) built by
-// pack_stream_kernel; blockIdx.y counts chunks within that slab.
+// `packed` is the image of the stream chunks [chunk0, chunk0 + n_chunks) built by pack_stream_kernel.
+// Workgroup -> (fixed block, chunk of the slab).  Workgroups are dealt round-robin to the 8 XCDs (each with
+// its own L2) in launch order; the first 8 floor(n_chunks / 8) chunks are numbered so that all fixed blocks
+// of a chunk run on one XCD, one chunk after the other, and the chunk's image is fetched into one L2 instead
+// of eight; the remaining chunks are spread over all XCDs, so that every XCD gets the same work.
 template <int NU, int KIND>
 __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs a, const f16x8 *__restrict__ packed,
-                                                                      int64_t chunk0)
+                                                                      int64_t chunk0, int n_fblocks, int n_chunks)
 {
+    int64_t fblock, chunk_local;
+    const int grouped = n_chunks & ~7; // chunks that are dealt to one XCD each
+    if ((int64_t)blockIdx.x < (int64_t)grouped * n_fblocks) {
+        const int64_t slot = (int64_t)blockIdx.x >> 3;
+        chunk_local = (slot / n_fblocks) * 8 + (blockIdx.x & 7);
+        fblock = slot % n_fblocks;
+    } else {
+        const int64_t rest = (int64_t)blockIdx.x - (int64_t)grouped * n_fblocks;
+        fblock = rest % n_fblocks;
+        chunk_local = grouped + rest / n_fblocks;
+    }
+
     constexpr bool kRadial = KIND != KNM_KERNEL_GAUSSIAN;
     constexpr int HU = NU / 2;                      // MFMAs per plane
     constexpr int kStage = stage_of(NU, KIND);
@@ -286,7 +301,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
     const int d = a.d;
 
     // ---- fixed operand: 2 blocks of 32 points per wavefront, in registers -----------------
-    const int64_t fixed0 = ((int64_t)blockIdx.x * kWaves + wave) * 64;
+    const int64_t fixed0 = (fblock * kWaves + wave) * 64;
     f16x8 fh[2][HU], fl[2][HU], fhv[2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
@@ -314,7 +329,7 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         clamped |= (__shfl_xor((int)clamped, 32) != 0); // the two lanes of a point
         // one count per point and sweep: the workgroups of the first chunk report (every chunk's
         // workgroups convert the same fixed points)
-        if (clamped && valid && h == 0 && blockIdx.y == 0 && chunk0 == 0) atomicAdd(a.range_count, 1u);
+        if (clamped && valid && h == 0 && chunk_local == 0 && chunk0 == 0) atomicAdd(a.range_count, 1u);
         _Float16 q[4];
         norm_digits(valid ? 0.5f * nrm : 0.0f, q);
         fhv[rb] = fh[rb][HU - 1];
@@ -331,12 +346,12 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         for (int r = 0; r < 16; ++r) sum[rb][r] = 0.0f;
 
     // ---- stream staging: a straight copy of the packed image, 16 bytes per thread and unit --------
-    const int64_t chunk = chunk0 + blockIdx.y;
+    const int64_t chunk = chunk0 + chunk_local;
     const int64_t chunk_begin = chunk * a.chunk_len;
     int64_t chunk_end = chunk_begin + a.chunk_len;
     if (chunk_end > a.nS) chunk_end = a.nS;
     const int n_stages = (int)((chunk_end - chunk_begin + kStage - 1) / kStage);
-    const f16x8 *src = packed + ((int64_t)blockIdx.y * a.chunk_len / kStage) * UPS + tid;
+    const f16x8 *src = packed + (chunk_local * a.chunk_len / kStage) * UPS + tid;
 
     // The image goes from memory into LDS by loads that write LDS directly (a wavefront's 64 units land in
     // the 1 KB at the address in M0), started one stage ahead; vmcnt counts them, and since the compiler
@@ -564,8 +579,10 @@ hipError_t launch_nu(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipS
         else
             hipLaunchKernelGGL((pack_stream_kernel<NU, 1>), pgrid, dim3(kThreads), 0, stream, a.S, a.nS, a.lds, a.mu, a.d,
                                a.sigma, row0, rows, packed, a.range_count);
-        const dim3 grid((unsigned)blocks, (unsigned)nc);
-        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, KIND>), grid, dim3(kThreads), 0, stream, a, packed, c0);
+        const int64_t wgs = blocks * nc;
+        if (wgs > 0x7fffffff) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((gauss_sweep_f16_kernel<NU, KIND>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, a, packed, c0,
+                           (int)blocks, (int)nc);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
