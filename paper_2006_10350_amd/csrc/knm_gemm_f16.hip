@@ -295,9 +295,9 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
 #pragma unroll
     for (int i = 0; i < 4; ++i) off[i] = (toff + (unsigned)(2 * i) * (unsigned)blk_units) * 16u;
     auto issue = [&](int tile, int st, int buf) {
-        const f16x8 *const fs = fbase + (int64_t)st * kUnits;
-        const f16x8 *const ss = sbase + (int64_t)tile * (kStream / 32) * blk_units + (int64_t)st * kUnits;
-        const unsigned l = lds_wave + (unsigned)buf * (unsigned)(kStageUnits * 16);
+        const f16x8 *const fs = uniform_pointer(fbase + (int64_t)st * kUnits);
+        const f16x8 *const ss = uniform_pointer(sbase + (int64_t)tile * (kStream / 32) * blk_units + (int64_t)st * kUnits);
+        const unsigned l = __builtin_amdgcn_readfirstlane(lds_wave + (unsigned)buf * (unsigned)(kStageUnits * 16));
         unsigned m0_saved;
         // (one wait state between a scalar write of M0 and the load that reads it)
         asm volatile("s_mov_b32 %[keep], m0\n\t"

@@ -102,4 +102,15 @@ __device__ __forceinline__ void mfma_results_ready()
     asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory");
 }
 
+// A pointer that is the same in every lane, as a value the compiler keeps in scalar registers (an "s"
+// operand of inline assembly does not by itself move a value there).
+template <typename T>
+__device__ __forceinline__ const T *uniform_pointer(const T *p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const T *>(((uint64_t)hi << 32) | lo);
+}
+
 } // namespace knm

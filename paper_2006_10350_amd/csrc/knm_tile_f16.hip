@@ -360,8 +360,8 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_sweep_f16_kernel(SweepArgs 
         (unsigned)(uintptr_t)(__attribute__((address_space(3))) f16x8 *)&img[0][0][0][0][0] + (unsigned)wave * 1024u);
     const unsigned src_off = (unsigned)tid * 16u;
     auto issue = [&](int stage, int buf) {
-        const f16x8 *const b = src - tid + (int64_t)stage * UPS; // uniform
-        const unsigned l = lds_wave + (unsigned)buf * (unsigned)(UPS * 16);
+        const f16x8 *const b = uniform_pointer(src - tid + (int64_t)stage * UPS);
+        const unsigned l = __builtin_amdgcn_readfirstlane(lds_wave + (unsigned)buf * (unsigned)(UPS * 16));
         unsigned m0_saved;
         static_assert(UPT == 4 || UPT == 6 || UPT == 8, "one block of inline assembly per count");
         // (one wait state between a scalar write of M0 and the load that reads it)
