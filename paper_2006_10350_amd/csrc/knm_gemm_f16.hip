@@ -39,7 +39,8 @@
 // into the fp16 range, split likewise and staged in LDS in A-operand layout, and three
 // products P_hi V_hi + P_lo V_hi + P_hi V_lo accumulate a 32-column x 32-point output tile in
 // fp32.  That replaces t FMAs per kernel value by about three conversion instructions and
-// serves up to 32 columns per launch.
+// serves up to 128 columns per launch: up to four groups of 32, each with its own output tile,
+// fed by the same split kernel values.
 
 #include <type_traits>
 
@@ -60,8 +61,11 @@ constexpr int kUnits = 128;                    // 16-byte units per block and ch
 constexpr int kLoads = kBlocks * kUnits / kThreads; // units copied per thread and stage (6)
 constexpr int kStageUnits = kBlocks * kUnits;       // 16-byte units of one LDS stage (24 KB)
 // Stages in the LDS ring: 3 (two stages of loads in flight) where two workgroups' rings and vector rows
-// fit a CU's 160 KB, 2 for the matrix-core reduction with its 16 KB of vector halves
-constexpr int ring_depth(bool mv) { return mv ? 2 : 3; }
+// fit a CU's 160 KB, 2 for the matrix-core reduction with one column group and its 16 KB of vector halves
+// (with more groups a workgroup has the CU's LDS for itself: 3 again)
+constexpr int ring_depth(bool mv, int tp) { return mv && tp == 2 ? 2 : 3; }
+// the matrix-core reduction with more than one group of 32 columns takes a CU for itself
+constexpr int workgroups_per_cu(bool mv, int tp) { return mv && tp > 2 ? 1 : 2; }
 constexpr float kPScale = 16384.0f; // matrix-core reduction: kernel values are split into fp16 halves after this scale
 // Image of points [row0, row0 + 32 gridDim.x) of P (points at or beyond nP become zero
 // points).  One workgroup per 32-point block; thread = (point, 8-feature unit), four
@@ -211,9 +215,12 @@ struct PatchMap {
 // Fimg: image of the fixed points [fixed_row0, fixed_row0 + 256 n_fblocks);
 // Simg: image of the stream chunks [chunk0, chunk0 + n_chunks).
 // TP: number of vector columns, padded to a multiple of 2 (vector-ALU reduction).  MV: reduce
-// on the matrix cores instead (up to 32 columns; TP unused); colmax[c] = bits of max |vec[:, c]|.
+// on the matrix cores instead, TP / 2 groups of 32 columns each (1, 2 or 4: the kernel values of a
+// tile are evaluated and split once and multiplied into every group; more than one group needs the
+// registers and the LDS of a whole CU, so those instantiations run one workgroup per CU);
+// colmax[c] = bits of max |vec[:, c]|.
 template <int TP, bool MV, int KIND>
-__global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
+__global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
                                                                      const f16x8 *__restrict__ Simg,
                                                                      int64_t fixed_row0, int64_t chunk0, int n_kc,
                                                                      PatchMap pm, const uint32_t *__restrict__ colmax)
@@ -229,7 +236,9 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     // Ring of operand stages (24 KB each) in dynamic LDS, filled by loads that write LDS directly, and
     // behind it the vector rows of a tile: fp32 [stream point][column], or for MV split halves in
     // A-operand layout [stream block][K-step][plane hi/lo][lane]
-    constexpr int kRing = ring_depth(MV);
+    constexpr int kRing = ring_depth(MV, TP);
+    constexpr int G = MV ? TP / 2 : 1; // column groups of the matrix-core reduction
+    static_assert(!MV || TP == 2 || TP == 4 || TP == 8, "1, 2 or 4 groups of 32 columns");
     extern __shared__ __align__(16) unsigned char lds_dyn[];
     f16x8 *const img = reinterpret_cast<f16x8 *>(lds_dyn);
     f16x8 *const vstore = img + kRing * kStageUnits;
@@ -274,13 +283,17 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
             if constexpr (kWide) wide[fb][c] = 0.0;
         }
     // MV: output tile [column][fixed point] of each fixed block, and this thread's column scale
-    f32x16 dacc[2];
+    f32x16 dacc[G][2];
+    float vscale[G];
 #pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
+    for (int g = 0; g < G; ++g) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) dacc[fb][r] = 0.0f;
-    float vscale = 1.0f;
-    if constexpr (MV) vscale = column_scale(colmax[lane & 31], false);
+        for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dacc[g][fb][r] = 0.0f;
+        vscale[g] = 1.0f;
+        if constexpr (MV) vscale[g] = column_scale(colmax[32 * g + (lane & 31)], false);
+    }
 
     // Staging.  The images are laid out as the LDS stage, so a stage is 6 loads of 16 bytes per thread
     // that go from memory into LDS without passing through registers: a wavefront's 64 units land in
@@ -400,32 +413,36 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
         // tile's first barrier, so it is done with the previous tile's vectors)
         if constexpr (MV) {
             // combination id = tid + 256 i: stream block id / 128, K-step (id / 64) % 2, lane id % 64
-            // = (column c, half hh); slot e of that lane is stream row 8 (2 q + e / 4) + 4 hh + e % 4
-            const int c = lane & 31, hh = lane >> 5;
+            // = (column c of the group, half hh); slot e of that lane is stream row 8 (2 q + e / 4) + 4 hh + e % 4
+            const int hh = lane >> 5;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int id = tid + kThreads * i;
-                const int sb = id >> 7, q = (id >> 6) & 1;
-                f16x8 hi, lo;
+            for (int g = 0; g < G; ++g) {
+                const int c = 32 * g + (lane & 31);
 #pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    float v2[2];
+                for (int i = 0; i < 2; ++i) {
+                    const int id = tid + kThreads * i;
+                    const int sb = id >> 7, q = (id >> 6) & 1;
+                    f16x8 hi, lo;
 #pragma unroll
-                    for (int k = 0; k < 2; ++k) {
-                        const int64_t idx = stream0 + sb * 32 + 8 * (2 * q + (e + k) / 4) + 4 * hh + (e + k) % 4;
-                        const bool in = idx < chunk_end && c < t;
-                        const int64_t vi = in ? idx : 0;
-                        float v = a.vec[vi * a.ldv + (in ? c : 0)];
-                        if (a.wgt != nullptr) v *= a.wgt[vi];
-                        v2[k] = in ? v * vscale : 0.0f;
+                    for (int e = 0; e < 8; e += 2) {
+                        float v2[2];
+#pragma unroll
+                        for (int k = 0; k < 2; ++k) {
+                            const int64_t idx = stream0 + sb * 32 + 8 * (2 * q + (e + k) / 4) + 4 * hh + (e + k) % 4;
+                            const bool in = idx < chunk_end && c < t;
+                            const int64_t vi = in ? idx : 0;
+                            float v = a.vec[vi * a.ldv + (in ? c : 0)];
+                            if (a.wgt != nullptr) v *= a.wgt[vi];
+                            v2[k] = in ? v * vscale[g] : 0.0f;
+                        }
+                        f16x2 ph, pl;
+                        split_pair(v2[0], v2[1], ph, pl);
+                        hi[e] = (_Float16)ph[0]; hi[e + 1] = (_Float16)ph[1];
+                        lo[e] = (_Float16)pl[0]; lo[e + 1] = (_Float16)pl[1];
                     }
-                    f16x2 ph, pl;
-                    split_pair(v2[0], v2[1], ph, pl);
-                    hi[e] = (_Float16)ph[0]; hi[e + 1] = (_Float16)ph[1];
-                    lo[e] = (_Float16)pl[0]; lo[e + 1] = (_Float16)pl[1];
+                    vstore[(((g * 4 + sb) * 2 + q) * 2 + 0) * 64 + lane] = hi;
+                    vstore[(((g * 4 + sb) * 2 + q) * 2 + 1) * 64 + lane] = lo;
                 }
-                vstore[((sb * 2 + q) * 2 + 0) * 64 + lane] = hi;
-                vstore[((sb * 2 + q) * 2 + 1) * 64 + lane] = lo;
             }
         } else {
             for (int k = tid; k < kStream * TP; k += kThreads) {
@@ -513,8 +530,12 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
             for (int sb = 0; sb < 4; ++sb)
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
-                    const f16x8 vh = vstore[((sb * 2 + q) * 2 + 0) * 64 + lane];
-                    const f16x8 vl = vstore[((sb * 2 + q) * 2 + 1) * 64 + lane];
+                    f16x8 vh[G], vl[G];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        vh[g] = vstore[(((g * 4 + sb) * 2 + q) * 2 + 0) * 64 + lane];
+                        vl[g] = vstore[(((g * 4 + sb) * 2 + q) * 2 + 1) * 64 + lane];
+                    }
 #pragma unroll
                     for (int fb = 0; fb < 2; ++fb) {
                         // kernel values of registers 8 q .. 8 q + 7, split into halves: K-slot e of
@@ -532,14 +553,17 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                             pl[e / 2] = __builtin_bit_cast(uint32_t, l2);
                         }
                         const f16x8 bh = __builtin_bit_cast(f16x8, ph), bl = __builtin_bit_cast(f16x8, pl);
-                        mfma_accv(dacc[fb], vh, bh);
-                        mfma_accv(dacc[fb], vh, bl);
-                        mfma_accv(dacc[fb], vl, bh);
+#pragma unroll
+                        for (int g = 0; g < G; ++g) {
+                            mfma_accv(dacc[g][fb], vh[g], bh);
+                            mfma_accv(dacc[g][fb], vh[g], bl);
+                            mfma_accv(dacc[g][fb], vl[g], bh);
+                        }
                     }
                 }
             if constexpr (KIND != KNM_KERNEL_GAUSSIAN) {
                 if (__builtin_amdgcn_ballot_w64(any_near) != 0) {
-                    // The 32 columns of a fixed point are spread over its two lanes (one per
+                    // The 32 columns of a group of a fixed point are spread over its two lanes (one per
                     // half-wave), so the two exchange their pairs and each adds both to its own
                     // columns, scaled like the vector image.
                     auto add_pair = [&](int fb, float p, int jl) {
@@ -547,10 +571,14 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
                         const int64_t j = stream0 + jl;
                         const float w = a.wgt != nullptr ? a.wgt[j] : 1.0f;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int c = 8 * (r / 4) + 4 * h + (r % 4);
-                            if (c < t) dacc[fb][r] = fmaf(kPScale * p * w * column_scale(colmax[c], false), a.vec[j * a.ldv + c], dacc[fb][r]);
-                        }
+                        for (int g = 0; g < G; ++g)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int c = 32 * g + 8 * (r / 4) + 4 * h + (r % 4);
+                                if (c < t)
+                                    dacc[g][fb][r] = fmaf(kPScale * p * w * column_scale(colmax[c], false), a.vec[j * a.ldv + c],
+                                                          dacc[g][fb][r]);
+                            }
                     };
 #pragma unroll
                     for (int fb = 0; fb < 2; ++fb) {
@@ -629,16 +657,18 @@ __global__ __launch_bounds__(kThreads, 2) void gauss_gemm_f16_kernel(SweepArgs a
     };
     mfma_results_ready();
     if constexpr (MV) {
-        // register r of a lane: column 8 (r / 4) + 4 h + r % 4 of fixed point lane % 32; undo the scale
+        // register r of a lane, group g: column 32 g + 8 (r / 4) + 4 h + r % 4 of fixed point lane % 32; undo the scale
 #pragma unroll
         for (int fb = 0; fb < 2; ++fb) {
             const int64_t idx = fixed0 + (wave * 2 + fb) * 32 + (lane & 31);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int c = 8 * (r / 4) + 4 * h + (r % 4);
-                if (idx < a.nF && c < t)
-                    store(idx * a.ldo + c, (double)((dacc[fb][r] * (1.0f / kPScale)) * column_scale(colmax[c], true)));
-            }
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int c = 32 * g + 8 * (r / 4) + 4 * h + (r % 4);
+                    if (idx < a.nF && c < t)
+                        store(idx * a.ldo + c, (double)((dacc[g][fb][r] * (1.0f / kPScale)) * column_scale(colmax[c], true)));
+                }
         }
     } else {
         // the two half-waves hold different stream rows of the same fixed point
@@ -664,10 +694,10 @@ __global__ void clear_head_kernel(uint32_t *__restrict__ head) { head[threadIdx.
 __global__ void col_absmax_kernel(const float *__restrict__ vec, int64_t ldv, const float *__restrict__ wgt, int64_t n,
                                   int t, uint32_t *__restrict__ out)
 {
-    const int c = threadIdx.x & 31;
+    const int c = threadIdx.x & 127;
     float m = 0.0f;
     if (c < t)
-        for (int64_t i = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5); i < n; i += (int64_t)gridDim.x * 8) {
+        for (int64_t i = (int64_t)blockIdx.x * 2 + (threadIdx.x >> 7); i < n; i += (int64_t)gridDim.x * 2) {
             float v = vec[i * ldv + c];
             if (wgt != nullptr) v *= wgt[i];
             m = fmaxf(m, fabsf(v));
@@ -691,7 +721,7 @@ constexpr int kPatch = 64;  // workgroups per patch = resident workgroups per XC
 constexpr int kPatchF = 8;  // fixed blocks per patch (measured: 2..8 within 4 % of each other, 64 is 25 % slower)
 
 constexpr int kMvMinT = 8;    // columns from which the reduction against the vectors may run on the matrix cores
-constexpr size_t kHeadBytes = 256; // head of the workspace: per-column magnitude words for that path
+constexpr size_t kHeadBytes = 512; // head of the workspace: per-column magnitude words for that path (128 columns)
 
 template <int TP, bool MV>
 void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t fixed_row0, int64_t f_blocks,
@@ -708,8 +738,8 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
     const dim3 grid((unsigned)(patches * kPatch));
     // dynamic LDS: the ring of stages and the vector rows of a tile (more than the 64 KB a kernel gets
     // without asking)
-    constexpr int kVecUnits = MV ? 4 * 2 * 2 * 64 : (kStream * TP * 4 + 15) / 16;
-    constexpr size_t lds_bytes = (size_t)(ring_depth(MV) * kStageUnits + kVecUnits) * sizeof(f16x8);
+    constexpr int kVecUnits = MV ? (TP / 2) * 4 * 2 * 2 * 64 : (kStream * TP * 4 + 15) / 16;
+    constexpr size_t lds_bytes = (size_t)(ring_depth(MV, TP) * kStageUnits + kVecUnits) * sizeof(f16x8);
     auto launch = [&](auto kind) {
         auto *const kernel = gauss_gemm_f16_kernel<TP, MV, decltype(kind)::value>;
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -739,7 +769,22 @@ size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len,
     return kHeadBytes + (f <= s ? f + (size_t)chunk_len * pp : s + (size_t)kFixed * pp);
 }
 
-int gemm_f16_max_t() { return 32; }
+int gemm_f16_max_t() { return 128; }
+
+// Columns to take in the next launch when t_left are still to do.  Up to 32 columns run two workgroups per
+// CU, whose finishing phases (vector staging, conversions, second contraction) hide behind each other's
+// cross terms; 64 or 128 columns evaluate the kernel values once for all of them but run one workgroup per
+// CU with nothing to hide behind, which pays once the cross term is long.  Per 1e11 kernel entries the
+// launches measured about (0.015 k + 0.06) s for up to 32 columns, (0.016 k + 0.36) s for 64 and
+// (0.016 k + 0.68) s for 128, with k = ceil(d / 16) chunks of features.
+int gemm_f16_group_t(int d, int t_left)
+{
+    const int n_kc = (d + kChunk - 1) / kChunk;
+    if (t_left > 96 && n_kc >= 10) return 128; // in place of four launches
+    if (t_left > 64 && n_kc >= 17) return 128; // in place of three
+    if (t_left > 32 && n_kc >= 17) return 64;  // in place of two
+    return 32;
+}
 
 hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
@@ -776,7 +821,7 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
         hipLaunchKernelGGL(clear_head_kernel, dim3(1), dim3(kHeadBytes / sizeof(uint32_t)), 0, stream, colmax);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        int64_t blocks = (a.nS + 7) / 8;
+        int64_t blocks = (a.nS + 1) / 2;
         if (blocks > 4096) blocks = 4096;
         hipLaunchKernelGGL(col_absmax_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a.vec, a.ldv, a.wgt, a.nS,
                            a.t, colmax);
@@ -794,7 +839,9 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
             }
             const int64_t fb = f_rows / kFixed;
             if (mv) {
-                launch_tp<2, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                if (a.t <= 32) launch_tp<2, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                else if (a.t <= 64) launch_tp<4, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                else launch_tp<8, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
             } else {
                 switch ((a.t + 1) / 2) {
                 case 1: launch_tp<2, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;

@@ -109,7 +109,8 @@ hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream);
 // the same shapes with the cross term as three f16 MFMA products (knm_gemm_f16.hip); both
 // operands are packed into the workspace, whole or slab by slab
 size_t gemm_f16_pack_bytes_per_point(int d);
-int gemm_f16_max_t(); // columns per launch
+int gemm_f16_max_t(); // columns per launch at most
+int gemm_f16_group_t(int d, int t_left); // columns the next launch should take
 size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len, int d);
 hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream);
 // out[j * ldo] = sum over chunks of part[chunk * chunk_stride + j * ldp], summed in fp64 in a fixed

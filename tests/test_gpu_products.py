@@ -56,10 +56,17 @@ SHAPES = [
     (600, 300, 784, 10, 24.0),
     (257, 385, 99, 3, 7.0),
     (1000, 2100, 16, 17, 3.0),
-    # 8-32 columns: reduction against the vectors on the matrix cores; 40 = two launches
+    # 8 columns and more: reduction against the vectors on the matrix cores, in 1, 2 or 4 groups of 32
+    # columns per launch; 144 = two launches (128 + 16)
     (700, 390, 20, 32, 3.0),
     (500, 300, 6, 40, 1.5),
     (2300, 700, 28, 9, 4.0),
+    (900, 520, 28, 64, 4.0),
+    (520, 900, 50, 65, 5.0),
+    (1100, 300, 440, 128, 20.0),
+    (640, 385, 33, 144, 5.0),
+    (300, 260, 300, 50, 18.0),
+    (257, 300, 280, 70, 17.0),
 ]
 
 

@@ -62,6 +62,9 @@ SHAPES = [
     (1100, 700, 20, 32, 5.0),
     (900, 300, 6, 40, 2.5),
     (2300, 700, 28, 9, 6.0),
+    (700, 520, 28, 70, 6.0),
+    (400, 320, 300, 70, 40.0),
+    (300, 260, 290, 40, 40.0),
 ]
 
 
