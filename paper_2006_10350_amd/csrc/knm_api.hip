@@ -89,6 +89,7 @@ int ensure(knm_ctx *ctx, float **buf, size_t *cur, size_t need)
 // end of the process.  Host code never uses this name as an address: knm_create looks up the
 // device's own copy with hipGetSymbolAddress and keeps the pointer in the context.
 constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr size_t kVectorImageCap = (size_t)16 << 30; // largest packed vector image the library allocates
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // One piece of a sweep's workspace: grown on demand in the context's own buffer, or, in a call that
@@ -274,7 +275,14 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
     // columns per launch
     int group = 1;
     for (int c = 0; c < t; c += group) {
-        group = !gemm ? 1 : (ctx->cross_term == KNM_CROSS_F16X3 ? gemm_f16_group_t(d, t - c) : gemm_max_t());
+        // (K-loop split-fp16 engine: wide launches when the vectors can be given as a packed image, which a
+        // call that must not allocate does without, as does one whose image would be very large)
+        bool vector_image = gemm && ctx->cross_term == KNM_CROSS_F16X3 && !ctx->static_mode;
+        if (vector_image) {
+            const int wide = gemm_f16_group_t(d, t - c, true);
+            vector_image = gemm_f16_vector_image_bytes(d, t - c < wide ? t - c : wide, chunks * chunk_len) <= kVectorImageCap;
+        }
+        group = !gemm ? 1 : (ctx->cross_term == KNM_CROSS_F16X3 ? gemm_f16_group_t(d, t - c, vector_image) : gemm_max_t());
         SweepArgs a;
         a.F = F; a.nF = nF; a.ldf = ldf;
         a.S = S; a.nS = nS; a.lds = lds;
@@ -324,6 +332,14 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
             int st = pack_room(&want);
             if (!st) st = acquire(ctx, &ctx->pack_buf, &ctx->pack_bytes, want, &pack);
             if (st) return st;
+            // the vectors as a packed image, when the matrix-core reduction runs and the image is of moderate
+            // size (a call that must not allocate leaves the conversion to the workgroups)
+            const size_t vbytes = vector_image ? gemm_f16_vector_image_bytes(d, a.t, chunks * chunk_len) : 0;
+            if (vbytes > 0) {
+                st = ensure(ctx, &ctx->vimg_buf, &ctx->vimg_bytes, vbytes);
+                if (st) return st;
+                a.vimg = ctx->vimg_buf;
+            }
             e = launch_sweep_gemm_f16(a, pack, want, ctx->stream);
         } else if (gemm) {
             e = launch_sweep_gemm(a, ctx->stream);
@@ -437,6 +453,7 @@ int knm_destroy(knm_ctx *ctx)
     if (ctx->w_buf) (void)hipFree(ctx->w_buf);
     if (ctx->part_buf) (void)hipFree(ctx->part_buf);
     if (ctx->pack_buf) (void)hipFree(ctx->pack_buf);
+    if (ctx->vimg_buf) (void)hipFree(ctx->vimg_buf);
     if (ctx->mu_buf) (void)hipFree(ctx->mu_buf);
     if (ctx->range_count) (void)hipFree(ctx->range_count);
     for (int i = 0; i < 5; ++i)

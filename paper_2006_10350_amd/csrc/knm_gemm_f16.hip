@@ -219,12 +219,15 @@ struct PatchMap {
 // tile are evaluated and split once and multiplied into every group; more than one group needs the
 // registers and the LDS of a whole CU, so those instantiations run one workgroup per CU);
 // colmax[c] = bits of max |vec[:, c]|.
-template <int TP, bool MV, int KIND>
+// VI (with MV): the vector halves of a tile come from the packed image a.vimg (pack_vectors_kernel) by
+// direct-to-LDS loads instead of being converted by the workgroup.
+template <int TP, bool MV, int KIND, bool VI = false>
 __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
                                                                      const f16x8 *__restrict__ Simg,
                                                                      int64_t fixed_row0, int64_t chunk0, int n_kc,
                                                                      PatchMap pm, const uint32_t *__restrict__ colmax)
 {
+    static_assert(MV || !VI, "the packed vector image belongs to the matrix-core reduction");
     const int per_patch = pm.pf * pm.pc;
     const int64_t slot = (int64_t)blockIdx.x >> 3;
     const int64_t patch = (slot / per_patch) * 8 + (blockIdx.x & 7);
@@ -351,15 +354,78 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
             }
         }
     };
-    // Start of stage g (ring slot `buf`): this thread's loads of the stage have landed when at most the
-    // loads of the kRing - 2 stages started after it are outstanding; after the barrier everyone's have,
-    // and everyone is done reading the slot of stage g - 1, which the stage kRing - 1 ahead takes over.
+    // The packed vector image of a tile (VI): 4 G loads per thread into the vector store behind the ring,
+    // started at the tile's first stage (every wavefront has passed that stage's barrier, so it is done
+    // with the previous tile's vectors) and needed at its last.
+    constexpr int kVecLoads = 4 * G;
+    const unsigned lds_vec = __builtin_amdgcn_readfirstlane(lds_wave + (unsigned)(kRing * kStageUnits * 16));
+    const f16x8 *const vchunk =
+        VI ? static_cast<const f16x8 *>(a.vimg) + (chunk * (a.chunk_len / kStream)) * (int64_t)(G * 4 * kThreads) : nullptr;
+    auto issue_vectors = [&](int tile) {
+        const f16x8 *const vt = vchunk + (int64_t)tile * (G * 4 * kThreads);
+#pragma unroll
+        for (int k4 = 0; k4 < G; ++k4) {
+            const f16x8 *const b = uniform_pointer(vt + k4 * 4 * kThreads);
+            const unsigned l = __builtin_amdgcn_readfirstlane(lds_vec + (unsigned)(k4 * 4 * kThreads * 16));
+            unsigned m0_saved;
+            asm volatile("s_mov_b32 %[keep], m0\n\t"
+                         "s_mov_b32 m0, %[l]\n\t"
+                         "s_nop 0\n\t"
+                         "global_load_lds_dwordx4 %[o], %[b0]\n\t"
+                         "s_add_u32 m0, m0, 0x1000\n\t"
+                         "s_nop 0\n\t"
+                         "global_load_lds_dwordx4 %[o], %[b1]\n\t"
+                         "s_add_u32 m0, m0, 0x1000\n\t"
+                         "s_nop 0\n\t"
+                         "global_load_lds_dwordx4 %[o], %[b2]\n\t"
+                         "s_add_u32 m0, m0, 0x1000\n\t"
+                         "s_nop 0\n\t"
+                         "global_load_lds_dwordx4 %[o], %[b3]\n\t"
+                         "s_mov_b32 m0, %[keep]"
+                         : [keep] "=&s"(m0_saved)
+                         : [l] "s"(l), [o] "v"((unsigned)tid * 16u), [b0] "s"(b), [b1] "s"(b + kThreads), [b2] "s"(b + 2 * kThreads),
+                           [b3] "s"(b + 3 * kThreads)
+                         : "memory", "scc");
+        }
+    };
+    // Start of stage g (ring slot `buf`).  Loads complete in the order they were started, so this thread's
+    // loads of the stage have landed when no more loads are outstanding than were started after them: those
+    // of the stages ahead (`ahead` of them, kRing - 2 unless the chunk ends) and, for kRing - 1 stage starts
+    // after a tile's first, that tile's vector loads.  At a tile's last stage its vectors must have landed as
+    // well, which holds once the stage loads started after them (one per stage start since) cover what is
+    // allowed to be outstanding.  After the barrier everyone's loads have landed, and everyone is done
+    // reading the slot of stage g - 1, which the stage kRing - 1 ahead takes over.
+    static_assert(kRing == 2 || kRing == 3, "the waits below are written for at most one stage ahead");
     int g = 0, buf = 0;
-    auto stage_begin = [&]() {
-        if (kRing > 2 && g + kRing - 2 < total) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads * (kRing - 2)) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int since_vectors = kRing; // stage starts since vector loads were started (none yet)
+    auto stage_begin = [&](bool first_of_tile, bool last_of_tile, int tile) {
+        int ahead = total - 1 - g;
+        if (ahead > kRing - 2) ahead = kRing - 2;
+        bool with_vectors = false;
+        if constexpr (VI) {
+            if (last_of_tile) {
+                if (ahead > n_st - 2) ahead = n_st - 2;
+            } else {
+                with_vectors = since_vectors <= kRing - 1;
+            }
+        }
+        if (ahead > 0) {
+            if (with_vectors) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads + kVecLoads) : "memory");
+            else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads) : "memory");
+        } else {
+            if (with_vectors) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kVecLoads) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         __syncthreads();
         issue_next();
+        if constexpr (VI) {
+            if (first_of_tile) {
+                issue_vectors(tile);
+                since_vectors = 1;
+            } else if (since_vectors < kRing) {
+                ++since_vectors;
+            }
+        }
     };
     auto stage_end = [&]() {
         ++g;
@@ -398,12 +464,12 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
         const int64_t stream0 = chunk_begin + (int64_t)tile * kStream;
 
         // first feature chunk: starts the accumulators
-        stage_begin();
+        stage_begin(true, false, tile);
         feature_stage(img + buf * kStageUnits, std::true_type{});
         stage_end();
 
         for (int st = 1; st < n_kc; ++st) {
-            stage_begin();
+            stage_begin(false, false, tile);
             feature_stage(img + buf * kStageUnits, std::false_type{});
             stage_end();
         }
@@ -411,7 +477,7 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
         // last stage: the norm slots, stream role (plane 1) against fixed role (plane 0);
         // the vectors of this tile are staged with it (every wavefront has passed this
         // tile's first barrier, so it is done with the previous tile's vectors)
-        if constexpr (MV) {
+        if constexpr (MV && !VI) {
             // combination id = tid + 256 i: stream block id / 128, K-step (id / 64) % 2, lane id % 64
             // = (column c of the group, half hh); slot e of that lane is stream row 8 (2 q + e / 4) + 4 hh + e % 4
             const int hh = lane >> 5;
@@ -444,7 +510,7 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
                     vstore[(((g * 4 + sb) * 2 + q) * 2 + 1) * 64 + lane] = lo;
                 }
             }
-        } else {
+        } else if constexpr (!MV) {
             for (int k = tid; k < kStream * TP; k += kThreads) {
                 const int j = k / TP, c = k % TP;
                 const int64_t idx = stream0 + j;
@@ -455,7 +521,7 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
                 vimg[k] = in ? v : 0.0f;
             }
         }
-        stage_begin();
+        stage_begin(false, true, tile);
         const f16x8 *const norm_img = img + buf * kStageUnits;
         {
             const f16x8 *ib = norm_img;
@@ -705,6 +771,52 @@ __global__ void col_absmax_kernel(const float *__restrict__ vec, int64_t ldv, co
     if (c < t && m > 0.0f) atomicMax(out + c, __float_as_uint(m));
 }
 
+// Packed vector image for the matrix-core reduction: per tile of 128 stream points and group g of 32
+// columns the split halves of the scaled vector rows in A-operand layout, [g][stream block][K-step][plane
+// hi/lo][lane] units of 8 halves, exactly what a workgroup would otherwise build in LDS for each of its
+// tiles.  One workgroup per tile; thread = (stream block, K-step, lane) twice.
+template <int G>
+__global__ __launch_bounds__(kThreads) void pack_vectors_kernel(const float *__restrict__ vec, int64_t ldv,
+                                                                const float *__restrict__ wgt, int64_t nS, int t,
+                                                                const uint32_t *__restrict__ colmax, f16x8 *__restrict__ vimg)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int hh = lane >> 5;
+    const int64_t stream0 = (int64_t)blockIdx.x * kStream;
+    f16x8 *const out = vimg + (int64_t)blockIdx.x * (G * 4 * kThreads);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int c = 32 * g + (lane & 31);
+        const float vscale = column_scale(colmax[c], false);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int id = tid + kThreads * i;
+            const int sb = id >> 7, q = (id >> 6) & 1;
+            f16x8 hi, lo;
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                float v2[2];
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const int64_t idx = stream0 + sb * 32 + 8 * (2 * q + (e + k) / 4) + 4 * hh + (e + k) % 4;
+                    const bool in = idx < nS && c < t;
+                    const int64_t vi = in ? idx : 0;
+                    float v = vec[vi * ldv + (in ? c : 0)];
+                    if (wgt != nullptr) v *= wgt[vi];
+                    v2[k] = in ? v * vscale : 0.0f;
+                }
+                f16x2 ph, pl;
+                split_pair(v2[0], v2[1], ph, pl);
+                hi[e] = (_Float16)ph[0]; hi[e + 1] = (_Float16)ph[1];
+                lo[e] = (_Float16)pl[0]; lo[e + 1] = (_Float16)pl[1];
+            }
+            out[(((g * 4 + sb) * 2 + q) * 2 + 0) * 64 + lane] = hi;
+            out[(((g * 4 + sb) * 2 + q) * 2 + 1) * 64 + lane] = lo;
+        }
+    }
+}
+
 hipError_t pack_points(const float *P, int64_t nP, int64_t ld, const float *mu, int d, float sigma, int64_t row0,
                        int64_t rows, int n_kc, f16x8 *img, unsigned int *range_count, hipStream_t stream)
 {
@@ -723,7 +835,7 @@ constexpr int kPatchF = 8;  // fixed blocks per patch (measured: 2..8 within 4 %
 constexpr int kMvMinT = 8;    // columns from which the reduction against the vectors may run on the matrix cores
 constexpr size_t kHeadBytes = 512; // head of the workspace: per-column magnitude words for that path (128 columns)
 
-template <int TP, bool MV>
+template <int TP, bool MV, bool VI = false>
 void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t fixed_row0, int64_t f_blocks,
                int64_t chunk0, int64_t chunks, int n_kc, const uint32_t *colmax, hipStream_t stream)
 {
@@ -741,7 +853,7 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
     constexpr int kVecUnits = MV ? (TP / 2) * 4 * 2 * 2 * 64 : (kStream * TP * 4 + 15) / 16;
     constexpr size_t lds_bytes = (size_t)(ring_depth(MV, TP) * kStageUnits + kVecUnits) * sizeof(f16x8);
     auto launch = [&](auto kind) {
-        auto *const kernel = gauss_gemm_f16_kernel<TP, MV, decltype(kind)::value>;
+        auto *const kernel = gauss_gemm_f16_kernel<TP, MV, decltype(kind)::value, VI>;
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes) != hipSuccess)
             return;
@@ -771,14 +883,32 @@ size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len,
 
 int gemm_f16_max_t() { return 128; }
 
-// Columns to take in the next launch when t_left are still to do.  Up to 32 columns run two workgroups per
-// CU, whose finishing phases (vector staging, conversions, second contraction) hide behind each other's
-// cross terms; 64 or 128 columns evaluate the kernel values once for all of them but run one workgroup per
-// CU with nothing to hide behind, which pays once the cross term is long.  Per 1e11 kernel entries the
-// launches measured about (0.015 k + 0.06) s for up to 32 columns, (0.016 k + 0.36) s for 64 and
-// (0.016 k + 0.68) s for 128, with k = ceil(d / 16) chunks of features.
-int gemm_f16_group_t(int d, int t_left)
+// Matrix-core reduction when it pays: from kMvMinT columns on, unless the cross term is so long
+// (large d) that the vector-ALU reduction hides behind it anyway.  Above 16 columns it is the
+// only path.
+static bool reduce_on_matrix_cores(int d, int t)
 {
+    const int n_kc = (d + kChunk - 1) / kChunk;
+    return t > 16 || (t >= kMvMinT && 4 * (3 + t) >= 3 * n_kc + 1);
+}
+static int column_groups(int t) { return t <= 32 ? 1 : (t <= 64 ? 2 : 4); }
+
+size_t gemm_f16_vector_image_bytes(int d, int t, int64_t nS_padded)
+{
+    if (t <= 0 || t > gemm_f16_max_t() || !reduce_on_matrix_cores(d, t)) return 0;
+    return (size_t)(nS_padded / kStream) * (size_t)(column_groups(t) * 4 * kThreads) * sizeof(f16x8);
+}
+
+// Columns to take in the next launch when t_left are still to do.  64 or 128 columns evaluate the kernel
+// values once for all of them but run one workgroup per CU.  With the packed vector image that is faster
+// at every d (per 1e11 kernel entries, d = 28: 0.187 s for 128 columns in one launch against 0.320 s in
+// four; d = 256: 0.438 s against 1.144 s).  Without the image every workgroup converts the vector rows of
+// its tiles itself, and with one workgroup per CU nothing hides that: the launches then measured about
+// (0.015 k + 0.06) s for up to 32 columns, (0.016 k + 0.36) s for 64 and (0.016 k + 0.68) s for 128, with
+// k = ceil(d / 16) chunks of features, so the wide launches pay only once the cross term is long.
+int gemm_f16_group_t(int d, int t_left, bool with_vector_image)
+{
+    if (with_vector_image) return gemm_f16_max_t();
     const int n_kc = (d + kChunk - 1) / kChunk;
     if (t_left > 96 && n_kc >= 10) return 128; // in place of four launches
     if (t_left > 64 && n_kc >= 17) return 128; // in place of three
@@ -811,10 +941,7 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
     f16x8 *Fimg = reinterpret_cast<f16x8 *>(static_cast<char *>(pack_buf) + kHeadBytes);
     const int64_t f_rows_max = f_slab < nFp ? f_slab : nFp;
     f16x8 *Simg = Fimg + (size_t)f_rows_max * pp / sizeof(f16x8);
-    // Matrix-core reduction when it pays: from kMvMinT columns on, unless the cross term is so long
-    // (large d) that the vector-ALU reduction hides behind it anyway.  Above 16 columns it is the
-    // only path.
-    const bool mv = a.t > 16 || (a.t >= kMvMinT && 4 * (3 + a.t) >= 3 * n_kc + 1);
+    const bool mv = reduce_on_matrix_cores(a.d, a.t);
     if (mv) {
         // largest magnitude of every vector column: the power-of-two scale into the fp16 range
         // cleared by a kernel, not a memset node: the product entry points may be captured into a graph
@@ -825,6 +952,18 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
         if (blocks > 4096) blocks = 4096;
         hipLaunchKernelGGL(col_absmax_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a.vec, a.ldv, a.wgt, a.nS,
                            a.t, colmax);
+        if (a.vimg != nullptr) {
+            // the vectors of the whole stream, converted once (the scales are on the device by now: same stream)
+            const dim3 vgrid((unsigned)(nSp / kStream));
+            f16x8 *const vimg = static_cast<f16x8 *>(a.vimg);
+            switch (column_groups(a.t)) {
+            case 1: hipLaunchKernelGGL(pack_vectors_kernel<1>, vgrid, dim3(kThreads), 0, stream, a.vec, a.ldv, a.wgt, a.nS, a.t, colmax, vimg); break;
+            case 2: hipLaunchKernelGGL(pack_vectors_kernel<2>, vgrid, dim3(kThreads), 0, stream, a.vec, a.ldv, a.wgt, a.nS, a.t, colmax, vimg); break;
+            default: hipLaunchKernelGGL(pack_vectors_kernel<4>, vgrid, dim3(kThreads), 0, stream, a.vec, a.ldv, a.wgt, a.nS, a.t, colmax, vimg); break;
+            }
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
 
     for (int64_t f0 = 0; f0 < nFp; f0 += f_slab) {
@@ -838,7 +977,11 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
                 if (e != hipSuccess) return e;
             }
             const int64_t fb = f_rows / kFixed;
-            if (mv) {
+            if (mv && a.vimg != nullptr) {
+                if (a.t <= 32) launch_tp<2, true, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                else if (a.t <= 64) launch_tp<4, true, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                else launch_tp<8, true, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+            } else if (mv) {
                 if (a.t <= 32) launch_tp<2, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
                 else if (a.t <= 64) launch_tp<4, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
                 else launch_tp<8, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);

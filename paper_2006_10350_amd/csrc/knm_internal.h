@@ -46,6 +46,10 @@ struct SweepArgs {
     unsigned int *range_count;
     float sigma;      // length scale the engines work with (for the Laplacian kernel the caller's, rescaled)
     int kind;         // knm_kernel_kind (the kernels of r = |x - c|: K-loop engines only)
+    // K-loop split-fp16 engine, reduction on the matrix cores: room of gemm_f16_vector_image_bytes() for the
+    // vectors converted once per sweep into the layout of the LDS stage; null = every workgroup converts
+    // the rows of its tiles itself
+    void *vimg = nullptr;
 };
 
 // ---- kernels of r = |x - c| (Laplacian, Matern) on the K-loop engines ---------------------
@@ -110,7 +114,9 @@ hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream);
 // operands are packed into the workspace, whole or slab by slab
 size_t gemm_f16_pack_bytes_per_point(int d);
 int gemm_f16_max_t(); // columns per launch at most
-int gemm_f16_group_t(int d, int t_left); // columns the next launch should take
+int gemm_f16_group_t(int d, int t_left, bool with_vector_image); // columns the next launch should take
+// bytes of the packed vector image of a launch with t columns over nS_padded stream points (0: no such image)
+size_t gemm_f16_vector_image_bytes(int d, int t, int64_t nS_padded);
 size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len, int d);
 hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream);
 // out[j * ldo] = sum over chunks of part[chunk * chunk_stride + j * ldp], summed in fp64 in a fixed
@@ -168,6 +174,8 @@ struct knm_ctx {
     size_t mu_bytes = 0;
     float *pack_buf = nullptr; // packed operand images of the split-fp16 engines
     size_t pack_bytes = 0;
+    float *vimg_buf = nullptr; // packed vector image of the K-loop split-fp16 engine's matrix-core reduction
+    size_t vimg_bytes = 0;
     size_t pack_limit = 0;     // cap on the image workspace chosen by the caller; 0 = engine defaults
     unsigned int *range_count = nullptr; // device word: operands the split-fp16 engines had to clamp (see SweepArgs)
     // this device's copy of the library's static scratch array (address looked up at knm_create), and

@@ -17,7 +17,9 @@ def rel_l2(got, ref):
     return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-@pytest.mark.parametrize("d,t", [(8, 1), (28, 1), (50, 3)])  # both register-resident layouts and the K-loop engine
+# both register-resident layouts and the K-loop engine; with 20, 40 and 70 columns its reduction on the matrix
+# cores, where the allocating call hands the vectors over as a packed image and takes more columns per launch
+@pytest.mark.parametrize("d,t", [(8, 1), (28, 1), (50, 3), (50, 20), (28, 40), (300, 70)])
 def test_static_scratch_product_matches_the_allocating_one(knm, d, t):
     ctx = knm.default_context()
     assert knm.knm_static_scratch_bytes() == 64 << 20
