@@ -58,8 +58,9 @@ int knm_max_d(void);
 int knm_max_t(void);
 /* Upper bound on the device bytes of library-owned workspace that the product entry points hold
  * for this shape with the default settings (any arithmetic mode, either kernel function): W when the
- * caller passes none, the partial results of the stream chunks, and the converted operands of the
- * split-fp16 engines.  knm_workspace_held: what the context holds now. */
+ * caller passes none, the partial results of the stream chunks, and the converted operands (points, and
+ * for 8 or more columns the vectors) of the split-fp16 engines.  knm_workspace_held: what the context
+ * holds now. */
 size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t);
 size_t knm_workspace_held(const knm_ctx *ctx);
 

@@ -221,7 +221,7 @@ static size_t pack_bytes_wanted(int64_t nF, int d, int t, int kind, size_t limit
         // whole and the other in slabs
         const size_t per_point = gemm_f16_pack_bytes_per_point(d);
         const int64_t nFp = (nF + gemm_fixed_per_block() - 1) / gemm_fixed_per_block() * gemm_fixed_per_block();
-        size_t want = 256 + per_point * (size_t)(nFp + chunks * chunk_len); // head + both images
+        size_t want = gemm_f16_head_bytes() + per_point * (size_t)(nFp + chunks * chunk_len); // head + both images
         const size_t cap = limit ? limit : (size_t)8 << 30;
         const size_t least = gemm_f16_min_pack_bytes(nF, chunks * chunk_len, chunk_len, d);
         if (want > cap) want = cap;
@@ -489,7 +489,7 @@ size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
     const size_t bytes = sizeof(float) * (size_t)n * t; // W
     // the largest needs over the arithmetic modes and kernel functions (they may cut the stream
     // differently): chunk partials, and the packed operands of the split-fp16 modes
-    size_t part = 0, pack = 0;
+    size_t part = 0, pack = 0, vimg = 0;
     for (int mode = 0; mode < 4; ++mode) {
         const int cross = mode & 1, kind = mode >> 1;
         const int64_t c1 = choose_chunks(n, M, d, t, cross, kind, &len);
@@ -506,14 +506,21 @@ size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
             const size_t k2 = packs ? pack_bytes_wanted(M, d, t, kind, 0, c2, l2) : 0;
             if (k1 > pack) pack = k1;
             if (k2 > pack) pack = k2;
+            if (use_gemm_engine(d, t, cross, kind)) {
+                // packed vector image of the widest launch (matrix-core reduction), for either sweep
+                const int wide = t < gemm_f16_max_t() ? t : gemm_f16_max_t();
+                const size_t v1 = gemm_f16_vector_image_bytes(d, wide, c1 * l1), v2 = gemm_f16_vector_image_bytes(d, wide, c2 * l2);
+                if (v1 <= kVectorImageCap && v1 > vimg) vimg = v1;
+                if (v2 <= kVectorImageCap && v2 > vimg) vimg = v2;
+            }
         }
     }
-    return bytes + part + pack + sizeof(float) * ((size_t)d + 1);
+    return bytes + part + pack + vimg + sizeof(float) * ((size_t)d + 1);
 }
 
 size_t knm_workspace_held(const knm_ctx *ctx)
 {
-    return ctx ? ctx->w_bytes + ctx->part_bytes + ctx->pack_bytes + ctx->mu_bytes : 0;
+    return ctx ? ctx->w_bytes + ctx->part_bytes + ctx->pack_bytes + ctx->vimg_bytes + ctx->mu_bytes : 0;
 }
 
 static int check_common(knm_ctx *ctx, const void *X, int64_t n, int d, int64_t ldx, const void *C, int64_t M,

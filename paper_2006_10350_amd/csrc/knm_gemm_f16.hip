@@ -870,6 +870,9 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
 
 } // namespace
 
+// bytes at the head of the workspace, before the images
+size_t gemm_f16_head_bytes() { return kHeadBytes; }
+
 // bytes of packed image per point
 size_t gemm_f16_pack_bytes_per_point(int d) { return (size_t)((d + kChunk - 1) / kChunk + 1) * 64; }
 

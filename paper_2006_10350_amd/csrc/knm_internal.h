@@ -113,6 +113,7 @@ hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream);
 // the same shapes with the cross term as three f16 MFMA products (knm_gemm_f16.hip); both
 // operands are packed into the workspace, whole or slab by slab
 size_t gemm_f16_pack_bytes_per_point(int d);
+size_t gemm_f16_head_bytes(); // bytes of the workspace in front of the images
 int gemm_f16_max_t(); // columns per launch at most
 int gemm_f16_group_t(int d, int t_left, bool with_vector_image); // columns the next launch should take
 // bytes of the packed vector image of a launch with t columns over nS_padded stream points (0: no such image)

@@ -364,7 +364,7 @@ def test_product_replays_in_a_graph(knm, n, M, d, t, sigma):
     ctx.close()
 
 
-@pytest.mark.parametrize("n,M,d,t", [(30000, 2000, 8, 1), (9000, 1500, 100, 3), (5000, 700, 28, 12)])
+@pytest.mark.parametrize("n,M,d,t", [(30000, 2000, 8, 1), (9000, 1500, 100, 3), (5000, 700, 28, 12), (4000, 900, 60, 70)])
 def test_workspace_held_stays_within_the_announced_bound(knm, n, M, d, t):
     """knm_workspace_bytes is an upper bound on what a context holds after the products of that
     shape, in every arithmetic mode and for both kernel functions."""
