@@ -138,7 +138,7 @@ def test_columns_of_very_different_scale(knm):
             assert rel_l2(U[:, c], Uo[:, c]) < TOL, c
 
 
-@pytest.mark.parametrize("t", [2, 9])
+@pytest.mark.parametrize("t", [2, 9, 70])  # vector-ALU reduction, matrix-core reduction, and its wide launch
 def test_weighted_product(knm, cross, t):
     n, M, d, sigma = 2500, 300, 9, 2.0
     X, C, V = _rand(n, d, 7), _rand(M, d, 8), _rand(M, t, 9)
