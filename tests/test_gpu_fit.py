@@ -157,6 +157,24 @@ def test_multi_output_fit(knm):
         assert rel_l2(pred[:, c], po[:, c]) < 1e-3
 
 
+def test_many_class_fit(knm):
+    """40 one-hot target columns (more than one launch of 32 would take): the products of the solver run
+    the matrix-core reduction in its wide form, with fp64 partials."""
+    n, M, d, t, sigma, lam, iters, jitter = 3000, 300, 20, 40, 4.0, 1e-6, 6, 1e-9
+    X = _rand(n, d, 137)
+    C = X[torch.randperm(n, generator=torch.Generator().manual_seed(138))[:M]].clone()
+    protos = _rand(t, d, 139)
+    labels = torch.cdist(X, protos).argmin(dim=1)
+    Y = torch.zeros(n, t)
+    Y[torch.arange(n), labels] = 1.0
+    alpha = knm.falkon_fit(X.cuda(), Y.cuda(), C.cuda(), sigma, lam, iters, jitter)
+    ao = oracle.falkon_fit(X.numpy(), Y.numpy(), C.numpy(), sigma, lam, iters, jitter)
+    Xt = _rand(400, d, 140)
+    pred = knm.falkon_predict(Xt.cuda(), C.cuda(), sigma, alpha).cpu().numpy()
+    po = oracle.falkon_predict(Xt.numpy(), C.numpy(), sigma, ao)
+    assert rel_l2(pred, po) < 1e-3
+
+
 @pytest.mark.parametrize("name,n,M,iters,cross_term", [("mid", 60000, 1500, 8, "f16x3"), ("lowdim", 60000, 1500, 8, "f16x3"),
                                                        ("highdim", 8000, 600, 5, "f16x3"), ("highdim", 8000, 600, 5, "f32")])
 def test_workload_shaped_fit(knm, name, n, M, iters, cross_term):
