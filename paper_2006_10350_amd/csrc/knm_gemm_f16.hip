@@ -441,21 +441,28 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
             bh[fb] = ib[(wave * 2 + fb) * kUnits + lane];
             bl[fb] = ib[(wave * 2 + fb) * kUnits + 64 + lane];
         }
+        // the stream block's operands are read one block ahead of the MFMAs that use them
+        f16x8 ah[2], al[2];
+        ah[0] = ib[(kFixed / 32) * kUnits + lane];
+        al[0] = ib[(kFixed / 32) * kUnits + 64 + lane];
 #pragma unroll
         for (int sb = 0; sb < 4; ++sb) {
-            const f16x8 ah = ib[(kFixed / 32 + sb) * kUnits + lane];
-            const f16x8 al = ib[(kFixed / 32 + sb) * kUnits + 64 + lane];
-            if constexpr (decltype(first)::value) {
-                mfma_zero(acc[0][sb], ah, bh[0]);
-                mfma_zero(acc[1][sb], ah, bh[1]);
-            } else {
-                mfma_acc(acc[0][sb], ah, bh[0]);
-                mfma_acc(acc[1][sb], ah, bh[1]);
+            const int cur = sb & 1;
+            if (sb + 1 < 4) {
+                ah[cur ^ 1] = ib[(kFixed / 32 + sb + 1) * kUnits + lane];
+                al[cur ^ 1] = ib[(kFixed / 32 + sb + 1) * kUnits + 64 + lane];
             }
-            mfma_acc(acc[0][sb], al, bh[0]);
-            mfma_acc(acc[1][sb], al, bh[1]);
-            mfma_acc(acc[0][sb], ah, bl[0]);
-            mfma_acc(acc[1][sb], ah, bl[1]);
+            if constexpr (decltype(first)::value) {
+                mfma_zero(acc[0][sb], ah[cur], bh[0]);
+                mfma_zero(acc[1][sb], ah[cur], bh[1]);
+            } else {
+                mfma_acc(acc[0][sb], ah[cur], bh[0]);
+                mfma_acc(acc[1][sb], ah[cur], bh[1]);
+            }
+            mfma_acc(acc[0][sb], al[cur], bh[0]);
+            mfma_acc(acc[1][sb], al[cur], bh[1]);
+            mfma_acc(acc[0][sb], ah[cur], bl[0]);
+            mfma_acc(acc[1][sb], ah[cur], bl[1]);
         }
     };
 
