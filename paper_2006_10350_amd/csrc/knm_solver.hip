@@ -45,30 +45,74 @@ using namespace knm;
 // differences: k = exp(-|c_r - c_c|^2 scale) with scale = 1 / (2 sigma^2) for the Gaussian kernel; for the
 // kernels of r = |c_r - c_c|, with u = r scale: exp(-u), scale = 1 / sigma (Laplacian);
 // (1 + u) exp(-u), scale = sqrt(3) / sigma; (1 + u + u^2 / 3) exp(-u), scale = sqrt(5) / sigma (Matern).  The factorisation reads nothing below the diagonal.
-__global__ void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_t ldc, int kind, double scale,
-                           double jitter, double *__restrict__ K, int64_t ldk)
+// One workgroup of 16 x 16 threads per 64 x 64 tile on or above the diagonal; thread (tx, ty) owns the entries
+// (r0 + tx + 16 i, c0 + ty + 16 j), i, j < 4.  The rows of both sides are staged through LDS 16 features at a
+// time as doubles, feature-major, so that the 16 threads of a row of the block read consecutive words; every
+// squared distance is summed over the features in their order.
+constexpr int kKmmTile = 64;
+constexpr int kKmmChunk = 16;
+__global__ __launch_bounds__(256) void kmm_kernel(const float *__restrict__ C, int64_t M, int d, int64_t ldc, int kind,
+                                                  double scale, double jitter, double *__restrict__ K, int64_t ldk)
 {
-    if ((int64_t)blockIdx.x * blockDim.x > (int64_t)blockIdx.y * blockDim.y + (blockDim.y - 1)) return; // below
-    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t c = (int64_t)blockIdx.y * blockDim.y + threadIdx.y;
-    if (r > c || c >= M) return;
-    const float *cr = C + r * ldc;
-    const float *cc = C + c * ldc;
-    double s = 0.0;
-    for (int k = 0; k < d; ++k) {
-        double diff = (double)cr[k] - (double)cc[k];
-        s += diff * diff;
+    if (blockIdx.x > blockIdx.y) return; // tile below the diagonal
+    __shared__ double rows_r[kKmmChunk][kKmmTile];
+    __shared__ double rows_c[kKmmChunk][kKmmTile];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int64_t r0 = (int64_t)blockIdx.x * kKmmTile, c0 = (int64_t)blockIdx.y * kKmmTile;
+    // staging role: row tid / 4 of the tile, features 4 (tid % 4) .. + 3 of the chunk
+    const int srow = tid >> 2, sf = (tid & 3) * 4;
+    const bool in_r = r0 + srow < M, in_c = c0 + srow < M;
+    const float *pr = C + (in_r ? r0 + srow : 0) * ldc;
+    const float *pc = C + (in_c ? c0 + srow : 0) * ldc;
+    double s[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s[i][j] = 0.0;
+    for (int k0 = 0; k0 < d; k0 += kKmmChunk) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int k = k0 + sf + e;
+            const bool kin = k < d;
+            rows_r[sf + e][srow] = (in_r && kin) ? (double)pr[kin ? k : 0] : 0.0;
+            rows_c[sf + e][srow] = (in_c && kin) ? (double)pc[kin ? k : 0] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kKmmChunk; ++k) {
+            double a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = rows_r[k][tx + 16 * i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = rows_c[k][ty + 16 * j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double diff = a[i] - b[j];
+                    s[i][j] += diff * diff;
+                }
+        }
+        __syncthreads();
     }
-    double v;
-    if (kind == KNM_KERNEL_GAUSSIAN) {
-        v = exp(-s * scale);
-    } else {
-        const double u = sqrt(s) * scale;
-        const double poly = kind == KNM_KERNEL_MATERN32 ? 1.0 + u : kind == KNM_KERNEL_MATERN52 ? 1.0 + u + u * u / 3.0 : 1.0;
-        v = poly * exp(-u);
-    }
-    if (r == c) v += jitter;
-    K[r + c * ldk] = v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t r = r0 + tx + 16 * i, c = c0 + ty + 16 * j;
+            if (r > c || c >= M) continue;
+            double v;
+            if (kind == KNM_KERNEL_GAUSSIAN) {
+                v = exp(-s[i][j] * scale);
+            } else {
+                const double u = sqrt(s[i][j]) * scale;
+                const double poly = kind == KNM_KERNEL_MATERN32 ? 1.0 + u : kind == KNM_KERNEL_MATERN52 ? 1.0 + u + u * u / 3.0 : 1.0;
+                v = poly * exp(-u);
+            }
+            if (r == c) v += jitter;
+            K[r + c * ldk] = v;
+        }
 }
 
 // first (1-based) index whose diagonal entry is not a positive finite number, else unchanged;
@@ -1107,8 +1151,8 @@ static int precond_build_impl(knm_ctx *ctx, const float *C, int64_t M, int d, in
     if (!C || M <= 0 || d <= 0 || ldc < d || !(sigma > 0.0f))
         return fail(ctx, KNM_INVALID_ARG, "bad preconditioner argument");
     auto fill = [=](double *K, int64_t ldk) {
-        const dim3 tb(32, 8);
-        const dim3 tg((unsigned)((M + 31) / 32), (unsigned)((M + 7) / 8));
+        const dim3 tb(256);
+        const dim3 tg((unsigned)((M + kKmmTile - 1) / kKmmTile), (unsigned)((M + kKmmTile - 1) / kKmmTile));
         const int kind = ctx->kernel_kind;
         const double scale = kind == KNM_KERNEL_GAUSSIAN   ? 1.0 / (2.0 * (double)sigma * (double)sigma)
                              : kind == KNM_KERNEL_MATERN32 ? sqrt(3.0) / (double)sigma
