@@ -16,6 +16,7 @@
 #include <cmath>
 #include <functional>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "knm_internal.h"
@@ -30,7 +31,7 @@ struct knm_precond {
     double *A = nullptr;   // = buf + 2: lower storage (what is in memory is A^T, a lower triangle)
     // inverses of the sb x sb diagonal blocks of T and A (column-major blocks, each mirrored onto
     // its lower triangle, the last one padded with the identity), used by the blocked
-    // triangular solves; xw (M entries) stages the solved blocks
+    // triangular solves; xw (M x kSolveCols entries) stages the solved blocks
     int sb = 0;
     double *Tdinv = nullptr;
     double *Adinv = nullptr;
@@ -202,11 +203,20 @@ __device__ __forceinline__ double wave_sum(double s)
     return s;
 }
 
+constexpr int kSolveCols = 8; // right-hand sides a blocked triangular solve takes through the factor together
+
+// The three kernels of the blocked triangular solves work on TC right-hand sides at once (columns of
+// a column-major M x t array, ldb apart; the staged solved blocks ldx apart), tc <= TC of them live: a
+// column past tc reads the last live one and is dropped.  Every entry of the factor and of the block
+// inverses is then read once per TC columns instead of once per column.
+
 // x = inv(R_kk) b (lower = 1: x[c] = sum_{i >= c} S[i, c] b[i]) or x = inv(R_kk)^T b (lower = 0:
 // x[c] = sum_{i <= c} S[i, c] b[i]) for one mirrored block S of live order nbk; one wavefront
 // per entry of x, lanes along the column of S.
+template <int TC>
 __global__ __launch_bounds__(256) void diag_apply_kernel(const double *__restrict__ S, int sb, int nbk, int lower,
-                                                        const double *__restrict__ b, double *__restrict__ x)
+                                                        const double *__restrict__ b, int64_t ldb, int tc,
+                                                        double *__restrict__ x, int64_t ldx)
 {
     const int lane = threadIdx.x & 63;
     const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -214,15 +224,31 @@ __global__ __launch_bounds__(256) void diag_apply_kernel(const double *__restric
     const double *col = S + (int64_t)c * sb;
     const int lo = lower ? c : 0;
     const int hi = lower ? nbk : c + 1;
-    double s0 = 0.0, s1 = 0.0;
+    const double *bq[TC];
+#pragma unroll
+    for (int q = 0; q < TC; ++q) bq[q] = b + (int64_t)(q < tc ? q : tc - 1) * ldb;
+    double s0[TC], s1[TC];
+#pragma unroll
+    for (int q = 0; q < TC; ++q) s0[q] = s1[q] = 0.0;
     int i = lo + lane;
     for (; i + 64 < hi; i += 128) {
-        s0 += col[i] * b[i];
-        s1 += col[i + 64] * b[i + 64];
+        const double a0 = col[i], a1 = col[i + 64];
+#pragma unroll
+        for (int q = 0; q < TC; ++q) {
+            s0[q] += a0 * bq[q][i];
+            s1[q] += a1 * bq[q][i + 64];
+        }
     }
-    if (i < hi) s0 += col[i] * b[i];
-    const double s = wave_sum(s0 + s1);
-    if (lane == 0) x[c] = s;
+    if (i < hi) {
+        const double a0 = col[i];
+#pragma unroll
+        for (int q = 0; q < TC; ++q) s0[q] += a0 * bq[q][i];
+    }
+#pragma unroll
+    for (int q = 0; q < TC; ++q) {
+        const double s = wave_sum(s0[q] + s1[q]);
+        if (lane == 0 && q < tc) x[(int64_t)q * ldx + c] = s;
+    }
 }
 
 constexpr int kPanelWaves = 8;  // wavefronts of a panel_update_n workgroup, sharing the columns
@@ -233,50 +259,59 @@ constexpr int kPanelCols = 4;   // columns of one panel_update_t wavefront
 // rows above the block of an upper-storage factor in its plain solve, the rows below the block of a
 // lower-storage factor in its transposed solve.  Workgroups past the row range copy x into
 // b[k0 : k0 + nbk].
+template <int TC>
 __global__ __launch_bounds__(kPanelWaves * 64) void panel_update_n_kernel(const double *__restrict__ R, int64_t M,
                                                                          int64_t k0, int nbk, int64_t r_lo,
                                                                          int64_t r_hi, const double *__restrict__ x,
-                                                                         double *__restrict__ b)
+                                                                         int64_t ldx, double *__restrict__ b, int64_t ldb,
+                                                                         int tc)
 {
-    __shared__ double part[kPanelWaves][kPanelRows];
+    __shared__ double part[kPanelWaves][TC][kPanelRows];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t row_groups = (r_hi - r_lo + kPanelRows - 1) / kPanelRows;
     if ((int64_t)blockIdx.x >= row_groups) {
         const int64_t i = ((int64_t)blockIdx.x - row_groups) * blockDim.x + threadIdx.x;
-        if (i < nbk) b[k0 + i] = x[i];
+        if (i < nbk)
+            for (int q = 0; q < tc; ++q) b[(int64_t)q * ldb + k0 + i] = x[(int64_t)q * ldx + i];
         return;
     }
     const int64_t r = r_lo + (int64_t)blockIdx.x * kPanelRows + lane;
     const bool live = r < r_hi;
     const double *p = R + (live ? r : r_lo) + k0 * M;
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    const double *xq[TC];
+#pragma unroll
+    for (int q = 0; q < TC; ++q) xq[q] = x + (int64_t)(q < tc ? q : tc - 1) * ldx;
+    double s0[TC], s1[TC];
+#pragma unroll
+    for (int q = 0; q < TC; ++q) s0[q] = s1[q] = 0.0;
     int j = w;
     for (; j + 7 * kPanelWaves < nbk; j += 8 * kPanelWaves) {
-        const double a0 = p[(int64_t)(j + 0 * kPanelWaves) * M];
-        const double a1 = p[(int64_t)(j + 1 * kPanelWaves) * M];
-        const double a2 = p[(int64_t)(j + 2 * kPanelWaves) * M];
-        const double a3 = p[(int64_t)(j + 3 * kPanelWaves) * M];
-        const double a4 = p[(int64_t)(j + 4 * kPanelWaves) * M];
-        const double a5 = p[(int64_t)(j + 5 * kPanelWaves) * M];
-        const double a6 = p[(int64_t)(j + 6 * kPanelWaves) * M];
-        const double a7 = p[(int64_t)(j + 7 * kPanelWaves) * M];
-        s0 += a0 * x[j + 0 * kPanelWaves];
-        s1 += a1 * x[j + 1 * kPanelWaves];
-        s2 += a2 * x[j + 2 * kPanelWaves];
-        s3 += a3 * x[j + 3 * kPanelWaves];
-        s0 += a4 * x[j + 4 * kPanelWaves];
-        s1 += a5 * x[j + 5 * kPanelWaves];
-        s2 += a6 * x[j + 6 * kPanelWaves];
-        s3 += a7 * x[j + 7 * kPanelWaves];
+        double a[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = p[(int64_t)(j + u * kPanelWaves) * M];
+#pragma unroll
+        for (int q = 0; q < TC; ++q) {
+#pragma unroll
+            for (int u = 0; u < 8; u += 2) {
+                s0[q] += a[u] * xq[q][j + u * kPanelWaves];
+                s1[q] += a[u + 1] * xq[q][j + (u + 1) * kPanelWaves];
+            }
+        }
     }
-    for (; j < nbk; j += kPanelWaves) s0 += p[(int64_t)j * M] * x[j];
-    part[w][lane] = (s0 + s1) + (s2 + s3);
+    for (; j < nbk; j += kPanelWaves) {
+        const double a0 = p[(int64_t)j * M];
+#pragma unroll
+        for (int q = 0; q < TC; ++q) s0[q] += a0 * xq[q][j];
+    }
+#pragma unroll
+    for (int q = 0; q < TC; ++q) part[w][q][lane] = s0[q] + s1[q];
     __syncthreads();
-    if (w == 0 && live) {
+    // wavefront q adds up right-hand side q (TC <= kPanelWaves)
+    if (w < TC && w < tc && live) {
         double s = 0.0;
-        for (int q = 0; q < kPanelWaves; ++q) s += part[q][lane];
-        b[r] -= s;
+        for (int u = 0; u < kPanelWaves; ++u) s += part[u][w][lane];
+        b[(int64_t)w * ldb + r] -= s;
     }
 }
 
@@ -284,31 +319,37 @@ __global__ __launch_bounds__(kPanelWaves * 64) void panel_update_n_kernel(const 
 // columns right of the block of an upper-storage factor in its transposed solve, the columns left of
 // the block of a lower-storage factor in its plain solve.  One wavefront per kPanelCols columns, lanes
 // along the rows.  Workgroups past the column range copy x into b[k0 : k0 + nbk].
+template <int TC>
 __global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__restrict__ R, int64_t M, int64_t k0,
                                                             int nbk, int64_t j0, int64_t j1,
-                                                            const double *__restrict__ x, double *__restrict__ b)
+                                                            const double *__restrict__ x, int64_t ldx,
+                                                            double *__restrict__ b, int64_t ldb, int tc)
 {
     const int lane = threadIdx.x & 63;
     const int64_t col_groups = (j1 - j0 + 4 * kPanelCols - 1) / (4 * kPanelCols);
     if ((int64_t)blockIdx.x >= col_groups) {
         const int64_t i = ((int64_t)blockIdx.x - col_groups) * blockDim.x + threadIdx.x;
-        if (i < nbk) b[k0 + i] = x[i];
+        if (i < nbk)
+            for (int q = 0; q < tc; ++q) b[(int64_t)q * ldb + k0 + i] = x[(int64_t)q * ldx + i];
         return;
     }
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t jb = j0 + wave * kPanelCols;
     if (jb >= j1) return;
     const double *p[kPanelCols];
-    double s[kPanelCols];
+    double s[kPanelCols][TC];
 #pragma unroll
     for (int c = 0; c < kPanelCols; ++c) {
         const int64_t j = (jb + c < j1) ? jb + c : j1 - 1; // a clamped column is computed and dropped
         p[c] = R + k0 + j * M;
-        s[c] = 0.0;
+#pragma unroll
+        for (int q = 0; q < TC; ++q) s[c][q] = 0.0;
     }
+    const double *xq[TC];
+#pragma unroll
+    for (int q = 0; q < TC; ++q) xq[q] = x + (int64_t)(q < tc ? q : tc - 1) * ldx;
     int i = lane;
     for (; i + 64 < nbk; i += 128) {
-        const double x0 = x[i], x1 = x[i + 64];
         double a[kPanelCols], c2[kPanelCols];
 #pragma unroll
         for (int c = 0; c < kPanelCols; ++c) {
@@ -316,18 +357,27 @@ __global__ __launch_bounds__(256) void panel_update_t_kernel(const double *__res
             c2[c] = p[c][i + 64];
         }
 #pragma unroll
-        for (int c = 0; c < kPanelCols; ++c) s[c] += a[c] * x0 + c2[c] * x1;
+        for (int q = 0; q < TC; ++q) {
+            const double x0 = xq[q][i], x1 = xq[q][i + 64];
+#pragma unroll
+            for (int c = 0; c < kPanelCols; ++c) s[c][q] += a[c] * x0 + c2[c] * x1;
+        }
     }
     if (i < nbk) {
-        const double x0 = x[i];
 #pragma unroll
-        for (int c = 0; c < kPanelCols; ++c) s[c] += p[c][i] * x0;
+        for (int q = 0; q < TC; ++q) {
+            const double x0 = xq[q][i];
+#pragma unroll
+            for (int c = 0; c < kPanelCols; ++c) s[c][q] += p[c][i] * x0;
+        }
     }
 #pragma unroll
-    for (int c = 0; c < kPanelCols; ++c) {
-        const double tot = wave_sum(s[c]);
-        if (lane == 0 && jb + c < j1) b[jb + c] -= tot;
-    }
+    for (int c = 0; c < kPanelCols; ++c)
+#pragma unroll
+        for (int q = 0; q < TC; ++q) {
+            const double tot = wave_sum(s[c][q]);
+            if (lane == 0 && jb + c < j1 && q < tc) b[(int64_t)q * ldb + jb + c] -= tot;
+        }
 }
 
 // ---- leaf of the blocked factorisation --------------------------------------------------------
@@ -620,29 +670,37 @@ int tri_solve(knm_ctx *ctx, const knm_precond *p, const double *R, const double 
     const bool lower = (R == p->A);
     const int sb = p->sb;
     const int64_t nblk = (M + sb - 1) / sb;
-    for (int c = 0; c < t; ++c) {
-        double *b = B + (int64_t)c * M;
+    // right-hand sides in groups of up to kSolveCols: a group streams the factor once
+    auto run = [&](auto width, int c0, int tc) {
+        constexpr int TC = decltype(width)::value;
+        double *b = B + (int64_t)c0 * M;
         for (int64_t step = 0; step < nblk; ++step) {
             const int64_t k = trans ? step : nblk - 1 - step; // R^T is lower: forward; R: backward
             const int64_t k0 = k * sb;
             const int nbk = (int)((M - k0 < sb) ? M - k0 : sb);
             double *x = p->xw + k0;
-            hipLaunchKernelGGL(diag_apply_kernel, dim3((unsigned)((nbk + 3) / 4)), dim3(256), 0, ctx->stream,
-                               S + k * sb * sb, sb, nbk, trans ? 0 : 1, b + k0, x);
+            hipLaunchKernelGGL(diag_apply_kernel<TC>, dim3((unsigned)((nbk + 3) / 4)), dim3(256), 0, ctx->stream,
+                               S + k * sb * sb, sb, nbk, trans ? 0 : 1, b + k0, M, tc, x, M);
             // the entries of b still to be solved: before the block (plain) or after it (transposed)
             const int64_t lo = trans ? k0 + nbk : 0, hi = trans ? M : k0;
             if (trans == lower) { // panel entries R(r, k0 + j) or R(k0 + j, r) contiguous in r
                 const int64_t groups = (hi - lo + kPanelRows - 1) / kPanelRows;
                 const int64_t copy = (nbk + kPanelWaves * 64 - 1) / (kPanelWaves * 64);
-                hipLaunchKernelGGL(panel_update_n_kernel, dim3((unsigned)(groups + copy)), dim3(kPanelWaves * 64), 0,
-                                   ctx->stream, R, ld, k0, nbk, lo, hi, x, b);
+                hipLaunchKernelGGL(panel_update_n_kernel<TC>, dim3((unsigned)(groups + copy)), dim3(kPanelWaves * 64), 0,
+                                   ctx->stream, R, ld, k0, nbk, lo, hi, x, M, b, M, tc);
             } else {              // contiguous in the block's own index
                 const int64_t groups = (hi - lo + 4 * kPanelCols - 1) / (4 * kPanelCols);
                 const int64_t copy = (nbk + 255) / 256;
-                hipLaunchKernelGGL(panel_update_t_kernel, dim3((unsigned)(groups + copy)), dim3(256), 0, ctx->stream,
-                                   R, ld, k0, nbk, lo, hi, x, b);
+                hipLaunchKernelGGL(panel_update_t_kernel<TC>, dim3((unsigned)(groups + copy)), dim3(256), 0, ctx->stream,
+                                   R, ld, k0, nbk, lo, hi, x, M, b, M, tc);
             }
         }
+    };
+    for (int c = 0; c < t; c += kSolveCols) {
+        const int tc = (t - c < kSolveCols) ? t - c : kSolveCols;
+        if (tc == 1) run(std::integral_constant<int, 1>{}, c, tc);
+        else if (tc <= 4) run(std::integral_constant<int, 4>{}, c, tc);
+        else run(std::integral_constant<int, kSolveCols>{}, c, tc);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "blocked triangular solve", e);
@@ -1074,7 +1132,7 @@ static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(d
     const size_t dbytes = sizeof(double) * (size_t)nblk * p->sb * p->sb;
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Tdinv), dbytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Adinv), dbytes);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->xw), sizeof(double) * (size_t)M);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->xw), sizeof(double) * (size_t)M * kSolveCols);
     DevBuf leaf;
     if (e != hipSuccess || leaf.alloc(ctx, sizeof(double) * kLeaf * kLeaf)) {
         (void)hipGetLastError();
