@@ -246,7 +246,7 @@ def product_leg(knm, synth, torch, ctx, w, steps: int, warmup: int, cross: str, 
     s_per_product = elapsed / steps
     entries = float(w.n) * float(w.M)
     kernel_name, k_loop, f16 = engine_of(w, cross, kernel)
-    group = 32 if (k_loop and f16) else 16  # columns per launch of the K-loop engines
+    group = 128 if (k_loop and f16) else 16  # columns per launch of the K-loop engines (split-fp16: with its packed vector image)
     launches = 2 * ((w.t + group - 1) // group if k_loop else 1) * steps
     avg_launch_ms = (sum(row_ms) + sum(col_ms)) / launches
     # Algorithmic contraction work of one launch (one sweep): every kernel entry once, 2 d flop each.
@@ -313,7 +313,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="mid", help="tiny | mid | lowdim | highdim | billion")
+    ap.add_argument("--workload", default="mid", help="tiny | mid | lowdim | highdim | billion | manyclass")
     ap.add_argument("--n", type=int, default=None, help="override the number of rows (same distribution)")
     ap.add_argument("--M", type=int, default=None, help="override the number of centres")
     ap.add_argument("--cpu-rows", type=int, default=None, help="rows of the oracle's timing sample")

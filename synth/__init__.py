@@ -1,11 +1,11 @@
-"""Seeded synthetic inputs with the shapes and value distributions of the five workloads.
+"""Seeded synthetic inputs with the shapes and value distributions of the workloads.
 
 This module only draws random numbers and labels; it holds none of the kernel method's
 arithmetic.  Both the CPU oracle's tests and the GPU library's tests/benchmark take
 their inputs from here, so both sides see identical fp32 bits.
 
 Each workload stands in for a public dataset the paper measures on (HIGGS-, AIRLINE-,
-image/multi-class- and TAXI-shaped problems); nothing of those datasets is reproduced,
+image/multi-class-, TAXI- and TIMIT-shaped problems); nothing of those datasets is reproduced,
 only (n, d, M, t), the value distributions and the hyper-parameters.
 """
 from __future__ import annotations
@@ -37,6 +37,9 @@ WORKLOADS = {
     "lowdim": Workload("lowdim", 5_900_000, 8, 100_000, 1, 1.0, 1e-8, 20, 3, "AIRLINE-shaped regression"),
     "highdim": Workload("highdim", 2_000_000, 784, 50_000, 10, 24.0, 1e-9, 20, 4, "image-like multi-class"),
     "billion": Workload("billion", 1_000_000_000, 9, 100_000, 1, 1.0, 1e-10, 10, 5, "TAXI-shaped regression"),
+    # not one of the five measured configurations: the paper's many-class shape and its settings (the
+    # hyper-parameter table of the experimental appendix), for products and solves with many right-hand sides
+    "manyclass": Workload("manyclass", 1_200_000, 440, 100_000, 144, 14.5, 5e-9, 5, 6, "TIMIT-shaped multi-class"),
 }
 
 
@@ -67,7 +70,7 @@ def _rows(w: Workload, n: int, g: torch.Generator, device, out: torch.Tensor) ->
         hi = min(n, lo + step)
         m = hi - lo
         dst = out[lo:hi]
-        if w.name in ("tiny", "mid"):
+        if w.name in ("tiny", "mid", "manyclass"):
             dst.copy_(torch.randn(m, d, generator=g, device=device, dtype=torch.float32))
         elif w.name == "lowdim":
             # 4 columns uniform integers in [0, 24], 4 columns lognormal(3, 1); standardised
@@ -124,7 +127,7 @@ def _targets(w: Workload, X: torch.Tensor, g: torch.Generator, device) -> torch.
             x = X[lo:hi]
             y[lo:hi] = 0.5 * torch.tanh(x @ a) + 0.5 * torch.randn(hi - lo, generator=g, device=device)
         return y.reshape(n, 1)
-    if w.name == "highdim":
+    if w.name in ("highdim", "manyclass"):
         protos = torch.empty(w.t, d, device=device, dtype=torch.float32)
         _rows(w, w.t, g, device, protos)
         Y = torch.zeros(n, w.t, device=device, dtype=torch.float32)
