@@ -36,6 +36,9 @@ struct knm_precond {
     double *Tdinv = nullptr;
     double *Adinv = nullptr;
     double *xw = nullptr;
+    // sb x sb doubles for the solves with many right-hand sides (one block inverse with its mirror image
+    // cleared); null for small M
+    double *blk = nullptr;
 };
 
 namespace {
@@ -659,6 +662,72 @@ struct DevBuf {
     template <class T> T *as() { return static_cast<T *>(p); }
 };
 
+// Many right-hand sides: the same blocked solve as products on the fp64 matrix cores.
+constexpr int kProductSolveMinCols = 16;    // from this many right-hand sides on
+constexpr int64_t kProductSolveMinM = 4096; // and this order of the factor
+
+// out <- the upper triangle (diagonal included) of one mirrored block inverse, zeros below it
+__global__ void upper_block_kernel(const double *__restrict__ S, int sb, double *__restrict__ out)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int c = blockIdx.y;
+    if (i < sb) out[i + (int64_t)c * sb] = (i <= c) ? S[i + (int64_t)c * sb] : 0.0;
+}
+
+// b[k0 + i + j ldb] = x[i + j ldx], i < nbk, j < tc
+__global__ void block_rows_kernel(const double *__restrict__ x, int64_t ldx, int nbk, int tc, double *__restrict__ b,
+                                  int64_t ldb)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int j = blockIdx.y;
+    if (i < nbk && j < tc) b[i + (int64_t)j * ldb] = x[i + (int64_t)j * ldx];
+}
+
+// The blocked solve of tri_solve with both of its steps as products: per block, X = inv(R_kk) B_k or
+// inv(R_kk)^T B_k (the block inverse with its mirror image cleared, so that a plain product applies the
+// triangular factor), then the rows still to be solved lose the panel times X.  The factor is read once
+// per group of columns (as many as the staging array holds: at least 128 from M = 4096 on), at the rate
+// of the matrix cores instead of once per 8 columns.
+int tri_solve_products(knm_ctx *ctx, const knm_precond *p, const double *R, const double *S, bool trans, double *B, int t)
+{
+    const int64_t M = p->M, ld = p->ld;
+    const bool lower = (R == p->A);
+    const int sb = p->sb;
+    const int64_t nblk = (M + sb - 1) / sb;
+    const int64_t cap = (M * kSolveCols) / sb; // columns the staging array holds at leading dimension sb
+    double *X = p->xw;
+    for (int c0 = 0; c0 < t;) {
+        const int tc = (int)((t - c0 < cap) ? t - c0 : cap);
+        double *Bc = B + (int64_t)c0 * M;
+        for (int64_t step = 0; step < nblk; ++step) {
+            const int64_t k = trans ? step : nblk - 1 - step; // R^T is lower: forward; R: backward
+            const int64_t k0 = k * sb;
+            const int nbk = (int)((M - k0 < sb) ? M - k0 : sb);
+            hipLaunchKernelGGL(upper_block_kernel, dim3((unsigned)((sb + 255) / 256), (unsigned)sb), dim3(256), 0, ctx->stream,
+                               S + k * sb * sb, sb, p->blk);
+            // x[c] = sum_i W[c, i] b[i] (plain) or sum_i W[i, c] b[i] (transposed), W = inv(R_kk) at blk[row + col sb]
+            hipError_t e = launch_gemm_f64(trans ? 0 : 1, nbk, tc, nbk, 1.0, p->blk, sb, Bc + k0, M, 0.0, X, sb, ctx->stream);
+            if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "triangular solve: block product", e);
+            hipLaunchKernelGGL(block_rows_kernel, dim3((unsigned)((nbk + 255) / 256), (unsigned)tc), dim3(256), 0, ctx->stream, X,
+                               (int64_t)sb, nbk, tc, Bc + k0, M);
+            // the rows of B still to be solved: before the block (plain) or after it (transposed)
+            const int64_t lo = trans ? k0 + nbk : 0, hi = trans ? M : k0;
+            if (hi > lo) {
+                // panel entry (row r of the rest, column kk of the block): R[r + (k0 + kk) ld] where the panels
+                // are contiguous in r, else R[(k0 + kk) + r ld]
+                e = (trans == lower)
+                        ? launch_gemm_f64(1, hi - lo, tc, nbk, -1.0, R + lo + k0 * ld, ld, X, sb, 1.0, Bc + lo, M, ctx->stream)
+                        : launch_gemm_f64(0, hi - lo, tc, nbk, -1.0, R + k0 + lo * ld, ld, X, sb, 1.0, Bc + lo, M, ctx->stream);
+                if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "triangular solve: panel product", e);
+            }
+        }
+        c0 += tc;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, KNM_HIP_ERROR, "blocked triangular solve", e);
+    return KNM_OK;
+}
+
 // B <- op(R)^-1 B for column-major B (M x t); S = mirrored inverses of the diagonal blocks of R
 // (R = p->T, upper storage, or p->A, lower storage).  p->xw stages each solved block; solves on one
 // context are stream-ordered.  Either storage streams its panels along contiguous columns of the
@@ -670,6 +739,7 @@ int tri_solve(knm_ctx *ctx, const knm_precond *p, const double *R, const double 
     const bool lower = (R == p->A);
     const int sb = p->sb;
     const int64_t nblk = (M + sb - 1) / sb;
+    if (t >= kProductSolveMinCols && p->blk != nullptr) return tri_solve_products(ctx, p, R, S, trans, B, t);
     // right-hand sides in groups of up to kSolveCols: a group streams the factor once
     auto run = [&](auto width, int c0, int tc) {
         constexpr int TC = decltype(width)::value;
@@ -895,6 +965,7 @@ int precond_free(knm_precond *p)
     if (p->Tdinv) (void)hipFree(p->Tdinv);
     if (p->Adinv) (void)hipFree(p->Adinv);
     if (p->xw) (void)hipFree(p->xw);
+    if (p->blk) (void)hipFree(p->blk);
     delete p;
     return KNM_OK;
 }
@@ -1133,6 +1204,8 @@ static int precond_build_from(knm_ctx *ctx, int64_t M, const std::function<int(d
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Tdinv), dbytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->Adinv), dbytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&p->xw), sizeof(double) * (size_t)M * kSolveCols);
+    if (e == hipSuccess && M >= kProductSolveMinM)
+        e = hipMalloc(reinterpret_cast<void **>(&p->blk), sizeof(double) * (size_t)p->sb * p->sb);
     DevBuf leaf;
     if (e != hipSuccess || leaf.alloc(ctx, sizeof(double) * kLeaf * kLeaf)) {
         (void)hipGetLastError();

@@ -84,7 +84,9 @@ def test_linop_matches_oracle(knm, t):
 
 
 @pytest.mark.parametrize("M", [300, 1100, 5000])  # 2 and 5 blocks of 256, 10 blocks of 512; ragged last blocks
-@pytest.mark.parametrize("t", [1, 2])
+# one column, a group of columns (up to 8 go through the factor together), two groups, and from 16 columns on
+# (M = 5000) the solves as products on the matrix cores
+@pytest.mark.parametrize("t", [1, 2, 11, 37])
 def test_preconditioner_solves_match_triangular_solves(knm, M, t):
     """The blocked solves against scipy's on the factors the library itself returns: fp64 both
     sides, so the bar is the conditioning of the factors times the unit roundoff."""
