@@ -246,7 +246,8 @@ def product_leg(knm, synth, torch, ctx, w, steps: int, warmup: int, cross: str, 
     s_per_product = elapsed / steps
     entries = float(w.n) * float(w.M)
     kernel_name, k_loop, f16 = engine_of(w, cross, kernel)
-    group = 128 if (k_loop and f16) else 16  # columns per launch of the K-loop engines (split-fp16: with its packed vector image)
+    # columns per launch of the K-loop engines (split-fp16: with its packed vector image)
+    group = (160 if kernel == "gaussian" else 128) if (k_loop and f16) else 16
     launches = 2 * ((w.t + group - 1) // group if k_loop else 1) * steps
     avg_launch_ms = (sum(row_ms) + sum(col_ms)) / launches
     # Algorithmic contraction work of one launch (one sweep): every kernel entry once, 2 d flop each.

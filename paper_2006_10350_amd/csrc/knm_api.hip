@@ -279,10 +279,10 @@ static int sweep(knm_ctx *ctx, const float *F, int64_t nF, int64_t ldf, const fl
         // call that must not allocate does without, as does one whose image would be very large)
         bool vector_image = gemm && ctx->cross_term == KNM_CROSS_F16X3 && !ctx->static_mode;
         if (vector_image) {
-            const int wide = gemm_f16_group_t(d, t - c, true);
+            const int wide = gemm_f16_group_t(d, t - c, ctx->kernel_kind, true);
             vector_image = gemm_f16_vector_image_bytes(d, t - c < wide ? t - c : wide, chunks * chunk_len) <= kVectorImageCap;
         }
-        group = !gemm ? 1 : (ctx->cross_term == KNM_CROSS_F16X3 ? gemm_f16_group_t(d, t - c, vector_image) : gemm_max_t());
+        group = !gemm ? 1 : (ctx->cross_term == KNM_CROSS_F16X3 ? gemm_f16_group_t(d, t - c, ctx->kernel_kind, vector_image) : gemm_max_t());
         SweepArgs a;
         a.F = F; a.nF = nF; a.ldf = ldf;
         a.S = S; a.nS = nS; a.lds = lds;
@@ -508,7 +508,7 @@ size_t knm_workspace_bytes(int64_t n, int64_t M, int d, int t)
             if (k2 > pack) pack = k2;
             if (use_gemm_engine(d, t, cross, kind)) {
                 // packed vector image of the widest launch (matrix-core reduction), for either sweep
-                const int wide = t < gemm_f16_max_t() ? t : gemm_f16_max_t();
+                const int wide = t < gemm_f16_max_t(kind) ? t : gemm_f16_max_t(kind);
                 const size_t v1 = gemm_f16_vector_image_bytes(d, wide, c1 * l1), v2 = gemm_f16_vector_image_bytes(d, wide, c2 * l2);
                 if (v1 <= kVectorImageCap && v1 > vimg) vimg = v1;
                 if (v2 <= kVectorImageCap && v2 > vimg) vimg = v2;

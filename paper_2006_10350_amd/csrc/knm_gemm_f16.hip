@@ -39,7 +39,7 @@
 // into the fp16 range, split likewise and staged in LDS in A-operand layout, and three
 // products P_hi V_hi + P_lo V_hi + P_hi V_lo accumulate a 32-column x 32-point output tile in
 // fp32.  That replaces t FMAs per kernel value by about three conversion instructions and
-// serves up to 128 columns per launch: up to four groups of 32, each with its own output tile,
+// serves up to 160 columns per launch: up to five groups of 32, each with its own output tile,
 // fed by the same split kernel values.
 
 #include <type_traits>
@@ -215,7 +215,7 @@ struct PatchMap {
 // Fimg: image of the fixed points [fixed_row0, fixed_row0 + 256 n_fblocks);
 // Simg: image of the stream chunks [chunk0, chunk0 + n_chunks).
 // TP: number of vector columns, padded to a multiple of 2 (vector-ALU reduction).  MV: reduce
-// on the matrix cores instead, TP / 2 groups of 32 columns each (1, 2 or 4: the kernel values of a
+// on the matrix cores instead, TP / 2 groups of 32 columns each (1, 2, 4 or 5: the kernel values of a
 // tile are evaluated and split once and multiplied into every group; more than one group needs the
 // registers and the LDS of a whole CU, so those instantiations run one workgroup per CU);
 // colmax[c] = bits of max |vec[:, c]|.
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
     // A-operand layout [stream block][K-step][plane hi/lo][lane]
     constexpr int kRing = ring_depth(MV, TP);
     constexpr int G = MV ? TP / 2 : 1; // column groups of the matrix-core reduction
-    static_assert(!MV || TP == 2 || TP == 4 || TP == 8, "1, 2 or 4 groups of 32 columns");
+    static_assert(!MV || TP == 2 || TP == 4 || TP == 8 || TP == 10, "1, 2, 4 or 5 groups of 32 columns");
     extern __shared__ __align__(16) unsigned char lds_dyn[];
     f16x8 *const img = reinterpret_cast<f16x8 *>(lds_dyn);
     f16x8 *const vstore = img + kRing * kStageUnits;
@@ -767,10 +767,10 @@ __global__ void clear_head_kernel(uint32_t *__restrict__ head) { head[threadIdx.
 __global__ void col_absmax_kernel(const float *__restrict__ vec, int64_t ldv, const float *__restrict__ wgt, int64_t n,
                                   int t, uint32_t *__restrict__ out)
 {
-    const int c = threadIdx.x & 127;
+    const int c = threadIdx.x; // one row per workgroup and pass, lanes along its columns (t <= 256)
     float m = 0.0f;
     if (c < t)
-        for (int64_t i = (int64_t)blockIdx.x * 2 + (threadIdx.x >> 7); i < n; i += (int64_t)gridDim.x * 2) {
+        for (int64_t i = blockIdx.x; i < n; i += gridDim.x) {
             float v = vec[i * ldv + c];
             if (wgt != nullptr) v *= wgt[i];
             m = fmaxf(m, fabsf(v));
@@ -840,7 +840,7 @@ constexpr int kPatch = 64;  // workgroups per patch = resident workgroups per XC
 constexpr int kPatchF = 8;  // fixed blocks per patch (measured: 2..8 within 4 % of each other, 64 is 25 % slower)
 
 constexpr int kMvMinT = 8;    // columns from which the reduction against the vectors may run on the matrix cores
-constexpr size_t kHeadBytes = 512; // head of the workspace: per-column magnitude words for that path (128 columns)
+constexpr size_t kHeadBytes = 1024; // head of the workspace: per-column magnitude words for that path (up to 256 columns)
 
 template <int TP, bool MV, bool VI = false>
 void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t fixed_row0, int64_t f_blocks,
@@ -860,12 +860,17 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
     constexpr int kVecUnits = MV ? (TP / 2) * 4 * 2 * 2 * 64 : (kStream * TP * 4 + 15) / 16;
     constexpr size_t lds_bytes = (size_t)(ring_depth(MV, TP) * kStageUnits + kVecUnits) * sizeof(f16x8);
     auto launch = [&](auto kind) {
+        // five column groups fill the register file only just for the Gaussian kernel; the kernels of r
+        // (which the dispatcher gives at most 128 columns at a time) have no such instantiation
+        if constexpr (MV && TP == 10 && decltype(kind)::value != KNM_KERNEL_GAUSSIAN) return;
+        else {
         auto *const kernel = gauss_gemm_f16_kernel<TP, MV, decltype(kind)::value, VI>;
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes) != hipSuccess)
             return;
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, stream, a, Fimg, Simg, fixed_row0, chunk0, n_kc, pm,
                            colmax);
+        }
     };
     switch (a.kind) {
     case KNM_KERNEL_LAPLACIAN: launch(std::integral_constant<int, KNM_KERNEL_LAPLACIAN>{}); break;
@@ -891,7 +896,7 @@ size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len,
     return kHeadBytes + (f <= s ? f + (size_t)chunk_len * pp : s + (size_t)kFixed * pp);
 }
 
-int gemm_f16_max_t() { return 128; }
+int gemm_f16_max_t(int kind) { return kind == KNM_KERNEL_GAUSSIAN ? 160 : 128; }
 
 // Matrix-core reduction when it pays: from kMvMinT columns on, unless the cross term is so long
 // (large d) that the vector-ALU reduction hides behind it anyway.  Above 16 columns it is the
@@ -901,11 +906,11 @@ static bool reduce_on_matrix_cores(int d, int t)
     const int n_kc = (d + kChunk - 1) / kChunk;
     return t > 16 || (t >= kMvMinT && 4 * (3 + t) >= 3 * n_kc + 1);
 }
-static int column_groups(int t) { return t <= 32 ? 1 : (t <= 64 ? 2 : 4); }
+static int column_groups(int t) { return t <= 32 ? 1 : (t <= 64 ? 2 : (t <= 128 ? 4 : 5)); }
 
 size_t gemm_f16_vector_image_bytes(int d, int t, int64_t nS_padded)
 {
-    if (t <= 0 || t > gemm_f16_max_t() || !reduce_on_matrix_cores(d, t)) return 0;
+    if (t <= 0 || t > gemm_f16_max_t(KNM_KERNEL_GAUSSIAN) || !reduce_on_matrix_cores(d, t)) return 0;
     return (size_t)(nS_padded / kStream) * (size_t)(column_groups(t) * 4 * kThreads) * sizeof(f16x8);
 }
 
@@ -916,9 +921,9 @@ size_t gemm_f16_vector_image_bytes(int d, int t, int64_t nS_padded)
 // its tiles itself, and with one workgroup per CU nothing hides that: the launches then measured about
 // (0.015 k + 0.06) s for up to 32 columns, (0.016 k + 0.36) s for 64 and (0.016 k + 0.68) s for 128, with
 // k = ceil(d / 16) chunks of features, so the wide launches pay only once the cross term is long.
-int gemm_f16_group_t(int d, int t_left, bool with_vector_image)
+int gemm_f16_group_t(int d, int t_left, int kind, bool with_vector_image)
 {
-    if (with_vector_image) return gemm_f16_max_t();
+    if (with_vector_image) return gemm_f16_max_t(kind); // (more than 128 columns at once only this way)
     const int n_kc = (d + kChunk - 1) / kChunk;
     if (t_left > 96 && n_kc >= 10) return 128; // in place of four launches
     if (t_left > 64 && n_kc >= 17) return 128; // in place of three
@@ -928,7 +933,7 @@ int gemm_f16_group_t(int d, int t_left, bool with_vector_image)
 
 hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack_bytes, hipStream_t stream)
 {
-    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > gemm_f16_max_t()) return hipErrorInvalidValue;
+    if (a.nF <= 0 || a.nS <= 0 || a.n_chunks <= 0 || a.t <= 0 || a.t > gemm_f16_max_t(a.kind)) return hipErrorInvalidValue;
     if (a.kind < KNM_KERNEL_GAUSSIAN || a.kind > KNM_KERNEL_MATERN52) return hipErrorInvalidValue;
     if (a.chunk_len % kStream != 0 || a.n_chunks * a.chunk_len < a.nS) return hipErrorInvalidValue;
     if (a.n_chunks > 65535) return hipErrorInvalidValue;
@@ -958,7 +963,7 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
         hipLaunchKernelGGL(clear_head_kernel, dim3(1), dim3(kHeadBytes / sizeof(uint32_t)), 0, stream, colmax);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        int64_t blocks = (a.nS + 1) / 2;
+        int64_t blocks = a.nS;
         if (blocks > 4096) blocks = 4096;
         hipLaunchKernelGGL(col_absmax_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a.vec, a.ldv, a.wgt, a.nS,
                            a.t, colmax);
@@ -969,7 +974,8 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
             switch (column_groups(a.t)) {
             case 1: hipLaunchKernelGGL(pack_vectors_kernel<1>, vgrid, dim3(kThreads), 0, stream, a.vec, a.ldv, a.wgt, a.nS, a.t, colmax, vimg); break;
             case 2: hipLaunchKernelGGL(pack_vectors_kernel<2>, vgrid, dim3(kThreads), 0, stream, a.vec, a.ldv, a.wgt, a.nS, a.t, colmax, vimg); break;
-            default: hipLaunchKernelGGL(pack_vectors_kernel<4>, vgrid, dim3(kThreads), 0, stream, a.vec, a.ldv, a.wgt, a.nS, a.t, colmax, vimg); break;
+            case 4: hipLaunchKernelGGL(pack_vectors_kernel<4>, vgrid, dim3(kThreads), 0, stream, a.vec, a.ldv, a.wgt, a.nS, a.t, colmax, vimg); break;
+            default: hipLaunchKernelGGL(pack_vectors_kernel<5>, vgrid, dim3(kThreads), 0, stream, a.vec, a.ldv, a.wgt, a.nS, a.t, colmax, vimg); break;
             }
         }
         e = hipGetLastError();
@@ -990,11 +996,13 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
             if (mv && a.vimg != nullptr) {
                 if (a.t <= 32) launch_tp<2, true, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
                 else if (a.t <= 64) launch_tp<4, true, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
-                else launch_tp<8, true, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                else if (a.t <= 128) launch_tp<8, true, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                else launch_tp<10, true, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
             } else if (mv) {
                 if (a.t <= 32) launch_tp<2, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
                 else if (a.t <= 64) launch_tp<4, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
-                else launch_tp<8, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                else if (a.t <= 128) launch_tp<8, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                else return hipErrorInvalidValue; // more than 128 columns only with the packed vector image
             } else {
                 switch ((a.t + 1) / 2) {
                 case 1: launch_tp<2, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;

@@ -114,8 +114,8 @@ hipError_t launch_sweep_gemm(const SweepArgs &a, hipStream_t stream);
 // operands are packed into the workspace, whole or slab by slab
 size_t gemm_f16_pack_bytes_per_point(int d);
 size_t gemm_f16_head_bytes(); // bytes of the workspace in front of the images
-int gemm_f16_max_t(); // columns per launch at most
-int gemm_f16_group_t(int d, int t_left, bool with_vector_image); // columns the next launch should take
+int gemm_f16_max_t(int kind); // columns per launch at most
+int gemm_f16_group_t(int d, int t_left, int kind, bool with_vector_image); // columns the next launch should take
 // bytes of the packed vector image of a launch with t columns over nS_padded stream points (0: no such image)
 size_t gemm_f16_vector_image_bytes(int d, int t, int64_t nS_padded);
 size_t gemm_f16_min_pack_bytes(int64_t nF, int64_t nS_padded, int64_t chunk_len, int d);

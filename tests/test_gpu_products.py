@@ -57,7 +57,7 @@ SHAPES = [
     (257, 385, 99, 3, 7.0),
     (1000, 2100, 16, 17, 3.0),
     # 8 columns and more: reduction against the vectors on the matrix cores, in 1, 2 or 4 groups of 32
-    # columns per launch; 144 = two launches (128 + 16)
+    # columns per launch (5 groups, 160 columns, for the Gaussian kernel)
     (700, 390, 20, 32, 3.0),
     (500, 300, 6, 40, 1.5),
     (2300, 700, 28, 9, 4.0),
@@ -67,6 +67,8 @@ SHAPES = [
     (640, 385, 33, 144, 5.0),
     (300, 260, 300, 50, 18.0),
     (257, 300, 280, 70, 17.0),
+    # five groups in one launch (160 columns), and one column left over
+    (520, 385, 40, 161, 6.0),
 ]
 
 

@@ -65,6 +65,7 @@ SHAPES = [
     (700, 520, 28, 70, 6.0),
     (400, 320, 300, 70, 40.0),
     (300, 260, 290, 40, 40.0),
+    (300, 260, 24, 150, 6.0),
 ]
 
 
