@@ -25,7 +25,8 @@
 // Images are built slab by slab when they exceed the workspace.
 //
 // Tile shape and orientation as in knm_gemm.hip: workgroup = 256 fixed x 128 stream
-// points, each wavefront 64 fixed x 128 stream = 8 accumulators of 32x32 pinned to AGPRs;
+// points, each wavefront 64 fixed x 128 stream = 8 accumulators of 32x32 in architectural VGPRs
+// (the vector ALU reads them directly; in AGPRs every kernel value cost a v_accvgpr_read first);
 // the stream block is the A operand, so a lane's accumulator registers run over stream
 // points of one fixed point and the reduction against the vector columns is in-lane.
 //
@@ -156,28 +157,28 @@ __global__ __launch_bounds__(kThreads) void pack_points_kernel(const float *__re
 
 __device__ __forceinline__ void mfma_zero(f32x16 &acc, const f16x8 &a, const f16x8 &b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&a"(acc) : "v"(a), "v"(b));
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma_acc(f32x16 &acc, const f16x8 &a, const f16x8 &b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 
 // exp2 of an accumulator element with the clamp modifier (Gaussian kernel value in [0, 1]).  Volatile
-// and reading the accumulation register itself: the compiler does not look inside inline assembly,
+// and reading the accumulator register itself: the compiler does not look inside inline assembly,
 // so it must neither move this read up towards the MFMA that produces the element (it knows
 // nothing of that instruction's latency) nor be relied on for the wait state a transcendental result needs before its first use.
 __device__ __forceinline__ float exp2_clamped(const float &x)
 {
     float p;
-    asm volatile("v_accvgpr_read_b32 %0, %1\n\tv_exp_f32_e64 %0, %0 clamp\n\ts_nop 0" : "=v"(p) : "a"(x));
+    asm volatile("v_exp_f32_e64 %0, %1 clamp\n\ts_nop 0" : "=v"(p) : "v"(x));
     return p;
 }
 // the accumulator element itself, for code the compiler schedules (same ordering argument)
 __device__ __forceinline__ float acc_read(const float &x)
 {
     float p;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(p) : "a"(x));
+    asm volatile("v_mov_b32 %0, %1" : "=v"(p) : "v"(x));
     return p;
 }
 
