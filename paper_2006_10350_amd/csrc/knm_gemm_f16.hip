@@ -215,7 +215,7 @@ struct PatchMap {
 
 // Fimg: image of the fixed points [fixed_row0, fixed_row0 + 256 n_fblocks);
 // Simg: image of the stream chunks [chunk0, chunk0 + n_chunks).
-// TP: number of vector columns, padded to a multiple of 2 (vector-ALU reduction).  MV: reduce
+// TP: number of vector columns, padded to a multiple of 2 unless there is only one (vector-ALU reduction).  MV: reduce
 // on the matrix cores instead, TP / 2 groups of 32 columns each (1, 2, 4 or 5: the kernel values of a
 // tile are evaluated and split once and multiplied into every group; more than one group needs the
 // registers and the LDS of a whole CU, so those instantiations run one workgroup per CU);
@@ -676,10 +676,15 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
             auto load_row = [&](float (&dst)[TP], int it) {
                 const int sb = it >> 4, r = it & 15;
                 const int j = sb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if constexpr (TP % 2 == 0) {
 #pragma unroll
-                for (int c2 = 0; c2 < TP; c2 += 2) {
-                    const f32x2 u = *reinterpret_cast<const f32x2 *>(&vimg[j * TP + c2]);
-                    dst[c2] = u[0]; dst[c2 + 1] = u[1];
+                    for (int c2 = 0; c2 < TP; c2 += 2) {
+                        const f32x2 u = *reinterpret_cast<const f32x2 *>(&vimg[j * TP + c2]);
+                        dst[c2] = u[0]; dst[c2 + 1] = u[1];
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < TP; ++c) dst[c] = vimg[j * TP + c];
                 }
             };
             load_row(vr[0], 0);
@@ -1005,6 +1010,9 @@ hipError_t launch_sweep_gemm_f16(const SweepArgs &a, void *pack_buf, size_t pack
                 else if (a.t <= 128) launch_tp<8, true>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
                 else return hipErrorInvalidValue; // more than 128 columns only with the packed vector image
             } else {
+                if (a.t == 1) { // one column: no padded second one
+                    launch_tp<1, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream);
+                } else
                 switch ((a.t + 1) / 2) {
                 case 1: launch_tp<2, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
                 case 2: launch_tp<4, false>(a, Fimg, Simg, f0, fb, c0, nc, n_kc, colmax, stream); break;
