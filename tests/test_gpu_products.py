@@ -330,7 +330,8 @@ def test_workload_shaped_sample(knm, cross, name, n_sub, M_sub):
     assert rel_l2(U, oracle.knm_prod(X.numpy(), C.numpy(), w.sigma, v.numpy())) < TOL
 
 
-@pytest.mark.parametrize("n,M,d,t,sigma", [(3000, 700, 28, 1, 4.0), (2100, 600, 100, 12, 7.0), (1500, 400, 9, 3, 2.0)])
+@pytest.mark.parametrize("n,M,d,t,sigma", [(3000, 700, 28, 1, 4.0), (2100, 600, 100, 12, 7.0), (1500, 400, 9, 3, 2.0),
+                                             (1800, 500, 40, 40, 5.0)])  # the last: packed vector image, wide launch
 def test_product_replays_in_a_graph(knm, n, M, d, t, sigma):
     """Once the workspace exists (one eager call with the same shapes) a product only enqueues kernels
     on the context's stream, so it can be captured into a graph.  Every replay, with new inputs and
