@@ -61,12 +61,18 @@ constexpr int kChunk = 16;                     // features per K-chunk = one MFM
 constexpr int kUnits = 128;                    // 16-byte units per block and chunk (2 planes x 64 lanes)
 constexpr int kLoads = kBlocks * kUnits / kThreads; // units copied per thread and stage (6)
 constexpr int kStageUnits = kBlocks * kUnits;       // 16-byte units of one LDS stage (24 KB)
-// Stages in the LDS ring: 3 (two stages of loads in flight) where two workgroups' rings and vector rows
-// fit a CU's 160 KB, 2 for the matrix-core reduction with one column group and its 16 KB of vector halves
-// (with more groups a workgroup has the CU's LDS for itself: 3 again)
-constexpr int ring_depth(bool mv, int tp) { return mv && tp == 2 ? 2 : 3; }
-// the matrix-core reduction with more than one group of 32 columns takes a CU for itself
-constexpr int workgroups_per_cu(bool mv, int tp) { return mv && tp > 2 ? 1 : 2; }
+// Workgroups per CU.  The vector-ALU reduction and the matrix-core reduction with one group of 32 columns
+// run two; so does the one with two groups for the Gaussian kernel when the vectors come as a packed image
+// (249 registers); every other instantiation with more than one group needs the registers and the LDS of a
+// whole CU.
+constexpr int workgroups_per_cu(bool mv, int tp, int kind, bool vi)
+{
+    return !mv || tp == 2 || (tp == 4 && kind == KNM_KERNEL_GAUSSIAN && vi) ? 2 : 1;
+}
+// Stages in the LDS ring: 3 (two stages of loads in flight) where the rings and vector rows of the workgroups
+// of a CU fit its 160 KB, 2 for the matrix-core reduction at two workgroups per CU with its 16 KB of vector
+// halves per group
+constexpr int ring_depth(bool mv, int tp, int kind, bool vi) { return mv && workgroups_per_cu(mv, tp, kind, vi) == 2 ? 2 : 3; }
 constexpr float kPScale = 16384.0f; // matrix-core reduction: kernel values are split into fp16 halves after this scale
 // Image of points [row0, row0 + 32 gridDim.x) of P (points at or beyond nP become zero
 // points).  One workgroup per 32-point block; thread = (point, 8-feature unit), four
@@ -223,7 +229,7 @@ struct PatchMap {
 // VI (with MV): the vector halves of a tile come from the packed image a.vimg (pack_vectors_kernel) by
 // direct-to-LDS loads instead of being converted by the workgroup.
 template <int TP, bool MV, int KIND, bool VI = false>
-__global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
+__global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP, KIND, VI)) void gauss_gemm_f16_kernel(SweepArgs a, const f16x8 *__restrict__ Fimg,
                                                                      const f16x8 *__restrict__ Simg,
                                                                      int64_t fixed_row0, int64_t chunk0, int n_kc,
                                                                      PatchMap pm, const uint32_t *__restrict__ colmax)
@@ -240,7 +246,7 @@ __global__ __launch_bounds__(kThreads, workgroups_per_cu(MV, TP)) void gauss_gem
     // Ring of operand stages (24 KB each) in dynamic LDS, filled by loads that write LDS directly, and
     // behind it the vector rows of a tile: fp32 [stream point][column], or for MV split halves in
     // A-operand layout [stream block][K-step][plane hi/lo][lane]
-    constexpr int kRing = ring_depth(MV, TP);
+    constexpr int kRing = ring_depth(MV, TP, KIND, VI);
     constexpr int G = MV ? TP / 2 : 1; // column groups of the matrix-core reduction
     static_assert(!MV || TP == 2 || TP == 4 || TP == 8 || TP == 10, "1, 2, 4 or 5 groups of 32 columns");
     extern __shared__ __align__(16) unsigned char lds_dyn[];
@@ -864,8 +870,8 @@ void launch_tp(const SweepArgs &a, const f16x8 *Fimg, const f16x8 *Simg, int64_t
     // dynamic LDS: the ring of stages and the vector rows of a tile (more than the 64 KB a kernel gets
     // without asking)
     constexpr int kVecUnits = MV ? (TP / 2) * 4 * 2 * 2 * 64 : (kStream * TP * 4 + 15) / 16;
-    constexpr size_t lds_bytes = (size_t)(ring_depth(MV, TP) * kStageUnits + kVecUnits) * sizeof(f16x8);
     auto launch = [&](auto kind) {
+        constexpr size_t lds_bytes = (size_t)(ring_depth(MV, TP, decltype(kind)::value, VI) * kStageUnits + kVecUnits) * sizeof(f16x8);
         // five column groups fill the register file only just for the Gaussian kernel; the kernels of r
         // (which the dispatcher gives at most 128 columns at a time) have no such instantiation
         if constexpr (MV && TP == 10 && decltype(kind)::value != KNM_KERNEL_GAUSSIAN) return;
